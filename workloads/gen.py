@@ -1,0 +1,44 @@
+"""Seeded synthetic tensors (plain NCHW / OIHW float32), shared by oracle and HIP tests.
+
+Everything is drawn from numpy's default_rng(seed) in a fixed order: the input
+first, then each layer's weights in layer order. No layer arithmetic lives here.
+"""
+import numpy as np
+
+BASE_SEED = 230304769   # seed of workload k is BASE_SEED + k
+
+
+def uniform_pm1(rng, shape):
+    """U[-1, 1) float32."""
+    return (rng.random(shape, dtype=np.float32) * np.float32(2.0) - np.float32(1.0)).astype(np.float32)
+
+
+def normal(rng, shape):
+    """N(0, 1) float32."""
+    return rng.standard_normal(shape, dtype=np.float32)
+
+
+def he_normal(rng, shape, fan_in):
+    """N(0, 2/fan_in) float32."""
+    return (rng.standard_normal(shape, dtype=np.float32) * np.float32(np.sqrt(2.0 / fan_in))).astype(np.float32)
+
+
+def network_tensors(net, N, seed):
+    """Input batch [N, C0, H0, W0] and the list of plain weights of `net`."""
+    rng = np.random.default_rng(seed)
+    shape = (N, net.C0, net.H0, net.W0)
+    x = uniform_pm1(rng, shape) if net.input_dist == "uniform" else normal(rng, shape)
+    ws = []
+    for shp, fan_in in net.wshapes:
+        ws.append(uniform_pm1(rng, shp) if net.weight_dist == "uniform" else he_normal(rng, shp, fan_in))
+    return x, ws
+
+
+# Roofline layer sweep: fp32, batch 64, Cb = 16, everything U[-1, 1).
+SWEEP_N = 64
+
+
+def sweep_shapes():
+    """(C, H) pairs of the conv / depthwise sweep, plus the pool / ReLU shape."""
+    return {"conv": [(64, 56), (128, 28), (256, 14), (512, 7)],
+            "pool_relu": (256, 56)}
