@@ -1,0 +1,142 @@
+/*
+ * small.h -- C ABI of libsmall_hip: the SMaLL abstract-layer hot path on one MI355X (gfx950).
+ *
+ * Every layer is an instance of one loop nest (paper Algorithm 1) over one shared,
+ * channel-blocked data format (paper Section 4.4 "Common Data Format"), so the output
+ * of any layer is the input of the next with no reformatting:
+ *
+ *   activations  [N][C/Cb][H][W][Cb]                     Cb fastest, batch outermost
+ *   filters      [Co/Cob][Ci/Cib][kh][kw][Cib][Cob]      Cob fastest (loop order of Algorithm 1)
+ *   dw filters   [C/Cb][kh][kw][Cb]                      (the same layout with F_Cb = 1, G_b = Cb)
+ *
+ * All data are IEEE fp32. Block sizes are run-time arguments; a tensor with C channels
+ * is stored with any block Cb that divides C (the tuned kernels expect Cb = 16 and fall
+ * back to a generic kernel otherwise; callers normally use min(16, C)).
+ *
+ * Conventions for every entry point unless stated otherwise:
+ *   - every pointer is a DEVICE pointer owned by the caller, valid until the enqueued
+ *     work has finished; the library allocates nothing, frees nothing and never
+ *     synchronises. Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream);
+ *   - `in` and `out` must not overlap, except small_relu and small_add where out may
+ *     equal an input exactly (in place);
+ *   - padding is explicit zero padding, 4-sided; output size per side is
+ *     floor((in + lo + hi - k) / stride) + 1 (the paper's output-size equation of
+ *     Section 3.1.2 extended with padding and floor);
+ *   - return value: SMALL_OK (0) or an error code below. When an error is returned
+ *     nothing has been enqueued. No exception crosses this boundary.
+ */
+#ifndef SMALL_H
+#define SMALL_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SMALL_OK = 0,
+    SMALL_ERR_NULL = 1,   /* a required pointer is NULL */
+    SMALL_ERR_SHAPE = 2,  /* non-positive dim, window larger than the padded input, C % Cb != 0, size overflow */
+    SMALL_ERR_BLOCK = 3,  /* block size with no kernel (Cb > 64) */
+    SMALL_ERR_ALIAS = 4,  /* in/out overlap where it is not allowed */
+    SMALL_ERR_LAUNCH = 5, /* the HIP runtime refused the launch */
+    SMALL_ERR_WORKSPACE = 6, /* workspace too small or misaligned (small_network_run) */
+    SMALL_ERR_LAYER = 7   /* malformed layer table (bad op, bad buffer id, block mismatch between layers) */
+};
+
+typedef struct { int t, b, l, r; } small_pad; /* zero padding: top, bottom, left, right */
+
+/* floor((in + pad_lo + pad_hi - k) / stride) + 1, or 0 when the window does not fit. Host only. */
+int small_out_dim(int in, int k, int stride, int pad_lo, int pad_hi);
+
+const char *small_strerror(int code);
+
+/* ---- layout conversion at the network boundary (Section 4.4). Bit-exact copies. ----
+ * small_pack:   plain [N][C][H][W]  ->  blocked [N][C/Cb][H][W][Cb];  small_unpack is its inverse.
+ * small_pack_filter:    plain [Co][Ci][kh][kw] -> [Co/Cob][Ci/Cib][kh][kw][Cib][Cob].
+ * small_pack_dw_filter: plain [C][1][kh][kw]   -> [C/Cb][kh][kw][Cb].
+ * Both buffers hold exactly N*C*H*W (resp. Co*Ci*kh*kw, C*kh*kw) floats. */
+int small_pack(const float *nchw, float *blocked, int N, int C, int H, int W, int Cb, void *stream);
+int small_unpack(const float *blocked, float *nchw, int N, int C, int H, int W, int Cb, void *stream);
+int small_pack_filter(const float *oihw, float *blocked, int Co, int Ci, int kh, int kw, int Cob, int Cib,
+                      void *stream);
+int small_pack_dw_filter(const float *c1hw, float *blocked, int C, int kh, int kw, int Cb, void *stream);
+
+/* ---- full-channel reduction: convolution (Table 1 row "Full Channel Reduction": F_C = I_C,
+ * K = O_C, G = 1; Table 2: reduction = FMA).
+ *   out[n,co,oh,ow] = sum_{ci,y,x} in[n,ci,oh*stride+y-pad.t, ow*stride+x-pad.l] * filt[co,ci,y,x],
+ * taps outside the input contribute 0. in: [N][Ci/Cib][H][W][Cib]; filt: blocked filter;
+ * out: [N][Co/Cob][Ho][Wo][Cob]. Cib = Cob = 16 runs on the fp32 matrix cores; any other
+ * block sizes (<= 64) run a generic kernel. fp32 accumulation, summation order unspecified. */
+int small_conv2d(const float *in, const float *filt, float *out, int N, int Ci, int Co, int H, int W, int kh,
+                 int kw, int stride, small_pad pad, int Cib, int Cob, void *stream);
+
+/* ---- single-channel reduction with weights: depthwise convolution (Table 1 row "Single
+ * Channel Reduction": F_C = 1, K = 1, G = I_C; Section 3.2 item 2).
+ *   out[n,c,oh,ow] = sum_{y,x} in[n,c,oh*stride+y-pad.t, ow*stride+x-pad.l] * filt[c,y,x]. */
+int small_dwconv2d(const float *in, const float *filt, float *out, int N, int C, int H, int W, int kh, int kw,
+                   int stride, small_pad pad, int Cb, void *stream);
+
+/* ---- single-channel reduction without weights: pooling (Section 3.2 item 2; Table 2 "Max Pooling").
+ * mode SMALL_POOL_MAX: m = -inf; taps visited row-major; m = v when v > m; taps outside the
+ *   input are skipped (bit-exact, ties keep the first value seen, NaN is never selected).
+ * mode SMALL_POOL_AVG: sum of the in-range taps divided by their count (the paper names only
+ *   "pooling"; average pooling is the Add reduction of the same class). */
+enum { SMALL_POOL_MAX = 0, SMALL_POOL_AVG = 1 };
+int small_pool2d(const float *in, float *out, int N, int C, int H, int W, int kh, int kw, int stride,
+                 small_pad pad, int Cb, int mode, void *stream);
+
+/* ---- single-element reductions (Table 1 row "Single Element Reduction"; Table 2 "Activation (ReLU)":
+ * reduction = Max; Section 3.2 item 1 names addition). Layout-agnostic over n_elems floats.
+ *   small_relu: out[i] = in[i] > 0 ? in[i] : +0   (so -0 -> +0 and NaN -> +0), bit-exact.
+ *   small_add:  out[i] = a[i] + b[i]  (one IEEE fp32 addition), used for residual connections
+ *               (Section "MLPerf:Tiny Inference Models": the block input is accumulated with its output). */
+int small_relu(const float *in, float *out, size_t n_elems, void *stream);
+int small_add(const float *a, const float *b, float *out, size_t n_elems, void *stream);
+
+/* ---- full reduction: dense / fully connected (Table 1 row "Full Reduction") on a 1x1 image.
+ *   out[n,o] = sum_i in[n,i] * filt[o,i];  in: [N][Ci/Cib][1][1][Cib] (= [N][Ci]),
+ *   filt: [Co/Cob][Ci/Cib][1][1][Cib][Cob], out: [N][Co/Cob][1][1][Cob] (= [N][Co]).
+ * A dense layer over an H x W image is small_conv2d with kh = H, kw = W and no padding. */
+int small_dense(const float *in, const float *filt, float *out, int N, int Ci, int Co, int Cib, int Cob,
+                void *stream);
+
+/* ---- a whole network: a table of layers over shared buffers (Section "Memory Usage
+ * Comparison": buffers are shared across layers; nothing is reformatted between layers).
+ * Logical buffer ids: SMALL_BUF_IN = the caller's blocked input (read-only), SMALL_BUF_OUT = the
+ * caller's blocked output, 0..SMALL_MAX_SLOTS-1 = slots carved out of the workspace. Each slot is
+ * sized for the largest tensor any layer writes to it.
+ * For op RELU / ADD / MAXPOOL / AVGPOOL, Ci is the channel count and Co must equal Ci.
+ * For ADD, src2 is the second operand. For DENSE, kh/kw must equal the input H/W.
+ * filt is the layer's blocked device filter (NULL for layers without weights). */
+enum { SMALL_OP_CONV = 0, SMALL_OP_DWCONV = 1, SMALL_OP_MAXPOOL = 2, SMALL_OP_AVGPOOL = 3, SMALL_OP_RELU = 4,
+       SMALL_OP_ADD = 5, SMALL_OP_DENSE = 6 };
+enum { SMALL_BUF_IN = -1, SMALL_BUF_OUT = -2, SMALL_MAX_SLOTS = 8 };
+
+typedef struct {
+    int op;
+    int Ci, Co, kh, kw, stride;
+    small_pad pad;
+    int Cib, Cob;
+    int src, src2, dst;
+    const float *filt;
+} small_layer;
+
+/* Bytes of workspace small_network_run needs for this table and input shape (host only, enqueues nothing).
+ * Slots are 256-byte aligned. */
+int small_network_workspace(const small_layer *layers, int n_layers, int N, int C0, int H0, int W0,
+                            size_t *bytes);
+
+/* Enqueues every layer of the table, in order, on `stream`. `layers` is a HOST array (read during the
+ * call only). in_blocked: [N][C0/Cb0][H0][W0][Cb0] with Cb0 = layers[0].Cib. out_blocked receives every
+ * write to SMALL_BUF_OUT. workspace: device memory, 256-byte aligned, workspace_bytes >= the size
+ * reported by small_network_workspace. The table is validated completely before anything is enqueued. */
+int small_network_run(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
+                      void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SMALL_H */

@@ -1,0 +1,217 @@
+"""ctypes binding of libsmall_hip.so: same names and arguments as include/small.h.
+
+Tensor arguments are torch CUDA tensors (float32, contiguous); only their device
+pointers cross the boundary. The stream is torch's current stream unless given.
+Every wrapper raises SmallError on a non-zero status. No arithmetic happens here.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsmall_hip.so")
+
+OK = 0
+POOL_MAX, POOL_AVG = 0, 1
+OP_CONV, OP_DWCONV, OP_MAXPOOL, OP_AVGPOOL, OP_RELU, OP_ADD, OP_DENSE = range(7)
+BUF_IN, BUF_OUT, MAX_SLOTS = -1, -2, 8
+_OPS = {"conv": OP_CONV, "dw": OP_DWCONV, "maxpool": OP_MAXPOOL, "avgpool": OP_AVGPOOL, "relu": OP_RELU,
+        "add": OP_ADD, "dense": OP_DENSE}
+
+EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "small_pack_filter",
+           "small_pack_dw_filter", "small_conv2d", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
+           "small_dense", "small_network_workspace", "small_network_run"]
+
+
+class SmallError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        super().__init__(f"{what}: error {code} ({strerror(code)})")
+
+
+class small_pad(C.Structure):
+    _fields_ = [("t", C.c_int), ("b", C.c_int), ("l", C.c_int), ("r", C.c_int)]
+
+
+class small_layer(C.Structure):
+    _fields_ = [("op", C.c_int), ("Ci", C.c_int), ("Co", C.c_int), ("kh", C.c_int), ("kw", C.c_int),
+                ("stride", C.c_int), ("pad", small_pad), ("Cib", C.c_int), ("Cob", C.c_int),
+                ("src", C.c_int), ("src2", C.c_int), ("dst", C.c_int), ("filt", C.c_void_p)]
+
+
+_lib = None
+
+
+def load():
+    """Loads the in-tree library; builds it first only when no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from .build import build_lib
+        build_lib()
+    lib = C.CDLL(LIB_PATH)
+    i, p, sz = C.c_int, C.c_void_p, C.c_size_t
+    sig = {
+        "small_out_dim": (i, [i, i, i, i, i]),
+        "small_strerror": (C.c_char_p, [i]),
+        "small_pack": (i, [p, p, i, i, i, i, i, p]),
+        "small_unpack": (i, [p, p, i, i, i, i, i, p]),
+        "small_pack_filter": (i, [p, p, i, i, i, i, i, i, p]),
+        "small_pack_dw_filter": (i, [p, p, i, i, i, i, p]),
+        "small_conv2d": (i, [p, p, p, i, i, i, i, i, i, i, i, small_pad, i, i, p]),
+        "small_dwconv2d": (i, [p, p, p, i, i, i, i, i, i, i, small_pad, i, p]),
+        "small_pool2d": (i, [p, p, i, i, i, i, i, i, i, small_pad, i, i, p]),
+        "small_relu": (i, [p, p, sz, p]),
+        "small_add": (i, [p, p, p, sz, p]),
+        "small_dense": (i, [p, p, p, i, i, i, i, i, p]),
+        "small_network_workspace": (i, [C.POINTER(small_layer), i, i, i, i, i, C.POINTER(sz)]),
+        "small_network_run": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
+    }
+    for name, (res, args) in sig.items():
+        f = getattr(lib, name)     # AttributeError if the library does not export it
+        f.restype, f.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def strerror(code):
+    return load().small_strerror(int(code)).decode()
+
+
+def _check(rc, what):
+    if rc != OK:
+        raise SmallError(rc, what)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError("expected a contiguous float32 CUDA tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _pad(pad):
+    return small_pad(*[int(v) for v in pad])
+
+
+def small_out_dim(i, k, stride, lo, hi):
+    return load().small_out_dim(i, k, stride, lo, hi)
+
+
+def small_pack(nchw, blocked, N, Cc, H, W, Cb, stream=None):
+    _check(load().small_pack(_ptr(nchw), _ptr(blocked), N, Cc, H, W, Cb, _stream(stream)), "small_pack")
+
+
+def small_unpack(blocked, nchw, N, Cc, H, W, Cb, stream=None):
+    _check(load().small_unpack(_ptr(blocked), _ptr(nchw), N, Cc, H, W, Cb, _stream(stream)), "small_unpack")
+
+
+def small_pack_filter(oihw, blocked, Co, Ci, kh, kw, Cob, Cib, stream=None):
+    _check(load().small_pack_filter(_ptr(oihw), _ptr(blocked), Co, Ci, kh, kw, Cob, Cib, _stream(stream)),
+           "small_pack_filter")
+
+
+def small_pack_dw_filter(c1hw, blocked, Cc, kh, kw, Cb, stream=None):
+    _check(load().small_pack_dw_filter(_ptr(c1hw), _ptr(blocked), Cc, kh, kw, Cb, _stream(stream)),
+           "small_pack_dw_filter")
+
+
+def small_conv2d(inp, filt, out, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob, stream=None):
+    _check(load().small_conv2d(_ptr(inp), _ptr(filt), _ptr(out), N, Ci, Co, H, W, kh, kw, stride, _pad(pad), Cib, Cob,
+                               _stream(stream)), "small_conv2d")
+
+
+def small_dwconv2d(inp, filt, out, N, Cc, H, W, kh, kw, stride, pad, Cb, stream=None):
+    _check(load().small_dwconv2d(_ptr(inp), _ptr(filt), _ptr(out), N, Cc, H, W, kh, kw, stride, _pad(pad), Cb,
+                                 _stream(stream)), "small_dwconv2d")
+
+
+def small_pool2d(inp, out, N, Cc, H, W, kh, kw, stride, pad, Cb, mode, stream=None):
+    _check(load().small_pool2d(_ptr(inp), _ptr(out), N, Cc, H, W, kh, kw, stride, _pad(pad), Cb, mode,
+                               _stream(stream)), "small_pool2d")
+
+
+def small_relu(inp, out, n_elems, stream=None):
+    _check(load().small_relu(_ptr(inp), _ptr(out), n_elems, _stream(stream)), "small_relu")
+
+
+def small_add(a, b, out, n_elems, stream=None):
+    _check(load().small_add(_ptr(a), _ptr(b), _ptr(out), n_elems, _stream(stream)), "small_add")
+
+
+def small_dense(inp, filt, out, N, Ci, Co, Cib, Cob, stream=None):
+    _check(load().small_dense(_ptr(inp), _ptr(filt), _ptr(out), N, Ci, Co, Cib, Cob, _stream(stream)), "small_dense")
+
+
+def make_layer_table(layers, filters):
+    """ctypes array of small_layer from records with fields op, Ci, Co, kh, kw, stride, pad,
+    Cib, Cob, src, src2, dst, w (index into `filters`, the blocked device filters, or None)."""
+    arr = (small_layer * len(layers))()
+    for k, L in enumerate(layers):
+        f = filters[L.w] if L.w is not None else None
+        arr[k] = small_layer(_OPS[L.op], L.Ci, L.Co, L.kh, L.kw, L.stride, _pad(L.pad), L.Cib, L.Cob,
+                             L.src, L.src2, L.dst, f.data_ptr() if f is not None else None)
+    return arr
+
+
+def small_network_workspace(table, N, C0, H0, W0):
+    n = C.c_size_t(0)
+    _check(load().small_network_workspace(table, len(table), N, C0, H0, W0, C.byref(n)), "small_network_workspace")
+    return n.value
+
+
+def small_network_run(table, in_blocked, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, stream=None):
+    _check(load().small_network_run(table, len(table), _ptr(in_blocked), _ptr(out_blocked),
+                                    C.c_void_p(workspace.data_ptr()) if workspace is not None else None,
+                                    workspace_bytes, N, C0, H0, W0, _stream(stream)), "small_network_run")
+
+
+class PackedNetwork:
+    """Device-resident form of a layer table: filters packed once into the blocked layout
+    (by small_pack_filter / small_pack_dw_filter), workspace allocated once per batch size."""
+
+    def __init__(self, net, weights, device="cuda:0"):
+        self.net, self.device = net, torch.device(device)
+        self.filters = []
+        by_w = {L.w: L for L in net.layers if L.w is not None}
+        for k, w in enumerate(weights):
+            L = by_w[k]
+            src = torch.from_numpy(w).to(self.device).contiguous()
+            dst = torch.empty(src.numel(), dtype=torch.float32, device=self.device)
+            if L.op == "dw":
+                small_pack_dw_filter(src, dst, L.Ci, L.kh, L.kw, L.Cib)
+            else:
+                small_pack_filter(src, dst, L.Co, L.Ci, L.kh, L.kw, L.Cob, L.Cib)
+            self.filters.append(dst)
+        self.table = make_layer_table(net.layers, self.filters)
+        self._ws = {}
+
+    def workspace(self, N):
+        if N not in self._ws:
+            nbytes = small_network_workspace(self.table, N, self.net.C0, self.net.H0, self.net.W0)
+            self._ws[N] = (torch.empty(max(nbytes, 256) // 4, dtype=torch.float32, device=self.device), nbytes)
+        return self._ws[N]
+
+    def pack_input(self, x_nchw):
+        N = x_nchw.shape[0]
+        xb = torch.empty(x_nchw.numel(), dtype=torch.float32, device=self.device)
+        small_pack(x_nchw, xb, N, self.net.C0, self.net.H0, self.net.W0, self.net.layers[0].Cib)
+        return xb
+
+    def out_elems(self, N):
+        L = self.net.layers[-1]
+        return N * L.Co * L.Ho * L.Wo
+
+    def run(self, in_blocked, out_blocked, N, stream=None):
+        ws, nbytes = self.workspace(N)
+        small_network_run(self.table, in_blocked, out_blocked, ws, nbytes, N, self.net.C0, self.net.H0, self.net.W0,
+                          stream)

@@ -1,0 +1,281 @@
+// Full-channel reduction: direct convolution on the blocked layout (paper Table 1 row 4,
+// Algorithm 1 with G = 1, K = Co, F_C = Ci; kernel phases of Algorithm 2).
+//
+// Mapping of Algorithm 1 onto gfx950:
+//   loops g, k (output-channel blocks, "in parallel")  -> blockIdx.y / wave column
+//   loops j, l (output pixels, tile O_wb)              -> blockIdx.x / wave row; pixels of all
+//                                                         images are one flattened axis
+//   loop  i    (input-channel blocks)                  -> moved INSIDE the tile: the output tile
+//                                                         stays in accumulator registers for the
+//                                                         whole reduction, LOAD/STORE happen once
+//   kernel loops x, y, ii over a O_wb x K_b tile       -> v_mfma_f32_16x16x4_f32 on LDS-staged
+//                                                         [pixel][Cib] and [Cib][Cob] slabs
+// The blocked layouts are already matrix-core operands: for a fixed (Ci block, tap) a run of
+// pixels is a row-major [pixels][16] matrix and the filter slab is a row-major [16][16] matrix.
+#include "small_internal.h"
+
+namespace small {
+
+namespace {
+
+struct ConvArgs {
+    const float *in;
+    const float *filt;
+    float *out;
+    int N, H, W, Ho, Wo;
+    int nCib, nCob;
+    int kh, kw, stride, pt, pl;
+    int M;        // N * Ho * Wo flattened output pixels
+    int HoWo;
+    int epilogue;
+};
+
+__device__ __forceinline__ floatx4 epilogue4(floatx4 v, int epi)
+{
+    if (epi & EPI_RELU) {
+        v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
+        v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
+    }
+    return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Matrix-core path, Cib = Cob = 16, any window / stride / padding.
+//
+// Workgroup tile: TM = WAVES_M*WM*16 flattened output pixels x TN = WAVES_N*WN*16 output channels.
+// Reduction step ("k-step") = one (Ci block, tap y, tap x): 16 input channels.
+//   A-stage: for every tile pixel the 16 input channels of the tap's input pixel (zeros when the
+//            tap falls outside the image or the pixel is beyond M), gathered into LDS as
+//            sA[quad q][pixel] float4 (q = which 4 of the 16 channels).
+//   B-stage: the [16 ci][TN co] filter slab, re-tiled in LDS per 16-co subtile as
+//            float4 groups (q, co) -> W[4q..4q+3][co], so that one ds_read_b128 per lane yields
+//            the operand registers of four MFMAs.
+// MFMA operand roles: "A" (16x4, row i) = filter with i = co; "B" (4x16, col j) = input with
+// j = pixel; D[i = co][j = pixel]: lane l holds co = 4*(l/16) + v (v = 0..3), pixel = l%16, i.e. a
+// float4 of four adjacent output channels of one pixel, and the 16 lanes x 4 lane-groups of a
+// wave store one contiguous 1 KiB run of the [pixel][Cob] output.
+// The reduction index inside a k-step is permuted (MFMA r takes ci = 4*(l/16) + r); both
+// operands use the same permutation, and a sum does not depend on it.
+// Global -> LDS copies are software-pipelined one k-step ahead through registers (double-buffered
+// LDS, one barrier per k-step).
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_mfma(ConvArgs a)
+{
+    constexpr int NT = 64 * WAVES_M * WAVES_N;
+    constexpr int TM = WAVES_M * WM * 16;
+    constexpr int TN = WAVES_N * WN * 16;
+    constexpr int NSUB = TN / 16;
+    constexpr int A_ITEMS = TM * 4, B_ITEMS = TN * 4;           // float4 items per stage
+    constexpr int A_IT = (A_ITEMS + NT - 1) / NT, B_IT = (B_ITEMS + NT - 1) / NT;
+    constexpr int A_LD = TM + 2;                                 // skewed quad stride (float4 units)
+
+    __shared__ floatx4 sA[2][4 * A_LD];
+    __shared__ float sB[2][TN * 16];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
+    const int m0 = blockIdx.x * TM;
+    const int cob0 = blockIdx.y * NSUB;
+    const int HW = a.H * a.W;
+
+    // ---- per-thread staging descriptors (fixed over the reduction)
+    int a_off[A_IT], a_ih0[A_IT], a_iw0[A_IT];
+    bool a_ok[A_IT];
+#pragma unroll
+    for (int i = 0; i < A_IT; ++i) {
+        const int item = tid + i * NT;
+        const int px = item >> 2, quad = item & 3;
+        const int m = m0 + px;
+        a_ok[i] = (item < A_ITEMS) && (m < a.M);
+        const int mm = a_ok[i] ? m : 0;
+        const int n = mm / a.HoWo, rem = mm - n * a.HoWo;
+        const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+        a_ih0[i] = oh * a.stride - a.pt;
+        a_iw0[i] = ow * a.stride - a.pl;
+        a_off[i] = n * a.nCib * HW * 16 + quad * 4;
+    }
+    int b_src[B_IT], b_dst[B_IT];
+    bool b_ok[B_IT];
+#pragma unroll
+    for (int i = 0; i < B_IT; ++i) {
+        const int item = tid + i * NT;
+        const int sub = item >> 6, w = item & 63;
+        const int ci = w >> 2, cq = w & 3;
+        b_ok[i] = (item < B_ITEMS) && (cob0 + sub < a.nCob);
+        // element offset inside the filter of (cob0+sub, cib = 0, tap 0), row ci, channels 4cq..4cq+3
+        b_src[i] = (cob0 + sub) * a.nCib * a.kh * a.kw * 256 + ci * 16 + cq * 4;
+        // LDS float index of group (q = ci/4, co = 4cq + j), component r = ci%4; j is added at store time
+        b_dst[i] = sub * 256 + (ci >> 2) * 64 + (ci & 3);
+    }
+
+    floatx4 ra[A_IT], rb[B_IT];
+    auto load_stage = [&](int cib, int y, int x) {
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) {
+            const int ih = a_ih0[i] + y, iw = a_iw0[i] + x;
+            const bool ok = a_ok[i] && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            ra[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (ok) ra[i] = *reinterpret_cast<const floatx4 *>(a.in + a_off[i] + (cib * HW + ih * a.W + iw) * 16);
+        }
+        const int tap = ((cib * a.kh + y) * a.kw + x) * 256;
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) {
+            rb[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (b_ok[i]) rb[i] = *reinterpret_cast<const floatx4 *>(a.filt + b_src[i] + tap);
+        }
+    };
+    auto store_stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A_IT; ++i) {
+            const int item = tid + i * NT;
+            if (item < A_ITEMS) sA[buf][(item & 3) * A_LD + (item >> 2)] = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_IT; ++i) {
+            const int item = tid + i * NT;
+            if (item < B_ITEMS) {
+                const int w = item & 63, q = w >> 4, cq = w & 3;
+                float *d = &sB[buf][b_dst[i]];
+                // group index inside the quarter is swizzled with q to spread LDS banks
+                d[((4 * cq + 0) ^ q) * 4] = rb[i].x;
+                d[((4 * cq + 1) ^ q) * 4] = rb[i].y;
+                d[((4 * cq + 2) ^ q) * 4] = rb[i].z;
+                d[((4 * cq + 3) ^ q) * 4] = rb[i].w;
+            }
+        }
+    };
+
+    floatx4 acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    const int lp = lane & 15, lq = lane >> 4;
+    const int ksteps = a.nCib * a.kh * a.kw;
+    int cib = 0, y = 0, x = 0;
+
+    load_stage(0, 0, 0);
+    store_stage(0);
+    __syncthreads();
+
+    for (int ks = 0; ks < ksteps; ++ks) {
+        const int buf = ks & 1;
+        // advance (cib, y, x) to k-step ks + 1
+        if (++x == a.kw) { x = 0; if (++y == a.kh) { y = 0; ++cib; } }
+        const bool more = ks + 1 < ksteps;
+        if (more) load_stage(cib, y, x);
+
+        floatx4 fa[WM], fb[WN];
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+            fb[j] = *reinterpret_cast<const floatx4 *>(&sB[buf][(wave_n * WN + j) * 256 + (lq * 16 + (lp ^ lq)) * 4]);
+#pragma unroll
+        for (int i = 0; i < WM; ++i) fa[i] = sA[buf][lq * A_LD + (wave_m * WM + i) * 16 + lp];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int i = 0; i < WM; ++i)
+#pragma unroll
+                for (int j = 0; j < WN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fb[j][r], fa[i][r], acc[i][j], 0, 0, 0);
+
+        if (more) store_stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- STORE phase: each lane owns 4 adjacent output channels of one pixel
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        const int m = m0 + (wave_m * WM + i) * 16 + lp;
+        if (m >= a.M) continue;
+        const int n = m / a.HoWo, rem = m - n * a.HoWo;
+#pragma unroll
+        for (int j = 0; j < WN; ++j) {
+            const int cob = cob0 + wave_n * WN + j;
+            if (cob >= a.nCob) continue;
+            float *dst = a.out + ((size_t)(n * a.nCob + cob) * a.HoWo + rem) * 16 + lq * 4;
+            *reinterpret_cast<floatx4 *>(dst) = epilogue4(acc[i][j], a.epilogue);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic path, any block sizes (first layers with Ci = 1 or 3, 8-channel blocks, dense heads
+// with Co = 2, 10, 12): one lane per output element, output channel fastest, so the filter
+// reads of a wavefront are contiguous and its input reads are broadcasts.
+__global__ void __launch_bounds__(256) conv_direct(ConvArgs a, int Cib, int Cob, size_t total)
+{
+    size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const size_t dst = e;
+    const int co = (int)(e % Cob); e /= Cob;
+    const int ow = (int)(e % a.Wo); e /= a.Wo;
+    const int oh = (int)(e % a.Ho); e /= a.Ho;
+    const int cob = (int)(e % a.nCob);
+    const int n = (int)(e / a.nCob);
+    float acc = 0.f;
+    for (int cib = 0; cib < a.nCib; ++cib)
+        for (int y = 0; y < a.kh; ++y) {
+            const int ih = oh * a.stride - a.pt + y;
+            if (ih < 0 || ih >= a.H) continue;
+            for (int x = 0; x < a.kw; ++x) {
+                const int iw = ow * a.stride - a.pl + x;
+                if (iw < 0 || iw >= a.W) continue;
+                const float *ip = a.in + (((size_t)(n * a.nCib + cib) * a.H + ih) * a.W + iw) * Cib;
+                const float *wp = a.filt + ((((size_t)cob * a.nCib + cib) * a.kh + y) * a.kw + x) * Cib * Cob + co;
+                for (int ci = 0; ci < Cib; ++ci) acc = fmaf(ip[ci], wp[(size_t)ci * Cob], acc);
+            }
+        }
+    if (a.epilogue & EPI_RELU) acc = acc > 0.f ? acc : 0.f;
+    a.out[dst] = acc;
+}
+
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+void launch_mfma(const ConvArgs &a, hipStream_t s)
+{
+    constexpr int TM = WAVES_M * WM * 16, TN = WAVES_N * WN * 16;
+    const dim3 grid((unsigned)((a.M + TM - 1) / TM), (unsigned)((a.nCob * 16 + TN - 1) / TN));
+    hipLaunchKernelGGL((conv16_mfma<WAVES_M, WAVES_N, WM, WN>), grid, dim3(64 * WAVES_M * WAVES_N), 0, s, a);
+}
+
+}  // namespace
+
+hipError_t launch_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue, hipStream_t s)
+{
+    ConvArgs a;
+    a.in = in; a.filt = filt; a.out = out;
+    a.N = g.N; a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo;
+    a.nCib = g.Ci / g.Cib; a.nCob = g.Co / g.Cob;
+    a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pt = g.pt; a.pl = g.pl;
+    a.HoWo = g.Ho * g.Wo;
+    a.M = g.N * a.HoWo;
+    a.epilogue = epilogue;
+
+    const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 15u) == 0);
+    if (g.Cib == 16 && g.Cob == 16 && aligned) {
+        // Tile choice: the widest channel tile the layer can fill, then the largest pixel tile that
+        // still yields at least one workgroup per compute unit.
+        const int Co = g.Co;
+        const long wg128 = (long)((a.M + 127) / 128);
+        if (Co >= 128) {
+            if (wg128 * ((Co + 127) / 128) >= 256) launch_mfma<2, 2, 4, 4>(a, s);   // 128 x 128
+            else launch_mfma<1, 4, 4, 2>(a, s);                                       //  64 x 128
+        } else if (Co >= 64) {
+            if (wg128 * ((Co + 63) / 64) >= 256) launch_mfma<2, 2, 4, 2>(a, s);     // 128 x 64
+            else launch_mfma<2, 2, 2, 2>(a, s);                                       //  64 x 64
+        } else if (Co >= 32) {
+            if (wg128 >= 256) launch_mfma<4, 1, 2, 2>(a, s);                         // 128 x 32
+            else launch_mfma<4, 1, 1, 2>(a, s);                                       //  64 x 32
+        } else {
+            if (wg128 >= 256) launch_mfma<4, 1, 2, 1>(a, s);                         // 128 x 16
+            else launch_mfma<4, 1, 1, 1>(a, s);                                       //  64 x 16
+        }
+    } else {
+        const size_t total = (size_t)a.M * g.Co;
+        hipLaunchKernelGGL(conv_direct, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cib, g.Cob, total);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace small

@@ -1,0 +1,353 @@
+// C-ABI layer of libsmall_hip (see include/small.h for the contract of every entry point).
+// Everything here is host code: argument validation, shape arithmetic, the layer-table walk.
+#include "../../include/small.h"
+#include "small_internal.h"
+
+#include <limits.h>
+#include <string.h>
+
+using namespace small;
+
+namespace {
+
+constexpr int kMaxBlock = 64;
+constexpr size_t kMaxElems = (size_t)INT_MAX;   // kernels index a tensor with 32-bit element offsets
+constexpr size_t kSlotAlign = 256;
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline int from_hip(hipError_t e) { return e == hipSuccess ? SMALL_OK : SMALL_ERR_LAUNCH; }
+
+inline bool overlap(const void *a, size_t na, const void *b, size_t nb)
+{
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb * sizeof(float) && b0 < a0 + na * sizeof(float);
+}
+
+// elems = product of the dims, or 0 when any dim is non-positive or the product exceeds kMaxElems
+size_t elems(int a, int b, int c, int d)
+{
+    if (a <= 0 || b <= 0 || c <= 0 || d <= 0) return 0;
+    size_t p = (size_t)a;
+    const int rest[3] = {b, c, d};
+    for (int v : rest) {
+        if (p > kMaxElems / (size_t)v) return 0;
+        p *= (size_t)v;
+    }
+    return p;
+}
+
+int check_block(int C, int Cb)
+{
+    if (C <= 0 || Cb <= 0) return SMALL_ERR_SHAPE;
+    if (Cb > kMaxBlock) return SMALL_ERR_BLOCK;
+    if (C % Cb) return SMALL_ERR_SHAPE;
+    return SMALL_OK;
+}
+
+// Fills the geometry of a windowed layer and validates it. Cob/Co may equal Cib/Ci (pool, depthwise).
+int window_geom(LayerGeom &g, int N, int Ci, int Co, int H, int W, int kh, int kw, int stride, small_pad pad, int Cib,
+                int Cob, size_t *in_elems, size_t *out_elems)
+{
+    if (N <= 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0) return SMALL_ERR_SHAPE;
+    if (pad.t < 0 || pad.b < 0 || pad.l < 0 || pad.r < 0) return SMALL_ERR_SHAPE;
+    int rc = check_block(Ci, Cib);
+    if (rc) return rc;
+    rc = check_block(Co, Cob);
+    if (rc) return rc;
+    // a window row/column that lies entirely in the padding would make empty reductions possible
+    if (pad.t >= kh || pad.b >= kh || pad.l >= kw || pad.r >= kw) return SMALL_ERR_SHAPE;
+    const int Ho = small_out_dim(H, kh, stride, pad.t, pad.b), Wo = small_out_dim(W, kw, stride, pad.l, pad.r);
+    if (Ho <= 0 || Wo <= 0) return SMALL_ERR_SHAPE;
+    *in_elems = elems(N, Ci, H, W);
+    *out_elems = elems(N, Co, Ho, Wo);
+    if (!*in_elems || !*out_elems) return SMALL_ERR_SHAPE;
+    g.N = N; g.H = H; g.W = W; g.Ho = Ho; g.Wo = Wo; g.Ci = Ci; g.Co = Co; g.Cib = Cib; g.Cob = Cob;
+    g.kh = kh; g.kw = kw; g.stride = stride; g.pt = pad.t; g.pl = pad.l;
+    return SMALL_OK;
+}
+
+struct ConvPlan { LayerGeom g; size_t in_elems, out_elems, filt_elems; };
+
+int plan_conv(ConvPlan &p, int N, int Ci, int Co, int H, int W, int kh, int kw, int stride, small_pad pad, int Cib,
+              int Cob)
+{
+    int rc = window_geom(p.g, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob, &p.in_elems, &p.out_elems);
+    if (rc) return rc;
+    p.filt_elems = elems(Co, Ci, kh, kw);
+    return p.filt_elems ? SMALL_OK : SMALL_ERR_SHAPE;
+}
+
+int run_conv(const float *in, const float *filt, float *out, const ConvPlan &p, int epilogue, hipStream_t s)
+{
+    if (!in || !filt || !out) return SMALL_ERR_NULL;
+    if (overlap(in, p.in_elems, out, p.out_elems) || overlap(filt, p.filt_elems, out, p.out_elems)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_conv(in, filt, out, p.g, epilogue, s));
+}
+
+}  // namespace
+
+extern "C" {
+
+int small_out_dim(int in, int k, int stride, int pad_lo, int pad_hi)
+{
+    if (in <= 0 || k <= 0 || stride <= 0 || pad_lo < 0 || pad_hi < 0) return 0;
+    const long t = (long)in + pad_lo + pad_hi - k;
+    if (t < 0) return 0;
+    return (int)(t / stride) + 1;
+}
+
+const char *small_strerror(int code)
+{
+    switch (code) {
+        case SMALL_OK: return "ok";
+        case SMALL_ERR_NULL: return "null pointer";
+        case SMALL_ERR_SHAPE: return "bad shape (non-positive dim, window does not fit, C % Cb != 0, or tensor too large)";
+        case SMALL_ERR_BLOCK: return "channel block size has no kernel (Cb > 64)";
+        case SMALL_ERR_ALIAS: return "input and output overlap";
+        case SMALL_ERR_LAUNCH: return "HIP launch failed";
+        case SMALL_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case SMALL_ERR_LAYER: return "malformed layer table";
+        default: return "unknown error";
+    }
+}
+
+int small_pack(const float *nchw, float *blocked, int N, int C, int H, int W, int Cb, void *stream)
+{
+    if (!nchw || !blocked) return SMALL_ERR_NULL;
+    if (int rc = check_block(C, Cb)) return rc;
+    const size_t n = elems(N, C, H, W);
+    if (!n) return SMALL_ERR_SHAPE;
+    if (overlap(nchw, n, blocked, n)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_pack(nchw, blocked, N, C, H, W, Cb, false, as_stream(stream)));
+}
+
+int small_unpack(const float *blocked, float *nchw, int N, int C, int H, int W, int Cb, void *stream)
+{
+    if (!nchw || !blocked) return SMALL_ERR_NULL;
+    if (int rc = check_block(C, Cb)) return rc;
+    const size_t n = elems(N, C, H, W);
+    if (!n) return SMALL_ERR_SHAPE;
+    if (overlap(nchw, n, blocked, n)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_pack(blocked, nchw, N, C, H, W, Cb, true, as_stream(stream)));
+}
+
+int small_pack_filter(const float *oihw, float *blocked, int Co, int Ci, int kh, int kw, int Cob, int Cib, void *stream)
+{
+    if (!oihw || !blocked) return SMALL_ERR_NULL;
+    if (int rc = check_block(Co, Cob)) return rc;
+    if (int rc = check_block(Ci, Cib)) return rc;
+    const size_t n = elems(Co, Ci, kh, kw);
+    if (!n) return SMALL_ERR_SHAPE;
+    if (overlap(oihw, n, blocked, n)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_pack_filter(oihw, blocked, Co, Ci, kh, kw, Cob, Cib, as_stream(stream)));
+}
+
+int small_pack_dw_filter(const float *c1hw, float *blocked, int C, int kh, int kw, int Cb, void *stream)
+{
+    // [C][1][kh][kw] -> [C/Cb][kh][kw][Cb] is the general filter layout with one input channel per filter
+    return small_pack_filter(c1hw, blocked, C, 1, kh, kw, Cb, 1, stream);
+}
+
+int small_conv2d(const float *in, const float *filt, float *out, int N, int Ci, int Co, int H, int W, int kh, int kw,
+                 int stride, small_pad pad, int Cib, int Cob, void *stream)
+{
+    ConvPlan p;
+    if (int rc = plan_conv(p, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob)) return rc;
+    return run_conv(in, filt, out, p, EPI_NONE, as_stream(stream));
+}
+
+int small_dwconv2d(const float *in, const float *filt, float *out, int N, int C, int H, int W, int kh, int kw,
+                   int stride, small_pad pad, int Cb, void *stream)
+{
+    LayerGeom g;
+    size_t ni, no;
+    if (int rc = window_geom(g, N, C, C, H, W, kh, kw, stride, pad, Cb, Cb, &ni, &no)) return rc;
+    if (!in || !filt || !out) return SMALL_ERR_NULL;
+    if (overlap(in, ni, out, no) || overlap(filt, (size_t)C * kh * kw, out, no)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_dwconv(in, filt, out, g, as_stream(stream)));
+}
+
+int small_pool2d(const float *in, float *out, int N, int C, int H, int W, int kh, int kw, int stride, small_pad pad,
+                 int Cb, int mode, void *stream)
+{
+    LayerGeom g;
+    size_t ni, no;
+    if (mode != SMALL_POOL_MAX && mode != SMALL_POOL_AVG) return SMALL_ERR_SHAPE;
+    if (int rc = window_geom(g, N, C, C, H, W, kh, kw, stride, pad, Cb, Cb, &ni, &no)) return rc;
+    if (!in || !out) return SMALL_ERR_NULL;
+    if (overlap(in, ni, out, no)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_pool(in, out, g, mode, as_stream(stream)));
+}
+
+int small_relu(const float *in, float *out, size_t n_elems, void *stream)
+{
+    if (!in || !out) return SMALL_ERR_NULL;
+    if (n_elems > (size_t)1 << 40) return SMALL_ERR_SHAPE;
+    if (in != out && overlap(in, n_elems, out, n_elems)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_relu(in, out, n_elems, as_stream(stream)));
+}
+
+int small_add(const float *a, const float *b, float *out, size_t n_elems, void *stream)
+{
+    if (!a || !b || !out) return SMALL_ERR_NULL;
+    if (n_elems > (size_t)1 << 40) return SMALL_ERR_SHAPE;
+    if ((a != out && overlap(a, n_elems, out, n_elems)) || (b != out && overlap(b, n_elems, out, n_elems)))
+        return SMALL_ERR_ALIAS;
+    return from_hip(launch_add(a, b, out, n_elems, as_stream(stream)));
+}
+
+int small_dense(const float *in, const float *filt, float *out, int N, int Ci, int Co, int Cib, int Cob, void *stream)
+{
+    // Full reduction on a 1x1 image == 1x1 convolution over N "pixels" (one per image).
+    ConvPlan p;
+    const small_pad nopad = {0, 0, 0, 0};
+    if (int rc = plan_conv(p, N, Ci, Co, 1, 1, 1, 1, 1, nopad, Cib, Cob)) return rc;
+    return run_conv(in, filt, out, p, EPI_NONE, as_stream(stream));
+}
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------------
+// Layer tables
+namespace {
+
+struct Shape { int C, H, W, Cb; bool set; };
+
+struct NetPlan {
+    size_t slot_elems[SMALL_MAX_SLOTS];
+    size_t slot_off[SMALL_MAX_SLOTS];
+    size_t bytes;
+    size_t out_elems;   // largest tensor written to SMALL_BUF_OUT
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Walks the table once: validates every layer, tracks the shape held by every logical buffer and
+// the largest tensor written to every workspace slot. With `run` set, launches as it goes (the
+// caller has already walked the table once without `run`, so no error can occur midway).
+int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &plan, bool run, const float *in_blocked,
+         float *out_blocked, char *ws, hipStream_t s)
+{
+    if (!L) return SMALL_ERR_NULL;
+    if (nL <= 0 || N <= 0 || C0 <= 0 || H0 <= 0 || W0 <= 0) return SMALL_ERR_SHAPE;
+    Shape shp[SMALL_MAX_SLOTS + 2];
+    memset(shp, 0, sizeof(shp));
+    auto idx = [](int id) { return id + 2; };   // OUT(-2) -> 0, IN(-1) -> 1, slot k -> k + 2
+    auto valid_id = [](int id) { return id >= SMALL_BUF_OUT && id < SMALL_MAX_SLOTS; };
+    auto ptr = [&](int id) -> float * {
+        if (id == SMALL_BUF_IN) return const_cast<float *>(in_blocked);
+        if (id == SMALL_BUF_OUT) return out_blocked;
+        return reinterpret_cast<float *>(ws + plan.slot_off[id]);
+    };
+    if (!run) memset(&plan, 0, sizeof(plan));
+    shp[idx(SMALL_BUF_IN)] = Shape{C0, H0, W0, L[0].Cib, true};
+    if (check_block(C0, L[0].Cib)) return SMALL_ERR_SHAPE;
+
+    for (int i = 0; i < nL; ++i) {
+        const small_layer &l = L[i];
+        if (!valid_id(l.src) || !valid_id(l.dst) || l.dst == SMALL_BUF_IN) return SMALL_ERR_LAYER;
+        const Shape a = shp[idx(l.src)];
+        if (!a.set || a.C != l.Ci || a.Cb != l.Cib) return SMALL_ERR_LAYER;
+        Shape o = a;
+        const size_t in_elems = elems(N, a.C, a.H, a.W);
+        int rc = SMALL_OK;
+        switch (l.op) {
+            case SMALL_OP_CONV:
+            case SMALL_OP_DENSE: {
+                ConvPlan p;
+                const bool dense = l.op == SMALL_OP_DENSE;
+                if (dense && (l.kh != a.H || l.kw != a.W)) return SMALL_ERR_LAYER;
+                const small_pad nopad = {0, 0, 0, 0};
+                rc = plan_conv(p, N, l.Ci, l.Co, a.H, a.W, l.kh, l.kw, dense ? 1 : l.stride, dense ? nopad : l.pad,
+                               l.Cib, l.Cob);
+                if (rc) return rc;
+                if (l.dst == l.src) return SMALL_ERR_ALIAS;
+                if (!l.filt) return SMALL_ERR_NULL;
+                o = Shape{l.Co, p.g.Ho, p.g.Wo, l.Cob, true};
+                if (run) rc = run_conv(ptr(l.src), l.filt, ptr(l.dst), p, EPI_NONE, s);
+                break;
+            }
+            case SMALL_OP_DWCONV:
+            case SMALL_OP_MAXPOOL:
+            case SMALL_OP_AVGPOOL: {
+                LayerGeom g;
+                size_t ni, no;
+                if (l.Co != l.Ci || l.Cob != l.Cib) return SMALL_ERR_LAYER;
+                rc = window_geom(g, N, l.Ci, l.Ci, a.H, a.W, l.kh, l.kw, l.stride, l.pad, l.Cib, l.Cib, &ni, &no);
+                if (rc) return rc;
+                if (l.dst == l.src) return SMALL_ERR_ALIAS;
+                if (l.op == SMALL_OP_DWCONV && !l.filt) return SMALL_ERR_NULL;
+                o = Shape{l.Ci, g.Ho, g.Wo, l.Cib, true};
+                if (run) {
+                    if (l.op == SMALL_OP_DWCONV) rc = from_hip(launch_dwconv(ptr(l.src), l.filt, ptr(l.dst), g, s));
+                    else rc = from_hip(launch_pool(ptr(l.src), ptr(l.dst), g,
+                                                   l.op == SMALL_OP_MAXPOOL ? SMALL_POOL_MAX : SMALL_POOL_AVG, s));
+                }
+                break;
+            }
+            case SMALL_OP_RELU:
+                if (l.Co != l.Ci || l.Cob != l.Cib) return SMALL_ERR_LAYER;
+                if (run) rc = from_hip(launch_relu(ptr(l.src), ptr(l.dst), in_elems, s));
+                break;
+            case SMALL_OP_ADD: {
+                if (l.Co != l.Ci || l.Cob != l.Cib || !valid_id(l.src2)) return SMALL_ERR_LAYER;
+                const Shape b = shp[idx(l.src2)];
+                if (!b.set || b.C != a.C || b.H != a.H || b.W != a.W || b.Cb != a.Cb) return SMALL_ERR_LAYER;
+                if (run) rc = from_hip(launch_add(ptr(l.src), ptr(l.src2), ptr(l.dst), in_elems, s));
+                break;
+            }
+            default:
+                return SMALL_ERR_LAYER;
+        }
+        if (rc) return rc;
+        const size_t out_elems = elems(N, o.C, o.H, o.W);
+        if (!out_elems) return SMALL_ERR_SHAPE;
+        shp[idx(l.dst)] = o;
+        if (!run && l.dst >= 0 && out_elems > plan.slot_elems[l.dst]) plan.slot_elems[l.dst] = out_elems;
+        if (!run && l.dst == SMALL_BUF_OUT && out_elems > plan.out_elems) plan.out_elems = out_elems;
+    }
+    if (!run) {
+        size_t off = 0;
+        for (int k = 0; k < SMALL_MAX_SLOTS; ++k) {
+            plan.slot_off[k] = off;
+            off += align_up(plan.slot_elems[k] * sizeof(float), kSlotAlign);
+        }
+        plan.bytes = off;
+    }
+    return SMALL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int small_network_workspace(const small_layer *layers, int n_layers, int N, int C0, int H0, int W0, size_t *bytes)
+{
+    if (!bytes) return SMALL_ERR_NULL;
+    NetPlan plan;
+    const int rc = walk(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr);
+    if (rc) return rc;
+    *bytes = plan.bytes;
+    return SMALL_OK;
+}
+
+int small_network_run(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
+                      void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream)
+{
+    NetPlan plan;
+    int rc = walk(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr);
+    if (rc) return rc;
+    if (!in_blocked || !out_blocked) return SMALL_ERR_NULL;
+    if (plan.bytes && !workspace) return SMALL_ERR_NULL;
+    if (workspace_bytes < plan.bytes || ((uintptr_t)workspace % kSlotAlign)) return SMALL_ERR_WORKSPACE;
+    const size_t in_elems = elems(N, C0, H0, W0), ws_elems = plan.bytes / sizeof(float);
+    if (overlap(in_blocked, in_elems, out_blocked, plan.out_elems) ||
+        (plan.bytes && (overlap(in_blocked, in_elems, workspace, ws_elems) ||
+                        overlap(out_blocked, plan.out_elems, workspace, ws_elems))))
+        return SMALL_ERR_ALIAS;
+    return walk(layers, n_layers, N, C0, H0, W0, plan, true, in_blocked, out_blocked, static_cast<char *>(workspace),
+                as_stream(stream));
+}
+
+}  // extern "C"

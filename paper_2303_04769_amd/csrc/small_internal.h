@@ -1,0 +1,37 @@
+// Internal declarations shared by the HIP translation units of libsmall_hip (gfx950 only).
+// Host-side launchers validate nothing: the C-ABI layer in small_api.hip has already
+// checked shapes, block sizes and aliasing before any launcher is called.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace small {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Geometry of one windowed layer on the blocked layout (conv, depthwise, pooling).
+struct LayerGeom {
+    int N, H, W, Ho, Wo;
+    int Ci, Co;          // channels (pool / depthwise: Ci == Co)
+    int Cib, Cob;        // channel blocks in memory
+    int kh, kw, stride, pt, pl;
+};
+
+// Epilogue fused into the convolution's STORE phase (the paper's "abstract fused layer" direction).
+enum : int { EPI_NONE = 0, EPI_RELU = 1 };
+
+hipError_t launch_relu(const float *in, float *out, size_t n, hipStream_t s);
+hipError_t launch_add(const float *a, const float *b, float *out, size_t n, hipStream_t s);
+
+hipError_t launch_pack(const float *nchw, float *blk, int N, int C, int H, int W, int Cb, bool unpack, hipStream_t s);
+hipError_t launch_pack_filter(const float *oihw, float *blk, int Co, int Ci, int kh, int kw, int Cob, int Cib,
+                              hipStream_t s);
+
+hipError_t launch_dwconv(const float *in, const float *filt, float *out, const LayerGeom &g, hipStream_t s);
+hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode, hipStream_t s);
+
+hipError_t launch_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue,
+                       hipStream_t s);
+
+}  // namespace small

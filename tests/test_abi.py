@@ -1,0 +1,90 @@
+"""The C-ABI library loads and exports every symbol include/small.h declares (no GPU needed:
+only host-side entry points are called here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2303_04769_amd import binding
+    return binding.load()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "small.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(small_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2303_04769_amd import binding
+    names = _declared()
+    assert len(names) == 14 and set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_out_dim_and_strerror(lib):
+    assert lib.small_out_dim(32, 3, 1, 1, 1) == 32
+    assert lib.small_out_dim(56, 3, 2, 0, 0) == 27
+    assert lib.small_out_dim(49, 10, 2, 4, 5) == 25
+    assert lib.small_out_dim(2, 3, 1, 0, 0) == 0
+    assert lib.small_strerror(0) == b"ok"
+    assert b"overlap" in lib.small_strerror(4)
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    from paper_2303_04769_amd.binding import small_pad
+    pad = small_pad(1, 1, 1, 1)
+    fake = C.c_void_p(0x1000)     # never dereferenced: every call below fails validation first
+    assert lib.small_relu(None, fake, 16, None) == 1
+    assert lib.small_conv2d(fake, fake, fake, 1, 16, 16, 8, 8, 3, 3, 1, pad, 16, 16, None) == 4      # alias
+    assert lib.small_conv2d(fake, fake, C.c_void_p(0x10000000), 1, 16, 24, 8, 8, 3, 3, 1, pad, 16, 16, None) == 2
+    assert lib.small_conv2d(fake, fake, C.c_void_p(0x10000000), 1, 128, 128, 8, 8, 3, 3, 1, pad, 128, 16, None) == 3
+    assert lib.small_conv2d(fake, fake, C.c_void_p(0x10000000), 0, 16, 16, 8, 8, 3, 3, 1, pad, 16, 16, None) == 2
+    assert lib.small_pool2d(fake, C.c_void_p(0x10000000), 1, 16, 2, 2, 3, 3, 1, small_pad(0, 0, 0, 0), 16, 0, None) == 2
+    assert lib.small_pool2d(fake, C.c_void_p(0x10000000), 1, 16, 8, 8, 3, 3, 1, pad, 16, 7, None) == 2
+    assert lib.small_pack(fake, fake, 1, 16, 4, 4, 16, None) == 4
+
+
+def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
+    """Section 'Memory Usage Comparison': only the largest buffers that are live together are
+    allocated. The printed autoencoder row pins the formula bytes = 4 * (params + largest in+out):
+    4 * (133120 + 2*128) B = 0.5088 MiB, printed as 0.509."""
+    import workloads as WL
+    from paper_2303_04769_amd import binding as B
+    g = golden("paper_constants.txt")
+    assert round(4 * (g["params"][3] + 2 * 128) / 2**20, 3) == g["memory_small_fp32_mib"][0]
+
+    def ws(net, N):
+        table = B.make_layer_table(net.layers, [None] * len(net.wshapes))
+        for k, L in enumerate(net.layers):      # validation wants non-NULL filters; never dereferenced
+            if L.w is not None:
+                table[k].filt = 0x1000
+        return B.small_network_workspace(table, N, net.C0, net.H0, net.W0)
+
+    a = WL.audio_cnn()
+    # chain network: two ping-pong slots, each as large as the largest tensor written to it
+    assert ws(a, 1) == 2 * 64 * 25 * 5 * 4
+    assert ws(a, 7) == 2 * 7 * 64 * 25 * 5 * 4
+    r = WL.residual_cnn()
+    # residual block: x, a, b live together (+ the projected shortcut from stage 2 on)
+    sizes = {}
+    for L in r.layers:
+        if L.dst >= 0:
+            sizes[L.dst] = max(sizes.get(L.dst, 0), L.Co * L.Ho * L.Wo * 4)
+    assert ws(r, 1) == sum((v + 255) // 256 * 256 for v in sizes.values())
+    assert ws(r, 1) <= 4 * 16 * 32 * 32 * 4
+    # malformed tables
+    t = B.make_layer_table(a.layers, [None] * len(a.wshapes))
+    assert lib.small_network_workspace(t, len(t), 1, a.C0, a.H0, a.W0, C.byref(C.c_size_t())) == 1   # NULL filter
+    for k, L in enumerate(a.layers):
+        if L.w is not None:
+            t[k].filt = 0x1000
+    t[3].Cib = 8
+    assert lib.small_network_workspace(t, len(t), 1, a.C0, a.H0, a.W0, C.byref(C.c_size_t())) == 7

@@ -1,0 +1,221 @@
+"""GPU parity: every layer of the hot path, through the C ABI, against the CPU oracle.
+
+Bit-exact for pack / unpack / max-pool / ReLU / add; |gpu - ref| <= 1e-4 (sqrt(K) max|ref| + 1)
+for conv (K = Ci kh kw), depthwise and avg-pool (K = kh kw) and dense (K = Ci)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2303_04769_amd as S
+from oracle import oracle as O
+from gpu_util import DEV, Guarded, assert_bits, assert_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _blk(C):
+    return min(16, C)
+
+
+# ------------------------------------------------------------------ layouts
+
+@pytest.mark.parametrize("N,C,H,W,Cb", [(2, 32, 5, 7, 16), (1, 3, 96, 96, 3), (3, 8, 9, 13, 8), (2, 1, 49, 10, 1),
+                                         (1, 64, 1, 1, 16), (2, 10, 1, 1, 10), (1, 48, 17, 9, 16), (1, 12, 3, 70, 4)])
+def test_pack_unpack_bit_exact(N, C, H, W, Cb):
+    rng = np.random.default_rng(N * 1000 + C)
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    g = Guarded(x.size)
+    S.small_pack(dev(x), g.t, N, C, H, W, Cb)
+    got = g.check()
+    assert_bits(got, O.pack(x, Cb), "pack")
+    g2 = Guarded(x.size)
+    S.small_unpack(dev(got), g2.t, N, C, H, W, Cb)
+    assert_bits(g2.check().reshape(x.shape), x, "unpack")
+
+
+def test_pack_filters_bit_exact():
+    rng = np.random.default_rng(3)
+    for (Co, Ci, kh, kw, Cob, Cib) in [(32, 48, 3, 3, 16, 16), (16, 3, 3, 3, 16, 3), (64, 1, 10, 4, 16, 1),
+                                       (10, 64, 1, 1, 10, 16), (16, 8, 1, 1, 16, 8)]:
+        w = rng.standard_normal((Co, Ci, kh, kw)).astype(np.float32)
+        g = Guarded(w.size)
+        S.small_pack_filter(dev(w), g.t, Co, Ci, kh, kw, Cob, Cib)
+        assert_bits(g.check(), O.pack_filter(w, Cob, Cib), "pack_filter")
+    for (C, Cb) in [(32, 16), (8, 8), (3, 3)]:
+        w = rng.standard_normal((C, 1, 3, 3)).astype(np.float32)
+        g = Guarded(w.size)
+        S.small_pack_dw_filter(dev(w), g.t, C, 3, 3, Cb)
+        assert_bits(g.check(), O.pack_dw_filter(w, Cb), "pack_dw_filter")
+
+
+# ------------------------------------------------------------------ single element
+
+@pytest.mark.parametrize("n", [1, 3, 4, 1023, 4096, 16384, 100003])
+def test_relu_add_bit_exact(n):
+    rng = np.random.default_rng(n)
+    a = rng.standard_normal(n).astype(np.float32)
+    b = rng.standard_normal(n).astype(np.float32)
+    special = np.array([-np.inf, -2.5, -0.0, 0.0, 1e-45, -1e-45, 3.0, np.inf, np.nan], np.float32)
+    a[:min(n, special.size)] = special[:n]
+    g = Guarded(n)
+    S.small_relu(dev(a), g.t, n)
+    assert_bits(g.check(), O.relu(a), "relu")
+    g = Guarded(n)
+    a2 = np.nan_to_num(a, nan=1.0, posinf=2.0, neginf=-2.0)
+    S.small_add(dev(a2), dev(b), g.t, n)
+    assert_bits(g.check(), O.add(a2, b), "add")
+    # in place, and from an unaligned offset (scalar path)
+    g = Guarded(n + 1)
+    g.t[1:].copy_(dev(a))
+    v = g.t[1:]
+    S.small_relu(v, v, n)
+    assert_bits(g.check()[1:], O.relu(a), "relu in place, unaligned")
+
+
+# ------------------------------------------------------------------ convolution
+
+def run_conv(x, w, stride, pad, Cib=None, Cob=None):
+    N, Ci, H, W = x.shape
+    Co, _, kh, kw = w.shape
+    Cib, Cob = Cib or _blk(Ci), Cob or _blk(Co)
+    xb, wb = dev(O.pack(x, Cib)), dev(O.pack_filter(w, Cob, Cib))
+    Ho, Wo = O.out_dim(H, kh, stride, pad[0], pad[1]), O.out_dim(W, kw, stride, pad[2], pad[3])
+    g = Guarded(N * Co * Ho * Wo)
+    S.small_conv2d(xb, wb, g.t, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob)
+    return O.unpack(g.check(), (N, Co, Ho, Wo), Cob)
+
+
+CONV_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad
+    (1, 16, 16, 32, 32, 3, 3, 1, (1, 1, 1, 1)),      # the single-layer workload
+    (3, 32, 48, 13, 11, 3, 3, 1, (1, 1, 1, 1)),      # ragged pixel tail, Co not a power of two
+    (2, 64, 64, 9, 9, 1, 1, 1, (0, 0, 0, 0)),
+    (2, 16, 32, 16, 16, 1, 1, 2, (0, 0, 0, 0)),      # projection shortcut
+    (2, 16, 32, 32, 32, 3, 3, 2, (0, 1, 0, 1)),      # 'same' stride 2
+    (1, 32, 16, 7, 9, 5, 3, 2, (2, 2, 1, 1)),        # odd window
+    (2, 16, 16, 6, 6, 3, 3, 1, (0, 0, 0, 0)),        # no padding
+    (4, 256, 128, 7, 7, 3, 3, 1, (1, 1, 1, 1)),      # tiles straddle images, 128-wide channel tile
+    (2, 1, 64, 49, 10, 10, 4, 2, (4, 5, 1, 1)),      # generic path: Ci = 1
+    (2, 3, 16, 32, 32, 3, 3, 1, (1, 1, 1, 1)),       # generic path: Ci = 3
+    (1, 3, 8, 96, 96, 3, 3, 2, (0, 1, 0, 1)),        # generic path: 8-channel output block
+    (2, 8, 16, 24, 24, 1, 1, 1, (0, 0, 0, 0)),       # generic path: 8-channel input block
+    (5, 64, 10, 1, 1, 1, 1, 1, (0, 0, 0, 0)),        # generic path: dense-like head
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv2d(case):
+    N, Ci, Co, H, W, kh, kw, s, pad = case
+    rng = np.random.default_rng(abs(hash(case)) % 2**31)
+    x = (rng.random((N, Ci, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    w = (rng.random((Co, Ci, kh, kw), dtype=np.float32) * 2 - 1).astype(np.float32)
+    got = run_conv(x, w, s, pad)
+    assert_close(got, O.conv2d(x, w, s, pad), Ci * kh * kw, f"conv {case}")
+
+
+def test_conv2d_large_tiles():
+    """Enough pixels that the 128-pixel tiles are chosen (>= 256 workgroups) for every channel-tile width."""
+    rng = np.random.default_rng(77)
+    for Ci, Co, N, H in [(32, 128, 18, 45), (16, 64, 10, 58), (16, 32, 9, 61), (16, 16, 9, 61)]:
+        x = (rng.random((N, Ci, H, H), dtype=np.float32) * 2 - 1).astype(np.float32)
+        w = (rng.random((Co, Ci, 3, 3), dtype=np.float32) * 2 - 1).astype(np.float32)
+        got = run_conv(x, w, 1, (1, 1, 1, 1))
+        assert_close(got, O.conv2d(x, w, 1, (1, 1, 1, 1)), Ci * 9, f"conv large {Ci}->{Co}")
+
+
+def test_conv_identity_filter_is_exact():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((2, 32, 10, 12)).astype(np.float32)
+    w = np.zeros((32, 32, 3, 3), np.float32)
+    w[np.arange(32), np.arange(32), 1, 1] = 1
+    assert_bits(run_conv(x, w, 1, (1, 1, 1, 1)), x, "delta filter")
+
+
+def test_dense():
+    rng = np.random.default_rng(6)
+    for N, Ci, Co in [(7, 64, 10), (1, 256, 2), (33, 64, 12), (130, 128, 128), (3, 16, 16)]:
+        x = rng.standard_normal((N, Ci, 1, 1)).astype(np.float32)
+        w = rng.standard_normal((Co, Ci, 1, 1)).astype(np.float32)
+        Cib, Cob = _blk(Ci), _blk(Co)
+        g = Guarded(N * Co)
+        S.small_dense(dev(O.pack(x, Cib)), dev(O.pack_filter(w, Cob, Cib)), g.t, N, Ci, Co, Cib, Cob)
+        got = O.unpack(g.check(), (N, Co, 1, 1), Cob)
+        assert_close(got, O.dense(x, w), Ci, f"dense {N}x{Ci}->{Co}")
+
+
+# ------------------------------------------------------------------ depthwise / pooling
+
+DW_CASES = [  # N, C, H, W, k, stride, pad
+    (2, 32, 13, 11, 3, 1, (1, 1, 1, 1)),
+    (2, 64, 12, 12, 3, 2, (0, 1, 0, 1)),
+    (1, 8, 48, 48, 3, 2, (0, 1, 0, 1)),        # 8-channel block
+    (3, 128, 3, 3, 3, 2, (1, 1, 1, 1)),
+    (2, 64, 25, 5, 3, 1, (1, 1, 1, 1)),
+    (1, 16, 9, 9, 5, 1, (2, 2, 2, 2)),         # run-time window
+    (2, 3, 10, 10, 3, 1, (1, 1, 1, 1)),        # scalar path
+    (2, 256, 7, 7, 3, 1, (1, 1, 1, 1)),
+]
+
+
+@pytest.mark.parametrize("case", DW_CASES)
+def test_dwconv2d(case):
+    N, C, H, W, k, s, pad = case
+    rng = np.random.default_rng(abs(hash(case)) % 2**31)
+    x = (rng.random((N, C, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    w = (rng.random((C, 1, k, k), dtype=np.float32) * 2 - 1).astype(np.float32)
+    Cb = _blk(C)
+    ref = O.dwconv2d(x, w, s, pad)
+    g = Guarded(ref.size)
+    S.small_dwconv2d(dev(O.pack(x, Cb)), dev(O.pack_dw_filter(w, Cb)), g.t, N, C, H, W, k, k, s, pad, Cb)
+    assert_close(O.unpack(g.check(), ref.shape, Cb), ref, k * k, f"dw {case}")
+
+
+POOL_CASES = [  # N, C, H, W, kh, kw, stride, pad
+    (2, 32, 13, 11, 3, 3, 2, (0, 0, 0, 0)),
+    (1, 16, 56, 56, 3, 3, 2, (0, 0, 0, 0)),
+    (2, 48, 9, 9, 3, 3, 1, (1, 1, 1, 1)),
+    (2, 16, 8, 8, 2, 2, 2, (0, 0, 0, 0)),
+    (3, 64, 8, 8, 8, 8, 1, (0, 0, 0, 0)),      # global
+    (3, 256, 2, 2, 2, 2, 1, (0, 0, 0, 0)),     # global
+    (5, 64, 25, 5, 25, 5, 1, (0, 0, 0, 0)),    # global
+    (2, 8, 6, 6, 6, 6, 1, (0, 0, 0, 0)),       # global, 8-channel block
+    (2, 3, 7, 7, 3, 3, 2, (1, 1, 1, 1)),       # scalar path
+]
+
+
+@pytest.mark.parametrize("case", POOL_CASES)
+@pytest.mark.parametrize("mode", ["max", "avg"])
+def test_pool2d(case, mode):
+    N, C, H, W, kh, kw, s, pad = case
+    rng = np.random.default_rng(abs(hash(case)) % 2**31)
+    x = (rng.random((N, C, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    Cb = _blk(C)
+    ref = O.pool2d(x, (kh, kw), s, pad, mode)
+    g = Guarded(ref.size)
+    S.small_pool2d(dev(O.pack(x, Cb)), g.t, N, C, H, W, kh, kw, s, pad, Cb, S.POOL_MAX if mode == "max" else S.POOL_AVG)
+    got = O.unpack(g.check(), ref.shape, Cb)
+    if mode == "max":
+        assert_bits(got, ref, f"maxpool {case}")
+    else:
+        assert_close(got, ref, kh * kw, f"avgpool {case}")
+
+
+def test_maxpool_ties_and_nan_bit_exact():
+    x = np.zeros((1, 16, 4, 4), np.float32)
+    x[0, :, 0, 0], x[0, :, 0, 1] = -0.0, 0.0          # first seen is -0
+    x[0, :, 2, 2], x[0, :, 2, 3], x[0, :, 3, 2], x[0, :, 3, 3] = np.nan, -3.0, np.nan, -5.0
+    x[0, :, 0, 2], x[0, :, 0, 3], x[0, :, 1, 2], x[0, :, 1, 3] = 0.0, -0.0, -1.0, -2.0
+    x[0, :, 1, 0], x[0, :, 1, 1] = -0.0, -0.0
+    ref = O.pool2d(x, (2, 2), 2)
+    g = Guarded(ref.size)
+    S.small_pool2d(dev(O.pack(x, 16)), g.t, 1, 16, 4, 4, 2, 2, 2, (0, 0, 0, 0), 16, S.POOL_MAX)
+    assert_bits(O.unpack(g.check(), ref.shape, 16), ref, "maxpool specials")
+
+
+def test_errors_leave_output_untouched():
+    x = dev(np.ones(16 * 64, np.float32))
+    g = Guarded(16 * 64)
+    with pytest.raises(S.binding.SmallError):
+        S.small_conv2d(x, x, g.t, 1, 16, 24, 8, 8, 3, 3, 1, (1, 1, 1, 1), 16, 16)
+    with pytest.raises(S.binding.SmallError):
+        S.small_pool2d(x, x, 1, 16, 8, 8, 3, 3, 1, (1, 1, 1, 1), 16, S.POOL_MAX)
+    assert (g.check() == np.float32(-7.25e37)).all()

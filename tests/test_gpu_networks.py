@@ -1,0 +1,134 @@
+"""GPU parity for small_network_run on the four stand-in networks, and full-size sampled
+checks of the roofline sweep layers in the launch configuration the benchmark times."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2303_04769_amd as S
+import workloads as WL
+from oracle import oracle as O
+from gpu_util import DEV, Guarded, assert_bits, assert_close, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(net, x, ws):
+    N = x.shape[0]
+    pn = S.PackedNetwork(net, ws, DEV)
+    xb = pn.pack_input(dev(x))
+    g = Guarded(pn.out_elems(N))
+    pn.run(xb, g.t, N)
+    out = g.check()
+    L = net.layers[-1]
+    return O.unpack(out, (N, L.Co, L.Ho, L.Wo), L.Cob)
+
+
+def _maxK(net):
+    return max(L.Ci * L.kh * L.kw for L in net.layers if L.op in ("conv", "dense"))
+
+
+def test_single_conv_relu_workload():
+    net = WL.single_conv_relu()
+    x, ws = WL.network_tensors(net, 1, WL.BASE_SEED + 1)
+    got = _run(net, x, ws)
+    ref = O.relu(O.conv2d(x, ws[0], 1, (1, 1, 1, 1)))
+    assert_close(got, ref, 144, "conv+relu workload")
+    assert (got >= 0).all() and (got == 0).sum() > 1000
+
+
+@pytest.mark.parametrize("name,idx", [("residual_cnn", 2), ("dsep_cnn", 3), ("audio_cnn", 4)])
+@pytest.mark.parametrize("N", [1, 3])
+def test_networks_small_batch(name, idx, N):
+    net = getattr(WL, name)()
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + idx)
+    got = _run(net, x, ws).reshape(N, -1)
+    ref = O.run_network(net, x, ws)
+    assert_close(got, ref, _maxK(net), f"{name} N={N}")
+
+
+def test_dsep_variant_block1_stride1():
+    net = WL.dsep_cnn(1)
+    x, ws = WL.network_tensors(net, 2, WL.BASE_SEED + 3)
+    assert_close(_run(net, x, ws).reshape(2, -1), O.run_network(net, x, ws), _maxK(net), "dsep b1s1")
+
+
+@pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 256), ("dsep_cnn", 3, 256), ("audio_cnn", 4, 1024)])
+def test_networks_full_batch_sampled(name, idx, N):
+    """Full batch on the GPU; the oracle recomputes a sample of images one by one (images are independent)."""
+    net = getattr(WL, name)()
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + idx)
+    got = _run(net, x, ws).reshape(N, -1)
+    assert np.isfinite(got).all()
+    for n in (0, N // 3, N - 1):
+        ref = O.run_network(net, x[n:n + 1], ws)
+        assert_close(got[n:n + 1], ref, _maxK(net), f"{name} image {n} of {N}")
+
+
+def test_intermediate_layers_of_residual_cnn():
+    """Layer-by-layer: every intermediate compared with its own layer's K (src/dst bookkeeping included)."""
+    net = WL.residual_cnn()
+    x, ws = WL.network_tensors(net, 2, WL.BASE_SEED + 2)
+    _, trace = O.run_network(net, x, ws, return_all=True)
+    pn = S.PackedNetwork(net, ws, DEV)
+    xb = pn.pack_input(dev(x))
+    for upto in (1, 2, 4, 5, 7, 9, 12, 16):
+        sub = net.layers[:upto]
+        last = sub[-1]
+        saved = last.dst
+        last.dst = WL.nets.OUT
+        try:
+            table = S.make_layer_table(sub, pn.filters)
+            nbytes = S.small_network_workspace(table, 2, net.C0, net.H0, net.W0)
+            ws_t = torch.empty(max(nbytes, 256) // 4, dtype=torch.float32, device=DEV)
+            g = Guarded(2 * last.Co * last.Ho * last.Wo)
+            S.small_network_run(table, xb, g.t, ws_t, nbytes, 2, net.C0, net.H0, net.W0)
+            got = O.unpack(g.check(), (2, last.Co, last.Ho, last.Wo), last.Cob)
+        finally:
+            last.dst = saved
+        K = last.Ci * last.kh * last.kw if last.op == "conv" else 1
+        assert_close(got, trace[upto - 1], max(K, 1), f"residual_cnn after layer {upto} ({last.op})")
+
+
+# ------------------------------------------------------------------ full-size sweep layers (sampled)
+
+@pytest.mark.parametrize("C,H", WL.sweep_shapes()["conv"])
+@pytest.mark.parametrize("kind", ["conv3x3", "conv1x1", "dw3x3"])
+def test_sweep_layers_full_size_sampled(kind, C, H):
+    N = WL.SWEEP_N
+    rng = np.random.default_rng(WL.BASE_SEED + 5)
+    x = WL.uniform_pm1(rng, (N, C, H, H))
+    xb = torch.empty(x.size, dtype=torch.float32, device=DEV)
+    S.small_pack(dev(x), xb, N, C, H, H, 16)
+    g = Guarded(x.size)
+    if kind == "dw3x3":
+        w = WL.uniform_pm1(rng, (C, 1, 3, 3))
+        S.small_dwconv2d(xb, dev(O.pack_dw_filter(w, 16)), g.t, N, C, H, H, 3, 3, 1, (1, 1, 1, 1), 16)
+        K = 9
+        ref_fn = lambda xs: O.dwconv2d(xs, w, 1, (1, 1, 1, 1))
+    else:
+        k = 3 if kind == "conv3x3" else 1
+        p = (1, 1, 1, 1) if k == 3 else (0, 0, 0, 0)
+        w = WL.uniform_pm1(rng, (C, C, k, k))
+        S.small_conv2d(xb, dev(O.pack_filter(w, 16, 16)), g.t, N, C, C, H, H, k, k, 1, p, 16, 16)
+        K = C * k * k
+        ref_fn = lambda xs: O.conv2d(xs, w, 1, p)
+    got = O.unpack(g.check(), x.shape, 16)
+    for n in (0, 37, N - 1):
+        assert_close(got[n:n + 1], ref_fn(x[n:n + 1]), K, f"{kind} C={C} H={H} image {n}")
+
+
+def test_sweep_pool_relu_full_size():
+    N, (C, H) = WL.SWEEP_N, WL.sweep_shapes()["pool_relu"]
+    rng = np.random.default_rng(WL.BASE_SEED + 5)
+    x = WL.uniform_pm1(rng, (N, C, H, H))
+    xb = torch.empty(x.size, dtype=torch.float32, device=DEV)
+    S.small_pack(dev(x), xb, N, C, H, H, 16)
+    g = Guarded(x.size)
+    S.small_relu(xb, g.t, x.size)
+    got = O.unpack(g.check(), x.shape, 16)
+    assert_bits(got, O.relu(x), "relu full size")
+    g = Guarded(N * C * 27 * 27)
+    S.small_pool2d(xb, g.t, N, C, H, H, 3, 3, 2, (0, 0, 0, 0), 16, S.POOL_MAX)
+    got = O.unpack(g.check(), (N, C, 27, 27), 16)
+    for n in (0, 21, N - 1):
+        assert_bits(got[n:n + 1], O.pool2d(x[n:n + 1], (3, 3), 2), f"maxpool image {n}")
