@@ -1,0 +1,330 @@
+#!/usr/bin/env python3
+"""Benchmark of the SMaLL hot path on one MI355X.
+
+A step = one pass of the whole path over one batch of the residual CNN workload (batch 256,
+32x32x3 fp32 images, seeded synthetic): small_pack of the NCHW input (already resident in HBM)
+-> small_network_run (conv 3x3 / 1x1, ReLU, add, average pool, dense on the shared blocked
+layout) -> small_unpack of the logits. value = images/s.
+
+Also reported on the same JSON line:
+  roofline      the kernel with the largest share of the step (per-layer HIP-event timing of the
+                same launches through the per-layer entry points), algorithmic flops / duration;
+  sweep         the roofline layer sweep (batch 64, Cb = 16): conv GFLOP/s against the fp32 MFMA peak,
+                depthwise / max-pool / ReLU GB/s against the HBM peak, buffers rotated so that
+                at least 512 MB are touched between reuses of a buffer;
+  networks      images/s of the three stand-in networks at batch 1 and at their large batch;
+  cpu_baseline  the CPU oracle (as it stands) on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32 = 157.3e12     # MI355X dense fp32 matrix, flop/s
+PEAK_HBM = 8.0e12            # MI355X HBM3E, B/s
+ROTATE_BYTES = 512e6         # touched between reuses of a buffer in HBM-bound timings (> 256 MB Infinity Cache)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-networks", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the CPU-oracle sample")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2303_04769_amd as S
+    import workloads as WL
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    S.binding.load()
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def timed(fn, reps):
+        """Average seconds per call of fn over reps back-to-back launches between two events on the launch stream."""
+        a, b = ev(), ev()
+        a.record()
+        for r in range(reps):
+            fn(r)
+        b.record()
+        b.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps
+
+    # ------------------------------------------------------------------ the step
+    net = WL.residual_cnn()
+    N = args.batch
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 2)
+    pn = S.PackedNetwork(net, ws, dev)
+    x_d = torch.from_numpy(x).to(dev)
+    xb = torch.empty(x_d.numel(), dtype=torch.float32, device=dev)
+    last = net.layers[-1]
+    out_b = torch.empty(pn.out_elems(N), dtype=torch.float32, device=dev)
+    logits = torch.empty(pn.out_elems(N), dtype=torch.float32, device=dev)
+    pn.workspace(N)
+
+    def step(_=0):
+        S.small_pack(x_d, xb, N, net.C0, net.H0, net.W0, net.layers[0].Cib)
+        pn.run(xb, out_b, N)
+        S.small_unpack(out_b, logits, N, last.Co, 1, 1, last.Cob)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    value = N * args.steps / wall
+    assert torch.isfinite(logits).all()
+
+    # ------------------------------------------------------------------ per-layer timing of the same launches
+    slots = {}
+
+    def buf(L, which):
+        bid = getattr(L, which)
+        if bid == WL.nets.IN:
+            return xb
+        if bid == WL.nets.OUT:
+            return out_b
+        return slots[bid]
+
+    for L in net.layers:
+        if L.dst >= 0:
+            n_el = N * L.Co * L.Ho * L.Wo
+            if L.dst not in slots or slots[L.dst].numel() < n_el:
+                slots[L.dst] = torch.empty(n_el, dtype=torch.float32, device=dev)
+
+    def launch_layer(L):
+        src, dst = buf(L, "src"), buf(L, "dst")
+        f = pn.filters[L.w] if L.w is not None else None
+        if L.op == "conv":
+            S.small_conv2d(src, f, dst, N, L.Ci, L.Co, L.H, L.W, L.kh, L.kw, L.stride, L.pad, L.Cib, L.Cob)
+        elif L.op == "dw":
+            S.small_dwconv2d(src, f, dst, N, L.Ci, L.H, L.W, L.kh, L.kw, L.stride, L.pad, L.Cib)
+        elif L.op in ("maxpool", "avgpool"):
+            S.small_pool2d(src, dst, N, L.Ci, L.H, L.W, L.kh, L.kw, L.stride, L.pad, L.Cib,
+                           S.POOL_MAX if L.op == "maxpool" else S.POOL_AVG)
+        elif L.op == "relu":
+            S.small_relu(src, dst, N * L.Ci * L.H * L.W)
+        elif L.op == "add":
+            S.small_add(src, buf(L, "src2"), dst, N * L.Ci * L.H * L.W)
+        elif L.op == "dense":
+            S.small_dense(src, f, dst, N, L.Ci, L.Co, L.Cib, L.Cob)
+
+    def kernel_of(L):
+        if L.op in ("conv", "dense"):
+            kh, kw = (L.kh, L.kw) if L.op == "conv" else (1, 1)
+            return S.small_conv2d_kernel(N, L.Ci, L.Co, L.H if L.op == "conv" else 1, L.W if L.op == "conv" else 1,
+                                         kh, kw, L.stride, L.pad, L.Cib, L.Cob)
+        return L.op
+
+    prof_steps = max(10, min(args.steps, 50))
+    per_kernel = {}
+    for it in range(prof_steps + 3):
+        evs = []
+        for L in net.layers:
+            a, b = ev(), ev()
+            a.record()
+            launch_layer(L)
+            b.record()
+            evs.append((L, a, b))
+        torch.cuda.synchronize()
+        if it < 3:
+            continue
+        for L, a, b in evs:
+            k = per_kernel.setdefault(kernel_of(L), {"time": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
+            k["time"] += a.elapsed_time(b) * 1e-3
+            k["launches"] += 1
+            if L.op in ("conv", "dense"):
+                k["flops"] += 2.0 * N * L.Co * L.Ho * L.Wo * L.Ci * L.kh * L.kw
+            n_in, n_out = N * L.Ci * L.H * L.W, N * L.Co * L.Ho * L.Wo
+            k["bytes"] += 4.0 * (n_in * (2 if L.op == "add" else 1) + n_out)
+    dom_name, dom = max(per_kernel.items(), key=lambda kv: kv[1]["time"])
+    if dom["flops"] > 0:
+        achieved = dom["flops"] / dom["time"] / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 3), "peak": PEAK_MFMA_F32 / 1e12, "unit": "TFLOP/s",
+                    "frac": round(achieved * 1e12 / PEAK_MFMA_F32, 4)}
+    else:
+        achieved = dom["bytes"] / dom["time"] / 1e9
+        roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                    "frac": round(achieved * 1e9 / PEAK_HBM, 4)}
+    roofline.update({"kernel": dom_name, "avg_launch_us": round(dom["time"] / dom["launches"] * 1e6, 2),
+                     "launches_per_step": dom["launches"] // prof_steps,
+                     "share_of_layer_time": round(dom["time"] / sum(k["time"] for k in per_kernel.values()), 3),
+                     "traffic": _traffic(dom_name)})
+
+    result = {
+        "metric": "network images/s (residual CNN, batch %d); sweep: conv GFLOP/s + dw/pool GB/s vs roofline" % N,
+        "value": round(value, 1), "unit": "images/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "residual CNN 32x32x3, batch %d: pack + small_network_run + unpack" % N,
+                   "global_batch": N, "seed": WL.BASE_SEED + 2, "layers": len(net.layers),
+                   "gflop_per_step": round(2e-9 * net.macs_per_image() * N, 3)},
+        "event_ms_per_step": round(e0.elapsed_time(e1) / args.steps, 4),
+        "roofline": roofline,
+        "kernels": {k: {"avg_us": round(v["time"] / v["launches"] * 1e6, 2), "per_step": v["launches"] // prof_steps}
+                    for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1]["time"])},
+    }
+
+    # ------------------------------------------------------------------ roofline layer sweep
+    if not args.no_sweep:
+        result["sweep"] = sweep(S, WL, torch, np, dev, timed)
+        c = [r for r in result["sweep"] if r["layer"] == "conv3x3"]
+        best = max(c, key=lambda r: r["frac"])
+        result["roofline_sweep_conv3x3"] = {"bound": "mfma", "achieved": best["tflops"], "peak": PEAK_MFMA_F32 / 1e12,
+                                            "unit": "TFLOP/s", "frac": best["frac"], "shape": best["shape"],
+                                            "kernel": best["kernel"]}
+
+    # ------------------------------------------------------------------ networks
+    if not args.no_networks:
+        result["networks"] = networks(S, WL, torch, dev, timed)
+
+    # ------------------------------------------------------------------ CPU oracle beside it
+    if not args.no_cpu:
+        from oracle import oracle as O
+        cores = len(os.sched_getaffinity(0))
+        cores = min(cores, int(os.environ.get("OMP_NUM_THREADS", cores)))
+        used = O.set_threads(cores)
+        t = time.perf_counter()
+        O.run_network(net, x[:2], ws)
+        per_img = (time.perf_counter() - t) / 2
+        n_s = int(max(2, min(N, args.cpu_seconds / max(per_img, 1e-6))))
+        t = time.perf_counter()
+        ref = O.run_network(net, x[:n_s], ws)
+        dt = time.perf_counter() - t
+        got = logits[:n_s * last.Co].cpu().numpy().reshape(n_s, last.Co)
+        err = float(np.abs(got - ref).max())
+        result["cpu_baseline"] = {"value": round(n_s / dt, 2), "unit": "images/s", "cores": used, "kind": "oracle",
+                                  "sample": "first %d of the %d images of the same batch, %.1f s" % (n_s, N, dt),
+                                  "max_abs_diff_vs_gpu": err}
+    print(json.dumps(result))
+
+
+def _traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, if one covers it."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def sweep(S, WL, torch, np, dev, timed):
+    """Layer sweep at batch 64: every layer on its own, HBM-bound layers with rotated buffers."""
+    Nb = WL.SWEEP_N
+    rng = np.random.default_rng(WL.BASE_SEED + 5)
+    rows = []
+
+    def rand(n):
+        return (torch.rand(n, device=dev, dtype=torch.float32) * 2 - 1)
+
+    def best_of(fn, reps, trials=3):
+        for r in range(5):
+            fn(r)
+        ts = [timed(fn, reps) for _ in range(trials)]
+        return min(ts), statistics.median(ts)
+
+    for C, H in WL.sweep_shapes()["conv"]:
+        n_act = Nb * C * H * H
+        act_bytes = 8.0 * n_act
+        sets = max(2, int(-(-ROTATE_BYTES // act_bytes)))
+        ins = [rand(n_act) for _ in range(sets)]
+        outs = [torch.empty(n_act, device=dev, dtype=torch.float32) for _ in range(sets)]
+        for k, name in ((3, "conv3x3"), (1, "conv1x1")):
+            w = torch.from_numpy(WL.uniform_pm1(rng, (C * C * k * k,))).to(dev)   # already "blocked": random values
+            pad = (1, 1, 1, 1) if k == 3 else (0, 0, 0, 0)
+            fn = lambda r: S.small_conv2d(ins[r % sets], w, outs[r % sets], Nb, C, C, H, H, k, k, 1, pad, 16, 16)
+            tmin, tmed = best_of(fn, 30 if k == 3 else 100)
+            flops = 2.0 * Nb * C * H * H * C * k * k
+            byts = 4.0 * (2 * n_act + C * C * k * k)
+            rows.append({"layer": name, "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                         "us_median": round(tmed * 1e6, 2), "tflops": round(flops / tmin / 1e12, 2),
+                         "frac": round(flops / tmin / PEAK_MFMA_F32, 4), "gbs": round(byts / tmin / 1e9, 1),
+                         "frac_hbm": round(byts / tmin / PEAK_HBM, 4),
+                         "kernel": S.small_conv2d_kernel(Nb, C, C, H, H, k, k, 1, pad, 16, 16)})
+        wd = torch.from_numpy(WL.uniform_pm1(rng, (C * 9,))).to(dev)
+        fn = lambda r: S.small_dwconv2d(ins[r % sets], wd, outs[r % sets], Nb, C, H, H, 3, 3, 1, (1, 1, 1, 1), 16)
+        tmin, tmed = best_of(fn, 100)
+        byts = 4.0 * (2 * n_act + 9 * C)
+        rows.append({"layer": "dw3x3", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                     "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
+                     "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": sets})
+        del ins, outs
+    C, H = WL.sweep_shapes()["pool_relu"]
+    n_act = Nb * C * H * H
+    n_pool = Nb * C * 27 * 27
+    sets = 2
+    ins = [rand(n_act) for _ in range(sets)]
+    outs = [torch.empty(n_act, device=dev, dtype=torch.float32) for _ in range(sets)]
+    fn = lambda r: S.small_relu(ins[r % sets], outs[r % sets], n_act)
+    tmin, tmed = best_of(fn, 50)
+    rows.append({"layer": "relu", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                 "us_median": round(tmed * 1e6, 2), "gbs": round(8.0 * n_act / tmin / 1e9, 1),
+                 "frac": round(8.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": sets})
+    ins.append(rand(n_act))
+    fn = lambda r: S.small_pool2d(ins[r % 3], outs[r % sets], Nb, C, H, H, 3, 3, 2, (0, 0, 0, 0), 16, S.POOL_MAX)
+    tmin, tmed = best_of(fn, 50)
+    byts = 4.0 * (n_act + n_pool)
+    rows.append({"layer": "maxpool3x3s2", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                 "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
+                 "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": 3})
+    # pack / unpack of the largest activation (network boundary only)
+    fn = lambda r: S.small_pack(ins[r % 3], outs[r % sets], Nb, C, H, H, 16)
+    tmin, tmed = best_of(fn, 30)
+    rows.append({"layer": "pack", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                 "us_median": round(tmed * 1e6, 2), "gbs": round(8.0 * n_act / tmin / 1e9, 1),
+                 "frac": round(8.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": 3})
+    return rows
+
+
+def networks(S, WL, torch, dev, timed):
+    out = []
+    for name, idx, big in (("residual_cnn", 2, 256), ("dsep_cnn", 3, 256), ("audio_cnn", 4, 1024)):
+        net = getattr(WL, name)()
+        for N in (1, big):
+            x, ws = WL.network_tensors(net, N, WL.BASE_SEED + idx)
+            pn = S.PackedNetwork(net, ws, dev)
+            xb = pn.pack_input(torch.from_numpy(x).to(dev))
+            o = torch.empty(pn.out_elems(N), dtype=torch.float32, device=dev)
+            fn = lambda r: pn.run(xb, o, N)
+            for r in range(5):
+                fn(r)
+            ts = [timed(fn, 100) for _ in range(3)]
+            t = min(ts)
+            out.append({"network": name, "batch": N, "ms": round(t * 1e3, 4), "images_per_s": round(N / t, 1),
+                        "tflops": round(2.0 * net.macs_per_image() * N / t / 1e12, 3), "launches": len(net.layers)})
+    return out
+
+
+if __name__ == "__main__":
+    main()

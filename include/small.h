@@ -73,6 +73,12 @@ int small_pack_dw_filter(const float *c1hw, float *blocked, int C, int kh, int k
 int small_conv2d(const float *in, const float *filt, float *out, int N, int Ci, int Co, int H, int W, int kh,
                  int kw, int stride, small_pad pad, int Cib, int Cob, void *stream);
 
+/* Host only, enqueues nothing: the name of the kernel small_conv2d launches for this shape (for example
+ * "conv16_mfma<4,1,2,1>" = 4x1 wavefronts of 2x1 16x16 matrix-core tiles, or "conv_direct"), so that a
+ * profile's per-kernel rows can be matched to layers. Returns NULL when the arguments are invalid. */
+const char *small_conv2d_kernel(int N, int Ci, int Co, int H, int W, int kh, int kw, int stride, small_pad pad,
+                                int Cib, int Cob);
+
 /* ---- single-channel reduction with weights: depthwise convolution (Table 1 row "Single
  * Channel Reduction": F_C = 1, K = 1, G = I_C; Section 3.2 item 2).
  *   out[n,c,oh,ow] = sum_{y,x} in[n,c,oh*stride+y-pad.t, ow*stride+x-pad.l] * filt[c,y,x]. */

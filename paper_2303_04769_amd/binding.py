@@ -20,7 +20,7 @@ _OPS = {"conv": OP_CONV, "dw": OP_DWCONV, "maxpool": OP_MAXPOOL, "avgpool": OP_A
         "add": OP_ADD, "dense": OP_DENSE}
 
 EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "small_pack_filter",
-           "small_pack_dw_filter", "small_conv2d", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
+           "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
            "small_dense", "small_network_workspace", "small_network_run"]
 
 
@@ -61,6 +61,7 @@ def load():
         "small_pack_filter": (i, [p, p, i, i, i, i, i, i, p]),
         "small_pack_dw_filter": (i, [p, p, i, i, i, i, p]),
         "small_conv2d": (i, [p, p, p, i, i, i, i, i, i, i, i, small_pad, i, i, p]),
+        "small_conv2d_kernel": (C.c_char_p, [i, i, i, i, i, i, i, i, small_pad, i, i]),
         "small_dwconv2d": (i, [p, p, p, i, i, i, i, i, i, i, small_pad, i, p]),
         "small_pool2d": (i, [p, p, i, i, i, i, i, i, i, small_pad, i, i, p]),
         "small_relu": (i, [p, p, sz, p]),
@@ -128,6 +129,11 @@ def small_pack_dw_filter(c1hw, blocked, Cc, kh, kw, Cb, stream=None):
 def small_conv2d(inp, filt, out, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob, stream=None):
     _check(load().small_conv2d(_ptr(inp), _ptr(filt), _ptr(out), N, Ci, Co, H, W, kh, kw, stride, _pad(pad), Cib, Cob,
                                _stream(stream)), "small_conv2d")
+
+
+def small_conv2d_kernel(N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob):
+    name = load().small_conv2d_kernel(N, Ci, Co, H, W, kh, kw, stride, _pad(pad), Cib, Cob)
+    return name.decode() if name else None
 
 
 def small_dwconv2d(inp, filt, out, N, Cc, H, W, kh, kw, stride, pad, Cb, stream=None):

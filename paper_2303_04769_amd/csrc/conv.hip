@@ -239,7 +239,38 @@ void launch_mfma(const ConvArgs &a, hipStream_t s)
     hipLaunchKernelGGL((conv16_mfma<WAVES_M, WAVES_N, WM, WN>), grid, dim3(64 * WAVES_M * WAVES_N), 0, s, a);
 }
 
+enum Variant { V_DIRECT, V_128x128, V_64x128, V_128x64, V_64x64, V_128x32, V_64x32, V_128x16, V_64x16 };
+
+// Tile choice: the widest channel tile the layer can fill, then the largest pixel tile that still
+// yields at least one workgroup per compute unit.
+Variant pick_variant(const LayerGeom &g)
+{
+    if (g.Cib != 16 || g.Cob != 16) return V_DIRECT;
+    const long M = (long)g.N * g.Ho * g.Wo;
+    const long wg128 = (M + 127) / 128;
+    const int Co = g.Co;
+    if (Co >= 128) return wg128 * ((Co + 127) / 128) >= 256 ? V_128x128 : V_64x128;
+    if (Co >= 64) return wg128 * ((Co + 63) / 64) >= 256 ? V_128x64 : V_64x64;
+    if (Co >= 32) return wg128 >= 256 ? V_128x32 : V_64x32;
+    return wg128 >= 256 ? V_128x16 : V_64x16;
+}
+
 }  // namespace
+
+const char *conv_kernel_name(const LayerGeom &g)
+{
+    switch (pick_variant(g)) {
+        case V_128x128: return "conv16_mfma<2,2,4,4>";
+        case V_64x128: return "conv16_mfma<1,4,4,2>";
+        case V_128x64: return "conv16_mfma<2,2,4,2>";
+        case V_64x64: return "conv16_mfma<2,2,2,2>";
+        case V_128x32: return "conv16_mfma<4,1,2,2>";
+        case V_64x32: return "conv16_mfma<4,1,1,2>";
+        case V_128x16: return "conv16_mfma<4,1,2,1>";
+        case V_64x16: return "conv16_mfma<4,1,1,1>";
+        default: return "conv_direct";
+    }
+}
 
 hipError_t launch_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue, hipStream_t s)
 {
@@ -253,27 +284,20 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const Lay
     a.epilogue = epilogue;
 
     const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 15u) == 0);
-    if (g.Cib == 16 && g.Cob == 16 && aligned) {
-        // Tile choice: the widest channel tile the layer can fill, then the largest pixel tile that
-        // still yields at least one workgroup per compute unit.
-        const int Co = g.Co;
-        const long wg128 = (long)((a.M + 127) / 128);
-        if (Co >= 128) {
-            if (wg128 * ((Co + 127) / 128) >= 256) launch_mfma<2, 2, 4, 4>(a, s);   // 128 x 128
-            else launch_mfma<1, 4, 4, 2>(a, s);                                       //  64 x 128
-        } else if (Co >= 64) {
-            if (wg128 * ((Co + 63) / 64) >= 256) launch_mfma<2, 2, 4, 2>(a, s);     // 128 x 64
-            else launch_mfma<2, 2, 2, 2>(a, s);                                       //  64 x 64
-        } else if (Co >= 32) {
-            if (wg128 >= 256) launch_mfma<4, 1, 2, 2>(a, s);                         // 128 x 32
-            else launch_mfma<4, 1, 1, 2>(a, s);                                       //  64 x 32
-        } else {
-            if (wg128 >= 256) launch_mfma<4, 1, 2, 1>(a, s);                         // 128 x 16
-            else launch_mfma<4, 1, 1, 1>(a, s);                                       //  64 x 16
+    switch (aligned ? pick_variant(g) : V_DIRECT) {
+        case V_128x128: launch_mfma<2, 2, 4, 4>(a, s); break;
+        case V_64x128: launch_mfma<1, 4, 4, 2>(a, s); break;
+        case V_128x64: launch_mfma<2, 2, 4, 2>(a, s); break;
+        case V_64x64: launch_mfma<2, 2, 2, 2>(a, s); break;
+        case V_128x32: launch_mfma<4, 1, 2, 2>(a, s); break;
+        case V_64x32: launch_mfma<4, 1, 1, 2>(a, s); break;
+        case V_128x16: launch_mfma<4, 1, 2, 1>(a, s); break;
+        case V_64x16: launch_mfma<4, 1, 1, 1>(a, s); break;
+        default: {
+            const size_t total = (size_t)a.M * g.Co;
+            hipLaunchKernelGGL(conv_direct, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cib, g.Cob,
+                               total);
         }
-    } else {
-        const size_t total = (size_t)a.M * g.Co;
-        hipLaunchKernelGGL(conv_direct, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cib, g.Cob, total);
     }
     return hipGetLastError();
 }

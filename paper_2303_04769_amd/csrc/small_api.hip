@@ -157,6 +157,14 @@ int small_conv2d(const float *in, const float *filt, float *out, int N, int Ci, 
     return run_conv(in, filt, out, p, EPI_NONE, as_stream(stream));
 }
 
+const char *small_conv2d_kernel(int N, int Ci, int Co, int H, int W, int kh, int kw, int stride, small_pad pad,
+                                int Cib, int Cob)
+{
+    ConvPlan p;
+    if (plan_conv(p, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob)) return nullptr;
+    return conv_kernel_name(p.g);
+}
+
 int small_dwconv2d(const float *in, const float *filt, float *out, int N, int C, int H, int W, int kh, int kw,
                    int stride, small_pad pad, int Cb, void *stream)
 {

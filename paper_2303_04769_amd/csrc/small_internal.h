@@ -33,5 +33,7 @@ hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode
 
 hipError_t launch_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue,
                        hipStream_t s);
+// Name of the kernel launch_conv picks for this geometry when all pointers are 16-byte aligned.
+const char *conv_kernel_name(const LayerGeom &g);
 
 }  // namespace small
