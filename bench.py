@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--only", default="", help="comma-separated sweep layers to run (e.g. dw3x3,relu); skips the rest")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-networks", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the CPU-oracle sample")
@@ -72,6 +73,11 @@ def main():
         b.record()
         b.synchronize()
         return a.elapsed_time(b) * 1e-3 / reps
+
+    if args.only:   # developer shortcut: selected sweep rows only, one JSON row per line
+        for row in sweep(S, WL, torch, np, dev, timed, set(args.only.split(","))):
+            print(json.dumps(row))
+        return
 
     # ------------------------------------------------------------------ the step
     net = WL.residual_cnn()
@@ -239,8 +245,10 @@ def _traffic(kernel):
         return None
 
 
-def sweep(S, WL, torch, np, dev, timed):
+def sweep(S, WL, torch, np, dev, timed, only=None):
     """Layer sweep at batch 64: every layer on its own, HBM-bound layers with rotated buffers."""
+    def want(name):
+        return not only or name in only
     Nb = WL.SWEEP_N
     rng = np.random.default_rng(WL.BASE_SEED + 5)
     rows = []
@@ -261,6 +269,8 @@ def sweep(S, WL, torch, np, dev, timed):
         ins = [rand(n_act) for _ in range(sets)]
         outs = [torch.empty(n_act, device=dev, dtype=torch.float32) for _ in range(sets)]
         for k, name in ((3, "conv3x3"), (1, "conv1x1")):
+            if not want(name):
+                continue
             w = torch.from_numpy(WL.uniform_pm1(rng, (C * C * k * k,))).to(dev)   # already "blocked": random values
             pad = (1, 1, 1, 1) if k == 3 else (0, 0, 0, 0)
             fn = lambda r: S.small_conv2d(ins[r % sets], w, outs[r % sets], Nb, C, C, H, H, k, k, 1, pad, 16, 16)
@@ -272,13 +282,14 @@ def sweep(S, WL, torch, np, dev, timed):
                          "frac": round(flops / tmin / PEAK_MFMA_F32, 4), "gbs": round(byts / tmin / 1e9, 1),
                          "frac_hbm": round(byts / tmin / PEAK_HBM, 4),
                          "kernel": S.small_conv2d_kernel(Nb, C, C, H, H, k, k, 1, pad, 16, 16)})
-        wd = torch.from_numpy(WL.uniform_pm1(rng, (C * 9,))).to(dev)
-        fn = lambda r: S.small_dwconv2d(ins[r % sets], wd, outs[r % sets], Nb, C, H, H, 3, 3, 1, (1, 1, 1, 1), 16)
-        tmin, tmed = best_of(fn, 100)
-        byts = 4.0 * (2 * n_act + 9 * C)
-        rows.append({"layer": "dw3x3", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
-                     "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
-                     "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": sets})
+        if want("dw3x3"):
+            wd = torch.from_numpy(WL.uniform_pm1(rng, (C * 9,))).to(dev)
+            fn = lambda r: S.small_dwconv2d(ins[r % sets], wd, outs[r % sets], Nb, C, H, H, 3, 3, 1, (1, 1, 1, 1), 16)
+            tmin, tmed = best_of(fn, 100)
+            byts = 4.0 * (2 * n_act + 9 * C)
+            rows.append({"layer": "dw3x3", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                         "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
+                         "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": sets})
         del ins, outs
     C, H = WL.sweep_shapes()["pool_relu"]
     n_act = Nb * C * H * H
@@ -286,6 +297,8 @@ def sweep(S, WL, torch, np, dev, timed):
     sets = 2
     ins = [rand(n_act) for _ in range(sets)]
     outs = [torch.empty(n_act, device=dev, dtype=torch.float32) for _ in range(sets)]
+    if not (want("relu") or want("maxpool3x3s2") or want("pack")):
+        return rows
     fn = lambda r: S.small_relu(ins[r % sets], outs[r % sets], n_act)
     tmin, tmed = best_of(fn, 50)
     rows.append({"layer": "relu", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),

@@ -18,6 +18,16 @@ struct LayerGeom {
     int kh, kw, stride, pt, pl;
 };
 
+// MI355X dispatches consecutive workgroup ids round-robin over its 8 XCDs, each with a private L2.
+// This maps the hardware id b of an n-workgroup 1-D grid to a logical id such that each XCD works
+// on one contiguous range of logical ids, so neighbouring tiles (which share halo rows or filter
+// slabs) meet in the same L2.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned n)
+{
+    const unsigned q = n >> 3, r = n & 7u, xcd = b & 7u, idx = b >> 3;
+    return xcd * q + (xcd < r ? xcd : r) + idx;
+}
+
 // Epilogue fused into the convolution's STORE phase (the paper's "abstract fused layer" direction).
 enum : int { EPI_NONE = 0, EPI_RELU = 1 };
 

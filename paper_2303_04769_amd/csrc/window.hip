@@ -3,8 +3,10 @@
 // average pooling. HBM-bound: no matrix cores. One lane owns four adjacent channels of one
 // output pixel (a 16-byte slice of the Cb-contiguous axis), so a wavefront covers 16
 // consecutive pixels = 1 KiB of contiguous output, and window taps that overlap between
-// neighbouring pixels are served by the vector L1 / L2 rather than by HBM.
+// neighbouring pixels are served from an LDS tile (Cb = 16) or the vector L1 / L2 (other blocks).
 #include "small_internal.h"
+
+#include <algorithm>
 
 namespace small {
 
@@ -15,21 +17,26 @@ enum : int { OP_DW = 0, OP_MAX = 1, OP_AVG = 2 };
 
 __device__ __forceinline__ floatx4 ld4(const float *p) { return *reinterpret_cast<const floatx4 *>(p); }
 __device__ __forceinline__ void st4(float *p, floatx4 v) { *reinterpret_cast<floatx4 *>(p) = v; }
+// streaming variants: data that is touched once should not displace reusable lines
+__device__ __forceinline__ floatx4 ld4_stream(const float *p) { return __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(p)); }
+__device__ __forceinline__ void st4_stream(float *p, floatx4 v) { __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(p)); }
 
 __device__ __forceinline__ float max_first(float m, float v) { return (v > m) ? v : m; }   // first value seen wins ties
 
-// grid.x = (image, channel block) plane, grid.y = chunks of kBlock lanes over Ho*Wo*(Cb/4).
+// 1-D grid over (plane, chunk): plane = (image, channel block), chunk = kBlock lanes of the plane's
+// Ho*Wo*(Cb/4) float4 outputs; chunks of one plane are consecutive logical workgroups on one XCD.
 // KS > 0: square KS x KS window fully unrolled; KS == 0: run-time kh x kw.
 // CQ > 0: Cb/4 known at compile time; CQ == 0: run-time.
 template <int OP, int KS, int CQ>
 __global__ void __launch_bounds__(kBlock) window_vec4(const float *__restrict__ in, const float *__restrict__ filt,
-                                                       float *__restrict__ out, LayerGeom g)
+                                                       float *__restrict__ out, LayerGeom g, int chunks)
 {
     const int Cb = g.Cib;
     const int cq = CQ > 0 ? CQ : Cb / 4;
     const int kh = KS > 0 ? KS : g.kh, kw = KS > 0 ? KS : g.kw;
-    const int plane = blockIdx.x;
-    const int e = blockIdx.y * kBlock + threadIdx.x;
+    const unsigned wg = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int plane = wg / chunks;
+    const int e = (wg - plane * chunks) * kBlock + threadIdx.x;
     if (e >= g.Ho * g.Wo * cq) return;
     const int p = e / cq, c4 = (e - p * cq) * 4;
     const int oh = p / g.Wo, ow = p - oh * g.Wo;
@@ -42,15 +49,22 @@ __global__ void __launch_bounds__(kBlock) window_vec4(const float *__restrict__ 
     if (OP == OP_MAX) acc = floatx4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
     else acc = floatx4{0.f, 0.f, 0.f, 0.f};
     int cnt = 0;
+    // Branch-free taps: an out-of-range tap reads a clamped (valid) address and is then replaced by
+    // the reduction's neutral value (0 for FMA / Add, -inf for Max, which "v > m" never selects), so
+    // all loads of a window can be in flight together.
+    const float neutral = OP == OP_MAX ? -INFINITY : 0.f;
 #pragma unroll
     for (int y = 0; y < kh; ++y) {
         const int ih = ih0 + y;
-        if (ih < 0 || ih >= g.H) continue;
+        const bool oky = ih >= 0 && ih < g.H;
+        const int ihc = min(max(ih, 0), g.H - 1);
 #pragma unroll
         for (int x = 0; x < kw; ++x) {
             const int iw = iw0 + x;
-            if (iw < 0 || iw >= g.W) continue;
-            const floatx4 v = ld4(src + (size_t)(ih * g.W + iw) * Cb);
+            const bool ok = oky && iw >= 0 && iw < g.W;
+            const int iwc = min(max(iw, 0), g.W - 1);
+            floatx4 v = ld4(src + (size_t)(ihc * g.W + iwc) * Cb);
+            if (!ok) v = floatx4{neutral, neutral, neutral, neutral};
             if (OP == OP_DW) {
                 const floatx4 w = ld4(wsrc + (y * kw + x) * Cb);
                 acc.x = fmaf(v.x, w.x, acc.x); acc.y = fmaf(v.y, w.y, acc.y);
@@ -60,7 +74,7 @@ __global__ void __launch_bounds__(kBlock) window_vec4(const float *__restrict__ 
                 acc.z = max_first(acc.z, v.z); acc.w = max_first(acc.w, v.w);
             } else {
                 acc += v;
-                ++cnt;
+                cnt += ok ? 1 : 0;
             }
         }
     }
@@ -69,6 +83,109 @@ __global__ void __launch_bounds__(kBlock) window_vec4(const float *__restrict__ 
         acc.x /= d; acc.y /= d; acc.z /= d; acc.w /= d;
     }
     st4(out + ((size_t)plane * g.Ho * g.Wo + p) * Cb + c4, acc);
+}
+
+// LDS-tiled single-channel reduction, Cb = 16: one workgroup owns TR output rows (full width) of one
+// (image, channel block) plane. Phase 1 copies the input rows the tile needs into LDS with
+// consecutive lanes on consecutive 16-byte pieces, so every global line is requested exactly once
+// per workgroup (repeated requests to a line that is still in flight stall the vector L1);
+// padding cells are written with the reduction's neutral value, so phase 2 has no bounds checks.
+// Phase 2: one lane = 4 channels of one output pixel, taps read from LDS (ds_read_b128, lanes on
+// consecutive addresses), depthwise filter taps held in registers.
+// LDS tile: IR rows x IW padded columns x 16 floats, IR = (TR-1)*stride + kh, IW = max(W + pl, (Wo-1)*stride + kw).
+template <int OP, int KS, int kCopyBatch>
+__global__ void __launch_bounds__(kBlock) window_lds16(const float *__restrict__ in, const float *__restrict__ filt,
+                                                        float *__restrict__ out, LayerGeom g, int TR, int tiles, int IW)
+{
+    extern __shared__ floatx4 tile[];                 // [IR][IW][4 quads]
+    const int kh = KS > 0 ? KS : g.kh, kw = KS > 0 ? KS : g.kw;
+    const unsigned wg = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int plane = wg / tiles;
+    const int oy0 = (wg - plane * tiles) * TR;
+    const int trc = min(TR, g.Ho - oy0);              // output rows of this tile
+    const int IR = (trc - 1) * g.stride + kh;
+    const int iy0 = oy0 * g.stride - g.pt;
+    const int tid = threadIdx.x;
+    const float neutral = OP == OP_MAX ? -INFINITY : 0.f;
+    const floatx4 nv{neutral, neutral, neutral, neutral};
+
+    // output decomposition of phase 2, computed early so the filter taps are requested before the tile
+    const int ow4 = g.Wo * 4;
+    const int rows_per_iter = ow4 >= kBlock ? 1 : kBlock / ow4;
+    const int ry = ow4 >= kBlock ? 0 : tid / ow4;
+    const int oc = ow4 >= kBlock ? tid : tid - ry * ow4;
+    const int cb = plane % (g.Ci / 16);
+    floatx4 w[KS > 0 ? KS * KS : 1];
+    if (OP == OP_DW && KS > 0) {
+        // a lane's channel quad is the same for all of its outputs (columns advance by 256 lanes = 64 pixels)
+#pragma unroll
+        for (int k = 0; k < KS * KS; ++k) w[k] = ld4(filt + ((size_t)cb * KS * KS + k) * 16 + (oc & 3) * 4);
+    }
+
+    // ---- phase 1: global -> LDS. Lane t copies float4 items t, t + 256, ... of the IR x IW x 4 tile;
+    // kCopyBatch loads are issued back to back (clamped addresses, so no branches) before the first
+    // LDS write, which keeps that many 16-byte requests per lane in flight.
+    {
+        const int iw4 = IW * 4, items = IR * iw4;
+        const int step_r = kBlock / iw4, step_c = kBlock - step_r * iw4;
+        int r = tid / iw4, c = tid - r * iw4;
+        const float *src = in + (size_t)plane * g.H * g.W * 16;
+        for (int base = 0; base < items; base += kCopyBatch * kBlock) {
+            floatx4 v[kCopyBatch];
+            bool ok[kCopyBatch];
+#pragma unroll
+            for (int k = 0; k < kCopyBatch; ++k) {
+                const int iy = iy0 + r, ix = (c >> 2) - g.pl;
+                ok[k] = iy >= 0 && iy < g.H && ix >= 0 && ix < g.W;
+                const int iyc = min(max(iy, 0), g.H - 1), ixc = min(max(ix, 0), g.W - 1);
+                v[k] = ld4_stream(src + ((size_t)iyc * g.W + ixc) * 16 + (c & 3) * 4);
+                c += step_c; r += step_r;
+                if (c >= iw4) { c -= iw4; ++r; }
+            }
+#pragma unroll
+            for (int k = 0; k < kCopyBatch; ++k) {
+                const int f = base + k * kBlock + tid;
+                if (f < items) tile[f] = ok[k] ? v[k] : nv;
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 2: LDS -> registers -> global
+    if (ry >= rows_per_iter) return;
+    float *dst = out + (size_t)plane * g.Ho * g.Wo * 16;
+    for (int c = oc; c < ow4; c += kBlock) {
+        const int ox = c >> 2, q = c & 3;
+        for (int r = ry; r < trc; r += rows_per_iter) {
+            const floatx4 *t0 = tile + ((r * g.stride) * IW + ox * g.stride) * 4 + q;
+            floatx4 acc = (OP == OP_MAX) ? nv : floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int y = 0; y < kh; ++y) {
+#pragma unroll
+                for (int x = 0; x < kw; ++x) {
+                    const floatx4 v = t0[(y * IW + x) * 4];
+                    if (OP == OP_DW) {
+                        const floatx4 wv = KS > 0 ? w[y * kw + x] : ld4(filt + ((size_t)(cb * kh + y) * kw + x) * 16 + q * 4);
+                        acc.x = fmaf(v.x, wv.x, acc.x); acc.y = fmaf(v.y, wv.y, acc.y);
+                        acc.z = fmaf(v.z, wv.z, acc.z); acc.w = fmaf(v.w, wv.w, acc.w);
+                    } else if (OP == OP_MAX) {
+                        acc.x = max_first(acc.x, v.x); acc.y = max_first(acc.y, v.y);
+                        acc.z = max_first(acc.z, v.z); acc.w = max_first(acc.w, v.w);
+                    } else {
+                        acc += v;
+                    }
+                }
+            }
+            if (OP == OP_AVG) {
+                // divisor = taps inside the image (padding cells hold 0 and are not counted)
+                const int y0 = (oy0 + r) * g.stride - g.pt, x0 = ox * g.stride - g.pl;
+                const int ny = min(y0 + kh, g.H) - max(y0, 0), nx = min(x0 + kw, g.W) - max(x0, 0);
+                const float d = (float)(ny * nx);
+                acc.x /= d; acc.y /= d; acc.z /= d; acc.w /= d;
+            }
+            st4_stream(dst + ((size_t)(oy0 + r) * g.Wo + ox) * 16 + q * 4, acc);
+        }
+    }
 }
 
 // Any block size: one lane per output element (used when Cb is not a multiple of 4).
@@ -136,17 +253,41 @@ hipError_t launch_window(const float *in, const float *filt, float *out, const L
     const int Cb = g.Cib;
     const int planes = g.N * (g.Ci / Cb);
     const bool vec = (Cb % 4 == 0) && ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 15u) == 0);
+    if (vec && Cb == 16) {
+        // LDS-tiled path when at least one output row's input rows fit the LDS budget
+        const int IW = std::max(g.W + g.pl, (g.Wo - 1) * g.stride + g.kw);
+        constexpr int kLdsBudget = 40 * 1024;   // measured best: 4 workgroups per compute unit
+        const int max_ir = kLdsBudget / (IW * 64);
+        if (max_ir >= g.kh) {
+            int TR = std::min(g.Ho, (max_ir - g.kh) / g.stride + 1);
+            // keep at least ~4 workgroups per compute unit when the layer is large enough
+            while (TR > 1 && (long)planes * ((g.Ho + TR - 1) / TR) < 1024) TR = (TR + 1) / 2;
+            const int tiles = (g.Ho + TR - 1) / TR;
+            const size_t lds = (size_t)((TR - 1) * g.stride + g.kh) * IW * 64;
+            const dim3 grid((unsigned)planes * (unsigned)tiles);
+            const int items = (int)(lds / 16);
+            const bool k3 = g.kh == 3 && g.kw == 3;
+#define SMALL_LAUNCH_LDS(KS, CB) \
+    hipLaunchKernelGGL((window_lds16<OP, KS, CB>), grid, dim3(kBlock), lds, s, in, filt, out, g, TR, tiles, IW)
+            if (items <= 2 * kBlock) { if (k3) SMALL_LAUNCH_LDS(3, 2); else SMALL_LAUNCH_LDS(0, 2); }
+            else if (items <= 4 * kBlock) { if (k3) SMALL_LAUNCH_LDS(3, 4); else SMALL_LAUNCH_LDS(0, 4); }
+            else { if (k3) SMALL_LAUNCH_LDS(3, 10); else SMALL_LAUNCH_LDS(0, 10); }
+#undef SMALL_LAUNCH_LDS
+            return hipGetLastError();
+        }
+    }
     if (vec) {
         const int cq = Cb / 4;
         const int per_plane = g.Ho * g.Wo * cq;
-        const dim3 grid((unsigned)planes, (unsigned)((per_plane + kBlock - 1) / kBlock));
+        const int chunks = (per_plane + kBlock - 1) / kBlock;
+        const dim3 grid((unsigned)planes * (unsigned)chunks);
         const bool k3 = g.kh == 3 && g.kw == 3;
         if (k3 && cq == 4)
-            hipLaunchKernelGGL((window_vec4<OP, 3, 4>), grid, dim3(kBlock), 0, s, in, filt, out, g);
+            hipLaunchKernelGGL((window_vec4<OP, 3, 4>), grid, dim3(kBlock), 0, s, in, filt, out, g, chunks);
         else if (cq == 4)
-            hipLaunchKernelGGL((window_vec4<OP, 0, 4>), grid, dim3(kBlock), 0, s, in, filt, out, g);
+            hipLaunchKernelGGL((window_vec4<OP, 0, 4>), grid, dim3(kBlock), 0, s, in, filt, out, g, chunks);
         else
-            hipLaunchKernelGGL((window_vec4<OP, 0, 0>), grid, dim3(kBlock), 0, s, in, filt, out, g);
+            hipLaunchKernelGGL((window_vec4<OP, 0, 0>), grid, dim3(kBlock), 0, s, in, filt, out, g, chunks);
     } else {
         const size_t total = (size_t)planes * g.Ho * g.Wo * Cb;
         hipLaunchKernelGGL((window_scalar<OP>), dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in,
