@@ -14,6 +14,9 @@
 // pixels is a row-major [pixels][16] matrix and the filter slab is a row-major [16][16] matrix.
 #include "small_internal.h"
 
+#include <cstdio>
+#include <cstdlib>
+
 namespace small {
 
 namespace {
@@ -239,37 +242,35 @@ void launch_mfma(const ConvArgs &a, hipStream_t s)
     hipLaunchKernelGGL((conv16_mfma<WAVES_M, WAVES_N, WM, WN>), grid, dim3(64 * WAVES_M * WAVES_N), 0, s, a);
 }
 
-enum Variant { V_DIRECT, V_128x128, V_64x128, V_128x64, V_64x64, V_128x32, V_64x32, V_128x16, V_64x16 };
-
 // Tile choice: the widest channel tile the layer can fill, then the largest pixel tile that still
 // yields at least one workgroup per compute unit.
-Variant pick_variant(const LayerGeom &g)
+int pick_tile(const LayerGeom &g)
 {
-    if (g.Cib != 16 || g.Cob != 16) return V_DIRECT;
+    if (const char *e = getenv("SMALL_TILE")) return atoi(e);   // TEMP
     const long M = (long)g.N * g.Ho * g.Wo;
     const long wg128 = (M + 127) / 128;
     const int Co = g.Co;
-    if (Co >= 128) return wg128 * ((Co + 127) / 128) >= 256 ? V_128x128 : V_64x128;
-    if (Co >= 64) return wg128 * ((Co + 63) / 64) >= 256 ? V_128x64 : V_64x64;
-    if (Co >= 32) return wg128 >= 256 ? V_128x32 : V_64x32;
-    return wg128 >= 256 ? V_128x16 : V_64x16;
+    if (Co >= 128) return wg128 * ((Co + 127) / 128) >= 256 ? SAME_128x128 : SAME_64x128;
+    if (Co >= 64) return wg128 * ((Co + 63) / 64) >= 256 ? SAME_128x64 : SAME_64x64;
+    if (Co >= 32) return wg128 >= 256 ? SAME_128x32 : SAME_64x32;
+    return wg128 >= 256 ? SAME_128x16 : SAME_64x16;
 }
+
+const char *const kTileWaves[] = {"2,2,4,4", "1,4,4,2", "2,2,4,2", "2,2,2,2", "4,1,2,2", "4,1,1,2", "4,1,2,1", "4,1,1,1",
+                                  "2,2,1,2", "2,2,1,1"};
 
 }  // namespace
 
 const char *conv_kernel_name(const LayerGeom &g)
 {
-    switch (pick_variant(g)) {
-        case V_128x128: return "conv16_mfma<2,2,4,4>";
-        case V_64x128: return "conv16_mfma<1,4,4,2>";
-        case V_128x64: return "conv16_mfma<2,2,4,2>";
-        case V_64x64: return "conv16_mfma<2,2,2,2>";
-        case V_128x32: return "conv16_mfma<4,1,2,2>";
-        case V_64x32: return "conv16_mfma<4,1,1,2>";
-        case V_128x16: return "conv16_mfma<4,1,2,1>";
-        case V_64x16: return "conv16_mfma<4,1,1,1>";
-        default: return "conv_direct";
-    }
+    static thread_local char name[64];
+    if (g.Cib != 16 || g.Cob != 16) return "conv_direct";
+    const int tile = pick_tile(g);
+    if (conv_same_eligible(g))
+        snprintf(name, sizeof(name), "conv16_same<%s,%d,%d>", kTileWaves[tile], g.kw, conv_same_planes(g));
+    else
+        snprintf(name, sizeof(name), "conv16_mfma<%s>", kTileWaves[tile]);
+    return name;
 }
 
 hipError_t launch_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue, hipStream_t s)
@@ -284,20 +285,24 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const Lay
     a.epilogue = epilogue;
 
     const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 15u) == 0);
-    switch (aligned ? pick_variant(g) : V_DIRECT) {
-        case V_128x128: launch_mfma<2, 2, 4, 4>(a, s); break;
-        case V_64x128: launch_mfma<1, 4, 4, 2>(a, s); break;
-        case V_128x64: launch_mfma<2, 2, 4, 2>(a, s); break;
-        case V_64x64: launch_mfma<2, 2, 2, 2>(a, s); break;
-        case V_128x32: launch_mfma<4, 1, 2, 2>(a, s); break;
-        case V_64x32: launch_mfma<4, 1, 1, 2>(a, s); break;
-        case V_128x16: launch_mfma<4, 1, 2, 1>(a, s); break;
-        case V_64x16: launch_mfma<4, 1, 1, 1>(a, s); break;
-        default: {
-            const size_t total = (size_t)a.M * g.Co;
-            hipLaunchKernelGGL(conv_direct, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cib, g.Cob,
-                               total);
-        }
+    if (!aligned || g.Cib != 16 || g.Cob != 16) {
+        const size_t total = (size_t)a.M * g.Co;
+        hipLaunchKernelGGL(conv_direct, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cib, g.Cob, total);
+        return hipGetLastError();
+    }
+    const int tile = pick_tile(g);
+    if (conv_same_eligible(g)) return launch_conv_same(in, filt, out, g, tile, epilogue, s);
+    switch (tile) {
+        case SAME_128x128: launch_mfma<2, 2, 4, 4>(a, s); break;
+        case SAME_64x128: launch_mfma<1, 4, 4, 2>(a, s); break;
+        case SAME_128x64: launch_mfma<2, 2, 4, 2>(a, s); break;
+        case SAME_64x64: launch_mfma<2, 2, 2, 2>(a, s); break;
+        case SAME_128x32: launch_mfma<4, 1, 2, 2>(a, s); break;
+        case SAME_64x32: launch_mfma<4, 1, 1, 2>(a, s); break;
+        case SAME_128x16: launch_mfma<4, 1, 2, 1>(a, s); break;
+        case SAME_32x64: launch_mfma<2, 2, 1, 2>(a, s); break;
+        case SAME_32x32: launch_mfma<2, 2, 1, 1>(a, s); break;
+        default: launch_mfma<4, 1, 1, 1>(a, s); break;
     }
     return hipGetLastError();
 }

@@ -46,4 +46,12 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const Lay
 // Name of the kernel launch_conv picks for this geometry when all pointers are 16-byte aligned.
 const char *conv_kernel_name(const LayerGeom &g);
 
+// Workgroup tiles (output pixels x output channels) of the matrix-core convolutions.
+enum : int { SAME_128x128, SAME_64x128, SAME_128x64, SAME_64x64, SAME_128x32, SAME_64x32, SAME_128x16, SAME_64x16,
+              SAME_32x64, SAME_32x32, SAME_NUM_TILES };
+bool conv_same_eligible(const LayerGeom &g);     // stride 1, output size == input size, kw in {1, 3}, 16-blocks
+int conv_same_planes(const LayerGeom &g);        // Ci blocks staged per reduction step (1x1 filters)
+hipError_t launch_conv_same(const float *in, const float *filt, float *out, const LayerGeom &g, int tile, int epilogue,
+                            hipStream_t s);
+
 }  // namespace small
