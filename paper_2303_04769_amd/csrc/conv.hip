@@ -15,7 +15,6 @@
 #include "small_internal.h"
 
 #include <cstdio>
-#include <cstdlib>
 
 namespace small {
 
@@ -242,18 +241,19 @@ void launch_mfma(const ConvArgs &a, hipStream_t s)
     hipLaunchKernelGGL((conv16_mfma<WAVES_M, WAVES_N, WM, WN>), grid, dim3(64 * WAVES_M * WAVES_N), 0, s, a);
 }
 
-// Tile choice: the widest channel tile the layer can fill, then the largest pixel tile that still
-// yields at least one workgroup per compute unit.
+// Tile choice (measured on MI355X, batch-64 layers at 64..512 channels): small tiles win, because
+// many short workgroups balance better over 256 compute units and leave 4 or more of them
+// resident per compute unit, which hides each other's prologue, barrier and store phases.
+// 3x3: 64 pixels x 32 channels; 1x1 (little work per pixel): 32 pixels x 64 channels.
 int pick_tile(const LayerGeom &g)
 {
-    if (const char *e = getenv("SMALL_TILE")) return atoi(e);   // TEMP
-    const long M = (long)g.N * g.Ho * g.Wo;
-    const long wg128 = (M + 127) / 128;
-    const int Co = g.Co;
-    if (Co >= 128) return wg128 * ((Co + 127) / 128) >= 256 ? SAME_128x128 : SAME_64x128;
-    if (Co >= 64) return wg128 * ((Co + 63) / 64) >= 256 ? SAME_128x64 : SAME_64x64;
-    if (Co >= 32) return wg128 >= 256 ? SAME_128x32 : SAME_64x32;
-    return wg128 >= 256 ? SAME_128x16 : SAME_64x16;
+    const bool pointwise = g.kh == 1 && g.kw == 1;
+    if (g.Co >= 64 && pointwise) return SAME_32x64;
+    if (g.Co >= 32) {
+        const long wg64 = ((long)g.N * g.Ho * g.Wo + 63) / 64 * ((g.Co + 31) / 32);
+        return (pointwise || wg64 < 512) ? SAME_32x32 : SAME_64x32;
+    }
+    return SAME_64x16;
 }
 
 const char *const kTileWaves[] = {"2,2,4,4", "1,4,4,2", "2,2,4,2", "2,2,2,2", "4,1,2,2", "4,1,1,2", "4,1,2,1", "4,1,1,1",
