@@ -142,6 +142,24 @@ int small_network_workspace(const small_layer *layers, int n_layers, int N, int 
 int small_network_run(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
                       void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream);
 
+/* Cross-layer fusion. small_network_run folds layers that only touch a convolution's output element by
+ * element into that convolution's store phase (the direction the paper's conclusion calls an abstract
+ * "fused" layer, possible because every layer shares one layout): a ReLU in place on the output of a
+ * convolution or depthwise convolution, and an addition of the convolution's output to another buffer
+ * (residual connection), optionally followed by an in-place ReLU. Results are bit-identical to the
+ * unfused sequence and every buffer that is read later holds what the table says.
+ *
+ * small_network_launches (host only): how many kernel launches the table becomes, and for each the index
+ * of the first layer it covers (folded layers follow it directly). first_layer may be NULL, else it must
+ * have room for n_layers ints.
+ * small_network_run_range: like small_network_run, but enqueues only the launches whose first layer index
+ * lies in [first, first + count); buffers keep whatever earlier calls left in them (for per-layer timing
+ * and debugging). */
+int small_network_launches(const small_layer *layers, int n_layers, int *first_layer, int *n_launches);
+int small_network_run_range(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
+                            void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first,
+                            int count, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,8 @@ _OPS = {"conv": OP_CONV, "dw": OP_DWCONV, "maxpool": OP_MAXPOOL, "avgpool": OP_A
 
 EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "small_pack_filter",
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
-           "small_dense", "small_network_workspace", "small_network_run"]
+           "small_dense", "small_network_workspace", "small_network_run", "small_network_launches",
+           "small_network_run_range"]
 
 
 class SmallError(RuntimeError):
@@ -69,6 +70,8 @@ def load():
         "small_dense": (i, [p, p, p, i, i, i, i, i, p]),
         "small_network_workspace": (i, [C.POINTER(small_layer), i, i, i, i, i, C.POINTER(sz)]),
         "small_network_run": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
+        "small_network_launches": (i, [C.POINTER(small_layer), i, C.POINTER(i), C.POINTER(i)]),
+        "small_network_run_range": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, i, i, p]),
     }
     for name, (res, args) in sig.items():
         f = getattr(lib, name)     # AttributeError if the library does not export it
@@ -181,6 +184,22 @@ def small_network_run(table, in_blocked, out_blocked, workspace, workspace_bytes
                                     workspace_bytes, N, C0, H0, W0, _stream(stream)), "small_network_run")
 
 
+def small_network_launches(table):
+    """List of first-layer indices, one per kernel launch of small_network_run."""
+    first = (C.c_int * len(table))()
+    n = C.c_int(0)
+    _check(load().small_network_launches(table, len(table), first, C.byref(n)), "small_network_launches")
+    return [first[k] for k in range(n.value)]
+
+
+def small_network_run_range(table, in_blocked, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, first, count,
+                            stream=None):
+    _check(load().small_network_run_range(table, len(table), _ptr(in_blocked), _ptr(out_blocked),
+                                          C.c_void_p(workspace.data_ptr()) if workspace is not None else None,
+                                          workspace_bytes, N, C0, H0, W0, first, count, _stream(stream)),
+           "small_network_run_range")
+
+
 class PackedNetwork:
     """Device-resident form of a layer table: filters packed once into the blocked layout
     (by small_pack_filter / small_pack_dw_filter), workspace allocated once per batch size."""
@@ -221,3 +240,8 @@ class PackedNetwork:
         ws, nbytes = self.workspace(N)
         small_network_run(self.table, in_blocked, out_blocked, ws, nbytes, N, self.net.C0, self.net.H0, self.net.W0,
                           stream)
+
+    def run_range(self, in_blocked, out_blocked, N, first, count, stream=None):
+        ws, nbytes = self.workspace(N)
+        small_network_run_range(self.table, in_blocked, out_blocked, ws, nbytes, N, self.net.C0, self.net.H0,
+                                self.net.W0, first, count, stream)

@@ -24,6 +24,7 @@ struct ConvArgs {
     const float *in;
     const float *filt;
     float *out;
+    const float *res;
     int N, H, W, Ho, Wo;
     int nCib, nCob;
     int kh, kw, stride, pt, pl;
@@ -32,8 +33,9 @@ struct ConvArgs {
     int epilogue;
 };
 
-__device__ __forceinline__ floatx4 epilogue4(floatx4 v, int epi)
+__device__ __forceinline__ floatx4 epilogue4(floatx4 v, int epi, const float *res)
 {
+    if (epi & EPI_ADD) v += *reinterpret_cast<const floatx4 *>(res);
     if (epi & EPI_RELU) {
         v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
         v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
@@ -196,8 +198,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_mfma(ConvArgs a
         for (int j = 0; j < WN; ++j) {
             const int cob = cob0 + wave_n * WN + j;
             if (cob >= a.nCob) continue;
-            float *dst = a.out + ((size_t)(n * a.nCob + cob) * a.HoWo + rem) * 16 + lq * 4;
-            *reinterpret_cast<floatx4 *>(dst) = epilogue4(acc[i][j], a.epilogue);
+            const size_t o = ((size_t)(n * a.nCob + cob) * a.HoWo + rem) * 16 + lq * 4;
+            *reinterpret_cast<floatx4 *>(a.out + o) = epilogue4(acc[i][j], a.epilogue, a.res + o);
         }
     }
 }
@@ -229,8 +231,83 @@ __global__ void __launch_bounds__(256) conv_direct(ConvArgs a, int Cib, int Cob,
                 for (int ci = 0; ci < Cib; ++ci) acc = fmaf(ip[ci], wp[(size_t)ci * Cob], acc);
             }
         }
+    if (a.epilogue & EPI_ADD) acc += a.res[dst];
     if (a.epilogue & EPI_RELU) acc = acc > 0.f ? acc : 0.f;
     a.out[dst] = acc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Small-channel path (first layers with Ci = 1 or 3, 8-channel blocks, dense heads with few
+// outputs): one lane computes one output pixel for a whole output-channel block (up to 16
+// accumulators = the G_b x K_b tile of Algorithm 1 with O_wb = 1 per lane, 256 pixels per
+// workgroup). The block's filters sit in LDS, zero-padded to 16 output channels, and are read as
+// broadcast float4; input values are read once per lane. HBM-bound in practice (K is tiny).
+constexpr int kSmallMaxFilterFloats = 12 * 1024;     // 48 KiB of LDS
+
+__global__ void __launch_bounds__(256) conv_small(ConvArgs a, int Cib, int Cob, int kfloats)
+{
+    extern __shared__ floatx4 wl[];                   // [nCib][kh][kw][Cib] rows of 16 output channels
+    const int cob = blockIdx.y;
+    const int K = a.nCib * a.kh * a.kw * Cib;         // reduction length
+    // filter of this block: [cib][y][x][ci][Cob] with cib stride kh*kw*Cib*Cob, block stride nCib * that
+    const float *wsrc = a.filt + (size_t)cob * K * Cob;
+    for (int e = threadIdx.x; e < K * 16; e += 256) {
+        const int k = e >> 4, co = e & 15;
+        reinterpret_cast<float *>(wl)[e] = co < Cob ? wsrc[(size_t)k * Cob + co] : 0.f;
+    }
+    __syncthreads();
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= a.M) return;
+    const int n = m / a.HoWo, rem = m - n * a.HoWo;
+    const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+    floatx4 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = floatx4{0.f, 0.f, 0.f, 0.f};
+    int k = 0;
+    for (int cib = 0; cib < a.nCib; ++cib) {
+        const float *plane = a.in + (size_t)(n * a.nCib + cib) * a.H * a.W * Cib;
+        for (int y = 0; y < a.kh; ++y) {
+            const int ih = oh * a.stride - a.pt + y;
+            const bool oky = ih >= 0 && ih < a.H;
+            for (int x = 0; x < a.kw; ++x, k += Cib) {
+                const int iw = ow * a.stride - a.pl + x;
+                if (!oky || iw < 0 || iw >= a.W) continue;
+                const float *ip = plane + (size_t)(ih * a.W + iw) * Cib;
+                for (int ci = 0; ci < Cib; ++ci) {
+                    const float v = ip[ci];
+                    const floatx4 *w = wl + (size_t)(k + ci) * 4;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const floatx4 wq = w[q];
+                        acc[q].x = fmaf(v, wq.x, acc[q].x); acc[q].y = fmaf(v, wq.y, acc[q].y);
+                        acc[q].z = fmaf(v, wq.z, acc[q].z); acc[q].w = fmaf(v, wq.w, acc[q].w);
+                    }
+                }
+            }
+        }
+    }
+    const size_t o = ((size_t)(n * a.nCob + cob) * a.HoWo + rem) * Cob;
+    float *dst = a.out + o;
+    if (Cob == 16 && (((uintptr_t)a.out | (uintptr_t)a.res) & 15u) == 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) reinterpret_cast<floatx4 *>(dst)[q] = epilogue4(acc[q], a.epilogue, a.res + o + 4 * q);
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            floatx4 r = acc[q];
+            if (a.epilogue & EPI_ADD) {
+                if (4 * q + 0 < Cob) r.x += a.res[o + 4 * q + 0];
+                if (4 * q + 1 < Cob) r.y += a.res[o + 4 * q + 1];
+                if (4 * q + 2 < Cob) r.z += a.res[o + 4 * q + 2];
+                if (4 * q + 3 < Cob) r.w += a.res[o + 4 * q + 3];
+            }
+            r = epilogue4(r, a.epilogue & ~EPI_ADD, nullptr);
+            if (4 * q + 0 < Cob) dst[4 * q + 0] = r.x;
+            if (4 * q + 1 < Cob) dst[4 * q + 1] = r.y;
+            if (4 * q + 2 < Cob) dst[4 * q + 2] = r.z;
+            if (4 * q + 3 < Cob) dst[4 * q + 3] = r.w;
+        }
+    }
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
@@ -247,6 +324,7 @@ void launch_mfma(const ConvArgs &a, hipStream_t s)
 // 3x3: 64 pixels x 32 channels; 1x1 (little work per pixel): 32 pixels x 64 channels.
 int pick_tile(const LayerGeom &g)
 {
+
     const bool pointwise = g.kh == 1 && g.kw == 1;
     if (g.Co >= 64 && pointwise) return SAME_32x64;
     if (g.Co >= 32) {
@@ -257,14 +335,15 @@ int pick_tile(const LayerGeom &g)
 }
 
 const char *const kTileWaves[] = {"2,2,4,4", "1,4,4,2", "2,2,4,2", "2,2,2,2", "4,1,2,2", "4,1,1,2", "4,1,2,1", "4,1,1,1",
-                                  "2,2,1,2", "2,2,1,1"};
+                                  "2,2,1,2", "2,2,1,1", "4,1,4,1"};
 
 }  // namespace
 
 const char *conv_kernel_name(const LayerGeom &g)
 {
     static thread_local char name[64];
-    if (g.Cib != 16 || g.Cob != 16) return "conv_direct";
+    if (g.Cib != 16 || g.Cob != 16)
+        return (g.Cob <= 16 && (g.Ci / g.Cib) * g.kh * g.kw * g.Cib * 16 <= kSmallMaxFilterFloats) ? "conv_small" : "conv_direct";
     const int tile = pick_tile(g);
     if (conv_same_eligible(g))
         snprintf(name, sizeof(name), "conv16_same<%s,%d,%d>", kTileWaves[tile], g.kw, conv_same_planes(g));
@@ -273,10 +352,11 @@ const char *conv_kernel_name(const LayerGeom &g)
     return name;
 }
 
-hipError_t launch_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue, hipStream_t s)
+hipError_t launch_conv(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g, int epilogue,
+                       hipStream_t s)
 {
     ConvArgs a;
-    a.in = in; a.filt = filt; a.out = out;
+    a.in = in; a.filt = filt; a.out = out; a.res = (epilogue & EPI_ADD) ? res : out;
     a.N = g.N; a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo;
     a.nCib = g.Ci / g.Cib; a.nCob = g.Co / g.Cob;
     a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pt = g.pt; a.pl = g.pl;
@@ -284,14 +364,20 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const Lay
     a.M = g.N * a.HoWo;
     a.epilogue = epilogue;
 
-    const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 15u) == 0);
+    const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt | (uintptr_t)a.res) & 15u) == 0);
     if (!aligned || g.Cib != 16 || g.Cob != 16) {
+        const int kfloats = a.nCib * g.kh * g.kw * g.Cib * 16;
+        if (g.Cob <= 16 && kfloats <= kSmallMaxFilterFloats) {
+            const dim3 grid((unsigned)((a.M + 255) / 256), (unsigned)a.nCob);
+            hipLaunchKernelGGL(conv_small, grid, dim3(256), (size_t)kfloats * 4, s, a, g.Cib, g.Cob, kfloats);
+            return hipGetLastError();
+        }
         const size_t total = (size_t)a.M * g.Co;
         hipLaunchKernelGGL(conv_direct, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cib, g.Cob, total);
         return hipGetLastError();
     }
     const int tile = pick_tile(g);
-    if (conv_same_eligible(g)) return launch_conv_same(in, filt, out, g, tile, epilogue, s);
+    if (conv_same_eligible(g)) return launch_conv_same(in, filt, out, a.res, g, tile, epilogue, s);
     switch (tile) {
         case SAME_128x128: launch_mfma<2, 2, 4, 4>(a, s); break;
         case SAME_64x128: launch_mfma<1, 4, 4, 2>(a, s); break;
@@ -302,6 +388,7 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const Lay
         case SAME_128x16: launch_mfma<4, 1, 2, 1>(a, s); break;
         case SAME_32x64: launch_mfma<2, 2, 1, 2>(a, s); break;
         case SAME_32x32: launch_mfma<2, 2, 1, 1>(a, s); break;
+        case SAME_256x16: launch_mfma<4, 1, 4, 1>(a, s); break;
         default: launch_mfma<4, 1, 1, 1>(a, s); break;
     }
     return hipGetLastError();

@@ -41,6 +41,7 @@ struct SameArgs {
     const float *in;
     const float *filt;
     float *out;
+    const float *res;
     int N, H, W, HW;
     int nCib, nCob;
     int kh, pt, pl;
@@ -49,8 +50,9 @@ struct SameArgs {
     int epilogue;
 };
 
-__device__ __forceinline__ floatx4 epi4(floatx4 v, int epi)
+__device__ __forceinline__ floatx4 epi4(floatx4 v, int epi, const float *res)
 {
+    if (epi & EPI_ADD) v += *reinterpret_cast<const floatx4 *>(res);
     if (epi & EPI_RELU) {
         v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
         v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
@@ -278,8 +280,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
         for (int j = 0; j < WN; ++j) {
             const int cob = cob0 + wave_n * WN + j;
             if (cob >= a.nCob) continue;
-            float *dst = a.out + ((size_t)(n * a.nCob + cob) * a.HW + rem) * 16 + lq * 4;
-            *reinterpret_cast<floatx4 *>(dst) = epi4(acc[i][j], a.epilogue);
+            const size_t o = ((size_t)(n * a.nCob + cob) * a.HW + rem) * 16 + lq * 4;
+            *reinterpret_cast<floatx4 *>(a.out + o) = epi4(acc[i][j], a.epilogue, a.res + o);
         }
     }
 }
@@ -315,6 +317,7 @@ hipError_t launch_tile(int tile, const SameArgs &a, hipStream_t s)
         case SAME_128x16: return launch_cfg<4, 1, 2, 1, KW, NA>(a, s);
         case SAME_32x64: return launch_cfg<2, 2, 1, 2, KW, NA>(a, s);
         case SAME_32x32: return launch_cfg<2, 2, 1, 1, KW, NA>(a, s);
+        case SAME_256x16: return launch_cfg<4, 1, 4, 1, KW, NA>(a, s);
         default: return launch_cfg<4, 1, 1, 1, KW, NA>(a, s);
     }
 }
@@ -337,11 +340,11 @@ int conv_same_planes(const LayerGeom &g)
     return nCib % 2 == 0 ? 2 : 1;
 }
 
-hipError_t launch_conv_same(const float *in, const float *filt, float *out, const LayerGeom &g, int tile, int epilogue,
-                            hipStream_t s)
+hipError_t launch_conv_same(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
+                            int tile, int epilogue, hipStream_t s)
 {
     SameArgs a;
-    a.in = in; a.filt = filt; a.out = out;
+    a.in = in; a.filt = filt; a.out = out; a.res = (epilogue & EPI_ADD) ? res : out;
     a.N = g.N; a.H = g.H; a.W = g.W; a.HW = g.H * g.W;
     a.nCib = g.Ci / 16; a.nCob = g.Co / 16;
     a.kh = g.kh; a.pt = g.pt; a.pl = g.pl;

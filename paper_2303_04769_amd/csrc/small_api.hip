@@ -78,11 +78,12 @@ int plan_conv(ConvPlan &p, int N, int Ci, int Co, int H, int W, int kh, int kw, 
     return p.filt_elems ? SMALL_OK : SMALL_ERR_SHAPE;
 }
 
-int run_conv(const float *in, const float *filt, float *out, const ConvPlan &p, int epilogue, hipStream_t s)
+int run_conv(const float *in, const float *filt, float *out, const float *res, const ConvPlan &p, int epilogue,
+             hipStream_t s)
 {
     if (!in || !filt || !out) return SMALL_ERR_NULL;
     if (overlap(in, p.in_elems, out, p.out_elems) || overlap(filt, p.filt_elems, out, p.out_elems)) return SMALL_ERR_ALIAS;
-    return from_hip(launch_conv(in, filt, out, p.g, epilogue, s));
+    return from_hip(launch_conv(in, filt, out, res, p.g, epilogue, s));
 }
 
 }  // namespace
@@ -154,7 +155,7 @@ int small_conv2d(const float *in, const float *filt, float *out, int N, int Ci, 
 {
     ConvPlan p;
     if (int rc = plan_conv(p, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob)) return rc;
-    return run_conv(in, filt, out, p, EPI_NONE, as_stream(stream));
+    return run_conv(in, filt, out, nullptr, p, EPI_NONE, as_stream(stream));
 }
 
 const char *small_conv2d_kernel(int N, int Ci, int Co, int H, int W, int kh, int kw, int stride, small_pad pad,
@@ -173,7 +174,7 @@ int small_dwconv2d(const float *in, const float *filt, float *out, int N, int C,
     if (int rc = window_geom(g, N, C, C, H, W, kh, kw, stride, pad, Cb, Cb, &ni, &no)) return rc;
     if (!in || !filt || !out) return SMALL_ERR_NULL;
     if (overlap(in, ni, out, no) || overlap(filt, (size_t)C * kh * kw, out, no)) return SMALL_ERR_ALIAS;
-    return from_hip(launch_dwconv(in, filt, out, g, as_stream(stream)));
+    return from_hip(launch_dwconv(in, filt, out, g, EPI_NONE, as_stream(stream)));
 }
 
 int small_pool2d(const float *in, float *out, int N, int C, int H, int W, int kh, int kw, int stride, small_pad pad,
@@ -211,7 +212,7 @@ int small_dense(const float *in, const float *filt, float *out, int N, int Ci, i
     ConvPlan p;
     const small_pad nopad = {0, 0, 0, 0};
     if (int rc = plan_conv(p, N, Ci, Co, 1, 1, 1, 1, 1, nopad, Cib, Cob)) return rc;
-    return run_conv(in, filt, out, p, EPI_NONE, as_stream(stream));
+    return run_conv(in, filt, out, nullptr, p, EPI_NONE, as_stream(stream));
 }
 
 }  // extern "C"
@@ -231,11 +232,53 @@ struct NetPlan {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+inline bool reads(const small_layer &l, int id) { return l.src == id || (l.op == SMALL_OP_ADD && l.src2 == id); }
+
+// Cross-layer fusion on the common layout (the paper's "abstract fused layer" direction): layers
+// that follow a convolution and only touch its output element by element are folded into the
+// convolution's STORE phase. The table keeps its meaning: every buffer that is read later holds
+// exactly what the unfused sequence would have left there.
+struct Fusion { int epilogue; int out_id; int res_id; int skip; };
+
+Fusion plan_fusion(const small_layer *L, int nL, int i)
+{
+    const small_layer &c = L[i];
+    Fusion f = {EPI_NONE, c.dst, c.dst, 0};
+    const bool conv = c.op == SMALL_OP_CONV || c.op == SMALL_OP_DENSE;
+    if (!conv && c.op != SMALL_OP_DWCONV) return f;
+    int j = i + 1;
+    const int D = c.dst;
+    if (conv && j < nL && L[j].op == SMALL_OP_ADD && L[j].src != L[j].src2 && (L[j].src == D || L[j].src2 == D)) {
+        const int E = L[j].src == D ? L[j].src2 : L[j].src, T = L[j].dst;
+        bool ok = (T == D || T == E) && T != c.src;
+        if (ok && T == E) {
+            if (E == SMALL_BUF_IN) ok = false;
+            // the convolution's own buffer D is then never written: nobody may read it before it is rewritten
+            for (int k = j + 1; ok && k < nL; ++k) {
+                if (reads(L[k], D)) ok = false;
+                else if (L[k].dst == D) break;
+            }
+        }
+        if (ok) {
+            f.epilogue |= EPI_ADD;
+            f.out_id = T;
+            f.res_id = E;
+            f.skip = 1;
+            ++j;
+        }
+    }
+    if (j < nL && L[j].op == SMALL_OP_RELU && L[j].src == f.out_id && L[j].dst == f.out_id) {
+        f.epilogue |= EPI_RELU;
+        ++f.skip;
+    }
+    return f;
+}
+
 // Walks the table once: validates every layer, tracks the shape held by every logical buffer and
 // the largest tensor written to every workspace slot. With `run` set, launches as it goes (the
 // caller has already walked the table once without `run`, so no error can occur midway).
 int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &plan, bool run, const float *in_blocked,
-         float *out_blocked, char *ws, hipStream_t s)
+         float *out_blocked, char *ws, hipStream_t s, int first = 0, int count = INT_MAX)
 {
     if (!L) return SMALL_ERR_NULL;
     if (nL <= 0 || N <= 0 || C0 <= 0 || H0 <= 0 || W0 <= 0) return SMALL_ERR_SHAPE;
@@ -252,8 +295,17 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
     shp[idx(SMALL_BUF_IN)] = Shape{C0, H0, W0, L[0].Cib, true};
     if (check_block(C0, L[0].Cib)) return SMALL_ERR_SHAPE;
 
+    int fused_away = 0;      // layers after the current one that its launch already covers
     for (int i = 0; i < nL; ++i) {
         const small_layer &l = L[i];
+        const bool head = fused_away == 0;             // this layer starts a launch (it is not folded into an earlier one)
+        if (fused_away > 0) --fused_away;
+        Fusion fu = {EPI_NONE, l.dst, l.dst, 0};
+        if (run && head) {
+            fu = plan_fusion(L, nL, i);
+            fused_away = fu.skip;
+        }
+        const bool launch = run && head && i >= first && (long)i < (long)first + count;
         if (!valid_id(l.src) || !valid_id(l.dst) || l.dst == SMALL_BUF_IN) return SMALL_ERR_LAYER;
         const Shape a = shp[idx(l.src)];
         if (!a.set || a.C != l.Ci || a.Cb != l.Cib) return SMALL_ERR_LAYER;
@@ -273,7 +325,7 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.dst == l.src) return SMALL_ERR_ALIAS;
                 if (!l.filt) return SMALL_ERR_NULL;
                 o = Shape{l.Co, p.g.Ho, p.g.Wo, l.Cob, true};
-                if (run) rc = run_conv(ptr(l.src), l.filt, ptr(l.dst), p, EPI_NONE, s);
+                if (launch) rc = run_conv(ptr(l.src), l.filt, ptr(fu.out_id), ptr(fu.res_id), p, fu.epilogue, s);
                 break;
             }
             case SMALL_OP_DWCONV:
@@ -287,8 +339,9 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.dst == l.src) return SMALL_ERR_ALIAS;
                 if (l.op == SMALL_OP_DWCONV && !l.filt) return SMALL_ERR_NULL;
                 o = Shape{l.Ci, g.Ho, g.Wo, l.Cib, true};
-                if (run) {
-                    if (l.op == SMALL_OP_DWCONV) rc = from_hip(launch_dwconv(ptr(l.src), l.filt, ptr(l.dst), g, s));
+                if (launch) {
+                    if (l.op == SMALL_OP_DWCONV)
+                        rc = from_hip(launch_dwconv(ptr(l.src), l.filt, ptr(l.dst), g, fu.epilogue, s));
                     else rc = from_hip(launch_pool(ptr(l.src), ptr(l.dst), g,
                                                    l.op == SMALL_OP_MAXPOOL ? SMALL_POOL_MAX : SMALL_POOL_AVG, s));
                 }
@@ -296,13 +349,13 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
             }
             case SMALL_OP_RELU:
                 if (l.Co != l.Ci || l.Cob != l.Cib) return SMALL_ERR_LAYER;
-                if (run) rc = from_hip(launch_relu(ptr(l.src), ptr(l.dst), in_elems, s));
+                if (launch) rc = from_hip(launch_relu(ptr(l.src), ptr(l.dst), in_elems, s));
                 break;
             case SMALL_OP_ADD: {
                 if (l.Co != l.Ci || l.Cob != l.Cib || !valid_id(l.src2)) return SMALL_ERR_LAYER;
                 const Shape b = shp[idx(l.src2)];
                 if (!b.set || b.C != a.C || b.H != a.H || b.W != a.W || b.Cb != a.Cb) return SMALL_ERR_LAYER;
-                if (run) rc = from_hip(launch_add(ptr(l.src), ptr(l.src2), ptr(l.dst), in_elems, s));
+                if (launch) rc = from_hip(launch_add(ptr(l.src), ptr(l.src2), ptr(l.dst), in_elems, s));
                 break;
             }
             default:
@@ -340,8 +393,43 @@ int small_network_workspace(const small_layer *layers, int n_layers, int N, int 
     return SMALL_OK;
 }
 
+int small_network_launches(const small_layer *layers, int n_layers, int *first_layer, int *n_launches)
+{
+    if (!layers || !n_launches) return SMALL_ERR_NULL;
+    if (n_layers <= 0) return SMALL_ERR_SHAPE;
+    int n = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        if (first_layer) first_layer[n] = i;
+        ++n;
+        i += plan_fusion(layers, n_layers, i).skip;
+    }
+    *n_launches = n;
+    return SMALL_OK;
+}
+
+static int network_run_impl(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
+                            void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first, int count,
+                            void *stream);
+
+int small_network_run_range(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
+                            void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first, int count,
+                            void *stream)
+{
+    if (first < 0 || count < 0) return SMALL_ERR_SHAPE;
+    return network_run_impl(layers, n_layers, in_blocked, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, first,
+                            count, stream);
+}
+
 int small_network_run(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
                       void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream)
+{
+    return network_run_impl(layers, n_layers, in_blocked, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, 0,
+                            INT_MAX, stream);
+}
+
+static int network_run_impl(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
+                            void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first, int count,
+                            void *stream)
 {
     NetPlan plan;
     int rc = walk(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr);
@@ -355,7 +443,7 @@ int small_network_run(const small_layer *layers, int n_layers, const float *in_b
                         overlap(out_blocked, plan.out_elems, workspace, ws_elems))))
         return SMALL_ERR_ALIAS;
     return walk(layers, n_layers, N, C0, H0, W0, plan, true, in_blocked, out_blocked, static_cast<char *>(workspace),
-                as_stream(stream));
+                as_stream(stream), first, count);
 }
 
 }  // extern "C"

@@ -29,7 +29,7 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned n)
 }
 
 // Epilogue fused into the convolution's STORE phase (the paper's "abstract fused layer" direction).
-enum : int { EPI_NONE = 0, EPI_RELU = 1 };
+enum : int { EPI_NONE = 0, EPI_RELU = 1, EPI_ADD = 2 };   // ADD: accumulate onto the tensor `res` (same layout as out)
 
 hipError_t launch_relu(const float *in, float *out, size_t n, hipStream_t s);
 hipError_t launch_add(const float *a, const float *b, float *out, size_t n, hipStream_t s);
@@ -38,20 +38,22 @@ hipError_t launch_pack(const float *nchw, float *blk, int N, int C, int H, int W
 hipError_t launch_pack_filter(const float *oihw, float *blk, int Co, int Ci, int kh, int kw, int Cob, int Cib,
                               hipStream_t s);
 
-hipError_t launch_dwconv(const float *in, const float *filt, float *out, const LayerGeom &g, hipStream_t s);
+hipError_t launch_dwconv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue, hipStream_t s);
 hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode, hipStream_t s);
 
-hipError_t launch_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue,
-                       hipStream_t s);
+// res: tensor added to the result when epilogue has EPI_ADD (may be `out` itself: each lane reads the
+// elements it is about to write), else ignored.
+hipError_t launch_conv(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
+                       int epilogue, hipStream_t s);
 // Name of the kernel launch_conv picks for this geometry when all pointers are 16-byte aligned.
 const char *conv_kernel_name(const LayerGeom &g);
 
 // Workgroup tiles (output pixels x output channels) of the matrix-core convolutions.
 enum : int { SAME_128x128, SAME_64x128, SAME_128x64, SAME_64x64, SAME_128x32, SAME_64x32, SAME_128x16, SAME_64x16,
-              SAME_32x64, SAME_32x32, SAME_NUM_TILES };
+              SAME_32x64, SAME_32x32, SAME_256x16, SAME_NUM_TILES };
 bool conv_same_eligible(const LayerGeom &g);     // stride 1, output size == input size, kw in {1, 3}, 16-blocks
 int conv_same_planes(const LayerGeom &g);        // Ci blocks staged per reduction step (1x1 filters)
-hipError_t launch_conv_same(const float *in, const float *filt, float *out, const LayerGeom &g, int tile, int epilogue,
-                            hipStream_t s);
+hipError_t launch_conv_same(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
+                            int tile, int epilogue, hipStream_t s);
 
 }  // namespace small

@@ -22,6 +22,10 @@ __device__ __forceinline__ floatx4 ld4_stream(const float *p) { return __builtin
 __device__ __forceinline__ void st4_stream(float *p, floatx4 v) { __builtin_nontemporal_store(v, reinterpret_cast<floatx4 *>(p)); }
 
 __device__ __forceinline__ float max_first(float m, float v) { return (v > m) ? v : m; }   // first value seen wins ties
+__device__ __forceinline__ floatx4 relu4(floatx4 v)
+{
+    return floatx4{v.x > 0.f ? v.x : 0.f, v.y > 0.f ? v.y : 0.f, v.z > 0.f ? v.z : 0.f, v.w > 0.f ? v.w : 0.f};
+}
 
 // 1-D grid over (plane, chunk): plane = (image, channel block), chunk = kBlock lanes of the plane's
 // Ho*Wo*(Cb/4) float4 outputs; chunks of one plane are consecutive logical workgroups on one XCD.
@@ -29,7 +33,7 @@ __device__ __forceinline__ float max_first(float m, float v) { return (v > m) ? 
 // CQ > 0: Cb/4 known at compile time; CQ == 0: run-time.
 template <int OP, int KS, int CQ>
 __global__ void __launch_bounds__(kBlock) window_vec4(const float *__restrict__ in, const float *__restrict__ filt,
-                                                       float *__restrict__ out, LayerGeom g, int chunks)
+                                                       float *__restrict__ out, LayerGeom g, int chunks, int epilogue)
 {
     const int Cb = g.Cib;
     const int cq = CQ > 0 ? CQ : Cb / 4;
@@ -82,6 +86,7 @@ __global__ void __launch_bounds__(kBlock) window_vec4(const float *__restrict__ 
         const float d = (float)(cnt > 0 ? cnt : 1);
         acc.x /= d; acc.y /= d; acc.z /= d; acc.w /= d;
     }
+    if (epilogue & EPI_RELU) acc = relu4(acc);
     st4(out + ((size_t)plane * g.Ho * g.Wo + p) * Cb + c4, acc);
 }
 
@@ -95,7 +100,7 @@ __global__ void __launch_bounds__(kBlock) window_vec4(const float *__restrict__ 
 // LDS tile: IR rows x IW padded columns x 16 floats, IR = (TR-1)*stride + kh, IW = max(W + pl, (Wo-1)*stride + kw).
 template <int OP, int KS, int kCopyBatch>
 __global__ void __launch_bounds__(kBlock) window_lds16(const float *__restrict__ in, const float *__restrict__ filt,
-                                                        float *__restrict__ out, LayerGeom g, int TR, int tiles, int IW)
+                                                        float *__restrict__ out, LayerGeom g, int TR, int tiles, int IW, int epilogue)
 {
     extern __shared__ floatx4 tile[];                 // [IR][IW][4 quads]
     const int kh = KS > 0 ? KS : g.kh, kw = KS > 0 ? KS : g.kw;
@@ -183,6 +188,7 @@ __global__ void __launch_bounds__(kBlock) window_lds16(const float *__restrict__
                 const float d = (float)(ny * nx);
                 acc.x /= d; acc.y /= d; acc.z /= d; acc.w /= d;
             }
+            if (epilogue & EPI_RELU) acc = relu4(acc);
             st4_stream(dst + ((size_t)(oy0 + r) * g.Wo + ox) * 16 + q * 4, acc);
         }
     }
@@ -191,7 +197,7 @@ __global__ void __launch_bounds__(kBlock) window_lds16(const float *__restrict__
 // Any block size: one lane per output element (used when Cb is not a multiple of 4).
 template <int OP>
 __global__ void __launch_bounds__(kBlock) window_scalar(const float *__restrict__ in, const float *__restrict__ filt,
-                                                         float *__restrict__ out, LayerGeom g, size_t total)
+                                                         float *__restrict__ out, LayerGeom g, size_t total, int epilogue)
 {
     size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (e >= total) return;
@@ -218,6 +224,7 @@ __global__ void __launch_bounds__(kBlock) window_scalar(const float *__restrict_
         }
     }
     if (OP == OP_AVG) acc /= (float)(cnt > 0 ? cnt : 1);
+    if (epilogue & EPI_RELU) acc = acc > 0.f ? acc : 0.f;
     out[dst] = acc;
 }
 
@@ -248,7 +255,7 @@ __global__ void __launch_bounds__(kBlock) global_avgpool(const float *__restrict
 }
 
 template <int OP>
-hipError_t launch_window(const float *in, const float *filt, float *out, const LayerGeom &g, hipStream_t s)
+hipError_t launch_window(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue, hipStream_t s)
 {
     const int Cb = g.Cib;
     const int planes = g.N * (g.Ci / Cb);
@@ -268,7 +275,7 @@ hipError_t launch_window(const float *in, const float *filt, float *out, const L
             const int items = (int)(lds / 16);
             const bool k3 = g.kh == 3 && g.kw == 3;
 #define SMALL_LAUNCH_LDS(KS, CB) \
-    hipLaunchKernelGGL((window_lds16<OP, KS, CB>), grid, dim3(kBlock), lds, s, in, filt, out, g, TR, tiles, IW)
+    hipLaunchKernelGGL((window_lds16<OP, KS, CB>), grid, dim3(kBlock), lds, s, in, filt, out, g, TR, tiles, IW, epilogue)
             if (items <= 2 * kBlock) { if (k3) SMALL_LAUNCH_LDS(3, 2); else SMALL_LAUNCH_LDS(0, 2); }
             else if (items <= 4 * kBlock) { if (k3) SMALL_LAUNCH_LDS(3, 4); else SMALL_LAUNCH_LDS(0, 4); }
             else { if (k3) SMALL_LAUNCH_LDS(3, 10); else SMALL_LAUNCH_LDS(0, 10); }
@@ -283,29 +290,29 @@ hipError_t launch_window(const float *in, const float *filt, float *out, const L
         const dim3 grid((unsigned)planes * (unsigned)chunks);
         const bool k3 = g.kh == 3 && g.kw == 3;
         if (k3 && cq == 4)
-            hipLaunchKernelGGL((window_vec4<OP, 3, 4>), grid, dim3(kBlock), 0, s, in, filt, out, g, chunks);
+            hipLaunchKernelGGL((window_vec4<OP, 3, 4>), grid, dim3(kBlock), 0, s, in, filt, out, g, chunks, epilogue);
         else if (cq == 4)
-            hipLaunchKernelGGL((window_vec4<OP, 0, 4>), grid, dim3(kBlock), 0, s, in, filt, out, g, chunks);
+            hipLaunchKernelGGL((window_vec4<OP, 0, 4>), grid, dim3(kBlock), 0, s, in, filt, out, g, chunks, epilogue);
         else
-            hipLaunchKernelGGL((window_vec4<OP, 0, 0>), grid, dim3(kBlock), 0, s, in, filt, out, g, chunks);
+            hipLaunchKernelGGL((window_vec4<OP, 0, 0>), grid, dim3(kBlock), 0, s, in, filt, out, g, chunks, epilogue);
     } else {
         const size_t total = (size_t)planes * g.Ho * g.Wo * Cb;
         hipLaunchKernelGGL((window_scalar<OP>), dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in,
-                           filt, out, g, total);
+                           filt, out, g, total, epilogue);
     }
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_dwconv(const float *in, const float *filt, float *out, const LayerGeom &g, hipStream_t s)
+hipError_t launch_dwconv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue, hipStream_t s)
 {
-    return launch_window<OP_DW>(in, filt, out, g, s);
+    return launch_window<OP_DW>(in, filt, out, g, epilogue, s);
 }
 
 hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode, hipStream_t s)
 {
-    if (mode == 0) return launch_window<OP_MAX>(in, nullptr, out, g, s);
+    if (mode == 0) return launch_window<OP_MAX>(in, nullptr, out, g, EPI_NONE, s);
     const bool global = g.Ho == 1 && g.Wo == 1 && g.kh == g.H && g.kw == g.W && g.pt == 0 && g.pl == 0;
     const bool aligned = ((((uintptr_t)in | (uintptr_t)out) & 15u) == 0);
     if (global && aligned && (g.Cib == 16 || g.Cib == 8 || g.Cib == 4)) {
@@ -316,7 +323,7 @@ hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode
         else hipLaunchKernelGGL((global_avgpool<1>), grid, dim3(kBlock), 0, s, in, out, planes, HW);
         return hipGetLastError();
     }
-    return launch_window<OP_AVG>(in, nullptr, out, g, s);
+    return launch_window<OP_AVG>(in, nullptr, out, g, EPI_NONE, s);
 }
 
 }  // namespace small

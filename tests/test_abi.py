@@ -24,7 +24,7 @@ def _declared():
 def test_every_declared_symbol_is_exported(lib):
     from paper_2303_04769_amd import binding
     names = _declared()
-    assert len(names) == 15 and set(names) == set(binding.EXPORTS)
+    assert len(names) == 17 and set(names) == set(binding.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -80,6 +80,13 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
             sizes[L.dst] = max(sizes.get(L.dst, 0), L.Co * L.Ho * L.Wo * 4)
     assert ws(r, 1) == sum((v + 255) // 256 * 256 for v in sizes.values())
     assert ws(r, 1) <= 4 * 16 * 32 * 32 * 4
+    # launches after cross-layer fusion: residual CNN = 9 convs (ReLU / add+ReLU folded) + avgpool + dense
+    table = B.make_layer_table(r.layers, [None] * len(r.wshapes))
+    heads = B.small_network_launches(table)
+    assert len(r.layers) == 21 and len(heads) == 11
+    assert [r.layers[h].op for h in heads] == ["conv"] * 9 + ["avgpool", "dense"]
+    ta = B.make_layer_table(a.layers, [None] * len(a.wshapes))
+    assert [a.layers[h].op for h in B.small_network_launches(ta)] == ["conv"] + ["dw", "conv"] * 4 + ["avgpool", "dense"]
     # malformed tables
     t = B.make_layer_table(a.layers, [None] * len(a.wshapes))
     assert lib.small_network_workspace(t, len(t), 1, a.C0, a.H0, a.W0, C.byref(C.c_size_t())) == 1   # NULL filter

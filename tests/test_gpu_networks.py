@@ -132,3 +132,31 @@ def test_sweep_pool_relu_full_size():
     got = O.unpack(g.check(), (N, C, 27, 27), 16)
     for n in (0, 21, N - 1):
         assert_bits(got[n:n + 1], O.pool2d(x[n:n + 1], (3, 3), 2), f"maxpool image {n}")
+
+
+def test_fusion_keeps_table_semantics():
+    """A convolution's output that is read again after the following add must still be there:
+    conv -> D; conv -> E; E = E + D (candidate for folding into the second conv); OUT = relu(E + D)."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("fusion_probe", 16, 9, 9)
+    net.wshapes = [((16, 16, 3, 3), 144), ((16, 16, 1, 1), 16)]
+    p1 = (1, 1, 1, 1)
+    net.layers = [
+        Layer("conv", 16, 16, 9, 9, 3, 3, 1, p1, src=IN, dst=0, w=0),
+        Layer("conv", 16, 16, 9, 9, 1, 1, 1, (0, 0, 0, 0), src=IN, dst=1, w=1),
+        Layer("add", 16, 16, 9, 9, src=0, src2=1, dst=0),      # folded into the 1x1 conv? only if slot 1 is dead
+        Layer("add", 16, 16, 9, 9, src=0, src2=1, dst=OUT),    # ... it is not: slot 1 is read again here
+        Layer("relu", 16, 16, 9, 9, src=OUT, dst=OUT),
+    ]
+    x, ws = WL.network_tensors(net, 2, 99)
+    got = _run(net, x, ws)
+    d = O.conv2d(x, ws[0], 1, p1)
+    e = O.conv2d(x, ws[1], 1, (0, 0, 0, 0))
+    ref = O.relu(O.add(O.add(d, e), e))
+    assert_close(got, ref, 144, "fusion probe")
+    # and the foldable variant: slot 1 dead after the add
+    net.layers[3] = Layer("relu", 16, 16, 9, 9, src=0, dst=0)
+    net.layers[4] = Layer("avgpool", 16, 16, 9, 9, 9, 9, 1, src=0, dst=OUT)
+    got = _run(net, x, ws)
+    ref = O.pool2d(O.relu(O.add(d, e)), (9, 9), 1, mode="avg")
+    assert_close(got, ref, 144, "fusion probe (folded)")
