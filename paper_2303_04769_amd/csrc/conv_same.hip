@@ -46,7 +46,8 @@ struct SameArgs {
     int nCib, nCob;
     int kh, pt, pl;
     int M;          // N * H * W
-    int n_mtiles;
+    int n_mtiles, n_cotiles;
+    int co_fast;    // workgroup order: channel tile fastest (input tile shared in L2) or pixel tile fastest (filter shared)
     int epilogue;
 };
 
@@ -115,8 +116,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
     const unsigned wg = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int co_tile = wg / a.n_mtiles;
-    const int m0 = (wg - co_tile * a.n_mtiles) * TM;
+    const int co_tile = a.co_fast ? (int)(wg % a.n_cotiles) : (int)(wg / a.n_mtiles);
+    const int m0 = (a.co_fast ? (int)(wg / a.n_cotiles) : (int)(wg - co_tile * a.n_mtiles)) * TM;
     const int cob0 = co_tile * NSUB;
     const int lp = lane & 15, lq = lane >> 4;
 
@@ -300,6 +301,7 @@ hipError_t launch_cfg(SameArgs a, hipStream_t s)
     }
     a.n_mtiles = (a.M + C::TM - 1) / C::TM;
     const unsigned co_tiles = (unsigned)((a.nCob + C::NSUB - 1) / C::NSUB);
+    a.n_cotiles = (int)co_tiles;
     hipLaunchKernelGGL(kern, dim3((unsigned)a.n_mtiles * co_tiles), dim3(C::NT), C::LDS_BYTES, s, a);
     return hipGetLastError();
 }
@@ -349,7 +351,11 @@ hipError_t launch_conv_same(const float *in, const float *filt, float *out, cons
     a.nCib = g.Ci / 16; a.nCob = g.Co / 16;
     a.kh = g.kh; a.pt = g.pt; a.pl = g.pl;
     a.M = g.N * a.HW;
-    a.n_mtiles = 0;
+    a.n_mtiles = 0; a.n_cotiles = 0;
+    // Consecutive workgroups run on one XCD and share its 4 MB L2: when the whole filter fits there, walk the
+    // channel tiles of one pixel tile first (the input is then fetched from HBM once, not once per channel
+    // tile); a larger filter is kept resident tile by tile instead.
+    a.co_fast = (size_t)g.Co * g.Ci * g.kh * g.kw * 4 <= (size_t)3 << 20;
     a.epilogue = epilogue;
     if (g.kw == 3) return launch_tile<3, 1>(tile, a, s);
     if (conv_same_planes(g) == 2) return launch_tile<1, 2>(tile, a, s);
