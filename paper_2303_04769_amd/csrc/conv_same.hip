@@ -47,6 +47,7 @@ struct SameArgs {
     int kh, pt, pl;
     int M;          // N * H * W
     int n_mtiles, n_cotiles;
+    FastDiv dHW, dW, dMt, dCt;   // divisions by H*W, W, n_mtiles, n_cotiles
     int co_fast;    // workgroup order: channel tile fastest (input tile shared in L2) or pixel tile fastest (filter shared)
     int epilogue;
 };
@@ -116,8 +117,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
     const unsigned wg = xcd_contiguous(blockIdx.x, gridDim.x);
-    const int co_tile = a.co_fast ? (int)(wg % a.n_cotiles) : (int)(wg / a.n_mtiles);
-    const int m0 = (a.co_fast ? (int)(wg / a.n_cotiles) : (int)(wg - co_tile * a.n_mtiles)) * TM;
+    int co_tile, m_tile;
+    if (a.co_fast) { m_tile = a.dCt.div((int)wg); co_tile = (int)wg - m_tile * a.n_cotiles; }
+    else { co_tile = a.dMt.div((int)wg); m_tile = (int)wg - co_tile * a.n_mtiles; }
+    const int m0 = m_tile * TM;
     const int cob0 = co_tile * NSUB;
     const int lp = lane & 15, lq = lane >> 4;
 
@@ -142,8 +145,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
             const int fb = m0 + e - a.pl;
             const bool ok = e < ENT && fb >= 0 && fb < a.M;
             const int fbc = ok ? fb : 0;
-            const int n = fbc / a.HW, pix = fbc - n * a.HW;
-            const int hb = pix / a.W, wb = pix - hb * a.W;
+            const int n = a.dHW.div(fbc), pix = fbc - n * a.HW;
+            const int hb = a.dW.div(pix), wb = pix - hb * a.W;
 #pragma unroll
             for (int y = 0; y < KS; ++y) {
                 const int row = min(max(hb + y - a.pt, 0), a.H - 1);
@@ -177,8 +180,8 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
     for (int i = 0; i < WM; ++i) {
         const int px = (wave_m * WM + i) * 16 + lp;
         const int m = min(m0 + px, a.M - 1);
-        const int n = m / a.HW, pix = m - n * a.HW;
-        const int oh = pix / a.W, ow = pix - oh * a.W;
+        const int n = a.dHW.div(m), pix = m - n * a.HW;
+        const int oh = a.dW.div(pix), ow = pix - oh * a.W;
 #pragma unroll
         for (int y = 0; y < KS; ++y)
 #pragma unroll
@@ -276,7 +279,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
     for (int i = 0; i < WM; ++i) {
         const int m = m0 + (wave_m * WM + i) * 16 + lp;
         if (m >= a.M) continue;
-        const int n = m / a.HW, rem = m - n * a.HW;
+        const int n = a.dHW.div(m), rem = m - n * a.HW;
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const int cob = cob0 + wave_n * WN + j;
@@ -302,6 +305,8 @@ hipError_t launch_cfg(SameArgs a, hipStream_t s)
     a.n_mtiles = (a.M + C::TM - 1) / C::TM;
     const unsigned co_tiles = (unsigned)((a.nCob + C::NSUB - 1) / C::NSUB);
     a.n_cotiles = (int)co_tiles;
+    a.dHW = make_fastdiv(a.HW); a.dW = make_fastdiv(a.W);
+    a.dMt = make_fastdiv(a.n_mtiles); a.dCt = make_fastdiv(a.n_cotiles);
     hipLaunchKernelGGL(kern, dim3((unsigned)a.n_mtiles * co_tiles), dim3(C::NT), C::LDS_BYTES, s, a);
     return hipGetLastError();
 }

@@ -28,6 +28,31 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned n)
     return xcd * q + (xcd < r ? xcd : r) + idx;
 }
 
+// Division of a non-negative int < 2^31 by a positive launch constant: q = mulhi(n, magic) >> shift with
+// magic = ceil(2^(31 + l) / d), l = ceil(log2 d), shift = l - 1 (exact for every n < 2^31). An integer
+// division costs ~25 vector-ALU instructions per lane, and vector-ALU time is matrix-pipe time on this chip.
+struct FastDiv {
+    unsigned magic, shift, d;
+    __host__ __device__ __forceinline__ int div(int n) const
+    {
+#ifdef __HIP_DEVICE_COMPILE__
+        return d == 1 ? n : (int)(__umulhi((unsigned)n, magic) >> shift);
+#else
+        return n / (int)d;
+#endif
+    }
+};
+inline FastDiv make_fastdiv(int d)
+{
+    FastDiv f;
+    f.d = (unsigned)d;
+    unsigned l = 0;
+    while ((1ull << l) < (unsigned long long)d) ++l;
+    f.shift = l ? l - 1 : 0;
+    f.magic = d > 1 ? (unsigned)(((1ull << (31 + l)) + (unsigned)d - 1) / (unsigned)d) : 0u;
+    return f;
+}
+
 // Epilogue fused into the convolution's STORE phase (the paper's "abstract fused layer" direction).
 enum : int { EPI_NONE = 0, EPI_RELU = 1, EPI_ADD = 2 };   // ADD: accumulate onto the tensor `res` (same layout as out)
 
