@@ -318,20 +318,30 @@ void launch_mfma(const ConvArgs &a, hipStream_t s)
     hipLaunchKernelGGL((conv16_mfma<WAVES_M, WAVES_N, WM, WN>), grid, dim3(64 * WAVES_M * WAVES_N), 0, s, a);
 }
 
-// Tile choice (measured on MI355X, batch-64 layers at 64..512 channels): small tiles win, because
-// many short workgroups balance better over 256 compute units and leave 4 or more of them
-// resident per compute unit, which hides each other's prologue, barrier and store phases.
-// 3x3: 64 pixels x 32 channels; 1x1 (little work per pixel): 32 pixels x 64 channels.
+// Tile choice for the 16 x 16 blocked matrix-core kernels, from measurements on the layer sweep at
+// steady clocks. Small tiles win: many short workgroups balance better over 256 compute units and
+// leave 4 or more of them resident per compute unit, which hides each other's prologue, barrier and
+// store phases. 1x1 (little work per pixel): 32 pixels x 64 channels, or 32 x 32 for narrow layers.
+// 3x3: the candidate with the least work on the busiest compute unit (workgroups are spread evenly,
+// so that is ceil(workgroups / 256) x tile area), 64 x 32 preferred on near-ties for its operand reuse.
 int pick_tile(const LayerGeom &g)
 {
-
+    const long M = (long)g.N * g.Ho * g.Wo;
     const bool pointwise = g.kh == 1 && g.kw == 1;
-    if (g.Co >= 64 && pointwise) return SAME_32x64;
-    if (g.Co >= 32) {
-        const long wg64 = ((long)g.N * g.Ho * g.Wo + 63) / 64 * ((g.Co + 31) / 32);
-        return (pointwise || wg64 < 512) ? SAME_32x32 : SAME_64x32;
+    if (pointwise) return g.Co >= 64 ? SAME_32x64 : g.Co >= 32 ? SAME_32x32 : SAME_64x16;
+    struct Cand { int tile, tm, tn; double penalty; };
+    static const Cand wide[] = {{SAME_64x32, 64, 32, 1.0}, {SAME_64x16, 64, 16, 1.07}, {SAME_32x32, 32, 32, 1.08}};
+    static const Cand narrow[] = {{SAME_128x16, 128, 16, 1.0}, {SAME_64x16, 64, 16, 1.05}};
+    const Cand *cands = g.Co >= 32 ? wide : narrow;
+    const int n = g.Co >= 32 ? 3 : 2;
+    int best = cands[0].tile;
+    double best_cost = 0;
+    for (int i = 0; i < n; ++i) {
+        const long wgs = ((M + cands[i].tm - 1) / cands[i].tm) * ((g.Co + cands[i].tn - 1) / cands[i].tn);
+        const double cost = (double)((wgs + 255) / 256) * cands[i].tm * cands[i].tn * cands[i].penalty;
+        if (i == 0 || cost < best_cost) { best = cands[i].tile; best_cost = cost; }
     }
-    return SAME_64x16;
+    return best;
 }
 
 const char *const kTileWaves[] = {"2,2,4,4", "1,4,4,2", "2,2,4,2", "2,2,2,2", "4,1,2,2", "4,1,1,2", "4,1,2,1", "4,1,1,1",
@@ -346,7 +356,8 @@ const char *conv_kernel_name(const LayerGeom &g)
         return (g.Cob <= 16 && (g.Ci / g.Cib) * g.kh * g.kw * g.Cib * 16 <= kSmallMaxFilterFloats) ? "conv_small" : "conv_direct";
     const int tile = pick_tile(g);
     if (conv_same_eligible(g))
-        snprintf(name, sizeof(name), "conv16_same<%s,%d,%d>", kTileWaves[tile], g.kw, conv_same_planes(g));
+        snprintf(name, sizeof(name), "%s<%s,%d,%d>", conv_same_images_per_workgroup(g, tile) ? "conv16_img" : "conv16_same",
+                 kTileWaves[tile], g.kw, conv_same_planes(g));
     else
         snprintf(name, sizeof(name), "conv16_mfma<%s>", kTileWaves[tile]);
     return name;

@@ -33,6 +33,8 @@
 // B = input (column = pixel); lane l ends up with 4 adjacent output channels of pixel l % 16.
 #include "small_internal.h"
 
+#include <type_traits>
+
 namespace small {
 
 namespace {
@@ -50,6 +52,10 @@ struct SameArgs {
     FastDiv dHW, dW, dMt, dCt;   // divisions by H*W, W, n_mtiles, n_cotiles
     int co_fast;    // workgroup order: channel tile fastest (input tile shared in L2) or pixel tile fastest (filter shared)
     int epilogue;
+    // image-aligned persistent variant only: n_mtiles counts the pixel tiles of ONE image; a workgroup owns one
+    // (pixel tile, channel tile) position and walks the images g, g + n_groups, g + 2 n_groups, ...
+    int n_groups;
+    FastDiv dGP;    // division by n_groups * n_mtiles
 };
 
 __device__ __forceinline__ floatx4 epi4(floatx4 v, int epi, const float *res)
@@ -134,7 +140,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
     // clamped into the image instead of being skipped: an entry whose true source is outside the
     // image is never read unredirected, so it may hold any in-bounds data.
     unsigned d_voff[LPS][KS];
-    unsigned d_lds[LPS];      // wave-uniform LDS byte offset inside a stage
+    unsigned d_lds[LPS];      // wave-uniform LDS byte offset inside a stage (held in scalar registers)
 #pragma unroll
     for (int j = 0; j < LPS; ++j) {
         const int k = min(j * NW + wave, C::NAI + C::NBI - 1);
@@ -152,7 +158,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
                 const int row = min(max(hb + y - a.pt, 0), a.H - 1);
                 d_voff[j][y] = (unsigned)((((n * a.nCib + dc) * a.H + row) * a.W + wb) * 16 + quad * 4) * 4u;
             }
-            d_lds[j] = (unsigned)((dc * ENTP + chunk * 16) * 64);
+            d_lds[j] = __builtin_amdgcn_readfirstlane((unsigned)((dc * ENTP + chunk * 16) * 64));
         } else {
             const int kb = k - C::NAI;
             const int slab = kb / NSUB, sub = kb - slab * NSUB;
@@ -162,7 +168,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
             const unsigned off = (unsigned)((((cob * a.nCib + dc) * KS) * KS + x) * 256 + ci * 16 + (lane & 3) * 4) * 4u;
 #pragma unroll
             for (int y = 0; y < KS; ++y) d_voff[j][y] = off;
-            d_lds[j] = (unsigned)(C::A_BYTES + (slab * NSUB + sub) * 1024);
+            d_lds[j] = __builtin_amdgcn_readfirstlane((unsigned)(C::A_BYTES + (slab * NSUB + sub) * 1024));
         }
     }
     // scalar bases of a step: input + (first Ci block) planes, filter + (first Ci block, row y) slabs
@@ -176,20 +182,30 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
     // ---- per-lane fragment addresses relative to a stage, one per (pixel tile, filter row, tap):
     // the real entry, or the stage's zero entry when the tap is outside the image.
     unsigned p_addr[WM][KS][KS];
+    unsigned o_off[WM];       // byte offset of (pixel, channel block 0, this lane's 4 channels) in the output
+    bool o_ok[WM];
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
         const int px = (wave_m * WM + i) * 16 + lp;
+        o_ok[i] = m0 + px < a.M;
         const int m = min(m0 + px, a.M - 1);
         const int n = a.dHW.div(m), pix = m - n * a.HW;
         const int oh = a.dW.div(pix), ow = pix - oh * a.W;
+        o_off[i] = (unsigned)((n * a.nCob * a.HW + pix) * 16 + lq * 4) * 4u;
+        bool row_ok[KS], col_ok[KS];
+        unsigned real[KS];
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+            row_ok[t] = (unsigned)(oh + t - a.pt) < (unsigned)a.H;
+            col_ok[t] = (unsigned)(ow + t - a.pl) < (unsigned)a.W;
+            const int e = px + t;
+            real[t] = (unsigned)((e * 4 + (lq ^ ((e >> 1) & 3))) * 16);
+        }
 #pragma unroll
         for (int y = 0; y < KS; ++y)
 #pragma unroll
-            for (int x = 0; x < KS; ++x) {
-                const int e = px + x;
-                const bool ok = (unsigned)(oh + y - a.pt) < (unsigned)a.H && (unsigned)(ow + x - a.pl) < (unsigned)a.W;
-                p_addr[i][y][x] = (ok || KS == 1) ? (unsigned)((e * 4 + (lq ^ ((e >> 1) & 3))) * 16) : (unsigned)C::ZERO_REL;
-            }
+            for (int x = 0; x < KS; ++x)
+                p_addr[i][y][x] = ((row_ok[y] && col_ok[x]) || KS == 1) ? real[x] : (unsigned)C::ZERO_REL;
     }
     const unsigned b_addr = (unsigned)(C::A_BYTES + wave_n * WN * 1024 + lane * 4);
 
@@ -244,7 +260,6 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
             else wait_vmcnt<0>();
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-            const bool more = tn < nsteps;
             const int cstep_n = tn / KS;
             const char *baseA = in_c + (size_t)cstep_n * planeA;
             const char *baseB = filt_c + ((size_t)cstep_n * NA * KS + y_n) * rowB;
@@ -252,89 +267,393 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
 
             // Fragments of slab s + 1 are requested before the matrix instructions of slab s are issued
             // (two register sets); the loads of step tn are issued between the matrix instructions of slab 0.
-            floatx4 fa[2][WM];
-            float fb[2][WN][4];
-            load_frags(fa[0], fb[0], slot, y, 0);
+            // Two copies of the body, with and without loads, so that no branch sits between the matrix instructions.
+            auto body = [&](auto more) __attribute__((always_inline)) {
+                floatx4 fa[2][WM];
+                float fb[2][WN][4];
+                load_frags(fa[0], fb[0], slot, y, 0);
 #pragma unroll
-            for (int sl = 0; sl < NS; ++sl) {
-                if (sl + 1 < NS) load_frags(fa[(sl + 1) & 1], fb[(sl + 1) & 1], slot, y, sl + 1);
+                for (int sl = 0; sl < NS; ++sl) {
+                    if (sl + 1 < NS) load_frags(fa[(sl + 1) & 1], fb[(sl + 1) & 1], slot, y, sl + 1);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    if (sl == 0 && more) {
+                    for (int r = 0; r < 4; ++r) {
+                        if constexpr (decltype(more)::value) {
+                            if (sl == 0) {
 #pragma unroll
-                        for (int j = r * LPS / 4; j < (r + 1) * LPS / 4; ++j) issue_one(j, y_n, baseA, baseB, stage_lds);
+                                for (int j = r * LPS / 4; j < (r + 1) * LPS / 4; ++j) issue_one(j, y_n, baseA, baseB, stage_lds);
+                            }
+                        }
+#pragma unroll
+                        for (int i = 0; i < WM; ++i)
+#pragma unroll
+                            for (int j = 0; j < WN; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fb[sl & 1][j][r], fa[sl & 1][i][r], acc[i][j], 0, 0, 0);
                     }
-#pragma unroll
-                    for (int i = 0; i < WM; ++i)
-#pragma unroll
-                        for (int j = 0; j < WN; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fb[sl & 1][j][r], fa[sl & 1][i][r], acc[i][j], 0, 0, 0);
                 }
-            }
+            };
+            if (tn < nsteps) body(std::true_type{});
+            else body(std::false_type{});
         }
     }
 
-    // ---- STORE phase
+    // ---- STORE phase: scalar base per output channel block + the per-lane offset kept from the set-up
+    char *out_c = reinterpret_cast<char *>(a.out);
+    const char *res_c = reinterpret_cast<const char *>(a.res);
 #pragma unroll
-    for (int i = 0; i < WM; ++i) {
-        const int m = m0 + (wave_m * WM + i) * 16 + lp;
-        if (m >= a.M) continue;
-        const int n = a.dHW.div(m), rem = m - n * a.HW;
+    for (int j = 0; j < WN; ++j) {
+        const int cob = cob0 + wave_n * WN + j;
+        if (cob >= a.nCob) continue;
+        const size_t cb = (size_t)cob * a.HW * 64;
 #pragma unroll
-        for (int j = 0; j < WN; ++j) {
-            const int cob = cob0 + wave_n * WN + j;
-            if (cob >= a.nCob) continue;
-            const size_t o = ((size_t)(n * a.nCob + cob) * a.HW + rem) * 16 + lq * 4;
-            *reinterpret_cast<floatx4 *>(a.out + o) = epi4(acc[i][j], a.epilogue, a.res + o);
+        for (int i = 0; i < WM; ++i) {
+            if (!o_ok[i]) continue;
+            *reinterpret_cast<floatx4 *>(out_c + cb + o_off[i]) =
+                epi4(acc[i][j], a.epilogue, reinterpret_cast<const float *>(res_c + cb + o_off[i]));
         }
     }
+}
+
+// Image-aligned persistent variant. Pixel tiles do not cross image boundaries, and a workgroup keeps one
+// (pixel tile, channel tile) position while it walks over images. Everything that depends on the lane
+// (load descriptors, fragment addresses, edge masks, output offsets) is then the same for all of its
+// tiles and is computed once; moving to the next image only adds to scalar base addresses. The ring of
+// LDS stages runs on across tiles: the first loads of the next image are in flight while the last steps
+// of the current one are computed and stored. The step loop is one endless sequence over all tiles of
+// the workgroup, unrolled by UNROLL = lcm(STAGES, KS): a tile has a multiple of KS steps, so (ring slot,
+// filter row) of unrolled step u are compile-time whatever the number of steps per tile; the end of a tile
+// is a run-time check after every step.
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int STAGES>
+__global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
+{
+    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, STAGES>;
+    constexpr int NW = C::NW, TM = C::TM, NSUB = C::NSUB, ENT = C::ENT, ENTP = C::ENTP, LPS = C::LPS, NS = C::NS;
+
+    extern __shared__ floatx4 lds[];
+    const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)lds;
+    const char *lds_c = reinterpret_cast<const char *>(lds);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave % WAVES_M, wave_n = wave / WAVES_M;
+    const int lp = lane & 15, lq = lane >> 4;
+
+    // workgroup -> (channel tile, image group, pixel tile of the image); neighbours in this order share L2 lines
+    const int wg = (int)xcd_contiguous(blockIdx.x, gridDim.x);
+    int co_tile, grp, m_tile;
+    if (a.co_fast) {
+        const int t = a.dCt.div(wg);
+        co_tile = wg - t * a.n_cotiles;
+        grp = a.dMt.div(t);
+        m_tile = t - grp * a.n_mtiles;
+    } else {
+        co_tile = a.dGP.div(wg);
+        const int t = wg - co_tile * (a.n_groups * a.n_mtiles);
+        grp = a.dMt.div(t);
+        m_tile = t - grp * a.n_mtiles;
+    }
+    const int m0 = m_tile * TM;            // first pixel of the tile inside its image
+    const int cob0 = co_tile * NSUB;
+
+    // ---- load descriptors, relative to the start of an image (see conv16_same for the scheme)
+    unsigned d_voff[LPS][KS];
+    unsigned d_lds[LPS];
+#pragma unroll
+    for (int j = 0; j < LPS; ++j) {
+        const int k = min(j * NW + wave, C::NAI + C::NBI - 1);
+        if (k < C::NAI) {
+            const int dc = k / (ENTP / 16), chunk = k - dc * (ENTP / 16);
+            const int e = chunk * 16 + (lane >> 2);
+            const int quad = (lane & 3) ^ ((e >> 1) & 3);
+            const int fb = m0 + e - a.pl;
+            const bool ok = e < ENT && fb >= 0 && fb < a.HW;
+            const int pix = ok ? fb : 0;
+            const int hb = a.dW.div(pix), wb = pix - hb * a.W;
+#pragma unroll
+            for (int y = 0; y < KS; ++y) {
+                const int row = min(max(hb + y - a.pt, 0), a.H - 1);
+                d_voff[j][y] = (unsigned)((((dc * a.H + row) * a.W + wb) * 16 + quad * 4) * 4);
+            }
+            d_lds[j] = __builtin_amdgcn_readfirstlane((unsigned)((dc * ENTP + chunk * 16) * 64));
+        } else {
+            const int kb = k - C::NAI;
+            const int slab = kb / NSUB, sub = kb - slab * NSUB;
+            const int dc = slab / KS, x = slab - dc * KS;
+            const int row = lane >> 2, ci = 4 * (row & 3) + (row >> 2);
+            const int cob = min(cob0 + sub, a.nCob - 1);
+            const unsigned off = (unsigned)((((cob * a.nCib + dc) * KS) * KS + x) * 256 + ci * 16 + (lane & 3) * 4) * 4u;
+#pragma unroll
+            for (int y = 0; y < KS; ++y) d_voff[j][y] = off;
+            d_lds[j] = __builtin_amdgcn_readfirstlane((unsigned)(C::A_BYTES + (slab * NSUB + sub) * 1024));
+        }
+    }
+    auto issue_one = [&](int j, int y, const char *baseA, const char *baseB, unsigned stage_lds) __attribute__((always_inline)) {
+        const bool isA = min(j * NW + wave, C::NAI + C::NBI - 1) < C::NAI;     // wave-uniform
+        dma16(isA ? baseA : baseB, d_voff[j][y], stage_lds + d_lds[j]);
+    };
+
+    if (tid < STAGES) lds[(tid * C::STAGE_BYTES + C::ZERO_REL) / 16] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // ---- fragment addresses and output offsets of this lane's pixels (the same in every image)
+    unsigned p_addr[WM][KS][KS];
+    unsigned o_off[WM];
+    bool o_ok[WM];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        const int px = (wave_m * WM + i) * 16 + lp;
+        o_ok[i] = m0 + px < a.HW;
+        const int pix = min(m0 + px, a.HW - 1);
+        const int oh = a.dW.div(pix), ow = pix - oh * a.W;
+        o_off[i] = (unsigned)(pix * 16 + lq * 4) * 4u;
+        bool row_ok[KS], col_ok[KS];
+        unsigned real[KS];
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+            row_ok[t] = (unsigned)(oh + t - a.pt) < (unsigned)a.H;
+            col_ok[t] = (unsigned)(ow + t - a.pl) < (unsigned)a.W;
+            const int e = px + t;
+            real[t] = (unsigned)((e * 4 + (lq ^ ((e >> 1) & 3))) * 16);
+        }
+#pragma unroll
+        for (int y = 0; y < KS; ++y)
+#pragma unroll
+            for (int x = 0; x < KS; ++x)
+                p_addr[i][y][x] = ((row_ok[y] && col_ok[x]) || KS == 1) ? real[x] : (unsigned)C::ZERO_REL;
+    }
+    const unsigned b_addr = (unsigned)(C::A_BYTES + wave_n * WN * 1024 + lane * 4);
+
+    // ---- issue side of the pipeline: (image, step) of the next step to load, STAGES - 1 steps ahead
+    const int nsteps = (a.nCib / NA) * KS;
+    const char *in_c = reinterpret_cast<const char *>(a.in);
+    const char *filt_c = reinterpret_cast<const char *>(a.filt);
+    char *out_c = reinterpret_cast<char *>(a.out);
+    const char *res_c = reinterpret_cast<const char *>(a.res);
+    const size_t planeA = (size_t)a.HW * 64 * NA;          // bytes between the inputs of consecutive steps' Ci blocks
+    const size_t imgA = (size_t)a.nCib * a.HW * 64;        // bytes of one input image
+    const size_t imgO = (size_t)a.nCob * a.HW * 64;        // bytes of one output image
+    constexpr size_t rowB = (size_t)KS * 1024;             // bytes between filter rows; a Ci block is KS rows
+    int i_n = grp, i_step = 0;                             // i_n >= N: nothing left to load
+    int ahead = 0;                                         // steps issued and not yet computed
+    auto issue_bases = [&](const char *&baseA, const char *&baseB, int y) __attribute__((always_inline)) {
+        const int cstep = i_step / KS;
+        baseA = in_c + (size_t)i_n * imgA + (size_t)cstep * planeA;
+        baseB = filt_c + ((size_t)cstep * NA * KS + y) * rowB;
+    };
+    auto issue_done = [&]() __attribute__((always_inline)) {
+        ++ahead;
+        if (++i_step == nsteps) { i_step = 0; i_n += a.n_groups; }
+    };
+#pragma unroll
+    for (int t = 0; t < STAGES - 1; ++t) {
+        if (i_n < a.N) {
+            const char *baseA, *baseB;
+            issue_bases(baseA, baseB, t % KS);
+            const unsigned stage_lds = lds_base + (unsigned)(t % STAGES) * C::STAGE_BYTES;
+#pragma unroll
+            for (int j = 0; j < LPS; ++j) issue_one(j, t % KS, baseA, baseB, stage_lds);
+            issue_done();
+        }
+    }
+    __syncthreads();                                      // the zero entries are visible to every wave
+
+    auto load_frags = [&](floatx4 *fa, float (*fb)[4], int slot, int y, int sl) __attribute__((always_inline)) {
+        const int dc = sl / KS, x = sl - dc * KS;
+        const char *bs = lds_c + b_addr + slot * C::STAGE_BYTES + sl * NSUB * 1024;
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) fb[j][r] = *reinterpret_cast<const float *>(bs + j * 1024 + r * 256);
+#pragma unroll
+        for (int i = 0; i < WM; ++i)
+            fa[i] = *reinterpret_cast<const floatx4 *>(lds_c + p_addr[i][y][x] + slot * C::STAGE_BYTES + dc * (ENTP * 64));
+    };
+
+    floatx4 acc[WM][WN];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    int n = grp, c_step = 0;                               // image and step being computed
+    for (;;) {
+#pragma unroll
+        for (int u = 0; u < C::UNROLL; ++u) {
+            const int slot = u % STAGES, y = u % KS;                       // compile-time after unrolling
+            const int slot_n = (u + STAGES - 1) % STAGES, y_n = (u + STAGES - 1) % KS;
+            // the step to compute has landed once at most the loads of the steps issued after it are outstanding
+            // (stores of the previous tile issued in between only make this wait stricter)
+            if (ahead > STAGES - 2) wait_vmcnt<(STAGES - 2) * LPS>();
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            --ahead;
+            const char *baseA, *baseB;
+            issue_bases(baseA, baseB, y_n);
+            const unsigned stage_lds = lds_base + (unsigned)slot_n * C::STAGE_BYTES;
+
+            // Two copies of the body, with and without loads, so that no branch sits between the matrix instructions.
+            auto body = [&](auto more) __attribute__((always_inline)) {
+                floatx4 fa[2][WM];
+                float fb[2][WN][4];
+                load_frags(fa[0], fb[0], slot, y, 0);
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl) {
+                    if (sl + 1 < NS) load_frags(fa[(sl + 1) & 1], fb[(sl + 1) & 1], slot, y, sl + 1);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        if constexpr (decltype(more)::value) {
+                            if (sl == 0) {
+#pragma unroll
+                                for (int j = r * LPS / 4; j < (r + 1) * LPS / 4; ++j) issue_one(j, y_n, baseA, baseB, stage_lds);
+                            }
+                        }
+#pragma unroll
+                        for (int i = 0; i < WM; ++i)
+#pragma unroll
+                            for (int j = 0; j < WN; ++j)
+                                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fb[sl & 1][j][r], fa[sl & 1][i][r], acc[i][j], 0, 0, 0);
+                    }
+                }
+            };
+            if (i_n < a.N) { body(std::true_type{}); issue_done(); }
+            else body(std::false_type{});
+
+            if (++c_step == nsteps) {
+                // ---- STORE phase of this image's tile
+#pragma unroll
+                for (int j = 0; j < WN; ++j) {
+                    const int cob = cob0 + wave_n * WN + j;
+                    if (cob < a.nCob) {
+                        const size_t cb = (size_t)n * imgO + (size_t)cob * a.HW * 64;
+#pragma unroll
+                        for (int i = 0; i < WM; ++i) {
+                            if (o_ok[i])
+                                *reinterpret_cast<floatx4 *>(out_c + cb + o_off[i]) =
+                                    epi4(acc[i][j], a.epilogue, reinterpret_cast<const float *>(res_c + cb + o_off[i]));
+                        }
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+                c_step = 0;
+                n += a.n_groups;
+                if (n >= a.N) return;                          // uniform: every wave of the workgroup leaves here
+            }
+        }
+    }
+}
+
+// three ring slots when they fit comfortably (at least two workgroups per compute unit), else two
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA>
+constexpr int stages_of = 3 * SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, 3>::STAGE_BYTES <= 80 * 1024 ? 3 : 2;
+
+// Images per workgroup for the image-aligned persistent variant, or 0 for the flat one-tile-per-workgroup
+// kernel. Host arithmetic only. The persistent variant wastes the lanes of each image's last tile, so it
+// is taken when that waste is small; the
+// number of images per workgroup trades the per-workgroup set-up (paid once) against balance over the
+// compute units and against keeping at least 4 workgroups per compute unit to hide latencies.
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA>
+int images_per_workgroup(int N, int HW, int nCib, int nCob)
+{
+    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, stages_of<WAVES_M, WAVES_N, WM, WN, KS, NA>>;
+    const int nsteps = (nCib / NA) * KS;
+    const long tpi = (HW + C::TM - 1) / C::TM;
+    if (KS == 1 || tpi * C::TM * 100 > (long)HW * 108 || N < 2) return 0;   // measured: no gain for 1x1 filters
+    const long positions = tpi * ((nCob + C::NSUB - 1) / C::NSUB);
+    constexpr long kCUs = 256, kMinPerCU = 4;
+    const double t_tile = (double)nsteps * C::NS * 4 * WM * WN * 32;   // matrix-pipe cycles of one wave per tile
+    const double t_setup = 2500;                                       // set-up, launch and first-load latency, cycles
+    int best = 0;
+    double best_cost = 0;
+    for (int t = 1; t <= N && t <= 64; ++t) {
+        const long groups = (N + t - 1) / t;
+        const int per_wg = (int)((N + groups - 1) / groups);
+        const long wgs = positions * groups;
+        if (t > 1 && wgs < kMinPerCU * kCUs) break;
+        const double cost = (double)((wgs + kCUs - 1) / kCUs) * (per_wg * t_tile + t_setup);
+        if (best == 0 || cost < best_cost * 0.98) { best = per_wg; best_cost = cost; }
+    }
+    return best > 1 ? best : 0;
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA>
 hipError_t launch_cfg(SameArgs a, hipStream_t s)
 {
-    // three ring slots when they fit comfortably (at least two workgroups per compute unit), else two
-    constexpr int kStages = 3 * SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, 3>::STAGE_BYTES <= 80 * 1024 ? 3 : 2;
+    constexpr int kStages = stages_of<WAVES_M, WAVES_N, WM, WN, KS, NA>;
     using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages>;
-    auto kern = conv16_same<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages>;
+    const int per_wg = images_per_workgroup<WAVES_M, WAVES_N, WM, WN, KS, NA>(a.N, a.HW, a.nCib, a.nCob);
+    auto kern = per_wg ? conv16_img<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages> : conv16_same<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages>;
     if (C::LDS_BYTES > 64 * 1024) {
-        static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
-        if (attr != hipSuccess) return attr;
+        static hipError_t attr_img = hipFuncSetAttribute(reinterpret_cast<const void *>(conv16_img<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages>),
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+        static hipError_t attr_flat = hipFuncSetAttribute(reinterpret_cast<const void *>(conv16_same<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages>),
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
+        if (attr_img != hipSuccess) return attr_img;
+        if (attr_flat != hipSuccess) return attr_flat;
     }
-    a.n_mtiles = (a.M + C::TM - 1) / C::TM;
     const unsigned co_tiles = (unsigned)((a.nCob + C::NSUB - 1) / C::NSUB);
     a.n_cotiles = (int)co_tiles;
     a.dHW = make_fastdiv(a.HW); a.dW = make_fastdiv(a.W);
-    a.dMt = make_fastdiv(a.n_mtiles); a.dCt = make_fastdiv(a.n_cotiles);
-    hipLaunchKernelGGL(kern, dim3((unsigned)a.n_mtiles * co_tiles), dim3(C::NT), C::LDS_BYTES, s, a);
+    a.dCt = make_fastdiv(a.n_cotiles);
+    unsigned grid;
+    if (per_wg) {
+        a.n_mtiles = (a.HW + C::TM - 1) / C::TM;
+        a.n_groups = (a.N + per_wg - 1) / per_wg;
+        a.dGP = make_fastdiv(a.n_groups * a.n_mtiles);
+        grid = (unsigned)a.n_mtiles * (unsigned)a.n_groups * co_tiles;
+    } else {
+        a.n_mtiles = (a.M + C::TM - 1) / C::TM;
+        a.n_groups = 1;
+        a.dGP = make_fastdiv(a.n_mtiles);
+        grid = (unsigned)a.n_mtiles * co_tiles;
+    }
+    a.dMt = make_fastdiv(a.n_mtiles);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), C::LDS_BYTES, s, a);
     return hipGetLastError();
 }
 
-template <int KW, int NA>
-hipError_t launch_tile(int tile, const SameArgs &a, hipStream_t s)
+// calls f.template operator()<WAVES_M, WAVES_N, WM, WN>() for the tile id
+template <class F>
+auto with_tile(int tile, F &&f)
 {
     switch (tile) {
-        case SAME_128x128: return launch_cfg<2, 2, 4, 4, KW, NA>(a, s);
-        case SAME_64x128: return launch_cfg<1, 4, 4, 2, KW, NA>(a, s);
-        case SAME_128x64: return launch_cfg<2, 2, 4, 2, KW, NA>(a, s);
-        case SAME_64x64: return launch_cfg<2, 2, 2, 2, KW, NA>(a, s);
-        case SAME_128x32: return launch_cfg<4, 1, 2, 2, KW, NA>(a, s);
-        case SAME_64x32: return launch_cfg<4, 1, 1, 2, KW, NA>(a, s);
-        case SAME_128x16: return launch_cfg<4, 1, 2, 1, KW, NA>(a, s);
-        case SAME_32x64: return launch_cfg<2, 2, 1, 2, KW, NA>(a, s);
-        case SAME_32x32: return launch_cfg<2, 2, 1, 1, KW, NA>(a, s);
-        case SAME_256x16: return launch_cfg<4, 1, 4, 1, KW, NA>(a, s);
-        default: return launch_cfg<4, 1, 1, 1, KW, NA>(a, s);
+        case SAME_128x128: return f.template operator()<2, 2, 4, 4>();
+        case SAME_64x128: return f.template operator()<1, 4, 4, 2>();
+        case SAME_128x64: return f.template operator()<2, 2, 4, 2>();
+        case SAME_64x64: return f.template operator()<2, 2, 2, 2>();
+        case SAME_128x32: return f.template operator()<4, 1, 2, 2>();
+        case SAME_64x32: return f.template operator()<4, 1, 1, 2>();
+        case SAME_128x16: return f.template operator()<4, 1, 2, 1>();
+        case SAME_32x64: return f.template operator()<2, 2, 1, 2>();
+        case SAME_32x32: return f.template operator()<2, 2, 1, 1>();
+        case SAME_256x16: return f.template operator()<4, 1, 4, 1>();
+        default: return f.template operator()<4, 1, 1, 1>();
     }
 }
+
+template <int KW, int NA>
+struct LaunchTile {
+    const SameArgs &a;
+    hipStream_t s;
+    template <int WAVES_M, int WAVES_N, int WM, int WN>
+    hipError_t operator()() const { return launch_cfg<WAVES_M, WAVES_N, WM, WN, KW, NA>(a, s); }
+};
+
+template <int KW, int NA>
+struct PlanTile {
+    int N, HW, nCib, nCob;
+    template <int WAVES_M, int WAVES_N, int WM, int WN>
+    int operator()() const { return images_per_workgroup<WAVES_M, WAVES_N, WM, WN, KW, NA>(N, HW, nCib, nCob); }
+};
 
 }  // namespace
 
 bool conv_same_eligible(const LayerGeom &g)
 {
-    // the last pixel's byte offset must fit the 32-bit per-lane offset of the load instruction
+    // the last pixel's byte offset must fit the 32-bit per-lane offset of the load and store instructions
     const bool small_enough = (size_t)g.N * g.Ci * g.H * g.W < ((size_t)1 << 30) &&
+                              (size_t)g.N * g.Co * g.H * g.W < ((size_t)1 << 30) &&
                               (size_t)g.Co * g.Ci * g.kh * g.kw < ((size_t)1 << 30);
     return g.Cib == 16 && g.Cob == 16 && g.stride == 1 && g.Ho == g.H && g.Wo == g.W && g.kh == g.kw &&
            (g.kw == 1 || g.kw == 3) && g.pl < g.kw && g.pt < g.kh && small_enough;
@@ -362,9 +681,18 @@ hipError_t launch_conv_same(const float *in, const float *filt, float *out, cons
     // tile); a larger filter is kept resident tile by tile instead.
     a.co_fast = (size_t)g.Co * g.Ci * g.kh * g.kw * 4 <= (size_t)3 << 20;
     a.epilogue = epilogue;
-    if (g.kw == 3) return launch_tile<3, 1>(tile, a, s);
-    if (conv_same_planes(g) == 2) return launch_tile<1, 2>(tile, a, s);
-    return launch_tile<1, 1>(tile, a, s);
+    a.n_groups = 1;
+    if (g.kw == 3) return with_tile(tile, LaunchTile<3, 1>{a, s});
+    if (conv_same_planes(g) == 2) return with_tile(tile, LaunchTile<1, 2>{a, s});
+    return with_tile(tile, LaunchTile<1, 1>{a, s});
+}
+
+int conv_same_images_per_workgroup(const LayerGeom &g, int tile)
+{
+    const int HW = g.H * g.W, nCib = g.Ci / 16, nCob = g.Co / 16;
+    if (g.kw == 3) return with_tile(tile, PlanTile<3, 1>{g.N, HW, nCib, nCob});
+    if (conv_same_planes(g) == 2) return with_tile(tile, PlanTile<1, 2>{g.N, HW, nCib, nCob});
+    return with_tile(tile, PlanTile<1, 1>{g.N, HW, nCib, nCob});
 }
 
 }  // namespace small

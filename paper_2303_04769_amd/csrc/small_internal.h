@@ -78,6 +78,8 @@ enum : int { SAME_128x128, SAME_64x128, SAME_128x64, SAME_64x64, SAME_128x32, SA
               SAME_32x64, SAME_32x32, SAME_256x16, SAME_NUM_TILES };
 bool conv_same_eligible(const LayerGeom &g);     // stride 1, output size == input size, kw in {1, 3}, 16-blocks
 int conv_same_planes(const LayerGeom &g);        // Ci blocks staged per reduction step (1x1 filters)
+// images each workgroup walks in the image-aligned persistent variant, 0 = flat variant (host arithmetic only)
+int conv_same_images_per_workgroup(const LayerGeom &g, int tile);
 hipError_t launch_conv_same(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
                             int tile, int epilogue, hipStream_t s);
 

@@ -122,6 +122,28 @@ def test_conv2d_large_tiles():
         assert_close(got, O.conv2d(x, w, 1, (1, 1, 1, 1)), Ci * 9, f"conv large {Ci}->{Co}")
 
 
+PERSISTENT_CASES = [  # N, Ci, Co, H, W, k: enough images that a workgroup walks several of them
+    (131, 16, 16, 32, 32, 3),      # 16 tiles per image, last image group ragged
+    (160, 16, 16, 30, 30, 3),      # image size not a multiple of the tile: masked lanes in each image's last tile
+    (240, 16, 32, 24, 24, 3),      # 24 x 24 images: 9 full tiles, two output-channel blocks per wave
+    (48, 32, 48, 40, 40, 3),       # three channel tiles per pixel tile
+    (256, 16, 16, 32, 32, 3),      # the 128-pixel tile of the residual network's first stage at batch 256
+]
+
+
+@pytest.mark.parametrize("case", PERSISTENT_CASES)
+def test_conv2d_persistent_variant(case):
+    """Image-aligned persistent kernel: same results as the definition, and it really is the one that runs."""
+    N, Ci, Co, H, W, k = case
+    pad = (1, 1, 1, 1) if k == 3 else (0, 0, 0, 0)
+    assert S.small_conv2d_kernel(N, Ci, Co, H, W, k, k, 1, pad, 16, 16).startswith("conv16_img"), case
+    rng = np.random.default_rng(1000 + N)
+    x = (rng.random((N, Ci, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    w = (rng.random((Co, Ci, k, k), dtype=np.float32) * 2 - 1).astype(np.float32)
+    got = run_conv(x, w, 1, pad)
+    assert_close(got, O.conv2d(x, w, 1, pad), Ci * k * k, f"conv persistent {case}")
+
+
 def test_conv_identity_filter_is_exact():
     rng = np.random.default_rng(5)
     x = rng.standard_normal((2, 32, 10, 12)).astype(np.float32)
