@@ -344,6 +344,14 @@ int pick_tile(const LayerGeom &g)
     return best;
 }
 
+// One lane per pixel (conv_small) needs enough pixels to fill the chip; dense heads and other layers with
+// few output pixels take one lane per output element instead.
+bool use_small(const LayerGeom &g)
+{
+    const long M = (long)g.N * g.Ho * g.Wo;
+    return g.Cob <= 16 && (g.Ci / g.Cib) * g.kh * g.kw * g.Cib * 16 <= kSmallMaxFilterFloats && M >= 16384;
+}
+
 const char *const kTileWaves[] = {"2,2,4,4", "1,4,4,2", "2,2,4,2", "2,2,2,2", "4,1,2,2", "4,1,1,2", "4,1,2,1", "4,1,1,1",
                                   "2,2,1,2", "2,2,1,1", "4,1,4,1"};
 
@@ -353,11 +361,11 @@ const char *conv_kernel_name(const LayerGeom &g)
 {
     static thread_local char name[64];
     if (g.Cib != 16 || g.Cob != 16)
-        return (g.Cob <= 16 && (g.Ci / g.Cib) * g.kh * g.kw * g.Cib * 16 <= kSmallMaxFilterFloats) ? "conv_small" : "conv_direct";
+        return use_small(g) ? "conv_small" : "conv_direct";
     const int tile = pick_tile(g);
     if (conv_same_eligible(g))
-        snprintf(name, sizeof(name), "%s<%s,%d,%d>", conv_same_images_per_workgroup(g, tile) ? "conv16_img" : "conv16_same",
-                 kTileWaves[tile], g.kw, conv_same_planes(g));
+        snprintf(name, sizeof(name), "%s<%s,%d,%d,%d>", conv_same_images_per_workgroup(g, tile) ? "conv16_img" : "conv16_same",
+                 kTileWaves[tile], g.kw, conv_same_planes(g), (g.kw == 3 && g.stride == 2) ? 2 : 1);
     else
         snprintf(name, sizeof(name), "conv16_mfma<%s>", kTileWaves[tile]);
     return name;
@@ -378,7 +386,7 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
     const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt | (uintptr_t)a.res) & 15u) == 0);
     if (!aligned || g.Cib != 16 || g.Cob != 16) {
         const int kfloats = a.nCib * g.kh * g.kw * g.Cib * 16;
-        if (g.Cob <= 16 && kfloats <= kSmallMaxFilterFloats) {
+        if (use_small(g)) {
             const dim3 grid((unsigned)((a.M + 255) / 256), (unsigned)a.nCob);
             hipLaunchKernelGGL(conv_small, grid, dim3(256), (size_t)kfloats * 4, s, a, g.Cib, g.Cob, kfloats);
             return hipGetLastError();

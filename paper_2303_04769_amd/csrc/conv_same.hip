@@ -44,12 +44,13 @@ struct SameArgs {
     const float *filt;
     float *out;
     const float *res;
-    int N, H, W, HW;
+    int N, H, W, HW;            // input image
+    int Ho, Wo, HWo, stride;    // output image
     int nCib, nCob;
     int kh, pt, pl;
-    int M;          // N * H * W
+    int M;          // N * Ho * Wo
     int n_mtiles, n_cotiles;
-    FastDiv dHW, dW, dMt, dCt;   // divisions by H*W, W, n_mtiles, n_cotiles
+    FastDiv dHWo, dWo, dMt, dCt;   // divisions by Ho*Wo, Wo, n_mtiles, n_cotiles
     int co_fast;    // workgroup order: channel tile fastest (input tile shared in L2) or pixel tile fastest (filter shared)
     int epilogue;
     // image-aligned persistent variant only: n_mtiles counts the pixel tiles of ONE image; a workgroup owns one
@@ -86,15 +87,16 @@ __device__ __forceinline__ void wait_vmcnt()
 
 constexpr int gcd_(int a, int b) { return b == 0 ? a : gcd_(b, a % b); }
 
-// KS: square filter size (1 or 3). NA: Ci blocks staged per reduction step (1 for 3x3).
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int STAGES>
+// KS: square filter size (1 or 3). NA: Ci blocks staged per reduction step (1 for 3x3). ES: staged entries
+// per output pixel step (1: stride 1, or any stride with a 1x1 filter; 2: 3x3 filter with stride 2).
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int STAGES, int ES = 1>
 struct SameCfg {
     static constexpr int NW = WAVES_M * WAVES_N;
     static constexpr int NT = 64 * NW;
     static constexpr int TM = WAVES_M * WM * 16;
     static constexpr int TN = WAVES_N * WN * 16;
     static constexpr int NSUB = TN / 16;
-    static constexpr int ENT = TM + KS - 1;                  // staged input pixels per plane
+    static constexpr int ENT = ES * (TM - 1) + KS;           // staged input pixels per plane
     static constexpr int ENTP = (ENT + 15) / 16 * 16;        // rounded up to whole wave instructions
     static constexpr int NS = NA * KS;                       // filter slabs per step
     static constexpr int A_BYTES = NA * ENTP * 64;
@@ -107,12 +109,13 @@ struct SameCfg {
     static constexpr size_t LDS_BYTES = (size_t)STAGES * STAGE_BYTES;
     static_assert((STAGES - 2) * LPS < 64, "too many loads in flight for vmcnt");
     static_assert(KS == 1 || NA == 1, "several planes per step only for 1x1 filters");
+    static_assert(ES == 1 || (ES == 2 && KS == 3), "two entries per pixel only for the strided 3x3 filter");
 };
 
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int STAGES>
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int STAGES, int ES>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a)
 {
-    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, STAGES>;
+    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, STAGES, ES>;
     constexpr int NW = C::NW, TM = C::TM, NSUB = C::NSUB, ENT = C::ENT, ENTP = C::ENTP, LPS = C::LPS, NS = C::NS;
 
     extern __shared__ floatx4 lds[];
@@ -148,11 +151,27 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
             const int dc = k / (ENTP / 16), chunk = k - dc * (ENTP / 16);
             const int e = chunk * 16 + (lane >> 2);
             const int quad = (lane & 3) ^ ((e >> 1) & 3);
-            const int fb = m0 + e - a.pl;
-            const bool ok = e < ENT && fb >= 0 && fb < a.M;
-            const int fbc = ok ? fb : 0;
-            const int n = a.dHW.div(fbc), pix = fbc - n * a.HW;
-            const int hb = a.dW.div(pix), wb = pix - hb * a.W;
+            // Source pixel of entry e for filter row 0. Stride-1 3x3: entries are consecutive input pixels
+            // (the flat order of input and output pixels is the same). Otherwise entry e belongs to output
+            // pixel e / ES and holds its tap e % ES (the last entry: tap KS - 1 of the last pixel).
+            int n, hb, wb;
+            if constexpr (KS == 3 && ES == 1) {
+                const int fb = m0 + e - a.pl;
+                const bool ok = e < ENT && fb >= 0 && fb < a.M;
+                const int fbc = ok ? fb : 0;
+                n = a.dHWo.div(fbc);
+                const int pix = fbc - n * a.HWo;
+                hb = a.dWo.div(pix);
+                wb = pix - hb * a.Wo;
+            } else {
+                const int pxe = min(e / ES, TM - 1), xe = min(e - pxe * ES, KS - 1);
+                const int mo = min(m0 + pxe, a.M - 1);
+                n = a.dHWo.div(mo);
+                const int pix = mo - n * a.HWo;
+                const int oh = a.dWo.div(pix), ow = pix - oh * a.Wo;
+                hb = oh * a.stride;
+                wb = min(max(ow * a.stride + xe - a.pl, 0), a.W - 1);
+            }
 #pragma unroll
             for (int y = 0; y < KS; ++y) {
                 const int row = min(max(hb + y - a.pt, 0), a.H - 1);
@@ -189,16 +208,16 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
         const int px = (wave_m * WM + i) * 16 + lp;
         o_ok[i] = m0 + px < a.M;
         const int m = min(m0 + px, a.M - 1);
-        const int n = a.dHW.div(m), pix = m - n * a.HW;
-        const int oh = a.dW.div(pix), ow = pix - oh * a.W;
-        o_off[i] = (unsigned)((n * a.nCob * a.HW + pix) * 16 + lq * 4) * 4u;
+        const int n = a.dHWo.div(m), pix = m - n * a.HWo;
+        const int oh = a.dWo.div(pix), ow = pix - oh * a.Wo;
+        o_off[i] = (unsigned)((n * a.nCob * a.HWo + pix) * 16 + lq * 4) * 4u;
         bool row_ok[KS], col_ok[KS];
         unsigned real[KS];
 #pragma unroll
         for (int t = 0; t < KS; ++t) {
-            row_ok[t] = (unsigned)(oh + t - a.pt) < (unsigned)a.H;
-            col_ok[t] = (unsigned)(ow + t - a.pl) < (unsigned)a.W;
-            const int e = px + t;
+            row_ok[t] = (unsigned)(oh * a.stride + t - a.pt) < (unsigned)a.H;
+            col_ok[t] = (unsigned)(ow * a.stride + t - a.pl) < (unsigned)a.W;
+            const int e = px * ES + t;
             real[t] = (unsigned)((e * 4 + (lq ^ ((e >> 1) & 3))) * 16);
         }
 #pragma unroll
@@ -303,7 +322,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
     for (int j = 0; j < WN; ++j) {
         const int cob = cob0 + wave_n * WN + j;
         if (cob >= a.nCob) continue;
-        const size_t cb = (size_t)cob * a.HW * 64;
+        const size_t cb = (size_t)cob * a.HWo * 64;
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             if (!o_ok[i]) continue;
@@ -322,10 +341,10 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
 // the workgroup, unrolled by UNROLL = lcm(STAGES, KS): a tile has a multiple of KS steps, so (ring slot,
 // filter row) of unrolled step u are compile-time whatever the number of steps per tile; the end of a tile
 // is a run-time check after every step.
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int STAGES>
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int STAGES, int ES>
 __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
 {
-    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, STAGES>;
+    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, STAGES, ES>;
     constexpr int NW = C::NW, TM = C::TM, NSUB = C::NSUB, ENT = C::ENT, ENTP = C::ENTP, LPS = C::LPS, NS = C::NS;
 
     extern __shared__ floatx4 lds[];
@@ -364,10 +383,20 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
             const int dc = k / (ENTP / 16), chunk = k - dc * (ENTP / 16);
             const int e = chunk * 16 + (lane >> 2);
             const int quad = (lane & 3) ^ ((e >> 1) & 3);
-            const int fb = m0 + e - a.pl;
-            const bool ok = e < ENT && fb >= 0 && fb < a.HW;
-            const int pix = ok ? fb : 0;
-            const int hb = a.dW.div(pix), wb = pix - hb * a.W;
+            int hb, wb;                       // source pixel of entry e for filter row 0 (see conv16_same)
+            if constexpr (KS == 3 && ES == 1) {
+                const int fb = m0 + e - a.pl;
+                const bool ok = e < ENT && fb >= 0 && fb < a.HWo;
+                const int pix = ok ? fb : 0;
+                hb = a.dWo.div(pix);
+                wb = pix - hb * a.Wo;
+            } else {
+                const int pxe = min(e / ES, TM - 1), xe = min(e - pxe * ES, KS - 1);
+                const int pix = min(m0 + pxe, a.HWo - 1);
+                const int oh = a.dWo.div(pix), ow = pix - oh * a.Wo;
+                hb = oh * a.stride;
+                wb = min(max(ow * a.stride + xe - a.pl, 0), a.W - 1);
+            }
 #pragma unroll
             for (int y = 0; y < KS; ++y) {
                 const int row = min(max(hb + y - a.pt, 0), a.H - 1);
@@ -400,17 +429,17 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
 #pragma unroll
     for (int i = 0; i < WM; ++i) {
         const int px = (wave_m * WM + i) * 16 + lp;
-        o_ok[i] = m0 + px < a.HW;
-        const int pix = min(m0 + px, a.HW - 1);
-        const int oh = a.dW.div(pix), ow = pix - oh * a.W;
+        o_ok[i] = m0 + px < a.HWo;
+        const int pix = min(m0 + px, a.HWo - 1);
+        const int oh = a.dWo.div(pix), ow = pix - oh * a.Wo;
         o_off[i] = (unsigned)(pix * 16 + lq * 4) * 4u;
         bool row_ok[KS], col_ok[KS];
         unsigned real[KS];
 #pragma unroll
         for (int t = 0; t < KS; ++t) {
-            row_ok[t] = (unsigned)(oh + t - a.pt) < (unsigned)a.H;
-            col_ok[t] = (unsigned)(ow + t - a.pl) < (unsigned)a.W;
-            const int e = px + t;
+            row_ok[t] = (unsigned)(oh * a.stride + t - a.pt) < (unsigned)a.H;
+            col_ok[t] = (unsigned)(ow * a.stride + t - a.pl) < (unsigned)a.W;
+            const int e = px * ES + t;
             real[t] = (unsigned)((e * 4 + (lq ^ ((e >> 1) & 3))) * 16);
         }
 #pragma unroll
@@ -429,7 +458,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
     const char *res_c = reinterpret_cast<const char *>(a.res);
     const size_t planeA = (size_t)a.HW * 64 * NA;          // bytes between the inputs of consecutive steps' Ci blocks
     const size_t imgA = (size_t)a.nCib * a.HW * 64;        // bytes of one input image
-    const size_t imgO = (size_t)a.nCob * a.HW * 64;        // bytes of one output image
+    const size_t imgO = (size_t)a.nCob * a.HWo * 64;       // bytes of one output image
     constexpr size_t rowB = (size_t)KS * 1024;             // bytes between filter rows; a Ci block is KS rows
     int i_n = grp, i_step = 0;                             // i_n >= N: nothing left to load
     int ahead = 0;                                         // steps issued and not yet computed
@@ -523,7 +552,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
                 for (int j = 0; j < WN; ++j) {
                     const int cob = cob0 + wave_n * WN + j;
                     if (cob < a.nCob) {
-                        const size_t cb = (size_t)n * imgO + (size_t)cob * a.HW * 64;
+                        const size_t cb = (size_t)n * imgO + (size_t)cob * a.HWo * 64;
 #pragma unroll
                         for (int i = 0; i < WM; ++i) {
                             if (o_ok[i])
@@ -545,18 +574,18 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
 }
 
 // three ring slots when they fit comfortably (at least two workgroups per compute unit), else two
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA>
-constexpr int stages_of = 3 * SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, 3>::STAGE_BYTES <= 80 * 1024 ? 3 : 2;
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int ES>
+constexpr int stages_of = 3 * SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, 3, ES>::STAGE_BYTES <= 80 * 1024 ? 3 : 2;
 
 // Images per workgroup for the image-aligned persistent variant, or 0 for the flat one-tile-per-workgroup
 // kernel. Host arithmetic only. The persistent variant wastes the lanes of each image's last tile, so it
 // is taken when that waste is small; the
 // number of images per workgroup trades the per-workgroup set-up (paid once) against balance over the
 // compute units and against keeping at least 4 workgroups per compute unit to hide latencies.
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA>
-int images_per_workgroup(int N, int HW, int nCib, int nCob)
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int ES>
+int images_per_workgroup(int N, int HW, int nCib, int nCob)     // HW: pixels of an OUTPUT image
 {
-    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, stages_of<WAVES_M, WAVES_N, WM, WN, KS, NA>>;
+    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, stages_of<WAVES_M, WAVES_N, WM, WN, KS, NA, ES>, ES>;
     const int nsteps = (nCib / NA) * KS;
     const long tpi = (HW + C::TM - 1) / C::TM;
     if (KS == 1 || tpi * C::TM * 100 > (long)HW * 108 || N < 2) return 0;   // measured: no gain for 1x1 filters
@@ -577,28 +606,28 @@ int images_per_workgroup(int N, int HW, int nCib, int nCob)
     return best > 1 ? best : 0;
 }
 
-template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA>
+template <int WAVES_M, int WAVES_N, int WM, int WN, int KS, int NA, int ES>
 hipError_t launch_cfg(SameArgs a, hipStream_t s)
 {
-    constexpr int kStages = stages_of<WAVES_M, WAVES_N, WM, WN, KS, NA>;
-    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages>;
-    const int per_wg = images_per_workgroup<WAVES_M, WAVES_N, WM, WN, KS, NA>(a.N, a.HW, a.nCib, a.nCob);
-    auto kern = per_wg ? conv16_img<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages> : conv16_same<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages>;
+    constexpr int kStages = stages_of<WAVES_M, WAVES_N, WM, WN, KS, NA, ES>;
+    using C = SameCfg<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages, ES>;
+    const int per_wg = images_per_workgroup<WAVES_M, WAVES_N, WM, WN, KS, NA, ES>(a.N, a.HWo, a.nCib, a.nCob);
+    auto kern = per_wg ? conv16_img<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages, ES> : conv16_same<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages, ES>;
     if (C::LDS_BYTES > 64 * 1024) {
-        static hipError_t attr_img = hipFuncSetAttribute(reinterpret_cast<const void *>(conv16_img<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages>),
+        static hipError_t attr_img = hipFuncSetAttribute(reinterpret_cast<const void *>(conv16_img<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages, ES>),
                                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
-        static hipError_t attr_flat = hipFuncSetAttribute(reinterpret_cast<const void *>(conv16_same<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages>),
+        static hipError_t attr_flat = hipFuncSetAttribute(reinterpret_cast<const void *>(conv16_same<WAVES_M, WAVES_N, WM, WN, KS, NA, kStages, ES>),
                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::LDS_BYTES);
         if (attr_img != hipSuccess) return attr_img;
         if (attr_flat != hipSuccess) return attr_flat;
     }
     const unsigned co_tiles = (unsigned)((a.nCob + C::NSUB - 1) / C::NSUB);
     a.n_cotiles = (int)co_tiles;
-    a.dHW = make_fastdiv(a.HW); a.dW = make_fastdiv(a.W);
+    a.dHWo = make_fastdiv(a.HWo); a.dWo = make_fastdiv(a.Wo);
     a.dCt = make_fastdiv(a.n_cotiles);
     unsigned grid;
     if (per_wg) {
-        a.n_mtiles = (a.HW + C::TM - 1) / C::TM;
+        a.n_mtiles = (a.HWo + C::TM - 1) / C::TM;
         a.n_groups = (a.N + per_wg - 1) / per_wg;
         a.dGP = make_fastdiv(a.n_groups * a.n_mtiles);
         grid = (unsigned)a.n_mtiles * (unsigned)a.n_groups * co_tiles;
@@ -632,19 +661,19 @@ auto with_tile(int tile, F &&f)
     }
 }
 
-template <int KW, int NA>
+template <int KW, int NA, int ES>
 struct LaunchTile {
     const SameArgs &a;
     hipStream_t s;
     template <int WAVES_M, int WAVES_N, int WM, int WN>
-    hipError_t operator()() const { return launch_cfg<WAVES_M, WAVES_N, WM, WN, KW, NA>(a, s); }
+    hipError_t operator()() const { return launch_cfg<WAVES_M, WAVES_N, WM, WN, KW, NA, ES>(a, s); }
 };
 
-template <int KW, int NA>
+template <int KW, int NA, int ES>
 struct PlanTile {
-    int N, HW, nCib, nCob;
+    int N, HWo, nCib, nCob;
     template <int WAVES_M, int WAVES_N, int WM, int WN>
-    int operator()() const { return images_per_workgroup<WAVES_M, WAVES_N, WM, WN, KW, NA>(N, HW, nCib, nCob); }
+    int operator()() const { return images_per_workgroup<WAVES_M, WAVES_N, WM, WN, KW, NA, ES>(N, HWo, nCib, nCob); }
 };
 
 }  // namespace
@@ -653,10 +682,16 @@ bool conv_same_eligible(const LayerGeom &g)
 {
     // the last pixel's byte offset must fit the 32-bit per-lane offset of the load and store instructions
     const bool small_enough = (size_t)g.N * g.Ci * g.H * g.W < ((size_t)1 << 30) &&
-                              (size_t)g.N * g.Co * g.H * g.W < ((size_t)1 << 30) &&
+                              (size_t)g.N * g.Co * g.Ho * g.Wo < ((size_t)1 << 30) &&
                               (size_t)g.Co * g.Ci * g.kh * g.kw < ((size_t)1 << 30);
-    return g.Cib == 16 && g.Cob == 16 && g.stride == 1 && g.Ho == g.H && g.Wo == g.W && g.kh == g.kw &&
-           (g.kw == 1 || g.kw == 3) && g.pl < g.kw && g.pt < g.kh && small_enough;
+    if (g.Cib != 16 || g.Cob != 16 || g.kh != g.kw || !small_enough) return false;
+    if (g.kw == 1)                                                          // every tap must be inside the image
+        return g.pt == 0 && g.pl == 0 && g.stride >= 1 && (g.Ho - 1) * g.stride < g.H && (g.Wo - 1) * g.stride < g.W;
+    if (g.kw != 3 || g.pl >= 3 || g.pt >= 3) return false;
+    if (g.stride == 1) return g.Ho == g.H && g.Wo == g.W;                   // output pixels in input order
+    // stride 2: taps 0, 1 of a pixel are its own staged entries, tap 2 is the next pixel's tap 0, which is
+    // only right if a row's last pixel has no tap 2 inside the image
+    return g.stride == 2 && 2 * (g.Wo - 1) + 2 - g.pl >= g.W;
 }
 
 int conv_same_planes(const LayerGeom &g)
@@ -666,15 +701,32 @@ int conv_same_planes(const LayerGeom &g)
     return nCib % 2 == 0 ? 2 : 1;
 }
 
+namespace {
+
+// calls f(LaunchTile / PlanTile functor type selector) for the layer's (filter size, planes per step, entry stride)
+template <template <int, int, int> class F, class... Args>
+auto with_shape(const LayerGeom &g, int tile, Args &&...args)
+{
+    if (g.kw == 3) {
+        if (g.stride == 2) return with_tile(tile, F<3, 1, 2>{args...});
+        return with_tile(tile, F<3, 1, 1>{args...});
+    }
+    if (conv_same_planes(g) == 2) return with_tile(tile, F<1, 2, 1>{args...});
+    return with_tile(tile, F<1, 1, 1>{args...});
+}
+
+}  // namespace
+
 hipError_t launch_conv_same(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
                             int tile, int epilogue, hipStream_t s)
 {
     SameArgs a;
     a.in = in; a.filt = filt; a.out = out; a.res = (epilogue & EPI_ADD) ? res : out;
     a.N = g.N; a.H = g.H; a.W = g.W; a.HW = g.H * g.W;
+    a.Ho = g.Ho; a.Wo = g.Wo; a.HWo = g.Ho * g.Wo; a.stride = g.stride;
     a.nCib = g.Ci / 16; a.nCob = g.Co / 16;
     a.kh = g.kh; a.pt = g.pt; a.pl = g.pl;
-    a.M = g.N * a.HW;
+    a.M = g.N * a.HWo;
     a.n_mtiles = 0; a.n_cotiles = 0;
     // Consecutive workgroups run on one XCD and share its 4 MB L2: when the whole filter fits there, walk the
     // channel tiles of one pixel tile first (the input is then fetched from HBM once, not once per channel
@@ -682,17 +734,12 @@ hipError_t launch_conv_same(const float *in, const float *filt, float *out, cons
     a.co_fast = (size_t)g.Co * g.Ci * g.kh * g.kw * 4 <= (size_t)3 << 20;
     a.epilogue = epilogue;
     a.n_groups = 1;
-    if (g.kw == 3) return with_tile(tile, LaunchTile<3, 1>{a, s});
-    if (conv_same_planes(g) == 2) return with_tile(tile, LaunchTile<1, 2>{a, s});
-    return with_tile(tile, LaunchTile<1, 1>{a, s});
+    return with_shape<LaunchTile>(g, tile, a, s);
 }
 
 int conv_same_images_per_workgroup(const LayerGeom &g, int tile)
 {
-    const int HW = g.H * g.W, nCib = g.Ci / 16, nCob = g.Co / 16;
-    if (g.kw == 3) return with_tile(tile, PlanTile<3, 1>{g.N, HW, nCib, nCob});
-    if (conv_same_planes(g) == 2) return with_tile(tile, PlanTile<1, 2>{g.N, HW, nCib, nCob});
-    return with_tile(tile, PlanTile<1, 1>{g.N, HW, nCib, nCob});
+    return with_shape<PlanTile>(g, tile, g.N, g.Ho * g.Wo, g.Ci / 16, g.Co / 16);
 }
 
 }  // namespace small

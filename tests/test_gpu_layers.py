@@ -91,6 +91,11 @@ CONV_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad
     (2, 64, 64, 9, 9, 1, 1, 1, (0, 0, 0, 0)),
     (2, 16, 32, 16, 16, 1, 1, 2, (0, 0, 0, 0)),      # projection shortcut
     (2, 16, 32, 32, 32, 3, 3, 2, (0, 1, 0, 1)),      # 'same' stride 2
+    (3, 32, 32, 31, 31, 3, 3, 2, (1, 1, 1, 1)),      # stride 2, odd image, left / top padding
+    (5, 48, 64, 20, 12, 3, 3, 2, (0, 1, 0, 1)),      # stride 2, non-square, three input-channel blocks
+    (2, 16, 32, 32, 32, 3, 3, 2, (1, 1, 1, 1)),      # stride 2 whose last tap stays inside the image: gather kernel
+    (4, 64, 32, 15, 15, 1, 1, 2, (0, 0, 0, 0)),      # 1x1 stride 2, odd image, two planes per step
+    (2, 16, 16, 9, 9, 1, 1, 3, (0, 0, 0, 0)),        # 1x1 stride 3
     (1, 32, 16, 7, 9, 5, 3, 2, (2, 2, 1, 1)),        # odd window
     (2, 16, 16, 6, 6, 3, 3, 1, (0, 0, 0, 0)),        # no padding
     (4, 256, 128, 7, 7, 3, 3, 1, (1, 1, 1, 1)),      # tiles straddle images, 128-wide channel tile
@@ -127,6 +132,7 @@ PERSISTENT_CASES = [  # N, Ci, Co, H, W, k: enough images that a workgroup walks
     (160, 16, 16, 30, 30, 3),      # image size not a multiple of the tile: masked lanes in each image's last tile
     (240, 16, 32, 24, 24, 3),      # 24 x 24 images: 9 full tiles, two output-channel blocks per wave
     (48, 32, 48, 40, 40, 3),       # three channel tiles per pixel tile
+    (150, 16, 32, 48, 48, 3, 2),   # stride 2: two staged entries per output pixel
     (256, 16, 16, 32, 32, 3),      # the 128-pixel tile of the residual network's first stage at batch 256
 ]
 
@@ -134,14 +140,15 @@ PERSISTENT_CASES = [  # N, Ci, Co, H, W, k: enough images that a workgroup walks
 @pytest.mark.parametrize("case", PERSISTENT_CASES)
 def test_conv2d_persistent_variant(case):
     """Image-aligned persistent kernel: same results as the definition, and it really is the one that runs."""
-    N, Ci, Co, H, W, k = case
-    pad = (1, 1, 1, 1) if k == 3 else (0, 0, 0, 0)
-    assert S.small_conv2d_kernel(N, Ci, Co, H, W, k, k, 1, pad, 16, 16).startswith("conv16_img"), case
+    N, Ci, Co, H, W, k = case[:6]
+    stride = case[6] if len(case) > 6 else 1
+    pad = ((1, 1, 1, 1) if stride == 1 else (0, 1, 0, 1)) if k == 3 else (0, 0, 0, 0)
+    assert S.small_conv2d_kernel(N, Ci, Co, H, W, k, k, stride, pad, 16, 16).startswith("conv16_img"), case
     rng = np.random.default_rng(1000 + N)
     x = (rng.random((N, Ci, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
     w = (rng.random((Co, Ci, k, k), dtype=np.float32) * 2 - 1).astype(np.float32)
-    got = run_conv(x, w, 1, pad)
-    assert_close(got, O.conv2d(x, w, 1, pad), Ci * k * k, f"conv persistent {case}")
+    got = run_conv(x, w, stride, pad)
+    assert_close(got, O.conv2d(x, w, stride, pad), Ci * k * k, f"conv persistent {case}")
 
 
 def test_conv_identity_filter_is_exact():
