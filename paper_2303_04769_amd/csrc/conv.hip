@@ -237,6 +237,40 @@ __global__ void __launch_bounds__(256) conv_direct(ConvArgs a, int Cib, int Cob,
 }
 
 // ---------------------------------------------------------------------------------------------
+// Dense head (window = whole unpadded image, one output pixel): the blocked input of an image is one
+// contiguous vector in exactly the filter's reduction order, so every output is a plain dot product.
+// One lane per output, output channel fastest (filter reads coalesced, input reads broadcast), four
+// independent partial sums and vector loads so that the short loop is not one long latency chain.
+__global__ void __launch_bounds__(256) dense_rows(ConvArgs a, int Cob, int K, size_t total, int vec)
+{
+    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int co = (int)(e % Cob);
+    const size_t t = e / Cob;
+    const int cob = (int)(t % a.nCob);
+    const size_t n = t / a.nCob;
+    const float *x = a.in + n * K;
+    const float *w = a.filt + (size_t)cob * K * Cob + co;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int k = 0;
+    if (vec) {
+#pragma unroll 4
+        for (; k + 4 <= K; k += 4) {
+            const floatx4 v = *reinterpret_cast<const floatx4 *>(x + k);
+            s0 = fmaf(v.x, w[(size_t)(k + 0) * Cob], s0);
+            s1 = fmaf(v.y, w[(size_t)(k + 1) * Cob], s1);
+            s2 = fmaf(v.z, w[(size_t)(k + 2) * Cob], s2);
+            s3 = fmaf(v.w, w[(size_t)(k + 3) * Cob], s3);
+        }
+    }
+    for (; k < K; ++k) s0 = fmaf(x[k], w[(size_t)k * Cob], s0);
+    float acc = (s0 + s1) + (s2 + s3);
+    if (a.epilogue & EPI_ADD) acc += a.res[e];
+    if (a.epilogue & EPI_RELU) acc = acc > 0.f ? acc : 0.f;
+    a.out[e] = acc;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Small-channel path (first layers with Ci = 1 or 3, 8-channel blocks, dense heads with few
 // outputs): one lane computes one output pixel for a whole output-channel block (up to 16
 // accumulators = the G_b x K_b tile of Algorithm 1 with O_wb = 1 per lane, 256 pixels per
@@ -352,6 +386,11 @@ bool use_small(const LayerGeom &g)
     return g.Cob <= 16 && (g.Ci / g.Cib) * g.kh * g.kw * g.Cib * 16 <= kSmallMaxFilterFloats && M >= 16384;
 }
 
+bool is_dense(const LayerGeom &g)
+{
+    return g.Ho == 1 && g.Wo == 1 && g.kh == g.H && g.kw == g.W && g.pt == 0 && g.pl == 0;
+}
+
 const char *const kTileWaves[] = {"2,2,4,4", "1,4,4,2", "2,2,4,2", "2,2,2,2", "4,1,2,2", "4,1,1,2", "4,1,2,1", "4,1,1,1",
                                   "2,2,1,2", "2,2,1,1", "4,1,4,1"};
 
@@ -361,7 +400,7 @@ const char *conv_kernel_name(const LayerGeom &g)
 {
     static thread_local char name[64];
     if (g.Cib != 16 || g.Cob != 16)
-        return use_small(g) ? "conv_small" : "conv_direct";
+        return use_small(g) ? "conv_small" : is_dense(g) ? "dense_rows" : "conv_direct";
     const int tile = pick_tile(g);
     if (conv_same_eligible(g))
         snprintf(name, sizeof(name), "%s<%s,%d,%d,%d>", conv_same_images_per_workgroup(g, tile) ? "conv16_img" : "conv16_same",
@@ -392,6 +431,12 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
             return hipGetLastError();
         }
         const size_t total = (size_t)a.M * g.Co;
+        if (is_dense(g)) {
+            const int K = g.Ci * g.kh * g.kw;
+            const int vec = K % 4 == 0 && ((uintptr_t)in & 15u) == 0;
+            hipLaunchKernelGGL(dense_rows, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cob, K, total, vec);
+            return hipGetLastError();
+        }
         hipLaunchKernelGGL(conv_direct, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cib, g.Cob, total);
         return hipGetLastError();
     }

@@ -104,6 +104,7 @@ CONV_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad
     (1, 3, 8, 96, 96, 3, 3, 2, (0, 1, 0, 1)),        # generic path: 8-channel output block
     (2, 8, 16, 24, 24, 1, 1, 1, (0, 0, 0, 0)),       # generic path: 8-channel input block
     (5, 64, 10, 1, 1, 1, 1, 1, (0, 0, 0, 0)),        # generic path: dense-like head
+    (3, 16, 10, 4, 5, 4, 5, 1, (0, 0, 0, 0)),        # dense over a 4 x 5 image (window = image)
 ]
 
 
@@ -161,7 +162,7 @@ def test_conv_identity_filter_is_exact():
 
 def test_dense():
     rng = np.random.default_rng(6)
-    for N, Ci, Co in [(7, 64, 10), (1, 256, 2), (33, 64, 12), (130, 128, 128), (3, 16, 16)]:
+    for N, Ci, Co in [(7, 64, 10), (1, 256, 2), (33, 64, 12), (130, 128, 128), (3, 16, 16), (5, 6, 3), (1024, 64, 12)]:
         x = rng.standard_normal((N, Ci, 1, 1)).astype(np.float32)
         w = rng.standard_normal((Co, Ci, 1, 1)).astype(np.float32)
         Cib, Cob = _blk(Ci), _blk(Co)
