@@ -148,9 +148,16 @@ int small_network_run(const small_layer *layers, int n_layers, const float *in_b
  * convolution or depthwise convolution, and an addition of the convolution's output to another buffer
  * (residual connection), optionally followed by an in-place ReLU. Results are bit-identical to the
  * unfused sequence and every buffer that is read later holds what the table says.
+ * A depthwise 3x3 convolution (16-channel blocks, stride 1 or 2, optional in-place ReLU) whose output is read
+ * only by an unpadded stride-1 1x1 convolution (optional in-place ReLU) runs with it in one kernel: the
+ * depthwise result stays on the compute unit and its buffer is never written (allowed only when no later
+ * layer reads that buffer before it is rewritten). The depthwise sum is then taken in a different order
+ * than by small_dwconv2d: results agree within the tolerance of the two layers, not bit for bit.
  *
  * small_network_launches (host only): how many kernel launches the table becomes, and for each the index
- * of the first layer it covers (folded layers follow it directly). first_layer may be NULL, else it must
+ * of the first layer it covers (folded layers follow it directly). It sees the table only: where a
+ * depthwise + 1x1 pair cannot run in one kernel for reasons outside the table (unaligned pointers, an
+ * image geometry the kernel does not take), the run launches the 1x1 convolution separately. first_layer may be NULL, else it must
  * have room for n_layers ints.
  * small_network_run_range: like small_network_run, but enqueues only the launches whose first layer index
  * lies in [first, first + count); buffers keep whatever earlier calls left in them (for per-layer timing

@@ -69,22 +69,6 @@ __device__ __forceinline__ floatx4 epi4(floatx4 v, int epi, const float *res)
     return v;
 }
 
-// 64 lanes x 16 B: global (base + per-lane byte offset) -> LDS (wave-uniform byte address + 16 * lane).
-__device__ __forceinline__ void dma16(const void *gbase, unsigned lane_off_bytes, unsigned lds_addr_uniform)
-{
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(lane_off_bytes), "s"(gbase), "s"(__builtin_amdgcn_readfirstlane(lds_addr_uniform))
-                 : "memory");
-}
-
-template <int N>
-__device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
-
 constexpr int gcd_(int a, int b) { return b == 0 ? a : gcd_(b, a % b); }
 
 // KS: square filter size (1 or 3). NA: Ci blocks staged per reduction step (1 for 3x3). ES: staged entries

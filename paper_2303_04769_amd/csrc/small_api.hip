@@ -3,6 +3,9 @@
 #include "../../include/small.h"
 #include "small_internal.h"
 
+#include <algorithm>
+#include <utility>
+
 #include <limits.h>
 #include <string.h>
 
@@ -238,12 +241,29 @@ inline bool reads(const small_layer &l, int id) { return l.src == id || (l.op ==
 // that follow a convolution and only touch its output element by element are folded into the
 // convolution's STORE phase. The table keeps its meaning: every buffer that is read later holds
 // exactly what the unfused sequence would have left there.
-struct Fusion { int epilogue; int out_id; int res_id; int skip; };
+// pw > 0: layer i is a depthwise 3x3 and layer i + pw the 1x1 convolution that alone consumes its output; both
+// run in one kernel (the depthwise buffer is never written), pw_relu: an in-place ReLU after that convolution.
+// rename: the convolution's destination is the depthwise layer's source (two buffers used in turn); one kernel
+// cannot overwrite the tensor its other workgroups still read, so it writes into the (dead) depthwise buffer
+// instead and the runner swaps the memory behind the two logical buffers from then on.
+struct Fusion { int epilogue; int out_id; int res_id; int skip; int pw; int pw_relu; int rename; };
+
+// What plan_fusion yields when the depthwise + pointwise kernel cannot take the layer (image geometry, alignment).
+Fusion without_pointwise(Fusion f)
+{
+    if (f.pw) {
+        f.skip = f.pw - 1;
+        f.pw = 0;
+        f.pw_relu = 0;
+        f.rename = 0;
+    }
+    return f;
+}
 
 Fusion plan_fusion(const small_layer *L, int nL, int i)
 {
     const small_layer &c = L[i];
-    Fusion f = {EPI_NONE, c.dst, c.dst, 0};
+    Fusion f = {EPI_NONE, c.dst, c.dst, 0, 0, 0, 0};
     const bool conv = c.op == SMALL_OP_CONV || c.op == SMALL_OP_DENSE;
     if (!conv && c.op != SMALL_OP_DWCONV) return f;
     int j = i + 1;
@@ -270,6 +290,29 @@ Fusion plan_fusion(const small_layer *L, int nL, int i)
     if (j < nL && L[j].op == SMALL_OP_RELU && L[j].src == f.out_id && L[j].dst == f.out_id) {
         f.epilogue |= EPI_RELU;
         ++f.skip;
+        ++j;
+    }
+    if (c.op == SMALL_OP_DWCONV && j < nL && L[j].op == SMALL_OP_CONV && L[j].src == D && L[j].dst != SMALL_BUF_IN &&
+        (L[j].dst != c.src || (c.src >= 0 && D >= 0)) && L[j].Cib == 16 && L[j].Ci == c.Ci &&
+        L[j].pad.t == 0 && L[j].pad.b == 0 && L[j].pad.l == 0 && L[j].pad.r == 0 &&
+        dwpw_eligible(c.Ci, L[j].Co, c.Cib, L[j].Cob, c.kh, c.kw, c.stride, L[j].kh, L[j].kw, L[j].stride)) {
+        // the depthwise buffer D is never written: nobody may read it before it is rewritten
+        bool ok = true, rewritten = L[j].dst == D;
+        for (int k = j + 1; ok && !rewritten && k < nL; ++k) {
+            if (reads(L[k], D)) ok = false;
+            else if (L[k].dst == D) rewritten = true;
+        }
+        if (ok && !rewritten && D == SMALL_BUF_OUT) ok = false;
+        if (ok) {
+            f.pw = j - i;
+            f.skip = j - i;
+            f.rename = L[j].dst == c.src;
+            const int T = L[j].dst;
+            if (j + 1 < nL && L[j + 1].op == SMALL_OP_RELU && L[j + 1].src == T && L[j + 1].dst == T) {
+                f.pw_relu = 1;
+                ++f.skip;
+            }
+        }
     }
     return f;
 }
@@ -286,10 +329,13 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
     memset(shp, 0, sizeof(shp));
     auto idx = [](int id) { return id + 2; };   // OUT(-2) -> 0, IN(-1) -> 1, slot k -> k + 2
     auto valid_id = [](int id) { return id >= SMALL_BUF_OUT && id < SMALL_MAX_SLOTS; };
+    int phys[SMALL_MAX_SLOTS];                     // memory slot behind every logical slot id (see Fusion::rename)
+    for (int k = 0; k < SMALL_MAX_SLOTS; ++k) phys[k] = k;
+    unsigned may_swap = 0;
     auto ptr = [&](int id) -> float * {
         if (id == SMALL_BUF_IN) return const_cast<float *>(in_blocked);
         if (id == SMALL_BUF_OUT) return out_blocked;
-        return reinterpret_cast<float *>(ws + plan.slot_off[id]);
+        return reinterpret_cast<float *>(ws + plan.slot_off[phys[id]]);
     };
     if (!run) memset(&plan, 0, sizeof(plan));
     shp[idx(SMALL_BUF_IN)] = Shape{C0, H0, W0, L[0].Cib, true};
@@ -300,10 +346,14 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
         const small_layer &l = L[i];
         const bool head = fused_away == 0;             // this layer starts a launch (it is not folded into an earlier one)
         if (fused_away > 0) --fused_away;
-        Fusion fu = {EPI_NONE, l.dst, l.dst, 0};
+        Fusion fu = {EPI_NONE, l.dst, l.dst, 0, 0, 0, 0};
         if (run && head) {
             fu = plan_fusion(L, nL, i);
             fused_away = fu.skip;
+        } else if (!run && l.op == SMALL_OP_DWCONV) {
+            // a run may swap the memory behind these two slots: both must then hold either one's tensors
+            const Fusion f = plan_fusion(L, nL, i);
+            if (f.rename) may_swap |= (1u << l.src) | (1u << l.dst);
         }
         const bool launch = run && head && i >= first && (long)i < (long)first + count;
         if (!valid_id(l.src) || !valid_id(l.dst) || l.dst == SMALL_BUF_IN) return SMALL_ERR_LAYER;
@@ -339,7 +389,25 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.dst == l.src) return SMALL_ERR_ALIAS;
                 if (l.op == SMALL_OP_DWCONV && !l.filt) return SMALL_ERR_NULL;
                 o = Shape{l.Ci, g.Ho, g.Wo, l.Cib, true};
-                if (launch) {
+                if (run && head && fu.pw) {
+                    // the one-kernel depthwise + pointwise path also needs a geometry and pointers it can take;
+                    // otherwise the pointwise convolution becomes a launch of its own
+                    const small_layer &pw = L[i + fu.pw];
+                    const uintptr_t bits = (uintptr_t)ptr(l.src) | (uintptr_t)ptr(fu.rename ? l.dst : pw.dst) |
+                                           (uintptr_t)l.filt | (uintptr_t)pw.filt;
+                    if (!dwpw_geom_ok(g) || (bits & 15u)) {
+                        fu = without_pointwise(fu);
+                        fused_away = fu.skip;
+                    }
+                }
+                if (l.op == SMALL_OP_DWCONV && fu.pw) {
+                    const small_layer &pw = L[i + fu.pw];
+                    float *dst = ptr(fu.rename ? l.dst : pw.dst);
+                    if (launch)
+                        rc = from_hip(launch_dwpw(ptr(l.src), l.filt, pw.filt, dst, g, pw.Co,
+                                                  (fu.epilogue & EPI_RELU) != 0, fu.pw_relu, s));
+                    if (fu.rename) std::swap(phys[l.dst], phys[pw.dst]);
+                } else if (launch) {
                     if (l.op == SMALL_OP_DWCONV)
                         rc = from_hip(launch_dwconv(ptr(l.src), l.filt, ptr(l.dst), g, fu.epilogue, s));
                     else rc = from_hip(launch_pool(ptr(l.src), ptr(l.dst), g,
@@ -369,6 +437,11 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
         if (!run && l.dst == SMALL_BUF_OUT && out_elems > plan.out_elems) plan.out_elems = out_elems;
     }
     if (!run) {
+        size_t m = 0;
+        for (int k = 0; k < SMALL_MAX_SLOTS; ++k)
+            if ((may_swap >> k) & 1u) m = std::max(m, plan.slot_elems[k]);
+        for (int k = 0; k < SMALL_MAX_SLOTS; ++k)
+            if ((may_swap >> k) & 1u) plan.slot_elems[k] = m;
         size_t off = 0;
         for (int k = 0; k < SMALL_MAX_SLOTS; ++k) {
             plan.slot_off[k] = off;

@@ -53,6 +53,24 @@ inline FastDiv make_fastdiv(int d)
     return f;
 }
 
+// Direct global -> LDS loads, issued from inline assembly so that the compiler does not serialise them
+// against every LDS read; the issuing kernel tracks them by hand with wait_vmcnt.
+// 64 lanes x 16 B: global (base + per-lane byte offset) -> LDS (wave-uniform byte address + 16 * lane).
+__device__ __forceinline__ void dma16(const void *gbase, unsigned lane_off_bytes, unsigned lds_addr_uniform)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_off_bytes), "s"(gbase), "s"(__builtin_amdgcn_readfirstlane(lds_addr_uniform))
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+
 // Epilogue fused into the convolution's STORE phase (the paper's "abstract fused layer" direction).
 enum : int { EPI_NONE = 0, EPI_RELU = 1, EPI_ADD = 2 };   // ADD: accumulate onto the tensor `res` (same layout as out)
 
@@ -82,5 +100,13 @@ int conv_same_planes(const LayerGeom &g);        // Ci blocks staged per reducti
 int conv_same_images_per_workgroup(const LayerGeom &g, int tile);
 hipError_t launch_conv_same(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
                             int tile, int epilogue, hipStream_t s);
+
+// Depthwise 3x3 (+ ReLU) followed by pointwise 1x1 (+ ReLU) in one launch, 16-channel blocks. dwpw_eligible looks
+// at what a layer table states (channels, blocks, windows, strides); dwpw_geom_ok at the image geometry.
+constexpr size_t kDwPwMaxLds = 160 * 1024;
+bool dwpw_eligible(int C, int Co, int Cb, int Cob_pw, int kh, int kw, int stride, int pw_kh, int pw_kw, int pw_stride);
+bool dwpw_geom_ok(const LayerGeom &dw_geom);
+hipError_t launch_dwpw(const float *in, const float *dw_filt, const float *pw_filt, float *out, const LayerGeom &dw_geom,
+                       int Co, int relu_mid, int relu_out, hipStream_t s);
 
 }  // namespace small

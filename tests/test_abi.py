@@ -86,7 +86,12 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
     assert len(r.layers) == 21 and len(heads) == 11
     assert [r.layers[h].op for h in heads] == ["conv"] * 9 + ["avgpool", "dense"]
     ta = B.make_layer_table(a.layers, [None] * len(a.wshapes))
-    assert [a.layers[h].op for h in B.small_network_launches(ta)] == ["conv"] + ["dw", "conv"] * 4 + ["avgpool", "dense"]
+    # depthwise + ReLU + pointwise + ReLU blocks are one launch each
+    assert [a.layers[h].op for h in B.small_network_launches(ta)] == ["conv"] + ["dw"] * 4 + ["avgpool", "dense"]
+    d = WL.dsep_cnn()
+    td = B.make_layer_table(d.layers, [None] * len(d.wshapes))
+    # the first block has 8-channel blocks (two launches), the other 12 are fused
+    assert [d.layers[h].op for h in B.small_network_launches(td)] == ["conv", "dw", "conv"] + ["dw"] * 12 + ["avgpool", "dense"]
     # malformed tables
     t = B.make_layer_table(a.layers, [None] * len(a.wshapes))
     assert lib.small_network_workspace(t, len(t), 1, a.C0, a.H0, a.W0, C.byref(C.c_size_t())) == 1   # NULL filter

@@ -89,6 +89,79 @@ def test_intermediate_layers_of_residual_cnn():
         assert_close(got, trace[upto - 1], max(K, 1), f"residual_cnn after layer {upto} ({last.op})")
 
 
+# ------------------------------------------------------------------ depthwise + pointwise in one kernel
+
+def _block_net(C, Co, H, W, stride, relu_mid, relu_out, dw_dst=1, pw_dst=0, tail=None):
+    """IN -> relu -> slot 0, then dw (slot 0 -> dw_dst) [relu] -> 1x1 conv (dw_dst -> pw_dst) [relu] -> copy to OUT."""
+    from workloads.nets import Layer, Network, IN, OUT, same_pad
+    Ho, Wo = -(-H // stride), -(-W // stride)
+    pad = (same_pad(H, 3, stride) + same_pad(W, 3, stride))
+    net = Network("block_probe", C, H, W)
+    net.wshapes = [((C, 1, 3, 3), 9), ((Co, C, 1, 1), C)]
+    L = [Layer("relu", C, C, H, W, src=IN, dst=0),
+         Layer("dw", C, C, H, W, 3, 3, stride, pad, src=0, dst=dw_dst, w=0)]
+    if relu_mid:
+        L.append(Layer("relu", C, C, Ho, Wo, src=dw_dst, dst=dw_dst))
+    L.append(Layer("conv", C, Co, Ho, Wo, 1, 1, 1, (0, 0, 0, 0), src=dw_dst, dst=pw_dst, w=1))
+    if relu_out:
+        L.append(Layer("relu", Co, Co, Ho, Wo, src=pw_dst, dst=pw_dst))
+    L += tail(Co, Ho, Wo) if tail else [Layer("maxpool", Co, Co, Ho, Wo, 1, 1, 1, (0, 0, 0, 0), src=pw_dst, dst=OUT)]
+    net.layers = L
+    return net, pad
+
+
+BLOCK_CASES = [  # N, C, Co, H, W, stride, relu_mid, relu_out
+    (3, 16, 32, 24, 24, 2, True, True),       # two staged entries per pixel, ragged last tile (144 pixels)
+    (5, 32, 32, 12, 12, 1, True, True),
+    (2, 64, 128, 6, 6, 2, True, True),        # 3 x 3 output, two channel tiles
+    (7, 128, 128, 3, 3, 1, True, False),
+    (4, 256, 256, 2, 2, 1, False, True),      # the largest LDS footprint
+    (33, 64, 64, 25, 5, 1, True, True),       # the audio network's block
+    (2, 32, 48, 17, 9, 1, False, False),      # three output blocks, odd image
+    (300, 16, 16, 16, 16, 1, True, True),     # several images per workgroup
+    (2, 48, 16, 31, 31, 2, True, True),       # stride 2 on an odd image (top / left padding)
+    (256, 128, 128, 3, 3, 1, True, True),     # 9-pixel images: seven images per tile, last group shifted back
+    (37, 256, 256, 2, 2, 1, True, True),      # 4-pixel images: sixteen per tile
+    (5, 128, 256, 3, 3, 2, True, True),       # fewer images than a tile could take
+    (70, 64, 64, 6, 6, 2, True, True),        # 6 x 6 -> 3 x 3 with stride 2
+    (9, 32, 32, 5, 5, 1, False, True),        # 25-pixel images: two per tile
+]
+
+
+@pytest.mark.parametrize("case", BLOCK_CASES)
+def test_depthwise_pointwise_block(case):
+    N, C, Co, H, W, stride, relu_mid, relu_out = case
+    net, pad = _block_net(C, Co, H, W, stride, relu_mid, relu_out)
+    table = S.make_layer_table(net.layers, [None] * 2)
+    heads = [net.layers[h].op for h in S.small_network_launches(table)]
+    assert heads == ["relu", "dw", "maxpool"], heads          # the block is one launch
+    x, ws = WL.network_tensors(net, N, 4242)
+    got = _run(net, x, ws)
+    mid = O.dwconv2d(O.relu(x), ws[0], stride, pad)
+    if relu_mid:
+        mid = O.relu(mid)
+    ref = O.conv2d(mid, ws[1], 1, (0, 0, 0, 0))
+    if relu_out:
+        ref = O.relu(ref)
+    # two chained reductions: the error of the depthwise sum (K = 9) is amplified by the pointwise one (K = C)
+    assert_close(got, ref, 9 * C, f"dw+pw block {case}")
+
+
+def test_depthwise_output_read_later_is_not_fused():
+    """The depthwise result is needed again after the 1x1 convolution: it must be written."""
+    from workloads.nets import Layer, OUT
+
+    def tail(Co, Ho, Wo):
+        return [Layer("add", Co, Co, Ho, Wo, src=2, src2=1, dst=OUT)]
+    net, pad = _block_net(32, 32, 10, 10, 1, True, False, dw_dst=1, pw_dst=2, tail=tail)
+    table = S.make_layer_table(net.layers, [None] * 2)
+    assert [net.layers[h].op for h in S.small_network_launches(table)] == ["relu", "dw", "conv", "add"]
+    x, ws = WL.network_tensors(net, 3, 77)
+    mid = O.relu(O.dwconv2d(O.relu(x), ws[0], 1, pad))
+    ref = O.add(O.conv2d(mid, ws[1], 1, (0, 0, 0, 0)), mid)
+    assert_close(_run(net, x, ws), ref, 9 * 32, "dw kept, conv + add")
+
+
 # ------------------------------------------------------------------ full-size sweep layers (sampled)
 
 @pytest.mark.parametrize("C,H", WL.sweep_shapes()["conv"])
