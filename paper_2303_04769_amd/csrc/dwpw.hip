@@ -8,14 +8,15 @@
 // A workgroup (4 waves) owns one tile of 64 output pixels and one tile of up to 64 output channels, and
 // walks over images with all per-lane state fixed (see conv16_img in conv_same.hip). Images of at most 32
 // output pixels are taken several at a time (a tile is then a group of whole consecutive images), so that
-// the 3 x 3 and 2 x 2 layers at the end of a network still fill their lanes:
-//   1. depthwise phase, one step per (channel block, filter row): the input pixels of that row are staged
-//      global -> LDS (ring of STAGES steps, loads run STAGES - 1 steps ahead); lane (pixel p, quad q) reads
-//      its three taps as float4 (channels 4q .. 4q + 3), multiplies by the filter taps held in LDS and
-//      accumulates; after the third row the (ReLU'd) float4 goes to the "mid" tile in LDS (one float4 per
-//      lane and channel block: it is also the float4 this lane feeds to the matrix instructions);
-//   2. pointwise phase: 16x16x4 fp32 MFMAs, filter slabs resident in LDS for the whole kernel
-//      (loaded once per workgroup), pixel operand = mid tile; accumulators -> (ReLU) -> global.
+// the 3 x 3 and 2 x 2 layers at the end of a network still fill their lanes.
+//   1. depthwise phase, one step per 16-channel block: all input rows the tile's windows touch are staged
+//      global -> LDS as whole rows (ring of `stages` steps, loads run stages - 1 steps ahead; for short
+//      channel counts that is the whole tile at once); lane (pixel p, quad q) reads its nine taps as float4
+//      (channels 4q .. 4q + 3) from precomputed addresses and multiplies by the filter taps held in LDS;
+//   2. pointwise part of the same step: that (ReLU'd) float4 is exactly this lane's pixel operand of the
+//      16x16x4 fp32 MFMAs (B[k = 4q + r][pixel p]), so it goes from registers straight into the matrix
+//      instructions against the filter slabs of this channel block, which stay resident in LDS for the
+//      whole kernel (loaded once per workgroup). After the last block: accumulators -> (ReLU) -> global.
 // Taps outside the image are redirected to an all-zero LDS entry, as in the convolution kernels.
 #include "small_internal.h"
 
@@ -24,6 +25,9 @@
 namespace small {
 
 namespace {
+
+constexpr int kTM = 64;              // output pixels per tile
+constexpr int kMaxStages = 8;
 
 struct DwPwArgs {
     const float *in;
@@ -38,45 +42,45 @@ struct DwPwArgs {
     int GHW;             // output pixels of a tile group: ipt * Ho * Wo
     int n_igroups;       // tile groups in the batch: ceil(N / ipt); the last one is shifted back to end at image N - 1
     int n_mtiles, n_cotiles, n_groups;     // tiles per tile group, channel tiles, workgroups along the batch
-    FastDiv dWo, dHWo, dMt, dCt;
+    int stages;          // ring depth
+    int stage_bytes;     // staged entries of a step (64 B each, a whole number of 16-entry chunks) + the zero entry
+    FastDiv dW, dH, dWo, dHWo, dMt, dCt;
     int relu_mid, relu_out;
 };
 
-// ES: staged entries per output pixel (1: stride 1, 2: stride 2). WN: 16-channel output blocks per workgroup.
-template <int WN, int ES, int STAGES>
-struct DwPwCfg {
-    static constexpr int NW = 4, NT = 256, TM = 64, KS = 3;
-    static constexpr int ENT = ES * (TM - 1) + KS;
-    static constexpr int ENTP = (ENT + 15) / 16 * 16;
-    static constexpr int ZERO_REL = ENTP * 64;
-    static constexpr int STAGE_BYTES = ZERO_REL + 16;
-    static constexpr int NAI = ENTP / 16;                  // wave load instructions per step
-    static constexpr int LPS = (NAI + NW - 1) / NW;        // ... per wave
-    static constexpr int RING_BYTES = (STAGES * STAGE_BYTES + 255) / 256 * 256;
-    static_assert(STAGES == 3, "(ring slot, filter row) of an unrolled step are compile-time because STAGES == KS");
-    static_assert((STAGES - 2) * LPS < 64, "too many loads in flight for vmcnt");
-    // LDS: ring | mid tile (nCb x 64 pixels x 64 B) | pointwise filter slabs (nCb x WN KiB) | depthwise taps (nCb x 576 B)
-    static size_t lds_bytes(int nCb) { return (size_t)RING_BYTES + (size_t)nCb * (TM * 64 + WN * 1024 + 9 * 64); }
-};
+// Staged input rows of the tile that starts at output pixel m0 of a tile group: rows are numbered through the
+// images of the group (image * H + row); the tile needs rows [lo, hi]. Same arithmetic on host and device.
+__host__ __device__ inline void tile_rows(int m0, int GHW, int HWo, int Wo, int H, int stride, int pt, int &lo, int &hi)
+{
+    const int f0 = m0, f1 = (m0 + kTM - 1 < GHW - 1) ? m0 + kTM - 1 : GHW - 1;
+    const int img0 = f0 / HWo, oh0 = (f0 - img0 * HWo) / Wo;
+    const int img1 = f1 / HWo, oh1 = (f1 - img1 * HWo) / Wo;
+    int r0 = oh0 * stride - pt, r1 = oh1 * stride - pt + 2;
+    r0 = r0 < 0 ? 0 : (r0 > H - 1 ? H - 1 : r0);
+    r1 = r1 < 0 ? 0 : (r1 > H - 1 ? H - 1 : r1);
+    lo = img0 * H + r0;
+    hi = img1 * H + r1;
+}
 
-template <int WN, int ES, int STAGES>
+// LPS: load instructions per wave and step (a stage holds up to 64 * LPS entries). WN: 16-channel output blocks.
+template <int WN, int LPS>
 __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
 {
-    using C = DwPwCfg<WN, ES, STAGES>;
-    constexpr int NW = C::NW, TM = C::TM, KS = 3, ENT = C::ENT, LPS = C::LPS;
+    constexpr int NW = 4, NT = 256, TM = kTM;
+    static_assert((kMaxStages - 1) * LPS < 64, "too many loads in flight for vmcnt");
 
     extern __shared__ floatx4 lds[];
     const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)lds;
     char *lds_c = reinterpret_cast<char *>(lds);
-    const int mid_off = C::RING_BYTES;
-    const int pwf_off = mid_off + a.nCb * (TM * 64);
+    const int zero_rel = a.stage_bytes - 16;
+    const int pwf_off = (a.stages * a.stage_bytes + 255) & ~255;
     const int dwf_off = pwf_off + a.nCb * (WN * 1024);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lp = lane & 15, lq = lane >> 4;
 
-    // workgroup -> (image group, pixel tile of the image, channel tile), channel tile fastest
+    // workgroup -> (image group, pixel tile of the group, channel tile), channel tile fastest
     const int wg = (int)xcd_contiguous(blockIdx.x, gridDim.x);
     const int t = a.dCt.div(wg);
     const int co_tile = wg - t * a.n_cotiles;
@@ -87,6 +91,67 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
     const size_t planeA = (size_t)a.HW * 64;
     const size_t imgA = (size_t)a.nCb * planeA;
     const size_t imgO = (size_t)a.nCob * a.HWo * 64;
+    int row_lo, row_hi;
+    tile_rows(m0, a.GHW, a.HWo, a.Wo, a.H, a.stride, a.pt, row_lo, row_hi);
+
+    // ---- load descriptors of a step (one 16-channel block of the tile's input rows), relative to the first
+    // image of the tile group and to the channel block. Chunks past the tile's rows repeat its last row.
+    unsigned d_voff[LPS];
+    unsigned d_lds[LPS];
+    const int n_chunks = (a.stage_bytes - 16) / 1024;
+#pragma unroll
+    for (int j = 0; j < LPS; ++j) {
+        const int chunk = min(j * NW + wave, n_chunks - 1);
+        const int e = chunk * 16 + (lane >> 2);
+        const int quad = (lane & 3) ^ ((e >> 1) & 3);
+        const int er = a.dW.div(e);
+        const int R = min(row_lo + er, row_hi), col = e - er * a.W;
+        const int img = a.dH.div(R), row = R - img * a.H;
+        d_voff[j] = (unsigned)(img * imgA) + (unsigned)(((row * a.W + col) * 16 + quad * 4) * 4);
+        d_lds[j] = __builtin_amdgcn_readfirstlane((unsigned)(chunk * 1024));
+    }
+
+    // ---- this lane's pixel: tap addresses in a stage, mid-tile address, output offset
+    const int px = wave * 16 + lp;
+    const bool o_ok = m0 + px < a.GHW;
+    unsigned p_addr[9];
+    unsigned o_off;
+    {
+        const int f = min(m0 + px, a.GHW - 1);
+        const int img = a.dHWo.div(f), pix = f - img * a.HWo;
+        const int oh = a.dWo.div(pix), ow = pix - oh * a.Wo;
+        o_off = (unsigned)(img * imgO) + (unsigned)((pix * 16 + lq * 4) * 4);
+#pragma unroll
+        for (int y = 0; y < 3; ++y)
+#pragma unroll
+            for (int x = 0; x < 3; ++x) {
+                const int ir = oh * a.stride + y - a.pt, ic = ow * a.stride + x - a.pl;
+                const bool ok = (unsigned)ir < (unsigned)a.H && (unsigned)ic < (unsigned)a.W;
+                const int e = (img * a.H + ir - row_lo) * a.W + ic;
+                p_addr[y * 3 + x] = ok ? (unsigned)((e * 4 + (lq ^ ((e >> 1) & 3))) * 16) : (unsigned)zero_rel;
+            }
+    }
+    const unsigned b_addr = (unsigned)(pwf_off + lane * 4);
+    const unsigned w_addr = (unsigned)(dwf_off + lq * 16);
+
+    // ---- issue side of the input pipeline: (tile group, channel block) of the next step to load
+    const char *in_c = reinterpret_cast<const char *>(a.in);
+    char *out_c = reinterpret_cast<char *>(a.out);
+    // tile group q covers images first_image(q) .. + ipt - 1
+    auto first_image = [&](int q) __attribute__((always_inline)) { return min(q * a.ipt, a.N - a.ipt); };
+    int i_n = grp, i_cb = 0, i_slot = 0, ahead = 0;        // i_n, n: tile groups
+    auto issue_step = [&]() __attribute__((always_inline)) {
+        const char *base = in_c + (size_t)first_image(i_n) * imgA + (size_t)i_cb * planeA;
+        const unsigned stage_lds = lds_base + (unsigned)(i_slot * a.stage_bytes);
+#pragma unroll
+        for (int j = 0; j < LPS; ++j) dma16(base, d_voff[j], stage_lds + d_lds[j]);
+        ++ahead;
+        if (++i_slot == a.stages) i_slot = 0;
+        if (++i_cb == a.nCb) { i_cb = 0; i_n += a.n_groups; }
+    };
+    // the input pipeline starts before the resident operands are fetched, so that both latencies overlap
+    for (int s = 0; s < a.stages - 1; ++s)
+        if (i_n < a.n_igroups) issue_step();
 
     // ---- resident operands: pointwise filter slabs of this channel tile and all depthwise taps
     {
@@ -99,143 +164,67 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
             dma16(a.pwf, off, lds_base + (unsigned)(pwf_off + sidx * 1024));
         }
         const int ndw = a.nCb * 9 * 4;                                   // float4s
-        for (int e = tid; e < ndw; e += C::NT)
+        for (int e = tid; e < ndw; e += NT)
             *reinterpret_cast<floatx4 *>(lds_c + dwf_off + e * 16) = reinterpret_cast<const floatx4 *>(a.dwf)[e];
-        if (tid < STAGES) *reinterpret_cast<floatx4 *>(lds_c + tid * C::STAGE_BYTES + C::ZERO_REL) = floatx4{0.f, 0.f, 0.f, 0.f};
-        wait_vmcnt<0>();
+        if (tid < a.stages) *reinterpret_cast<floatx4 *>(lds_c + tid * a.stage_bytes + zero_rel) = floatx4{0.f, 0.f, 0.f, 0.f};
+        wait_vmcnt<0>();                                                 // also the first input steps: they are older
         __syncthreads();
     }
 
-    // ---- load descriptors of the input steps, relative to the start of an image and a channel block
-    unsigned d_voff[LPS][KS];
-    unsigned d_lds[LPS];
+    int cb = 0, slot = 0;                                  // channel block being reduced, its ring slot
+    floatx4 acc[WN];
 #pragma unroll
-    for (int j = 0; j < LPS; ++j) {
-        const int chunk = min(j * NW + wave, C::NAI - 1);
-        const int e = chunk * 16 + (lane >> 2);
-        const int quad = (lane & 3) ^ ((e >> 1) & 3);
-        int img, hb, wb;                         // image in the tile group and source pixel of entry e for filter row 0
-        if constexpr (ES == 1) {                 // consecutive input pixels (input and output pixel order agree)
-            const int fb = m0 + e - a.pl;
-            const bool ok = e < ENT && fb >= 0 && fb < a.GHW;
-            const int f = ok ? fb : 0;
-            img = a.dHWo.div(f);
-            const int pix = f - img * a.HWo;
-            hb = a.dWo.div(pix);
-            wb = pix - hb * a.Wo;
-        } else {                                 // entry e: tap e % 2 of output pixel e / 2 (last entry: tap 2 of the last pixel)
-            const int pxe = min(e / ES, TM - 1), xe = min(e - pxe * ES, KS - 1);
-            const int f = min(m0 + pxe, a.GHW - 1);
-            img = a.dHWo.div(f);
-            const int pix = f - img * a.HWo;
-            const int oh = a.dWo.div(pix), ow = pix - oh * a.Wo;
-            hb = oh * a.stride;
-            wb = min(max(ow * a.stride + xe - a.pl, 0), a.W - 1);
-        }
-#pragma unroll
-        for (int y = 0; y < KS; ++y) {
-            const int row = min(max(hb + y - a.pt, 0), a.H - 1);
-            d_voff[j][y] = (unsigned)(img * imgA) + (unsigned)(((row * a.W + wb) * 16 + quad * 4) * 4);
-        }
-        d_lds[j] = __builtin_amdgcn_readfirstlane((unsigned)(chunk * 16 * 64));
-    }
-
-    // ---- this lane's pixel: tap addresses in a stage, mid-tile address, output offset
-    const int px = wave * 16 + lp;
-    const bool o_ok = m0 + px < a.GHW;
-    unsigned p_addr[KS][KS];
-    unsigned o_off;
-    {
-        const int f = min(m0 + px, a.GHW - 1);
-        const int img = a.dHWo.div(f), pix = f - img * a.HWo;
-        const int oh = a.dWo.div(pix), ow = pix - oh * a.Wo;
-        o_off = (unsigned)(img * imgO) + (unsigned)((pix * 16 + lq * 4) * 4);
-        bool row_ok[KS], col_ok[KS];
-        unsigned real[KS];
-#pragma unroll
-        for (int k = 0; k < KS; ++k) {
-            row_ok[k] = (unsigned)(oh * a.stride + k - a.pt) < (unsigned)a.H;
-            col_ok[k] = (unsigned)(ow * a.stride + k - a.pl) < (unsigned)a.W;
-            const int e = px * ES + k;
-            real[k] = (unsigned)((e * 4 + (lq ^ ((e >> 1) & 3))) * 16);
-        }
-#pragma unroll
-        for (int y = 0; y < KS; ++y)
-#pragma unroll
-            for (int x = 0; x < KS; ++x) p_addr[y][x] = (row_ok[y] && col_ok[x]) ? real[x] : (unsigned)C::ZERO_REL;
-    }
-    // mid tile of channel block cb: pixel-major entries of 64 B, quads swizzled like a staged input chunk
-    const unsigned mid_addr = (unsigned)(mid_off + (px * 4 + (lq ^ ((px >> 1) & 3))) * 16);
-    const unsigned b_addr = (unsigned)(pwf_off + lane * 4);
-    const unsigned w_addr = (unsigned)(dwf_off + lq * 16);
-
-    // ---- issue side of the input pipeline: (image, channel block, filter row) of the next step to load
-    const int nsteps = a.nCb * KS;
-    const char *in_c = reinterpret_cast<const char *>(a.in);
-    char *out_c = reinterpret_cast<char *>(a.out);
-    // tile group q covers images first_image(q) .. + ipt - 1
-    auto first_image = [&](int q) __attribute__((always_inline)) { return min(q * a.ipt, a.N - a.ipt); };
-    int i_n = grp, i_step = 0, ahead = 0;                  // i_n, n: tile groups
-    auto issue_step = [&](int y, int slot) __attribute__((always_inline)) {
-        const char *base = in_c + (size_t)first_image(i_n) * imgA + (size_t)(i_step / KS) * planeA;
-        const unsigned stage_lds = lds_base + (unsigned)slot * C::STAGE_BYTES;
-#pragma unroll
-        for (int j = 0; j < LPS; ++j) dma16(base, d_voff[j][y], stage_lds + d_lds[j]);
-        ++ahead;
-        if (++i_step == nsteps) { i_step = 0; i_n += a.n_groups; }
-    };
-#pragma unroll
-    for (int s = 0; s < STAGES - 1; ++s)
-        if (i_n < a.n_igroups) issue_step(s % KS, s % STAGES);
-
-    floatx4 dw = floatx4{0.f, 0.f, 0.f, 0.f};
-    int cb = 0;                                            // channel block being reduced
+    for (int j = 0; j < WN; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
     for (int n = grp; n < a.n_igroups;) {
-#pragma unroll
-        for (int u = 0; u < KS; ++u) {                     // ring slot == filter row == u (STAGES == KS)
-            if (ahead > STAGES - 2) wait_vmcnt<(STAGES - 2) * LPS>();
-            else wait_vmcnt<0>();
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-            --ahead;
-            if (i_n < a.n_igroups) issue_step((u + STAGES - 1) % KS, (u + STAGES - 1) % STAGES);
-            const char *stage = lds_c + u * C::STAGE_BYTES;
-            const char *wrow = lds_c + w_addr + (cb * 9 + u * 3) * 64;
-#pragma unroll
-            for (int x = 0; x < KS; ++x) {
-                const floatx4 v = *reinterpret_cast<const floatx4 *>(stage + p_addr[u][x]);
-                const floatx4 w = *reinterpret_cast<const floatx4 *>(wrow + x * 64);
-                dw.x = fmaf(v.x, w.x, dw.x); dw.y = fmaf(v.y, w.y, dw.y);
-                dw.z = fmaf(v.z, w.z, dw.z); dw.w = fmaf(v.w, w.w, dw.w);
-            }
-        }
-        if (a.relu_mid) {
-            dw.x = dw.x > 0.f ? dw.x : 0.f; dw.y = dw.y > 0.f ? dw.y : 0.f;
-            dw.z = dw.z > 0.f ? dw.z : 0.f; dw.w = dw.w > 0.f ? dw.w : 0.f;
-        }
-        *reinterpret_cast<floatx4 *>(lds_c + mid_addr + cb * (TM * 64)) = dw;
-        dw = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (++cb < a.nCb) continue;
-        cb = 0;
-
-        // ---- pointwise phase. The matrix instruction's pixel operand of lane (p, q) is channels 4q .. 4q + 3 of
-        // pixel p: exactly the float4s this lane wrote, so no barrier is needed between the two phases.
-        floatx4 acc[WN];
-#pragma unroll
-        for (int j = 0; j < WN; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < a.nCb; ++c) {
-            const floatx4 fa = *reinterpret_cast<const floatx4 *>(lds_c + mid_addr + c * (TM * 64));
-            const char *bs = lds_c + b_addr + c * (WN * 1024);
-            float fb[WN][4];
+        // pointwise filter fragments of this channel block: independent of the staged input, requested first
+        float fb[WN][4];
+        {
+            const char *bs = lds_c + b_addr + cb * (WN * 1024);
 #pragma unroll
             for (int j = 0; j < WN; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) fb[j][r] = *reinterpret_cast<const float *>(bs + j * 1024 + r * 256);
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int j = 0; j < WN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fb[j][r], fa[r], acc[j], 0, 0, 0);
         }
+        // the step to compute has landed once at most the loads of the steps issued after it are outstanding
+        switch (ahead - 1) {
+            case 0: wait_vmcnt<0>(); break;
+            case 1: wait_vmcnt<LPS>(); break;
+            case 2: wait_vmcnt<2 * LPS>(); break;
+            case 3: wait_vmcnt<3 * LPS>(); break;
+            case 4: wait_vmcnt<4 * LPS>(); break;
+            case 5: wait_vmcnt<5 * LPS>(); break;
+            case 6: wait_vmcnt<6 * LPS>(); break;
+            default: wait_vmcnt<7 * LPS>(); break;
+        }
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        --ahead;
+        if (i_n < a.n_igroups) issue_step();               // into the slot that was computed one step ago
+        floatx4 dw = floatx4{0.f, 0.f, 0.f, 0.f};
+        {
+            const char *stage = lds_c + slot * a.stage_bytes;
+            const char *wrow = lds_c + w_addr + cb * (9 * 64);
+#pragma unroll
+            for (int k = 0; k < 9; ++k) {
+                const floatx4 v = *reinterpret_cast<const floatx4 *>(stage + p_addr[k]);
+                const floatx4 w = *reinterpret_cast<const floatx4 *>(wrow + k * 64);
+                dw.x = fmaf(v.x, w.x, dw.x); dw.y = fmaf(v.y, w.y, dw.y);
+                dw.z = fmaf(v.z, w.z, dw.z); dw.w = fmaf(v.w, w.w, dw.w);
+            }
+            if (a.relu_mid) {
+                dw.x = dw.x > 0.f ? dw.x : 0.f; dw.y = dw.y > 0.f ? dw.y : 0.f;
+                dw.z = dw.z > 0.f ? dw.z : 0.f; dw.w = dw.w > 0.f ? dw.w : 0.f;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int j = 0; j < WN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fb[j][r], dw[r], acc[j], 0, 0, 0);
+        if (++slot == a.stages) slot = 0;
+        if (++cb < a.nCb) continue;
+        cb = 0;
+
+        // ---- STORE phase of this tile
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const int cob = cob0 + j;
@@ -247,89 +236,139 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
                 }
                 *reinterpret_cast<floatx4 *>(out_c + (size_t)first_image(n) * imgO + (size_t)cob * a.HWo * 64 + o_off) = v;
             }
+            acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
         }
         n += a.n_groups;
     }
 }
 
-template <int WN, int ES>
-hipError_t launch_cfg(DwPwArgs a, hipStream_t s)
+// Host-side shape of a launch: images per tile, staged entries per step, ring depth, LDS bytes.
+struct DwPwPlan {
+    int ipt, GHW, n_mtiles, chunks, stage_bytes, stages, lps, wn;
+    size_t lds;
+    bool ok;
+};
+
+DwPwPlan make_plan(const LayerGeom &g, int Co)
 {
-    using C = DwPwCfg<WN, ES, 3>;
-    auto kern = dwpw16_img<WN, ES, 3>;
-    const size_t lds = C::lds_bytes(a.nCb);
+    DwPwPlan p = {};
+    const int HWo = g.Ho * g.Wo, nCb = g.Ci / 16, nCob = Co / 16;
+    p.ipt = HWo <= 32 ? std::max(1, std::min(g.N, kTM / HWo)) : 1;
+    p.GHW = p.ipt * HWo;
+    p.n_mtiles = (p.GHW + kTM - 1) / kTM;
+    // output channel blocks per workgroup: up to 4 (the depthwise part is redone by every channel tile), fewer
+    // when that leaves compute units without a workgroup
+    int wn = std::min(4, nCob);
+    const long tiles = (long)p.n_mtiles * ((g.N + p.ipt - 1) / p.ipt);
+    while (wn > 1 && tiles * ((nCob + wn - 1) / wn) < 256) wn = (wn + 1) / 2;
+    p.wn = wn;
+    int ent = 0;
+    for (int m = 0; m < p.n_mtiles; ++m) {
+        int lo, hi;
+        tile_rows(m * kTM, p.GHW, HWo, g.Wo, g.H, g.stride, g.pt, lo, hi);
+        ent = std::max(ent, (hi - lo + 1) * g.W);
+    }
+    p.chunks = (ent + 15) / 16;
+    p.stage_bytes = p.chunks * 1024 + 16;
+    p.lps = (p.chunks + 3) / 4;
+    p.lps = p.lps <= 2 ? 2 : p.lps <= 4 ? 4 : p.lps <= 6 ? 6 : 8;
+    const size_t fixed = (size_t)nCb * (wn * 1024 + 9 * 64);
+    // ring: as deep as 8 steps and never more loads in flight than the 6-bit counter can track. With work for
+    // four workgroups per compute unit, latencies are hidden by occupancy: the workgroup stays within 40 KiB of
+    // LDS if three stages fit in that; otherwise by depth: up to 48 KiB of ring.
+    const size_t room = kDwPwMaxLds > fixed + 256 ? kDwPwMaxLds - fixed - 256 : 0;
+    size_t budget = std::min<size_t>(48 * 1024, room);
+    if (tiles * ((nCob + wn - 1) / wn) >= 1024 && fixed + 256 + 3 * (size_t)p.stage_bytes <= 40 * 1024)
+        budget = 40 * 1024 - fixed - 256;
+    p.stages = (int)std::min<size_t>({(size_t)kMaxStages, budget / (size_t)p.stage_bytes, (size_t)(63 / p.lps + 1)});
+    p.lds = (size_t)((p.stages * p.stage_bytes + 255) & ~255) + fixed;
+    p.ok = p.chunks <= 32 && p.stages >= 2 && p.lds <= kDwPwMaxLds;
+    return p;
+}
+
+template <int WN, int LPS>
+hipError_t launch_cfg(DwPwArgs a, const DwPwPlan &p, hipStream_t s)
+{
+    auto kern = dwpw16_img<WN, LPS>;
     static size_t lds_allowed = 64 * 1024;
-    if (lds > lds_allowed) {
+    if (p.lds > lds_allowed) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                                  (int)kDwPwMaxLds);
         if (e != hipSuccess) return e;
         lds_allowed = kDwPwMaxLds;
     }
-    a.ipt = a.HWo <= 32 ? std::max(1, std::min(a.N, C::TM / a.HWo)) : 1;
-    a.GHW = a.ipt * a.HWo;
+    a.ipt = p.ipt;
+    a.GHW = p.GHW;
     a.n_igroups = (a.N + a.ipt - 1) / a.ipt;
-    a.n_mtiles = (a.GHW + C::TM - 1) / C::TM;
+    a.n_mtiles = p.n_mtiles;
     a.n_cotiles = (a.nCob + WN - 1) / WN;
+    a.stages = p.stages;
+    a.stage_bytes = p.stage_bytes;
     // tile groups per workgroup: enough workgroups to fill the chip (as many as LDS lets be resident, at most 4
     // per compute unit), the rest of the batch is walked by each workgroup with its set-up paid once
     const long positions = (long)a.n_mtiles * a.n_cotiles;
-    const long resident = 256 * std::max<long>(1, std::min<long>(4, (long)(160 * 1024 / lds)));
+    const long resident = 256 * std::max<long>(1, std::min<long>(4, (long)(160 * 1024 / p.lds)));
     const long per_wg = std::max<long>(1, std::min<long>(a.n_igroups, (positions * a.n_igroups + resident - 1) / resident));
     a.n_groups = (int)((a.n_igroups + per_wg - 1) / per_wg);
+    a.dW = make_fastdiv(a.W);
+    a.dH = make_fastdiv(a.H);
     a.dWo = make_fastdiv(a.Wo);
     a.dHWo = make_fastdiv(a.HWo);
     a.dMt = make_fastdiv(a.n_mtiles);
     a.dCt = make_fastdiv(a.n_cotiles);
     const unsigned grid = (unsigned)(positions * a.n_groups);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::NT), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), p.lds, s, a);
     return hipGetLastError();
+}
+
+template <int WN>
+hipError_t launch_wn(const DwPwArgs &a, const DwPwPlan &p, hipStream_t s)
+{
+    switch (p.lps) {
+        case 2: return launch_cfg<WN, 2>(a, p, s);
+        case 4: return launch_cfg<WN, 4>(a, p, s);
+        case 6: return launch_cfg<WN, 6>(a, p, s);
+        default: return launch_cfg<WN, 8>(a, p, s);
+    }
 }
 
 }  // namespace
 
 bool dwpw_eligible(int C, int Co, int Cb, int Cob_pw, int kh, int kw, int stride, int pw_kh, int pw_kw, int pw_stride)
 {
-    if (Cb != 16 || Cob_pw != 16 || kh != 3 || kw != 3 || (stride != 1 && stride != 2)) return false;
+    if (Cb != 16 || Cob_pw != 16 || kh != 3 || kw != 3 || stride < 1) return false;
     if (pw_kh != 1 || pw_kw != 1 || pw_stride != 1 || C % 16 || Co % 16) return false;
-    const int wn = std::min(4, Co / 16);
-    const size_t lds = (size_t)(stride == 1 ? 16 * 1024 : 28 * 1024) + (size_t)(C / 16) * (64 * 64 + wn * 1024 + 9 * 64);
-    return lds <= kDwPwMaxLds;
+    // resident filters + the smallest ring must fit
+    const size_t fixed = (size_t)(C / 16) * (std::min(4, Co / 16) * 1024 + 9 * 64);
+    return fixed + 2 * (4 * 1024 + 16) + 256 <= kDwPwMaxLds;
 }
 
-bool dwpw_geom_ok(const LayerGeom &g)
+bool dwpw_geom_ok(const LayerGeom &g, int Co)
 {
-    const bool small_enough = (size_t)g.N * g.Ci * g.H * g.W < ((size_t)1 << 30) && (size_t)g.Ci * g.H * g.W < ((size_t)1 << 26);
-    if (!small_enough || g.pt >= 3 || g.pl >= 3) return false;
-    // several small images per tile: their offsets are part of the 32-bit per-lane offsets
-    if ((size_t)64 * g.Ci * g.H * g.W * 4 >= ((size_t)1 << 31) && g.Ho * g.Wo <= 32) return false;
-    if (g.stride == 1) return g.Ho == g.H && g.Wo == g.W;
-    return g.stride == 2 && 2 * (g.Wo - 1) + 2 - g.pl >= g.W;    // see conv_same_eligible
+    // per-lane 32-bit byte offsets span the images of a tile group
+    const bool small_enough = (size_t)g.N * g.Ci * g.H * g.W < ((size_t)1 << 30) &&
+                              (size_t)64 * g.Ci * g.H * g.W * 4 < ((size_t)1 << 31) &&
+                              (size_t)64 * Co * g.Ho * g.Wo * 4 < ((size_t)1 << 31);
+    return small_enough && g.pt < 3 && g.pl < 3 && make_plan(g, Co).ok;
 }
 
 hipError_t launch_dwpw(const float *in, const float *dw_filt, const float *pw_filt, float *out, const LayerGeom &g, int Co,
                        int relu_mid, int relu_out, hipStream_t s)
 {
-    DwPwArgs a;
+    DwPwArgs a = {};
     a.in = in; a.dwf = dw_filt; a.pwf = pw_filt; a.out = out;
     a.N = g.N; a.H = g.H; a.W = g.W; a.HW = g.H * g.W;
     a.Ho = g.Ho; a.Wo = g.Wo; a.HWo = g.Ho * g.Wo; a.stride = g.stride;
     a.nCb = g.Ci / 16; a.nCob = Co / 16;
     a.pt = g.pt; a.pl = g.pl;
     a.relu_mid = relu_mid; a.relu_out = relu_out;
-    const int wn = std::min(4, a.nCob);
-    if (g.stride == 1) {
-        switch (wn) {
-            case 1: return launch_cfg<1, 1>(a, s);
-            case 2: return launch_cfg<2, 1>(a, s);
-            case 3: return launch_cfg<3, 1>(a, s);
-            default: return launch_cfg<4, 1>(a, s);
-        }
-    }
-    switch (wn) {
-        case 1: return launch_cfg<1, 2>(a, s);
-        case 2: return launch_cfg<2, 2>(a, s);
-        case 3: return launch_cfg<3, 2>(a, s);
-        default: return launch_cfg<4, 2>(a, s);
+    const DwPwPlan p = make_plan(g, Co);
+    if (!p.ok) return hipErrorInvalidValue;
+    switch (p.wn) {
+        case 1: return launch_wn<1>(a, p, s);
+        case 2: return launch_wn<2>(a, p, s);
+        case 3: return launch_wn<3>(a, p, s);
+        default: return launch_wn<4>(a, p, s);
     }
 }
 

@@ -395,7 +395,7 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                     const small_layer &pw = L[i + fu.pw];
                     const uintptr_t bits = (uintptr_t)ptr(l.src) | (uintptr_t)ptr(fu.rename ? l.dst : pw.dst) |
                                            (uintptr_t)l.filt | (uintptr_t)pw.filt;
-                    if (!dwpw_geom_ok(g) || (bits & 15u)) {
+                    if (!dwpw_geom_ok(g, pw.Co) || (bits & 15u)) {
                         fu = without_pointwise(fu);
                         fused_away = fu.skip;
                     }

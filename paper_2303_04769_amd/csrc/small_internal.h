@@ -105,7 +105,7 @@ hipError_t launch_conv_same(const float *in, const float *filt, float *out, cons
 // at what a layer table states (channels, blocks, windows, strides); dwpw_geom_ok at the image geometry.
 constexpr size_t kDwPwMaxLds = 160 * 1024;
 bool dwpw_eligible(int C, int Co, int Cb, int Cob_pw, int kh, int kw, int stride, int pw_kh, int pw_kw, int pw_stride);
-bool dwpw_geom_ok(const LayerGeom &dw_geom);
+bool dwpw_geom_ok(const LayerGeom &dw_geom, int Co);
 hipError_t launch_dwpw(const float *in, const float *dw_filt, const float *pw_filt, float *out, const LayerGeom &dw_geom,
                        int Co, int relu_mid, int relu_out, hipStream_t s);
 
