@@ -278,11 +278,16 @@ __global__ void __launch_bounds__(256) dense_rows(ConvArgs a, int Cob, int K, si
 // broadcast float4; input values are read once per lane. HBM-bound in practice (K is tiny).
 constexpr int kSmallMaxFilterFloats = 12 * 1024;     // 48 KiB of LDS
 
-__global__ void __launch_bounds__(256) conv_small(ConvArgs a, int Cib, int Cob, int kfloats)
+// CIB, KH, KW: compile-time input block and window of the common first layers (0: taken from the arguments).
+// Taps are branch-free (address clamped into the image, value replaced by zero outside), so with
+// compile-time bounds all input loads of a pixel are in flight together instead of one round trip per tap.
+template <int CIB, int KH, int KW>
+__global__ void __launch_bounds__(256) conv_small(ConvArgs a, int Cib_rt, int Cob, int kfloats)
 {
+    const int Cib = CIB ? CIB : Cib_rt, kh = KH ? KH : a.kh, kw = KW ? KW : a.kw;
     extern __shared__ floatx4 wl[];                   // [nCib][kh][kw][Cib] rows of 16 output channels
     const int cob = blockIdx.y;
-    const int K = a.nCib * a.kh * a.kw * Cib;         // reduction length
+    const int K = a.nCib * kh * kw * Cib;             // reduction length
     // filter of this block: [cib][y][x][ci][Cob] with cib stride kh*kw*Cib*Cob, block stride nCib * that
     const float *wsrc = a.filt + (size_t)cob * K * Cob;
     for (int e = threadIdx.x; e < K * 16; e += 256) {
@@ -300,21 +305,53 @@ __global__ void __launch_bounds__(256) conv_small(ConvArgs a, int Cib, int Cob, 
     int k = 0;
     for (int cib = 0; cib < a.nCib; ++cib) {
         const float *plane = a.in + (size_t)(n * a.nCib + cib) * a.H * a.W * Cib;
-        for (int y = 0; y < a.kh; ++y) {
-            const int ih = oh * a.stride - a.pt + y;
-            const bool oky = ih >= 0 && ih < a.H;
-            for (int x = 0; x < a.kw; ++x, k += Cib) {
-                const int iw = ow * a.stride - a.pl + x;
-                if (!oky || iw < 0 || iw >= a.W) continue;
-                const float *ip = plane + (size_t)(ih * a.W + iw) * Cib;
-                for (int ci = 0; ci < Cib; ++ci) {
-                    const float v = ip[ci];
-                    const floatx4 *w = wl + (size_t)(k + ci) * 4;
+        if constexpr (CIB * KH * KW != 0) {
+            // all input values of the window first (one batch of loads), then the multiply-adds tap by tap
+            float v[KH * KW * CIB];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const floatx4 wq = w[q];
-                        acc[q].x = fmaf(v, wq.x, acc[q].x); acc[q].y = fmaf(v, wq.y, acc[q].y);
-                        acc[q].z = fmaf(v, wq.z, acc[q].z); acc[q].w = fmaf(v, wq.w, acc[q].w);
+            for (int y = 0; y < KH; ++y) {
+                const int ih = oh * a.stride - a.pt + y;
+                const int ihc = min(max(ih, 0), a.H - 1);
+#pragma unroll
+                for (int x = 0; x < KW; ++x) {
+                    const int iw = ow * a.stride - a.pl + x;
+                    const int iwc = min(max(iw, 0), a.W - 1);
+                    const bool ok = ih == ihc && iw == iwc;
+                    const float *ip = plane + (size_t)(ihc * a.W + iwc) * CIB;
+#pragma unroll
+                    for (int ci = 0; ci < CIB; ++ci) v[(y * KW + x) * CIB + ci] = ok ? ip[ci] : 0.f;
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < KH * KW * CIB; ++t) {
+                const floatx4 *w = wl + (size_t)(k + t) * 4;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const floatx4 wq = w[q];
+                    acc[q].x = fmaf(v[t], wq.x, acc[q].x); acc[q].y = fmaf(v[t], wq.y, acc[q].y);
+                    acc[q].z = fmaf(v[t], wq.z, acc[q].z); acc[q].w = fmaf(v[t], wq.w, acc[q].w);
+                }
+                if (t % 2 == 1) __builtin_amdgcn_sched_barrier(0);    // keeps the filter reads from being hoisted wholesale
+            }
+            k += KH * KW * CIB;
+        } else {
+            for (int y = 0; y < kh; ++y) {
+                const int ih = oh * a.stride - a.pt + y;
+                const int ihc = min(max(ih, 0), a.H - 1);
+                for (int x = 0; x < kw; ++x, k += Cib) {
+                    const int iw = ow * a.stride - a.pl + x;
+                    const int iwc = min(max(iw, 0), a.W - 1);
+                    const bool ok = ih == ihc && iw == iwc;
+                    const float *ip = plane + (size_t)(ihc * a.W + iwc) * Cib;
+                    for (int ci = 0; ci < Cib; ++ci) {
+                        const float v = ok ? ip[ci] : 0.f;
+                        const floatx4 *w = wl + (size_t)(k + ci) * 4;
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const floatx4 wq = w[q];
+                            acc[q].x = fmaf(v, wq.x, acc[q].x); acc[q].y = fmaf(v, wq.y, acc[q].y);
+                            acc[q].z = fmaf(v, wq.z, acc[q].z); acc[q].w = fmaf(v, wq.w, acc[q].w);
+                        }
                     }
                 }
             }
@@ -427,7 +464,15 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
         const int kfloats = a.nCib * g.kh * g.kw * g.Cib * 16;
         if (use_small(g)) {
             const dim3 grid((unsigned)((a.M + 255) / 256), (unsigned)a.nCob);
-            hipLaunchKernelGGL(conv_small, grid, dim3(256), (size_t)kfloats * 4, s, a, g.Cib, g.Cob, kfloats);
+            const size_t lds = (size_t)kfloats * 4;
+            if (g.Cib == 3 && g.kh == 3 && g.kw == 3)
+                hipLaunchKernelGGL((conv_small<3, 3, 3>), grid, dim3(256), lds, s, a, g.Cib, g.Cob, kfloats);
+            else if (g.Cib == 1 && g.kh == 10 && g.kw == 4)
+                hipLaunchKernelGGL((conv_small<1, 10, 4>), grid, dim3(256), lds, s, a, g.Cib, g.Cob, kfloats);
+            else if (g.Cib == 8 && g.kh == 1 && g.kw == 1)
+                hipLaunchKernelGGL((conv_small<8, 1, 1>), grid, dim3(256), lds, s, a, g.Cib, g.Cob, kfloats);
+            else
+                hipLaunchKernelGGL((conv_small<0, 0, 0>), grid, dim3(256), lds, s, a, g.Cib, g.Cob, kfloats);
             return hipGetLastError();
         }
         const size_t total = (size_t)a.M * g.Co;
