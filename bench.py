@@ -331,8 +331,16 @@ def networks(S, WL, torch, dev, timed):
             spin(fn)
             ts = [timed(fn, 100) for _ in range(3)]
             t = min(ts)
-            out.append({"network": name, "batch": N, "ms": round(t * 1e3, 4), "images_per_s": round(N / t, 1),
-                        "tflops": round(2.0 * net.macs_per_image() * N / t / 1e12, 3), "launches": len(net.layers)})
+            row = {"network": name, "batch": N, "ms": round(t * 1e3, 4), "images_per_s": round(N / t, 1),
+                   "tflops": round(2.0 * net.macs_per_image() * N / t / 1e12, 3), "layers": len(net.layers),
+                   "launches": len(S.small_network_launches(pn.table))}
+            if N == 1:      # the same run replayed from a HIP graph: no per-launch host cost
+                graph = pn.capture(xb, o, N)
+                gfn = lambda r: graph.replay()
+                spin(gfn)
+                tg = min(timed(gfn, 100) for _ in range(3))
+                row.update({"graph_ms": round(tg * 1e3, 4), "graph_images_per_s": round(N / tg, 1)})
+            out.append(row)
     return out
 
 

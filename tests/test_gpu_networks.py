@@ -89,6 +89,28 @@ def test_intermediate_layers_of_residual_cnn():
         assert_close(got, trace[upto - 1], max(K, 1), f"residual_cnn after layer {upto} ({last.op})")
 
 
+@pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 1), ("dsep_cnn", 3, 2), ("audio_cnn", 4, 5)])
+def test_graph_replay_matches_eager(name, idx, N):
+    """A captured run replayed several times, with new inputs and eager work between the replays, gives the
+    eager results bit for bit."""
+    net = getattr(WL, name)()
+    pn = S.PackedNetwork(net, WL.network_tensors(net, N, WL.BASE_SEED + idx)[1], DEV)
+    xb = torch.empty(N * net.C0 * net.H0 * net.W0, dtype=torch.float32, device=DEV)
+    out_g = torch.empty(pn.out_elems(N), dtype=torch.float32, device=DEV)
+    out_e = torch.empty_like(out_g)
+    graph = pn.capture(xb, out_g, N)
+    for rep in range(4):
+        x = WL.network_tensors(net, N, 900 + rep)[0]
+        xb.copy_(pn.pack_input(dev(x)))
+        out_g.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        pn.run(xb, out_e, N)
+        torch.cuda.synchronize()
+        assert_bits(out_g.cpu().numpy(), out_e.cpu().numpy(), f"{name} replay {rep}")
+        assert np.isfinite(out_e.cpu().numpy()).all()
+
+
 # ------------------------------------------------------------------ depthwise + pointwise in one kernel
 
 def _block_net(C, Co, H, W, stride, relu_mid, relu_out, dw_dst=1, pw_dst=0, tail=None):
