@@ -437,7 +437,13 @@ const char *conv_kernel_name(const LayerGeom &g)
 {
     static thread_local char name[64];
     if (g.Cib != 16 || g.Cob != 16)
-        return use_small(g) ? "conv_small" : is_dense(g) ? "dense_rows" : "conv_direct";
+    {
+        if (!use_small(g)) return is_dense(g) ? "dense_rows" : "conv_direct";
+        if (g.Cib == 3 && g.kh == 3 && g.kw == 3) return "conv_small<3,3,3>";
+        if (g.Cib == 1 && g.kh == 10 && g.kw == 4) return "conv_small<1,10,4>";
+        if (g.Cib == 8 && g.kh == 1 && g.kw == 1) return "conv_small<8,1,1>";
+        return "conv_small<0,0,0>";
+    }
     const int tile = pick_tile(g);
     if (conv_same_eligible(g))
         snprintf(name, sizeof(name), "%s<%s,%d,%d,%d>", conv_same_images_per_workgroup(g, tile) ? "conv16_img" : "conv16_same",
