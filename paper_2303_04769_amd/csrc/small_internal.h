@@ -83,6 +83,9 @@ hipError_t launch_pack_filter(const float *oihw, float *blk, int Co, int Ci, int
 
 hipError_t launch_dwconv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue, hipStream_t s);
 hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode, hipStream_t s);
+// depthwise 3x3, 16-channel blocks, input rows staged by the load unit (window_rows.hip); pointers 16-byte aligned
+bool dw_rows_eligible(const LayerGeom &g);
+hipError_t launch_dw_rows(const float *in, const float *filt, float *out, const LayerGeom &g, int relu, hipStream_t s);
 
 // res: tensor added to the result when epilogue has EPI_ADD (may be `out` itself: each lane reads the
 // elements it is about to write), else ignored.

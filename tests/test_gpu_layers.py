@@ -199,6 +199,29 @@ def test_dwconv2d(case):
     assert_close(O.unpack(g.check(), ref.shape, Cb), ref, k * k, f"dw {case}")
 
 
+DW_LARGE_CASES = [  # N, C, H, W, stride, pad: at least 40 MB of traffic, where the row-staged kernel takes over
+    (8, 64, 161, 97, 1, (1, 1, 1, 1)),         # odd image: ragged row tiles, two row tiles of different height
+    (6, 128, 120, 120, 2, (0, 1, 0, 1)),       # stride 2
+    (700, 64, 25, 5, 1, (1, 1, 1, 1)),         # two whole small images per tile, last group shifted back (N odd / 2)
+    (3501, 32, 7, 7, 1, (1, 1, 1, 1)),         # five images per tile, batch not a multiple of five
+    (9, 16, 300, 140, 1, (0, 0, 0, 0)),        # rows wider than half a tile: one row per tile; no padding
+    (8, 16, 150, 300, 1, (1, 1, 1, 1)),        # rows wider than a tile: too much to stage, the LDS-tiled kernel runs
+]
+
+
+@pytest.mark.parametrize("case", DW_LARGE_CASES)
+def test_dwconv2d_large(case):
+    N, C, H, W, s, pad = case
+    rng = np.random.default_rng(abs(hash(case)) % 2**31)
+    x = (rng.random((N, C, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    w = (rng.random((C, 1, 3, 3), dtype=np.float32) * 2 - 1).astype(np.float32)
+    ref = O.dwconv2d(x, w, s, pad)
+    assert (x.size + ref.size) * 4 >= 40 << 20
+    g = Guarded(ref.size)
+    S.small_dwconv2d(dev(O.pack(x, 16)), dev(O.pack_dw_filter(w, 16)), g.t, N, C, H, W, 3, 3, s, pad, 16)
+    assert_close(O.unpack(g.check(), ref.shape, 16), ref, 9, f"dw large {case}")
+
+
 POOL_CASES = [  # N, C, H, W, kh, kw, stride, pad
     (2, 32, 13, 11, 3, 3, 2, (0, 0, 0, 0)),
     (1, 16, 56, 56, 3, 3, 2, (0, 0, 0, 0)),
