@@ -252,6 +252,37 @@ def test_pool2d(case, mode):
         assert_close(got, ref, kh * kw, f"avgpool {case}")
 
 
+POOL_LARGE_CASES = [  # N, C, H, W, stride, pad: tens of MB, many workgroups per plane
+    (16, 64, 112, 112, 2, (0, 0, 0, 0)),       # the sweep's pooling geometry, smaller batch
+    (8, 64, 161, 97, 1, (1, 1, 1, 1)),         # padded: taps outside the image
+    (4201, 32, 8, 8, 2, (0, 1, 0, 1)),         # many tiny images
+]
+
+
+@pytest.mark.parametrize("case", POOL_LARGE_CASES)
+@pytest.mark.parametrize("mode", ["max", "avg"])
+def test_pool2d_large(case, mode):
+    N, C, H, W, s, pad = case
+    rng = np.random.default_rng(abs(hash(case)) % 2**31)
+    x = (rng.random((N, C, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    if mode == "max":      # ties between +0 and -0, NaNs, whole windows of NaN
+        flat = x.reshape(-1)
+        idx = rng.integers(0, flat.size, flat.size // 7)
+        flat[idx[0::3]] = 0.0
+        flat[idx[1::3]] = -0.0
+        flat[idx[2::3]] = np.nan
+        x[0, :, :6, :6] = np.nan
+        x[-1, :, -5:, :] = -0.0
+    ref = O.pool2d(x, (3, 3), s, pad, mode)
+    g = Guarded(ref.size)
+    S.small_pool2d(dev(O.pack(x, 16)), g.t, N, C, H, W, 3, 3, s, pad, 16, S.POOL_MAX if mode == "max" else S.POOL_AVG)
+    got = O.unpack(g.check(), ref.shape, 16)
+    if mode == "max":
+        assert_bits(got, ref, f"maxpool large {case}")
+    else:
+        assert_close(got, ref, 9, f"avgpool large {case}")
+
+
 def test_maxpool_ties_and_nan_bit_exact():
     x = np.zeros((1, 16, 4, 4), np.float32)
     x[0, :, 0, 0], x[0, :, 0, 1] = -0.0, 0.0          # first seen is -0
