@@ -98,6 +98,39 @@ def add(a, b):
     return y
 
 
+def batchnorm(x, scale, shift):
+    """y = x * scale[c] + shift[c] on [N, C, H, W]."""
+    x, scale, shift = _f32(x), _f32(scale), _f32(shift)
+    N, Cc, H, W = x.shape
+    assert scale.shape == (Cc,) and shift.shape == (Cc,)
+    y = np.empty_like(x)
+    lib().so_batchnorm(_p(x), _p(scale), _p(shift), _p(y), N, Cc, H, W)
+    return y
+
+
+def upsample(x, fh, fw):
+    """Nearest-neighbour upsampling by integer factors."""
+    x = _f32(x)
+    N, Cc, H, W = x.shape
+    y = np.empty((N, Cc, H * fh, W * fw), np.float32)
+    lib().so_upsample(_p(x), _p(y), N, Cc, H, W, fh, fw)
+    return y
+
+
+def group_conv2d(x, w, F_C, S_C, K, stride=1, pad=(0, 0, 0, 0)):
+    """x [N, Ci, H, W], w [G * K, F_C, kh, kw] with G = (Ci - F_C) / S_C + 1 -> [N, G * K, Ho, Wo]."""
+    x, w = _f32(x), _f32(w)
+    N, Ci, H, W = x.shape
+    assert (Ci - F_C) % S_C == 0
+    G = (Ci - F_C) // S_C + 1
+    assert w.shape[0] == G * K and w.shape[1] == F_C
+    kh, kw = w.shape[2:]
+    t, b, l, r = pad
+    y = np.empty((N, G * K, out_dim(H, kh, stride, t, b), out_dim(W, kw, stride, l, r)), np.float32)
+    lib().so_group_conv2d(_p(x), _p(w), _p(y), N, Ci, F_C, S_C, K, H, W, kh, kw, stride, t, b, l, r)
+    return y
+
+
 def dense(x, w):
     """x [N, Ci, H, W], w [Co, Ci, H, W] -> [N, Co, 1, 1]."""
     x, w = _f32(x), _f32(w)

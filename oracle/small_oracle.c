@@ -28,7 +28,9 @@
  * Parity pins (tests/test_oracle_*.py): hand-worked examples under tests/golden/,
  * delta / all-ones closed forms, 1x1 conv == GEMM, depthwise == block-diagonal
  * conv, dense == full-window conv, O2 == O1, pack/unpack offsets from the layout
- * statement. No function in this file is unpinned.
+ * statement; group convolution == per-group full convolutions == a library grouped
+ * convolution == O2; batch normalization == a library's inference batch-norm with the
+ * statistics folded; upsampling == element repetition. No function in this file is unpinned.
  */
 #include <math.h>
 #include <stddef.h>
@@ -140,6 +142,59 @@ void so_relu(const float *x, float *y, size_t n)
 void so_add(const float *a, const float *b, float *y, size_t n)
 {
     for (size_t i = 0; i < n; ++i) y[i] = (float)((double)a[i] + (double)b[i]);
+}
+
+/* Batch normalization as the single-element FMA of Table 2: y = x * scale[c] + shift[c] (the layer's
+ * statistics folded into one scale and one shift per channel), one rounding per output. */
+void so_batchnorm(const float *x, const float *scale, const float *shift, float *y, int N, int C, int H, int W)
+{
+    const size_t HW = (size_t)H * W;
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (size_t i = 0; i < HW; ++i) {
+                const size_t o = ((size_t)n * C + c) * HW + i;
+                y[o] = (float)((double)x[o] * (double)scale[c] + (double)shift[c]);
+            }
+}
+
+/* Nearest-neighbour upsampling by integer factors (Table 2): output pixel (oh, ow) copies input pixel
+ * (oh / fh, ow / fw). */
+void so_upsample(const float *x, float *y, int N, int C, int H, int W, int fh, int fw)
+{
+    const int Ho = H * fh, Wo = W * fw;
+    for (int n = 0; n < N; ++n)
+        for (int c = 0; c < C; ++c)
+            for (int oh = 0; oh < Ho; ++oh)
+                for (int ow = 0; ow < Wo; ++ow)
+                    y[(((size_t)n * C + c) * Ho + oh) * Wo + ow] = x[(((size_t)n * C + c) * H + oh / fh) * W + ow / fw];
+}
+
+/* Partial-channel reduction (Table 1 row 3, group convolution): G = (Ci - F_C) / S_C + 1 groups; group g reduces
+ * input channels g * S_C .. g * S_C + F_C - 1 with K filters; output channel = g * K + k (Section 3.1.2).
+ * w is [G * K][F_C][kh][kw]. */
+void so_group_conv2d(const float *x, const float *w, float *y, int N, int Ci, int F_C, int S_C, int K, int H, int W,
+                     int kh, int kw, int s, int pt, int pb, int pl, int pr)
+{
+    const int G = (Ci - F_C) / S_C + 1, Co = G * K;
+    const int Ho = so_out_dim(H, kh, s, pt, pb), Wo = so_out_dim(W, kw, s, pl, pr);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int co = 0; co < Co; ++co) {
+            const int g = co / K;
+            for (int oh = 0; oh < Ho; ++oh)
+                for (int ow = 0; ow < Wo; ++ow) {
+                    double acc = 0.0;
+                    for (int fc = 0; fc < F_C; ++fc)
+                        for (int ky = 0; ky < kh; ++ky)
+                            for (int kx = 0; kx < kw; ++kx) {
+                                const int ih = oh * s + ky - pt, iw = ow * s + kx - pl;
+                                if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+                                acc += (double)x[(((size_t)n * Ci + g * S_C + fc) * H + ih) * W + iw] *
+                                       (double)w[(((size_t)co * F_C + fc) * kh + ky) * kw + kx];
+                            }
+                    y[(((size_t)n * Co + co) * Ho + oh) * Wo + ow] = (float)acc;
+                }
+        }
 }
 
 /* Full reduction (Table 1 row 5): x is [N][Ci][H][W], w is [Co][Ci][H][W], y is [N][Co]. */
