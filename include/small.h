@@ -18,8 +18,8 @@
  *     work has finished; the library allocates nothing, frees nothing and never
  *     synchronises. Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream);
- *   - `in` and `out` must not overlap, except small_relu and small_add where out may
- *     equal an input exactly (in place);
+ *   - `in` and `out` must not overlap, except small_relu, small_add and small_batchnorm where out
+ *     may equal an input exactly (in place);
  *   - padding is explicit zero padding, 4-sided; output size per side is
  *     floor((in + lo + hi - k) / stride) + 1 (the paper's output-size equation of
  *     Section 3.1.2 extended with padding and floor);
@@ -108,6 +108,25 @@ int small_add(const float *a, const float *b, float *out, size_t n_elems, void *
  * A dense layer over an H x W image is small_conv2d with kh = H, kw = W and no padding. */
 int small_dense(const float *in, const float *filt, float *out, int N, int Ci, int Co, int Cib, int Cob,
                 void *stream);
+
+/* ---- the remaining layers of Table 2. They are not part of small_network_run's layer table.
+ * small_batchnorm: batch normalization as the single-element FMA of Table 2, statistics folded by the
+ *   caller: out[n,c,h,w] = in[n,c,h,w] * scale[c] + shift[c] (one fused multiply-add). scale, shift: C floats
+ *   in plain channel order. out may equal in exactly (in place).
+ * small_upsample: nearest-neighbour interpolation (Table 2 "Upsample") by integer factors:
+ *   out[n,c,oh,ow] = in[n,c,oh / fh,ow / fw]; out is [N][C/Cb][H*fh][W*fw][Cb]. Bit-exact copy.
+ * small_group_conv2d: partial-channel reduction (Section 3.2 item 3, Table 2 "Group Convolutions").
+ *   G = (Ci - F_C) / S_C + 1 groups (the division must be exact); group g reduces input channels
+ *   g * S_C .. g * S_C + F_C - 1 with K filters; output channel g * K + k (Section 3.1.2: O_C = K * G).
+ *   S_C = F_C gives the usual disjoint groups; S_C < F_C overlapping ones.
+ *   in: [N][Ci/Cib][H][W][Cib]; out: [N][Co/Cob][Ho][Wo][Cob] with Co = G * K;
+ *   filt: the plain tensor [Co][F_C][kh][kw] in the general filter layout [Co/Cob][F_C/F_Cb][kh][kw][F_Cb][Cob]
+ *   (small_pack_filter with Ci = F_C, Cib = F_Cb). */
+int small_batchnorm(const float *in, const float *scale, const float *shift, float *out, int N, int C, int H, int W, int Cb,
+                    void *stream);
+int small_upsample(const float *in, float *out, int N, int C, int H, int W, int fh, int fw, int Cb, void *stream);
+int small_group_conv2d(const float *in, const float *filt, float *out, int N, int Ci, int F_C, int S_C, int K, int H, int W,
+                       int kh, int kw, int stride, small_pad pad, int Cib, int F_Cb, int Cob, void *stream);
 
 /* ---- a whole network: a table of layers over shared buffers (Section "Memory Usage
  * Comparison": buffers are shared across layers; nothing is reformatted between layers).

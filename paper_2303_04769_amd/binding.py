@@ -21,7 +21,7 @@ _OPS = {"conv": OP_CONV, "dw": OP_DWCONV, "maxpool": OP_MAXPOOL, "avgpool": OP_A
 
 EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "small_pack_filter",
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
-           "small_dense", "small_network_workspace", "small_network_run", "small_network_launches",
+           "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_network_workspace", "small_network_run", "small_network_launches",
            "small_network_run_range"]
 
 
@@ -68,6 +68,9 @@ def load():
         "small_relu": (i, [p, p, sz, p]),
         "small_add": (i, [p, p, p, sz, p]),
         "small_dense": (i, [p, p, p, i, i, i, i, i, p]),
+        "small_batchnorm": (i, [p, p, p, p, i, i, i, i, i, p]),
+        "small_upsample": (i, [p, p, i, i, i, i, i, i, i, p]),
+        "small_group_conv2d": (i, [p, p, p, i, i, i, i, i, i, i, i, i, i, small_pad, i, i, i, p]),
         "small_network_workspace": (i, [C.POINTER(small_layer), i, i, i, i, i, C.POINTER(sz)]),
         "small_network_run": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
         "small_network_launches": (i, [C.POINTER(small_layer), i, C.POINTER(i), C.POINTER(i)]),
@@ -159,6 +162,20 @@ def small_add(a, b, out, n_elems, stream=None):
 
 def small_dense(inp, filt, out, N, Ci, Co, Cib, Cob, stream=None):
     _check(load().small_dense(_ptr(inp), _ptr(filt), _ptr(out), N, Ci, Co, Cib, Cob, _stream(stream)), "small_dense")
+
+
+def small_batchnorm(inp, scale, shift, out, N, Cc, H, W, Cb, stream=None):
+    _check(load().small_batchnorm(_ptr(inp), _ptr(scale), _ptr(shift), _ptr(out), N, Cc, H, W, Cb, _stream(stream)),
+           "small_batchnorm")
+
+
+def small_upsample(inp, out, N, Cc, H, W, fh, fw, Cb, stream=None):
+    _check(load().small_upsample(_ptr(inp), _ptr(out), N, Cc, H, W, fh, fw, Cb, _stream(stream)), "small_upsample")
+
+
+def small_group_conv2d(inp, filt, out, N, Ci, F_C, S_C, K, H, W, kh, kw, stride, pad, Cib, F_Cb, Cob, stream=None):
+    _check(load().small_group_conv2d(_ptr(inp), _ptr(filt), _ptr(out), N, Ci, F_C, S_C, K, H, W, kh, kw, stride, _pad(pad),
+                                     Cib, F_Cb, Cob, _stream(stream)), "small_group_conv2d")
 
 
 def make_layer_table(layers, filters):

@@ -218,6 +218,47 @@ int small_dense(const float *in, const float *filt, float *out, int N, int Ci, i
     return run_conv(in, filt, out, nullptr, p, EPI_NONE, as_stream(stream));
 }
 
+int small_batchnorm(const float *in, const float *scale, const float *shift, float *out, int N, int C, int H, int W, int Cb,
+                    void *stream)
+{
+    if (!in || !scale || !shift || !out) return SMALL_ERR_NULL;
+    if (int rc = check_block(C, Cb)) return rc;
+    const size_t n = elems(N, C, H, W);
+    if (!n || (size_t)H * W * Cb > kMaxElems) return SMALL_ERR_SHAPE;
+    if (in != out && overlap(in, n, out, n)) return SMALL_ERR_ALIAS;
+    if (overlap(scale, (size_t)C, out, n) || overlap(shift, (size_t)C, out, n)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_batchnorm(in, scale, shift, out, N, C, H, W, Cb, as_stream(stream)));
+}
+
+int small_upsample(const float *in, float *out, int N, int C, int H, int W, int fh, int fw, int Cb, void *stream)
+{
+    if (!in || !out) return SMALL_ERR_NULL;
+    if (int rc = check_block(C, Cb)) return rc;
+    if (fh <= 0 || fw <= 0 || H <= 0 || W <= 0 || (size_t)H * fh > kMaxElems || (size_t)W * fw > kMaxElems) return SMALL_ERR_SHAPE;
+    const size_t ni = elems(N, C, H, W), no = elems(N, C, H * fh, W * fw);
+    if (!ni || !no) return SMALL_ERR_SHAPE;
+    if (overlap(in, ni, out, no)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_upsample(in, out, N, C, H, W, fh, fw, Cb, as_stream(stream)));
+}
+
+int small_group_conv2d(const float *in, const float *filt, float *out, int N, int Ci, int F_C, int S_C, int K, int H, int W,
+                       int kh, int kw, int stride, small_pad pad, int Cib, int F_Cb, int Cob, void *stream)
+{
+    if (F_C <= 0 || S_C <= 0 || K <= 0 || F_C > Ci || (Ci - F_C) % S_C) return SMALL_ERR_SHAPE;
+    const long groups = (Ci - F_C) / S_C + 1;
+    if (groups * K > INT_MAX) return SMALL_ERR_SHAPE;
+    const int Co = (int)(groups * K);
+    if (int rc = check_block(F_C, F_Cb)) return rc;
+    LayerGeom g;
+    size_t ni, no;
+    if (int rc = window_geom(g, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob, &ni, &no)) return rc;
+    const size_t nf = elems(Co, F_C, kh, kw);
+    if (!nf) return SMALL_ERR_SHAPE;
+    if (!in || !filt || !out) return SMALL_ERR_NULL;
+    if (overlap(in, ni, out, no) || overlap(filt, nf, out, no)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_group_conv(in, filt, out, g, F_C, S_C, K, F_Cb, as_stream(stream)));
+}
+
 }  // extern "C"
 
 // ------------------------------------------------------------------------------------------------

@@ -112,4 +112,12 @@ bool dwpw_geom_ok(const LayerGeom &dw_geom, int Co);
 hipError_t launch_dwpw(const float *in, const float *dw_filt, const float *pw_filt, float *out, const LayerGeom &dw_geom,
                        int Co, int relu_mid, int relu_out, hipStream_t s);
 
+// Remaining Table 2 layers (table2.hip): y = x * scale[c] + shift[c]; nearest-neighbour upsampling by integer
+// factors; group convolution (geometry in g with g.Ci = all input channels, g.Co = G * K, g.Cib the activation block).
+hipError_t launch_batchnorm(const float *in, const float *scale, const float *shift, float *out, int N, int C, int H, int W,
+                            int Cb, hipStream_t s);
+hipError_t launch_upsample(const float *in, float *out, int N, int C, int H, int W, int fh, int fw, int Cb, hipStream_t s);
+hipError_t launch_group_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int F_C, int S_C, int K,
+                             int F_Cb, hipStream_t s);
+
 }  // namespace small

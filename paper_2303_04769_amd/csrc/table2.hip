@@ -1,0 +1,148 @@
+// The remaining layers of the paper's Table 2 on the shared blocked layout (gfx950): batch normalization
+// (single-element reduction, FMA), nearest-neighbour upsampling (single element, strided mapping) and group
+// convolution (partial-channel reduction, Table 1 row 3). None of them is on the networks' hot path: plain
+// one-lane-per-output kernels, memory-bound, coalesced along the channel block.
+#include "small_internal.h"
+
+namespace small {
+
+namespace {
+
+constexpr int kBlock = 256;
+
+// y = x * scale[c] + shift[c]; element e of [N][C/Cb][HW][Cb] belongs to channel ((e / (HW * Cb)) % nCb) * Cb + e % Cb.
+// VEC = 4: Cb % 4 == 0 and 16-byte aligned tensors, the four lanes' channels are consecutive.
+template <int VEC>
+__global__ void __launch_bounds__(kBlock) batchnorm_kernel(const float *__restrict__ in, const float *__restrict__ scale,
+                                                           const float *__restrict__ shift, float *__restrict__ out,
+                                                           size_t n_vec, int Cb, int nCb, FastDiv dPlane)
+{
+    const size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= n_vec) return;
+    const size_t e = v * VEC;
+    // plane index and position inside the plane; planes hold HW * Cb elements (< 2^31, checked by the caller)
+    const size_t plane_elems = dPlane.d;
+    const size_t plane = e / plane_elems;
+    const int within = (int)(e - plane * plane_elems);
+    const int c = (int)(plane % (size_t)nCb) * Cb + within % Cb;
+    if (VEC == 4) {
+        const floatx4 x = *reinterpret_cast<const floatx4 *>(in + e);
+        floatx4 y;
+        y.x = fmaf(x.x, scale[c + 0], shift[c + 0]); y.y = fmaf(x.y, scale[c + 1], shift[c + 1]);
+        y.z = fmaf(x.z, scale[c + 2], shift[c + 2]); y.w = fmaf(x.w, scale[c + 3], shift[c + 3]);
+        *reinterpret_cast<floatx4 *>(out + e) = y;
+    } else {
+        out[e] = fmaf(in[e], scale[c], shift[c]);
+    }
+}
+
+// out[n][cb][oh][ow][:] = in[n][cb][oh / fh][ow / fw][:]; one lane per VEC output floats.
+template <int VEC>
+__global__ void __launch_bounds__(kBlock) upsample_kernel(const float *__restrict__ in, float *__restrict__ out, size_t n_vec,
+                                                          int H, int W, int fh, int fw, int Cb)
+{
+    const size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= n_vec) return;
+    const int Ho = H * fh, Wo = W * fw, per_px = Cb / VEC;
+    size_t t = v;
+    const int q = (int)(t % per_px); t /= per_px;
+    const int ow = (int)(t % Wo); t /= Wo;
+    const int oh = (int)(t % Ho);
+    const size_t plane = t / Ho;                     // n * nCb + cb
+    const size_t src = ((plane * H + oh / fh) * W + ow / fw) * Cb + (size_t)q * VEC;
+    if (VEC == 4) *reinterpret_cast<floatx4 *>(out + v * 4) = *reinterpret_cast<const floatx4 *>(in + src);
+    else out[v] = in[src];
+}
+
+struct GroupArgs {
+    const float *in;
+    const float *filt;
+    float *out;
+    int N, H, W, Ho, Wo;
+    int Ci, F_C, S_C, K, Co;
+    int Cib, F_Cb, Cob;
+    int kh, kw, stride, pt, pl;
+};
+
+// One lane per output element, output channel fastest inside a block (filter reads coalesced, input reads
+// broadcast within a group). Output channel oc = g * K + k reduces input channels g * S_C .. g * S_C + F_C - 1.
+__global__ void __launch_bounds__(kBlock) group_conv_direct(GroupArgs a, size_t total)
+{
+    size_t e = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    if (e >= total) return;
+    const size_t dst = e;
+    const int co_in = (int)(e % a.Cob); e /= a.Cob;
+    const int ow = (int)(e % a.Wo); e /= a.Wo;
+    const int oh = (int)(e % a.Ho); e /= a.Ho;
+    const int nCob = a.Co / a.Cob, nCib = a.Ci / a.Cib, nFb = a.F_C / a.F_Cb;
+    const int cob = (int)(e % nCob);
+    const int n = (int)(e / nCob);
+    const int oc = cob * a.Cob + co_in;
+    const int c0 = (oc / a.K) * a.S_C;               // first input channel of the group
+    float acc = 0.f;
+    for (int fc = 0; fc < a.F_C; ++fc) {
+        const int ic = c0 + fc;
+        const float *plane = a.in + (size_t)(n * nCib + ic / a.Cib) * a.H * a.W * a.Cib + ic % a.Cib;
+        const float *wp = a.filt + ((size_t)(cob * nFb + fc / a.F_Cb) * a.kh * a.kw * a.F_Cb + fc % a.F_Cb) * a.Cob + co_in;
+        for (int y = 0; y < a.kh; ++y) {
+            const int ih = oh * a.stride - a.pt + y;
+            if (ih < 0 || ih >= a.H) continue;
+            for (int x = 0; x < a.kw; ++x) {
+                const int iw = ow * a.stride - a.pl + x;
+                if (iw < 0 || iw >= a.W) continue;
+                acc = fmaf(plane[(size_t)(ih * a.W + iw) * a.Cib], wp[(size_t)(y * a.kw + x) * a.F_Cb * a.Cob], acc);
+            }
+        }
+    }
+    a.out[dst] = acc;
+}
+
+}  // namespace
+
+hipError_t launch_batchnorm(const float *in, const float *scale, const float *shift, float *out, int N, int C, int H, int W,
+                            int Cb, hipStream_t s)
+{
+    const size_t total = (size_t)N * C * H * W;
+    const FastDiv plane = make_fastdiv(H * W * Cb);
+    const bool vec = Cb % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out) & 15u) == 0);
+    if (vec) {
+        const size_t n_vec = total / 4;
+        hipLaunchKernelGGL((batchnorm_kernel<4>), dim3((unsigned)((n_vec + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, scale,
+                           shift, out, n_vec, Cb, C / Cb, plane);
+    } else {
+        hipLaunchKernelGGL((batchnorm_kernel<1>), dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, scale,
+                           shift, out, total, Cb, C / Cb, plane);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_upsample(const float *in, float *out, int N, int C, int H, int W, int fh, int fw, int Cb, hipStream_t s)
+{
+    const size_t total = (size_t)N * C * H * fh * W * fw;
+    const bool vec = Cb % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out) & 15u) == 0);
+    if (vec) {
+        const size_t n_vec = total / 4;
+        hipLaunchKernelGGL((upsample_kernel<4>), dim3((unsigned)((n_vec + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, out, n_vec,
+                           H, W, fh, fw, Cb);
+    } else {
+        hipLaunchKernelGGL((upsample_kernel<1>), dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, out, total,
+                           H, W, fh, fw, Cb);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_group_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int F_C, int S_C, int K,
+                             int F_Cb, hipStream_t s)
+{
+    GroupArgs a;
+    a.in = in; a.filt = filt; a.out = out;
+    a.N = g.N; a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo;
+    a.Ci = g.Ci; a.F_C = F_C; a.S_C = S_C; a.K = K; a.Co = g.Co;
+    a.Cib = g.Cib; a.F_Cb = F_Cb; a.Cob = g.Cob;
+    a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pt = g.pt; a.pl = g.pl;
+    const size_t total = (size_t)g.N * g.Co * g.Ho * g.Wo;
+    hipLaunchKernelGGL(group_conv_direct, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, a, total);
+    return hipGetLastError();
+}
+
+}  // namespace small
