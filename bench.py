@@ -320,9 +320,10 @@ def sweep(S, WL, torch, np, dev, timed, only=None):
 
 def networks(S, WL, torch, dev, timed):
     out = []
-    for name, idx, big in (("residual_cnn", 2, 256), ("dsep_cnn", 3, 256), ("audio_cnn", 4, 1024)):
+    for name, idx, batches in (("residual_cnn", 2, (1, 256)), ("dsep_cnn", 3, (1, 256)), ("audio_cnn", 4, (1, 1024)),
+                               ("dense_autoencoder", 5, (1, 256, 262144))):
         net = getattr(WL, name)()
-        for N in (1, big):
+        for N in batches:
             x, ws = WL.network_tensors(net, N, WL.BASE_SEED + idx)
             pn = S.PackedNetwork(net, ws, dev)
             xb = pn.pack_input(torch.from_numpy(x).to(dev))

@@ -287,7 +287,64 @@ inline bool reads(const small_layer &l, int id) { return l.src == id || (l.op ==
 // rename: the convolution's destination is the depthwise layer's source (two buffers used in turn); one kernel
 // cannot overwrite the tensor its other workgroups still read, so it writes into the (dead) depthwise buffer
 // instead and the runner swaps the memory behind the two logical buffers from then on.
-struct Fusion { int epilogue; int out_id; int res_id; int skip; int pw; int pw_relu; int rename; };
+// chain >= 2: layer i starts a run of `chain` pointwise layers (dense on 1x1 images, 1x1 stride-1 unpadded
+// convolution), each consumed only by the next, that one kernel takes from the first layer's source to the last
+// layer's destination; chain_idx / chain_relu: their table indices and whether an in-place ReLU follows each.
+// The tensors between them are never written.
+struct Fusion {
+    int epilogue; int out_id; int res_id; int skip; int pw; int pw_relu; int rename;
+    int chain; int chain_idx[kChainMaxLayers]; int chain_relu[kChainMaxLayers];
+};
+
+bool pointwise(const small_layer &l)
+{
+    if (l.op == SMALL_OP_CONV) {
+        if (l.stride != 1 || l.pad.t || l.pad.b || l.pad.l || l.pad.r) return false;
+    } else if (l.op != SMALL_OP_DENSE) {
+        return false;
+    }
+    return l.kh == 1 && l.kw == 1 && l.dst != l.src && l.dst != SMALL_BUF_IN && chain_layer_eligible(l.Ci, l.Co, l.Cib, l.Cob);
+}
+
+// True when nothing from layer `from` on needs the tensor that buffer D holds at that point.
+bool dead_from(const small_layer *L, int nL, int from, int D)
+{
+    for (int k = from; k < nL; ++k) {
+        if (reads(L[k], D)) return false;
+        if (L[k].dst == D) return true;
+    }
+    return D != SMALL_BUF_OUT;
+}
+
+// Fills f.chain* for the longest run of pointwise layers that starts at layer i; f.skip covers the run.
+void plan_chain(const small_layer *L, int nL, int i, Fusion &f)
+{
+    int n = 0, end[kChainMaxLayers];
+    int k = i;
+    while (k < nL && n < kChainMaxLayers && pointwise(L[k])) {
+        if (n > 0) {
+            const small_layer &prev = L[f.chain_idx[n - 1]];
+            // the previous result is this layer's input, and nothing else ever looks at it
+            if (L[k].src != prev.dst || L[k].Ci != prev.Co || L[k].Cib != prev.Cob || !dead_from(L, nL, k + 1, prev.dst)) break;
+        }
+        f.chain_idx[n] = k;
+        f.chain_relu[n] = 0;
+        int next = k + 1;
+        if (next < nL && L[next].op == SMALL_OP_RELU && L[next].src == L[k].dst && L[next].dst == L[k].dst) {
+            f.chain_relu[n] = 1;
+            ++next;
+        }
+        end[n++] = next;
+        k = next;
+    }
+    if (n && L[i].Cib != 16) n = 0;
+    // the run's output is a 16-blocked tensor in a buffer other than the run's input
+    while (n && (L[f.chain_idx[n - 1]].Cob != 16 || L[f.chain_idx[n - 1]].dst == L[i].src)) --n;
+    if (n < 2) return;
+    f.chain = n;
+    f.skip = end[n - 1] - i - 1;
+    f.out_id = f.res_id = L[f.chain_idx[n - 1]].dst;
+}
 
 // What plan_fusion yields when the depthwise + pointwise kernel cannot take the layer (image geometry, alignment).
 Fusion without_pointwise(Fusion f)
@@ -301,12 +358,16 @@ Fusion without_pointwise(Fusion f)
     return f;
 }
 
-Fusion plan_fusion(const small_layer *L, int nL, int i)
+Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
 {
     const small_layer &c = L[i];
     Fusion f = {EPI_NONE, c.dst, c.dst, 0, 0, 0, 0};
     const bool conv = c.op == SMALL_OP_CONV || c.op == SMALL_OP_DENSE;
     if (!conv && c.op != SMALL_OP_DWCONV) return f;
+    if (conv && allow_chain) {
+        plan_chain(L, nL, i, f);
+        if (f.chain) return f;
+    }
     int j = i + 1;
     const int D = c.dst;
     if (conv && j < nL && L[j].op == SMALL_OP_ADD && L[j].src != L[j].src2 && (L[j].src == D || L[j].src2 == D)) {
@@ -416,7 +477,29 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.dst == l.src) return SMALL_ERR_ALIAS;
                 if (!l.filt) return SMALL_ERR_NULL;
                 o = Shape{l.Co, p.g.Ho, p.g.Wo, l.Cob, true};
-                if (launch) rc = run_conv(ptr(l.src), l.filt, ptr(fu.out_id), ptr(fu.res_id), p, fu.epilogue, s);
+                if (run && head && fu.chain) {
+                    // the one-kernel run of pointwise layers needs aligned pointers and 32-bit input offsets;
+                    // otherwise every layer of the run is planned on its own
+                    uintptr_t bits = (uintptr_t)ptr(l.src) | (uintptr_t)ptr(fu.out_id);
+                    for (int k = 0; k < fu.chain; ++k) bits |= (uintptr_t)L[fu.chain_idx[k]].filt;
+                    const size_t n_out = elems(N, L[fu.chain_idx[fu.chain - 1]].Co, a.H, a.W);
+                    if ((bits & 15u) || in_elems * sizeof(float) >= (1ull << 32) || (size_t)N * a.H * a.W > (size_t)INT_MAX - 64 ||
+                        overlap(ptr(l.src), in_elems, ptr(fu.out_id), n_out)) {
+                        fu = plan_fusion(L, nL, i, false);
+                        fused_away = fu.skip;
+                    }
+                }
+                if (launch && fu.chain) {
+                    ChainLayer cl[kChainMaxLayers];
+                    for (int k = 0; k < fu.chain; ++k) {
+                        const small_layer &t = L[fu.chain_idx[k]];
+                        if (!t.filt) return SMALL_ERR_NULL;
+                        cl[k] = ChainLayer{t.filt, t.Ci, t.Co, fu.chain_relu[k]};
+                    }
+                    rc = from_hip(launch_dense_chain(ptr(l.src), ptr(fu.out_id), cl, fu.chain, (long)N * a.H * a.W, a.H * a.W, s));
+                } else if (launch) {
+                    rc = run_conv(ptr(l.src), l.filt, ptr(fu.out_id), ptr(fu.res_id), p, fu.epilogue, s);
+                }
                 break;
             }
             case SMALL_OP_DWCONV:

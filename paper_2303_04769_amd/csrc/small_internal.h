@@ -112,6 +112,17 @@ bool dwpw_geom_ok(const LayerGeom &dw_geom, int Co);
 hipError_t launch_dwpw(const float *in, const float *dw_filt, const float *pw_filt, float *out, const LayerGeom &dw_geom,
                        int Co, int relu_mid, int relu_out, hipStream_t s);
 
+// A run of pointwise layers (dense on 1x1 images, 1x1 stride-1 unpadded convolution), each with an optional ReLU,
+// in one launch (chain.hip). Tensors of the run have a multiple of 16 channels (at most 16 * kChainMaxBlocks) in
+// 16-channel blocks; tensors inside the run may instead have 8 channels in one 8-channel block. The run's input must
+// be smaller than 4 GiB and may not overlap its output; all pointers 16-byte aligned.
+constexpr int kChainMaxLayers = 16;
+constexpr int kChainMaxBlocks = 8;
+struct ChainLayer { const float *filt; int Ci, Co, relu; };
+bool chain_layer_eligible(int Ci, int Co, int Cib, int Cob);
+hipError_t launch_dense_chain(const float *in, float *out, const ChainLayer *layers, int n_layers, long M, int HW,
+                              hipStream_t s);
+
 // Remaining Table 2 layers (table2.hip): y = x * scale[c] + shift[c]; nearest-neighbour upsampling by integer
 // factors; group convolution (geometry in g with g.Ci = all input channels, g.Co = G * K, g.Cib the activation block).
 hipError_t launch_batchnorm(const float *in, const float *scale, const float *shift, float *out, int N, int C, int H, int W,

@@ -92,6 +92,11 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
     td = B.make_layer_table(d.layers, [None] * len(d.wshapes))
     # the first block has 8-channel blocks (two launches), the other 12 are fused
     assert [d.layers[h].op for h in B.small_network_launches(td)] == ["conv", "dw", "conv"] + ["dw"] * 12 + ["avgpool", "dense"]
+    # the dense-only autoencoder is one run of pointwise layers: a single launch; workspace = two ping-pong rows
+    e = WL.dense_autoencoder()
+    te = B.make_layer_table(e.layers, [None] * len(e.wshapes))
+    assert len(e.layers) == 19 and B.small_network_launches(te) == [0]
+    assert ws(e, 3) == 2 * 3 * 128 * 4
     # malformed tables
     t = B.make_layer_table(a.layers, [None] * len(a.wshapes))
     assert lib.small_network_workspace(t, len(t), 1, a.C0, a.H0, a.W0, C.byref(C.c_size_t())) == 1   # NULL filter

@@ -36,7 +36,7 @@ def test_single_conv_relu_workload():
     assert (got >= 0).all() and (got == 0).sum() > 1000
 
 
-@pytest.mark.parametrize("name,idx", [("residual_cnn", 2), ("dsep_cnn", 3), ("audio_cnn", 4)])
+@pytest.mark.parametrize("name,idx", [("residual_cnn", 2), ("dsep_cnn", 3), ("audio_cnn", 4), ("dense_autoencoder", 5)])
 @pytest.mark.parametrize("N", [1, 3])
 def test_networks_small_batch(name, idx, N):
     net = getattr(WL, name)()
@@ -52,7 +52,8 @@ def test_dsep_variant_block1_stride1():
     assert_close(_run(net, x, ws).reshape(2, -1), O.run_network(net, x, ws), _maxK(net), "dsep b1s1")
 
 
-@pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 256), ("dsep_cnn", 3, 256), ("audio_cnn", 4, 1024)])
+@pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 256), ("dsep_cnn", 3, 256), ("audio_cnn", 4, 1024),
+                                        ("dense_autoencoder", 5, 256), ("dense_autoencoder", 5, 40000)])
 def test_networks_full_batch_sampled(name, idx, N):
     """Full batch on the GPU; the oracle recomputes a sample of images one by one (images are independent)."""
     net = getattr(WL, name)()
@@ -89,7 +90,8 @@ def test_intermediate_layers_of_residual_cnn():
         assert_close(got, trace[upto - 1], max(K, 1), f"residual_cnn after layer {upto} ({last.op})")
 
 
-@pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 1), ("dsep_cnn", 3, 2), ("audio_cnn", 4, 5)])
+@pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 1), ("dsep_cnn", 3, 2), ("audio_cnn", 4, 5),
+                                        ("dense_autoencoder", 5, 70)])
 def test_graph_replay_matches_eager(name, idx, N):
     """A captured run replayed several times, with new inputs and eager work between the replays, gives the
     eager results bit for bit."""
@@ -182,6 +184,101 @@ def test_depthwise_output_read_later_is_not_fused():
     mid = O.relu(O.dwconv2d(O.relu(x), ws[0], 1, pad))
     ref = O.add(O.conv2d(mid, ws[1], 1, (0, 0, 0, 0)), mid)
     assert_close(_run(net, x, ws), ref, 9 * 32, "dw kept, conv + add")
+
+
+# ------------------------------------------------------------------ runs of pointwise layers in one kernel
+
+def _chain_net(widths, H, W, relus, op="dense", src0_relu=False):
+    """IN -> pointwise layers of the given widths through slots 0 / 1 in turn -> OUT. op "dense" needs H = W = 1."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("chain_probe", widths[0], H, W)
+    L, src = [], IN
+    if src0_relu:
+        L.append(Layer("relu", widths[0], widths[0], H, W, src=IN, dst=2))
+        src = 2
+    for i in range(len(widths) - 1):
+        Ci, Co = widths[i], widths[i + 1]
+        last = i == len(widths) - 2
+        dst = OUT if last else i % 2
+        net.wshapes.append(((Co, Ci, 1, 1), Ci))
+        if op == "dense":
+            L.append(Layer("dense", Ci, Co, 1, 1, 1, 1, 1, src=src, dst=dst, w=i, Ho=1, Wo=1))
+        else:
+            L.append(Layer("conv", Ci, Co, H, W, 1, 1, 1, (0, 0, 0, 0), src=src, dst=dst, w=i))
+        if relus[i]:
+            L.append(Layer("relu", Co, Co, H, W, src=dst, dst=dst))
+        src = dst
+    net.layers = L
+    return net
+
+
+def _chain_ref(x, ws, relus):
+    h = x
+    for w, r in zip(ws, relus):
+        h = O.conv2d(h, w, 1, (0, 0, 0, 0))
+        if r:
+            h = O.relu(h)
+    return h
+
+
+CHAIN_CASES = [  # N, widths, (H, W), ReLU after each layer, op
+    (37, [128, 128, 128], (1, 1), [1, 1], "dense"),                    # ragged last tile of 16 pixels
+    (3, [16, 32, 64, 16, 128], (5, 7), [1, 0, 1, 1], "conv"),          # images of 35 pixels: tiles cross images
+    (50, [128, 8, 128], (1, 1), [1, 0], "dense"),                      # 8-channel tensor inside the run
+    (19, [64, 48, 8, 32, 16], (1, 1), [0, 1, 1, 0], "dense"),
+    (2, [32, 8, 16], (9, 4), [1, 1], "conv"),
+    (1, [16, 16, 16], (1, 1), [0, 0], "dense"),                        # one pixel
+    (16500, [32, 16, 32], (1, 2), [1, 1], "conv"),                     # 33000 pixels: 64-pixel tiles, ragged end
+    (20000, [16, 48, 16], (1, 1), [1, 0], "dense"),                    # 32-pixel tiles
+    (5, [32] * 19, (1, 1), [1] * 18, "dense"),                         # longer than one launch takes: 16 + 2 layers
+]
+
+
+@pytest.mark.parametrize("case", CHAIN_CASES)
+def test_pointwise_run(case):
+    N, widths, (H, W), relus, op = case
+    net = _chain_net(widths, H, W, relus, op)
+    table = S.make_layer_table(net.layers, [None] * len(net.wshapes))
+    heads = S.small_network_launches(table)
+    n_pw = len(widths) - 1
+    assert len(heads) == (1 if n_pw <= 16 else 2), heads
+    x, ws = WL.network_tensors(net, N, 777)
+    got = _run(net, x, ws)
+    ref = _chain_ref(x, ws, relus)
+    K = 1
+    for c in widths[:-1]:
+        K *= c
+    # chained reductions amplify each other's rounding error; He-scaled weights keep magnitudes level,
+    # so the error grows like the number of layers, not like the product of the widths
+    assert_close(got, ref, max(widths) * n_pw, f"pointwise run {widths} {H}x{W} N={N}")
+
+
+def test_pointwise_run_keeps_tensors_that_are_read_later():
+    """slot 0 is read again after the second layer consumed it: it must be written, so the run starts after it;
+    and a run never writes into the buffer it reads."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("chain_probe", 32, 1, 1)
+    net.wshapes = [((32, 32, 1, 1), 32)] * 4
+    D = lambda i, s, d: Layer("dense", 32, 32, 1, 1, 1, 1, 1, src=s, dst=d, w=i, Ho=1, Wo=1)
+    net.layers = [D(0, IN, 0), D(1, 0, 1), D(2, 1, 2), Layer("add", 32, 32, 1, 1, src=2, src2=0, dst=2),
+                  D(3, 2, OUT)]
+    table = S.make_layer_table(net.layers, [None] * 4)
+    assert S.small_network_launches(table) == [0, 1, 3, 4]     # layers 1 + 2 are a run; 0 is not part of it
+    x, ws = WL.network_tensors(net, 40, 5)
+    c = lambda h, w: O.conv2d(h, w, 1, (0, 0, 0, 0))
+    t0 = c(x, ws[0])
+    ref = c(O.add(c(c(t0, ws[1]), ws[2]), t0), ws[3])
+    assert_close(_run(net, x, ws), ref, 32 * 4, "run with a tensor kept for a later add")
+    # 0 -> 1 -> 2 -> 0: the third layer would overwrite the run's own input while other workgroups still read
+    # it, so the run ends before it
+    net.layers = [Layer("relu", 32, 32, 1, 1, src=IN, dst=0), D(0, 0, 1), D(1, 1, 2), D(2, 2, 0),
+                  Layer("maxpool", 32, 32, 1, 1, 1, 1, 1, (0, 0, 0, 0), src=0, dst=OUT)]
+    net.wshapes = net.wshapes[:3]
+    table = S.make_layer_table(net.layers, [None] * 3)
+    assert S.small_network_launches(table) == [0, 1, 3, 4]
+    x, ws = WL.network_tensors(net, 33, 6)
+    ref = c(c(c(O.relu(x), ws[0]), ws[1]), ws[2])
+    assert_close(_run(net, x, ws), ref, 32 * 3, "run that may not end in its own input")
 
 
 # ------------------------------------------------------------------ full-size sweep layers (sampled)

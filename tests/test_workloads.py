@@ -12,6 +12,10 @@ def test_weight_and_mac_counts():
     assert d.macs_per_image() == 2_424_128
     assert WL.dsep_cnn(1).macs_per_image() > 7_000_000
     assert WL.single_conv_relu().macs_per_image() * 2 == 4_718_592
+    # Table "tinyml_models": the autoencoder row prints 133120 parameters and a (1, 1, 128) input
+    e = WL.dense_autoencoder()
+    assert e.n_weights == 133120 == e.macs_per_image() and (e.C0, e.H0, e.W0) == (128, 1, 1)
+    assert [L.Co for L in e.layers if L.op == "dense"] == [128] * 4 + [8] + [128] * 5
 
 
 def test_spatial_sequences_and_paddings():
@@ -31,7 +35,7 @@ def test_spatial_sequences_and_paddings():
 
 
 def test_no_reformat_invariant_and_buffer_plan():
-    for net in (WL.residual_cnn(), WL.dsep_cnn(), WL.audio_cnn(), WL.single_conv_relu()):
+    for net in (WL.residual_cnn(), WL.dsep_cnn(), WL.audio_cnn(), WL.dense_autoencoder(), WL.single_conv_relu()):
         block = {WL.nets.IN: WL.block_of(net.C0)}
         live = {}
         for L in net.layers:
@@ -76,3 +80,21 @@ def test_residual_network_matches_torch_composition():
         h = F.relu(b + sc)
     logits = h.mean(dim=(2, 3)) @ t[i].reshape(10, 64).T
     np.testing.assert_allclose(y, logits.float().numpy(), rtol=0, atol=1e-4)
+
+
+def test_autoencoder_matches_matrix_products():
+    """The dense-only network is a chain of matrix products: rebuild it from numpy matmuls in fp64
+    (a fully connected layer on a 1x1 image is y = W x) and compare."""
+    net = WL.dense_autoencoder()
+    x, ws = WL.network_tensors(net, 5, 11)
+    y = O.run_network(net, x, ws)
+    h = x.reshape(5, 128).astype(np.float64)
+    for i, w in enumerate(ws):
+        h = h @ w.reshape(w.shape[0], w.shape[1]).astype(np.float64).T
+        if i + 1 < len(ws):
+            h = np.maximum(h, 0.0)
+    assert y.shape == (5, 128) and np.abs(y).max() > 0.01
+    np.testing.assert_allclose(y, h.astype(np.float32), rtol=0, atol=1e-5)
+    # the 8-wide code in the middle: the tensor after the fifth dense layer (+ ReLU) has 8 channels
+    _, trace = O.run_network(net, x, ws, return_all=True)
+    assert trace[9].shape[1] == 8 and (trace[9] >= 0).all() and trace[9].max() > 0

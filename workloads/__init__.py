@@ -4,6 +4,6 @@ This package describes WHAT is run (shapes, seeds, value distributions, layer
 sequences, explicit paddings) and holds none of the layers' arithmetic. Both the
 CPU oracle and the HIP library consume it; neither of those imports the other.
 """
-from .nets import Layer, Network, residual_cnn, dsep_cnn, audio_cnn, single_conv_relu, block_of  # noqa: F401
+from .nets import Layer, Network, residual_cnn, dsep_cnn, audio_cnn, dense_autoencoder, single_conv_relu, block_of  # noqa: F401
 from .gen import (BASE_SEED, uniform_pm1, normal, he_normal, network_tensors,  # noqa: F401
                   sweep_shapes, SWEEP_N)

@@ -159,12 +159,13 @@ class _Builder:
         self.net.layers.append(L)
         self._set(dst, self.C, 1, 1)
 
-    def dense(self, Co):
+    def dense(self, Co, last=True):
+        dst = OUT if last else self._free(self.buf)
         w = self._weight((Co, self.C, self.H, self.W), self.C * self.H * self.W)
         L = Layer("dense", self.C, Co, self.H, self.W, self.H, self.W, 1,
-                  src=self.buf, dst=OUT, w=w, Ho=1, Wo=1)
+                  src=self.buf, dst=dst, w=w, Ho=1, Wo=1)
         self.net.layers.append(L)
-        self._set(OUT, Co, 1, 1)
+        self._set(dst, Co, 1, 1)
 
     # shapes per buffer so a skip branch can read an older buffer
     def _set(self, buf, C, H, W):
@@ -249,6 +250,23 @@ def audio_cnn() -> Network:
         B.relu()
     B.global_avgpool()
     B.dense(12)
+    return B.net
+
+
+_AUTOENCODER_WIDTHS = (128, 128, 128, 128, 8, 128, 128, 128, 128, 128)
+
+
+def dense_autoencoder() -> Network:
+    """(1, 1, 128) dense-only autoencoder: ten fully connected layers, 128 wide except
+    the 8-wide code in the middle, ReLU after every layer but the last. The widths
+    are the ones that reproduce the weight count the paper lists for this model
+    (Table "tinyml_models": 133120 = 8 * 128 * 128 + 2 * 128 * 8, no biases)."""
+    B = _Builder("dense_autoencoder", 128, 1, 1).start()
+    for i, C in enumerate(_AUTOENCODER_WIDTHS):
+        last = i == len(_AUTOENCODER_WIDTHS) - 1
+        B.dense(C, last=last)
+        if not last:
+            B.relu()
     return B.net
 
 
