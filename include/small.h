@@ -172,11 +172,19 @@ int small_network_run(const small_layer *layers, int n_layers, const float *in_b
  * depthwise result stays on the compute unit and its buffer is never written (allowed only when no later
  * layer reads that buffer before it is rewritten). The depthwise sum is then taken in a different order
  * than by small_dwconv2d: results agree within the tolerance of the two layers, not bit for bit.
+ * A run of two to sixteen pointwise layers (SMALL_OP_DENSE on 1x1 images, unpadded stride-1 1x1 SMALL_OP_CONV;
+ * at most 128 channels per tensor, in 16-channel blocks, or 8 channels in one 8-channel block for tensors
+ * inside the run), each optionally followed by an in-place ReLU and each read only by the next, runs in one
+ * kernel from the first layer's source to the last layer's destination: the tensors between them stay on
+ * the compute unit and their buffers are never written (same liveness rule as above; the run never ends in
+ * the buffer it starts from). The fully connected autoencoder of Section "MLPerf:Tiny Inference Models"
+ * is one such run. Sums are taken in the same order as by small_conv2d's matrix-core kernels.
  *
  * small_network_launches (host only): how many kernel launches the table becomes, and for each the index
  * of the first layer it covers (folded layers follow it directly). It sees the table only: where a
- * depthwise + 1x1 pair cannot run in one kernel for reasons outside the table (unaligned pointers, an
- * image geometry the kernel does not take), the run launches the 1x1 convolution separately. first_layer may be NULL, else it must
+ * depthwise + 1x1 pair or a pointwise run cannot run in one kernel for reasons outside the table (unaligned
+ * pointers, an image geometry the kernel does not take, a run input of 4 GiB or more), the run launches
+ * the layers separately. first_layer may be NULL, else it must
  * have room for n_layers ints.
  * small_network_run_range: like small_network_run, but enqueues only the launches whose first layer index
  * lies in [first, first + count); buffers keep whatever earlier calls left in them (for per-layer timing
