@@ -178,7 +178,8 @@ int small_network_run(const small_layer *layers, int n_layers, const float *in_b
  * kernel from the first layer's source to the last layer's destination: the tensors between them stay on
  * the compute unit and their buffers are never written (same liveness rule as above; the run never ends in
  * the buffer it starts from). The fully connected autoencoder of Section "MLPerf:Tiny Inference Models"
- * is one such run. Sums are taken in the same order as by small_conv2d's matrix-core kernels.
+ * is one such run. Results agree with the layer-by-layer run within the tolerance of the chained
+ * reductions, not bit for bit.
  *
  * small_network_launches (host only): how many kernel launches the table becomes, and for each the index
  * of the first layer it covers (folded layers follow it directly). It sees the table only: where a
