@@ -42,3 +42,17 @@ def sweep_shapes():
     """(C, H) pairs of the conv / depthwise sweep, plus the pool / ReLU shape."""
     return {"conv": [(64, 56), (128, 28), (256, 14), (512, 7)],
             "pool_relu": (256, 56)}
+
+
+# Quantized (uint8) layers: codes are uniform over 0..255; zero points and the fixed-point multiplier are
+# parameters of the layer, chosen here so that the outputs spread over the whole code range.
+def u8_codes(rng, shape):
+    return rng.integers(0, 256, size=shape, dtype=np.uint8)
+
+
+def u8_multiplier(K, spread=40.0, shift=31):
+    """(mult, shift) with mult / 2**shift = spread / (sqrt(K) * 74 * 74): a sum of K products of two
+    uniform codes minus their zero points has a standard deviation of about sqrt(K) * 74 * 74."""
+    m = spread / (np.sqrt(float(K)) * 74.0 * 74.0)
+    mult = int(round(m * (1 << shift)))
+    return min(max(mult, 1), (1 << 31) - 1), shift
