@@ -43,7 +43,8 @@ enum {
     SMALL_ERR_ALIAS = 4,  /* in/out overlap where it is not allowed */
     SMALL_ERR_LAUNCH = 5, /* the HIP runtime refused the launch */
     SMALL_ERR_WORKSPACE = 6, /* workspace too small or misaligned (small_network_run) */
-    SMALL_ERR_LAYER = 7   /* malformed layer table (bad op, bad buffer id, block mismatch between layers) */
+    SMALL_ERR_LAYER = 7,  /* malformed layer table (bad op, bad buffer id, block mismatch between layers) */
+    SMALL_ERR_QUANT = 8   /* quantization parameters out of range, or a reduction too long for int32 sums */
 };
 
 typedef struct { int t, b, l, r; } small_pad; /* zero padding: top, bottom, left, right */
@@ -127,6 +128,40 @@ int small_batchnorm(const float *in, const float *scale, const float *shift, flo
 int small_upsample(const float *in, float *out, int N, int C, int H, int W, int fh, int fw, int Cb, void *stream);
 int small_group_conv2d(const float *in, const float *filt, float *out, int N, int Ci, int F_C, int S_C, int K, int H, int W,
                        int kh, int kw, int stride, small_pad pad, int Cib, int F_Cb, int Cob, void *stream);
+
+/* ---- quantized layers: uint8 codes in and out, int32 sums (Section "Memory Usage Comparison": inputs and
+ * outputs of the quantized models are uint8, partial results are accumulated in int32; Section "Quantized
+ * Inference"). The paper gives no rule for turning the sum back into a code; this library uses the usual
+ * integer-only affine rule, with real value = scale * (code - zero point):
+ *   acc = sum over the taps inside the image of (x - zx) * (w - zw)                       (int32, exact)
+ *   y   = clamp(zy + floor((acc * mult + 2^(shift-1)) / 2^shift), lo, hi)                 (64-bit product,
+ *         ties round up; no rounding term when shift == 0)
+ * 0 <= zx, zw, zy <= 255; 0 <= mult <= 2^31 - 1; 0 <= shift <= 31; 0 <= lo <= hi <= 255 (a ReLU after the layer
+ * is lo = zy). The reduction length K = Ci*kh*kw (kh*kw for depthwise) must satisfy K * 255 * 255 < 2^31.
+ * Layouts (bytes): activations [N][C/Cb][H][W][Cb] as for fp32; convolution filters
+ * [Co/Cob][Ci/Cib][kh][kw][Cob][Cib] -- the two innermost dimensions are swapped with respect to the fp32
+ * filter layout, because the 8-bit matrix instruction multiplies runs of consecutive reduction elements:
+ * the Cib bytes of one output channel must be contiguous (Section 4.4 chooses the layout for the machine's
+ * kernel); depthwise filters [C/Cb][kh][kw][Cb]. Results are bit-exact (integer arithmetic).
+ * small_conv2d_u8: Cib = Cob = 16 with in and filt 16-byte aligned and out 4-byte aligned runs on the int8
+ *   matrix cores, anything else one lane per output. small_dense_u8 is the window = image case on a 1x1 image.
+ * small_pool2d_u8: SMALL_POOL_MAX compares codes and skips taps outside the image; SMALL_POOL_AVG is
+ *   floor((sum + n/2) / n) over the n taps inside the image. small_relu_u8: out = max(in, z). */
+typedef struct { int zx, zw, zy, mult, shift, lo, hi; } small_quant;
+int small_pack_u8(const unsigned char *nchw, unsigned char *blocked, int N, int C, int H, int W, int Cb, void *stream);
+int small_unpack_u8(const unsigned char *blocked, unsigned char *nchw, int N, int C, int H, int W, int Cb, void *stream);
+int small_pack_filter_u8(const unsigned char *oihw, unsigned char *blocked, int Co, int Ci, int kh, int kw, int Cob,
+                         int Cib, void *stream);
+int small_conv2d_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int Ci, int Co, int H,
+                    int W, int kh, int kw, int stride, small_pad pad, int Cib, int Cob, const small_quant *q,
+                    void *stream);
+int small_dwconv2d_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int C, int H, int W,
+                      int kh, int kw, int stride, small_pad pad, int Cb, const small_quant *q, void *stream);
+int small_dense_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int Ci, int Co, int Cib,
+                   int Cob, const small_quant *q, void *stream);
+int small_pool2d_u8(const unsigned char *in, unsigned char *out, int N, int C, int H, int W, int kh, int kw, int stride,
+                    small_pad pad, int Cb, int mode, void *stream);
+int small_relu_u8(const unsigned char *in, unsigned char *out, size_t n_elems, int z, void *stream);
 
 /* ---- a whole network: a table of layers over shared buffers (Section "Memory Usage
  * Comparison": buffers are shared across layers; nothing is reformatted between layers).

@@ -21,7 +21,9 @@ _OPS = {"conv": OP_CONV, "dw": OP_DWCONV, "maxpool": OP_MAXPOOL, "avgpool": OP_A
 
 EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "small_pack_filter",
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
-           "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_network_workspace", "small_network_run", "small_network_launches",
+           "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_pack_u8", "small_unpack_u8",
+           "small_pack_filter_u8", "small_conv2d_u8", "small_dwconv2d_u8", "small_dense_u8", "small_pool2d_u8", "small_relu_u8",
+           "small_network_workspace", "small_network_run", "small_network_launches",
            "small_network_run_range"]
 
 
@@ -33,6 +35,12 @@ class SmallError(RuntimeError):
 
 class small_pad(C.Structure):
     _fields_ = [("t", C.c_int), ("b", C.c_int), ("l", C.c_int), ("r", C.c_int)]
+
+
+class small_quant(C.Structure):
+    """y = clamp(zy + round_half_up(acc * mult / 2**shift), lo, hi), acc = sum (x - zx) * (w - zw)."""
+    _fields_ = [("zx", C.c_int), ("zw", C.c_int), ("zy", C.c_int), ("mult", C.c_int), ("shift", C.c_int),
+                ("lo", C.c_int), ("hi", C.c_int)]
 
 
 class small_layer(C.Structure):
@@ -71,6 +79,14 @@ def load():
         "small_batchnorm": (i, [p, p, p, p, i, i, i, i, i, p]),
         "small_upsample": (i, [p, p, i, i, i, i, i, i, i, p]),
         "small_group_conv2d": (i, [p, p, p, i, i, i, i, i, i, i, i, i, i, small_pad, i, i, i, p]),
+        "small_pack_u8": (i, [p, p, i, i, i, i, i, p]),
+        "small_unpack_u8": (i, [p, p, i, i, i, i, i, p]),
+        "small_pack_filter_u8": (i, [p, p, i, i, i, i, i, i, p]),
+        "small_conv2d_u8": (i, [p, p, p, i, i, i, i, i, i, i, i, small_pad, i, i, C.POINTER(small_quant), p]),
+        "small_dwconv2d_u8": (i, [p, p, p, i, i, i, i, i, i, i, small_pad, i, C.POINTER(small_quant), p]),
+        "small_dense_u8": (i, [p, p, p, i, i, i, i, i, C.POINTER(small_quant), p]),
+        "small_pool2d_u8": (i, [p, p, i, i, i, i, i, i, i, small_pad, i, i, p]),
+        "small_relu_u8": (i, [p, p, sz, i, p]),
         "small_network_workspace": (i, [C.POINTER(small_layer), i, i, i, i, i, C.POINTER(sz)]),
         "small_network_run": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
         "small_network_launches": (i, [C.POINTER(small_layer), i, C.POINTER(i), C.POINTER(i)]),
@@ -176,6 +192,58 @@ def small_upsample(inp, out, N, Cc, H, W, fh, fw, Cb, stream=None):
 def small_group_conv2d(inp, filt, out, N, Ci, F_C, S_C, K, H, W, kh, kw, stride, pad, Cib, F_Cb, Cob, stream=None):
     _check(load().small_group_conv2d(_ptr(inp), _ptr(filt), _ptr(out), N, Ci, F_C, S_C, K, H, W, kh, kw, stride, _pad(pad),
                                      Cib, F_Cb, Cob, _stream(stream)), "small_group_conv2d")
+
+
+def _ptr8(t):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == torch.uint8 and t.is_contiguous()):
+        raise TypeError("expected a contiguous uint8 CUDA tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def _quant(q):
+    """q: small_quant, or any record with fields zx, zw, zy, mult, shift, lo, hi."""
+    if isinstance(q, small_quant):
+        return C.byref(q)
+    return C.byref(small_quant(int(q.zx), int(q.zw), int(q.zy), int(q.mult), int(q.shift), int(q.lo), int(q.hi)))
+
+
+def small_pack_u8(nchw, blocked, N, Cc, H, W, Cb, stream=None):
+    _check(load().small_pack_u8(_ptr8(nchw), _ptr8(blocked), N, Cc, H, W, Cb, _stream(stream)), "small_pack_u8")
+
+
+def small_unpack_u8(blocked, nchw, N, Cc, H, W, Cb, stream=None):
+    _check(load().small_unpack_u8(_ptr8(blocked), _ptr8(nchw), N, Cc, H, W, Cb, _stream(stream)), "small_unpack_u8")
+
+
+def small_pack_filter_u8(oihw, blocked, Co, Ci, kh, kw, Cob, Cib, stream=None):
+    _check(load().small_pack_filter_u8(_ptr8(oihw), _ptr8(blocked), Co, Ci, kh, kw, Cob, Cib, _stream(stream)),
+           "small_pack_filter_u8")
+
+
+def small_conv2d_u8(inp, filt, out, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob, q, stream=None):
+    _check(load().small_conv2d_u8(_ptr8(inp), _ptr8(filt), _ptr8(out), N, Ci, Co, H, W, kh, kw, stride, _pad(pad), Cib, Cob,
+                                  _quant(q), _stream(stream)), "small_conv2d_u8")
+
+
+def small_dwconv2d_u8(inp, filt, out, N, Cc, H, W, kh, kw, stride, pad, Cb, q, stream=None):
+    _check(load().small_dwconv2d_u8(_ptr8(inp), _ptr8(filt), _ptr8(out), N, Cc, H, W, kh, kw, stride, _pad(pad), Cb,
+                                    _quant(q), _stream(stream)), "small_dwconv2d_u8")
+
+
+def small_dense_u8(inp, filt, out, N, Ci, Co, Cib, Cob, q, stream=None):
+    _check(load().small_dense_u8(_ptr8(inp), _ptr8(filt), _ptr8(out), N, Ci, Co, Cib, Cob, _quant(q), _stream(stream)),
+           "small_dense_u8")
+
+
+def small_pool2d_u8(inp, out, N, Cc, H, W, kh, kw, stride, pad, Cb, mode, stream=None):
+    _check(load().small_pool2d_u8(_ptr8(inp), _ptr8(out), N, Cc, H, W, kh, kw, stride, _pad(pad), Cb, mode,
+                                  _stream(stream)), "small_pool2d_u8")
+
+
+def small_relu_u8(inp, out, n, z, stream=None):
+    _check(load().small_relu_u8(_ptr8(inp), _ptr8(out), n, z, _stream(stream)), "small_relu_u8")
 
 
 def make_layer_table(layers, filters):

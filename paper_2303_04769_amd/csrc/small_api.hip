@@ -112,6 +112,7 @@ const char *small_strerror(int code)
         case SMALL_ERR_LAUNCH: return "HIP launch failed";
         case SMALL_ERR_WORKSPACE: return "workspace too small or misaligned";
         case SMALL_ERR_LAYER: return "malformed layer table";
+        case SMALL_ERR_QUANT: return "quantization parameters out of range or reduction too long for int32";
         default: return "unknown error";
     }
 }
@@ -257,6 +258,124 @@ int small_group_conv2d(const float *in, const float *filt, float *out, int N, in
     if (!in || !filt || !out) return SMALL_ERR_NULL;
     if (overlap(in, ni, out, no) || overlap(filt, nf, out, no)) return SMALL_ERR_ALIAS;
     return from_hip(launch_group_conv(in, filt, out, g, F_C, S_C, K, F_Cb, as_stream(stream)));
+}
+
+// ---- quantized (uint8) layers
+
+}  // extern "C"
+
+namespace {
+
+inline bool overlap_bytes(const void *a, size_t na, const void *b, size_t nb)
+{
+    const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+    return a0 < b0 + nb && b0 < a0 + na;
+}
+
+// K: reduction length; |acc| <= K * 255 * 255 must stay below 2^31
+int check_quant(const small_quant *q, long K, QuantParams &out)
+{
+    if (!q) return SMALL_ERR_NULL;
+    if (q->zx < 0 || q->zx > 255 || q->zw < 0 || q->zw > 255 || q->zy < 0 || q->zy > 255) return SMALL_ERR_QUANT;
+    if (q->mult < 0 || q->shift < 0 || q->shift > 31) return SMALL_ERR_QUANT;
+    if (q->lo < 0 || q->hi > 255 || q->lo > q->hi) return SMALL_ERR_QUANT;
+    if (K <= 0 || K * 255L * 255L >= (1L << 31)) return SMALL_ERR_QUANT;
+    out = QuantParams{q->zx, q->zw, q->zy, q->mult, q->shift, q->lo, q->hi};
+    return SMALL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int small_pack_u8(const unsigned char *nchw, unsigned char *blocked, int N, int C, int H, int W, int Cb, void *stream)
+{
+    if (!nchw || !blocked) return SMALL_ERR_NULL;
+    if (int rc = check_block(C, Cb)) return rc;
+    const size_t n = elems(N, C, H, W);
+    if (!n) return SMALL_ERR_SHAPE;
+    if (overlap_bytes(nchw, n, blocked, n)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_pack_u8(nchw, blocked, N, C, H, W, Cb, false, as_stream(stream)));
+}
+
+int small_unpack_u8(const unsigned char *blocked, unsigned char *nchw, int N, int C, int H, int W, int Cb, void *stream)
+{
+    if (!nchw || !blocked) return SMALL_ERR_NULL;
+    if (int rc = check_block(C, Cb)) return rc;
+    const size_t n = elems(N, C, H, W);
+    if (!n) return SMALL_ERR_SHAPE;
+    if (overlap_bytes(nchw, n, blocked, n)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_pack_u8(nchw, const_cast<unsigned char *>(blocked), N, C, H, W, Cb, true, as_stream(stream)));
+}
+
+int small_pack_filter_u8(const unsigned char *oihw, unsigned char *blocked, int Co, int Ci, int kh, int kw, int Cob,
+                         int Cib, void *stream)
+{
+    if (!oihw || !blocked) return SMALL_ERR_NULL;
+    if (int rc = check_block(Co, Cob)) return rc;
+    if (int rc = check_block(Ci, Cib)) return rc;
+    const size_t n = elems(Co, Ci, kh, kw);
+    if (!n) return SMALL_ERR_SHAPE;
+    if (overlap_bytes(oihw, n, blocked, n)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_pack_filter_u8(oihw, blocked, Co, Ci, kh, kw, Cob, Cib, as_stream(stream)));
+}
+
+int small_conv2d_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int Ci, int Co, int H,
+                    int W, int kh, int kw, int stride, small_pad pad, int Cib, int Cob, const small_quant *q,
+                    void *stream)
+{
+    ConvPlan p;
+    if (int rc = plan_conv(p, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob)) return rc;
+    QuantParams qp;
+    if (int rc = check_quant(q, (long)Ci * kh * kw, qp)) return rc;
+    if (!in || !filt || !out) return SMALL_ERR_NULL;
+    if (overlap_bytes(in, p.in_elems, out, p.out_elems) || overlap_bytes(filt, p.filt_elems, out, p.out_elems))
+        return SMALL_ERR_ALIAS;
+    return from_hip(launch_conv_u8(in, filt, out, p.g, qp, as_stream(stream)));
+}
+
+int small_dense_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int Ci, int Co, int Cib,
+                   int Cob, const small_quant *q, void *stream)
+{
+    const small_pad nopad = {0, 0, 0, 0};
+    return small_conv2d_u8(in, filt, out, N, Ci, Co, 1, 1, 1, 1, 1, nopad, Cib, Cob, q, stream);
+}
+
+int small_dwconv2d_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int C, int H, int W,
+                      int kh, int kw, int stride, small_pad pad, int Cb, const small_quant *q, void *stream)
+{
+    LayerGeom g;
+    size_t ni, no;
+    if (int rc = window_geom(g, N, C, C, H, W, kh, kw, stride, pad, Cb, Cb, &ni, &no)) return rc;
+    QuantParams qp;
+    if (int rc = check_quant(q, (long)kh * kw, qp)) return rc;
+    const size_t nf = elems(C, 1, kh, kw);
+    if (!nf) return SMALL_ERR_SHAPE;
+    if (!in || !filt || !out) return SMALL_ERR_NULL;
+    if (overlap_bytes(in, ni, out, no) || overlap_bytes(filt, nf, out, no)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_window_u8(in, filt, out, g, 0, qp, as_stream(stream)));
+}
+
+int small_pool2d_u8(const unsigned char *in, unsigned char *out, int N, int C, int H, int W, int kh, int kw, int stride,
+                    small_pad pad, int Cb, int mode, void *stream)
+{
+    LayerGeom g;
+    size_t ni, no;
+    if (mode != SMALL_POOL_MAX && mode != SMALL_POOL_AVG) return SMALL_ERR_SHAPE;
+    if (int rc = window_geom(g, N, C, C, H, W, kh, kw, stride, pad, Cb, Cb, &ni, &no)) return rc;
+    if ((long)kh * kw * 255L >= (1L << 31)) return SMALL_ERR_SHAPE;
+    if (!in || !out) return SMALL_ERR_NULL;
+    if (overlap_bytes(in, ni, out, no)) return SMALL_ERR_ALIAS;
+    const QuantParams none = {0, 0, 0, 0, 0, 0, 255};
+    return from_hip(launch_window_u8(in, nullptr, out, g, mode == SMALL_POOL_MAX ? 1 : 2, none, as_stream(stream)));
+}
+
+int small_relu_u8(const unsigned char *in, unsigned char *out, size_t n_elems, int z, void *stream)
+{
+    if (!in || !out) return SMALL_ERR_NULL;
+    if (!n_elems || z < 0 || z > 255) return SMALL_ERR_SHAPE;
+    if (in != out && overlap_bytes(in, n_elems, out, n_elems)) return SMALL_ERR_ALIAS;
+    return from_hip(launch_relu_u8(in, out, n_elems, z, as_stream(stream)));
 }
 
 }  // extern "C"

@@ -131,4 +131,20 @@ hipError_t launch_upsample(const float *in, float *out, int N, int C, int H, int
 hipError_t launch_group_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int F_C, int S_C, int K,
                              int F_Cb, hipStream_t s);
 
+// Quantized (uint8) layers (quant.hip). acc = sum over in-image taps of (x - zx)(w - zw) in int32;
+// y = clamp(zy + ((int64)acc * mult + 2^(shift-1)) >> shift, lo, hi) (no rounding term when shift == 0).
+struct QuantParams { int zx, zw, zy, mult, shift, lo, hi; };
+hipError_t launch_pack_u8(const unsigned char *nchw, unsigned char *blk, int N, int C, int H, int W, int Cb, bool unpack,
+                          hipStream_t s);
+hipError_t launch_pack_filter_u8(const unsigned char *oihw, unsigned char *blk, int Co, int Ci, int kh, int kw, int Cob,
+                                 int Cib, hipStream_t s);
+// true when the 8-bit matrix-core kernel takes the layer (16-byte blocks, aligned pointers), else one lane per output
+bool conv_u8_uses_mfma(const LayerGeom &g, const void *in, const void *filt, const void *out);
+hipError_t launch_conv_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
+                          const QuantParams &q, hipStream_t s);
+// mode 0: depthwise (filt [C/Cb][kh][kw][Cb]), 1: max pooling, 2: average pooling (filt unused, may be null)
+hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
+                            int mode, const QuantParams &q, hipStream_t s);
+hipError_t launch_relu_u8(const unsigned char *in, unsigned char *out, size_t n, int z, hipStream_t s);
+
 }  // namespace small

@@ -47,3 +47,23 @@ def assert_close(got, ref, K, what=""):
 def assert_bits(got, ref, what=""):
     assert got.shape == ref.shape, (got.shape, ref.shape)
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), f"{what}: not bit-exact"
+
+
+def dev8(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).to(DEV)
+
+
+class Guarded8:
+    """uint8 output buffer (16-byte aligned start) with canaries on both sides and a canary fill inside,
+    so both stray writes and bytes never written show."""
+
+    def __init__(self, n):
+        self.full = torch.full((n + 2 * GUARD,), 0xA5, dtype=torch.uint8, device=DEV)
+        self.t = self.full[GUARD:GUARD + n]
+        self.n = n
+
+    def check(self):
+        torch.cuda.synchronize()
+        f = self.full.cpu().numpy()
+        assert (f[:GUARD] == 0xA5).all() and (f[GUARD + self.n:] == 0xA5).all(), "kernel wrote outside its output buffer"
+        return f[GUARD:GUARD + self.n].copy()

@@ -1,0 +1,200 @@
+"""GPU parity of the quantized (uint8) layers against the integer oracle, through the C ABI: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2303_04769_amd as S
+import workloads as WL
+from oracle import oracle_u8 as Q
+from gpu_util import DEV, Guarded8, dev8
+
+pytestmark = pytest.mark.gpu
+
+
+def _rng(k):
+    return np.random.default_rng(WL.BASE_SEED + 100 + k)
+
+
+def _quant(K, zx, zw, zy=128, relu=False, **kw):
+    mult, shift = WL.u8_multiplier(K)
+    q = Q.Quant(zx=zx, zw=zw, zy=zy, mult=mult, shift=shift, lo=zy if relu else 0, hi=255)
+    for k, v in kw.items():
+        setattr(q, k, v)
+    return q
+
+
+def _quant_for(acc, zx, zw, relu=False):
+    """Multiplier and output zero point that keep the codes of these accumulators (the oracle's) off the clamps."""
+    mean, std = float(acc.mean()), float(acc.std()) + 1.0
+    m = min(40.0 / std, 100.0 / (abs(mean) + 1.0))
+    zy = int(min(max(round(128 - mean * m), 0), 255))
+    mult = min(max(int(round(m * (1 << 31))), 1), (1 << 31) - 1)
+    # relu: a lower clamp in the middle of the code distribution (the mean maps to about 128), so that about
+    # half of the outputs sit on it
+    return Q.Quant(zx=zx, zw=zw, zy=zy, mult=mult, shift=31, lo=min(zy, 128) if relu else 0, hi=255)
+
+
+def _same(got, ref, what):
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    bad = np.argwhere(got != ref)
+    assert bad.size == 0, f"{what}: {len(bad)} of {got.size} codes differ, first at {bad[0]}: gpu {got[tuple(bad[0])]} ref {ref[tuple(bad[0])]}"
+
+
+@pytest.mark.parametrize("shape,Cb", [((2, 32, 5, 7), 16), ((3, 3, 8, 8), 3), ((1, 8, 9, 2), 8), ((2, 48, 1, 1), 16)])
+def test_pack_unpack(shape, Cb):
+    x = WL.u8_codes(_rng(0), shape)
+    N, C, H, W = shape
+    g = Guarded8(x.size)
+    S.small_pack_u8(dev8(x), g.t, N, C, H, W, Cb)
+    blk = g.check()
+    assert np.array_equal(blk, Q.pack(x, Cb))
+    g2 = Guarded8(x.size)
+    S.small_unpack_u8(dev8(blk), g2.t, N, C, H, W, Cb)
+    assert np.array_equal(g2.check().reshape(shape), x)
+
+
+@pytest.mark.parametrize("Co,Ci,kh,kw,Cob,Cib", [(32, 48, 3, 3, 16, 16), (8, 3, 3, 3, 8, 3), (16, 1, 10, 4, 16, 1), (16, 8, 1, 1, 16, 8)])
+def test_pack_filter(Co, Ci, kh, kw, Cob, Cib):
+    w = WL.u8_codes(_rng(1), (Co, Ci, kh, kw))
+    g = Guarded8(w.size)
+    S.small_pack_filter_u8(dev8(w), g.t, Co, Ci, kh, kw, Cob, Cib)
+    assert np.array_equal(g.check(), Q.pack_filter(w, Cob, Cib))
+
+
+def _conv(x, w, stride, pad, q, Cib, Cob):
+    N, Ci, H, W = x.shape
+    Co, _, kh, kw = w.shape
+    Ho, Wo = Q.out_dim(H, kh, stride, pad[0], pad[1]), Q.out_dim(W, kw, stride, pad[2], pad[3])
+    g = Guarded8(N * Co * Ho * Wo)
+    S.small_conv2d_u8(dev8(Q.pack(x, Cib)), dev8(Q.pack_filter(w, Cob, Cib)), g.t, N, Ci, Co, H, W, kh, kw, stride, pad,
+                      Cib, Cob, q)
+    return Q.unpack(g.check(), (N, Co, Ho, Wo), Cob)
+
+
+CONV_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad, zx, zw, relu
+    (2, 16, 16, 7, 9, 3, 3, 1, (1, 1, 1, 1), 128, 128, False),     # no correction sums; 9 chunks: ragged last step
+    (3, 32, 48, 13, 11, 3, 3, 1, (1, 1, 1, 1), 120, 131, True),    # both correction sums, 18 chunks
+    (2, 64, 32, 9, 9, 3, 3, 2, (0, 1, 0, 1), 0, 255, False),       # extreme zero points, stride 2
+    (5, 16, 16, 5, 5, 1, 1, 1, (0, 0, 0, 0), 255, 0, False),       # one chunk: three idle lane groups
+    (1, 48, 16, 10, 6, 3, 2, 2, (1, 0, 1, 1), 17, 200, True),
+    (3, 16, 16, 5, 7, 3, 3, 1, (1, 1, 1, 1), 130, 128, False),     # 105 pixels: ragged pixel tile; only the filter sum
+    (2, 16, 32, 6, 6, 3, 3, 1, (1, 1, 1, 1), 128, 77, False),      # only the pixel sum
+    (4, 32, 16, 4, 4, 4, 4, 1, (0, 0, 0, 0), 100, 150, False),     # window = image (dense over 4 x 4)
+    (37, 128, 16, 1, 1, 1, 1, 1, (0, 0, 0, 0), 128, 128, True),    # dense on 1 x 1 images
+    (2, 512, 16, 3, 3, 3, 3, 1, (1, 1, 1, 1), 3, 250, False),      # long reduction (K = 4608)
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_matrix_core(case):
+    N, Ci, Co, H, W, kh, kw, s, pad, zx, zw, relu = case
+    r = _rng(2)
+    x, w = WL.u8_codes(r, (N, Ci, H, W)), WL.u8_codes(r, (Co, Ci, kh, kw))
+    q = _quant_for(Q.conv2d_acc(x, w, s, pad, zx, zw), zx, zw, relu)
+    ref = Q.conv2d(x, w, s, pad, q)
+    _same(_conv(x, w, s, pad, q, 16, 16), ref, f"conv u8 {case}")
+    assert ref.std() > 1.5 and len(np.unique(ref)) > 8
+
+
+@pytest.mark.parametrize("case", [
+    (2, 3, 8, 9, 9, 3, 3, 2, (0, 1, 0, 1), 128, 128, 3, 8),        # first layer of the depthwise-separable CNN
+    (2, 1, 16, 13, 10, 10, 4, 2, (4, 5, 1, 1), 5, 140, 1, 16),     # first layer of the audio CNN
+    (3, 8, 16, 6, 5, 1, 1, 1, (0, 0, 0, 0), 200, 100, 8, 16),
+    (2, 16, 8, 5, 5, 3, 3, 1, (1, 1, 1, 1), 128, 128, 16, 8),
+    (1, 32, 32, 4, 4, 3, 3, 1, (1, 1, 1, 1), 1, 2, 32, 32),
+])
+def test_conv_other_blocks(case):
+    N, Ci, Co, H, W, kh, kw, s, pad, zx, zw, Cib, Cob = case
+    r = _rng(3)
+    x, w = WL.u8_codes(r, (N, Ci, H, W)), WL.u8_codes(r, (Co, Ci, kh, kw))
+    q = _quant_for(Q.conv2d_acc(x, w, s, pad, zx, zw), zx, zw)
+    ref = Q.conv2d(x, w, s, pad, q)
+    _same(_conv(x, w, s, pad, q, Cib, Cob), ref, f"conv u8 generic {case}")
+    assert len(np.unique(ref)) > 8
+
+
+def test_requantization_corner_parameters():
+    """shift 0, the largest multiplier, clamps at both ends, ReLU ranges: same codes as the oracle."""
+    r = _rng(4)
+    x, w = WL.u8_codes(r, (2, 16, 6, 6)), WL.u8_codes(r, (16, 16, 3, 3))
+    for kw in (dict(mult=1, shift=0), dict(mult=(1 << 31) - 1, shift=31), dict(mult=0, shift=5), dict(mult=3, shift=3, zy=0),
+               dict(mult=12345, shift=20, zy=255), dict(mult=9000, shift=31, lo=100, hi=140, zy=120)):
+        q = _quant(144, 128, 128, **kw)
+        _same(_conv(x, w, 1, (1, 1, 1, 1), q, 16, 16), Q.conv2d(x, w, 1, (1, 1, 1, 1), q), f"requant {kw}")
+    S.small_dense_u8  # exported
+    xd, wd = WL.u8_codes(r, (9, 32, 1, 1)), WL.u8_codes(r, (16, 32, 1, 1))
+    q = _quant(32, 99, 101)
+    g = Guarded8(9 * 16)
+    S.small_dense_u8(dev8(Q.pack(xd, 16)), dev8(Q.pack_filter(wd, 16, 16)), g.t, 9, 32, 16, 16, 16, q)
+    _same(Q.unpack(g.check(), (9, 16, 1, 1), 16), Q.dense(xd, wd, q), "dense u8")
+
+
+def test_conv_full_size_sampled():
+    """A sweep-sized layer in the launch configuration the benchmark times (64 pixels per wave); the oracle
+    recomputes three images (images are independent)."""
+    N, C, H = 64, 64, 56
+    r = _rng(5)
+    x, w = WL.u8_codes(r, (N, C, H, H)), WL.u8_codes(r, (C, C, 3, 3))
+    q = _quant(C * 9, 121, 135, relu=True)
+    got = _conv(x, w, 1, (1, 1, 1, 1), q, 16, 16)
+    for n in (0, 31, N - 1):
+        _same(got[n:n + 1], Q.conv2d(x[n:n + 1], w, 1, (1, 1, 1, 1), q), f"conv u8 64x64x56x56 image {n}")
+
+
+DW_CASES = [  # N, C, H, W, kh, kw, stride, pad, Cb, zx, zw
+    (2, 32, 9, 7, 3, 3, 1, (1, 1, 1, 1), 16, 128, 128),
+    (3, 16, 12, 12, 3, 3, 2, (0, 1, 0, 1), 16, 7, 250),
+    (2, 8, 6, 6, 3, 3, 1, (1, 1, 1, 1), 8, 100, 60),
+    (2, 3, 5, 5, 3, 3, 1, (1, 1, 1, 1), 3, 128, 128),             # one lane per code
+    (1, 64, 25, 5, 3, 3, 1, (1, 1, 1, 1), 16, 130, 120),
+    (2, 16, 7, 7, 5, 2, 2, (2, 2, 0, 1), 16, 0, 0),
+]
+
+
+@pytest.mark.parametrize("case", DW_CASES)
+def test_depthwise(case):
+    N, C, H, W, kh, kw, s, pad, Cb, zx, zw = case
+    r = _rng(6)
+    x, w = WL.u8_codes(r, (N, C, H, W)), WL.u8_codes(r, (C, 1, kh, kw))
+    q = _quant_for(Q.dwconv2d_acc(x, w, s, pad, zx, zw), zx, zw, relu=True)
+    ref = Q.dwconv2d(x, w, s, pad, q)
+    assert len(np.unique(ref)) > 8
+    g = Guarded8(ref.size)
+    S.small_dwconv2d_u8(dev8(Q.pack(x, Cb)), dev8(Q.pack_dw_filter(w, Cb)), g.t, N, C, H, W, kh, kw, s, pad, Cb, q)
+    _same(Q.unpack(g.check(), ref.shape, Cb), ref, f"dw u8 {case}")
+
+
+@pytest.mark.parametrize("case", [(2, 32, 9, 7, 3, 3, 2, (0, 0, 0, 0), 16), (2, 16, 8, 8, 2, 2, 2, (0, 1, 0, 1), 16),
+                                  (3, 64, 5, 5, 5, 5, 1, (0, 0, 0, 0), 16), (2, 3, 7, 7, 3, 3, 1, (1, 1, 1, 1), 3),
+                                  (1, 8, 6, 9, 3, 2, 1, (1, 1, 0, 1), 8)])
+@pytest.mark.parametrize("mode", ["max", "avg"])
+def test_pooling(case, mode):
+    N, C, H, W, kh, kw, s, pad, Cb = case
+    x = WL.u8_codes(_rng(7), (N, C, H, W))
+    ref = Q.pool2d(x, (kh, kw), s, pad, mode)
+    g = Guarded8(ref.size)
+    S.small_pool2d_u8(dev8(Q.pack(x, Cb)), g.t, N, C, H, W, kh, kw, s, pad, Cb, S.POOL_MAX if mode == "max" else S.POOL_AVG)
+    _same(Q.unpack(g.check(), ref.shape, Cb), ref, f"pool u8 {mode} {case}")
+
+
+@pytest.mark.parametrize("n", [1, 4, 1023, 4096, 100003])
+def test_relu(n):
+    x = WL.u8_codes(_rng(8), (n,))
+    for z in (0, 128, 255):
+        g = Guarded8(n)
+        S.small_relu_u8(dev8(x), g.t, n, z)
+        assert np.array_equal(g.check(), Q.relu(x, z))
+    t = dev8(x)
+    S.small_relu_u8(t, t, n, 77)       # in place
+    torch.cuda.synchronize()
+    assert np.array_equal(t.cpu().numpy(), np.maximum(x, 77))
+
+
+def test_errors_are_raised():
+    t = torch.zeros(4096, dtype=torch.uint8, device=DEV)
+    o = torch.zeros(4096, dtype=torch.uint8, device=DEV)
+    with pytest.raises(S.SmallError) as e:
+        S.small_conv2d_u8(t, t, o, 1, 16, 16, 4, 4, 3, 3, 1, (1, 1, 1, 1), 16, 16, Q.Quant(zx=300))
+    assert e.value.code == 8
+    with pytest.raises(TypeError):
+        S.small_relu_u8(torch.zeros(4, device=DEV), o, 4, 0)
