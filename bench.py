@@ -12,7 +12,9 @@ Also reported on the same JSON line:
   sweep         the roofline layer sweep (batch 64, Cb = 16): conv GFLOP/s against the fp32 MFMA peak,
                 depthwise / max-pool / ReLU GB/s against the HBM peak, buffers rotated so that
                 at least 512 MB are touched between reuses of a buffer;
-  networks      images/s of the three stand-in networks at batch 1 and at their large batch;
+  sweep_u8      the same layers on the quantized path (uint8 codes, int32 sums): conv TOP/s against the int8
+                MFMA peak and GB/s against the HBM peak;
+  networks      images/s of the four stand-in networks at batch 1 and at their large batch;
   cpu_baseline  the CPU oracle (as it stands) on a bounded sample of the same workload.
 """
 import argparse
@@ -27,6 +29,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32 = 157.3e12     # MI355X dense fp32 matrix, flop/s
+PEAK_MFMA_I8 = 5.0e15        # MI355X dense int8 matrix, op/s
 PEAK_HBM = 8.0e12            # MI355X HBM3E, B/s
 ROTATE_BYTES = 512e6         # touched between reuses of a buffer in HBM-bound timings (> 256 MB Infinity Cache)
 
@@ -194,6 +197,8 @@ def main():
                                             "unit": "TFLOP/s", "frac": best["frac"], "shape": best["shape"],
                                             "kernel": best["kernel"]}
 
+        result["sweep_u8"] = sweep_u8(S, WL, torch, dev, timed)
+
     # ------------------------------------------------------------------ networks
     if not args.no_networks:
         result["networks"] = networks(S, WL, torch, dev, timed)
@@ -315,6 +320,64 @@ def sweep(S, WL, torch, np, dev, timed, only=None):
     rows.append({"layer": "pack", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
                  "us_median": round(tmed * 1e6, 2), "gbs": round(8.0 * n_act / tmin / 1e9, 1),
                  "frac": round(8.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": 3})
+    return rows
+
+
+def sweep_u8(S, WL, torch, dev, timed):
+    """The sweep layers on the quantized path: uint8 codes in and out, int32 sums, both zero-point corrections on."""
+    from paper_2303_04769_amd.binding import small_quant
+    Nb = WL.SWEEP_N
+    rows = []
+
+    def codes(n):
+        return torch.randint(0, 256, (n,), dtype=torch.uint8, device=dev)
+
+    def best_of(fn, reps, trials=3):
+        spin(fn)
+        ts = [timed(fn, reps) for _ in range(trials)]
+        return min(ts), statistics.median(ts)
+
+    for C, H in WL.sweep_shapes()["conv"]:
+        n_act = Nb * C * H * H
+        sets = max(2, min(48, int(-(-ROTATE_BYTES // (2.0 * n_act)))))
+        ins = [codes(n_act) for _ in range(sets)]
+        outs = [torch.empty(n_act, dtype=torch.uint8, device=dev) for _ in range(sets)]
+        shape = "N64 C%d %dx%d" % (C, H, H)
+        for k, name in ((3, "conv3x3"), (1, "conv1x1")):
+            w = codes(C * C * k * k)
+            mult, shift = WL.u8_multiplier(C * k * k)
+            q = small_quant(120, 131, 128, mult, shift, 0, 255)
+            pad = (1, 1, 1, 1) if k == 3 else (0, 0, 0, 0)
+            fn = lambda r: S.small_conv2d_u8(ins[r % sets], w, outs[r % sets], Nb, C, C, H, H, k, k, 1, pad, 16, 16, q)
+            tmin, tmed = best_of(fn, 50)
+            ops = 2.0 * Nb * C * H * H * C * k * k
+            byts = 2.0 * n_act + C * C * k * k
+            rows.append({"layer": name, "shape": shape, "us": round(tmin * 1e6, 2), "us_median": round(tmed * 1e6, 2),
+                         "tops": round(ops / tmin / 1e12, 1), "frac": round(ops / tmin / PEAK_MFMA_I8, 4),
+                         "gbs": round(byts / tmin / 1e9, 1), "frac_hbm": round(byts / tmin / PEAK_HBM, 4)})
+        wd = codes(C * 9)
+        q = small_quant(120, 131, 128, WL.u8_multiplier(9)[0], 31, 0, 255)
+        fn = lambda r: S.small_dwconv2d_u8(ins[r % sets], wd, outs[r % sets], Nb, C, H, H, 3, 3, 1, (1, 1, 1, 1), 16, q)
+        tmin, tmed = best_of(fn, 50)
+        rows.append({"layer": "dw3x3", "shape": shape, "us": round(tmin * 1e6, 2), "us_median": round(tmed * 1e6, 2),
+                     "gbs": round(2.0 * n_act / tmin / 1e9, 1), "frac": round(2.0 * n_act / tmin / PEAK_HBM, 4),
+                     "buffer_sets": sets})
+        del ins, outs
+    C, H = WL.sweep_shapes()["pool_relu"]
+    n_act, n_pool = Nb * C * H * H, Nb * C * 27 * 27
+    sets = 6
+    ins = [codes(n_act) for _ in range(sets)]
+    outs = [torch.empty(n_act, dtype=torch.uint8, device=dev) for _ in range(sets)]
+    shape = "N64 C%d %dx%d" % (C, H, H)
+    fn = lambda r: S.small_relu_u8(ins[r % sets], outs[r % sets], n_act, 128)
+    tmin, tmed = best_of(fn, 50)
+    rows.append({"layer": "relu", "shape": shape, "us": round(tmin * 1e6, 2), "us_median": round(tmed * 1e6, 2),
+                 "gbs": round(2.0 * n_act / tmin / 1e9, 1), "frac": round(2.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": sets})
+    fn = lambda r: S.small_pool2d_u8(ins[r % sets], outs[r % sets], Nb, C, H, H, 3, 3, 2, (0, 0, 0, 0), 16, S.POOL_MAX)
+    tmin, tmed = best_of(fn, 50)
+    rows.append({"layer": "maxpool3x3s2", "shape": shape, "us": round(tmin * 1e6, 2), "us_median": round(tmed * 1e6, 2),
+                 "gbs": round((n_act + n_pool) / tmin / 1e9, 1), "frac": round((n_act + n_pool) / tmin / PEAK_HBM, 4),
+                 "buffer_sets": sets})
     return rows
 
 

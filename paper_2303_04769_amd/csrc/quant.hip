@@ -109,12 +109,13 @@ __global__ void __launch_bounds__(256) conv_u8_direct(QConvArgs a, size_t total)
     a.out[i] = (unsigned char)requant(acc, a.q);
 }
 
-template <int WM>
+// Each wave: WM groups of 16 output pixels x WN blocks of 16 output channels (blockIdx.y counts groups of WN blocks).
+template <int WM, int WN>
 __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int p = lane & 15, g = lane >> 4;
-    const int cob = blockIdx.y;
+    const int cob0 = blockIdx.y * WN;
     const int tile0 = ((int)blockIdx.x * 4 + wave) * (16 * WM);
     const int HW = a.H * a.W;
     const int za = a.q.zx - 128, zb = a.q.zw - 128;
@@ -135,34 +136,53 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
     // this lane group's reduction chunk: c = (cib * kh + ky) * kw + kx, advanced by 4 per step
     int c = g;
     int kx = c % a.kw, ky = (c / a.kw) % a.kh, cib = c / (a.kw * a.kh);
-    const intx4 *filt = reinterpret_cast<const intx4 *>(a.filt) + (size_t)cob * a.n_chunks * 16 + p;
+    const intx4 *filt = reinterpret_cast<const intx4 *>(a.filt) + (size_t)cob0 * a.n_chunks * 16 + p;
+    const size_t cob_stride = (size_t)a.n_chunks * 16;
     const intx4 *in = reinterpret_cast<const intx4 *>(a.in);
     const int flip = (int)0x80808080u;
     const int zx4 = a.q.zx * 0x01010101;
     const intx4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
     const intx4 zero = {0, 0, 0, 0};
 
-    intx4 acc[WM], acc_s[WM], acc_w = zero;
+    intx4 acc[WM][WN], acc_s[WM], acc_w[WN];
 #pragma unroll
-    for (int wm = 0; wm < WM; ++wm) acc[wm] = acc_s[wm] = zero;
+    for (int wm = 0; wm < WM; ++wm) {
+        acc_s[wm] = zero;
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) acc[wm][wn] = zero;
+    }
+#pragma unroll
+    for (int wn = 0; wn < WN; ++wn) acc_w[wn] = zero;
 
     const int steps = (a.n_chunks + 3) >> 2;
     for (int t = 0; t < steps; ++t) {
         const bool live = c < a.n_chunks;
-        intx4 fa = zero;
-        if (live) fa = filt[(size_t)c * 16] ^ flip;
+        intx4 fa[WN], fb[WM];
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) {
+            fa[wn] = zero;
+            if (live) fa[wn] = filt[wn * cob_stride + (size_t)c * 16] ^ flip;
+        }
 #pragma unroll
         for (int wm = 0; wm < WM; ++wm) {
             const int ih = ih0[wm] + ky, iw = iw0[wm] + kx;
             const bool inside = live && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-            intx4 fb = {zx4, zx4, zx4, zx4};
-            if (inside) fb = in[img[wm] + (size_t)cib * HW + ih * a.W + iw];
-            fb ^= flip;
-            if (!live) fb = zero;
-            acc[wm] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa, fb, acc[wm], 0, 0, 0);
-            if (use_s) acc_s[wm] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb, acc_s[wm], 0, 0, 0);
+            fb[wm] = intx4{zx4, zx4, zx4, zx4};
+            if (inside) fb[wm] = in[img[wm] + (size_t)cib * HW + ih * a.W + iw];
+            fb[wm] ^= flip;
+            if (!live) fb[wm] = zero;
         }
-        if (use_w) acc_w = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa, ones, acc_w, 0, 0, 0);
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm) {
+#pragma unroll
+            for (int wn = 0; wn < WN; ++wn)
+                acc[wm][wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], fb[wm], acc[wm][wn], 0, 0, 0);
+            if (use_s) acc_s[wm] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb[wm], acc_s[wm], 0, 0, 0);
+        }
+        if (use_w) {
+#pragma unroll
+            for (int wn = 0; wn < WN; ++wn) acc_w[wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], ones, acc_w[wn], 0, 0, 0);
+        }
         c += 4;
         kx += 4;
         while (kx >= a.kw) { kx -= a.kw; ++ky; }
@@ -176,16 +196,20 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
     for (int wm = 0; wm < WM; ++wm) {
         const int m = tile0 + wm * 16 + p;
         if (m >= a.M) continue;
-        unsigned packed = 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            // wrap-around arithmetic: the true sum fits 32 bits, the partial terms need not
-            const unsigned v = (unsigned)acc[wm][r] - (unsigned)zb * (unsigned)acc_s[wm][r] - (unsigned)za * (unsigned)acc_w[r] + kab;
-            packed |= (unsigned)requant((int)v, a.q) << (8 * r);
-        }
         const int n = m / a.HoWo, pix = m - n * a.HoWo;
-        unsigned *o = reinterpret_cast<unsigned *>(a.out + (((size_t)n * a.nCob + cob) * a.HoWo + pix) * 16 + g * 4);
-        *o = packed;
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) {
+            unsigned packed = 0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // wrap-around arithmetic: the true sum fits 32 bits, the partial terms need not
+                const unsigned v = (unsigned)acc[wm][wn][r] - (unsigned)zb * (unsigned)acc_s[wm][r] -
+                                   (unsigned)za * (unsigned)acc_w[wn][r] + kab;
+                packed |= (unsigned)requant((int)v, a.q) << (8 * r);
+            }
+            unsigned *o = reinterpret_cast<unsigned *>(a.out + (((size_t)n * a.nCob + cob0 + wn) * a.HoWo + pix) * 16 + g * 4);
+            *o = packed;
+        }
     }
 }
 
@@ -288,6 +312,16 @@ __global__ void __launch_bounds__(256) relu_u8_words(const unsigned *in, unsigne
 
 inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 
+// Pixel groups (wm) and output blocks (wn) per wave: an input operand serves wn matrix instructions and a filter
+// operand wm of them. Measured at the sweep shapes, 2 x 2 is within a few per cent of the best of the nine
+// combinations up to 4 x 4 everywhere (the kernel is bound by the latency of its unstaged operand loads).
+void pick_conv_tile(int M, int nCob, int &wm, int &wn)
+{
+    (void)M;
+    wm = 2;
+    wn = nCob % 2 == 0 ? 2 : 1;
+}
+
 QConvArgs conv_args(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
                     const QuantParams &q)
 {
@@ -330,13 +364,13 @@ hipError_t launch_conv_u8(const unsigned char *in, const unsigned char *filt, un
 {
     const QConvArgs a = conv_args(in, filt, out, g, q);
     if (conv_u8_uses_mfma(g, in, filt, out)) {
-        // pixels per wave: 64 when that still leaves four workgroups per compute unit, else 16
-        const long wgs4 = ((long)a.M + 255) / 256 * a.nCob;
-        if (wgs4 >= 1024) {
-            hipLaunchKernelGGL((conv_u8_mfma<4>), dim3((unsigned)((a.M + 255) / 256), (unsigned)a.nCob), dim3(256), 0, s, a);
-        } else {
-            hipLaunchKernelGGL((conv_u8_mfma<1>), dim3((unsigned)((a.M + 63) / 64), (unsigned)a.nCob), dim3(256), 0, s, a);
-        }
+        int wm = 4, wn = 4;
+        pick_conv_tile(a.M, a.nCob, wm, wn);
+        const dim3 grid((unsigned)((a.M + 64 * wm - 1) / (64 * wm)), (unsigned)(a.nCob / wn));
+#define SMALL_U8_CASE(M_, N_) \
+    if (wm == M_ && wn == N_) hipLaunchKernelGGL((conv_u8_mfma<M_, N_>), grid, dim3(256), 0, s, a)
+        SMALL_U8_CASE(2, 2); SMALL_U8_CASE(2, 1);
+#undef SMALL_U8_CASE
         return hipGetLastError();
     }
     const size_t total = (size_t)a.M * g.Co;
