@@ -154,10 +154,9 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
 #pragma unroll
     for (int wn = 0; wn < WN; ++wn) acc_w[wn] = zero;
 
-    const int steps = (a.n_chunks + 3) >> 2;
-    for (int t = 0; t < steps; ++t) {
+    // operands of one step: this lane group's chunk c = (cib, ky, kx); chunks past the end read as zero
+    auto load = [&](intx4 (&fa)[WN], intx4 (&fb)[WM]) __attribute__((always_inline)) {
         const bool live = c < a.n_chunks;
-        intx4 fa[WN], fb[WM];
 #pragma unroll
         for (int wn = 0; wn < WN; ++wn) {
             fa[wn] = zero;
@@ -172,6 +171,12 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
             fb[wm] ^= flip;
             if (!live) fb[wm] = zero;
         }
+        c += 4;
+        kx += 4;
+        while (kx >= a.kw) { kx -= a.kw; ++ky; }
+        while (ky >= a.kh) { ky -= a.kh; ++cib; }
+    };
+    auto multiply = [&](const intx4 (&fa)[WN], const intx4 (&fb)[WM]) __attribute__((always_inline)) {
 #pragma unroll
         for (int wm = 0; wm < WM; ++wm) {
 #pragma unroll
@@ -183,10 +188,17 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
 #pragma unroll
             for (int wn = 0; wn < WN; ++wn) acc_w[wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], ones, acc_w[wn], 0, 0, 0);
         }
-        c += 4;
-        kx += 4;
-        while (kx >= a.kw) { kx -= a.kw; ++ky; }
-        while (ky >= a.kh) { ky -= a.kh; ++cib; }
+    };
+
+    // two operand sets in turn: the loads of step t + 1 are in flight while step t multiplies
+    const int steps = (a.n_chunks + 3) >> 2;
+    intx4 fa0[WN], fb0[WM], fa1[WN], fb1[WM];
+    load(fa0, fb0);
+    for (int t = 0; t < steps; t += 2) {
+        load(fa1, fb1);               // step t + 1 (all zero past the end)
+        multiply(fa0, fb0);
+        load(fa0, fb0);               // step t + 2
+        multiply(fa1, fb1);
     }
 
     // lane (p, g) holds output channels 4g .. 4g+3 of pixel p: four consecutive bytes of the blocked output
@@ -203,6 +215,113 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 // wrap-around arithmetic: the true sum fits 32 bits, the partial terms need not
+                const unsigned v = (unsigned)acc[wm][wn][r] - (unsigned)zb * (unsigned)acc_s[wm][r] -
+                                   (unsigned)za * (unsigned)acc_w[wn][r] + kab;
+                packed |= (unsigned)requant((int)v, a.q) << (8 * r);
+            }
+            unsigned *o = reinterpret_cast<unsigned *>(a.out + (((size_t)n * a.nCob + cob0 + wn) * a.HoWo + pix) * 16 + g * 4);
+            *o = packed;
+        }
+    }
+}
+
+// The same tile for layers whose input has a multiple of four 16-channel blocks: one matrix instruction takes one
+// filter tap of four consecutive input blocks (lane group g = block 4j + g), so the tap, its bounds test and the
+// operand addresses are per-tap values and the walk over j only adds constants.
+template <int WM, int WN>
+__global__ void __launch_bounds__(256) conv_u8_mfma4(QConvArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p = lane & 15, g = lane >> 4;
+    const int cob0 = blockIdx.y * WN;
+    const int tile0 = ((int)blockIdx.x * 4 + wave) * (16 * WM);
+    const int HW = a.H * a.W;
+    const int za = a.q.zx - 128, zb = a.q.zw - 128;
+    const bool use_s = zb != 0, use_w = za != 0;
+    const int taps = a.kh * a.kw;
+
+    int ih0[WM], iw0[WM];
+    const intx4 *img[WM];       // this lane group's first input block of the pixel's image
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm) {
+        int m = tile0 + wm * 16 + p;
+        m = m < a.M ? m : a.M - 1;
+        const int n = m / a.HoWo, rem = m - n * a.HoWo;
+        const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+        ih0[wm] = oh * a.stride - a.pt;
+        iw0[wm] = ow * a.stride - a.pl;
+        img[wm] = reinterpret_cast<const intx4 *>(a.in) + ((size_t)n * a.nCib + g) * HW;
+    }
+    // filter block (cob, cib, tap) holds 16 rows of 16 bytes: row p of block (cob0, g, 0)
+    const intx4 *filt = reinterpret_cast<const intx4 *>(a.filt) + ((size_t)cob0 * a.n_chunks + (size_t)g * taps) * 16 + p;
+    const size_t cob_stride = (size_t)a.n_chunks * 16;
+    const int flip = (int)0x80808080u;
+    const int zx4 = a.q.zx * 0x01010101;
+    const intx4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    const intx4 zero = {0, 0, 0, 0};
+    const intx4 pad = {zx4 ^ flip, zx4 ^ flip, zx4 ^ flip, zx4 ^ flip};
+
+    intx4 acc[WM][WN], acc_s[WM], acc_w[WN];
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm) {
+        acc_s[wm] = zero;
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) acc[wm][wn] = zero;
+    }
+#pragma unroll
+    for (int wn = 0; wn < WN; ++wn) acc_w[wn] = zero;
+
+    const int groups = a.nCib >> 2;
+    int ky = 0, kx = 0;
+    for (int tap = 0; tap < taps; ++tap) {
+        const intx4 *bp[WM];
+        bool inside[WM];
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm) {
+            const int ih = ih0[wm] + ky, iw = iw0[wm] + kx;
+            inside[wm] = ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            bp[wm] = img[wm] + (inside[wm] ? ih * a.W + iw : 0);
+        }
+        const intx4 *ap = filt + (size_t)tap * 16;
+        for (int j = 0; j < groups; ++j) {
+            intx4 fa[WN], fb[WM];
+#pragma unroll
+            for (int wn = 0; wn < WN; ++wn) fa[wn] = ap[wn * cob_stride] ^ flip;
+#pragma unroll
+            for (int wm = 0; wm < WM; ++wm) {
+                fb[wm] = pad;
+                if (inside[wm]) fb[wm] = *bp[wm] ^ flip;
+                bp[wm] += (size_t)4 * HW;
+            }
+            ap += (size_t)4 * taps * 16;
+#pragma unroll
+            for (int wm = 0; wm < WM; ++wm) {
+#pragma unroll
+                for (int wn = 0; wn < WN; ++wn)
+                    acc[wm][wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], fb[wm], acc[wm][wn], 0, 0, 0);
+                if (use_s) acc_s[wm] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb[wm], acc_s[wm], 0, 0, 0);
+            }
+            if (use_w) {
+#pragma unroll
+                for (int wn = 0; wn < WN; ++wn)
+                    acc_w[wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], ones, acc_w[wn], 0, 0, 0);
+            }
+        }
+        if (++kx == a.kw) { kx = 0; ++ky; }
+    }
+
+    const unsigned K = (unsigned)a.n_chunks * 16u;
+    const unsigned kab = K * (unsigned)(za * zb);
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm) {
+        const int m = tile0 + wm * 16 + p;
+        if (m >= a.M) continue;
+        const int n = m / a.HoWo, pix = m - n * a.HoWo;
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) {
+            unsigned packed = 0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
                 const unsigned v = (unsigned)acc[wm][wn][r] - (unsigned)zb * (unsigned)acc_s[wm][r] -
                                    (unsigned)za * (unsigned)acc_w[wn][r] + kab;
                 packed |= (unsigned)requant((int)v, a.q) << (8 * r);
@@ -313,13 +432,15 @@ __global__ void __launch_bounds__(256) relu_u8_words(const unsigned *in, unsigne
 inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 
 // Pixel groups (wm) and output blocks (wn) per wave: an input operand serves wn matrix instructions and a filter
-// operand wm of them. Measured at the sweep shapes, 2 x 2 is within a few per cent of the best of the nine
-// combinations up to 4 x 4 everywhere (the kernel is bound by the latency of its unstaged operand loads).
+// operand wm of them. Four output blocks and two pixel groups measured best at the sweep shapes; smaller tiles
+// when the grid would otherwise have fewer than two workgroups per compute unit.
 void pick_conv_tile(int M, int nCob, int &wm, int &wn)
 {
-    (void)M;
+    wn = nCob % 4 == 0 ? 4 : (nCob % 2 == 0 ? 2 : 1);
     wm = 2;
-    wn = nCob % 2 == 0 ? 2 : 1;
+    auto wgs = [&](int m, int n) { return ((long)M + 64 * m - 1) / (64 * m) * (nCob / n); };
+    if (wgs(wm, wn) < 512) wm = 1;
+    if (wgs(wm, wn) < 512 && wn == 4) wn = 2;
 }
 
 QConvArgs conv_args(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
@@ -367,9 +488,13 @@ hipError_t launch_conv_u8(const unsigned char *in, const unsigned char *filt, un
         int wm = 4, wn = 4;
         pick_conv_tile(a.M, a.nCob, wm, wn);
         const dim3 grid((unsigned)((a.M + 64 * wm - 1) / (64 * wm)), (unsigned)(a.nCob / wn));
-#define SMALL_U8_CASE(M_, N_) \
-    if (wm == M_ && wn == N_) hipLaunchKernelGGL((conv_u8_mfma<M_, N_>), grid, dim3(256), 0, s, a)
-        SMALL_U8_CASE(2, 2); SMALL_U8_CASE(2, 1);
+#define SMALL_U8_CASE(M_, N_)                                                                         \
+    if (wm == M_ && wn == N_) {                                                                       \
+        if (a.nCib % 4 == 0) hipLaunchKernelGGL((conv_u8_mfma4<M_, N_>), grid, dim3(256), 0, s, a);   \
+        else hipLaunchKernelGGL((conv_u8_mfma<M_, N_>), grid, dim3(256), 0, s, a);                    \
+    }
+        SMALL_U8_CASE(2, 4); SMALL_U8_CASE(2, 2); SMALL_U8_CASE(2, 1);
+        SMALL_U8_CASE(1, 4); SMALL_U8_CASE(1, 2); SMALL_U8_CASE(1, 1);
 #undef SMALL_U8_CASE
         return hipGetLastError();
     }
