@@ -375,7 +375,9 @@ def sweep_u8(S, WL, torch, dev, timed):
             mult, shift = WL.u8_multiplier(C * k * k)
             q = small_quant(120, 131, 128, mult, shift, 0, 255)
             pad = (1, 1, 1, 1) if k == 3 else (0, 0, 0, 0)
-            fn = lambda r: S.small_conv2d_u8(ins[r % sets], w, outs[r % sets], Nb, C, C, H, H, k, k, 1, pad, 16, 16, q)
+            sums = torch.empty(C, dtype=torch.int32, device=dev)
+            S.small_filter_sums_u8(w, sums, C, C, k, k, 16, 16)     # kept with the filter, like the filter itself
+            fn = lambda r: S.small_conv2d_u8(ins[r % sets], w, outs[r % sets], Nb, C, C, H, H, k, k, 1, pad, 16, 16, q, sums)
             tmin, tmed = best_of(fn, 240)
             ops = 2.0 * Nb * C * H * H * C * k * k
             byts = 2.0 * n_act + C * C * k * k

@@ -152,13 +152,20 @@ int small_pack_u8(const unsigned char *nchw, unsigned char *blocked, int N, int 
 int small_unpack_u8(const unsigned char *blocked, unsigned char *nchw, int N, int C, int H, int W, int Cb, void *stream);
 int small_pack_filter_u8(const unsigned char *oihw, unsigned char *blocked, int Co, int Ci, int kh, int kw, int Cob,
                          int Cib, void *stream);
+/* small_filter_sums_u8: sums[co] = sum of the codes of output channel co's filter over its whole reduction
+ * (Ci*kh*kw values), from the blocked filter; Co ints. small_conv2d_u8 / small_dense_u8 take it as filt_sums
+ * (16-byte aligned, or NULL): the term zx-dependent part of the sum, (zx - 128) * sum(w - 128), is the same for
+ * every pixel, so a caller that keeps the filter keeps these sums with it; with NULL the kernels take the sums
+ * themselves on every call (same results, more matrix instructions). */
+int small_filter_sums_u8(const unsigned char *filt, int *sums, int Co, int Ci, int kh, int kw, int Cob, int Cib,
+                         void *stream);
 int small_conv2d_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int Ci, int Co, int H,
                     int W, int kh, int kw, int stride, small_pad pad, int Cib, int Cob, const small_quant *q,
-                    void *stream);
+                    const int *filt_sums, void *stream);
 int small_dwconv2d_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int C, int H, int W,
                       int kh, int kw, int stride, small_pad pad, int Cb, const small_quant *q, void *stream);
 int small_dense_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int Ci, int Co, int Cib,
-                   int Cob, const small_quant *q, void *stream);
+                   int Cob, const small_quant *q, const int *filt_sums, void *stream);
 int small_pool2d_u8(const unsigned char *in, unsigned char *out, int N, int C, int H, int W, int kh, int kw, int stride,
                     small_pad pad, int Cb, int mode, void *stream);
 int small_relu_u8(const unsigned char *in, unsigned char *out, size_t n_elems, int z, void *stream);

@@ -22,7 +22,7 @@ _OPS = {"conv": OP_CONV, "dw": OP_DWCONV, "maxpool": OP_MAXPOOL, "avgpool": OP_A
 EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "small_pack_filter",
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
            "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_pack_u8", "small_unpack_u8",
-           "small_pack_filter_u8", "small_conv2d_u8", "small_dwconv2d_u8", "small_dense_u8", "small_pool2d_u8", "small_relu_u8",
+           "small_pack_filter_u8", "small_filter_sums_u8", "small_conv2d_u8", "small_dwconv2d_u8", "small_dense_u8", "small_pool2d_u8", "small_relu_u8",
            "small_network_workspace", "small_network_run", "small_network_launches",
            "small_network_run_range"]
 
@@ -82,9 +82,10 @@ def load():
         "small_pack_u8": (i, [p, p, i, i, i, i, i, p]),
         "small_unpack_u8": (i, [p, p, i, i, i, i, i, p]),
         "small_pack_filter_u8": (i, [p, p, i, i, i, i, i, i, p]),
-        "small_conv2d_u8": (i, [p, p, p, i, i, i, i, i, i, i, i, small_pad, i, i, C.POINTER(small_quant), p]),
+        "small_filter_sums_u8": (i, [p, p, i, i, i, i, i, i, p]),
+        "small_conv2d_u8": (i, [p, p, p, i, i, i, i, i, i, i, i, small_pad, i, i, C.POINTER(small_quant), p, p]),
         "small_dwconv2d_u8": (i, [p, p, p, i, i, i, i, i, i, i, small_pad, i, C.POINTER(small_quant), p]),
-        "small_dense_u8": (i, [p, p, p, i, i, i, i, i, C.POINTER(small_quant), p]),
+        "small_dense_u8": (i, [p, p, p, i, i, i, i, i, C.POINTER(small_quant), p, p]),
         "small_pool2d_u8": (i, [p, p, i, i, i, i, i, i, i, small_pad, i, i, p]),
         "small_relu_u8": (i, [p, p, sz, i, p]),
         "small_network_workspace": (i, [C.POINTER(small_layer), i, i, i, i, i, C.POINTER(sz)]),
@@ -222,9 +223,22 @@ def small_pack_filter_u8(oihw, blocked, Co, Ci, kh, kw, Cob, Cib, stream=None):
            "small_pack_filter_u8")
 
 
-def small_conv2d_u8(inp, filt, out, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob, q, stream=None):
+def _ptr32i(t):
+    if t is None:
+        return None
+    if not (t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise TypeError("expected a contiguous int32 CUDA tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+def small_filter_sums_u8(filt, sums, Co, Ci, kh, kw, Cob, Cib, stream=None):
+    _check(load().small_filter_sums_u8(_ptr8(filt), _ptr32i(sums), Co, Ci, kh, kw, Cob, Cib, _stream(stream)),
+           "small_filter_sums_u8")
+
+
+def small_conv2d_u8(inp, filt, out, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob, q, filt_sums=None, stream=None):
     _check(load().small_conv2d_u8(_ptr8(inp), _ptr8(filt), _ptr8(out), N, Ci, Co, H, W, kh, kw, stride, _pad(pad), Cib, Cob,
-                                  _quant(q), _stream(stream)), "small_conv2d_u8")
+                                  _quant(q), _ptr32i(filt_sums), _stream(stream)), "small_conv2d_u8")
 
 
 def small_dwconv2d_u8(inp, filt, out, N, Cc, H, W, kh, kw, stride, pad, Cb, q, stream=None):
@@ -232,9 +246,9 @@ def small_dwconv2d_u8(inp, filt, out, N, Cc, H, W, kh, kw, stride, pad, Cb, q, s
                                     _quant(q), _stream(stream)), "small_dwconv2d_u8")
 
 
-def small_dense_u8(inp, filt, out, N, Ci, Co, Cib, Cob, q, stream=None):
-    _check(load().small_dense_u8(_ptr8(inp), _ptr8(filt), _ptr8(out), N, Ci, Co, Cib, Cob, _quant(q), _stream(stream)),
-           "small_dense_u8")
+def small_dense_u8(inp, filt, out, N, Ci, Co, Cib, Cob, q, filt_sums=None, stream=None):
+    _check(load().small_dense_u8(_ptr8(inp), _ptr8(filt), _ptr8(out), N, Ci, Co, Cib, Cob, _quant(q), _ptr32i(filt_sums),
+                                 _stream(stream)), "small_dense_u8")
 
 
 def small_pool2d_u8(inp, out, N, Cc, H, W, kh, kw, stride, pad, Cb, mode, stream=None):

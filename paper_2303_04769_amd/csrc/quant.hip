@@ -22,8 +22,19 @@ namespace {
 
 typedef int intx4 __attribute__((ext_vector_type(4)));
 
+// q.amax > 0: sums beyond +-amax saturate the output anyway (|amax * mult / 2^shift| >= 512) and within it the
+// scaled value fits 32 bits, so one clamp of the sum replaces 64-bit compares and selects after the product
+// (the host derives amax; 0 = scale too large for that, take the wide path). Same codes either way.
 __device__ __forceinline__ int requant(int acc, const QuantParams &q)
 {
+    if (q.amax > 0) {
+        const int c = acc < -q.amax ? -q.amax : (acc > q.amax ? q.amax : acc);
+        long v = (long)c * (long)q.mult;
+        if (q.shift > 0) v = (v + (1L << (q.shift - 1))) >> q.shift;
+        int r = (int)v + q.zy;
+        r = r < q.lo ? q.lo : r;
+        return r > q.hi ? q.hi : r;
+    }
     long v = (long)acc * (long)q.mult;
     if (q.shift > 0) v = (v + (1L << (q.shift - 1))) >> q.shift;
     v += q.zy;
@@ -38,8 +49,48 @@ struct QConvArgs {
     int N, H, W, Ho, Wo, HoWo, M;
     int nCib, nCob, Cib, Cob, kh, kw, stride, pt, pl;
     int n_chunks;     // nCib * kh * kw (matrix-core kernel)
+    FastDiv div_HoWo, div_Wo;
+    const int *filt_sums;   // per output channel: sum of the filter's codes over the whole reduction, or null
     QuantParams q;
 };
+
+// Zero-point corrections and requantization of a wave's accumulators, four consecutive output channels
+// (one 32-bit word of the blocked output) per lane and tile. acc_w: sum of the signed filter bytes per channel.
+template <int WM, int WN>
+__device__ __forceinline__ void store_tiles(const QConvArgs &a, const intx4 (&acc)[WM][WN], const intx4 (&acc_s)[WM],
+                                            const intx4 (&acc_w)[WN], int tile0, int cob0, int p, int g)
+{
+    const int za = a.q.zx - 128, zb = a.q.zw - 128;
+    const unsigned K = (unsigned)a.n_chunks * 16u;
+    const unsigned kab = K * (unsigned)(za * zb);
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm) {
+        const int m = tile0 + wm * 16 + p;
+        if (m >= a.M) continue;
+        const int n = a.div_HoWo.div(m), pix = m - n * a.HoWo;
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) {
+            unsigned packed = 0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                // wrap-around arithmetic: the true sum fits 32 bits, the partial terms need not
+                const unsigned v = (unsigned)acc[wm][wn][r] - (unsigned)zb * (unsigned)acc_s[wm][r] -
+                                   (unsigned)za * (unsigned)acc_w[wn][r] + kab;
+                packed |= (unsigned)requant((int)v, a.q) << (8 * r);
+            }
+            unsigned *o = reinterpret_cast<unsigned *>(a.out + (((size_t)n * a.nCob + cob0 + wn) * a.HoWo + pix) * 16 + g * 4);
+            *o = packed;
+        }
+    }
+}
+
+// sum of the signed filter bytes of output channels 4g .. 4g+3 of block cob, from the caller's sums of codes
+__device__ __forceinline__ intx4 signed_filter_sums(const QConvArgs &a, int cob, int g)
+{
+    const intx4 v = *reinterpret_cast<const intx4 *>(a.filt_sums + cob * 16 + 4 * g);
+    const int k128 = a.n_chunks * 16 * 128;
+    return intx4{v[0] - k128, v[1] - k128, v[2] - k128, v[3] - k128};
+}
 
 // ------------------------------------------------------------------------------------------------ layouts
 
@@ -78,6 +129,21 @@ __global__ void __launch_bounds__(256) pack_filter_u8_kernel(const unsigned char
     blk[i] = oihw[(co * Ci + ci) * khw + tap];
 }
 
+// One lane per output channel: the sum of its codes over (input block, tap, input channel).
+__global__ void __launch_bounds__(256) filter_sums_u8_kernel(const unsigned char *blk, int *sums, int Co, int nCib, int khw,
+                                                             int Cob, int Cib)
+{
+    const int co = blockIdx.x * 256 + threadIdx.x;
+    if (co >= Co) return;
+    const int cob = co / Cob, co_in = co - cob * Cob;
+    int sum = 0;
+    for (int c = 0; c < nCib * khw; ++c) {
+        const unsigned char *w = blk + (((size_t)cob * nCib * khw + c) * Cob + co_in) * Cib;
+        for (int i = 0; i < Cib; ++i) sum += w[i];
+    }
+    sums[co] = sum;
+}
+
 // ------------------------------------------------------------------------------------------------ convolution
 
 // Any block sizes: one lane per output code.
@@ -110,7 +176,9 @@ __global__ void __launch_bounds__(256) conv_u8_direct(QConvArgs a, size_t total)
 }
 
 // Each wave: WM groups of 16 output pixels x WN blocks of 16 output channels (blockIdx.y counts groups of WN blocks).
-template <int WM, int WN>
+// CORR: which zero-point correction sums the loop takes with all-ones operands: 0 none, 1 the pixel sums
+// (zw != 128), 2 the pixel sums and the filter sums (zx != 128 and the caller gave no filter sums).
+template <int WM, int WN, int CORR>
 __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -119,7 +187,8 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
     const int tile0 = ((int)blockIdx.x * 4 + wave) * (16 * WM);
     const int HW = a.H * a.W;
     const int za = a.q.zx - 128, zb = a.q.zw - 128;
-    const bool use_s = zb != 0, use_w = za != 0;
+    constexpr bool use_s = CORR >= 1, mfma_w = CORR == 2;
+    const bool use_w = za != 0;
 
     int ih0[WM], iw0[WM];
     size_t img[WM];       // 16-byte pixel index of the image's first block
@@ -127,8 +196,8 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
     for (int wm = 0; wm < WM; ++wm) {
         int m = tile0 + wm * 16 + p;
         m = m < a.M ? m : a.M - 1;
-        const int n = m / a.HoWo, rem = m - n * a.HoWo;
-        const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+        const int n = a.div_HoWo.div(m), rem = m - n * a.HoWo;
+        const int oh = a.div_Wo.div(rem), ow = rem - oh * a.Wo;
         ih0[wm] = oh * a.stride - a.pt;
         iw0[wm] = ow * a.stride - a.pl;
         img[wm] = (size_t)n * a.nCib * HW;
@@ -166,10 +235,10 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
         for (int wm = 0; wm < WM; ++wm) {
             const int ih = ih0[wm] + ky, iw = iw0[wm] + kx;
             const bool inside = live && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-            fb[wm] = intx4{zx4, zx4, zx4, zx4};
-            if (inside) fb[wm] = in[img[wm] + (size_t)cib * HW + ih * a.W + iw];
-            fb[wm] ^= flip;
-            if (!live) fb[wm] = zero;
+            // always a load from a valid address (no branch around it), then the choice
+            const intx4 v = in[inside ? img[wm] + (size_t)cib * HW + ih * a.W + iw : img[wm]];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) fb[wm][k] = live ? (inside ? v[k] ^ flip : zx4 ^ flip) : 0;
         }
         c += 4;
         kx += 4;
@@ -184,7 +253,7 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
                 acc[wm][wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], fb[wm], acc[wm][wn], 0, 0, 0);
             if (use_s) acc_s[wm] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb[wm], acc_s[wm], 0, 0, 0);
         }
-        if (use_w) {
+        if (mfma_w) {
 #pragma unroll
             for (int wn = 0; wn < WN; ++wn) acc_w[wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], ones, acc_w[wn], 0, 0, 0);
         }
@@ -201,34 +270,20 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
         multiply(fa1, fb1);
     }
 
-    // lane (p, g) holds output channels 4g .. 4g+3 of pixel p: four consecutive bytes of the blocked output
-    const unsigned K = (unsigned)a.n_chunks * 16u;
-    const unsigned kab = K * (unsigned)(za * zb);
+    if (use_w && a.filt_sums) {
 #pragma unroll
-    for (int wm = 0; wm < WM; ++wm) {
-        const int m = tile0 + wm * 16 + p;
-        if (m >= a.M) continue;
-        const int n = m / a.HoWo, pix = m - n * a.HoWo;
-#pragma unroll
-        for (int wn = 0; wn < WN; ++wn) {
-            unsigned packed = 0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                // wrap-around arithmetic: the true sum fits 32 bits, the partial terms need not
-                const unsigned v = (unsigned)acc[wm][wn][r] - (unsigned)zb * (unsigned)acc_s[wm][r] -
-                                   (unsigned)za * (unsigned)acc_w[wn][r] + kab;
-                packed |= (unsigned)requant((int)v, a.q) << (8 * r);
-            }
-            unsigned *o = reinterpret_cast<unsigned *>(a.out + (((size_t)n * a.nCob + cob0 + wn) * a.HoWo + pix) * 16 + g * 4);
-            *o = packed;
-        }
+        for (int wn = 0; wn < WN; ++wn) acc_w[wn] = signed_filter_sums(a, cob0 + wn, g);
     }
+    store_tiles<WM, WN>(a, acc, acc_s, acc_w, tile0, cob0, p, g);
 }
 
 // The same tile for layers whose input has a multiple of four 16-channel blocks: one matrix instruction takes one
 // filter tap of four consecutive input blocks (lane group g = block 4j + g), so the tap, its bounds test and the
-// operand addresses are per-tap values and the walk over j only adds constants.
-template <int WM, int WN>
+// operand addresses are per-tap values and the walk over j only adds constants. Steps (tap, j) run through a ring
+// of DEPTH register sets: the loads of step s + DEPTH - 1 are issued before step s multiplies, every load is
+// unconditional (out-of-image taps read the image's first pixel and are replaced afterwards), so a wave keeps
+// DEPTH - 1 steps of operands in flight instead of waiting for each step's loads in turn.
+template <int WM, int WN, int CORR, int DEPTH>
 __global__ void __launch_bounds__(256) conv_u8_mfma4(QConvArgs a)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -236,8 +291,9 @@ __global__ void __launch_bounds__(256) conv_u8_mfma4(QConvArgs a)
     const int cob0 = blockIdx.y * WN;
     const int tile0 = ((int)blockIdx.x * 4 + wave) * (16 * WM);
     const int HW = a.H * a.W;
-    const int za = a.q.zx - 128, zb = a.q.zw - 128;
-    const bool use_s = zb != 0, use_w = za != 0;
+    const int za = a.q.zx - 128;
+    constexpr bool use_s = CORR >= 1, mfma_w = CORR == 2;
+    const bool use_w = za != 0;
     const int taps = a.kh * a.kw;
 
     int ih0[WM], iw0[WM];
@@ -246,8 +302,8 @@ __global__ void __launch_bounds__(256) conv_u8_mfma4(QConvArgs a)
     for (int wm = 0; wm < WM; ++wm) {
         int m = tile0 + wm * 16 + p;
         m = m < a.M ? m : a.M - 1;
-        const int n = m / a.HoWo, rem = m - n * a.HoWo;
-        const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+        const int n = a.div_HoWo.div(m), rem = m - n * a.HoWo;
+        const int oh = a.div_Wo.div(rem), ow = rem - oh * a.Wo;
         ih0[wm] = oh * a.stride - a.pt;
         iw0[wm] = ow * a.stride - a.pl;
         img[wm] = reinterpret_cast<const intx4 *>(a.in) + ((size_t)n * a.nCib + g) * HW;
@@ -256,10 +312,9 @@ __global__ void __launch_bounds__(256) conv_u8_mfma4(QConvArgs a)
     const intx4 *filt = reinterpret_cast<const intx4 *>(a.filt) + ((size_t)cob0 * a.n_chunks + (size_t)g * taps) * 16 + p;
     const size_t cob_stride = (size_t)a.n_chunks * 16;
     const int flip = (int)0x80808080u;
-    const int zx4 = a.q.zx * 0x01010101;
+    const int pad = (a.q.zx * 0x01010101) ^ flip;
     const intx4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
     const intx4 zero = {0, 0, 0, 0};
-    const intx4 pad = {zx4 ^ flip, zx4 ^ flip, zx4 ^ flip, zx4 ^ flip};
 
     intx4 acc[WM][WN], acc_s[WM], acc_w[WN];
 #pragma unroll
@@ -272,64 +327,79 @@ __global__ void __launch_bounds__(256) conv_u8_mfma4(QConvArgs a)
     for (int wn = 0; wn < WN; ++wn) acc_w[wn] = zero;
 
     const int groups = a.nCib >> 2;
-    int ky = 0, kx = 0;
-    for (int tap = 0; tap < taps; ++tap) {
-        const intx4 *bp[WM];
-        bool inside[WM];
+    const int total = taps * groups;
+    // request cursor
+    int r_s = 0, r_j = 0, r_ky = 0, r_kx = 0, r_tap = 0;
+    const intx4 *bp[WM], *ap = filt;
+    int inside[WM];
+    auto enter_tap = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int wm = 0; wm < WM; ++wm) {
-            const int ih = ih0[wm] + ky, iw = iw0[wm] + kx;
+            const int ih = ih0[wm] + r_ky, iw = iw0[wm] + r_kx;
             inside[wm] = ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
             bp[wm] = img[wm] + (inside[wm] ? ih * a.W + iw : 0);
         }
-        const intx4 *ap = filt + (size_t)tap * 16;
-        for (int j = 0; j < groups; ++j) {
-            intx4 fa[WN], fb[WM];
+        ap = filt + (size_t)r_tap * 16;
+    };
+    intx4 ra[DEPTH][WN], rb[DEPTH][WM];
+    int rin[DEPTH][WM];
+    auto request = [&](int d) __attribute__((always_inline)) {
+        if (r_s >= total) return;
 #pragma unroll
-            for (int wn = 0; wn < WN; ++wn) fa[wn] = ap[wn * cob_stride] ^ flip;
+        for (int wn = 0; wn < WN; ++wn) ra[d][wn] = ap[wn * cob_stride];
 #pragma unroll
-            for (int wm = 0; wm < WM; ++wm) {
-                fb[wm] = pad;
-                if (inside[wm]) fb[wm] = *bp[wm] ^ flip;
-                bp[wm] += (size_t)4 * HW;
-            }
-            ap += (size_t)4 * taps * 16;
+        for (int wm = 0; wm < WM; ++wm) {
+            rb[d][wm] = *bp[wm];
+            rin[d][wm] = inside[wm];
+            bp[wm] += (size_t)4 * HW;
+        }
+        ap += (size_t)4 * taps * 16;
+        ++r_s;
+        if (++r_j == groups) {
+            r_j = 0;
+            ++r_tap;
+            if (++r_kx == a.kw) { r_kx = 0; ++r_ky; }
+            enter_tap();
+        }
+    };
+    enter_tap();
 #pragma unroll
-            for (int wm = 0; wm < WM; ++wm) {
+    for (int d = 0; d < DEPTH - 1; ++d) request(d);
+
+    for (int s0 = 0; s0 < total; s0 += DEPTH) {
 #pragma unroll
-                for (int wn = 0; wn < WN; ++wn)
-                    acc[wm][wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], fb[wm], acc[wm][wn], 0, 0, 0);
-                if (use_s) acc_s[wm] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb[wm], acc_s[wm], 0, 0, 0);
-            }
-            if (use_w) {
+        for (int d = 0; d < DEPTH; ++d) {
+            if (s0 + d < total) {
+                request((d + DEPTH - 1) % DEPTH);      // the set used in the step before this one
+                intx4 fa[WN], fb[WM];
 #pragma unroll
-                for (int wn = 0; wn < WN; ++wn)
-                    acc_w[wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], ones, acc_w[wn], 0, 0, 0);
+                for (int wn = 0; wn < WN; ++wn) fa[wn] = ra[d][wn] ^ flip;
+#pragma unroll
+                for (int wm = 0; wm < WM; ++wm) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) fb[wm][k] = rin[d][wm] ? rb[d][wm][k] ^ flip : pad;
+                }
+#pragma unroll
+                for (int wm = 0; wm < WM; ++wm) {
+#pragma unroll
+                    for (int wn = 0; wn < WN; ++wn)
+                        acc[wm][wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], fb[wm], acc[wm][wn], 0, 0, 0);
+                    if (use_s) acc_s[wm] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb[wm], acc_s[wm], 0, 0, 0);
+                }
+                if (mfma_w) {
+#pragma unroll
+                    for (int wn = 0; wn < WN; ++wn)
+                        acc_w[wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], ones, acc_w[wn], 0, 0, 0);
+                }
             }
         }
-        if (++kx == a.kw) { kx = 0; ++ky; }
     }
 
-    const unsigned K = (unsigned)a.n_chunks * 16u;
-    const unsigned kab = K * (unsigned)(za * zb);
+    if (use_w && a.filt_sums) {
 #pragma unroll
-    for (int wm = 0; wm < WM; ++wm) {
-        const int m = tile0 + wm * 16 + p;
-        if (m >= a.M) continue;
-        const int n = m / a.HoWo, pix = m - n * a.HoWo;
-#pragma unroll
-        for (int wn = 0; wn < WN; ++wn) {
-            unsigned packed = 0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const unsigned v = (unsigned)acc[wm][wn][r] - (unsigned)zb * (unsigned)acc_s[wm][r] -
-                                   (unsigned)za * (unsigned)acc_w[wn][r] + kab;
-                packed |= (unsigned)requant((int)v, a.q) << (8 * r);
-            }
-            unsigned *o = reinterpret_cast<unsigned *>(a.out + (((size_t)n * a.nCob + cob0 + wn) * a.HoWo + pix) * 16 + g * 4);
-            *o = packed;
-        }
+        for (int wn = 0; wn < WN; ++wn) acc_w[wn] = signed_filter_sums(a, cob0 + wn, g);
     }
+    store_tiles<WM, WN>(a, acc, acc_s, acc_w, tile0, cob0, p, g);
 }
 
 // ------------------------------------------------------------------------------------------------ single channel
@@ -339,6 +409,7 @@ struct QWindowArgs {
     unsigned char *out;
     int N, H, W, Ho, Wo, nCb, Cb, kh, kw, stride, pt, pl;
     int mode;   // 0 depthwise, 1 max, 2 average
+    FastDiv div_groups, div_Wo, div_Ho, div_nCb;
     QuantParams q;
 };
 
@@ -348,14 +419,15 @@ __global__ void __launch_bounds__(256) window_u8(QWindowArgs a, size_t total)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // index of a VEC-channel group of the blocked output
     if (i >= total) return;
+    // i < 2^31 (the host checks the tensor size): divisions by launch constants
     const int groups = a.Cb / VEC;
-    const int cg = (int)(i % groups);
-    size_t t = i / groups;
-    const int ow = (int)(t % a.Wo);
-    t /= a.Wo;
-    const int oh = (int)(t % a.Ho);
-    t /= a.Ho;   // n * nCb + cb
-    const int cb = (int)(t % a.nCb);
+    int t = a.div_groups.div((int)i);
+    const int cg = (int)i - t * groups;
+    int t2 = a.div_Wo.div(t);
+    const int ow = t - t2 * a.Wo;
+    t = a.div_Ho.div(t2);   // n * nCb + cb
+    const int oh = t2 - t * a.Ho;
+    const int cb = t - a.div_nCb.div(t) * a.nCb;
     int acc[VEC], cnt = 0;
 #pragma unroll
     for (int v = 0; v < VEC; ++v) acc[v] = 0;
@@ -365,7 +437,7 @@ __global__ void __launch_bounds__(256) window_u8(QWindowArgs a, size_t total)
         for (int kx = 0; kx < a.kw; ++kx) {
             const int iw = ow * a.stride + kx - a.pl;
             if (iw < 0 || iw >= a.W) continue;
-            const unsigned char *x = a.in + ((t * a.H + ih) * a.W + iw) * a.Cb + cg * VEC;
+            const unsigned char *x = a.in + (((size_t)t * a.H + ih) * a.W + iw) * a.Cb + cg * VEC;
             int xv[VEC], wv[VEC];
             if (VEC == 4) {
                 const unsigned xw = *reinterpret_cast<const unsigned *>(x);
@@ -432,19 +504,17 @@ __global__ void __launch_bounds__(256) relu_u8_words(const unsigned *in, unsigne
 inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 
 // Pixel groups (wm) and output blocks (wn) per wave: an input operand serves wn matrix instructions and a filter
-// operand wm of them. Four output blocks and two pixel groups measured best at the sweep shapes; smaller tiles
-// when the grid would otherwise have fewer than two workgroups per compute unit.
-void pick_conv_tile(int M, int nCob, int &wm, int &wn)
+// operand wm of them, and the sign flips of both cost vector instructions, which is what bounds these kernels:
+// two pixel groups and as many output blocks (up to four) as divide the layer measured best at the sweep shapes,
+// also where that leaves fewer workgroups than compute units.
+void pick_conv_tile(int nCob, int &wm, int &wn)
 {
-    wn = nCob % 4 == 0 ? 4 : (nCob % 2 == 0 ? 2 : 1);
     wm = 2;
-    auto wgs = [&](int m, int n) { return ((long)M + 64 * m - 1) / (64 * m) * (nCob / n); };
-    if (wgs(wm, wn) < 512) wm = 1;
-    if (wgs(wm, wn) < 512 && wn == 4) wn = 2;
+    wn = nCob % 4 == 0 ? 4 : (nCob % 2 == 0 ? 2 : 1);
 }
 
 QConvArgs conv_args(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
-                    const QuantParams &q)
+                    const QuantParams &q, const int *filt_sums)
 {
     QConvArgs a;
     a.in = in; a.filt = filt; a.out = out;
@@ -452,6 +522,9 @@ QConvArgs conv_args(const unsigned char *in, const unsigned char *filt, unsigned
     a.nCib = g.Ci / g.Cib; a.nCob = g.Co / g.Cob; a.Cib = g.Cib; a.Cob = g.Cob;
     a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pt = g.pt; a.pl = g.pl;
     a.n_chunks = a.nCib * g.kh * g.kw;
+    a.div_HoWo = make_fastdiv(a.HoWo);
+    a.div_Wo = make_fastdiv(g.Wo);
+    a.filt_sums = filt_sums;
     a.q = q;
     return a;
 }
@@ -474,6 +547,14 @@ hipError_t launch_pack_filter_u8(const unsigned char *oihw, unsigned char *blk, 
     return hipGetLastError();
 }
 
+hipError_t launch_filter_sums_u8(const unsigned char *filt, int *sums, int Co, int Ci, int kh, int kw, int Cob, int Cib,
+                                 hipStream_t s)
+{
+    hipLaunchKernelGGL(filter_sums_u8_kernel, dim3(blocks_for((size_t)Co)), dim3(256), 0, s, filt, sums, Co, Ci / Cib, kh * kw,
+                       Cob, Cib);
+    return hipGetLastError();
+}
+
 bool conv_u8_uses_mfma(const LayerGeom &g, const void *in, const void *filt, const void *out)
 {
     const bool aligned = ((((uintptr_t)in | (uintptr_t)filt) & 15u) == 0) && (((uintptr_t)out & 3u) == 0);
@@ -481,20 +562,22 @@ bool conv_u8_uses_mfma(const LayerGeom &g, const void *in, const void *filt, con
 }
 
 hipError_t launch_conv_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
-                          const QuantParams &q, hipStream_t s)
+                          const QuantParams &q, const int *filt_sums, hipStream_t s)
 {
-    const QConvArgs a = conv_args(in, filt, out, g, q);
+    const QConvArgs a = conv_args(in, filt, out, g, q, filt_sums);
     if (conv_u8_uses_mfma(g, in, filt, out)) {
         int wm = 4, wn = 4;
-        pick_conv_tile(a.M, a.nCob, wm, wn);
+        pick_conv_tile(a.nCob, wm, wn);
         const dim3 grid((unsigned)((a.M + 64 * wm - 1) / (64 * wm)), (unsigned)(a.nCob / wn));
-#define SMALL_U8_CASE(M_, N_)                                                                         \
-    if (wm == M_ && wn == N_) {                                                                       \
-        if (a.nCib % 4 == 0) hipLaunchKernelGGL((conv_u8_mfma4<M_, N_>), grid, dim3(256), 0, s, a);   \
-        else hipLaunchKernelGGL((conv_u8_mfma<M_, N_>), grid, dim3(256), 0, s, a);                    \
+        const int corr = (q.zx != 128 && !filt_sums) ? 2 : (q.zw != 128 ? 1 : 0);
+#define SMALL_U8_CASE(M_, N_, C_)                                                                            \
+    if (wm == M_ && wn == N_ && corr == C_) {                                                                \
+        if (a.nCib % 4 == 0) hipLaunchKernelGGL((conv_u8_mfma4<M_, N_, C_, 3>), grid, dim3(256), 0, s, a);   \
+        else hipLaunchKernelGGL((conv_u8_mfma<M_, N_, C_>), grid, dim3(256), 0, s, a);                       \
     }
-        SMALL_U8_CASE(2, 4); SMALL_U8_CASE(2, 2); SMALL_U8_CASE(2, 1);
-        SMALL_U8_CASE(1, 4); SMALL_U8_CASE(1, 2); SMALL_U8_CASE(1, 1);
+#define SMALL_U8_TILE(M_, N_) SMALL_U8_CASE(M_, N_, 0) SMALL_U8_CASE(M_, N_, 1) SMALL_U8_CASE(M_, N_, 2)
+        SMALL_U8_TILE(2, 4) SMALL_U8_TILE(2, 2) SMALL_U8_TILE(2, 1)
+#undef SMALL_U8_TILE
 #undef SMALL_U8_CASE
         return hipGetLastError();
     }
@@ -513,6 +596,11 @@ hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, 
     a.mode = mode;
     a.q = q;
     const size_t n_out = (size_t)g.N * g.Ci * g.Ho * g.Wo;
+    const bool words4 = g.Cib % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)(filt ? filt : in)) & 3u) == 0);
+    a.div_groups = make_fastdiv(words4 ? g.Cib / 4 : g.Cib);
+    a.div_Wo = make_fastdiv(g.Wo);
+    a.div_Ho = make_fastdiv(g.Ho);
+    a.div_nCb = make_fastdiv(a.nCb);
     const bool words = g.Cib % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)(filt ? filt : in)) & 3u) == 0);
     if (words) hipLaunchKernelGGL((window_u8<4>), dim3(blocks_for(n_out / 4)), dim3(256), 0, s, a, n_out / 4);
     else hipLaunchKernelGGL((window_u8<1>), dim3(blocks_for(n_out)), dim3(256), 0, s, a, n_out);

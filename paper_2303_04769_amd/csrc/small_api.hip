@@ -280,7 +280,18 @@ int check_quant(const small_quant *q, long K, QuantParams &out)
     if (q->mult < 0 || q->shift < 0 || q->shift > 31) return SMALL_ERR_QUANT;
     if (q->lo < 0 || q->hi > 255 || q->lo > q->hi) return SMALL_ERR_QUANT;
     if (K <= 0 || K * 255L * 255L >= (1L << 31)) return SMALL_ERR_QUANT;
-    out = QuantParams{q->zx, q->zw, q->zy, q->mult, q->shift, q->lo, q->hi};
+    // Sums beyond +-amax saturate the output whatever they are (amax * mult / 2^shift >= 512 > 255 + 255), and
+    // up to amax the scaled sum fits 32 bits: the kernels then clamp the sum first and work in 32 bits.
+    int amax = 0;
+    if (q->mult == 0) {
+        amax = INT_MAX;
+    } else {
+        const __int128 num = (__int128)512 << q->shift;
+        const __int128 need = (num + q->mult - 1) / q->mult;
+        if (need > INT_MAX) amax = INT_MAX;
+        else if (need * q->mult < ((__int128)((1LL << 31) - 1024) << q->shift)) amax = (int)need;
+    }
+    out = QuantParams{q->zx, q->zw, q->zy, q->mult, q->shift, q->lo, q->hi, amax};
     return SMALL_OK;
 }
 
@@ -320,9 +331,21 @@ int small_pack_filter_u8(const unsigned char *oihw, unsigned char *blocked, int 
     return from_hip(launch_pack_filter_u8(oihw, blocked, Co, Ci, kh, kw, Cob, Cib, as_stream(stream)));
 }
 
+int small_filter_sums_u8(const unsigned char *filt, int *sums, int Co, int Ci, int kh, int kw, int Cob, int Cib, void *stream)
+{
+    if (!filt || !sums) return SMALL_ERR_NULL;
+    if (int rc = check_block(Co, Cob)) return rc;
+    if (int rc = check_block(Ci, Cib)) return rc;
+    const size_t n = elems(Co, Ci, kh, kw);
+    if (!n) return SMALL_ERR_SHAPE;
+    if ((long)Ci * kh * kw * 255L >= (1L << 31)) return SMALL_ERR_QUANT;
+    if (overlap_bytes(filt, n, sums, (size_t)Co * sizeof(int))) return SMALL_ERR_ALIAS;
+    return from_hip(launch_filter_sums_u8(filt, sums, Co, Ci, kh, kw, Cob, Cib, as_stream(stream)));
+}
+
 int small_conv2d_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int Ci, int Co, int H,
                     int W, int kh, int kw, int stride, small_pad pad, int Cib, int Cob, const small_quant *q,
-                    void *stream)
+                    const int *filt_sums, void *stream)
 {
     ConvPlan p;
     if (int rc = plan_conv(p, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob)) return rc;
@@ -331,14 +354,18 @@ int small_conv2d_u8(const unsigned char *in, const unsigned char *filt, unsigned
     if (!in || !filt || !out) return SMALL_ERR_NULL;
     if (overlap_bytes(in, p.in_elems, out, p.out_elems) || overlap_bytes(filt, p.filt_elems, out, p.out_elems))
         return SMALL_ERR_ALIAS;
-    return from_hip(launch_conv_u8(in, filt, out, p.g, qp, as_stream(stream)));
+    if (filt_sums) {
+        if ((uintptr_t)filt_sums & 15u) return SMALL_ERR_SHAPE;
+        if (overlap_bytes(filt_sums, (size_t)Co * sizeof(int), out, p.out_elems)) return SMALL_ERR_ALIAS;
+    }
+    return from_hip(launch_conv_u8(in, filt, out, p.g, qp, filt_sums, as_stream(stream)));
 }
 
 int small_dense_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int Ci, int Co, int Cib,
-                   int Cob, const small_quant *q, void *stream)
+                   int Cob, const small_quant *q, const int *filt_sums, void *stream)
 {
     const small_pad nopad = {0, 0, 0, 0};
-    return small_conv2d_u8(in, filt, out, N, Ci, Co, 1, 1, 1, 1, 1, nopad, Cib, Cob, q, stream);
+    return small_conv2d_u8(in, filt, out, N, Ci, Co, 1, 1, 1, 1, 1, nopad, Cib, Cob, q, filt_sums, stream);
 }
 
 int small_dwconv2d_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, int N, int C, int H, int W,
@@ -366,7 +393,7 @@ int small_pool2d_u8(const unsigned char *in, unsigned char *out, int N, int C, i
     if ((long)kh * kw * 255L >= (1L << 31)) return SMALL_ERR_SHAPE;
     if (!in || !out) return SMALL_ERR_NULL;
     if (overlap_bytes(in, ni, out, no)) return SMALL_ERR_ALIAS;
-    const QuantParams none = {0, 0, 0, 0, 0, 0, 255};
+    const QuantParams none = {0, 0, 0, 0, 0, 0, 255, 0};
     return from_hip(launch_window_u8(in, nullptr, out, g, mode == SMALL_POOL_MAX ? 1 : 2, none, as_stream(stream)));
 }
 

@@ -133,15 +133,20 @@ hipError_t launch_group_conv(const float *in, const float *filt, float *out, con
 
 // Quantized (uint8) layers (quant.hip). acc = sum over in-image taps of (x - zx)(w - zw) in int32;
 // y = clamp(zy + ((int64)acc * mult + 2^(shift-1)) >> shift, lo, hi) (no rounding term when shift == 0).
-struct QuantParams { int zx, zw, zy, mult, shift, lo, hi; };
+// amax: host-derived clamp of the sum that makes the 32-bit requantization path exact (0 = not available).
+struct QuantParams { int zx, zw, zy, mult, shift, lo, hi, amax; };
 hipError_t launch_pack_u8(const unsigned char *nchw, unsigned char *blk, int N, int C, int H, int W, int Cb, bool unpack,
                           hipStream_t s);
 hipError_t launch_pack_filter_u8(const unsigned char *oihw, unsigned char *blk, int Co, int Ci, int kh, int kw, int Cob,
                                  int Cib, hipStream_t s);
 // true when the 8-bit matrix-core kernel takes the layer (16-byte blocks, aligned pointers), else one lane per output
 bool conv_u8_uses_mfma(const LayerGeom &g, const void *in, const void *filt, const void *out);
+// filt_sums: per output channel the sum of the filter's codes over its whole reduction (launch_filter_sums_u8), or
+// null: the kernels then take these sums themselves, with one more matrix instruction per filter operand.
 hipError_t launch_conv_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
-                          const QuantParams &q, hipStream_t s);
+                          const QuantParams &q, const int *filt_sums, hipStream_t s);
+hipError_t launch_filter_sums_u8(const unsigned char *filt, int *sums, int Co, int Ci, int kh, int kw, int Cob, int Cib,
+                                 hipStream_t s);
 // mode 0: depthwise (filt [C/Cb][kh][kw][Cb]), 1: max pooling, 2: average pooling (filt unused, may be null)
 hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
                             int mode, const QuantParams &q, hipStream_t s);

@@ -24,7 +24,7 @@ def _declared():
 def test_every_declared_symbol_is_exported(lib):
     from paper_2303_04769_amd import binding
     names = _declared()
-    assert len(names) == 28 and set(names) == set(binding.EXPORTS)
+    assert len(names) == 29 and set(names) == set(binding.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -55,12 +55,13 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     far = C.c_void_p(0x10000000)
     ok = small_quant(128, 128, 128, 1 << 20, 30, 0, 255)
     q = lambda **k: C.byref(small_quant(*[k.get(f, getattr(ok, f)) for f, _ in small_quant._fields_]))
-    conv = lambda qq, Ci=16, k=3: lib.small_conv2d_u8(fake, fake, far, 1, Ci, 16, 8, 8, k, k, 1, pad, 16, 16, qq, None)
+    conv = lambda qq, Ci=16, k=3: lib.small_conv2d_u8(fake, fake, far, 1, Ci, 16, 8, 8, k, k, 1, pad, 16, 16, qq, None, None)
     assert conv(None) == 1
     assert conv(q(zx=256)) == 8 and conv(q(zw=-1)) == 8 and conv(q(shift=32)) == 8 and conv(q(mult=-1)) == 8
     assert conv(q(lo=200, hi=100)) == 8 and conv(q(hi=256)) == 8
     assert conv(C.byref(ok), Ci=3680) == 8            # K = 33120: K * 255^2 >= 2^31
-    assert lib.small_conv2d_u8(fake, fake, fake, 1, 16, 16, 8, 8, 3, 3, 1, pad, 16, 16, C.byref(ok), None) == 4
+    assert lib.small_conv2d_u8(fake, fake, fake, 1, 16, 16, 8, 8, 3, 3, 1, pad, 16, 16, C.byref(ok), None, None) == 4
+    assert lib.small_conv2d_u8(fake, fake, far, 1, 16, 16, 8, 8, 3, 3, 1, pad, 16, 16, C.byref(ok), C.c_void_p(0x2004), None) == 2
     assert lib.small_relu_u8(fake, far, 16, 256, None) == 2
     assert lib.small_pool2d_u8(fake, far, 1, 16, 8, 8, 3, 3, 1, pad, 16, 5, None) == 2
 

@@ -61,13 +61,21 @@ def test_pack_filter(Co, Ci, kh, kw, Cob, Cib):
     assert np.array_equal(g.check(), Q.pack_filter(w, Cob, Cib))
 
 
-def _conv(x, w, stride, pad, q, Cib, Cob):
+def _conv(x, w, stride, pad, q, Cib, Cob, with_sums=False):
+    """with_sums: the per-channel sums of the filter's codes come from small_filter_sums_u8 instead of being taken
+    inside the convolution."""
     N, Ci, H, W = x.shape
     Co, _, kh, kw = w.shape
     Ho, Wo = Q.out_dim(H, kh, stride, pad[0], pad[1]), Q.out_dim(W, kw, stride, pad[2], pad[3])
     g = Guarded8(N * Co * Ho * Wo)
-    S.small_conv2d_u8(dev8(Q.pack(x, Cib)), dev8(Q.pack_filter(w, Cob, Cib)), g.t, N, Ci, Co, H, W, kh, kw, stride, pad,
-                      Cib, Cob, q)
+    wb = dev8(Q.pack_filter(w, Cob, Cib))
+    sums = None
+    if with_sums:
+        sums = torch.full((Co,), -1, dtype=torch.int32, device=DEV)
+        S.small_filter_sums_u8(wb, sums, Co, Ci, kh, kw, Cob, Cib)
+        torch.cuda.synchronize()
+        assert np.array_equal(sums.cpu().numpy(), w.reshape(Co, -1).astype(np.int64).sum(axis=1))
+    S.small_conv2d_u8(dev8(Q.pack(x, Cib)), wb, g.t, N, Ci, Co, H, W, kh, kw, stride, pad, Cib, Cob, q, sums)
     return Q.unpack(g.check(), (N, Co, Ho, Wo), Cob)
 
 
@@ -93,6 +101,7 @@ def test_conv_matrix_core(case):
     q = _quant_for(Q.conv2d_acc(x, w, s, pad, zx, zw), zx, zw, relu)
     ref = Q.conv2d(x, w, s, pad, q)
     _same(_conv(x, w, s, pad, q, 16, 16), ref, f"conv u8 {case}")
+    _same(_conv(x, w, s, pad, q, 16, 16, with_sums=True), ref, f"conv u8 with filter sums {case}")
     assert ref.std() > 1.5 and len(np.unique(ref)) > 8
 
 
@@ -127,6 +136,11 @@ def test_requantization_corner_parameters():
     g = Guarded8(9 * 16)
     S.small_dense_u8(dev8(Q.pack(xd, 16)), dev8(Q.pack_filter(wd, 16, 16)), g.t, 9, 32, 16, 16, 16, q)
     _same(Q.unpack(g.check(), (9, 16, 1, 1), 16), Q.dense(xd, wd, q), "dense u8")
+    # a scale too large for the 32-bit requantization path (one step of the sum is 2^20 codes): wide path
+    q = _quant(144, 128, 128, mult=1 << 30, shift=10)
+    _same(_conv(x, w, 1, (1, 1, 1, 1), q, 16, 16), Q.conv2d(x, w, 1, (1, 1, 1, 1), q), "requant wide path")
+    q = _quant(144, 128, 128, mult=(1 << 31) - 1, shift=0, zy=7)
+    _same(_conv(x, w, 1, (1, 1, 1, 1), q, 16, 16), Q.conv2d(x, w, 1, (1, 1, 1, 1), q), "requant largest scale")
 
 
 def test_conv_full_size_sampled():
@@ -137,6 +151,8 @@ def test_conv_full_size_sampled():
     x, w = WL.u8_codes(r, (N, C, H, H)), WL.u8_codes(r, (C, C, 3, 3))
     q = _quant(C * 9, 121, 135, relu=True)
     got = _conv(x, w, 1, (1, 1, 1, 1), q, 16, 16)
+    got2 = _conv(x, w, 1, (1, 1, 1, 1), q, 16, 16, with_sums=True)
+    assert np.array_equal(got, got2)
     for n in (0, 31, N - 1):
         _same(got[n:n + 1], Q.conv2d(x[n:n + 1], w, 1, (1, 1, 1, 1), q), f"conv u8 64x64x56x56 image {n}")
 
