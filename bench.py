@@ -193,6 +193,14 @@ def main():
         "launches_per_step": len(heads) + 2,
     }
 
+    # ------------------------------------------------------------------ what this machine sustains
+    peaks = measured_peaks(S, torch, dev, timed)
+    result["measured_peaks"] = peaks
+    if roofline["bound"] == "mfma":
+        roofline["frac_of_measured_peak"] = round(roofline["achieved"] / peaks["mfma_f32_tflops"], 4)
+    else:
+        roofline["frac_of_measured_peak"] = round(roofline["achieved"] / peaks["hbm_copy_gbs"], 4)
+
     # ------------------------------------------------------------------ roofline layer sweep
     if not args.no_sweep:
         result["sweep"] = sweep(S, WL, torch, np, dev, timed)
@@ -242,6 +250,31 @@ def spin(fn, seconds=0.12):
             fn(r)
             r += 1
         torch.cuda.synchronize()
+
+
+def measured_peaks(S, torch, dev, timed):
+    """Reference points measured in this run: a register-resident loop of fp32 matrix instructions
+    (small_probe_mfma) and a plain device-to-device copy of 1 GiB (2 GiB of traffic), next to the published
+    157.3 TFLOP/s and 8 TB/s the fractions are quoted against."""
+    wgs, iters = 256 * 8, 4096
+    out = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
+    fn = lambda r: S.small_probe_mfma(out, wgs, iters)
+    spin(fn)
+    t = min(timed(fn, 10) for _ in range(3))
+    mfma = wgs * 4 * iters * 8 * 2048.0 / t / 1e12
+    n = 1 << 28                                              # 1 GiB of floats
+    src = torch.empty(n, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    fc = lambda r: dst.copy_(src)
+    spin(fc)
+    tc = min(timed(fc, 10) for _ in range(3))
+    fr = lambda r: S.small_relu(src, dst, n)
+    spin(fr)
+    tr = min(timed(fr, 10) for _ in range(3))
+    del src, dst
+    return {"mfma_f32_tflops": round(mfma, 1), "hbm_copy_gbs": round(8.0 * n / tc / 1e9, 1),
+            "hbm_relu_gbs": round(8.0 * n / tr / 1e9, 1),
+            "note": "small_probe_mfma (register-resident 16x16x4 fp32 MFMA loop); torch copy_ and small_relu over 1 GiB in + 1 GiB out"}
 
 
 def _traffic(kernel):
@@ -305,10 +338,13 @@ def sweep(S, WL, torch, np, dev, timed, only=None):
             wd = torch.from_numpy(WL.uniform_pm1(rng, (C * 9,))).to(dev)
             fn = lambda r: S.small_dwconv2d(ins[r % sets], wd, outs[r % sets], Nb, C, H, H, 3, 3, 1, (1, 1, 1, 1), 16)
             tmin, tmed = best_of(fn, 100)
+            # the same layer on one buffer pair: the tensors then stay in the 256 MB Infinity Cache (not an HBM figure)
+            twarm, _ = best_of(lambda r: S.small_dwconv2d(ins[0], wd, outs[0], Nb, C, H, H, 3, 3, 1, (1, 1, 1, 1), 16), 100)
             byts = 4.0 * (2 * n_act + 9 * C)
             rows.append({"layer": "dw3x3", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
                          "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
-                         "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": sets})
+                         "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": sets,
+                         "us_cache_warm": round(twarm * 1e6, 2), "gbs_cache_warm": round(byts / twarm / 1e9, 1)})
         del ins, outs
     C, H = WL.sweep_shapes()["pool_relu"]
     n_act = Nb * C * H * H

@@ -129,6 +129,12 @@ int small_upsample(const float *in, float *out, int N, int C, int H, int W, int 
 int small_group_conv2d(const float *in, const float *filt, float *out, int N, int Ci, int F_C, int S_C, int K, int H, int W,
                        int kh, int kw, int stride, small_pad pad, int Cib, int F_Cb, int Cob, void *stream);
 
+/* ---- measurement aid, not a layer: the fp32 matrix rate the chip sustains, for quoting roofline fractions against
+ * a measured peak as well as the published one. Launches `workgroups` x 4 wavefronts, each running `iters` rounds
+ * of eight independent 16x16x4 fp32 matrix instructions on registers (2048 flop per instruction and wavefront:
+ * workgroups * 4 * iters * 8 * 2048 flop in all); out receives workgroups * 256 floats (checksums). */
+int small_probe_mfma(float *out, int workgroups, int iters, void *stream);
+
 /* ---- quantized layers: uint8 codes in and out, int32 sums (Section "Memory Usage Comparison": inputs and
  * outputs of the quantized models are uint8, partial results are accumulated in int32; Section "Quantized
  * Inference"). The paper gives no rule for turning the sum back into a code; this library uses the usual

@@ -21,7 +21,7 @@ _OPS = {"conv": OP_CONV, "dw": OP_DWCONV, "maxpool": OP_MAXPOOL, "avgpool": OP_A
 
 EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "small_pack_filter",
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
-           "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_pack_u8", "small_unpack_u8",
+           "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_probe_mfma", "small_pack_u8", "small_unpack_u8",
            "small_pack_filter_u8", "small_filter_sums_u8", "small_conv2d_u8", "small_dwconv2d_u8", "small_dense_u8", "small_pool2d_u8", "small_relu_u8",
            "small_network_workspace", "small_network_run", "small_network_launches",
            "small_network_run_range"]
@@ -79,6 +79,7 @@ def load():
         "small_batchnorm": (i, [p, p, p, p, i, i, i, i, i, p]),
         "small_upsample": (i, [p, p, i, i, i, i, i, i, i, p]),
         "small_group_conv2d": (i, [p, p, p, i, i, i, i, i, i, i, i, i, i, small_pad, i, i, i, p]),
+        "small_probe_mfma": (i, [p, i, i, p]),
         "small_pack_u8": (i, [p, p, i, i, i, i, i, p]),
         "small_unpack_u8": (i, [p, p, i, i, i, i, i, p]),
         "small_pack_filter_u8": (i, [p, p, i, i, i, i, i, i, p]),
@@ -193,6 +194,10 @@ def small_upsample(inp, out, N, Cc, H, W, fh, fw, Cb, stream=None):
 def small_group_conv2d(inp, filt, out, N, Ci, F_C, S_C, K, H, W, kh, kw, stride, pad, Cib, F_Cb, Cob, stream=None):
     _check(load().small_group_conv2d(_ptr(inp), _ptr(filt), _ptr(out), N, Ci, F_C, S_C, K, H, W, kh, kw, stride, _pad(pad),
                                      Cib, F_Cb, Cob, _stream(stream)), "small_group_conv2d")
+
+
+def small_probe_mfma(out, workgroups, iters, stream=None):
+    _check(load().small_probe_mfma(_ptr(out), workgroups, iters, _stream(stream)), "small_probe_mfma")
 
 
 def _ptr8(t):

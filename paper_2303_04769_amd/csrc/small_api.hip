@@ -260,6 +260,13 @@ int small_group_conv2d(const float *in, const float *filt, float *out, int N, in
     return from_hip(launch_group_conv(in, filt, out, g, F_C, S_C, K, F_Cb, as_stream(stream)));
 }
 
+int small_probe_mfma(float *out, int workgroups, int iters, void *stream)
+{
+    if (!out) return SMALL_ERR_NULL;
+    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0) return SMALL_ERR_SHAPE;
+    return from_hip(launch_mfma_probe(out, workgroups, iters, as_stream(stream)));
+}
+
 // ---- quantized (uint8) layers
 
 }  // extern "C"

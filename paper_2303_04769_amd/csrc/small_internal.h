@@ -152,4 +152,8 @@ hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, 
                             int mode, const QuantParams &q, hipStream_t s);
 hipError_t launch_relu_u8(const unsigned char *in, unsigned char *out, size_t n, int z, hipStream_t s);
 
+// Measurement aid (probe.hip): `workgroups` x 4 waves, each `iters` x 8 independent 16x16x4 fp32 matrix instructions
+// on registers; out receives workgroups * 256 floats.
+hipError_t launch_mfma_probe(float *out, int workgroups, int iters, hipStream_t s);
+
 }  // namespace small

@@ -303,3 +303,17 @@ def test_errors_leave_output_untouched():
     with pytest.raises(S.binding.SmallError):
         S.small_pool2d(x, x, 1, 16, 8, 8, 3, 3, 1, (1, 1, 1, 1), 16, S.POOL_MAX)
     assert (g.check() == np.float32(-7.25e37)).all()
+
+
+def test_matrix_rate_probe_computes_what_it_says():
+    """small_probe_mfma: eight accumulators, each `iters` times A x B with A[i][k] = 0.25 + (i & 7) / 1000 and
+    B = 0.75, so D[i][j] = iters * 4 * 0.75 * A[i]; a lane holds rows 4q .. 4q+3 and stores the sum over its 32 values."""
+    wgs, iters = 3, 5
+    g = Guarded(wgs * 256)
+    S.small_probe_mfma(g.t, wgs, iters)
+    got = g.check().reshape(wgs, 4, 64)
+    lane = np.arange(64)
+    q = lane // 16
+    rows = np.stack([4 * q + r for r in range(4)])                   # rows held by a lane
+    ref = (8 * iters * 4 * 0.75 * (0.25 + (rows & 7) / 1000.0).sum(axis=0)).astype(np.float32)
+    assert np.allclose(got, ref[None, None, :], rtol=1e-5, atol=0)
