@@ -234,8 +234,17 @@ def main():
         dt = (time.perf_counter() - t) / passes
         got = logits[:n_s * last.Co].cpu().numpy().reshape(n_s, last.Co)
         err = float(np.abs(got - ref).max())
+        # and on one thread, on a smaller slice (images are independent: the rate scales linearly)
+        O.set_threads(1)
+        n_1 = max(1, min(n_s, 8))
+        t = time.perf_counter()
+        O.run_network(net, x[:n_1], ws)
+        dt1 = time.perf_counter() - t
+        O.set_threads(used)
         result["cpu_baseline"] = {"value": round(n_s / dt, 2), "unit": "images/s", "cores": used, "kind": "oracle",
                                   "sample": "first %d of the %d images of the same batch, %d passes of %.2f s" % (n_s, N, passes, dt),
+                                  "single_thread_value": round(n_1 / dt1, 2),
+                                  "single_thread_sample": "first %d images, one pass of %.2f s" % (n_1, dt1),
                                   "max_abs_diff_vs_gpu": err}
     print(json.dumps(result))
 
