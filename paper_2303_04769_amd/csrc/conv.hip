@@ -415,6 +415,99 @@ int pick_tile(const LayerGeom &g)
     return best;
 }
 
+// ---------------------------------------------------------------------------------------------
+// First layers on the matrix cores: one input block of fewer than 16 channels (Ci = 1, 3, ...) and a short
+// reduction K = Ci * kh * kw (27 for the 3x3 RGB layers, 40 for the 10x4 single-channel one), 8 or 16 output
+// channels per block. The reduction is padded to 4 * KT and runs as KT 16x16x4 matrix instructions per 16
+// pixels: the filter operands (one float per lane and instruction) stay in registers for the whole kernel, the
+// input operand of lane (pixel p, q) in instruction t is the single input value k = 4t + q = (tap, channel) of
+// the pixel's window, gathered straight from global memory (neighbouring lanes read neighbouring pixels; the
+// nine values of one filter row are contiguous). No LDS: conv_small spends its time re-reading broadcast filter
+// values from LDS, 16 per tap and lane.
+struct FirstArgs {
+    ConvArgs c;
+    int Cib, Cob, K;
+    FastDiv div_HoWo, div_Wo;
+};
+
+// CIB, KW > 0: the layer's input block and window width as compile-time constants (the decoding of k into
+// (tap, channel) is then free); 0, 0: read from the arguments.
+template <int KT, int WM, int CIB, int KW>
+__global__ void __launch_bounds__(256) conv_first_mfma(FirstArgs f)
+{
+    const ConvArgs &a = f.c;
+    const int cib = CIB ? CIB : f.Cib, kw = KW ? KW : a.kw;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p = lane & 15, q = lane >> 4;
+    const int cob = blockIdx.y;
+    const int tile0 = ((int)blockIdx.x * 4 + wave) * (16 * WM);
+
+    // this lane's reduction elements: k = 4t + q -> (dy, dx, ci), offset inside the window in floats
+    float fa[KT];
+    int koff[KT], kdy[KT], kdx[KT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+        const int k = 4 * t + q;
+        const int tap = k / cib, ci = k - tap * cib;
+        kdy[t] = tap / kw;
+        kdx[t] = tap - kdy[t] * kw;
+        koff[t] = (kdy[t] * a.W + kdx[t]) * cib + ci;
+        const bool live = k < f.K && p < f.Cob;
+        fa[t] = live ? a.filt[((size_t)cob * f.K + k) * f.Cob + p] : 0.f;
+        if (k >= f.K) kdy[t] = 1 << 20;      // never inside the image: the operand reads as zero
+    }
+
+    // All input values of the wave's WM pixel groups are requested before the first matrix instruction: a wave
+    // has only a few hundred cycles of arithmetic, so the loads of one group after the other would each expose
+    // their full latency (and the grid is a single round of waves).
+    float fb[WM][KT];
+    unsigned valid[WM];
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm) {
+        int m = tile0 + wm * 16 + p;
+        m = m < a.M ? m : a.M - 1;
+        const int n = f.div_HoWo.div(m), rem = m - n * a.HoWo;
+        const int oy = f.div_Wo.div(rem), ox = rem - oy * a.Wo;
+        const int iy0 = oy * a.stride - a.pt, ix0 = ox * a.stride - a.pl;
+        const int org = (iy0 * a.W + ix0) * cib;                       // window origin inside the image, may be negative
+        const float *image = a.in + (size_t)n * a.H * a.W * cib;
+        valid[wm] = 0;
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+            const bool inside = (unsigned)(iy0 + kdy[t]) < (unsigned)a.H && (unsigned)(ix0 + kdx[t]) < (unsigned)a.W;
+            fb[wm][t] = image[inside ? org + koff[t] : 0];            // outside: the image's first value, replaced below
+            valid[wm] |= inside ? 1u << t : 0u;
+        }
+    }
+    floatx4 acc[WM];
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm) {
+        acc[wm] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < KT; ++t)
+            acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[t], (valid[wm] >> t) & 1u ? fb[wm][t] : 0.f, acc[wm], 0, 0, 0);
+    }
+
+    // lane (p, q) holds output channels 4q .. 4q+3 of pixel p
+    if (4 * q >= f.Cob) return;
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm) {
+        const int m = tile0 + wm * 16 + p;
+        if (m >= a.M) continue;
+        const int n = f.div_HoWo.div(m), pix = m - n * a.HoWo;
+        const size_t e = (((size_t)n * a.nCob + cob) * a.HoWo + pix) * f.Cob + 4 * q;
+        *reinterpret_cast<floatx4 *>(a.out + e) = epilogue4(acc[wm], a.epilogue, a.res + e);
+    }
+}
+
+// Which first layers the kernel above takes: one input block, a reduction of 25..28 or 37..40 values.
+int first_mfma_steps(const LayerGeom &g)
+{
+    if (g.Ci != g.Cib || g.Cib >= 16 || (g.Cob != 8 && g.Cob != 16)) return 0;
+    const int K = g.Cib * g.kh * g.kw, kt = (K + 3) / 4;
+    return (kt == 7 || kt == 10) ? kt : 0;
+}
+
 // One lane per pixel (conv_small) needs enough pixels to fill the chip; dense heads and other layers with
 // few output pixels take one lane per output element instead.
 bool use_small(const LayerGeom &g)
@@ -439,6 +532,7 @@ const char *conv_kernel_name(const LayerGeom &g)
     if (g.Cib != 16 || g.Cob != 16)
     {
         if (!use_small(g)) return is_dense(g) ? "dense_rows" : "conv_direct";
+        if (first_mfma_steps(g)) return first_mfma_steps(g) == 7 ? "conv_first_mfma<7,4>" : "conv_first_mfma<10,4>";
         if (g.Cib == 3 && g.kh == 3 && g.kw == 3) return "conv_small<3,3,3>";
         if (g.Cib == 1 && g.kh == 10 && g.kw == 4) return "conv_small<1,10,4>";
         if (g.Cib == 8 && g.kh == 1 && g.kw == 1) return "conv_small<8,1,1>";
@@ -466,6 +560,20 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
     a.epilogue = epilogue;
 
     const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt | (uintptr_t)a.res) & 15u) == 0);
+    if (aligned && first_mfma_steps(g) && use_small(g)) {
+        FirstArgs f;
+        f.c = a;
+        f.Cib = g.Cib; f.Cob = g.Cob; f.K = g.Cib * g.kh * g.kw;
+        f.div_HoWo = make_fastdiv(a.HoWo);
+        f.div_Wo = make_fastdiv(g.Wo);
+        const dim3 grid((unsigned)((a.M + 255) / 256), (unsigned)a.nCob);
+        const int kt = first_mfma_steps(g);
+        if (g.Cib == 3 && g.kw == 3 && kt == 7) hipLaunchKernelGGL((conv_first_mfma<7, 4, 3, 3>), grid, dim3(256), 0, s, f);
+        else if (g.Cib == 1 && g.kw == 4 && kt == 10) hipLaunchKernelGGL((conv_first_mfma<10, 4, 1, 4>), grid, dim3(256), 0, s, f);
+        else if (kt == 7) hipLaunchKernelGGL((conv_first_mfma<7, 4, 0, 0>), grid, dim3(256), 0, s, f);
+        else hipLaunchKernelGGL((conv_first_mfma<10, 4, 0, 0>), grid, dim3(256), 0, s, f);
+        return hipGetLastError();
+    }
     if (!aligned || g.Cib != 16 || g.Cob != 16) {
         const int kfloats = a.nCib * g.kh * g.kw * g.Cib * 16;
         if (use_small(g)) {

@@ -152,6 +152,34 @@ def test_conv2d_persistent_variant(case):
     assert_close(got, O.conv2d(x, w, stride, pad), Ci * k * k, f"conv persistent {case}")
 
 
+FIRST_LAYER_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad: at least 16384 output pixels, one short input block
+    (17, 3, 16, 32, 32, 3, 3, 1, (1, 1, 1, 1)),      # K = 27: the residual network's first layer, ragged pixel tail
+    (8, 3, 8, 96, 96, 3, 3, 2, (0, 1, 0, 1)),        # 8-channel output block, stride 2, bottom / right padding
+    (140, 1, 64, 49, 10, 10, 4, 2, (4, 5, 1, 1)),    # K = 40: the audio network's first layer, four output blocks
+    (20, 1, 16, 30, 31, 5, 5, 1, (2, 2, 2, 2)),      # K = 25 (padded to 28), wide padding on all sides
+    (5, 2, 32, 60, 61, 2, 7, 1, (0, 1, 3, 3)),       # K = 28 exactly, two input channels
+    (9, 5, 16, 44, 45, 2, 4, 1, (1, 0, 2, 1)),       # K = 40 with five input channels
+    (3, 3, 16, 80, 81, 13, 1, 1, (6, 6, 0, 0)),      # K = 39: a tall window
+]
+
+
+@pytest.mark.parametrize("case", FIRST_LAYER_CASES)
+def test_conv2d_first_layer_matrix_core(case):
+    N, Ci, Co, H, W, kh, kw, s, pad = case
+    name = S.small_conv2d_kernel(N, Ci, Co, H, W, kh, kw, s, pad, Ci, _blk(Co))
+    assert name.startswith("conv_first_mfma"), (case, name)
+    rng = np.random.default_rng(4000 + N)
+    x = (rng.random((N, Ci, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    w = (rng.random((Co, Ci, kh, kw), dtype=np.float32) * 2 - 1).astype(np.float32)
+    got = run_conv(x, w, s, pad)
+    ref = O.conv2d(x, w, s, pad) if N <= 20 else None
+    if ref is None:      # many images: the oracle recomputes a sample (images are independent)
+        for n in (0, N // 2, N - 1):
+            assert_close(got[n:n + 1], O.conv2d(x[n:n + 1], w, s, pad), Ci * kh * kw, f"first layer {case} image {n}")
+    else:
+        assert_close(got, ref, Ci * kh * kw, f"first layer {case}")
+
+
 def test_conv_identity_filter_is_exact():
     rng = np.random.default_rng(5)
     x = rng.standard_normal((2, 32, 10, 12)).astype(np.float32)
