@@ -500,12 +500,13 @@ __global__ void __launch_bounds__(256) conv_first_mfma(FirstArgs f)
     }
 }
 
-// Which first layers the kernel above takes: one input block, a reduction of 25..28 or 37..40 values.
+// Which layers the kernel above takes: one input block of fewer than 16 channels, a reduction of 5..8 (the
+// pointwise layer after an 8-channel depthwise one), 25..28 or 37..40 values.
 int first_mfma_steps(const LayerGeom &g)
 {
     if (g.Ci != g.Cib || g.Cib >= 16 || (g.Cob != 8 && g.Cob != 16)) return 0;
     const int K = g.Cib * g.kh * g.kw, kt = (K + 3) / 4;
-    return (kt == 7 || kt == 10) ? kt : 0;
+    return (kt == 2 || kt == 7 || kt == 10) ? kt : 0;
 }
 
 // One lane per pixel (conv_small) needs enough pixels to fill the chip; dense heads and other layers with
@@ -532,6 +533,7 @@ const char *conv_kernel_name(const LayerGeom &g)
     if (g.Cib != 16 || g.Cob != 16)
     {
         if (!use_small(g)) return is_dense(g) ? "dense_rows" : "conv_direct";
+        if (first_mfma_steps(g) == 2) return "conv_first_mfma<2,4>";
         if (first_mfma_steps(g)) return first_mfma_steps(g) == 7 ? "conv_first_mfma<7,4>" : "conv_first_mfma<10,4>";
         if (g.Cib == 3 && g.kh == 3 && g.kw == 3) return "conv_small<3,3,3>";
         if (g.Cib == 1 && g.kh == 10 && g.kw == 4) return "conv_small<1,10,4>";
@@ -570,6 +572,8 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
         const int kt = first_mfma_steps(g);
         if (g.Cib == 3 && g.kw == 3 && kt == 7) hipLaunchKernelGGL((conv_first_mfma<7, 4, 3, 3>), grid, dim3(256), 0, s, f);
         else if (g.Cib == 1 && g.kw == 4 && kt == 10) hipLaunchKernelGGL((conv_first_mfma<10, 4, 1, 4>), grid, dim3(256), 0, s, f);
+        else if (g.Cib == 8 && g.kw == 1 && kt == 2) hipLaunchKernelGGL((conv_first_mfma<2, 4, 8, 1>), grid, dim3(256), 0, s, f);
+        else if (kt == 2) hipLaunchKernelGGL((conv_first_mfma<2, 4, 0, 0>), grid, dim3(256), 0, s, f);
         else if (kt == 7) hipLaunchKernelGGL((conv_first_mfma<7, 4, 0, 0>), grid, dim3(256), 0, s, f);
         else hipLaunchKernelGGL((conv_first_mfma<10, 4, 0, 0>), grid, dim3(256), 0, s, f);
         return hipGetLastError();

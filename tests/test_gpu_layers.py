@@ -160,6 +160,9 @@ FIRST_LAYER_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad: at least 16384 ou
     (5, 2, 32, 60, 61, 2, 7, 1, (0, 1, 3, 3)),       # K = 28 exactly, two input channels
     (9, 5, 16, 44, 45, 2, 4, 1, (1, 0, 2, 1)),       # K = 40 with five input channels
     (3, 3, 16, 80, 81, 13, 1, 1, (6, 6, 0, 0)),      # K = 39: a tall window
+    (40, 8, 16, 24, 24, 1, 1, 1, (0, 0, 0, 0)),      # K = 8: the pointwise layer after the 8-channel depthwise one
+    (12, 2, 8, 40, 41, 2, 2, 1, (0, 1, 1, 0)),       # K = 8 from a 2 x 2 window of two channels
+    (30, 5, 16, 30, 30, 1, 1, 1, (0, 0, 0, 0)),      # K = 5 (padded to 8)
 ]
 
 
