@@ -229,6 +229,10 @@ int small_network_run(const small_layer *layers, int n_layers, const float *in_b
  * is one such run. Results agree with the layer-by-layer run within the tolerance of the chained
  * reductions, not bit for bit.
  *
+ * An average pooling over the whole image (no padding, 16-channel blocks, at most 256 channels) whose output only
+ * the following SMALL_OP_DENSE layer (at most 16 outputs) reads runs with it in one kernel; the pooled tensor's
+ * buffer is never written (same liveness rule).
+ *
  * small_network_launches (host only): how many kernel launches the table becomes, and for each the index
  * of the first layer it covers (folded layers follow it directly). It sees the table only: where a
  * depthwise + 1x1 pair or a pointwise run cannot run in one kernel for reasons outside the table (unaligned

@@ -444,9 +444,12 @@ inline bool reads(const small_layer &l, int id) { return l.src == id || (l.op ==
 // convolution), each consumed only by the next, that one kernel takes from the first layer's source to the last
 // layer's destination; chain_idx / chain_relu: their table indices and whether an in-place ReLU follows each.
 // The tensors between them are never written.
+// head: layer i is an average pooling whose output only the fully connected layer i + 1 reads; when the pooling
+// window turns out to be the whole image, both run in one kernel and the pooled tensor is never written.
 struct Fusion {
     int epilogue; int out_id; int res_id; int skip; int pw; int pw_relu; int rename;
     int chain; int chain_idx[kChainMaxLayers]; int chain_relu[kChainMaxLayers];
+    int head;
 };
 
 bool pointwise(const small_layer &l)
@@ -516,6 +519,17 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
     const small_layer &c = L[i];
     Fusion f = {EPI_NONE, c.dst, c.dst, 0, 0, 0, 0};
     const bool conv = c.op == SMALL_OP_CONV || c.op == SMALL_OP_DENSE;
+    if (c.op == SMALL_OP_AVGPOOL && allow_chain && i + 1 < nL) {
+        const small_layer &d = L[i + 1];
+        if (d.op == SMALL_OP_DENSE && d.src == c.dst && d.kh == 1 && d.kw == 1 && d.Ci == c.Ci && d.Cib == c.Cib &&
+            d.dst != c.src && d.dst != SMALL_BUF_IN && c.pad.t == 0 && c.pad.b == 0 && c.pad.l == 0 && c.pad.r == 0 &&
+            avgpool_dense_eligible(c.Ci, c.Cib, d.Co, d.Cob) && dead_from(L, nL, i + 2, c.dst)) {
+            f.head = 1;
+            f.skip = 1;
+            f.out_id = f.res_id = d.dst;
+        }
+        return f;
+    }
     if (!conv && c.op != SMALL_OP_DWCONV) return f;
     if (conv && allow_chain) {
         plan_chain(L, nL, i, f);
@@ -684,6 +698,17 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                         rc = from_hip(launch_dwpw(ptr(l.src), l.filt, pw.filt, dst, g, pw.Co,
                                                   (fu.epilogue & EPI_RELU) != 0, fu.pw_relu, s));
                     if (fu.rename) std::swap(phys[l.dst], phys[pw.dst]);
+                } else if (run && head && fu.head) {
+                    // pooling over the whole image + the fully connected layer in one kernel, if that is what it is
+                    const small_layer &d = L[i + 1];
+                    const bool global = g.Ho == 1 && g.Wo == 1 && l.kh == a.H && l.kw == a.W;
+                    if (!global || !d.filt || (((uintptr_t)ptr(l.src) | (uintptr_t)d.filt) & 15u)) {
+                        fu.head = 0;
+                        fused_away = 0;
+                        if (launch) rc = from_hip(launch_pool(ptr(l.src), ptr(l.dst), g, SMALL_POOL_AVG, s));
+                    } else if (launch) {
+                        rc = from_hip(launch_avgpool_dense(ptr(l.src), d.filt, ptr(d.dst), N, l.Ci, a.H * a.W, d.Co, d.Cob, s));
+                    }
                 } else if (launch) {
                     if (l.op == SMALL_OP_DWCONV)
                         rc = from_hip(launch_dwconv(ptr(l.src), l.filt, ptr(l.dst), g, fu.epilogue, s));

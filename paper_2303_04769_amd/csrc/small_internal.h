@@ -87,6 +87,12 @@ hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode
 bool dw_rows_eligible(const LayerGeom &g);
 hipError_t launch_dw_rows(const float *in, const float *filt, float *out, const LayerGeom &g, int relu, hipStream_t s);
 
+// Global average pooling + fully connected layer in one launch (network heads): in [N][C/16][HW][16] (16-byte
+// aligned), filt [Co/Cob][C/16][1][1][16][Cob], out [N][Co]; C <= 256, Co <= 16.
+bool avgpool_dense_eligible(int C, int Cb, int Co, int Cob);
+hipError_t launch_avgpool_dense(const float *in, const float *filt, float *out, int N, int C, int HW, int Co, int Cob,
+                                hipStream_t s);
+
 // res: tensor added to the result when epilogue has EPI_ADD (may be `out` itself: each lane reads the
 // elements it is about to write), else ignored.
 hipError_t launch_conv(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,

@@ -313,6 +313,70 @@ hipError_t launch_dwconv(const float *in, const float *filt, float *out, const L
     return launch_window<OP_DW>(in, filt, out, g, epilogue, s);
 }
 
+namespace {
+
+// Network head in one launch: global average pooling followed by a fully connected layer, one workgroup per image.
+// in [N][C/16][HW][16], filt [Co/Cob][C/16][1][1][16][Cob], out [N][Co]. Phase 1: 64 lanes per 16-channel block
+// (a float4 of channels each, 16 pixels in flight) sum the block's pixels; phase 2: lane (o, part) adds up a
+// sixteenth of the channels for output o. C <= 256, Co <= 16 (LDS: 256 means and 256 partial sums).
+__global__ void __launch_bounds__(256) avgpool_dense_head(const float *__restrict__ in, const float *__restrict__ filt,
+                                                          float *__restrict__ out, int C, int HW, int Co, int Cob)
+{
+    __shared__ float part4[16][16][4][4];    // [pixel lane][block][quad][channel in quad]
+    __shared__ float mean[256];
+    __shared__ float partial[16][16];
+    const int t = threadIdx.x, n = blockIdx.x;
+    const int nCb = C >> 4;
+    const int quad = t & 3, plane_lane = (t >> 2) & 15, cbl = t >> 6;          // 4 blocks in flight, 16 pixels x 4 quads each
+    for (int cb0 = 0; cb0 < nCb; cb0 += 4) {
+        const int cb = cb0 + cbl;
+        floatx4 sum = {0.f, 0.f, 0.f, 0.f};
+        if (cb < nCb) {
+            const floatx4 *src = reinterpret_cast<const floatx4 *>(in + ((size_t)n * nCb + cb) * HW * 16) + quad;
+            for (int px = plane_lane; px < HW; px += 16) sum += src[px * 4];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) part4[plane_lane][cbl][quad][k] = sum[k];
+        __syncthreads();
+        if (t < 64 && cb0 + (t >> 4) < nCb) {                                    // 4 blocks x 16 channels
+            float v = 0.f;
+#pragma unroll
+            for (int l = 0; l < 16; ++l) v += part4[l][t >> 4][(t >> 2) & 3][t & 3];
+            mean[(cb0 + (t >> 4)) * 16 + (t & 15)] = v / (float)HW;
+        }
+        __syncthreads();
+    }
+    const int o = t & 15, part = t >> 4;
+    float acc = 0.f;
+    if (o < Co) {
+        const int cob = o / Cob, co_in = o - cob * Cob;
+        for (int c = part; c < C; c += 16)
+            acc += mean[c] * filt[(((size_t)cob * nCb + (c >> 4)) * 16 + (c & 15)) * Cob + co_in];
+    }
+    partial[part][o] = acc;
+    __syncthreads();
+    if (t < Co) {
+        float v = 0.f;
+#pragma unroll
+        for (int l = 0; l < 16; ++l) v += partial[l][t];
+        out[(size_t)n * Co + t] = v;
+    }
+}
+
+}  // namespace
+
+bool avgpool_dense_eligible(int C, int Cb, int Co, int Cob)
+{
+    return Cb == 16 && C % 16 == 0 && C <= 256 && Co >= 1 && Co <= 16 && Cob >= 1 && Co % Cob == 0;
+}
+
+hipError_t launch_avgpool_dense(const float *in, const float *filt, float *out, int N, int C, int HW, int Co, int Cob,
+                                hipStream_t s)
+{
+    hipLaunchKernelGGL(avgpool_dense_head, dim3((unsigned)N), dim3(256), 0, s, in, filt, out, C, HW, Co, Cob);
+    return hipGetLastError();
+}
+
 hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode, hipStream_t s)
 {
     if (mode == 0) return launch_window<OP_MAX>(in, nullptr, out, g, EPI_NONE, s);

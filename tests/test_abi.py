@@ -94,18 +94,18 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
             sizes[L.dst] = max(sizes.get(L.dst, 0), L.Co * L.Ho * L.Wo * 4)
     assert ws(r, 1) == sum((v + 255) // 256 * 256 for v in sizes.values())
     assert ws(r, 1) <= 4 * 16 * 32 * 32 * 4
-    # launches after cross-layer fusion: residual CNN = 9 convs (ReLU / add+ReLU folded) + avgpool + dense
+    # launches after cross-layer fusion: residual CNN = 9 convs (ReLU / add+ReLU folded) + the head (avgpool + dense)
     table = B.make_layer_table(r.layers, [None] * len(r.wshapes))
     heads = B.small_network_launches(table)
-    assert len(r.layers) == 21 and len(heads) == 11
-    assert [r.layers[h].op for h in heads] == ["conv"] * 9 + ["avgpool", "dense"]
+    assert len(r.layers) == 21 and len(heads) == 10
+    assert [r.layers[h].op for h in heads] == ["conv"] * 9 + ["avgpool"]
     ta = B.make_layer_table(a.layers, [None] * len(a.wshapes))
     # depthwise + ReLU + pointwise + ReLU blocks are one launch each
-    assert [a.layers[h].op for h in B.small_network_launches(ta)] == ["conv"] + ["dw"] * 4 + ["avgpool", "dense"]
+    assert [a.layers[h].op for h in B.small_network_launches(ta)] == ["conv"] + ["dw"] * 4 + ["avgpool"]
     d = WL.dsep_cnn()
     td = B.make_layer_table(d.layers, [None] * len(d.wshapes))
     # the first block has 8-channel blocks (two launches), the other 12 are fused
-    assert [d.layers[h].op for h in B.small_network_launches(td)] == ["conv", "dw", "conv"] + ["dw"] * 12 + ["avgpool", "dense"]
+    assert [d.layers[h].op for h in B.small_network_launches(td)] == ["conv", "dw", "conv"] + ["dw"] * 12 + ["avgpool"]
     # the dense-only autoencoder is one run of pointwise layers: a single launch; workspace = two ping-pong rows
     e = WL.dense_autoencoder()
     te = B.make_layer_table(e.layers, [None] * len(e.wshapes))

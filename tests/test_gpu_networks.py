@@ -281,6 +281,44 @@ def test_pointwise_run_keeps_tensors_that_are_read_later():
     assert_close(_run(net, x, ws), ref, 32 * 3, "run that may not end in its own input")
 
 
+# ------------------------------------------------------------------ network head in one kernel
+
+@pytest.mark.parametrize("case", [(3, 48, 7, 1, 16, 16), (2, 256, 1, 1, 5, 5), (5, 16, 9, 13, 12, 12), (1, 128, 3, 3, 16, 8),
+                                  (4, 64, 8, 8, 10, 10), (2, 208, 2, 5, 1, 1)])
+def test_average_pool_and_dense_head(case):
+    """Global average pooling followed by a fully connected layer is one launch; the pooled tensor is never written."""
+    from workloads.nets import Layer, Network, IN, OUT
+    N, C, H, W, Co, Cob = case
+    net = Network("head_probe", C, H, W)
+    net.wshapes = [((Co, C, 1, 1), C)]
+    net.layers = [Layer("relu", C, C, H, W, src=IN, dst=0),
+                  Layer("avgpool", C, C, H, W, H, W, 1, src=0, dst=1),
+                  Layer("dense", C, Co, 1, 1, 1, 1, 1, Cob=Cob, src=1, dst=OUT, w=0, Ho=1, Wo=1)]
+    table = S.make_layer_table(net.layers, [None])
+    assert S.small_network_launches(table) == [0, 1]
+    x, ws = WL.network_tensors(net, N, 31)
+    ref = O.dense(O.pool2d(O.relu(x), (H, W), 1, (0, 0, 0, 0), "avg"), ws[0])
+    got = _run(net, x, ws).reshape(N, Co)
+    assert_close(got, ref.reshape(N, Co), C, f"avgpool + dense head {case}")
+
+
+def test_pooled_tensor_read_later_keeps_the_head_unfused():
+    from workloads.nets import Layer, Network, IN, OUT
+    C, H, W = 32, 4, 4
+    net = Network("head_probe", C, H, W)
+    net.wshapes = [((32, C, 1, 1), C)]
+    net.layers = [Layer("relu", C, C, H, W, src=IN, dst=0),
+                  Layer("avgpool", C, C, H, W, H, W, 1, src=0, dst=1),
+                  Layer("dense", C, 32, 1, 1, 1, 1, 1, src=1, dst=2, w=0, Ho=1, Wo=1),
+                  Layer("add", 32, 32, 1, 1, src=2, src2=1, dst=OUT)]
+    table = S.make_layer_table(net.layers, [None])
+    assert S.small_network_launches(table) == [0, 1, 2, 3]   # pooling on its own: its result is an operand of the add
+    x, ws = WL.network_tensors(net, 3, 32)
+    pooled = O.pool2d(O.relu(x), (H, W), 1, (0, 0, 0, 0), "avg")
+    ref = O.add(O.dense(pooled, ws[0]).reshape(3, 32, 1, 1), pooled)
+    assert_close(_run(net, x, ws), ref, C, "pooled tensor kept for a later add")
+
+
 # ------------------------------------------------------------------ full-size sweep layers (sampled)
 
 @pytest.mark.parametrize("C,H", WL.sweep_shapes()["conv"])
