@@ -319,6 +319,32 @@ def test_pooled_tensor_read_later_keeps_the_head_unfused():
     assert_close(_run(net, x, ws), ref, C, "pooled tensor kept for a later add")
 
 
+# ------------------------------------------------------------------ fused kernels need aligned pointers
+
+@pytest.mark.parametrize("name,idx,N", [("dense_autoencoder", 5, 20), ("audio_cnn", 4, 3), ("residual_cnn", 2, 2)])
+def test_misaligned_filters_take_the_unfused_kernels(name, idx, N):
+    """Filters that start 4 bytes off a 16-byte boundary: the one-kernel paths (pointwise runs, depthwise +
+    pointwise blocks, the pooling + dense head, the matrix-core convolutions) step aside for kernels that take any
+    pointer, and the results still match the oracle."""
+    net = getattr(WL, name)()
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + idx)
+    pn = S.PackedNetwork(net, ws, DEV)
+    shifted = []
+    for f in pn.filters:
+        buf = torch.empty(f.numel() + 1, dtype=torch.float32, device=DEV)
+        buf[1:].copy_(f)
+        shifted.append(buf[1:])
+        assert shifted[-1].data_ptr() % 16 == 4
+    table = S.make_layer_table(net.layers, shifted)
+    nbytes = S.small_network_workspace(table, N, net.C0, net.H0, net.W0)
+    wsp = torch.empty(max(nbytes, 256) // 4, dtype=torch.float32, device=DEV)
+    g = Guarded(pn.out_elems(N))
+    S.small_network_run(table, pn.pack_input(dev(x)), g.t, wsp, nbytes, N, net.C0, net.H0, net.W0)
+    L = net.layers[-1]
+    got = O.unpack(g.check(), (N, L.Co, L.Ho, L.Wo), L.Cob).reshape(N, -1)
+    assert_close(got, O.run_network(net, x, ws), _maxK(net), f"{name} with misaligned filters")
+
+
 # ------------------------------------------------------------------ full-size sweep layers (sampled)
 
 @pytest.mark.parametrize("C,H", WL.sweep_shapes()["conv"])
