@@ -112,6 +112,47 @@ __global__ void __launch_bounds__(kBlock) pack_tile(float *__restrict__ plain_ba
     }
 }
 
+// Cb = 16 with a 16-byte aligned blocked tensor: 256 pixels x 16 channels per workgroup. A lane reads (writes) its
+// pixel's 16 channel values with one coalesced 4-byte access per channel row, all in flight together, and the
+// blocked side moves as whole float4s, 1 KB per wave instruction; LDS only transposes ([pixel][16 + 4 pad]).
+constexpr int kPix16 = 256;
+
+template <bool kUnpack>
+__global__ void __launch_bounds__(kBlock) pack16(float *__restrict__ plain_base, float *__restrict__ blk_base, int C, int HW)
+{
+    __shared__ floatx4 tile[kPix16][5];
+    const int nCb = C >> 4;
+    const int plane = blockIdx.x;          // n * nCb + cb
+    const int n = plane / nCb, cb = plane - n * nCb;
+    const int p0 = blockIdx.y * kPix16;
+    const int np = min(kPix16, HW - p0);
+    float *plain = plain_base + ((size_t)n * C + (size_t)cb * 16) * HW + p0;
+    floatx4 *blk = reinterpret_cast<floatx4 *>(blk_base + ((size_t)plane * HW + p0) * 16);
+    const int t = threadIdx.x;
+    if (!kUnpack) {
+        if (t < np) {
+            float v[16];
+#pragma unroll
+            for (int c = 0; c < 16; ++c) v[c] = __builtin_nontemporal_load(plain + (size_t)c * HW + t);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) tile[t][k] = floatx4{v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]};
+        }
+        __syncthreads();
+        for (int e = t; e < np * 4; e += kBlock) __builtin_nontemporal_store(tile[e >> 2][e & 3], blk + e);
+    } else {
+        for (int e = t; e < np * 4; e += kBlock) tile[e >> 2][e & 3] = __builtin_nontemporal_load(blk + e);
+        __syncthreads();
+        if (t < np) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const floatx4 v = tile[t][k];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) __builtin_nontemporal_store(v[c], plain + (size_t)(4 * k + c) * HW + t);
+            }
+        }
+    }
+}
+
 // Filters are packed once per network; one thread per blocked element.
 __global__ void __launch_bounds__(kBlock) pack_filter_kernel(const float *__restrict__ oihw, float *__restrict__ blk,
                                                               int Co, int Ci, int kh, int kw, int Cob, int Cib)
@@ -139,6 +180,12 @@ hipError_t launch_add(const float *a, const float *b, float *out, size_t n, hipS
 hipError_t launch_pack(const float *src, float *dst, int N, int C, int H, int W, int Cb, bool unpack, hipStream_t s)
 {
     const int HW = H * W;
+    if (Cb == 16 && HW >= 64 && ((uintptr_t)(unpack ? src : dst) & 15u) == 0) {
+        const dim3 grid16((unsigned)(N * (C / 16)), (unsigned)((HW + kPix16 - 1) / kPix16));
+        if (unpack) hipLaunchKernelGGL(pack16<true>, grid16, dim3(kBlock), 0, s, dst, const_cast<float *>(src), C, HW);
+        else hipLaunchKernelGGL(pack16<false>, grid16, dim3(kBlock), 0, s, const_cast<float *>(src), dst, C, HW);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)(N * (C / Cb)), (unsigned)((HW + kPix - 1) / kPix));
     // the source side is only read; the kernel takes both as plain pointers to share one body
     if (unpack)
