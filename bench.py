@@ -204,7 +204,7 @@ def main():
     # ------------------------------------------------------------------ roofline layer sweep
     if not args.no_sweep:
         result["sweep"] = sweep(S, WL, torch, np, dev, timed)
-        c = [r for r in result["sweep"] if r["layer"] == "conv3x3"]
+        c = [r for r in result["sweep"] if r["layer"] == "conv3x3" and not r.get("paper_layer_study")]
         best = max(c, key=lambda r: r["frac"])
         result["roofline_sweep_conv3x3"] = {"bound": "mfma", "achieved": best["tflops"], "peak": PEAK_MFMA_F32 / 1e12,
                                             "unit": "TFLOP/s", "frac": best["frac"], "shape": best["shape"],
@@ -323,7 +323,8 @@ def sweep(S, WL, torch, np, dev, timed, only=None):
         ts = [timed(gfn, n) / per_graph for _ in range(trials)]
         return min(ts), statistics.median(ts)
 
-    for C, H in WL.sweep_shapes()["conv"]:
+    shapes = WL.sweep_shapes()
+    for C, H in shapes["conv"] + shapes["paper_layer_study"]:
         n_act = Nb * C * H * H
         act_bytes = 8.0 * n_act
         sets = max(2, int(-(-ROTATE_BYTES // act_bytes)))
@@ -338,7 +339,8 @@ def sweep(S, WL, torch, np, dev, timed, only=None):
             tmin, tmed = best_of(fn, 30 if k == 3 else 100)
             flops = 2.0 * Nb * C * H * H * C * k * k
             byts = 4.0 * (2 * n_act + C * C * k * k)
-            rows.append({"layer": name, "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+            rows.append({"layer": name, "shape": "N64 C%d %dx%d" % (C, H, H), "paper_layer_study": (C, H) in shapes["paper_layer_study"],
+                         "us": round(tmin * 1e6, 2),
                          "us_median": round(tmed * 1e6, 2), "tflops": round(flops / tmin / 1e12, 2),
                          "frac": round(flops / tmin / PEAK_MFMA_F32, 4), "gbs": round(byts / tmin / 1e9, 1),
                          "frac_hbm": round(byts / tmin / PEAK_HBM, 4),

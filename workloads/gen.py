@@ -41,7 +41,10 @@ SWEEP_N = 64
 def sweep_shapes():
     """(C, H) pairs of the conv / depthwise sweep, plus the pool / ReLU shape."""
     return {"conv": [(64, 56), (128, 28), (256, 14), (512, 7)],
-            "pool_relu": (256, 56)}
+            "pool_relu": (256, 56),
+            # the two input sizes of the paper's own layer study (Section "Choice of layer types and sizes"):
+            # 48 x 48 x 16 and 6 x 6 x 512 (height x width x channels), here at the sweep's batch of 64
+            "paper_layer_study": [(16, 48), (512, 6)]}
 
 
 # Quantized (uint8) layers: codes are uniform over 0..255; zero points and the fixed-point multiplier are
