@@ -349,3 +349,54 @@ def test_matrix_rate_probe_computes_what_it_says():
     rows = np.stack([4 * q + r for r in range(4)])                   # rows held by a lane
     ref = (8 * iters * 4 * 0.75 * (0.25 + (rows & 7) / 1000.0).sum(axis=0)).astype(np.float32)
     assert np.allclose(got, ref[None, None, :], rtol=1e-5, atol=0)
+
+
+# ------------------------------------------------------------------ seeded random geometries
+
+def _random_geometry(rng, max_hw=34):
+    kh, kw = int(rng.choice([1, 1, 3, 3, 3, 2, 5])), int(rng.choice([1, 1, 3, 3, 3, 2, 4]))
+    if rng.random() < 0.6:
+        kw = kh
+    stride = int(rng.choice([1, 1, 1, 2, 2, 3]))
+    H, W = int(rng.integers(kh, max_hw)), int(rng.integers(kw, max_hw))
+    pad = (int(rng.integers(0, kh)), int(rng.integers(0, kh)), int(rng.integers(0, kw)), int(rng.integers(0, kw)))
+    return H, W, kh, kw, stride, pad
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_conv2d_random_geometries(seed):
+    """Channel counts, image sizes, windows, strides and paddings drawn from a seeded generator: whatever kernel the
+    dispatcher picks for the geometry has to agree with the definition."""
+    rng = np.random.default_rng(9000 + seed)
+    Ci = int(rng.choice([1, 3, 8, 16, 16, 32, 48, 64, 128]))
+    Co = int(rng.choice([8, 10, 16, 16, 32, 48, 64, 128]))
+    H, W, kh, kw, stride, pad = _random_geometry(rng)
+    N = int(rng.integers(1, 6)) if seed % 4 else int(rng.integers(20, 70))
+    x = (rng.random((N, Ci, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    w = (rng.random((Co, Ci, kh, kw), dtype=np.float32) * 2 - 1).astype(np.float32)
+    got = run_conv(x, w, stride, pad)
+    assert_close(got, O.conv2d(x, w, stride, pad), Ci * kh * kw,
+                 f"conv N={N} {Ci}->{Co} {H}x{W} k={kh}x{kw} s={stride} pad={pad}")
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_window_layers_random_geometries(seed):
+    rng = np.random.default_rng(9500 + seed)
+    C = int(rng.choice([3, 8, 16, 16, 32, 64, 80]))
+    Cb = _blk(C)
+    H, W, kh, kw, stride, pad = _random_geometry(rng, 40)
+    N = int(rng.integers(1, 5)) if seed % 3 else int(rng.integers(30, 90))
+    x = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = rng.standard_normal((C, 1, kh, kw)).astype(np.float32)
+    Ho, Wo = O.out_dim(H, kh, stride, pad[0], pad[1]), O.out_dim(W, kw, stride, pad[2], pad[3])
+    xb = dev(O.pack(x, Cb))
+    what = f"N={N} C={C} {H}x{W} k={kh}x{kw} s={stride} pad={pad}"
+    g = Guarded(N * C * Ho * Wo)
+    S.small_dwconv2d(xb, dev(O.pack_dw_filter(w, Cb)), g.t, N, C, H, W, kh, kw, stride, pad, Cb)
+    assert_close(O.unpack(g.check(), (N, C, Ho, Wo), Cb), O.dwconv2d(x, w, stride, pad), kh * kw, "dw " + what)
+    g = Guarded(N * C * Ho * Wo)
+    S.small_pool2d(xb, g.t, N, C, H, W, kh, kw, stride, pad, Cb, S.POOL_MAX)
+    assert_bits(O.unpack(g.check(), (N, C, Ho, Wo), Cb), O.pool2d(x, (kh, kw), stride, pad, "max"), "max pool " + what)
+    g = Guarded(N * C * Ho * Wo)
+    S.small_pool2d(xb, g.t, N, C, H, W, kh, kw, stride, pad, Cb, S.POOL_AVG)
+    assert_close(O.unpack(g.check(), (N, C, Ho, Wo), Cb), O.pool2d(x, (kh, kw), stride, pad, "avg"), kh * kw, "avg pool " + what)

@@ -214,3 +214,24 @@ def test_errors_are_raised():
     assert e.value.code == 8
     with pytest.raises(TypeError):
         S.small_relu_u8(torch.zeros(4, device=DEV), o, 4, 0)
+
+
+@pytest.mark.parametrize("seed", range(32))
+def test_conv_random_geometries(seed):
+    """Seeded random channel counts, images, windows, strides, paddings and zero points: bit-exact whatever kernel runs."""
+    r = np.random.default_rng(7000 + seed)
+    Ci = int(r.choice([3, 8, 16, 16, 32, 48, 64, 128]))
+    Co = int(r.choice([8, 16, 16, 32, 48, 64]))
+    kh = int(r.choice([1, 3, 3, 2, 5]))
+    kw = kh if r.random() < 0.6 else int(r.choice([1, 3, 2, 4]))
+    s = int(r.choice([1, 1, 2, 3]))
+    H, W = int(r.integers(kh, 30)), int(r.integers(kw, 30))
+    pad = (int(r.integers(0, kh)), int(r.integers(0, kh)), int(r.integers(0, kw)), int(r.integers(0, kw)))
+    N = int(r.integers(1, 5)) if seed % 4 else int(r.integers(20, 50))
+    zx, zw = int(r.choice([0, 128, 128, 255, r.integers(0, 256)])), int(r.choice([0, 128, 128, 255, r.integers(0, 256)]))
+    x, w = WL.u8_codes(r, (N, Ci, H, W)), WL.u8_codes(r, (Co, Ci, kh, kw))
+    q = _quant_for(Q.conv2d_acc(x, w, s, pad, zx, zw), zx, zw, relu=bool(seed & 1))
+    ref = Q.conv2d(x, w, s, pad, q)
+    Cib, Cob = min(16, Ci), min(16, Co)
+    what = f"conv u8 N={N} {Ci}->{Co} {H}x{W} k={kh}x{kw} s={s} pad={pad} z=({zx},{zw})"
+    _same(_conv(x, w, s, pad, q, Cib, Cob, with_sums=bool(seed & 2)), ref, what)
