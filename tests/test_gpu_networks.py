@@ -345,6 +345,95 @@ def test_misaligned_filters_take_the_unfused_kernels(name, idx, N):
     assert_close(got, O.run_network(net, x, ws), _maxK(net), f"{name} with misaligned filters")
 
 
+# ------------------------------------------------------------------ seeded random layer tables
+
+def _random_table(rng):
+    """A valid table of 6..18 layers over four workspace slots: convolutions (1x1 / 3x3, stride 1 or 2), depthwise,
+    ReLU, add, pooling and a final pointwise layer into OUT, with sources and destinations drawn at random among the
+    buffers that hold a tensor of the right shape. Exercises the fusion planner's liveness rules."""
+    from workloads.nets import Layer, Network, IN, OUT
+    C0 = int(rng.choice([16, 32, 64]))
+    H0 = W0 = int(rng.choice([4, 6, 9, 12]))
+    net = Network("random_table", C0, H0, W0)
+    shape = {IN: (C0, H0, W0)}
+    layers, cur = [], IN
+
+    def free_slot(*busy):
+        cands = [k for k in range(4) if k not in busy]
+        return int(rng.choice(cands))
+
+    n_layers = int(rng.integers(6, 18))
+    for _ in range(n_layers):
+        C, H, W = shape[cur]
+        op = rng.choice(["conv1", "conv3", "dw", "relu", "add", "pool", "conv1", "relu"])
+        if op in ("conv1", "conv3"):
+            k = 1 if op == "conv1" else 3
+            s = 2 if (k == 3 and H >= 6 and rng.random() < 0.3) else 1
+            Co = int(rng.choice([16, 32, 64]))
+            pad = (0, 0, 0, 0) if k == 1 else ((1, 1, 1, 1) if s == 1 else (0, 1, 0, 1))
+            dst = free_slot(cur)
+            net.wshapes.append(((Co, C, k, k), C * k * k))
+            L = Layer("conv", C, Co, H, W, k, k, s, pad, src=cur, dst=dst, w=len(net.wshapes) - 1)
+            shape[dst] = (Co, L.Ho, L.Wo)
+        elif op == "dw":
+            s = 2 if (H >= 6 and rng.random() < 0.3) else 1
+            pad = (1, 1, 1, 1) if s == 1 else (0, 1, 0, 1)
+            dst = free_slot(cur)
+            net.wshapes.append(((C, 1, 3, 3), 9))
+            L = Layer("dw", C, C, H, W, 3, 3, s, pad, src=cur, dst=dst, w=len(net.wshapes) - 1)
+            shape[dst] = (C, L.Ho, L.Wo)
+        elif op == "relu":
+            if cur == IN:
+                dst = free_slot()
+                L = Layer("relu", C, C, H, W, src=cur, dst=dst)
+                shape[dst] = (C, H, W)
+            else:
+                dst = cur
+                L = Layer("relu", C, C, H, W, src=cur, dst=cur)
+        elif op == "add":
+            others = [b for b, sh in shape.items() if sh == (C, H, W) and b != cur]
+            if not others:
+                continue
+            other = int(rng.choice(others))
+            dst = cur if (cur != IN and rng.random() < 0.7) else free_slot(cur, other)
+            L = Layer("add", C, C, H, W, src=cur, src2=other, dst=dst)
+            shape[dst] = (C, H, W)
+        else:
+            if H < 4:
+                continue
+            dst = free_slot(cur)
+            L = Layer("maxpool" if rng.random() < 0.5 else "avgpool", C, C, H, W, 2, 2, 2, (0, 0, 0, 0), src=cur, dst=dst)
+            shape[dst] = (C, L.Ho, L.Wo)
+        layers.append(L)
+        cur = dst
+    C, H, W = shape[cur]
+    if rng.random() < 0.5:      # head: global average pooling + dense
+        dst = free_slot(cur)
+        layers.append(Layer("avgpool", C, C, H, W, H, W, 1, src=cur, dst=dst))
+        net.wshapes.append(((10, C, 1, 1), C))
+        layers.append(Layer("dense", C, 10, 1, 1, 1, 1, 1, src=dst, dst=OUT, w=len(net.wshapes) - 1, Ho=1, Wo=1))
+    else:
+        net.wshapes.append(((32, C, 1, 1), C))
+        layers.append(Layer("conv", C, 32, H, W, 1, 1, 1, (0, 0, 0, 0), src=cur, dst=OUT, w=len(net.wshapes) - 1))
+    net.layers = layers
+    return net
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_layer_tables(seed):
+    rng = np.random.default_rng(12000 + seed)
+    net = _random_table(rng)
+    N = int(rng.integers(1, 5))
+    x, ws = WL.network_tensors(net, N, 13000 + seed)
+    ref = O.run_network(net, x, ws)
+    got = _run(net, x, ws).reshape(ref.shape)
+    # errors of chained layers compound: the bound is that of the largest reduction, times the depth
+    depth = sum(L.op in ("conv", "dw", "dense") for L in net.layers)
+    K = max([L.Ci * L.kh * L.kw for L in net.layers if L.op in ("conv", "dense")] + [9])
+    ops = "/".join(L.op for L in net.layers)
+    assert_close(got, ref, K * max(depth, 1) ** 2, f"random table {seed}: {ops}")
+
+
 # ------------------------------------------------------------------ full-size sweep layers (sampled)
 
 @pytest.mark.parametrize("C,H", WL.sweep_shapes()["conv"])
