@@ -481,6 +481,64 @@ __global__ void __launch_bounds__(256) window_u8(QWindowArgs a, size_t total)
     else o[0] = (unsigned char)packed;
 }
 
+// Depthwise 3x3 on 16-byte blocks: a lane owns four channels (one 32-bit word of the block) of four output pixels
+// 64 apart, so the nine filter words are unpacked to (w - zw) once per lane and every access of a wave is one
+// contiguous kilobyte. Taps outside the image read a valid address and are replaced by the code zx, so that
+// sum over all nine taps of x (w - zw) - zx * sum (w - zw) is the sum over the taps inside the image of (x - zx)(w - zw).
+struct QDw3Args {
+    const unsigned *in, *filt;
+    unsigned *out;
+    int H, W, Ho, Wo, HoWo, nCb, stride, pt, pl;
+    FastDiv div_Wo, div_nCb;
+    QuantParams q;
+};
+
+__global__ void __launch_bounds__(256) dw3x3_u8(QDw3Args a)
+{
+    const int cg = threadIdx.x & 3, pl64 = threadIdx.x >> 2;
+    const int plane = blockIdx.y;                               // n * nCb + cb
+    const int cb = plane - a.div_nCb.div(plane) * a.nCb;
+    int wq[9][4], wsum[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        const unsigned w = a.filt[(cb * 9 + t) * 4 + cg];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            wq[t][c] = (int)((w >> (8 * c)) & 255u) - a.q.zw;
+            wsum[c] += wq[t][c];
+        }
+    }
+    const unsigned *img = a.in + (size_t)plane * a.H * a.W * 4 + cg;
+    unsigned *dst = a.out + (size_t)plane * a.HoWo * 4 + cg;
+    const unsigned zx4 = (unsigned)a.q.zx * 0x01010101u;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int pix = (int)blockIdx.x * 256 + i * 64 + pl64;
+        if (pix >= a.HoWo) break;
+        const int oh = a.div_Wo.div(pix), ow = pix - oh * a.Wo;
+        const int ih0 = oh * a.stride - a.pt, iw0 = ow * a.stride - a.pl;
+        unsigned x[9];
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < 3; ++kx) {
+                const int ih = ih0 + ky, iw = iw0 + kx;
+                const bool inside = (unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W;
+                const unsigned v = img[inside ? (ih * a.W + iw) * 4 : 0];
+                x[ky * 3 + kx] = inside ? v : zx4;
+            }
+        unsigned packed = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            int acc = -a.q.zx * wsum[c];
+#pragma unroll
+            for (int t = 0; t < 9; ++t) acc += (int)((x[t] >> (8 * c)) & 255u) * wq[t][c];
+            packed |= (unsigned)requant(acc, a.q) << (8 * c);
+        }
+        dst[(size_t)pix * 4] = packed;
+    }
+}
+
 __global__ void __launch_bounds__(256) relu_u8_kernel(const unsigned char *in, unsigned char *out, size_t n, int z)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -595,6 +653,18 @@ hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, 
     a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pt = g.pt; a.pl = g.pl;
     a.mode = mode;
     a.q = q;
+    if (mode == 0 && g.Cib == 16 && g.kh == 3 && g.kw == 3 &&
+        ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 3u) == 0) && (size_t)g.N * a.nCb <= 65535) {
+        QDw3Args d;
+        d.in = reinterpret_cast<const unsigned *>(in); d.filt = reinterpret_cast<const unsigned *>(filt);
+        d.out = reinterpret_cast<unsigned *>(out);
+        d.H = g.H; d.W = g.W; d.Ho = g.Ho; d.Wo = g.Wo; d.HoWo = g.Ho * g.Wo; d.nCb = a.nCb;
+        d.stride = g.stride; d.pt = g.pt; d.pl = g.pl;
+        d.div_Wo = make_fastdiv(g.Wo); d.div_nCb = make_fastdiv(a.nCb);
+        d.q = q;
+        hipLaunchKernelGGL(dw3x3_u8, dim3((unsigned)((d.HoWo + 255) / 256), (unsigned)(g.N * a.nCb)), dim3(256), 0, s, d);
+        return hipGetLastError();
+    }
     const size_t n_out = (size_t)g.N * g.Ci * g.Ho * g.Wo;
     const bool words4 = g.Cib % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)(filt ? filt : in)) & 3u) == 0);
     a.div_groups = make_fastdiv(words4 ? g.Cib / 4 : g.Cib);
