@@ -209,6 +209,15 @@ int small_network_workspace(const small_layer *layers, int n_layers, int N, int 
 int small_network_run(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
                       void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream);
 
+/* small_network_run_plain: the same run from a plain [N][C0][H0][W0] input: the layout change of the network boundary
+ * (Section 4.4: formats are converted only where the network meets the outside) happens inside the first layer's
+ * kernel instead of in a small_pack launch of its own. Only for tables whose input is read by layer 0 alone, a
+ * convolution with one input block of fewer than 16 channels and a reduction Ci*kh*kw of 5..8, 25..28 or 37..40
+ * values (the first layers of the CNNs here) producing at least 16384 output pixels; otherwise SMALL_ERR_LAYER and
+ * nothing is enqueued (pack the input and call small_network_run). Same results as small_pack + small_network_run. */
+int small_network_run_plain(const small_layer *layers, int n_layers, const float *in_nchw, float *out_blocked,
+                            void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream);
+
 /* Cross-layer fusion. small_network_run folds layers that only touch a convolution's output element by
  * element into that convolution's store phase (the direction the paper's conclusion calls an abstract
  * "fused" layer, possible because every layer shares one layout): a ReLU in place on the output of a

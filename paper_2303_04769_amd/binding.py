@@ -23,7 +23,7 @@ EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "sma
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
            "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_probe_mfma", "small_pack_u8", "small_unpack_u8",
            "small_pack_filter_u8", "small_filter_sums_u8", "small_conv2d_u8", "small_dwconv2d_u8", "small_dense_u8", "small_pool2d_u8", "small_relu_u8",
-           "small_network_workspace", "small_network_run", "small_network_launches",
+           "small_network_workspace", "small_network_run", "small_network_run_plain", "small_network_launches",
            "small_network_run_range"]
 
 
@@ -91,6 +91,7 @@ def load():
         "small_relu_u8": (i, [p, p, sz, i, p]),
         "small_network_workspace": (i, [C.POINTER(small_layer), i, i, i, i, i, C.POINTER(sz)]),
         "small_network_run": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
+        "small_network_run_plain": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
         "small_network_launches": (i, [C.POINTER(small_layer), i, C.POINTER(i), C.POINTER(i)]),
         "small_network_run_range": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, i, i, p]),
     }
@@ -288,6 +289,12 @@ def small_network_run(table, in_blocked, out_blocked, workspace, workspace_bytes
                                     workspace_bytes, N, C0, H0, W0, _stream(stream)), "small_network_run")
 
 
+def small_network_run_plain(table, in_nchw, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, stream=None):
+    _check(load().small_network_run_plain(table, len(table), _ptr(in_nchw), _ptr(out_blocked),
+                                          C.c_void_p(workspace.data_ptr()) if workspace is not None else None,
+                                          workspace_bytes, N, C0, H0, W0, _stream(stream)), "small_network_run_plain")
+
+
 def small_network_launches(table):
     """List of first-layer indices, one per kernel launch of small_network_run."""
     first = (C.c_int * len(table))()
@@ -344,6 +351,13 @@ class PackedNetwork:
         ws, nbytes = self.workspace(N)
         small_network_run(self.table, in_blocked, out_blocked, ws, nbytes, N, self.net.C0, self.net.H0, self.net.W0,
                           stream)
+
+    def run_plain(self, in_nchw, out_blocked, N, stream=None):
+        """The run from a plain [N][C0][H0][W0] input (no small_pack launch); raises SmallError with
+        SMALL_ERR_LAYER when the first layer cannot take a plain tensor."""
+        ws, nbytes = self.workspace(N)
+        small_network_run_plain(self.table, in_nchw, out_blocked, ws, nbytes, N, self.net.C0, self.net.H0,
+                                self.net.W0, stream)
 
     def capture(self, in_blocked, out_blocked, N):
         """Records one run on these buffers into a HIP graph (torch.cuda.CUDAGraph). graph.replay() enqueues the

@@ -427,6 +427,8 @@ int pick_tile(const LayerGeom &g)
 struct FirstArgs {
     ConvArgs c;
     int Cib, Cob, K;
+    int plain_input;      // the input is a plain [N][C][H][W] tensor (the network's own input): the layout change
+                          // of the network boundary then happens in this kernel's gathers
     FastDiv div_HoWo, div_Wo;
 };
 
@@ -451,7 +453,7 @@ __global__ void __launch_bounds__(256) conv_first_mfma(FirstArgs f)
         const int tap = k / cib, ci = k - tap * cib;
         kdy[t] = tap / kw;
         kdx[t] = tap - kdy[t] * kw;
-        koff[t] = (kdy[t] * a.W + kdx[t]) * cib + ci;
+        koff[t] = f.plain_input ? ci * a.H * a.W + kdy[t] * a.W + kdx[t] : (kdy[t] * a.W + kdx[t]) * cib + ci;
         const bool live = k < f.K && p < f.Cob;
         fa[t] = live ? a.filt[((size_t)cob * f.K + k) * f.Cob + p] : 0.f;
         if (k >= f.K) kdy[t] = 1 << 20;      // never inside the image: the operand reads as zero
@@ -469,7 +471,7 @@ __global__ void __launch_bounds__(256) conv_first_mfma(FirstArgs f)
         const int n = f.div_HoWo.div(m), rem = m - n * a.HoWo;
         const int oy = f.div_Wo.div(rem), ox = rem - oy * a.Wo;
         const int iy0 = oy * a.stride - a.pt, ix0 = ox * a.stride - a.pl;
-        const int org = (iy0 * a.W + ix0) * cib;                       // window origin inside the image, may be negative
+        const int org = (iy0 * a.W + ix0) * (f.plain_input ? 1 : cib); // window origin inside the image, may be negative
         const float *image = a.in + (size_t)n * a.H * a.W * cib;
         valid[wm] = 0;
 #pragma unroll
@@ -549,8 +551,14 @@ const char *conv_kernel_name(const LayerGeom &g)
     return name;
 }
 
+bool conv_takes_plain_input(const LayerGeom &g, const void *in, const void *filt, const void *out, const void *res)
+{
+    const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt | (uintptr_t)res) & 15u) == 0);
+    return aligned && first_mfma_steps(g) && use_small(g);
+}
+
 hipError_t launch_conv(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g, int epilogue,
-                       hipStream_t s)
+                       hipStream_t s, bool plain_input)
 {
     ConvArgs a;
     a.in = in; a.filt = filt; a.out = out; a.res = (epilogue & EPI_ADD) ? res : out;
@@ -562,10 +570,12 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
     a.epilogue = epilogue;
 
     const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt | (uintptr_t)a.res) & 15u) == 0);
+    if (plain_input && !conv_takes_plain_input(g, in, filt, out, a.res)) return hipErrorInvalidValue;
     if (aligned && first_mfma_steps(g) && use_small(g)) {
         FirstArgs f;
         f.c = a;
         f.Cib = g.Cib; f.Cob = g.Cob; f.K = g.Cib * g.kh * g.kw;
+        f.plain_input = plain_input ? 1 : 0;
         f.div_HoWo = make_fastdiv(a.HoWo);
         f.div_Wo = make_fastdiv(g.Wo);
         const dim3 grid((unsigned)((a.M + 255) / 256), (unsigned)a.nCob);

@@ -82,11 +82,11 @@ int plan_conv(ConvPlan &p, int N, int Ci, int Co, int H, int W, int kh, int kw, 
 }
 
 int run_conv(const float *in, const float *filt, float *out, const float *res, const ConvPlan &p, int epilogue,
-             hipStream_t s)
+             hipStream_t s, bool plain_input = false)
 {
     if (!in || !filt || !out) return SMALL_ERR_NULL;
     if (overlap(in, p.in_elems, out, p.out_elems) || overlap(filt, p.filt_elems, out, p.out_elems)) return SMALL_ERR_ALIAS;
-    return from_hip(launch_conv(in, filt, out, res, p.g, epilogue, s));
+    return from_hip(launch_conv(in, filt, out, res, p.g, epilogue, s, plain_input));
 }
 
 }  // namespace
@@ -589,8 +589,10 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
 // Walks the table once: validates every layer, tracks the shape held by every logical buffer and
 // the largest tensor written to every workspace slot. With `run` set, launches as it goes (the
 // caller has already walked the table once without `run`, so no error can occur midway).
+// in_plain: the network input is a plain [N][C0][H0][W0] tensor; only layer 0 may read it, and only as a
+// convolution that launch_conv can feed from a plain tensor (the layout change then happens inside that kernel).
 int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &plan, bool run, const float *in_blocked,
-         float *out_blocked, char *ws, hipStream_t s, int first = 0, int count = INT_MAX)
+         float *out_blocked, char *ws, hipStream_t s, int first = 0, int count = INT_MAX, bool in_plain = false)
 {
     if (!L) return SMALL_ERR_NULL;
     if (nL <= 0 || N <= 0 || C0 <= 0 || H0 <= 0 || W0 <= 0) return SMALL_ERR_SHAPE;
@@ -626,6 +628,7 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
         }
         const bool launch = run && head && i >= first && (long)i < (long)first + count;
         if (!valid_id(l.src) || !valid_id(l.dst) || l.dst == SMALL_BUF_IN) return SMALL_ERR_LAYER;
+        if (in_plain && reads(l, SMALL_BUF_IN) && !(i == 0 && l.op == SMALL_OP_CONV)) return SMALL_ERR_LAYER;
         const Shape a = shp[idx(l.src)];
         if (!a.set || a.C != l.Ci || a.Cb != l.Cib) return SMALL_ERR_LAYER;
         Shape o = a;
@@ -644,6 +647,14 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.dst == l.src) return SMALL_ERR_ALIAS;
                 if (!l.filt) return SMALL_ERR_NULL;
                 o = Shape{l.Co, p.g.Ho, p.g.Wo, l.Cob, true};
+                const bool plain = in_plain && i == 0;
+                if (plain) {
+                    if (fu.chain) return SMALL_ERR_LAYER;        // a pointwise run does not start from a plain tensor
+                    const bool with_ptrs = run && head;
+                    if (!conv_takes_plain_input(p.g, with_ptrs ? ptr(l.src) : nullptr, with_ptrs ? l.filt : nullptr,
+                                                with_ptrs ? ptr(fu.out_id) : nullptr, with_ptrs ? ptr(fu.res_id) : nullptr))
+                        return SMALL_ERR_LAYER;
+                }
                 if (run && head && fu.chain) {
                     // the one-kernel run of pointwise layers needs aligned pointers and 32-bit input offsets;
                     // otherwise every layer of the run is planned on its own
@@ -665,7 +676,7 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                     }
                     rc = from_hip(launch_dense_chain(ptr(l.src), ptr(fu.out_id), cl, fu.chain, (long)N * a.H * a.W, a.H * a.W, s));
                 } else if (launch) {
-                    rc = run_conv(ptr(l.src), l.filt, ptr(fu.out_id), ptr(fu.res_id), p, fu.epilogue, s);
+                    rc = run_conv(ptr(l.src), l.filt, ptr(fu.out_id), ptr(fu.res_id), p, fu.epilogue, s, plain);
                 }
                 break;
             }
@@ -784,7 +795,14 @@ int small_network_launches(const small_layer *layers, int n_layers, int *first_l
 
 static int network_run_impl(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
                             void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first, int count,
-                            void *stream);
+                            void *stream, bool in_plain = false);
+
+int small_network_run_plain(const small_layer *layers, int n_layers, const float *in_nchw, float *out_blocked,
+                            void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream)
+{
+    return network_run_impl(layers, n_layers, in_nchw, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, 0,
+                            INT_MAX, stream, true);
+}
 
 int small_network_run_range(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
                             void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first, int count,
@@ -804,10 +822,10 @@ int small_network_run(const small_layer *layers, int n_layers, const float *in_b
 
 static int network_run_impl(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
                             void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first, int count,
-                            void *stream)
+                            void *stream, bool in_plain)
 {
     NetPlan plan;
-    int rc = walk(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr);
+    int rc = walk(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr, 0, INT_MAX, in_plain);
     if (rc) return rc;
     if (!in_blocked || !out_blocked) return SMALL_ERR_NULL;
     if (plan.bytes && !workspace) return SMALL_ERR_NULL;
@@ -818,7 +836,7 @@ static int network_run_impl(const small_layer *layers, int n_layers, const float
                         overlap(out_blocked, plan.out_elems, workspace, ws_elems))))
         return SMALL_ERR_ALIAS;
     return walk(layers, n_layers, N, C0, H0, W0, plan, true, in_blocked, out_blocked, static_cast<char *>(workspace),
-                as_stream(stream), first, count);
+                as_stream(stream), first, count, in_plain);
 }
 
 }  // extern "C"

@@ -96,7 +96,11 @@ hipError_t launch_avgpool_dense(const float *in, const float *filt, float *out, 
 // res: tensor added to the result when epilogue has EPI_ADD (may be `out` itself: each lane reads the
 // elements it is about to write), else ignored.
 hipError_t launch_conv(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
-                       int epilogue, hipStream_t s);
+                       int epilogue, hipStream_t s, bool plain_input = false);
+// plain_input: `in` is a plain [N][Ci][H][W] tensor instead of a blocked one. Only the first-layer matrix-core kernel
+// takes that (one input block of fewer than 16 channels, a reduction of 5..8, 25..28 or 37..40 values, at least
+// 16384 output pixels, 16-byte aligned pointers); conv_takes_plain_input tells, and launch_conv fails otherwise.
+bool conv_takes_plain_input(const LayerGeom &g, const void *in, const void *filt, const void *out, const void *res);
 // Name of the kernel launch_conv picks for this geometry when all pointers are 16-byte aligned.
 const char *conv_kernel_name(const LayerGeom &g);
 

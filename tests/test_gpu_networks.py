@@ -7,7 +7,7 @@ import torch
 import paper_2303_04769_amd as S
 import workloads as WL
 from oracle import oracle as O
-from gpu_util import DEV, Guarded, assert_bits, assert_close, dev
+from gpu_util import CANARY, DEV, Guarded, assert_bits, assert_close, dev
 
 pytestmark = pytest.mark.gpu
 
@@ -511,3 +511,81 @@ def test_fusion_keeps_table_semantics():
     got = _run(net, x, ws)
     ref = O.pool2d(O.relu(O.add(d, e)), (9, 9), 1, mode="avg")
     assert_close(got, ref, 144, "fusion probe (folded)")
+
+
+def _run_both(net, x, ws):
+    """Blocked outputs of small_pack + small_network_run and of small_network_run_plain on the same input."""
+    N = x.shape[0]
+    pn = S.PackedNetwork(net, ws, DEV)
+    xd = dev(x)
+    g0, g1 = Guarded(pn.out_elems(N)), Guarded(pn.out_elems(N))
+    pn.run(pn.pack_input(xd), g0.t, N)
+    before = xd.clone()
+    pn.run_plain(xd, g1.t, N)
+    out0, out1 = g0.check(), g1.check()
+    assert torch.equal(xd, before), "the plain input was written"
+    return out0, out1
+
+
+@pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 16), ("residual_cnn", 2, 37), ("dsep_cnn", 3, 8),
+                                        ("dsep_cnn", 3, 19), ("audio_cnn", 4, 132), ("audio_cnn", 4, 301)])
+def test_run_from_plain_input(name, idx, N):
+    """The first layer reads the plain tensor itself: same bits as packing first (the same products are added in
+    the same order), and the sampled images agree with the oracle."""
+    net = getattr(WL, name)()
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + idx + 20)
+    out0, out1 = _run_both(net, x, ws)
+    assert_bits(out1, out0, f"{name} N={N}: plain input vs packed input")
+    L = net.layers[-1]
+    got = O.unpack(out1, (N, L.Co, L.Ho, L.Wo), L.Cob).reshape(N, -1)
+    for n in (0, N // 2, N - 1):
+        assert_close(got[n:n + 1], O.run_network(net, x[n:n + 1], ws), _maxK(net), f"{name} image {n} of {N}")
+
+
+def test_run_from_plain_input_refuses_what_it_cannot_take():
+    """Too few output pixels for the first-layer kernel, a first layer that is not a convolution, or a later layer
+    that reads the network input: error 7, nothing written."""
+    from workloads.nets import Layer, Network, IN, OUT
+    cases = [(WL.residual_cnn(), 15), (WL.audio_cnn(), 131), (WL.dense_autoencoder(), 4096),
+             (WL.single_conv_relu(), 64)]
+    probe = Network("reads_input_twice", 3, 32, 32)
+    probe.wshapes = [((16, 3, 3, 3), 27), ((16, 3, 3, 3), 27)]
+    p1 = (1, 1, 1, 1)
+    probe.layers = [
+        Layer("conv", 3, 16, 32, 32, 3, 3, 1, p1, src=IN, dst=0, w=0),
+        Layer("conv", 3, 16, 32, 32, 3, 3, 1, p1, src=IN, dst=1, w=1),
+        Layer("add", 16, 16, 32, 32, src=0, src2=1, dst=OUT),
+    ]
+    cases.append((probe, 32))
+    for net, N in cases:
+        x, ws = WL.network_tensors(net, N, 7)
+        pn = S.PackedNetwork(net, ws, DEV)
+        g = Guarded(pn.out_elems(N))
+        with pytest.raises(S.SmallError) as e:
+            pn.run_plain(dev(x), g.t, N)
+        assert e.value.code == 7, net.name
+        assert (g.check() == np.float32(CANARY)).all(), f"{net.name}: output written despite the error"
+        # the same table runs from a packed input
+        g2 = Guarded(pn.out_elems(N))
+        pn.run(pn.pack_input(dev(x)), g2.t, N)
+        assert np.isfinite(g2.check()).all()
+
+
+def test_run_from_plain_input_with_first_layer_into_add():
+    """First layer whose result a later add reads (kept buffer) and which carries a fused ReLU."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("plain_first_kept", 3, 40, 24)
+    net.wshapes = [((16, 3, 3, 3), 27), ((16, 16, 1, 1), 16)]
+    net.layers = [
+        Layer("conv", 3, 16, 40, 24, 3, 3, 2, (0, 1, 0, 1), src=IN, dst=0, w=0),
+        Layer("relu", 16, 16, 20, 12, src=0, dst=0),
+        Layer("conv", 16, 16, 20, 12, 1, 1, 1, (0, 0, 0, 0), src=0, dst=1, w=1),
+        Layer("add", 16, 16, 20, 12, src=1, src2=0, dst=OUT),
+    ]
+    N = 70
+    x, ws = WL.network_tensors(net, N, 123)
+    out0, out1 = _run_both(net, x, ws)
+    assert_bits(out1, out0, "plain vs packed")
+    a = O.relu(O.conv2d(x[:3], ws[0], 2, (0, 1, 0, 1)))
+    ref = O.add(O.conv2d(a, ws[1], 1, (0, 0, 0, 0)), a)
+    assert_close(O.unpack(out1, (N, 16, 20, 12), 16)[:3], ref, 27, "plain first layer, kept")
