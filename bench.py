@@ -139,10 +139,12 @@ def main():
     # ------------------------------------------------------------------ per-launch timing of the same launches
     # small_network_run folds ReLU / residual add into the producing convolution; every launch of the
     # step is replayed on its own through small_network_run_range between two events.
-    heads = S.small_network_launches(pn.table)
+    heads = pn.launches_at(N)
     groups = [net.layers[h:(heads[k + 1] if k + 1 < len(heads) else len(net.layers))] for k, h in enumerate(heads)]
 
-    def kernel_of(L):
+    def kernel_of(L, g=()):
+        if sum(x.op == "conv" for x in g) > 1:
+            return "resident_run"          # several convolutions in one launch: the image-resident run
         if L.op == "conv":
             return S.small_conv2d_kernel(N, L.Ci, L.Co, L.H, L.W, L.kh, L.kw, L.stride, L.pad, L.Cib, L.Cob)
         if L.op == "dense":
@@ -166,15 +168,23 @@ def main():
             continue
         for g, a, b in evs:
             L = g[0]
-            k = per_kernel.setdefault(kernel_of(L), {"time": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0,
+            k = per_kernel.setdefault(kernel_of(L, g), {"time": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0,
                                                      "fused": "+".join(x.op for x in g)})
             k["time"] += a.elapsed_time(b) * 1e-3 / REP
             k["launches"] += 1
             n_in, n_out = N * L.Ci * L.H * L.W, N * L.Co * L.Ho * L.Wo
-            if L.op in ("conv", "dense"):
+            if kernel_of(L, g) == "resident_run":
+                # HBM sees the run's input, its last result and the filters once; the flops are those of every layer
+                convs = [x for x in g if x.op == "conv"]
+                k["flops"] += sum(2.0 * N * x.Co * x.Ho * x.Wo * x.Ci * x.kh * x.kw for x in convs)
+                n_in += sum(x.Co * x.Ci * x.kh * x.kw for x in convs)
+                n_out = N * convs[-1].Co * convs[-1].Ho * convs[-1].Wo
+            elif L.op in ("conv", "dense"):
                 k["flops"] += 2.0 * N * L.Co * L.Ho * L.Wo * L.Ci * L.kh * L.kw
                 n_in += L.Co * L.Ci * L.kh * L.kw
-            if L.op == "add" or any(x.op == "add" for x in g[1:]):
+                if any(x.op == "add" for x in g[1:]):
+                    n_in += n_out
+            elif L.op == "add":
                 n_in += n_out
             k["bytes"] += 4.0 * (n_in + n_out)
     dom_name, dom = max(per_kernel.items(), key=lambda kv: kv[1]["time"])

@@ -218,6 +218,26 @@ int small_network_run(const small_layer *layers, int n_layers, const float *in_b
 int small_network_run_plain(const small_layer *layers, int n_layers, const float *in_nchw, float *out_blocked,
                             void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream);
 
+/* small_network_run_opt: small_network_run with options (flags, a sum of SMALL_RUN_*; unknown bits: SMALL_ERR_SHAPE).
+ *   SMALL_RUN_PLAIN_INPUT   `in` is a plain [N][C0][H0][W0] tensor: exactly small_network_run_plain.
+ *   SMALL_RUN_RESIDENT_OFF  never use image-resident runs (below); SMALL_RUN_RESIDENT_ON: use them at any batch size.
+ * Image-resident runs: consecutive convolutions (16-channel blocks in and out, 1 or 9 filter taps, any stride and
+ * padding, with their folded ReLU / residual add) whose per-image tensors fit 160 KB of LDS together run as ONE
+ * launch, one image per workgroup (256 workgroups, further images in further rounds): only the run's input, its
+ * last result and the filters touch HBM; the tensors between them are never written (allowed only when nothing
+ * outside the run reads them, as for every fusion here). This is the fused layer of the paper's "Conclusion &
+ * Future Directions" across layers of Table 1's partial-reduction class. Without either RESIDENT flag such runs
+ * are used when N >= 128 and N fills at least 3/4 of ceil(N / 256) * 256; small_network_run,
+ * small_network_run_plain and small_network_run_range follow that rule too. Results agree with the layer-by-layer
+ * kernels within the conv tolerance, not bit for bit (another summation order).
+ * small_network_launches_at: the first layer of every launch that a run with these N, C0, H0, W0 and flags makes
+ * (small_network_launches: the batch-independent list without image-resident runs). Host-only, no GPU needed. */
+enum { SMALL_RUN_PLAIN_INPUT = 1, SMALL_RUN_RESIDENT_OFF = 2, SMALL_RUN_RESIDENT_ON = 4 };
+int small_network_run_opt(const small_layer *layers, int n_layers, const float *in, float *out_blocked, void *workspace,
+                          size_t workspace_bytes, int N, int C0, int H0, int W0, unsigned flags, void *stream);
+int small_network_launches_at(const small_layer *layers, int n_layers, int N, int C0, int H0, int W0, unsigned flags,
+                              int *first_layer, int *n_launches);
+
 /* Cross-layer fusion. small_network_run folds layers that only touch a convolution's output element by
  * element into that convolution's store phase (the direction the paper's conclusion calls an abstract
  * "fused" layer, possible because every layer shares one layout): a ReLU in place on the output of a

@@ -23,7 +23,7 @@ EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "sma
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
            "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_probe_mfma", "small_pack_u8", "small_unpack_u8",
            "small_pack_filter_u8", "small_filter_sums_u8", "small_conv2d_u8", "small_dwconv2d_u8", "small_dense_u8", "small_pool2d_u8", "small_relu_u8",
-           "small_network_workspace", "small_network_run", "small_network_run_plain", "small_network_launches",
+           "small_network_workspace", "small_network_run", "small_network_run_plain", "small_network_run_opt", "small_network_launches", "small_network_launches_at",
            "small_network_run_range"]
 
 
@@ -92,6 +92,9 @@ def load():
         "small_network_workspace": (i, [C.POINTER(small_layer), i, i, i, i, i, C.POINTER(sz)]),
         "small_network_run": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
         "small_network_run_plain": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
+        "small_network_run_opt": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, C.c_uint, p]),
+        "small_network_launches_at": (i, [C.POINTER(small_layer), i, i, i, i, i, C.c_uint, C.POINTER(C.c_int),
+                                          C.POINTER(C.c_int)]),
         "small_network_launches": (i, [C.POINTER(small_layer), i, C.POINTER(i), C.POINTER(i)]),
         "small_network_run_range": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, i, i, p]),
     }
@@ -295,6 +298,24 @@ def small_network_run_plain(table, in_nchw, out_blocked, workspace, workspace_by
                                           workspace_bytes, N, C0, H0, W0, _stream(stream)), "small_network_run_plain")
 
 
+SMALL_RUN_PLAIN_INPUT, SMALL_RUN_RESIDENT_OFF, SMALL_RUN_RESIDENT_ON = 1, 2, 4
+
+
+def small_network_run_opt(table, in_tensor, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, flags, stream=None):
+    _check(load().small_network_run_opt(table, len(table), _ptr(in_tensor), _ptr(out_blocked),
+                                        C.c_void_p(workspace.data_ptr()) if workspace is not None else None,
+                                        workspace_bytes, N, C0, H0, W0, flags, _stream(stream)), "small_network_run_opt")
+
+
+def small_network_launches_at(table, N, C0, H0, W0, flags=0):
+    """List of first-layer indices, one per kernel launch of a run with this batch size and these flags."""
+    first = (C.c_int * len(table))()
+    n = C.c_int(0)
+    _check(load().small_network_launches_at(table, len(table), N, C0, H0, W0, flags, first, C.byref(n)),
+           "small_network_launches_at")
+    return list(first[:n.value])
+
+
 def small_network_launches(table):
     """List of first-layer indices, one per kernel launch of small_network_run."""
     first = (C.c_int * len(table))()
@@ -351,6 +372,14 @@ class PackedNetwork:
         ws, nbytes = self.workspace(N)
         small_network_run(self.table, in_blocked, out_blocked, ws, nbytes, N, self.net.C0, self.net.H0, self.net.W0,
                           stream)
+
+    def run_opt(self, in_tensor, out_blocked, N, flags, stream=None):
+        ws, nbytes = self.workspace(N)
+        small_network_run_opt(self.table, in_tensor, out_blocked, ws, nbytes, N, self.net.C0, self.net.H0, self.net.W0,
+                              flags, stream)
+
+    def launches_at(self, N, flags=0):
+        return small_network_launches_at(self.table, N, self.net.C0, self.net.H0, self.net.W0, flags)
 
     def run_plain(self, in_nchw, out_blocked, N, stream=None):
         """The run from a plain [N][C0][H0][W0] input (no small_pack launch); raises SmallError with

@@ -1,0 +1,432 @@
+// A run of convolutions in one kernel, one image per workgroup, every tensor between them in LDS.
+//
+// The small networks of Section "MLPerf:Tiny Inference Models" have activations of a few tens of kilobytes per
+// image: 16 x 32 x 32 floats are 64 KB, and a compute unit of this chip has 160 KB of LDS. So a workgroup can
+// take one image through a whole run of convolution layers (with their folded ReLU / residual add, Table 2) and
+// touch HBM only for the run's input, its last output and the filters (which all workgroups share through L2).
+// This is the abstract fused layer of the paper's "Conclusion & Future Directions" taken across layers of the
+// partial-reduction class of Table 1, where a pixel tile cannot be carried from layer to layer because of the
+// halo: the whole image is the tile. What it removes is per-launch cost (ramp, drain, the gap between dependent
+// kernels), which dominates layer-by-layer runs of these networks at a batch of a few hundred images.
+//
+// LDS layout. Every tensor of the run lives in LDS in the blocked layout [C/16][rows][pixels][16], zero-padded
+// by as many rows / columns as its consumers' windows reach outside the image, so that the reduction loop reads
+// with no bounds test at all: the address of an input value is (tile base) + (tap, input block offset), the
+// second term wave-uniform. A layer's workgroup first clears the border of its output tensor, then computes the
+// interior; a barrier separates layers. Regions are handed out by the host from the tensors' lifetimes; the
+// result of a convolution with a residual add overwrites the residual in place when nothing else reads it
+// (each lane reads exactly the elements it then writes), which is what lets the 16-channel stage of the
+// residual CNN (three live 72 KB tensors in the table) fit.
+//
+// Work split. 8 waves. A wave takes (output channel block, group of T 16-pixel tiles) pairs; per reduction step
+// (input block, tap) it reads T float4 B operands from LDS and 4 A operands (filter values, from global memory,
+// L2-resident, requested one input block ahead) and issues 4 T matrix instructions:
+//   A (filter):  lane (p = l % 16, q = l / 16) in MFMA j supplies filt[ci = 4q + j][co = p];
+//   B (input):   lane (p, q) supplies channels 4q .. 4q + 3 of pixel p as one float4 (MFMA j takes element j);
+//   D (output):  lane (p, q) receives channels 4q .. 4q + 3 of pixel p: the B layout again, stored as one float4.
+#include "small_internal.h"
+
+#include <string.h>
+
+namespace small {
+namespace {
+
+constexpr int kResWaves = 8;
+constexpr int kResThreads = kResWaves * 64;
+constexpr int kResLdsBytes = 160 * 1024;
+constexpr int kResMaxTaps = 9;
+constexpr int kResMaxIds = 40;      // logical buffer ids + 2, as the runner numbers them
+
+// A tensor in LDS. Units: float4 for `off`, pixels (= 4 float4) for the rest.
+struct ResTensorDev {
+    int off;      // first padded pixel of channel block 0
+    int Wp;       // padded row length
+    int plane;    // padded pixels per channel block
+    int org;      // index inside a plane of image pixel (0, 0)
+};
+
+struct ResLayerDev {
+    const float *filt;
+    ResTensorDev in, out, res;      // out.off < 0: the run's last layer, the result goes to HBM
+    int Wo, HoWo, nCib, nCob, stride, taps;
+    int win0;                       // index inside an input plane of the window origin of output pixel (0, 0)
+    int epilogue, T, nTg, nGroups;  // nTg: tile groups per output block; nGroups = nCob * nTg
+    int tapoff[kResMaxTaps];        // dy * in.Wp + dx
+    int oH, oW, opt, opb, opl, opr; // the output tensor's image size and padding (border clearing)
+    FastDiv div_Wo, div_nTg;
+};
+
+struct ResArgs {
+    const float *in;
+    float *out;
+    int N, n_layers;
+    ResTensorDev src;               // where the run's input goes
+    int sH, sW, snCb, spt, spb, spl, spr;
+    int in_f4, out_f4;              // float4 per image of the run's input and output in HBM
+    FastDiv div_sW, div_sH;
+    ResLayerDev layer[kResMaxLayers];
+};
+
+typedef const __attribute__((address_space(4))) ResArgs *ResKernArgs;
+
+__device__ __forceinline__ const float *uniform_ptr(const float *p)
+{
+    const uintptr_t v = (uintptr_t)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return (const float *)(((uintptr_t)hi << 32) | lo);
+}
+
+// Clears the padding rows and columns of a tensor at float4 index `off` (all threads of the workgroup).
+__device__ __forceinline__ void clear_border(floatx4 *lds, int off, int nCb, int H, int W, int pt, int pb, int pl, int pr)
+{
+    const int Wp = pl + W + pr, plane4 = (pt + H + pb) * Wp * 4;
+    const int top = pt * Wp * 4, bot = pb * Wp * 4, side = (pl + pr) * 4, per = top + bot + H * side;
+    if (per == 0) return;
+    for (int i = (int)threadIdx.x; i < per * nCb; i += kResThreads) {
+        const int cb = i / per, r = i - cb * per;
+        int idx;
+        if (r < top) {
+            idx = r;
+        } else if (r < top + bot) {
+            idx = (pt + H) * Wp * 4 + (r - top);
+        } else {
+            const int j = r - top - bot, row = j / side, k = j - row * side, px = k >> 2;
+            idx = ((pt + row) * Wp + (px < pl ? px : W + px)) * 4 + (k & 3);
+        }
+        lds[off + cb * plane4 + idx] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
+}
+
+template <int T, int TAPS>
+__device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *lds, floatx4 *gout, int w, int lane)
+{
+    const int p = lane & 15, q = lane >> 4;
+    const float *const filt = ka->layer[li].filt;
+    const int in_off = ka->layer[li].in.off, in_Wp = ka->layer[li].in.Wp, in_plane = ka->layer[li].in.plane;
+    const int out_off = ka->layer[li].out.off, out_Wp = ka->layer[li].out.Wp, out_plane = ka->layer[li].out.plane,
+              out_org = ka->layer[li].out.org;
+    const int res_off = ka->layer[li].res.off, res_Wp = ka->layer[li].res.Wp, res_plane = ka->layer[li].res.plane,
+              res_org = ka->layer[li].res.org;
+    const int Wo = ka->layer[li].Wo, HoWo = ka->layer[li].HoWo, nCib = ka->layer[li].nCib, stride = ka->layer[li].stride;
+    const int win0 = ka->layer[li].win0, epilogue = ka->layer[li].epilogue;
+    const int nTg = ka->layer[li].nTg, nGroups = ka->layer[li].nGroups;
+    FastDiv div_Wo, div_nTg;
+    div_Wo.magic = ka->layer[li].div_Wo.magic; div_Wo.shift = ka->layer[li].div_Wo.shift; div_Wo.d = ka->layer[li].div_Wo.d;
+    div_nTg.magic = ka->layer[li].div_nTg.magic; div_nTg.shift = ka->layer[li].div_nTg.shift; div_nTg.d = ka->layer[li].div_nTg.d;
+    int tapoff[TAPS];
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t) tapoff[t] = ka->layer[li].tapoff[t] * 4;
+
+    for (int g = w; g < nGroups; g += kResWaves) {
+        const int cob = div_nTg.div(g), tg = g - cob * nTg;
+        int base[T], m[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            m[t] = (tg * T + t) * 16 + p;
+            const int mc = m[t] < HoWo ? m[t] : HoWo - 1;
+            const int oy = div_Wo.div(mc), ox = mc - oy * Wo;
+            base[t] = in_off + (win0 + oy * stride * in_Wp + ox * stride) * 4 + q;
+        }
+        floatx4 acc[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+        // filter values of this lane: block (cob, cib), tap, row ci = 4q + j, column co = p
+        const float *fa = uniform_ptr(filt + (size_t)cob * nCib * TAPS * 256) + (4 * q) * 16 + p;
+        float a_next[TAPS][4];
+#pragma unroll
+        for (int tap = 0; tap < TAPS; ++tap)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a_next[tap][j] = fa[tap * 256 + j * 16];
+
+        for (int cib = 0; cib < nCib; ++cib) {
+            const int coff = cib * in_plane * 4;
+            // the next input block's filter values (the last block asks for its own again: same number of
+            // requests in every round, none past the filter)
+            const float *fn = fa + (size_t)(cib + 1 < nCib ? cib + 1 : cib) * TAPS * 256;
+#pragma unroll
+            for (int tap = 0; tap < TAPS; ++tap) {
+                floatx4 b[T];
+#pragma unroll
+                for (int t = 0; t < T; ++t) b[t] = lds[base[t] + coff + tapoff[tap]];
+                float a[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    a[j] = a_next[tap][j];
+                    a_next[tap][j] = fn[tap * 256 + j * 16];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int t = 0; t < T; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j], b[t][j], acc[t], 0, 0, 0);
+            }
+        }
+
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            if (m[t] >= HoWo) continue;
+            const int oy = div_Wo.div(m[t]), ox = m[t] - oy * Wo;
+            floatx4 v = acc[t];
+            if (epilogue & EPI_ADD) v += lds[res_off + (cob * res_plane + res_org + oy * res_Wp + ox) * 4 + q];
+            if (epilogue & EPI_RELU) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
+            }
+            if (out_off >= 0) lds[out_off + (cob * out_plane + out_org + oy * out_Wp + ox) * 4 + q] = v;
+            else gout[(cob * HoWo + m[t]) * 4 + q] = v;
+        }
+    }
+}
+
+__global__ void __launch_bounds__(kResThreads) resident_run(ResArgs args)
+{
+    (void)args;
+    const ResKernArgs ka = (ResKernArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    extern __shared__ floatx4 lds[];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int N = ka->N, n_layers = ka->n_layers, in_f4 = ka->in_f4, out_f4 = ka->out_f4;
+    const int s_off = ka->src.off, s_Wp = ka->src.Wp, s_plane = ka->src.plane, s_org = ka->src.org;
+    const int sH = ka->sH, sW = ka->sW;
+    FastDiv div_sW, div_sH;
+    div_sW.magic = ka->div_sW.magic; div_sW.shift = ka->div_sW.shift; div_sW.d = ka->div_sW.d;
+    div_sH.magic = ka->div_sH.magic; div_sH.shift = ka->div_sH.shift; div_sH.d = ka->div_sH.d;
+
+    for (int n = (int)blockIdx.x; n < N; n += (int)gridDim.x) {
+        // the image's input tensor: HBM [cb][y][x] pixels -> its padded place in LDS
+        const floatx4 *gin = reinterpret_cast<const floatx4 *>(ka->in) + (size_t)n * in_f4;
+#pragma unroll 4
+        for (int i = (int)threadIdx.x; i < in_f4; i += kResThreads) {
+            const int pixel = i >> 2;
+            const int cbrow = div_sW.div(pixel), x = pixel - cbrow * sW;
+            const int cb = div_sH.div(cbrow), y = cbrow - cb * sH;
+            lds[s_off + (cb * s_plane + s_org + y * s_Wp + x) * 4 + (i & 3)] = gin[i];
+        }
+        clear_border(lds, s_off, ka->snCb, sH, sW, ka->spt, ka->spb, ka->spl, ka->spr);
+        __syncthreads();
+
+        floatx4 *gout = reinterpret_cast<floatx4 *>(ka->out) + (size_t)n * out_f4;
+        for (int li = 0; li < n_layers; ++li) {
+            if (ka->layer[li].out.off >= 0)
+                clear_border(lds, ka->layer[li].out.off, ka->layer[li].nCob, ka->layer[li].oH, ka->layer[li].oW,
+                             ka->layer[li].opt, ka->layer[li].opb, ka->layer[li].opl, ka->layer[li].opr);
+            const int T = ka->layer[li].T, taps = ka->layer[li].taps;
+            if (taps == 9) {
+                if (T == 4) resident_conv<4, 9>(ka, li, lds, gout, w, lane);
+                else if (T == 2) resident_conv<2, 9>(ka, li, lds, gout, w, lane);
+                else resident_conv<1, 9>(ka, li, lds, gout, w, lane);
+            } else {
+                if (T == 4) resident_conv<4, 1>(ka, li, lds, gout, w, lane);
+                else if (T == 2) resident_conv<2, 1>(ka, li, lds, gout, w, lane);
+                else resident_conv<1, 1>(ka, li, lds, gout, w, lane);
+            }
+            __syncthreads();   // the layer's output is complete, its input may be overwritten
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ host side
+
+struct Pads { int t, b, l, r; };
+
+struct Instance {          // one tensor of the run
+    int C, H, W;
+    Pads pad;
+    int last_use;          // last group that reads it (-1: none)
+    int off, bytes;        // LDS region
+};
+
+inline int imax(int a, int b) { return a > b ? a : b; }
+
+// First fit over the regions in use (at most a handful).
+int first_fit(const int (*used)[2], int n_used, int bytes, int capacity)
+{
+    int at = 0;
+    for (;;) {
+        bool moved = false;
+        for (int k = 0; k < n_used; ++k) {
+            if (at < used[k][0] + used[k][1] && used[k][0] < at + bytes) {
+                at = used[k][0] + used[k][1];
+                moved = true;
+            }
+        }
+        if (!moved) break;
+    }
+    return at + bytes <= capacity ? at : -1;
+}
+
+bool group_ok(const ResGroup &g)
+{
+    const int taps = g.kh * g.kw;
+    return g.filt && g.Cib == 16 && g.Cob == 16 && g.Ci > 0 && g.Co > 0 && g.Ci % 16 == 0 && g.Co % 16 == 0 &&
+           (taps == 1 || taps == 9) && g.stride >= 1 && g.Ho > 0 && g.Wo > 0 && g.pt >= 0 && g.pl >= 0 &&
+           g.src + 2 >= 0 && g.src + 2 < kResMaxIds && g.dst + 2 >= 0 && g.dst + 2 < kResMaxIds &&
+           (!(g.epilogue & EPI_ADD) || (g.res + 2 >= 0 && g.res + 2 < kResMaxIds));
+}
+
+// Plans groups [0, n) as one run; false when a tensor is read that the run does not hold, or LDS does not fit.
+bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
+{
+    Instance inst[kResMaxLayers + 1];
+    int in_i[kResMaxLayers], res_i[kResMaxLayers], out_i[kResMaxLayers];
+    bool alias[kResMaxLayers];
+    int cur[kResMaxIds];
+    for (int k = 0; k < kResMaxIds; ++k) cur[k] = -1;
+    int n_inst = 1;
+    inst[0] = Instance{g[0].Ci, g[0].H, g[0].W, Pads{0, 0, 0, 0}, -1, -1, 0};
+    cur[g[0].src + 2] = 0;
+    for (int k = 0; k < n; ++k) {
+        const ResGroup &c = g[k];
+        in_i[k] = cur[c.src + 2];
+        res_i[k] = (c.epilogue & EPI_ADD) ? cur[c.res + 2] : -1;
+        if (in_i[k] < 0 || ((c.epilogue & EPI_ADD) && res_i[k] < 0)) return false;
+        const Instance &x = inst[in_i[k]];
+        if (x.C != c.Ci || x.H != c.H || x.W != c.W) return false;
+        if (res_i[k] >= 0 && (inst[res_i[k]].C != c.Co || inst[res_i[k]].H != c.Ho || inst[res_i[k]].W != c.Wo)) return false;
+        // rows / columns outside the image that the windows really reach
+        Pads &pd = inst[in_i[k]].pad;
+        pd.t = imax(pd.t, c.pt);
+        pd.l = imax(pd.l, c.pl);
+        pd.b = imax(pd.b, (c.Ho - 1) * c.stride - c.pt + c.kh - c.H);
+        pd.r = imax(pd.r, (c.Wo - 1) * c.stride - c.pl + c.kw - c.W);
+        inst[in_i[k]].last_use = k;
+        if (res_i[k] >= 0) inst[res_i[k]].last_use = k;
+        out_i[k] = n_inst;
+        inst[n_inst++] = Instance{c.Co, c.Ho, c.Wo, Pads{0, 0, 0, 0}, -1, -1, 0};
+        cur[c.dst + 2] = out_i[k];
+    }
+    // a residual that nothing else reads afterwards is overwritten in place: both tensors then share one padding
+    for (int k = 0; k < n; ++k) alias[k] = k + 1 < n && res_i[k] >= 0 && res_i[k] != in_i[k] && inst[res_i[k]].last_use == k;
+    for (int round = 0; round < n; ++round) {
+        for (int k = 0; k < n; ++k) {
+            if (!alias[k]) continue;
+            Pads &x = inst[res_i[k]].pad, &y = inst[out_i[k]].pad;
+            x.t = y.t = imax(x.t, y.t);
+            x.b = y.b = imax(x.b, y.b);
+            x.l = y.l = imax(x.l, y.l);
+            x.r = y.r = imax(x.r, y.r);
+        }
+    }
+    for (int k = 0; k < n_inst; ++k) {
+        const Pads &pd = inst[k].pad;
+        inst[k].bytes = (inst[k].C / 16) * (pd.t + inst[k].H + pd.b) * (pd.l + inst[k].W + pd.r) * 64;
+    }
+    // regions, in the order of the run
+    int used[kResMaxLayers + 1][2], used_inst[kResMaxLayers + 1], n_used = 0, peak = 0;
+    auto take = [&](int i, int off) {
+        inst[i].off = off;
+        used[n_used][0] = off;
+        used[n_used][1] = inst[i].bytes;
+        used_inst[n_used++] = i;
+        peak = imax(peak, off + inst[i].bytes);
+    };
+    auto release = [&](int i) {
+        for (int k = 0; k < n_used; ++k) {
+            if (used_inst[k] == i) {
+                --n_used;
+                used[k][0] = used[n_used][0];
+                used[k][1] = used[n_used][1];
+                used_inst[k] = used_inst[n_used];
+                return;
+            }
+        }
+    };
+    if (inst[0].bytes > kResLdsBytes) return false;
+    take(0, 0);
+    for (int k = 0; k < n; ++k) {
+        const int o = out_i[k];
+        if (k + 1 < n) {
+            if (alias[k]) {
+                inst[o].off = inst[res_i[k]].off;
+                for (int u = 0; u < n_used; ++u)
+                    if (used_inst[u] == res_i[k]) used_inst[u] = o;       // the region changes hands
+            } else {
+                const int off = first_fit(used, n_used, inst[o].bytes, kResLdsBytes);
+                if (off < 0) return false;
+                take(o, off);
+            }
+        }
+        if (inst[in_i[k]].last_use == k) release(in_i[k]);
+        if (res_i[k] >= 0 && !alias[k] && inst[res_i[k]].last_use == k) release(res_i[k]);
+        if (k + 1 < n && inst[o].last_use < 0) release(o);
+    }
+    lds_bytes = peak;
+
+    auto dev = [&](int i) {
+        const Instance &t = inst[i];
+        const int Wp = t.pad.l + t.W + t.pad.r;
+        return ResTensorDev{t.off / 16, Wp, (t.pad.t + t.H + t.pad.b) * Wp, t.pad.t * Wp + t.pad.l};
+    };
+    memset(&a, 0, sizeof(a));
+    a.n_layers = n;
+    a.src = dev(0);
+    a.sH = inst[0].H; a.sW = inst[0].W; a.snCb = inst[0].C / 16;
+    a.spt = inst[0].pad.t; a.spb = inst[0].pad.b; a.spl = inst[0].pad.l; a.spr = inst[0].pad.r;
+    a.in_f4 = a.snCb * a.sH * a.sW * 4;
+    a.out_f4 = (g[n - 1].Co / 16) * g[n - 1].Ho * g[n - 1].Wo * 4;
+    a.div_sW = make_fastdiv(a.sW);
+    a.div_sH = make_fastdiv(a.sH);
+    for (int k = 0; k < n; ++k) {
+        const ResGroup &c = g[k];
+        ResLayerDev &d = a.layer[k];
+        const Instance &x = inst[in_i[k]], &y = inst[out_i[k]];
+        d.filt = c.filt;
+        d.in = dev(in_i[k]);
+        d.out = k + 1 < n ? dev(out_i[k]) : ResTensorDev{-1, 0, 0, 0};
+        d.res = res_i[k] >= 0 ? dev(res_i[k]) : ResTensorDev{0, 0, 0, 0};
+        d.Wo = c.Wo; d.HoWo = c.Ho * c.Wo; d.nCib = c.Ci / 16; d.nCob = c.Co / 16; d.stride = c.stride; d.taps = c.kh * c.kw;
+        d.win0 = (x.pad.t - c.pt) * d.in.Wp + (x.pad.l - c.pl);
+        d.epilogue = c.epilogue;
+        // tiles per wave and step: the split that needs the fewest rounds of the 8 waves, the larger group on a tie
+        const int tiles = (d.HoWo + 15) / 16;
+        int best_cost = 1 << 30;
+        for (int T = 4; T >= 1; T >>= 1) {
+            const int groups = d.nCob * ((tiles + T - 1) / T);
+            const int cost = ((groups + kResWaves - 1) / kResWaves) * T;
+            if (cost < best_cost) {
+                best_cost = cost;
+                d.T = T;
+            }
+        }
+        d.nTg = (tiles + d.T - 1) / d.T;
+        d.nGroups = d.nCob * d.nTg;
+        for (int t = 0; t < d.taps; ++t) d.tapoff[t] = (t / c.kw) * d.in.Wp + (t % c.kw);
+        d.oH = y.H; d.oW = y.W; d.opt = y.pad.t; d.opb = y.pad.b; d.opl = y.pad.l; d.opr = y.pad.r;
+        d.div_Wo = make_fastdiv(c.Wo);
+        d.div_nTg = make_fastdiv(d.nTg);
+    }
+    return true;
+}
+
+}  // namespace
+
+int resident_groups(const ResGroup *g, int n, const bool *closed_after)
+{
+    if (n > kResMaxLayers) n = kResMaxLayers;
+    int ok = 0;
+    while (ok < n && group_ok(g[ok])) ++ok;
+    ResArgs local;
+    for (int e = ok; e >= 2; --e) {
+        int lds = 0;
+        if (closed_after[e - 1] && plan_prefix(g, e, local, lds)) return e;
+    }
+    return 0;
+}
+
+hipError_t launch_resident(const ResGroup *g, int n, const float *in, float *out, int N, hipStream_t s)
+{
+    ResArgs a;
+    int lds = 0;
+    if (n < 2 || n > kResMaxLayers || !plan_prefix(g, n, a, lds)) return hipErrorInvalidValue;
+    a.in = in;
+    a.out = out;
+    a.N = N;
+    static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(resident_run),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kResLdsBytes);
+    if (attr != hipSuccess) return attr;
+    const int grid = N < kResidentWorkgroups ? N : kResidentWorkgroups;
+    hipLaunchKernelGGL(resident_run, dim3((unsigned)grid), dim3(kResThreads), (size_t)lds, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace small

@@ -586,14 +586,72 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
     return f;
 }
 
+// The convolution groups from layer i on that may run as one image-resident launch (resident.hip): fills rg
+// and the table index of every group's last layer, returns how many groups the launch takes (0: none).
+// shp: the shapes the logical buffers hold before layer i (indexed by id + 2).
+int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now, ResGroup *rg, int *last_layer)
+{
+    Shape shp[SMALL_MAX_SLOTS + 2];
+    memcpy(shp, shp_now, sizeof(shp));
+    bool closed[kResMaxLayers];
+    unsigned long long produced = 0;      // buffers written inside the run so far
+    int n = 0, k = i;
+    while (k < nL && n < kResMaxLayers) {
+        const small_layer &l = L[k];
+        if (l.op != SMALL_OP_CONV || l.dst == l.src || l.dst == SMALL_BUF_IN || !l.filt) break;
+        if (l.src < SMALL_BUF_OUT || l.src >= SMALL_MAX_SLOTS || l.dst < SMALL_BUF_OUT || l.dst >= SMALL_MAX_SLOTS) break;
+        const Shape a = shp[l.src + 2];
+        if (!a.set || a.C != l.Ci || a.Cb != l.Cib) break;
+        ConvPlan p;
+        if (plan_conv(p, 1, l.Ci, l.Co, a.H, a.W, l.kh, l.kw, l.stride, l.pad, l.Cib, l.Cob)) break;
+        const Fusion fu = plan_fusion(L, nL, k, false);
+        if (fu.pw || fu.head || fu.chain) break;
+        const Shape o = Shape{l.Co, p.g.Ho, p.g.Wo, l.Cob, true};
+        if (fu.epilogue & EPI_ADD) {
+            const Shape r = shp[fu.res_id + 2];
+            if (!r.set || r.C != o.C || r.H != o.H || r.W != o.W || r.Cb != o.Cb) break;
+        }
+        rg[n] = ResGroup{l.filt, l.src, fu.res_id, fu.out_id, l.Ci, l.Co, l.Cib, l.Cob, a.H, a.W, p.g.Ho, p.g.Wo,
+                         l.kh, l.kw, l.stride, l.pad.t, l.pad.l, fu.epilogue};
+        shp[l.dst + 2] = o;
+        shp[fu.out_id + 2] = o;
+        const int next = k + 1 + fu.skip;
+        last_layer[n] = next - 1;
+        // closed: nothing the run has produced, other than this group's result, is read from here on
+        bool c = true;
+        for (int id = SMALL_BUF_OUT; id < SMALL_MAX_SLOTS; ++id)
+            if (((produced >> (id + 2)) & 1ull) && id != fu.out_id && !dead_from(L, nL, next, id)) c = false;
+        closed[n] = c;
+        produced |= 1ull << (fu.out_id + 2);
+        ++n;
+        k = next;
+    }
+    return n >= 2 ? resident_groups(rg, n, closed) : 0;
+}
+
+// Image-resident runs pay off when the batch fills the chip's compute units in whole rounds.
+bool resident_batch(int N, unsigned flags)
+{
+    if (flags & SMALL_RUN_RESIDENT_OFF) return false;
+    if (flags & SMALL_RUN_RESIDENT_ON) return true;
+    const int rounds = (N + kResidentWorkgroups - 1) / kResidentWorkgroups;
+    return N >= kResidentWorkgroups / 2 && 4 * N >= 3 * rounds * kResidentWorkgroups;
+}
+
 // Walks the table once: validates every layer, tracks the shape held by every logical buffer and
 // the largest tensor written to every workspace slot. With `run` set, launches as it goes (the
 // caller has already walked the table once without `run`, so no error can occur midway).
 // in_plain: the network input is a plain [N][C0][H0][W0] tensor; only layer 0 may read it, and only as a
 // convolution that launch_conv can feed from a plain tensor (the layout change then happens inside that kernel).
+// flags: SMALL_RUN_*; heads / n_heads (optional, without `run`): the first layer of every launch a run would make.
 int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &plan, bool run, const float *in_blocked,
-         float *out_blocked, char *ws, hipStream_t s, int first = 0, int count = INT_MAX, bool in_plain = false)
+         float *out_blocked, char *ws, hipStream_t s, int first = 0, int count = INT_MAX, unsigned flags = 0,
+         int *heads = nullptr, int *n_heads = nullptr)
 {
+    const bool in_plain = (flags & SMALL_RUN_PLAIN_INPUT) != 0;
+    const bool track = run || n_heads != nullptr;      // follow which layers start a launch
+    const bool resident = resident_batch(N, flags);
+    if (n_heads) *n_heads = 0;
     if (!L) return SMALL_ERR_NULL;
     if (nL <= 0 || N <= 0 || C0 <= 0 || H0 <= 0 || W0 <= 0) return SMALL_ERR_SHAPE;
     Shape shp[SMALL_MAX_SLOTS + 2];
@@ -618,13 +676,32 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
         const bool head = fused_away == 0;             // this layer starts a launch (it is not folded into an earlier one)
         if (fused_away > 0) --fused_away;
         Fusion fu = {EPI_NONE, l.dst, l.dst, 0, 0, 0, 0};
-        if (run && head) {
+        if (track && head) {
             fu = plan_fusion(L, nL, i);
             fused_away = fu.skip;
-        } else if (!run && l.op == SMALL_OP_DWCONV) {
+            if (n_heads) {
+                if (heads) heads[*n_heads] = i;
+                ++*n_heads;
+            }
+        }
+        if (!run && l.op == SMALL_OP_DWCONV) {
             // a run may swap the memory behind these two slots: both must then hold either one's tensors
             const Fusion f = plan_fusion(L, nL, i);
             if (f.rename) may_swap |= (1u << l.src) | (1u << l.dst);
+        }
+        // a run of convolutions with every tensor between them in LDS, one image per workgroup
+        int res_n = 0;
+        ResGroup res_g[kResMaxLayers];
+        if (track && head && resident && l.op == SMALL_OP_CONV && !fu.chain && !(in_plain && i == 0) && valid_id(l.src) &&
+            valid_id(l.dst)) {
+            int last_layer[kResMaxLayers];
+            res_n = plan_resident_run(L, nL, i, shp, res_g, last_layer);
+            if (res_n && run &&
+                ((((uintptr_t)ptr(l.src) | (uintptr_t)ptr(res_g[res_n - 1].dst)) & 15u) ||
+                 overlap(ptr(l.src), elems(N, l.Ci, shp[idx(l.src)].H, shp[idx(l.src)].W), ptr(res_g[res_n - 1].dst),
+                         elems(N, res_g[res_n - 1].Co, res_g[res_n - 1].Ho, res_g[res_n - 1].Wo))))
+                res_n = 0;
+            if (res_n) fused_away = last_layer[res_n - 1] - i;
         }
         const bool launch = run && head && i >= first && (long)i < (long)first + count;
         if (!valid_id(l.src) || !valid_id(l.dst) || l.dst == SMALL_BUF_IN) return SMALL_ERR_LAYER;
@@ -675,6 +752,8 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                         cl[k] = ChainLayer{t.filt, t.Ci, t.Co, fu.chain_relu[k]};
                     }
                     rc = from_hip(launch_dense_chain(ptr(l.src), ptr(fu.out_id), cl, fu.chain, (long)N * a.H * a.W, a.H * a.W, s));
+                } else if (launch && res_n) {
+                    rc = from_hip(launch_resident(res_g, res_n, ptr(l.src), ptr(res_g[res_n - 1].dst), N, s));
                 } else if (launch) {
                     rc = run_conv(ptr(l.src), l.filt, ptr(fu.out_id), ptr(fu.res_id), p, fu.epilogue, s, plain);
                 }
@@ -795,13 +874,31 @@ int small_network_launches(const small_layer *layers, int n_layers, int *first_l
 
 static int network_run_impl(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
                             void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first, int count,
-                            void *stream, bool in_plain = false);
+                            void *stream, unsigned flags = 0);
+
+int small_network_run_opt(const small_layer *layers, int n_layers, const float *in, float *out_blocked, void *workspace,
+                          size_t workspace_bytes, int N, int C0, int H0, int W0, unsigned flags, void *stream)
+{
+    if (flags & ~(unsigned)(SMALL_RUN_PLAIN_INPUT | SMALL_RUN_RESIDENT_OFF | SMALL_RUN_RESIDENT_ON)) return SMALL_ERR_SHAPE;
+    return network_run_impl(layers, n_layers, in, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, 0, INT_MAX,
+                            stream, flags);
+}
+
+int small_network_launches_at(const small_layer *layers, int n_layers, int N, int C0, int H0, int W0, unsigned flags,
+                              int *first_layer, int *n_launches)
+{
+    if (!layers || !n_launches) return SMALL_ERR_NULL;
+    if (flags & ~(unsigned)(SMALL_RUN_PLAIN_INPUT | SMALL_RUN_RESIDENT_OFF | SMALL_RUN_RESIDENT_ON)) return SMALL_ERR_SHAPE;
+    NetPlan plan;
+    return walk(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr, 0, INT_MAX, flags,
+                first_layer, n_launches);
+}
 
 int small_network_run_plain(const small_layer *layers, int n_layers, const float *in_nchw, float *out_blocked,
                             void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream)
 {
     return network_run_impl(layers, n_layers, in_nchw, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, 0,
-                            INT_MAX, stream, true);
+                            INT_MAX, stream, SMALL_RUN_PLAIN_INPUT);
 }
 
 int small_network_run_range(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
@@ -822,10 +919,10 @@ int small_network_run(const small_layer *layers, int n_layers, const float *in_b
 
 static int network_run_impl(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
                             void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first, int count,
-                            void *stream, bool in_plain)
+                            void *stream, unsigned flags)
 {
     NetPlan plan;
-    int rc = walk(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr, 0, INT_MAX, in_plain);
+    int rc = walk(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr, 0, INT_MAX, flags);
     if (rc) return rc;
     if (!in_blocked || !out_blocked) return SMALL_ERR_NULL;
     if (plan.bytes && !workspace) return SMALL_ERR_NULL;
@@ -836,7 +933,7 @@ static int network_run_impl(const small_layer *layers, int n_layers, const float
                         overlap(out_blocked, plan.out_elems, workspace, ws_elems))))
         return SMALL_ERR_ALIAS;
     return walk(layers, n_layers, N, C0, H0, W0, plan, true, in_blocked, out_blocked, static_cast<char *>(workspace),
-                as_stream(stream), first, count, in_plain);
+                as_stream(stream), first, count, flags);
 }
 
 }  // extern "C"

@@ -101,6 +101,24 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
 // takes that (one input block of fewer than 16 channels, a reduction of 5..8, 25..28 or 37..40 values, at least
 // 16384 output pixels, 16-byte aligned pointers); conv_takes_plain_input tells, and launch_conv fails otherwise.
 bool conv_takes_plain_input(const LayerGeom &g, const void *in, const void *filt, const void *out, const void *res);
+// A run of convolutions (with their folded epilogues) in one kernel, one image per workgroup, all tensors between
+// them in LDS (resident.hip). A group is one convolution as the runner launches it: logical buffer ids of its
+// input, residual (EPI_ADD only) and result, geometry, epilogue.
+constexpr int kResMaxLayers = 12;
+constexpr int kResidentWorkgroups = 256;     // one per compute unit; images beyond that are taken in further rounds
+struct ResGroup {
+    const float *filt;
+    int src, res, dst;
+    int Ci, Co, Cib, Cob, H, W, Ho, Wo, kh, kw, stride, pt, pl;
+    int epilogue;
+};
+// How many of the groups g[0..n) (a prefix, 0 or at least 2) one launch takes: 16-channel blocks, 1 or 9 taps, every
+// tensor read is the first group's input or produced inside, the live tensors fit 160 KB of LDS per image, and
+// closed_after[k - 1] holds (after group k - 1 nothing produced inside but its result is needed any more).
+int resident_groups(const ResGroup *g, int n, const bool *closed_after);
+// in: the first group's input tensor, out: the last group's result, both blocked, 16-byte aligned.
+hipError_t launch_resident(const ResGroup *g, int n, const float *in, float *out, int N, hipStream_t s);
+
 // Name of the kernel launch_conv picks for this geometry when all pointers are 16-byte aligned.
 const char *conv_kernel_name(const LayerGeom &g);
 

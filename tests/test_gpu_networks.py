@@ -12,12 +12,15 @@ from gpu_util import CANARY, DEV, Guarded, assert_bits, assert_close, dev
 pytestmark = pytest.mark.gpu
 
 
-def _run(net, x, ws):
+def _run(net, x, ws, flags=None):
     N = x.shape[0]
     pn = S.PackedNetwork(net, ws, DEV)
     xb = pn.pack_input(dev(x))
     g = Guarded(pn.out_elems(N))
-    pn.run(xb, g.t, N)
+    if flags is None:
+        pn.run(xb, g.t, N)
+    else:
+        pn.run_opt(xb, g.t, N, flags)
     out = g.check()
     L = net.layers[-1]
     return O.unpack(out, (N, L.Co, L.Ho, L.Wo), L.Cob)
@@ -589,3 +592,116 @@ def test_run_from_plain_input_with_first_layer_into_add():
     a = O.relu(O.conv2d(x[:3], ws[0], 2, (0, 1, 0, 1)))
     ref = O.add(O.conv2d(a, ws[1], 1, (0, 0, 0, 0)), a)
     assert_close(O.unpack(out1, (N, 16, 20, 12), 16)[:3], ref, 27, "plain first layer, kept")
+
+
+# ------------------------------------------------------------------ image-resident runs (one image per workgroup)
+
+@pytest.mark.parametrize("N", [1, 3, 130, 256, 300, 515])
+def test_resident_run_residual_cnn(N):
+    """Layers 2..18 of the residual CNN (eight convolutions with ReLU / residual add, strides 1 and 2, 1x1 projections)
+    as one launch with all tensors in LDS: against the oracle on sampled images, and against the layer-by-layer run."""
+    net = WL.residual_cnn()
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 40 + N)
+    pn = S.PackedNetwork(net, ws, DEV)
+    assert pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON) == [0, 2, 19]
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(N, -1)
+    base = _run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF).reshape(N, -1)
+    K = _maxK(net) * 9
+    assert_close(got, base, K, f"resident vs layer by layer, N={N}")
+    for n in sorted({0, N // 2, N - 1}):
+        assert_close(got[n:n + 1], O.run_network(net, x[n:n + 1], ws), K, f"resident image {n} of {N}")
+
+
+def test_resident_run_is_the_default_at_full_batches():
+    net = WL.residual_cnn()
+    N = 256
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 2)
+    pn = S.PackedNetwork(net, ws, DEV)
+    assert pn.launches_at(N) == [0, 2, 19] and len(pn.launches_at(N, S.SMALL_RUN_RESIDENT_OFF)) == 10
+    assert len(pn.launches_at(64)) == 10 and len(pn.launches_at(300)) == 10 and len(pn.launches_at(500)) == 3
+    a = _run(net, x, ws).reshape(N, -1)
+    b = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(N, -1)
+    assert_bits(a, b, "default run at batch 256 is the resident run")
+    # from the plain input as well
+    xd = dev(x)
+    g = Guarded(pn.out_elems(N))
+    pn.run_plain(xd, g.t, N)
+    assert_bits(g.check().reshape(N, -1), a, "plain input + resident run")
+
+
+def _conv_table(rng):
+    """Convolution-only tables (3x3 / 1x1, strides 1 and 2, ReLU, residual adds, odd image sizes) on 16-channel
+    blocks: what an image-resident run takes, with sources drawn among the buffers of the right shape."""
+    from workloads.nets import Layer, Network, IN, OUT
+    C0 = int(rng.choice([16, 32]))
+    H0, W0 = int(rng.choice([5, 8, 11, 16, 19])), int(rng.choice([4, 8, 13, 16]))
+    net = Network("conv_table", C0, H0, W0)
+    shape = {IN: (C0, H0, W0)}
+    layers, cur = [], IN
+    n_layers = int(rng.integers(4, 12))
+    for step in range(n_layers):
+        C, H, W = shape[cur]
+        op = rng.choice(["conv3", "conv3", "conv1", "relu", "add"])
+        last = step + 1 == n_layers
+        if op in ("conv1", "conv3") or last:
+            k = 3 if op == "conv3" else 1
+            s = 2 if (min(H, W) >= 4 and rng.random() < 0.3) else 1
+            Co = int(rng.choice([16, 32, 48]))
+            if k == 3:
+                pad = (1, 1, 1, 1) if s == 1 else (0, 1, 0, 1)
+                if rng.random() < 0.2 and min(H, W) >= 5:
+                    pad = (0, 0, 0, 0)       # 'valid' 3x3
+            else:
+                pad = (0, 0, 0, 0)
+            dst = OUT if last else int(rng.choice([k_ for k_ in range(4) if k_ != cur]))
+            net.wshapes.append(((Co, C, k, k), C * k * k))
+            L = Layer("conv", C, Co, H, W, k, k, s, pad, src=cur, dst=dst, w=len(net.wshapes) - 1)
+            shape[dst] = (Co, L.Ho, L.Wo)
+        elif op == "relu":
+            if cur == IN:
+                continue
+            dst = cur
+            L = Layer("relu", C, C, H, W, src=cur, dst=cur)
+        else:
+            others = [b for b, sh in shape.items() if sh == (C, H, W) and b != cur]
+            if not others or cur == IN:
+                continue
+            other = int(rng.choice(others))
+            dst = cur
+            L = Layer("add", C, C, H, W, src=cur, src2=other, dst=dst)
+        layers.append(L)
+        cur = dst
+    if not layers or layers[-1].dst != OUT:
+        C, H, W = shape[cur]
+        net.wshapes.append(((16, C, 1, 1), C))
+        layers.append(Layer("conv", C, 16, H, W, 1, 1, 1, (0, 0, 0, 0), src=cur, dst=OUT, w=len(net.wshapes) - 1))
+    net.layers = layers
+    return net
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_resident_runs_on_random_conv_tables(seed):
+    rng = np.random.default_rng(31000 + seed)
+    net = _conv_table(rng)
+    N = int(rng.integers(1, 7))
+    x, ws = WL.network_tensors(net, N, 32000 + seed)
+    ref = O.run_network(net, x, ws)
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(ref.shape)
+    depth = sum(L.op == "conv" for L in net.layers)
+    K = max(L.Ci * L.kh * L.kw for L in net.layers if L.op == "conv")
+    ops = "/".join(f"{L.op}{L.kh}s{L.stride}" if L.op == "conv" else L.op for L in net.layers)
+    assert_close(got, ref, K * depth ** 2, f"conv table {seed}: {ops}")
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_layer_tables_with_resident_runs(seed):
+    """The mixed random tables again with image-resident runs forced on wherever they apply."""
+    rng = np.random.default_rng(12000 + seed)
+    net = _random_table(rng)
+    N = int(rng.integers(1, 5))
+    x, ws = WL.network_tensors(net, N, 13000 + seed)
+    ref = O.run_network(net, x, ws)
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(ref.shape)
+    depth = sum(L.op in ("conv", "dw", "dense") for L in net.layers)
+    K = max([L.Ci * L.kh * L.kw for L in net.layers if L.op in ("conv", "dense")] + [9])
+    assert_close(got, ref, K * max(depth, 1) ** 2, f"random table {seed} (resident)")
