@@ -9,7 +9,9 @@
 // halo: the whole image is the tile. What it removes is per-launch cost (ramp, drain, the gap between dependent
 // kernels), which dominates layer-by-layer runs of these networks at a batch of a few hundred images.
 //
-// LDS layout. Every tensor of the run lives in LDS in the blocked layout [C/16][rows][pixels][16], zero-padded
+// LDS layout. Every tensor of the run lives in LDS as [C/16][4][rows][pixels][4]: a 16-channel block is split into
+// four planes of 4 channels, so that the 16 lanes which read 16 neighbouring pixels' float4 touch 256 contiguous
+// bytes (with all 16 channels of a pixel together they would be 64 bytes apart and share LDS banks). Zero-padded
 // by as many rows / columns as its consumers' windows reach outside the image, so that the reduction loop reads
 // with no bounds test at all: the address of an input value is (tile base) + (tap, input block offset), the
 // second term wave-uniform. A layer's workgroup first clears the border of its output tensor, then computes the
@@ -34,14 +36,17 @@ namespace {
 constexpr int kResWaves = 8;
 constexpr int kResThreads = kResWaves * 64;
 constexpr int kResLdsBytes = 160 * 1024;
+constexpr int kResSlotBytes = kResWaves * 1024;       // per wave: one 16 x 16 filter block in transit
+constexpr int kResTensorBytes = kResLdsBytes - kResSlotBytes;
 constexpr int kResMaxTaps = 9;
 constexpr int kResMaxIds = 40;      // logical buffer ids + 2, as the runner numbers them
 
-// A tensor in LDS. Units: float4 for `off`, pixels (= 4 float4) for the rest.
+// A tensor in LDS, in float4 units: element (channel block cb, channels 4q .. 4q + 3, padded pixel x) is at
+// off + (4 cb + q) * plane + x.
 struct ResTensorDev {
-    int off;      // first padded pixel of channel block 0
+    int off;      // first padded pixel of plane 0
     int Wp;       // padded row length
-    int plane;    // padded pixels per channel block
+    int plane;    // padded pixels per plane
     int org;      // index inside a plane of image pixel (0, 0)
 };
 
@@ -63,42 +68,86 @@ struct ResArgs {
     ResTensorDev src;               // where the run's input goes
     int sH, sW, snCb, spt, spb, spl, spr;
     int in_f4, out_f4;              // float4 per image of the run's input and output in HBM
+    int slot;                       // float4 index of the waves' private kilobytes (filter blocks in transit)
     FastDiv div_sW, div_sH;
     ResLayerDev layer[kResMaxLayers];
 };
 
 typedef const __attribute__((address_space(4))) ResArgs *ResKernArgs;
 
-__device__ __forceinline__ const float *uniform_ptr(const float *p)
-{
-    const uintptr_t v = (uintptr_t)p;
-    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
-    return (const float *)(((uintptr_t)hi << 32) | lo);
-}
 
-// Clears the padding rows and columns of a tensor at float4 index `off` (all threads of the workgroup).
-__device__ __forceinline__ void clear_border(floatx4 *lds, int off, int nCb, int H, int W, int pt, int pb, int pl, int pr)
+// Clears the padding rows and columns of the 4 nCb planes of a tensor at float4 index `off`: wave w takes planes
+// w, w + 8, ...; no divisions (vector-ALU time is matrix-pipe time here).
+__device__ __forceinline__ void clear_border(floatx4 *lds, int off, int nCb, int H, int W, int pt, int pb, int pl, int pr,
+                                             int w, int lane)
 {
-    const int Wp = pl + W + pr, plane4 = (pt + H + pb) * Wp * 4;
-    const int top = pt * Wp * 4, bot = pb * Wp * 4, side = (pl + pr) * 4, per = top + bot + H * side;
-    if (per == 0) return;
-    for (int i = (int)threadIdx.x; i < per * nCb; i += kResThreads) {
-        const int cb = i / per, r = i - cb * per;
-        int idx;
-        if (r < top) {
-            idx = r;
-        } else if (r < top + bot) {
-            idx = (pt + H) * Wp * 4 + (r - top);
-        } else {
-            const int j = r - top - bot, row = j / side, k = j - row * side, px = k >> 2;
-            idx = ((pt + row) * Wp + (px < pl ? px : W + px)) * 4 + (k & 3);
+    const int Wp = pl + W + pr, plane = (pt + H + pb) * Wp;
+    const int top = pt * Wp, bot = pb * Wp;
+    const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int k = w; k < nCb * 4; k += kResWaves) {
+        floatx4 *t = lds + off + k * plane;
+        for (int r = lane; r < top; r += 64) t[r] = zero;
+        for (int r = lane; r < bot; r += 64) t[(pt + H) * Wp + r] = zero;
+        if (pl + pr) {
+            for (int row = lane; row < H; row += 64) {
+                floatx4 *line = t + (pt + row) * Wp;
+                for (int x = 0; x < pl; ++x) line[x] = zero;
+                for (int x = 0; x < pr; ++x) line[pl + W + x] = zero;
+            }
         }
-        lds[off + cb * plane4 + idx] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
 }
 
+typedef const __attribute__((address_space(1))) floatx4 *GlobalFloat4s;
+
+// Position in a wave's sequence of reduction rounds: (group, input block).
+struct Round { int g, cib; };
+
+__device__ __forceinline__ Round next_round(Round r, int nCib, int nGroups)
+{
+    if (r.cib + 1 < nCib) return Round{r.g, r.cib + 1};
+    if (r.g + kResWaves < nGroups) return Round{r.g + kResWaves, 0};
+    return r;       // past the wave's last round: the same block again (a request that is never used)
+}
+
+// This lane's float4 of tap 0 of the round's filter block (f0: the filter's first float4 of this lane).
+template <int TAPS>
+__device__ __forceinline__ GlobalFloat4s round_block(GlobalFloat4s f0, Round r, const FastDiv &div_nTg, int nCib)
+{
+    return f0 + ((size_t)div_nTg.div(r.g) * nCib + r.cib) * (TAPS * 64);
+}
+
+// Filter values as they come from memory: a (cob, cib, tap) block is 16 x 16 floats [ci][co]; lane l requests
+// float4 l of it (row ci = l / 4, columns 4 (l % 4) ..), one fully coalesced 1 KB request per wave and block.
+// The matrix instruction wants lane (p, q) to hold [ci = 4q + j][co = p] for j = 0 .. 3, so a block passes through
+// 1 KB of LDS private to the wave: written as float4 with row ci at row 4 (ci % 4) + ci / 4, read back as four
+// conflict-free 32-bit reads (rows 4j + q, column p).
+
+// Requests the filter blocks of wave w's first round of layer li (every tap) into ar: issued before the barrier
+// that ends the previous layer, so that they are under way while the waves meet.
+__device__ __forceinline__ void prefetch_first(ResKernArgs ka, int li, int w, int lane, floatx4 (&ar)[kResMaxTaps])
+{
+    if (w >= ka->layer[li].nGroups) return;
+    const int taps = ka->layer[li].taps, nCib = ka->layer[li].nCib;
+    FastDiv div_nTg;
+    div_nTg.magic = ka->layer[li].div_nTg.magic; div_nTg.shift = ka->layer[li].div_nTg.shift; div_nTg.d = ka->layer[li].div_nTg.d;
+    const int cob = div_nTg.div(w);
+    GlobalFloat4s fa = (GlobalFloat4s)(ka->layer[li].filt + (size_t)cob * nCib * taps * 256) + lane;
+    asm volatile("" : "+v"(fa));
+    if (taps == kResMaxTaps) {
+#pragma unroll
+        for (int tap = 0; tap < kResMaxTaps; ++tap) ar[tap] = fa[tap * 64];
+    } else {
+        ar[0] = fa[0];
+    }
+}
+
+// ar: on entry the filter blocks of this wave's first round (prefetch_first). Ring entry x > 0 holds tap x of the
+// current round until step x - 1 passes it on to LDS, and is then refilled with tap x of the next round; entry 0
+// is passed on in a round's last step (for the next round's first) and refilled from the round after that.
 template <int T, int TAPS>
-__device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *lds, floatx4 *gout, int w, int lane)
+__device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *lds, floatx4 *gout, int w, int lane,
+                                              floatx4 (&ar)[kResMaxTaps], int slot)
 {
     const int p = lane & 15, q = lane >> 4;
     const float *const filt = ka->layer[li].filt;
@@ -115,70 +164,107 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
     div_nTg.magic = ka->layer[li].div_nTg.magic; div_nTg.shift = ka->layer[li].div_nTg.shift; div_nTg.d = ka->layer[li].div_nTg.d;
     int tapoff[TAPS];
 #pragma unroll
-    for (int t = 0; t < TAPS; ++t) tapoff[t] = ka->layer[li].tapoff[t] * 4;
+    for (int t = 0; t < TAPS; ++t) tapoff[t] = ka->layer[li].tapoff[t];
+    if (w >= nGroups) return;
+
+    // the wave's LDS kilobyte: where this lane writes its float4 of a block, where it reads its four values
+    floatx4 *const slot_w = lds + slot + w * 64 + (((lane >> 2) & 3) * 4 + (lane >> 4)) * 4 + (lane & 3);
+    const float *const slot_r = reinterpret_cast<const float *>(lds + slot + w * 64) + q * 16 + p;
+    const GlobalFloat4s f0 = (GlobalFloat4s)filt + lane;
+
+    // the first step's filter values
+    float a_cur[4];
+    {
+        *slot_w = ar[0];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a_cur[j] = slot_r[j * 64];
+        GlobalFloat4s p1 = round_block<TAPS>(f0, next_round(Round{w, 0}, nCib, nGroups), div_nTg, nCib);
+        asm volatile("" : "+v"(p1));
+        ar[0] = p1[0];
+    }
 
     for (int g = w; g < nGroups; g += kResWaves) {
+        // Index arithmetic and stores of one wave compete with the matrix instructions of the wave that shares its
+        // SIMD, and lose: without a higher priority a wave's set-up takes several times longer, and the two waves
+        // end up running their reduction loops one after the other instead of side by side.
+        __builtin_amdgcn_s_setprio(3);
         const int cob = div_nTg.div(g), tg = g - cob * nTg;
-        int base[T], m[T];
+        int base[T], m[T], o_at[T], r_at[T];      // where the tile's values are read, stored, and the residual read
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             m[t] = (tg * T + t) * 16 + p;
             const int mc = m[t] < HoWo ? m[t] : HoWo - 1;
             const int oy = div_Wo.div(mc), ox = mc - oy * Wo;
-            base[t] = in_off + (win0 + oy * stride * in_Wp + ox * stride) * 4 + q;
+            base[t] = in_off + q * in_plane + win0 + oy * stride * in_Wp + ox * stride;
+            o_at[t] = out_off >= 0 ? out_off + (cob * 4 + q) * out_plane + out_org + oy * out_Wp + ox : (cob * HoWo + mc) * 4 + q;
+            r_at[t] = res_off + (cob * 4 + q) * res_plane + res_org + oy * res_Wp + ox;
         }
-        floatx4 acc[T];
+        floatx4 acc[T], b[T];
 #pragma unroll
-        for (int t = 0; t < T; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-
-        // filter values of this lane: block (cob, cib), tap, row ci = 4q + j, column co = p
-        const float *fa = uniform_ptr(filt + (size_t)cob * nCib * TAPS * 256) + (4 * q) * 16 + p;
-        float a_next[TAPS][4];
-#pragma unroll
-        for (int tap = 0; tap < TAPS; ++tap)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) a_next[tap][j] = fa[tap * 256 + j * 16];
+        for (int t = 0; t < T; ++t) {
+            acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+            b[t] = lds[base[t] + tapoff[0]];
+        }
+        __builtin_amdgcn_s_setprio(0);
 
         for (int cib = 0; cib < nCib; ++cib) {
-            const int coff = cib * in_plane * 4;
-            // the next input block's filter values (the last block asks for its own again: same number of
-            // requests in every round, none past the filter)
-            const float *fn = fa + (size_t)(cib + 1 < nCib ? cib + 1 : cib) * TAPS * 256;
+            const int coff = cib * 4 * in_plane;
+            const Round r1 = next_round(Round{g, cib}, nCib, nGroups), r2 = next_round(r1, nCib, nGroups);
+            // the compiler must not see that these are the addresses later rounds read: it would turn the requests
+            // made a round ahead into requests made at the point of use
+            GlobalFloat4s p1 = round_block<TAPS>(f0, r1, div_nTg, nCib), p2 = round_block<TAPS>(f0, r2, div_nTg, nCib);
+            asm volatile("" : "+v"(p1), "+v"(p2));
 #pragma unroll
             for (int tap = 0; tap < TAPS; ++tap) {
-                floatx4 b[T];
+                constexpr int kLast = TAPS - 1;
+                const int x = tap == kLast ? 0 : tap + 1;
+                // the next step's operands: its filter block through the wave's LDS kilobyte, its input values
+                float a_nxt[4];
+                floatx4 b_nxt[T];
+                *slot_w = ar[x];
 #pragma unroll
-                for (int t = 0; t < T; ++t) b[t] = lds[base[t] + coff + tapoff[tap]];
-                float a[4];
+                for (int j = 0; j < 4; ++j) a_nxt[j] = slot_r[j * 64];
+                ar[x] = x ? p1[x * 64] : p2[0];
+                if (tap < kLast) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    a[j] = a_next[tap][j];
-                    a_next[tap][j] = fn[tap * 256 + j * 16];
+                    for (int t = 0; t < T; ++t) b_nxt[t] = lds[base[t] + coff + tapoff[tap + 1]];
+                } else if (cib + 1 < nCib) {
+#pragma unroll
+                    for (int t = 0; t < T; ++t) b_nxt[t] = lds[base[t] + coff + 4 * in_plane + tapoff[0]];
+                } else {
+#pragma unroll
+                    for (int t = 0; t < T; ++t) b_nxt[t] = b[t];      // the group ends: the next one reads its own
                 }
+                __builtin_amdgcn_sched_barrier(0);     // the requests above stay ahead of the arithmetic below
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int t = 0; t < T; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j], b[t][j], acc[t], 0, 0, 0);
+                    for (int t = 0; t < T; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[j], b[t][j], acc[t], 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) a_cur[j] = a_nxt[j];
+#pragma unroll
+                for (int t = 0; t < T; ++t) b[t] = b_nxt[t];
             }
         }
 
+        __builtin_amdgcn_s_setprio(3);
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             if (m[t] >= HoWo) continue;
-            const int oy = div_Wo.div(m[t]), ox = m[t] - oy * Wo;
             floatx4 v = acc[t];
-            if (epilogue & EPI_ADD) v += lds[res_off + (cob * res_plane + res_org + oy * res_Wp + ox) * 4 + q];
+            if (epilogue & EPI_ADD) v += lds[r_at[t]];
             if (epilogue & EPI_RELU) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
             }
-            if (out_off >= 0) lds[out_off + (cob * out_plane + out_org + oy * out_Wp + ox) * 4 + q] = v;
-            else gout[(cob * HoWo + m[t]) * 4 + q] = v;
+            if (out_off >= 0) lds[o_at[t]] = v;
+            else gout[o_at[t]] = v;
         }
     }
 }
 
-__global__ void __launch_bounds__(kResThreads) resident_run(ResArgs args)
+// One workgroup per compute unit (LDS): two waves per SIMD, 256 vector registers each.
+__global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) resident_run(ResArgs args)
 {
     (void)args;
     const ResKernArgs ka = (ResKernArgs)__builtin_amdgcn_kernarg_segment_ptr();
@@ -192,6 +278,11 @@ __global__ void __launch_bounds__(kResThreads) resident_run(ResArgs args)
     div_sW.magic = ka->div_sW.magic; div_sW.shift = ka->div_sW.shift; div_sW.d = ka->div_sW.d;
     div_sH.magic = ka->div_sH.magic; div_sH.shift = ka->div_sH.shift; div_sH.d = ka->div_sH.d;
 
+    const int slot = ka->slot;
+    floatx4 a_pre[kResMaxTaps];
+#pragma unroll
+    for (int tap = 0; tap < kResMaxTaps; ++tap) a_pre[tap] = floatx4{0.f, 0.f, 0.f, 0.f};
+    if ((int)blockIdx.x < N) prefetch_first(ka, 0, w, lane, a_pre);
     for (int n = (int)blockIdx.x; n < N; n += (int)gridDim.x) {
         // the image's input tensor: HBM [cb][y][x] pixels -> its padded place in LDS
         const floatx4 *gin = reinterpret_cast<const floatx4 *>(ka->in) + (size_t)n * in_f4;
@@ -200,28 +291,33 @@ __global__ void __launch_bounds__(kResThreads) resident_run(ResArgs args)
             const int pixel = i >> 2;
             const int cbrow = div_sW.div(pixel), x = pixel - cbrow * sW;
             const int cb = div_sH.div(cbrow), y = cbrow - cb * sH;
-            lds[s_off + (cb * s_plane + s_org + y * s_Wp + x) * 4 + (i & 3)] = gin[i];
+            lds[s_off + (cb * 4 + (i & 3)) * s_plane + s_org + y * s_Wp + x] = gin[i];
         }
-        clear_border(lds, s_off, ka->snCb, sH, sW, ka->spt, ka->spb, ka->spl, ka->spr);
+        clear_border(lds, s_off, ka->snCb, sH, sW, ka->spt, ka->spb, ka->spl, ka->spr, w, lane);
         __syncthreads();
 
         floatx4 *gout = reinterpret_cast<floatx4 *>(ka->out) + (size_t)n * out_f4;
         for (int li = 0; li < n_layers; ++li) {
-            if (ka->layer[li].out.off >= 0)
-                clear_border(lds, ka->layer[li].out.off, ka->layer[li].nCob, ka->layer[li].oH, ka->layer[li].oW,
-                             ka->layer[li].opt, ka->layer[li].opb, ka->layer[li].opl, ka->layer[li].opr);
+            // (a_pre holds this wave's first filter values of layer li)
             const int T = ka->layer[li].T, taps = ka->layer[li].taps;
             if (taps == 9) {
-                if (T == 4) resident_conv<4, 9>(ka, li, lds, gout, w, lane);
-                else if (T == 2) resident_conv<2, 9>(ka, li, lds, gout, w, lane);
-                else resident_conv<1, 9>(ka, li, lds, gout, w, lane);
+                if (T == 4) resident_conv<4, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
+                else if (T == 2) resident_conv<2, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
+                else resident_conv<1, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
             } else {
-                if (T == 4) resident_conv<4, 1>(ka, li, lds, gout, w, lane);
-                else if (T == 2) resident_conv<2, 1>(ka, li, lds, gout, w, lane);
-                else resident_conv<1, 1>(ka, li, lds, gout, w, lane);
+                if (T == 4) resident_conv<4, 1>(ka, li, lds, gout, w, lane, a_pre, slot);
+                else if (T == 2) resident_conv<2, 1>(ka, li, lds, gout, w, lane, a_pre, slot);
+                else resident_conv<1, 1>(ka, li, lds, gout, w, lane, a_pre, slot);
             }
+            // the padding of the result (nobody reads it before the barrier; a wave that is done early does this
+            // while the others still compute)
+            if (ka->layer[li].out.off >= 0)
+                clear_border(lds, ka->layer[li].out.off, ka->layer[li].nCob, ka->layer[li].oH, ka->layer[li].oW,
+                             ka->layer[li].opt, ka->layer[li].opb, ka->layer[li].opl, ka->layer[li].opr, w, lane);
+            if (li + 1 < n_layers) prefetch_first(ka, li + 1, w, lane, a_pre);
+            else if (n + (int)gridDim.x < N) prefetch_first(ka, 0, w, lane, a_pre);
             __syncthreads();   // the layer's output is complete, its input may be overwritten
-        }
+            }
     }
 }
 
@@ -331,7 +427,7 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
             }
         }
     };
-    if (inst[0].bytes > kResLdsBytes) return false;
+    if (inst[0].bytes > kResTensorBytes) return false;
     take(0, 0);
     for (int k = 0; k < n; ++k) {
         const int o = out_i[k];
@@ -341,7 +437,7 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
                 for (int u = 0; u < n_used; ++u)
                     if (used_inst[u] == res_i[k]) used_inst[u] = o;       // the region changes hands
             } else {
-                const int off = first_fit(used, n_used, inst[o].bytes, kResLdsBytes);
+                const int off = first_fit(used, n_used, inst[o].bytes, kResTensorBytes);
                 if (off < 0) return false;
                 take(o, off);
             }
@@ -350,7 +446,7 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
         if (res_i[k] >= 0 && !alias[k] && inst[res_i[k]].last_use == k) release(res_i[k]);
         if (k + 1 < n && inst[o].last_use < 0) release(o);
     }
-    lds_bytes = peak;
+    lds_bytes = peak + kResSlotBytes;
 
     auto dev = [&](int i) {
         const Instance &t = inst[i];
@@ -359,6 +455,7 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
     };
     memset(&a, 0, sizeof(a));
     a.n_layers = n;
+    a.slot = peak / 16;
     a.src = dev(0);
     a.sH = inst[0].H; a.sW = inst[0].W; a.snCb = inst[0].C / 16;
     a.spt = inst[0].pad.t; a.spb = inst[0].pad.b; a.spl = inst[0].pad.l; a.spr = inst[0].pad.r;
