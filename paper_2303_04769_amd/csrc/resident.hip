@@ -50,7 +50,15 @@ struct ResTensorDev {
     int org;      // index inside a plane of image pixel (0, 0)
 };
 
+enum : int { RES_CONV = 0, RES_STEM = 1, RES_HEAD = 2 };
+constexpr int kStemMaxK = 40;        // reduction length of a first layer (input channels x taps), 10 steps of 4
+
 struct ResLayerDev {
+    int kind;                       // RES_CONV; RES_STEM: the first layer on an input of fewer than 16 channels (LDS
+                                    // holds it as [C][rows][pixels] floats); RES_HEAD: average pooling over the whole
+                                    // image + fully connected layer
+    int K;                          // STEM: Ci * kh * kw; HEAD: channels
+    int Co, Cob;                    // HEAD: outputs and their block
     const float *filt;
     ResTensorDev in, out, res;      // out.off < 0: the run's last layer, the result goes to HBM
     int Wo, HoWo, nCib, nCob, stride, taps;
@@ -67,30 +75,34 @@ struct ResArgs {
     int N, n_layers;
     ResTensorDev src;               // where the run's input goes
     int sH, sW, snCb, spt, spb, spl, spr;
-    int in_f4, out_f4;              // float4 per image of the run's input and output in HBM
+    int in_floats, out_floats;      // floats per image of the run's input and output in HBM
+    int stem_in;                    // the input has sC < 16 channels: 0 no, 1 blocked [H][W][sC], 2 plain [sC][H][W]
+    int sC;
+    FastDiv div_skw;                // STEM: division by the filter width
     int slot;                       // float4 index of the waves' private kilobytes (filter blocks in transit)
-    FastDiv div_sW, div_sH;
+    FastDiv div_sW, div_sH, div_sC;
     ResLayerDev layer[kResMaxLayers];
 };
 
 typedef const __attribute__((address_space(4))) ResArgs *ResKernArgs;
 
 
-// Clears the padding rows and columns of the 4 nCb planes of a tensor at float4 index `off`: wave w takes planes
-// w, w + 8, ...; no divisions (vector-ALU time is matrix-pipe time here).
-__device__ __forceinline__ void clear_border(floatx4 *lds, int off, int nCb, int H, int W, int pt, int pb, int pl, int pr,
-                                             int w, int lane)
+// Clears the padding rows and columns of the planes of a tensor (float4 planes of 4 channels, or float planes of
+// one channel for a first layer's input): wave w takes planes w, w + 8, ...; no divisions (vector-ALU time is
+// matrix-pipe time here).
+template <typename E>
+__device__ __forceinline__ void clear_border(E *tensor, int n_planes, int H, int W, int pt, int pb, int pl, int pr, int w, int lane)
 {
     const int Wp = pl + W + pr, plane = (pt + H + pb) * Wp;
     const int top = pt * Wp, bot = pb * Wp;
-    const floatx4 zero = floatx4{0.f, 0.f, 0.f, 0.f};
-    for (int k = w; k < nCb * 4; k += kResWaves) {
-        floatx4 *t = lds + off + k * plane;
+    const E zero = E{};
+    for (int k = w; k < n_planes; k += kResWaves) {
+        E *t = tensor + k * plane;
         for (int r = lane; r < top; r += 64) t[r] = zero;
         for (int r = lane; r < bot; r += 64) t[(pt + H) * Wp + r] = zero;
         if (pl + pr) {
             for (int row = lane; row < H; row += 64) {
-                floatx4 *line = t + (pt + row) * Wp;
+                E *line = t + (pt + row) * Wp;
                 for (int x = 0; x < pl; ++x) line[x] = zero;
                 for (int x = 0; x < pr; ++x) line[pl + W + x] = zero;
             }
@@ -127,7 +139,7 @@ __device__ __forceinline__ GlobalFloat4s round_block(GlobalFloat4s f0, Round r, 
 // that ends the previous layer, so that they are under way while the waves meet.
 __device__ __forceinline__ void prefetch_first(ResKernArgs ka, int li, int w, int lane, floatx4 (&ar)[kResMaxTaps])
 {
-    if (w >= ka->layer[li].nGroups) return;
+    if (ka->layer[li].kind != RES_CONV || w >= ka->layer[li].nGroups) return;
     const int taps = ka->layer[li].taps, nCib = ka->layer[li].nCib;
     FastDiv div_nTg;
     div_nTg.magic = ka->layer[li].div_nTg.magic; div_nTg.shift = ka->layer[li].div_nTg.shift; div_nTg.d = ka->layer[li].div_nTg.d;
@@ -263,6 +275,154 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
     }
 }
 
+// The first layer: an input of fewer than 16 channels, held in LDS as zero-padded [C][rows][pixels] floats. The
+// reduction runs over k = tap * C + ci (the order of the filter's [kh][kw][Cib] dimensions) in steps of 4: lane
+// (p, q) supplies filt[k = 4t + q][co = p] and the input value of pixel p for that k, whose offset inside the tensor
+// follows from (ci, dy, dx). Four 16-pixel tiles at a time. fa: the filter values of the wave's first group
+// (stem_filter), requested before the image arrives.
+constexpr int kStemSteps = kStemMaxK / 4;
+
+__device__ __forceinline__ void stem_filter(ResKernArgs ka, int cob, int lane, float (&fa)[kStemSteps])
+{
+    const int p = lane & 15, q = lane >> 4, K = ka->layer[0].K;
+    const float *const filt = ka->layer[0].filt;
+#pragma unroll
+    for (int t = 0; t < kStemSteps; ++t) fa[t] = 4 * t + q < K ? filt[((size_t)cob * K + 4 * t + q) * 16 + p] : 0.f;
+}
+
+__device__ __forceinline__ void resident_stem(ResKernArgs ka, floatx4 *lds, floatx4 *gout, int w, int lane,
+                                              float (&fa)[kStemSteps])
+{
+    constexpr int li = 0, kSteps = kStemSteps, T = 4;
+    const int p = lane & 15, q = lane >> 4;
+    const int K = ka->layer[li].K, steps = (K + 3) >> 2;
+    const int in_off = ka->layer[li].in.off, in_Wp = ka->layer[li].in.Wp, in_plane = ka->layer[li].in.plane;
+    const int out_off = ka->layer[li].out.off, out_Wp = ka->layer[li].out.Wp, out_plane = ka->layer[li].out.plane,
+              out_org = ka->layer[li].out.org;
+    const int Wo = ka->layer[li].Wo, HoWo = ka->layer[li].HoWo, stride = ka->layer[li].stride, win0 = ka->layer[li].win0;
+    const int epilogue = ka->layer[li].epilogue, nTg = ka->layer[li].nTg, nGroups = ka->layer[li].nGroups;
+    FastDiv div_Wo, div_nTg;
+    div_Wo.magic = ka->layer[li].div_Wo.magic; div_Wo.shift = ka->layer[li].div_Wo.shift; div_Wo.d = ka->layer[li].div_Wo.d;
+    div_nTg.magic = ka->layer[li].div_nTg.magic; div_nTg.shift = ka->layer[li].div_nTg.shift; div_nTg.d = ka->layer[li].div_nTg.d;
+    const float *const ldsf = reinterpret_cast<const float *>(lds) + in_off * 4;
+    FastDiv div_C, div_kw;
+    div_C.magic = ka->div_sC.magic; div_C.shift = ka->div_sC.shift; div_C.d = ka->div_sC.d;
+    div_kw.magic = ka->div_skw.magic; div_kw.shift = ka->div_skw.shift; div_kw.d = ka->div_skw.d;
+    const int sC = ka->sC, kw = (int)div_kw.d;
+    int koff[kSteps];
+#pragma unroll
+    for (int t = 0; t < kSteps; ++t) {
+        const int k = 4 * t + q, tap = div_C.div(k), ci = k - tap * sC, dy = div_kw.div(tap), dx = tap - dy * kw;
+        koff[t] = k < K ? ci * in_plane + dy * in_Wp + dx : 0;
+    }
+
+    __builtin_amdgcn_s_setprio(3);
+    if (w >= nGroups) return;
+    int cob_held = div_nTg.div(w);
+    for (int g = w; g < nGroups; g += kResWaves) {
+        const int cob = div_nTg.div(g), tg = g - cob * nTg;
+        if (cob != cob_held) {
+            stem_filter(ka, cob, lane, fa);
+            cob_held = cob;
+        }
+        int base[T], m[T], o_at[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            m[t] = (tg * T + t) * 16 + p;
+            const int mc = m[t] < HoWo ? m[t] : HoWo - 1;
+            const int oy = div_Wo.div(mc), ox = mc - oy * Wo;
+            base[t] = win0 + oy * stride * in_Wp + ox * stride;
+            o_at[t] = out_off >= 0 ? out_off + (cob * 4 + q) * out_plane + out_org + oy * out_Wp + ox : (cob * HoWo + mc) * 4 + q;
+        }
+        floatx4 acc[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < kSteps; ++k) {
+            if (k < steps) {
+                float b[T];
+#pragma unroll
+                for (int t = 0; t < T; ++t) b[t] = ldsf[base[t] + koff[k]];
+#pragma unroll
+                for (int t = 0; t < T; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[k], b[t], acc[t], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            if (m[t] >= HoWo) continue;
+            floatx4 v = acc[t];
+            if (epilogue & EPI_RELU) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[r] = v[r] > 0.f ? v[r] : 0.f;
+            }
+            if (out_off >= 0) lds[o_at[t]] = v;
+            else gout[o_at[t]] = v;
+        }
+    }
+}
+
+// Average pooling over the whole image + fully connected layer on the run's last tensor. Pooling: a thread takes
+// one channel and a quarter of the pixels (independent LDS reads, no long shuffle chain), the four quarters meet by
+// two quad shuffles, the means go to LDS (`scratch`, 64 float4). Dot products: 16 lanes over the outputs x 32 parts
+// over the channels, the filter values requested before the pooling starts; summed across the four parts of a wave
+// by shuffles and across the waves through LDS.
+__device__ __forceinline__ void resident_head(ResKernArgs ka, int li, floatx4 *lds, float *gout, int scratch, int w, int lane)
+{
+    constexpr int kParts = kResThreads / 16, kMaxPer = 256 / kParts;       // channels per part: at most 8
+    const int in_off = ka->layer[li].in.off, in_Wp = ka->layer[li].in.Wp, in_plane = ka->layer[li].in.plane,
+              in_org = ka->layer[li].in.org;
+    const int W = ka->layer[li].Wo, HW = ka->layer[li].HoWo, nCib = ka->layer[li].nCib, C = nCib * 16;
+    const int Co = ka->layer[li].Co, Cob = ka->layer[li].Cob;
+    const float *const filt = ka->layer[li].filt;
+    FastDiv div_W;
+    div_W.magic = ka->layer[li].div_Wo.magic; div_W.shift = ka->layer[li].div_Wo.shift; div_W.d = ka->layer[li].div_Wo.d;
+
+    const int co = lane & 15, part = (int)threadIdx.x >> 4;
+    float fv[kMaxPer];
+    {
+        const int cob = co < Co ? co / Cob : 0, cc = co < Co ? co - cob * Cob : 0;
+#pragma unroll
+        for (int k = 0; k < kMaxPer; ++k) {
+            const int c = part + k * kParts;
+            fv[k] = (co < Co && c < C) ? filt[((size_t)(cob * nCib + (c >> 4)) * 16 + (c & 15)) * Cob + cc] : 0.f;
+        }
+    }
+
+    const float *t = reinterpret_cast<const float *>(lds + in_off);
+    float *mean = reinterpret_cast<float *>(lds + scratch);
+    const float inv = 1.0f / (float)HW;
+    for (int idx = (int)threadIdx.x; idx < C * 4; idx += kResThreads) {
+        const int c = idx >> 2, quarter = idx & 3;            // channel c = 4 plane + element
+        const float *src = t + ((c >> 2) * in_plane + in_org) * 4 + (c & 3);
+        float sum = 0.f;
+        for (int m = quarter; m < HW; m += 4) {
+            const int y = div_W.div(m), x = m - y * W;
+            sum += src[(y * in_Wp + x) * 4];
+        }
+        sum += __shfl_xor(sum, 1, 64);
+        sum += __shfl_xor(sum, 2, 64);
+        if (quarter == 0) mean[c] = sum * inv;
+    }
+    __syncthreads();
+    float *partial = mean + 256;
+    float acc = 0.f;
+#pragma unroll
+    for (int k = 0; k < kMaxPer; ++k) {
+        const int c = part + k * kParts;
+        if (c < C) acc += mean[c] * fv[k];
+    }
+    acc += __shfl_xor(acc, 16, 64);
+    acc += __shfl_xor(acc, 32, 64);
+    if (lane < 16) partial[w * 16 + lane] = acc;
+    __syncthreads();
+    if ((int)threadIdx.x < Co) {
+        float sum = 0.f;
+#pragma unroll
+        for (int k = 0; k < kResWaves; ++k) sum += partial[k * 16 + (int)threadIdx.x];
+        gout[threadIdx.x] = sum;
+    }
+}
+
 // One workgroup per compute unit (LDS): two waves per SIMD, 256 vector registers each.
 __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) resident_run(ResArgs args)
 {
@@ -271,7 +431,8 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
     extern __shared__ floatx4 lds[];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int N = ka->N, n_layers = ka->n_layers, in_f4 = ka->in_f4, out_f4 = ka->out_f4;
+    const int N = ka->N, n_layers = ka->n_layers, in_floats = ka->in_floats, out_floats = ka->out_floats;
+    const int stem_in = ka->stem_in, sC = ka->sC;
     const int s_off = ka->src.off, s_Wp = ka->src.Wp, s_plane = ka->src.plane, s_org = ka->src.org;
     const int sH = ka->sH, sW = ka->sW;
     FastDiv div_sW, div_sH;
@@ -284,23 +445,60 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
     for (int tap = 0; tap < kResMaxTaps; ++tap) a_pre[tap] = floatx4{0.f, 0.f, 0.f, 0.f};
     if ((int)blockIdx.x < N) prefetch_first(ka, 0, w, lane, a_pre);
     for (int n = (int)blockIdx.x; n < N; n += (int)gridDim.x) {
-        // the image's input tensor: HBM [cb][y][x] pixels -> its padded place in LDS
-        const floatx4 *gin = reinterpret_cast<const floatx4 *>(ka->in) + (size_t)n * in_f4;
+        // the image's input tensor: HBM -> its padded place in LDS
+        float stem_fa[kStemSteps];
+        if (stem_in) {
+            // the first layer's filter values of this wave's first group, under way while the image arrives
+            if (w < ka->layer[0].nGroups) {
+                FastDiv d0;
+                d0.magic = ka->layer[0].div_nTg.magic; d0.shift = ka->layer[0].div_nTg.shift; d0.d = ka->layer[0].div_nTg.d;
+                stem_filter(ka, d0.div(w), lane, stem_fa);
+            }
+            // fewer than 16 channels, blocked [y][x][c] or plain [c][y][x]: float planes [c][rows][pixels] in LDS
+            const float *gin = ka->in + (size_t)n * in_floats;
+            float *t = reinterpret_cast<float *>(lds + s_off);
+            FastDiv div_sC;
+            div_sC.magic = ka->div_sC.magic; div_sC.shift = ka->div_sC.shift; div_sC.d = ka->div_sC.d;
 #pragma unroll 4
-        for (int i = (int)threadIdx.x; i < in_f4; i += kResThreads) {
-            const int pixel = i >> 2;
-            const int cbrow = div_sW.div(pixel), x = pixel - cbrow * sW;
-            const int cb = div_sH.div(cbrow), y = cbrow - cb * sH;
-            lds[s_off + (cb * 4 + (i & 3)) * s_plane + s_org + y * s_Wp + x] = gin[i];
+            for (int i = (int)threadIdx.x; i < in_floats; i += kResThreads) {
+                int c, y, x;
+                if (stem_in == 2) {
+                    const int row = div_sW.div(i);          // c * H + y
+                    x = i - row * sW;
+                    c = div_sH.div(row);
+                    y = row - c * sH;
+                } else {
+                    const int pixel = div_sC.div(i);
+                    c = i - pixel * sC;
+                    y = div_sW.div(pixel);
+                    x = pixel - y * sW;
+                }
+                t[c * s_plane + s_org + y * s_Wp + x] = gin[i];
+            }
+            clear_border(t, sC, sH, sW, ka->spt, ka->spb, ka->spl, ka->spr, w, lane);
+        } else {
+            const floatx4 *gin = reinterpret_cast<const floatx4 *>(ka->in + (size_t)n * in_floats);
+#pragma unroll 4
+            for (int i = (int)threadIdx.x; i < (in_floats >> 2); i += kResThreads) {
+                const int pixel = i >> 2;
+                const int cbrow = div_sW.div(pixel), x = pixel - cbrow * sW;
+                const int cb = div_sH.div(cbrow), y = cbrow - cb * sH;
+                lds[s_off + (cb * 4 + (i & 3)) * s_plane + s_org + y * s_Wp + x] = gin[i];
+            }
+            clear_border(lds + s_off, ka->snCb * 4, sH, sW, ka->spt, ka->spb, ka->spl, ka->spr, w, lane);
         }
-        clear_border(lds, s_off, ka->snCb, sH, sW, ka->spt, ka->spb, ka->spl, ka->spr, w, lane);
         __syncthreads();
 
-        floatx4 *gout = reinterpret_cast<floatx4 *>(ka->out) + (size_t)n * out_f4;
+        float *gout_f = ka->out + (size_t)n * out_floats;
+        floatx4 *gout = reinterpret_cast<floatx4 *>(gout_f);
         for (int li = 0; li < n_layers; ++li) {
             // (a_pre holds this wave's first filter values of layer li)
-            const int T = ka->layer[li].T, taps = ka->layer[li].taps;
-            if (taps == 9) {
+            const int T = ka->layer[li].T, taps = ka->layer[li].taps, kind = ka->layer[li].kind;
+            if (kind == RES_STEM) {
+                resident_stem(ka, lds, gout, w, lane, stem_fa);
+            } else if (kind == RES_HEAD) {
+                resident_head(ka, li, lds, gout_f, slot, w, lane);
+            } else if (taps == 9) {
                 if (T == 4) resident_conv<4, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
                 else if (T == 2) resident_conv<2, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
                 else resident_conv<1, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
@@ -311,8 +509,8 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
             }
             // the padding of the result (nobody reads it before the barrier; a wave that is done early does this
             // while the others still compute)
-            if (ka->layer[li].out.off >= 0)
-                clear_border(lds, ka->layer[li].out.off, ka->layer[li].nCob, ka->layer[li].oH, ka->layer[li].oW,
+            if (kind != RES_HEAD && ka->layer[li].out.off >= 0)
+                clear_border(lds + ka->layer[li].out.off, ka->layer[li].nCob * 4, ka->layer[li].oH, ka->layer[li].oW,
                              ka->layer[li].opt, ka->layer[li].opb, ka->layer[li].opl, ka->layer[li].opr, w, lane);
             if (li + 1 < n_layers) prefetch_first(ka, li + 1, w, lane, a_pre);
             else if (n + (int)gridDim.x < N) prefetch_first(ka, 0, w, lane, a_pre);
@@ -327,6 +525,7 @@ struct Pads { int t, b, l, r; };
 
 struct Instance {          // one tensor of the run
     int C, H, W;
+    bool planar;           // a first layer's input: [C][rows][pixels] floats instead of four-channel float4 planes
     Pads pad;
     int last_use;          // last group that reads it (-1: none)
     int off, bytes;        // LDS region
@@ -351,13 +550,20 @@ int first_fit(const int (*used)[2], int n_used, int bytes, int capacity)
     return at + bytes <= capacity ? at : -1;
 }
 
-bool group_ok(const ResGroup &g)
+bool group_ok(const ResGroup &g, int position)
 {
     const int taps = g.kh * g.kw;
-    return g.filt && g.Cib == 16 && g.Cob == 16 && g.Ci > 0 && g.Co > 0 && g.Ci % 16 == 0 && g.Co % 16 == 0 &&
-           (taps == 1 || taps == 9) && g.stride >= 1 && g.Ho > 0 && g.Wo > 0 && g.pt >= 0 && g.pl >= 0 &&
-           g.src + 2 >= 0 && g.src + 2 < kResMaxIds && g.dst + 2 >= 0 && g.dst + 2 < kResMaxIds &&
-           (!(g.epilogue & EPI_ADD) || (g.res + 2 >= 0 && g.res + 2 < kResMaxIds));
+    const bool ids = g.src + 2 >= 0 && g.src + 2 < kResMaxIds && g.dst + 2 >= 0 && g.dst + 2 < kResMaxIds &&
+                     (!(g.epilogue & EPI_ADD) || (g.res + 2 >= 0 && g.res + 2 < kResMaxIds));
+    if (!ids || !g.filt || g.Ci <= 0 || g.Co <= 0 || g.Ho <= 0 || g.Wo <= 0) return false;
+    if (g.kind == RESIDENT_STEM)
+        return position == 0 && g.Ci < 16 && g.Cib == g.Ci && g.Cob == 16 && g.Co % 16 == 0 && g.Ci * taps <= kStemMaxK &&
+               taps >= 1 && g.stride >= 1 && g.pt >= 0 && g.pl >= 0 && !(g.epilogue & EPI_ADD);
+    if (g.kind == RESIDENT_HEAD)
+        return position > 0 && g.Cib == 16 && g.Ci % 16 == 0 && g.Ci <= 256 && g.Co <= 16 && g.Cob > 0 && g.Co % g.Cob == 0 &&
+               g.kh == g.H && g.kw == g.W && g.pt == 0 && g.pl == 0 && g.Ho == 1 && g.Wo == 1 && g.epilogue == EPI_NONE;
+    return g.Cib == 16 && g.Cob == 16 && g.Ci % 16 == 0 && g.Co % 16 == 0 && (taps == 1 || taps == 9) && g.stride >= 1 &&
+           g.pt >= 0 && g.pl >= 0;
 }
 
 // Plans groups [0, n) as one run; false when a tensor is read that the run does not hold, or LDS does not fit.
@@ -369,7 +575,7 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
     int cur[kResMaxIds];
     for (int k = 0; k < kResMaxIds; ++k) cur[k] = -1;
     int n_inst = 1;
-    inst[0] = Instance{g[0].Ci, g[0].H, g[0].W, Pads{0, 0, 0, 0}, -1, -1, 0};
+    inst[0] = Instance{g[0].Ci, g[0].H, g[0].W, g[0].kind == RESIDENT_STEM, Pads{0, 0, 0, 0}, -1, -1, 0};
     cur[g[0].src + 2] = 0;
     for (int k = 0; k < n; ++k) {
         const ResGroup &c = g[k];
@@ -377,7 +583,8 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
         res_i[k] = (c.epilogue & EPI_ADD) ? cur[c.res + 2] : -1;
         if (in_i[k] < 0 || ((c.epilogue & EPI_ADD) && res_i[k] < 0)) return false;
         const Instance &x = inst[in_i[k]];
-        if (x.C != c.Ci || x.H != c.H || x.W != c.W) return false;
+        if (x.C != c.Ci || x.H != c.H || x.W != c.W || x.planar != (c.kind == RESIDENT_STEM)) return false;
+        if (c.kind == RESIDENT_HEAD && k + 1 != n) return false;
         if (res_i[k] >= 0 && (inst[res_i[k]].C != c.Co || inst[res_i[k]].H != c.Ho || inst[res_i[k]].W != c.Wo)) return false;
         // rows / columns outside the image that the windows really reach
         Pads &pd = inst[in_i[k]].pad;
@@ -388,7 +595,7 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
         inst[in_i[k]].last_use = k;
         if (res_i[k] >= 0) inst[res_i[k]].last_use = k;
         out_i[k] = n_inst;
-        inst[n_inst++] = Instance{c.Co, c.Ho, c.Wo, Pads{0, 0, 0, 0}, -1, -1, 0};
+        inst[n_inst++] = Instance{c.Co, c.Ho, c.Wo, false, Pads{0, 0, 0, 0}, -1, -1, 0};
         cur[c.dst + 2] = out_i[k];
     }
     // a residual that nothing else reads afterwards is overwritten in place: both tensors then share one padding
@@ -405,7 +612,8 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
     }
     for (int k = 0; k < n_inst; ++k) {
         const Pads &pd = inst[k].pad;
-        inst[k].bytes = (inst[k].C / 16) * (pd.t + inst[k].H + pd.b) * (pd.l + inst[k].W + pd.r) * 64;
+        const int padded = (pd.t + inst[k].H + pd.b) * (pd.l + inst[k].W + pd.r);
+        inst[k].bytes = inst[k].planar ? (inst[k].C * padded * 4 + 63) / 64 * 64 : (inst[k].C / 16) * padded * 64;
     }
     // regions, in the order of the run
     int used[kResMaxLayers + 1][2], used_inst[kResMaxLayers + 1], n_used = 0, peak = 0;
@@ -428,7 +636,8 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
         }
     };
     if (inst[0].bytes > kResTensorBytes) return false;
-    take(0, 0);
+    // a first layer's small input lives only during that layer: at the top, so that it does not split the space
+    take(0, inst[0].planar ? kResTensorBytes - inst[0].bytes : 0);
     for (int k = 0; k < n; ++k) {
         const int o = out_i[k];
         if (k + 1 < n) {
@@ -457,17 +666,22 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
     a.n_layers = n;
     a.slot = peak / 16;
     a.src = dev(0);
-    a.sH = inst[0].H; a.sW = inst[0].W; a.snCb = inst[0].C / 16;
+    a.sH = inst[0].H; a.sW = inst[0].W; a.snCb = inst[0].C / 16; a.sC = inst[0].C;
     a.spt = inst[0].pad.t; a.spb = inst[0].pad.b; a.spl = inst[0].pad.l; a.spr = inst[0].pad.r;
-    a.in_f4 = a.snCb * a.sH * a.sW * 4;
-    a.out_f4 = (g[n - 1].Co / 16) * g[n - 1].Ho * g[n - 1].Wo * 4;
+    a.stem_in = g[0].kind == RESIDENT_STEM ? (g[0].plain_input ? 2 : 1) : 0;
+    a.in_floats = inst[0].C * a.sH * a.sW;
+    a.out_floats = g[n - 1].Co * g[n - 1].Ho * g[n - 1].Wo;
     a.div_sW = make_fastdiv(a.sW);
     a.div_sH = make_fastdiv(a.sH);
+    a.div_sC = make_fastdiv(a.sC);
     for (int k = 0; k < n; ++k) {
         const ResGroup &c = g[k];
         ResLayerDev &d = a.layer[k];
         const Instance &x = inst[in_i[k]], &y = inst[out_i[k]];
         d.filt = c.filt;
+        d.kind = c.kind == RESIDENT_STEM ? RES_STEM : (c.kind == RESIDENT_HEAD ? RES_HEAD : RES_CONV);
+        d.K = c.kind == RESIDENT_STEM ? c.Ci * c.kh * c.kw : c.Ci;
+        d.Co = c.Co; d.Cob = c.Cob;
         d.in = dev(in_i[k]);
         d.out = k + 1 < n ? dev(out_i[k]) : ResTensorDev{-1, 0, 0, 0};
         d.res = res_i[k] >= 0 ? dev(res_i[k]) : ResTensorDev{0, 0, 0, 0};
@@ -485,9 +699,22 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
                 d.T = T;
             }
         }
+        if (d.kind == RES_STEM) d.T = 4;
         d.nTg = (tiles + d.T - 1) / d.T;
         d.nGroups = d.nCob * d.nTg;
-        for (int t = 0; t < d.taps; ++t) d.tapoff[t] = (t / c.kw) * d.in.Wp + (t % c.kw);
+        if (d.kind == RES_CONV)
+            for (int t = 0; t < d.taps; ++t) d.tapoff[t] = (t / c.kw) * d.in.Wp + (t % c.kw);
+        if (d.kind == RES_STEM) {
+            a.div_skw = make_fastdiv(c.kw);
+            d.taps = 0;
+        }
+        if (d.kind == RES_HEAD) {
+            d.Wo = c.W;             // the pooled image
+            d.HoWo = c.H * c.W;
+            d.div_Wo = make_fastdiv(c.W);
+            d.nCob = 1; d.T = 1; d.nTg = 1; d.nGroups = 1; d.taps = 0;
+            continue;
+        }
         d.oH = y.H; d.oW = y.W; d.opt = y.pad.t; d.opb = y.pad.b; d.opl = y.pad.l; d.opr = y.pad.r;
         d.div_Wo = make_fastdiv(c.Wo);
         d.div_nTg = make_fastdiv(d.nTg);
@@ -501,7 +728,7 @@ int resident_groups(const ResGroup *g, int n, const bool *closed_after)
 {
     if (n > kResMaxLayers) n = kResMaxLayers;
     int ok = 0;
-    while (ok < n && group_ok(g[ok])) ++ok;
+    while (ok < n && group_ok(g[ok], ok)) ++ok;
     ResArgs local;
     for (int e = ok; e >= 2; --e) {
         int lds = 0;

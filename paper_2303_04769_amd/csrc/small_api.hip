@@ -589,7 +589,8 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
 // The convolution groups from layer i on that may run as one image-resident launch (resident.hip): fills rg
 // and the table index of every group's last layer, returns how many groups the launch takes (0: none).
 // shp: the shapes the logical buffers hold before layer i (indexed by id + 2).
-int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now, ResGroup *rg, int *last_layer)
+int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now, ResGroup *rg, int *last_layer,
+                      bool in_plain)
 {
     Shape shp[SMALL_MAX_SLOTS + 2];
     memcpy(shp, shp_now, sizeof(shp));
@@ -598,6 +599,24 @@ int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now,
     int n = 0, k = i;
     while (k < nL && n < kResMaxLayers) {
         const small_layer &l = L[k];
+        if (l.op == SMALL_OP_AVGPOOL && n > 0 && k + 1 < nL) {
+            // a head: pooling over the whole image of the run's last result + fully connected layer
+            const small_layer &d = L[k + 1];
+            const Fusion fu = plan_fusion(L, nL, k);
+            const Shape a = l.src >= SMALL_BUF_OUT && l.src < SMALL_MAX_SLOTS ? shp[l.src + 2] : Shape{};
+            if (fu.head && d.filt && a.set && a.C == l.Ci && a.Cb == 16 && l.Cib == 16 && l.kh == a.H && l.kw == a.W &&
+                l.src == rg[n - 1].dst && d.dst >= SMALL_BUF_OUT && d.dst < SMALL_MAX_SLOTS) {
+                rg[n] = ResGroup{d.filt, l.src, d.dst, d.dst, l.Ci, d.Co, 16, d.Cob, a.H, a.W, 1, 1, l.kh, l.kw, 1, 0, 0,
+                                 EPI_NONE, RESIDENT_HEAD, 0};
+                last_layer[n] = k + 1;
+                bool c = true;
+                for (int id = SMALL_BUF_OUT; id < SMALL_MAX_SLOTS; ++id)
+                    if (((produced >> (id + 2)) & 1ull) && id != d.dst && !dead_from(L, nL, k + 2, id)) c = false;
+                closed[n] = c;
+                ++n;
+            }
+            break;
+        }
         if (l.op != SMALL_OP_CONV || l.dst == l.src || l.dst == SMALL_BUF_IN || !l.filt) break;
         if (l.src < SMALL_BUF_OUT || l.src >= SMALL_MAX_SLOTS || l.dst < SMALL_BUF_OUT || l.dst >= SMALL_MAX_SLOTS) break;
         const Shape a = shp[l.src + 2];
@@ -611,8 +630,12 @@ int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now,
             const Shape r = shp[fu.res_id + 2];
             if (!r.set || r.C != o.C || r.H != o.H || r.W != o.W || r.Cb != o.Cb) break;
         }
+        // a first layer on fewer than 16 channels can only open a run, reading the network input
+        const bool stem = l.Cib < 16;
+        if (stem && !(k == 0 && n == 0 && l.src == SMALL_BUF_IN)) break;
         rg[n] = ResGroup{l.filt, l.src, fu.res_id, fu.out_id, l.Ci, l.Co, l.Cib, l.Cob, a.H, a.W, p.g.Ho, p.g.Wo,
-                         l.kh, l.kw, l.stride, l.pad.t, l.pad.l, fu.epilogue};
+                         l.kh, l.kw, l.stride, l.pad.t, l.pad.l, fu.epilogue, stem ? RESIDENT_STEM : RESIDENT_CONV,
+                         stem && in_plain ? 1 : 0};
         shp[l.dst + 2] = o;
         shp[fu.out_id + 2] = o;
         const int next = k + 1 + fu.skip;
@@ -649,7 +672,7 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
          int *heads = nullptr, int *n_heads = nullptr)
 {
     const bool in_plain = (flags & SMALL_RUN_PLAIN_INPUT) != 0;
-    const bool track = run || n_heads != nullptr;      // follow which layers start a launch
+    const bool track = true;                           // follow which layers start a launch
     const bool resident = resident_batch(N, flags);
     if (n_heads) *n_heads = 0;
     if (!L) return SMALL_ERR_NULL;
@@ -692,10 +715,11 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
         // a run of convolutions with every tensor between them in LDS, one image per workgroup
         int res_n = 0;
         ResGroup res_g[kResMaxLayers];
-        if (track && head && resident && l.op == SMALL_OP_CONV && !fu.chain && !(in_plain && i == 0) && valid_id(l.src) &&
-            valid_id(l.dst)) {
+        if (track && head && resident && l.op == SMALL_OP_CONV && !fu.chain && valid_id(l.src) && valid_id(l.dst) &&
+            (l.Cib == 16 || i == 0)) {
             int last_layer[kResMaxLayers];
-            res_n = plan_resident_run(L, nL, i, shp, res_g, last_layer);
+            res_n = plan_resident_run(L, nL, i, shp, res_g, last_layer, in_plain);
+            if (in_plain && i == 0 && res_n && res_g[0].kind != RESIDENT_STEM) res_n = 0;
             if (res_n && run &&
                 ((((uintptr_t)ptr(l.src) | (uintptr_t)ptr(res_g[res_n - 1].dst)) & 15u) ||
                  overlap(ptr(l.src), elems(N, l.Ci, shp[idx(l.src)].H, shp[idx(l.src)].W), ptr(res_g[res_n - 1].dst),
@@ -724,7 +748,7 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.dst == l.src) return SMALL_ERR_ALIAS;
                 if (!l.filt) return SMALL_ERR_NULL;
                 o = Shape{l.Co, p.g.Ho, p.g.Wo, l.Cob, true};
-                const bool plain = in_plain && i == 0;
+                const bool plain = in_plain && i == 0 && !res_n;
                 if (plain) {
                     if (fu.chain) return SMALL_ERR_LAYER;        // a pointwise run does not start from a plain tensor
                     const bool with_ptrs = run && head;

@@ -106,13 +106,20 @@ bool conv_takes_plain_input(const LayerGeom &g, const void *in, const void *filt
 // input, residual (EPI_ADD only) and result, geometry, epilogue.
 constexpr int kResMaxLayers = 12;
 constexpr int kResidentWorkgroups = 256;     // one per compute unit; images beyond that are taken in further rounds
+// kind: RESIDENT_CONV (16-channel blocks in and out); RESIDENT_STEM: a first layer on fewer than 16 input channels
+// (only as group 0; plain_input: its input tensor is a plain [N][Ci][H][W] one, else blocked with Cib = Ci);
+// RESIDENT_HEAD: average pooling over the whole image followed by a fully connected layer (only as the last group;
+// filt, Co, Cob are the fully connected layer's, kh = H, kw = W the pooling window, dst its result [N][Co]).
+enum : int { RESIDENT_CONV = 0, RESIDENT_STEM = 1, RESIDENT_HEAD = 2 };
 struct ResGroup {
     const float *filt;
     int src, res, dst;
     int Ci, Co, Cib, Cob, H, W, Ho, Wo, kh, kw, stride, pt, pl;
     int epilogue;
+    int kind, plain_input;
 };
-// How many of the groups g[0..n) (a prefix, 0 or at least 2) one launch takes: 16-channel blocks, 1 or 9 taps, every
+// How many of the groups g[0..n) (a prefix, 0 or at least 2) one launch takes: 16-channel blocks, 1 or 9 taps (a
+// stem: a reduction of at most 40 values), every
 // tensor read is the first group's input or produced inside, the live tensors fit 160 KB of LDS per image, and
 // closed_after[k - 1] holds (after group k - 1 nothing produced inside but its result is needed any more).
 int resident_groups(const ResGroup *g, int n, const bool *closed_after);

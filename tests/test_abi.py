@@ -99,17 +99,18 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
     heads = B.small_network_launches(table)
     assert len(r.layers) == 21 and len(heads) == 10
     assert [r.layers[h].op for h in heads] == ["conv"] * 9 + ["avgpool"]
-    # image-resident runs: at batches that fill the chip in whole rounds, layers 2..18 (eight convolutions with their
-    # ReLU / residual add, 72 KB + 72 KB of padded tensors at the widest point) are ONE launch; never with the OFF flag,
+    # image-resident runs: at batches that fill the chip in whole rounds the whole network (first layer, eight
+    # convolutions with their ReLU / residual add, 72 KB + 72 KB of padded tensors at the widest point, and the pooling
+    # + fully connected head) is ONE launch; never with the OFF flag,
     # always with the ON flag; the batch-independent list above stays as it is
     tr = B.make_layer_table(r.layers, [None] * len(r.wshapes))
     for k, L in enumerate(r.layers):
         if L.w is not None:
             tr[k].filt = 0x1000
     at = lambda N, flags=0: B.small_network_launches_at(tr, N, r.C0, r.H0, r.W0, flags)
-    assert at(256) == [0, 2, 19] == at(512) == at(200) == at(1, B.SMALL_RUN_RESIDENT_ON)
+    assert at(256) == [0] == at(512) == at(200) == at(1, B.SMALL_RUN_RESIDENT_ON)
     assert at(1) == at(127) == at(300) == at(256, B.SMALL_RUN_RESIDENT_OFF) == B.small_network_launches(tr)
-    assert at(256, B.SMALL_RUN_PLAIN_INPUT) == [0, 2, 19]
+    assert at(256, B.SMALL_RUN_PLAIN_INPUT) == [0] == at(2, B.SMALL_RUN_PLAIN_INPUT | B.SMALL_RUN_RESIDENT_ON)
     n = C.c_int(0)
     assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 8, None, C.byref(n)) == 2     # unknown flag
     assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 0, None, None) == 1

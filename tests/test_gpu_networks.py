@@ -598,12 +598,13 @@ def test_run_from_plain_input_with_first_layer_into_add():
 
 @pytest.mark.parametrize("N", [1, 3, 130, 256, 300, 515])
 def test_resident_run_residual_cnn(N):
-    """Layers 2..18 of the residual CNN (eight convolutions with ReLU / residual add, strides 1 and 2, 1x1 projections)
-    as one launch with all tensors in LDS: against the oracle on sampled images, and against the layer-by-layer run."""
+    """The whole residual CNN (3-channel first layer, eight convolutions with ReLU / residual add, strides 1 and 2,
+    1x1 projections, average pooling + fully connected layer) as one launch with all tensors in LDS: against the
+    oracle on sampled images, and against the layer-by-layer run."""
     net = WL.residual_cnn()
     x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 40 + N)
     pn = S.PackedNetwork(net, ws, DEV)
-    assert pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON) == [0, 2, 19]
+    assert pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON) == [0]       # first layer, eight convolutions and the head
     got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(N, -1)
     base = _run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF).reshape(N, -1)
     K = _maxK(net) * 9
@@ -617,8 +618,8 @@ def test_resident_run_is_the_default_at_full_batches():
     N = 256
     x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 2)
     pn = S.PackedNetwork(net, ws, DEV)
-    assert pn.launches_at(N) == [0, 2, 19] and len(pn.launches_at(N, S.SMALL_RUN_RESIDENT_OFF)) == 10
-    assert len(pn.launches_at(64)) == 10 and len(pn.launches_at(300)) == 10 and len(pn.launches_at(500)) == 3
+    assert pn.launches_at(N) == [0] and len(pn.launches_at(N, S.SMALL_RUN_RESIDENT_OFF)) == 10
+    assert len(pn.launches_at(64)) == 10 and len(pn.launches_at(300)) == 10 and len(pn.launches_at(500)) == 1
     a = _run(net, x, ws).reshape(N, -1)
     b = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(N, -1)
     assert_bits(a, b, "default run at batch 256 is the resident run")
