@@ -3,9 +3,10 @@
 
 A step = one pass of the whole path over one batch of the residual CNN workload (batch 256,
 32x32x3 fp32 images, seeded synthetic): the NCHW input (already resident in HBM) goes through
-small_network_run_plain (the first convolution reads it and writes the blocked layout; then conv 3x3 / 1x1,
-ReLU, add, average pool, dense on the shared blocked layout) -> small_unpack of the logits. At batches too
-small for that first-layer kernel the step is small_pack + small_network_run + small_unpack. value = images/s.
+small_network_run_plain (at this batch one image-resident launch: a workgroup takes an image through the first
+convolution, which reads the plain input, the conv 3x3 / 1x1 layers with ReLU and residual add, average pool and
+dense, every tensor between them in LDS) -> small_unpack of the logits. At batches where neither that nor the
+plain-input first-layer kernel applies the step is small_pack + small_network_run + small_unpack. value = images/s.
 
 Also reported on the same JSON line:
   roofline      the kernel with the largest share of the step (per-layer HIP-event timing of the

@@ -221,15 +221,18 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
 /* small_network_run_opt: small_network_run with options (flags, a sum of SMALL_RUN_*; unknown bits: SMALL_ERR_SHAPE).
  *   SMALL_RUN_PLAIN_INPUT   `in` is a plain [N][C0][H0][W0] tensor: exactly small_network_run_plain.
  *   SMALL_RUN_RESIDENT_OFF  never use image-resident runs (below); SMALL_RUN_RESIDENT_ON: use them at any batch size.
- * Image-resident runs: consecutive convolutions (16-channel blocks in and out, 1 or 9 filter taps, any stride and
- * padding, with their folded ReLU / residual add) whose per-image tensors fit 160 KB of LDS together run as ONE
- * launch, one image per workgroup (256 workgroups, further images in further rounds): only the run's input, its
- * last result and the filters touch HBM; the tensors between them are never written (allowed only when nothing
- * outside the run reads them, as for every fusion here). This is the fused layer of the paper's "Conclusion &
- * Future Directions" across layers of Table 1's partial-reduction class. Without either RESIDENT flag such runs
- * are used when N >= 128 and N fills at least 3/4 of ceil(N / 256) * 256; small_network_run,
- * small_network_run_plain and small_network_run_range follow that rule too. Results agree with the layer-by-layer
- * kernels within the conv tolerance, not bit for bit (another summation order).
+ * Image-resident runs: consecutive layers whose per-image tensors fit 152 KB of LDS together run as ONE launch,
+ * one image per workgroup (256 workgroups, further images in further rounds): optionally a first convolution on
+ * fewer than 16 input channels that reads the network input (Ci * kh * kw <= 40), then convolutions with 16-channel
+ * blocks in and out (1 or 9 filter taps, any stride and padding, with their folded ReLU / residual add), optionally
+ * closed by an average pooling over the whole image + fully connected layer (C <= 256, Co <= 16). Only the run's
+ * input, its last result and the filters touch HBM; the tensors between them are never written (allowed only when
+ * nothing outside the run reads them, as for every fusion here). This is the fused layer of the paper's
+ * "Conclusion & Future Directions" across layers of Table 1's partial-reduction class. Without either RESIDENT
+ * flag such runs are used when N >= 128 and N fills at least 3/4 of ceil(N / 256) * 256; small_network_run,
+ * small_network_run_plain and small_network_run_range follow that rule too (small_network_run_plain then also
+ * accepts tables whose first layer only the run's own first-layer code can take from a plain tensor). Results
+ * agree with the layer-by-layer kernels within the conv tolerance, not bit for bit (another summation order).
  * small_network_launches_at: the first layer of every launch that a run with these N, C0, H0, W0 and flags makes
  * (small_network_launches: the batch-independent list without image-resident runs). Host-only, no GPU needed. */
 enum { SMALL_RUN_PLAIN_INPUT = 1, SMALL_RUN_RESIDENT_OFF = 2, SMALL_RUN_RESIDENT_ON = 4 };
