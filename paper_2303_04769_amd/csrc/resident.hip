@@ -39,6 +39,7 @@ constexpr int kResLdsBytes = 160 * 1024;
 constexpr int kResSlotBytes = kResWaves * 1024;       // per wave: one 16 x 16 filter block in transit
 constexpr int kResTensorBytes = kResLdsBytes - kResSlotBytes;
 constexpr int kResMaxTaps = 9;
+constexpr int kResMaxProj = 4;       // input blocks of a projection shortcut folded into a convolution
 constexpr int kResMaxIds = 40;      // logical buffer ids + 2, as the runner numbers them
 
 // A tensor in LDS, in float4 units: element (channel block cb, channels 4q .. 4q + 3, padded pixel x) is at
@@ -60,6 +61,9 @@ struct ResLayerDev {
     int K;                          // STEM: Ci * kh * kw; HEAD: channels
     int Co, Cob;                    // HEAD: outputs and their block
     const float *filt;
+    const float *filt2;             // CONV: a 1x1 convolution of a second tensor (in2) summed into the same result:
+    ResTensorDev in2;               // the projection shortcut of a residual block as extra reduction rounds
+    int nCib2, stride2, win2;       // (nCib2 = 0: none)
     ResTensorDev in, out, res;      // out.off < 0: the run's last layer, the result goes to HBM
     int Wo, HoWo, nCib, nCob, stride, taps;
     int win0;                       // index inside an input plane of the window origin of output pixel (0, 0)
@@ -171,6 +175,9 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
     const int Wo = ka->layer[li].Wo, HoWo = ka->layer[li].HoWo, nCib = ka->layer[li].nCib, stride = ka->layer[li].stride;
     const int win0 = ka->layer[li].win0, epilogue = ka->layer[li].epilogue;
     const int nTg = ka->layer[li].nTg, nGroups = ka->layer[li].nGroups;
+    const int nCib2 = ka->layer[li].nCib2, stride2 = ka->layer[li].stride2, win2 = ka->layer[li].win2;
+    const int in2_off = ka->layer[li].in2.off, in2_Wp = ka->layer[li].in2.Wp, in2_plane = ka->layer[li].in2.plane;
+    const float *const filt2 = ka->layer[li].filt2;
     FastDiv div_Wo, div_nTg;
     div_Wo.magic = ka->layer[li].div_Wo.magic; div_Wo.shift = ka->layer[li].div_Wo.shift; div_Wo.d = ka->layer[li].div_Wo.d;
     div_nTg.magic = ka->layer[li].div_nTg.magic; div_nTg.shift = ka->layer[li].div_nTg.shift; div_nTg.d = ka->layer[li].div_nTg.d;
@@ -201,13 +208,21 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
         // end up running their reduction loops one after the other instead of side by side.
         __builtin_amdgcn_s_setprio(3);
         const int cob = div_nTg.div(g), tg = g - cob * nTg;
-        int base[T], m[T], o_at[T], r_at[T];      // where the tile's values are read, stored, and the residual read
+        // a folded projection: its filter blocks of this output block, requested now, used after the main rounds
+        floatx4 proj[kResMaxProj];
+        if (nCib2) {
+            GlobalFloat4s f2 = (GlobalFloat4s)filt2 + (size_t)cob * nCib2 * 64 + lane;
+#pragma unroll
+            for (int c = 0; c < kResMaxProj; ++c) proj[c] = f2[(c < nCib2 ? c : 0) * 64];
+        }
+        int base[T], base2[T], m[T], o_at[T], r_at[T];   // where the tile's values are read, stored, the residual read
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             m[t] = (tg * T + t) * 16 + p;
             const int mc = m[t] < HoWo ? m[t] : HoWo - 1;
             const int oy = div_Wo.div(mc), ox = mc - oy * Wo;
             base[t] = in_off + q * in_plane + win0 + oy * stride * in_Wp + ox * stride;
+            base2[t] = in2_off + q * in2_plane + win2 + oy * stride2 * in2_Wp + ox * stride2;
             o_at[t] = out_off >= 0 ? out_off + (cob * 4 + q) * out_plane + out_org + oy * out_Wp + ox : (cob * HoWo + mc) * 4 + q;
             r_at[t] = res_off + (cob * 4 + q) * res_plane + res_org + oy * res_Wp + ox;
         }
@@ -259,6 +274,25 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
             }
         }
 
+        if (nCib2) {
+            // a_cur holds the next group's first filter values by now: the projection takes registers of its own
+#pragma unroll
+            for (int c = 0; c < kResMaxProj; ++c) {
+                if (c < nCib2) {
+                    float a2[4];
+                    floatx4 b2[T];
+                    *slot_w = proj[c];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) a2[j] = slot_r[j * 64];
+#pragma unroll
+                    for (int t = 0; t < T; ++t) b2[t] = lds[base2[t] + c * 4 * in2_plane];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int t = 0; t < T; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[j], b2[t][j], acc[t], 0, 0, 0);
+                }
+            }
+        }
         __builtin_amdgcn_s_setprio(3);
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -337,14 +371,19 @@ __device__ __forceinline__ void resident_stem(ResKernArgs ka, floatx4 *lds, floa
         floatx4 acc[T];
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+        // every input value of the group is requested before the first matrix instruction (steps past the
+        // reduction read offset 0 and meet a zero filter value): one LDS latency per group, not one per step
+        float b[kSteps][T];
+#pragma unroll
+        for (int k = 0; k < kSteps; ++k)
+#pragma unroll
+            for (int t = 0; t < T; ++t) b[k][t] = ldsf[base[t] + koff[k]];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int k = 0; k < kSteps; ++k) {
             if (k < steps) {
-                float b[T];
 #pragma unroll
-                for (int t = 0; t < T; ++t) b[t] = ldsf[base[t] + koff[k]];
-#pragma unroll
-                for (int t = 0; t < T; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[k], b[t], acc[t], 0, 0, 0);
+                for (int t = 0; t < T; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[k], b[k][t], acc[t], 0, 0, 0);
             }
         }
 #pragma unroll
@@ -567,10 +606,32 @@ bool group_ok(const ResGroup &g, int position)
 }
 
 // Plans groups [0, n) as one run; false when a tensor is read that the run does not hold, or LDS does not fit.
-bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
+bool plan_prefix(const ResGroup *g_in, int n_in, ResArgs &a, int &lds_bytes)
 {
+    // A 1x1 convolution that is added onto the result of the convolution before it (the projection shortcut of a
+    // residual block: y = relu(conv3x3(a) + conv1x1(x))) becomes extra reduction rounds of that convolution: one
+    // pass over the layer, and the tensor between the two is never formed.
+    ResGroup g[kResMaxLayers];
+    const ResGroup *pj[kResMaxLayers];
+    int n = 0;
+    for (int k = 0; k < n_in; ++k) {
+        g[n] = g_in[k];
+        pj[n] = nullptr;
+        if (k + 1 < n_in) {
+            const ResGroup &c = g_in[k], &s2 = g_in[k + 1];
+            if (c.kind == RESIDENT_CONV && s2.kind == RESIDENT_CONV && c.epilogue == EPI_NONE && (s2.epilogue & EPI_ADD) &&
+                s2.kh * s2.kw == 1 && s2.pt == 0 && s2.pl == 0 && s2.res == c.dst && s2.dst == c.dst && s2.src != c.dst &&
+                s2.Co == c.Co && s2.Ho == c.Ho && s2.Wo == c.Wo && s2.Ci % 16 == 0 && s2.Ci / 16 <= kResMaxProj && s2.filt) {
+                pj[n] = &s2;
+                g[n].epilogue = s2.epilogue & ~EPI_ADD;
+                ++k;
+            }
+        }
+        ++n;
+    }
+    if (n < 1) return false;
     Instance inst[kResMaxLayers + 1];
-    int in_i[kResMaxLayers], res_i[kResMaxLayers], out_i[kResMaxLayers];
+    int in_i[kResMaxLayers], res_i[kResMaxLayers], out_i[kResMaxLayers], in2_i[kResMaxLayers];
     bool alias[kResMaxLayers];
     int cur[kResMaxIds];
     for (int k = 0; k < kResMaxIds; ++k) cur[k] = -1;
@@ -594,6 +655,14 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
         pd.r = imax(pd.r, (c.Wo - 1) * c.stride - c.pl + c.kw - c.W);
         inst[in_i[k]].last_use = k;
         if (res_i[k] >= 0) inst[res_i[k]].last_use = k;
+        in2_i[k] = -1;
+        if (pj[k]) {
+            in2_i[k] = cur[pj[k]->src + 2];
+            if (in2_i[k] < 0) return false;
+            const Instance &x2 = inst[in2_i[k]];
+            if (x2.planar || x2.C != pj[k]->Ci || x2.H != pj[k]->H || x2.W != pj[k]->W) return false;
+            inst[in2_i[k]].last_use = k;
+        }
         out_i[k] = n_inst;
         inst[n_inst++] = Instance{c.Co, c.Ho, c.Wo, false, Pads{0, 0, 0, 0}, -1, -1, 0};
         cur[c.dst + 2] = out_i[k];
@@ -652,6 +721,7 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
             }
         }
         if (inst[in_i[k]].last_use == k) release(in_i[k]);
+        if (in2_i[k] >= 0 && in2_i[k] != in_i[k] && inst[in2_i[k]].last_use == k) release(in2_i[k]);
         if (res_i[k] >= 0 && !alias[k] && inst[res_i[k]].last_use == k) release(res_i[k]);
         if (k + 1 < n && inst[o].last_use < 0) release(o);
     }
@@ -687,6 +757,14 @@ bool plan_prefix(const ResGroup *g, int n, ResArgs &a, int &lds_bytes)
         d.res = res_i[k] >= 0 ? dev(res_i[k]) : ResTensorDev{0, 0, 0, 0};
         d.Wo = c.Wo; d.HoWo = c.Ho * c.Wo; d.nCib = c.Ci / 16; d.nCob = c.Co / 16; d.stride = c.stride; d.taps = c.kh * c.kw;
         d.win0 = (x.pad.t - c.pt) * d.in.Wp + (x.pad.l - c.pl);
+        if (pj[k]) {
+            const Instance &x2 = inst[in2_i[k]];
+            d.filt2 = pj[k]->filt;
+            d.in2 = dev(in2_i[k]);
+            d.nCib2 = pj[k]->Ci / 16;
+            d.stride2 = pj[k]->stride;
+            d.win2 = x2.pad.t * d.in2.Wp + x2.pad.l;
+        }
         d.epilogue = c.epilogue;
         // tiles per wave and step: the split that needs the fewest rounds of the 8 waves, the larger group on a tie
         const int tiles = (d.HoWo + 15) / 16;

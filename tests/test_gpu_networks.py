@@ -706,3 +706,34 @@ def test_random_layer_tables_with_resident_runs(seed):
     depth = sum(L.op in ("conv", "dw", "dense") for L in net.layers)
     K = max([L.Ci * L.kh * L.kw for L in net.layers if L.op in ("conv", "dense")] + [9])
     assert_close(got, ref, K * max(depth, 1) ** 2, f"random table {seed} (resident)")
+
+
+@pytest.mark.parametrize("C,Co,H,W,s", [(48, 32, 11, 9, 2), (16, 16, 8, 8, 1), (64, 48, 13, 16, 2), (32, 64, 6, 5, 1)])
+def test_resident_run_folds_the_projection_shortcut(C, Co, H, W, s):
+    """y = relu(conv3x3(relu(conv3x3_s(x))) + conv1x1_s(x)): inside an image-resident run the 1x1 projection becomes
+    extra reduction rounds of the second 3x3 convolution (up to four input blocks), odd sizes and both strides."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("projection_block", C, H, W)
+    # 'same' padding: the strided 3x3 window then yields the sizes of the strided 1x1 convolution
+    pad_a = (1, 1, 1, 1) if s == 1 else (H % 2, 1, W % 2, 1)
+    a = Layer("conv", C, Co, H, W, 3, 3, s, pad_a, src=IN, dst=0, w=0)
+    Ho, Wo = a.Ho, a.Wo
+    net.wshapes = [((Co, C, 3, 3), C * 9), ((Co, Co, 3, 3), Co * 9), ((Co, C, 1, 1), C), ((16, Co, 1, 1), Co)]
+    net.layers = [
+        a,
+        Layer("relu", Co, Co, Ho, Wo, src=0, dst=0),
+        Layer("conv", Co, Co, Ho, Wo, 3, 3, 1, (1, 1, 1, 1), src=0, dst=1, w=1),
+        Layer("conv", C, Co, H, W, 1, 1, s, (0, 0, 0, 0), src=IN, dst=0, w=2),
+        Layer("add", Co, Co, Ho, Wo, src=1, src2=0, dst=1),
+        Layer("relu", Co, Co, Ho, Wo, src=1, dst=1),
+        Layer("conv", Co, 16, Ho, Wo, 1, 1, 1, (0, 0, 0, 0), src=1, dst=OUT, w=3),
+    ]
+    assert (net.layers[3].Ho, net.layers[3].Wo) == (Ho, Wo)
+    N = 3
+    x, ws = WL.network_tensors(net, N, 777 + C + H)
+    pn = S.PackedNetwork(net, ws, DEV)
+    assert pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON) == [0]
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON)
+    ref = O.run_network(net, x, ws).reshape(got.shape)
+    assert_close(got, ref, max(C, Co) * 9 * 9, "projection block, resident")
+    assert_close(_run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF), ref, max(C, Co) * 9 * 9, "projection block, layer by layer")
