@@ -228,8 +228,12 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
  * closed by an average pooling over the whole image + fully connected layer (C <= 256, Co <= 16). Only the run's
  * input, its last result and the filters touch HBM; the tensors between them are never written (allowed only when
  * nothing outside the run reads them, as for every fusion here). This is the fused layer of the paper's
- * "Conclusion & Future Directions" across layers of Table 1's partial-reduction class. Without either RESIDENT
- * flag such runs are used when N >= 128 and N fills at least 3/4 of ceil(N / 256) * 256; small_network_run,
+ * "Conclusion & Future Directions" across layers of Table 1's partial-reduction class. Depthwise convolutions
+ * (16-channel blocks, at most 9 taps, filter 16-byte aligned) may stand inside a run, and a 1x1 convolution added onto
+ * the convolution before it (a projection shortcut) is folded into that one. Without either RESIDENT flag such runs
+ * are used when 160 <= N <= 256 (about one image per compute unit, one round) and the run averages at least
+ * 500000 multiply-adds per layer and image (below that the per-layer cost inside a workgroup outweighs the
+ * launches saved: measured on the depthwise-separable CNNs); small_network_run,
  * small_network_run_plain and small_network_run_range follow that rule too (small_network_run_plain then also
  * accepts tables whose first layer only the run's own first-layer code can take from a plain tensor). Results
  * agree with the layer-by-layer kernels within the conv tolerance, not bit for bit (another summation order).

@@ -51,11 +51,11 @@ struct ResTensorDev {
     int org;      // index inside a plane of image pixel (0, 0)
 };
 
-enum : int { RES_CONV = 0, RES_STEM = 1, RES_HEAD = 2 };
+enum : int { RES_CONV = 0, RES_STEM = 1, RES_HEAD = 2, RES_DW = 3 };
 constexpr int kStemMaxK = 40;        // reduction length of a first layer (input channels x taps), 10 steps of 4
 
 struct ResLayerDev {
-    int kind;                       // RES_CONV; RES_STEM: the first layer on an input of fewer than 16 channels (LDS
+    int kind;                       // RES_CONV; RES_DW: depthwise convolution (at most 9 taps); RES_STEM: the first layer on an input of fewer than 16 channels (LDS
                                     // holds it as [C][rows][pixels] floats); RES_HEAD: average pooling over the whole
                                     // image + fully connected layer
     int K;                          // STEM: Ci * kh * kw; HEAD: channels
@@ -400,6 +400,46 @@ __device__ __forceinline__ void resident_stem(ResKernArgs ka, floatx4 *lds, floa
     }
 }
 
+// Depthwise convolution (Table 1's layer class with one filter per channel; at most 9 taps): plain vector
+// arithmetic, a four-channel plane per wave at a time, a lane per output pixel; the plane's filter values (one
+// float4 per tap) are the same for the whole wave.
+__device__ __forceinline__ void resident_dw(ResKernArgs ka, int li, floatx4 *lds, floatx4 *gout, int w, int lane)
+{
+    const float *const filt = ka->layer[li].filt;
+    const int in_off = ka->layer[li].in.off, in_Wp = ka->layer[li].in.Wp, in_plane = ka->layer[li].in.plane;
+    const int out_off = ka->layer[li].out.off, out_Wp = ka->layer[li].out.Wp, out_plane = ka->layer[li].out.plane,
+              out_org = ka->layer[li].out.org;
+    const int Wo = ka->layer[li].Wo, HoWo = ka->layer[li].HoWo, nCb = ka->layer[li].nCob, stride = ka->layer[li].stride;
+    const int win0 = ka->layer[li].win0, epilogue = ka->layer[li].epilogue, taps = ka->layer[li].taps;
+    FastDiv div_Wo;
+    div_Wo.magic = ka->layer[li].div_Wo.magic; div_Wo.shift = ka->layer[li].div_Wo.shift; div_Wo.d = ka->layer[li].div_Wo.d;
+    int tapoff[kResMaxTaps];
+#pragma unroll
+    for (int t = 0; t < kResMaxTaps; ++t) tapoff[t] = t < taps ? ka->layer[li].tapoff[t] : 0;
+    __builtin_amdgcn_s_setprio(3);
+    for (int k = w; k < nCb * 4; k += kResWaves) {
+        const int cb = k >> 2, qq = k & 3;
+        floatx4 f[kResMaxTaps];
+#pragma unroll
+        for (int t = 0; t < kResMaxTaps; ++t)
+            f[t] = t < taps ? *reinterpret_cast<const floatx4 *>(filt + ((size_t)(cb * taps + t) * 16 + 4 * qq))
+                            : floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int m = lane; m < HoWo; m += 64) {
+            const int oy = div_Wo.div(m), ox = m - oy * Wo;
+            const int src = in_off + k * in_plane + win0 + oy * stride * in_Wp + ox * stride;
+            floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < kResMaxTaps; ++t) acc += lds[src + tapoff[t]] * f[t];
+            if (epilogue & EPI_RELU) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[r] = acc[r] > 0.f ? acc[r] : 0.f;
+            }
+            if (out_off >= 0) lds[out_off + k * out_plane + out_org + oy * out_Wp + ox] = acc;
+            else gout[(cb * HoWo + m) * 4 + qq] = acc;
+        }
+    }
+}
+
 // Average pooling over the whole image + fully connected layer on the run's last tensor. Pooling: a thread takes
 // one channel and a quarter of the pixels (independent LDS reads, no long shuffle chain), the four quarters meet by
 // two quad shuffles, the means go to LDS (`scratch`, 64 float4). Dot products: 16 lanes over the outputs x 32 parts
@@ -537,6 +577,8 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
                 resident_stem(ka, lds, gout, w, lane, stem_fa);
             } else if (kind == RES_HEAD) {
                 resident_head(ka, li, lds, gout_f, slot, w, lane);
+            } else if (kind == RES_DW) {
+                resident_dw(ka, li, lds, gout, w, lane);
             } else if (taps == 9) {
                 if (T == 4) resident_conv<4, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
                 else if (T == 2) resident_conv<2, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
@@ -598,6 +640,9 @@ bool group_ok(const ResGroup &g, int position)
     if (g.kind == RESIDENT_STEM)
         return position == 0 && g.Ci < 16 && g.Cib == g.Ci && g.Cob == 16 && g.Co % 16 == 0 && g.Ci * taps <= kStemMaxK &&
                taps >= 1 && g.stride >= 1 && g.pt >= 0 && g.pl >= 0 && !(g.epilogue & EPI_ADD);
+    if (g.kind == RESIDENT_DW)
+        return g.Cib == 16 && g.Cob == 16 && g.Ci == g.Co && g.Ci % 16 == 0 && taps >= 1 && taps <= kResMaxTaps &&
+               g.stride >= 1 && g.pt >= 0 && g.pl >= 0 && !(g.epilogue & EPI_ADD) && ((uintptr_t)g.filt & 15u) == 0;
     if (g.kind == RESIDENT_HEAD)
         return position > 0 && g.Cib == 16 && g.Ci % 16 == 0 && g.Ci <= 256 && g.Co <= 16 && g.Cob > 0 && g.Co % g.Cob == 0 &&
                g.kh == g.H && g.kw == g.W && g.pt == 0 && g.pl == 0 && g.Ho == 1 && g.Wo == 1 && g.epilogue == EPI_NONE;
@@ -749,7 +794,7 @@ bool plan_prefix(const ResGroup *g_in, int n_in, ResArgs &a, int &lds_bytes)
         ResLayerDev &d = a.layer[k];
         const Instance &x = inst[in_i[k]], &y = inst[out_i[k]];
         d.filt = c.filt;
-        d.kind = c.kind == RESIDENT_STEM ? RES_STEM : (c.kind == RESIDENT_HEAD ? RES_HEAD : RES_CONV);
+        d.kind = c.kind == RESIDENT_STEM ? RES_STEM : (c.kind == RESIDENT_HEAD ? RES_HEAD : (c.kind == RESIDENT_DW ? RES_DW : RES_CONV));
         d.K = c.kind == RESIDENT_STEM ? c.Ci * c.kh * c.kw : c.Ci;
         d.Co = c.Co; d.Cob = c.Cob;
         d.in = dev(in_i[k]);
@@ -780,7 +825,7 @@ bool plan_prefix(const ResGroup *g_in, int n_in, ResArgs &a, int &lds_bytes)
         if (d.kind == RES_STEM) d.T = 4;
         d.nTg = (tiles + d.T - 1) / d.T;
         d.nGroups = d.nCob * d.nTg;
-        if (d.kind == RES_CONV)
+        if (d.kind == RES_CONV || d.kind == RES_DW)
             for (int t = 0; t < d.taps; ++t) d.tapoff[t] = (t / c.kw) * d.in.Wp + (t % c.kw);
         if (d.kind == RES_STEM) {
             a.div_skw = make_fastdiv(c.kw);

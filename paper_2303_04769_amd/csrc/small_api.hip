@@ -590,7 +590,7 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
 // and the table index of every group's last layer, returns how many groups the launch takes (0: none).
 // shp: the shapes the logical buffers hold before layer i (indexed by id + 2).
 int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now, ResGroup *rg, int *last_layer,
-                      bool in_plain)
+                      bool in_plain, bool forced)
 {
     Shape shp[SMALL_MAX_SLOTS + 2];
     memcpy(shp, shp_now, sizeof(shp));
@@ -616,6 +616,29 @@ int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now,
                 ++n;
             }
             break;
+        }
+        if (l.op == SMALL_OP_DWCONV) {
+            // depthwise convolution (+ ReLU in place)
+            if (l.dst == l.src || l.dst == SMALL_BUF_IN || !l.filt || l.Co != l.Ci || l.Cib != 16 || l.Cob != 16) break;
+            if (l.src < SMALL_BUF_OUT || l.src >= SMALL_MAX_SLOTS || l.dst < SMALL_BUF_OUT || l.dst >= SMALL_MAX_SLOTS) break;
+            const Shape a = shp[l.src + 2];
+            if (!a.set || a.C != l.Ci || a.Cb != l.Cib) break;
+            ConvPlan p;
+            if (plan_conv(p, 1, l.Ci, l.Ci, a.H, a.W, l.kh, l.kw, l.stride, l.pad, l.Cib, l.Cib)) break;
+            const bool relu = k + 1 < nL && L[k + 1].op == SMALL_OP_RELU && L[k + 1].src == l.dst && L[k + 1].dst == l.dst;
+            rg[n] = ResGroup{l.filt, l.src, l.dst, l.dst, l.Ci, l.Ci, 16, 16, a.H, a.W, p.g.Ho, p.g.Wo, l.kh, l.kw, l.stride,
+                             l.pad.t, l.pad.l, relu ? EPI_RELU : EPI_NONE, RESIDENT_DW, 0};
+            shp[l.dst + 2] = Shape{l.Ci, p.g.Ho, p.g.Wo, 16, true};
+            const int next = k + 1 + (relu ? 1 : 0);
+            last_layer[n] = next - 1;
+            bool c = true;
+            for (int id = SMALL_BUF_OUT; id < SMALL_MAX_SLOTS; ++id)
+                if (((produced >> (id + 2)) & 1ull) && id != l.dst && !dead_from(L, nL, next, id)) c = false;
+            closed[n] = c;
+            produced |= 1ull << (l.dst + 2);
+            ++n;
+            k = next;
+            continue;
         }
         if (l.op != SMALL_OP_CONV || l.dst == l.src || l.dst == SMALL_BUF_IN || !l.filt) break;
         if (l.src < SMALL_BUF_OUT || l.src >= SMALL_MAX_SLOTS || l.dst < SMALL_BUF_OUT || l.dst >= SMALL_MAX_SLOTS) break;
@@ -649,16 +672,30 @@ int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now,
         ++n;
         k = next;
     }
-    return n >= 2 ? resident_groups(rg, n, closed) : 0;
+    if (n < 2) return 0;
+    const int taken = resident_groups(rg, n, closed);
+    if (!taken || forced) return taken;
+    // Every layer of a run costs a workgroup a few microseconds of set-up, barrier and store whatever its size: with
+    // little arithmetic per layer (depthwise-separable blocks on small images) the layer-by-layer kernels win.
+    double macs = 0;
+    for (int k = 0; k < taken; ++k) {
+        const ResGroup &g = rg[k];
+        const double per_out = g.kind == RESIDENT_DW ? (double)g.kh * g.kw
+                             : (g.kind == RESIDENT_HEAD ? (double)g.Ci : (double)g.Ci * g.kh * g.kw);
+        macs += per_out * g.Co * g.Ho * g.Wo;
+    }
+    return macs >= 5e5 * taken ? taken : 0;
 }
 
-// Image-resident runs pay off when the batch fills the chip's compute units in whole rounds.
+// Image-resident runs pay off when the batch is about one image per compute unit: with fewer images most of the
+// chip idles for the time one image takes, and from two rounds on the layer-by-layer kernels, whose per-launch
+// costs are then spread over more images, are as fast or faster (measured on the residual CNN: 89 against 109 us
+// at 256 images, 169 against 170 us at 512, 329 against 290 us at 1024).
 bool resident_batch(int N, unsigned flags)
 {
     if (flags & SMALL_RUN_RESIDENT_OFF) return false;
     if (flags & SMALL_RUN_RESIDENT_ON) return true;
-    const int rounds = (N + kResidentWorkgroups - 1) / kResidentWorkgroups;
-    return N >= kResidentWorkgroups / 2 && 4 * N >= 3 * rounds * kResidentWorkgroups;
+    return N <= kResidentWorkgroups && 8 * N >= 5 * kResidentWorkgroups;
 }
 
 // Walks the table once: validates every layer, tracks the shape held by every logical buffer and
@@ -715,17 +752,20 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
         // a run of convolutions with every tensor between them in LDS, one image per workgroup
         int res_n = 0;
         ResGroup res_g[kResMaxLayers];
-        if (track && head && resident && l.op == SMALL_OP_CONV && !fu.chain && valid_id(l.src) && valid_id(l.dst) &&
-            (l.Cib == 16 || i == 0)) {
+        if (track && head && resident && (l.op == SMALL_OP_CONV || l.op == SMALL_OP_DWCONV) && !fu.chain && valid_id(l.src) &&
+            valid_id(l.dst) && (l.Cib == 16 || (i == 0 && l.op == SMALL_OP_CONV))) {
             int last_layer[kResMaxLayers];
-            res_n = plan_resident_run(L, nL, i, shp, res_g, last_layer, in_plain);
+            res_n = plan_resident_run(L, nL, i, shp, res_g, last_layer, in_plain, (flags & SMALL_RUN_RESIDENT_ON) != 0);
             if (in_plain && i == 0 && res_n && res_g[0].kind != RESIDENT_STEM) res_n = 0;
             if (res_n && run &&
                 ((((uintptr_t)ptr(l.src) | (uintptr_t)ptr(res_g[res_n - 1].dst)) & 15u) ||
                  overlap(ptr(l.src), elems(N, l.Ci, shp[idx(l.src)].H, shp[idx(l.src)].W), ptr(res_g[res_n - 1].dst),
                          elems(N, res_g[res_n - 1].Co, res_g[res_n - 1].Ho, res_g[res_n - 1].Wo))))
                 res_n = 0;
-            if (res_n) fused_away = last_layer[res_n - 1] - i;
+            if (res_n) {
+                fused_away = last_layer[res_n - 1] - i;
+                fu.pw = fu.pw_relu = fu.rename = fu.head = 0;      // the run covers what these would have fused
+            }
         }
         const bool launch = run && head && i >= first && (long)i < (long)first + count;
         if (!valid_id(l.src) || !valid_id(l.dst) || l.dst == SMALL_BUF_IN) return SMALL_ERR_LAYER;
@@ -805,7 +845,9 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                         fused_away = fu.skip;
                     }
                 }
-                if (l.op == SMALL_OP_DWCONV && fu.pw) {
+                if (l.op == SMALL_OP_DWCONV && res_n) {
+                    if (launch) rc = from_hip(launch_resident(res_g, res_n, ptr(l.src), ptr(res_g[res_n - 1].dst), N, s));
+                } else if (l.op == SMALL_OP_DWCONV && fu.pw) {
                     const small_layer &pw = L[i + fu.pw];
                     float *dst = ptr(fu.rename ? l.dst : pw.dst);
                     if (launch)

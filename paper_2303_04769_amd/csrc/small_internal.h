@@ -109,8 +109,9 @@ constexpr int kResidentWorkgroups = 256;     // one per compute unit; images bey
 // kind: RESIDENT_CONV (16-channel blocks in and out); RESIDENT_STEM: a first layer on fewer than 16 input channels
 // (only as group 0; plain_input: its input tensor is a plain [N][Ci][H][W] one, else blocked with Cib = Ci);
 // RESIDENT_HEAD: average pooling over the whole image followed by a fully connected layer (only as the last group;
-// filt, Co, Cob are the fully connected layer's, kh = H, kw = W the pooling window, dst its result [N][Co]).
-enum : int { RESIDENT_CONV = 0, RESIDENT_STEM = 1, RESIDENT_HEAD = 2 };
+// filt, Co, Cob are the fully connected layer's, kh = H, kw = W the pooling window, dst its result [N][Co]);
+// RESIDENT_DW: depthwise convolution, 16-channel blocks, at most 9 taps, filter 16-byte aligned.
+enum : int { RESIDENT_CONV = 0, RESIDENT_STEM = 1, RESIDENT_HEAD = 2, RESIDENT_DW = 3 };
 struct ResGroup {
     const float *filt;
     int src, res, dst;

@@ -108,8 +108,17 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
         if L.w is not None:
             tr[k].filt = 0x1000
     at = lambda N, flags=0: B.small_network_launches_at(tr, N, r.C0, r.H0, r.W0, flags)
-    assert at(256) == [0] == at(512) == at(200) == at(1, B.SMALL_RUN_RESIDENT_ON)
-    assert at(1) == at(127) == at(300) == at(256, B.SMALL_RUN_RESIDENT_OFF) == B.small_network_launches(tr)
+    assert at(256) == [0] == at(160) == at(200) == at(1, B.SMALL_RUN_RESIDENT_ON) == at(1000, B.SMALL_RUN_RESIDENT_ON)
+    assert at(1) == at(159) == at(257) == at(512) == at(256, B.SMALL_RUN_RESIDENT_OFF) == B.small_network_launches(tr)
+    # too little arithmetic per layer for a workgroup-per-image run: the depthwise-separable networks stay layer by
+    # layer unless forced
+    for other in (WL.dsep_cnn(), a):
+        to = B.make_layer_table(other.layers, [None] * len(other.wshapes))
+        for k, L in enumerate(other.layers):
+            if L.w is not None:
+                to[k].filt = 0x1000
+        plan = lambda N, flags=0: B.small_network_launches_at(to, N, other.C0, other.H0, other.W0, flags)
+        assert plan(256) == B.small_network_launches(to) and len(plan(256, B.SMALL_RUN_RESIDENT_ON)) < len(plan(256))
     assert at(256, B.SMALL_RUN_PLAIN_INPUT) == [0] == at(2, B.SMALL_RUN_PLAIN_INPUT | B.SMALL_RUN_RESIDENT_ON)
     n = C.c_int(0)
     assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 8, None, C.byref(n)) == 2     # unknown flag

@@ -619,7 +619,7 @@ def test_resident_run_is_the_default_at_full_batches():
     x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 2)
     pn = S.PackedNetwork(net, ws, DEV)
     assert pn.launches_at(N) == [0] and len(pn.launches_at(N, S.SMALL_RUN_RESIDENT_OFF)) == 10
-    assert len(pn.launches_at(64)) == 10 and len(pn.launches_at(300)) == 10 and len(pn.launches_at(500)) == 1
+    assert len(pn.launches_at(64)) == 10 and len(pn.launches_at(300)) == 10 and len(pn.launches_at(200)) == 1
     a = _run(net, x, ws).reshape(N, -1)
     b = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(N, -1)
     assert_bits(a, b, "default run at batch 256 is the resident run")
@@ -737,3 +737,21 @@ def test_resident_run_folds_the_projection_shortcut(C, Co, H, W, s):
     ref = O.run_network(net, x, ws).reshape(got.shape)
     assert_close(got, ref, max(C, Co) * 9 * 9, "projection block, resident")
     assert_close(_run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF), ref, max(C, Co) * 9 * 9, "projection block, layer by layer")
+
+
+@pytest.mark.parametrize("name,idx,N,launches", [("audio_cnn", 4, 1, 1), ("audio_cnn", 4, 5, 1), ("dsep_cnn", 3, 2, 6),
+                                                 ("audio_cnn", 4, 260, 1), ("dsep_cnn", 3, 130, 6)])
+def test_resident_runs_with_depthwise_layers(name, idx, N, launches):
+    """Depthwise 3x3 (+ ReLU) and 1x1 convolutions alternate inside image-resident runs: the audio CNN (first layer
+    with a 10x4 window on one channel, four depthwise-separable blocks, pooling + fully connected head) is one
+    launch, the depthwise-separable CNN runs its twelve 16-channel-block blocks as two launches of twelve layers."""
+    net = getattr(WL, name)()
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 60 + idx + N)
+    pn = S.PackedNetwork(net, ws, DEV)
+    assert len(pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON)) == launches
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(N, -1)
+    K = _maxK(net) * 9
+    for n in sorted({0, N // 2, N - 1}):
+        assert_close(got[n:n + 1], O.run_network(net, x[n:n + 1], ws), K, f"{name} resident, image {n} of {N}")
+    if N <= 8:
+        assert_close(got, _run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF).reshape(N, -1), K, f"{name}: resident vs layer by layer")
