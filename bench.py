@@ -501,7 +501,7 @@ def networks(S, WL, torch, dev, timed):
             t = min(ts)
             row = {"network": name, "batch": N, "ms": round(t * 1e3, 4), "images_per_s": round(N / t, 1),
                    "tflops": round(2.0 * net.macs_per_image() * N / t / 1e12, 3), "layers": len(net.layers),
-                   "launches": len(S.small_network_launches(pn.table))}
+                   "launches": len(pn.launches_at(N))}
             if N == 1:      # the same run replayed from a HIP graph: no per-launch host cost
                 graph = pn.capture(xb, o, N)
                 gfn = lambda r: graph.replay()

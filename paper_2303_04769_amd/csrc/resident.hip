@@ -90,7 +90,6 @@ struct ResArgs {
 
 typedef const __attribute__((address_space(4))) ResArgs *ResKernArgs;
 
-
 // Clears the padding rows and columns of the planes of a tensor (float4 planes of 4 channels, or float planes of
 // one channel for a first layer's input): wave w takes planes w, w + 8, ...; no divisions (vector-ALU time is
 // matrix-pipe time here).
@@ -143,6 +142,11 @@ __device__ __forceinline__ GlobalFloat4s round_block(GlobalFloat4s f0, Round r, 
 // that ends the previous layer, so that they are under way while the waves meet.
 __device__ __forceinline__ void prefetch_first(ResKernArgs ka, int li, int w, int lane, floatx4 (&ar)[kResMaxTaps])
 {
+    {
+        // the layer's descriptor (four cache lines of kernel arguments) into the scalar cache ahead of its use
+        const int touch = ka->layer[li].win2 + ka->layer[li].HoWo + ka->layer[li].tapoff[kResMaxTaps - 1] + (int)ka->layer[li].div_nTg.d;
+        asm volatile("" : : "s"(touch));
+    }
     if (ka->layer[li].kind != RES_CONV || w >= ka->layer[li].nGroups) return;
     const int taps = ka->layer[li].taps, nCib = ka->layer[li].nCib;
     FastDiv div_nTg;
