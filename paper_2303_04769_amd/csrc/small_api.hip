@@ -648,6 +648,10 @@ int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now,
         if (plan_conv(p, 1, l.Ci, l.Co, a.H, a.W, l.kh, l.kw, l.stride, l.pad, l.Cib, l.Cob)) break;
         const Fusion fu = plan_fusion(L, nL, k, false);
         if (fu.pw || fu.head || fu.chain) break;
+        // (the layers ahead have not been validated yet: ids taken from them are checked here)
+        if (fu.out_id < SMALL_BUF_OUT || fu.out_id >= SMALL_MAX_SLOTS || fu.out_id == SMALL_BUF_IN ||
+            fu.res_id < SMALL_BUF_OUT || fu.res_id >= SMALL_MAX_SLOTS)
+            break;
         const Shape o = Shape{l.Co, p.g.Ho, p.g.Wo, l.Cob, true};
         if (fu.epilogue & EPI_ADD) {
             const Shape r = shp[fu.res_id + 2];

@@ -123,6 +123,19 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
     n = C.c_int(0)
     assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 8, None, C.byref(n)) == 2     # unknown flag
     assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 0, None, None) == 1
+    # planning looks ahead over layers that have not been validated yet: a bad buffer id further down is an error
+    # code, whatever the flags
+    bad = B.make_layer_table(r.layers, [None] * len(r.wshapes))
+    for k, L in enumerate(r.layers):
+        if L.w is not None:
+            bad[k].filt = 0x1000
+    bad[5].src2 = 1000          # the first residual add
+    for flags in (0, B.SMALL_RUN_RESIDENT_ON, B.SMALL_RUN_RESIDENT_OFF):
+        assert lib.small_network_launches_at(bad, len(bad), 256, r.C0, r.H0, r.W0, flags, None, C.byref(n)) == 7
+        assert lib.small_network_workspace(bad, len(bad), 256, r.C0, r.H0, r.W0, C.byref(C.c_size_t())) == 7
+    bad[5].src2 = r.layers[5].src2
+    bad[11].dst = -7
+    assert lib.small_network_launches_at(bad, len(bad), 256, r.C0, r.H0, r.W0, 0, None, C.byref(n)) == 7
     ta = B.make_layer_table(a.layers, [None] * len(a.wshapes))
     # depthwise + ReLU + pointwise + ReLU blocks are one launch each
     assert [a.layers[h].op for h in B.small_network_launches(ta)] == ["conv"] + ["dw"] * 4 + ["avgpool"]
