@@ -115,6 +115,15 @@ __device__ __forceinline__ void clear_border(E *tensor, int n_planes, int H, int
 
 typedef const __attribute__((address_space(1))) floatx4 *GlobalFloat4s;
 
+// Division by a launch constant without a branch: the quotient by multiplication is always computed and a divisor of
+// 1 (for which that form has no 32-bit constant) selected afterwards. The two-way form in the shared header turns
+// into a branch per use here, and the set-up code of a tile group has a dozen of them.
+__device__ __forceinline__ int fdiv(const FastDiv &f, int n)
+{
+    const unsigned q = __umulhi((unsigned)n, f.magic) >> f.shift;
+    return f.d == 1 ? n : (int)q;
+}
+
 // Position in a wave's sequence of reduction rounds: (group, input block).
 struct Round { int g, cib; };
 
@@ -129,7 +138,7 @@ __device__ __forceinline__ Round next_round(Round r, int nCib, int nGroups)
 template <int TAPS>
 __device__ __forceinline__ GlobalFloat4s round_block(GlobalFloat4s f0, Round r, const FastDiv &div_nTg, int nCib)
 {
-    return f0 + ((size_t)div_nTg.div(r.g) * nCib + r.cib) * (TAPS * 64);
+    return f0 + ((size_t)fdiv(div_nTg, r.g) * nCib + r.cib) * (TAPS * 64);
 }
 
 // Filter values as they come from memory: a (cob, cib, tap) block is 16 x 16 floats [ci][co]; lane l requests
@@ -151,7 +160,7 @@ __device__ __forceinline__ void prefetch_first(ResKernArgs ka, int li, int w, in
     const int taps = ka->layer[li].taps, nCib = ka->layer[li].nCib;
     FastDiv div_nTg;
     div_nTg.magic = ka->layer[li].div_nTg.magic; div_nTg.shift = ka->layer[li].div_nTg.shift; div_nTg.d = ka->layer[li].div_nTg.d;
-    const int cob = div_nTg.div(w);
+    const int cob = fdiv(div_nTg, w);
     GlobalFloat4s fa = (GlobalFloat4s)(ka->layer[li].filt + (size_t)cob * nCib * taps * 256) + lane;
     asm volatile("" : "+v"(fa));
     if (taps == kResMaxTaps) {
@@ -211,7 +220,7 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
         // SIMD, and lose: without a higher priority a wave's set-up takes several times longer, and the two waves
         // end up running their reduction loops one after the other instead of side by side.
         __builtin_amdgcn_s_setprio(3);
-        const int cob = div_nTg.div(g), tg = g - cob * nTg;
+        const int cob = fdiv(div_nTg, g), tg = g - cob * nTg;
         // a folded projection: its filter blocks of this output block, requested now, used after the main rounds
         floatx4 proj[kResMaxProj];
         if (nCib2) {
@@ -224,7 +233,7 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
         for (int t = 0; t < T; ++t) {
             m[t] = (tg * T + t) * 16 + p;
             const int mc = m[t] < HoWo ? m[t] : HoWo - 1;
-            const int oy = div_Wo.div(mc), ox = mc - oy * Wo;
+            const int oy = fdiv(div_Wo, mc), ox = mc - oy * Wo;
             base[t] = in_off + q * in_plane + win0 + oy * stride * in_Wp + ox * stride;
             base2[t] = in2_off + q * in2_plane + win2 + oy * stride2 * in2_Wp + ox * stride2;
             o_at[t] = out_off >= 0 ? out_off + (cob * 4 + q) * out_plane + out_org + oy * out_Wp + ox : (cob * HoWo + mc) * 4 + q;
@@ -350,15 +359,15 @@ __device__ __forceinline__ void resident_stem(ResKernArgs ka, floatx4 *lds, floa
     int koff[kSteps];
 #pragma unroll
     for (int t = 0; t < kSteps; ++t) {
-        const int k = 4 * t + q, tap = div_C.div(k), ci = k - tap * sC, dy = div_kw.div(tap), dx = tap - dy * kw;
+        const int k = 4 * t + q, tap = fdiv(div_C, k), ci = k - tap * sC, dy = fdiv(div_kw, tap), dx = tap - dy * kw;
         koff[t] = k < K ? ci * in_plane + dy * in_Wp + dx : 0;
     }
 
     __builtin_amdgcn_s_setprio(3);
     if (w >= nGroups) return;
-    int cob_held = div_nTg.div(w);
+    int cob_held = fdiv(div_nTg, w);
     for (int g = w; g < nGroups; g += kResWaves) {
-        const int cob = div_nTg.div(g), tg = g - cob * nTg;
+        const int cob = fdiv(div_nTg, g), tg = g - cob * nTg;
         if (cob != cob_held) {
             stem_filter(ka, cob, lane, fa);
             cob_held = cob;
@@ -368,7 +377,7 @@ __device__ __forceinline__ void resident_stem(ResKernArgs ka, floatx4 *lds, floa
         for (int t = 0; t < T; ++t) {
             m[t] = (tg * T + t) * 16 + p;
             const int mc = m[t] < HoWo ? m[t] : HoWo - 1;
-            const int oy = div_Wo.div(mc), ox = mc - oy * Wo;
+            const int oy = fdiv(div_Wo, mc), ox = mc - oy * Wo;
             base[t] = win0 + oy * stride * in_Wp + ox * stride;
             o_at[t] = out_off >= 0 ? out_off + (cob * 4 + q) * out_plane + out_org + oy * out_Wp + ox : (cob * HoWo + mc) * 4 + q;
         }
@@ -429,7 +438,7 @@ __device__ __forceinline__ void resident_dw(ResKernArgs ka, int li, floatx4 *lds
             f[t] = t < taps ? *reinterpret_cast<const floatx4 *>(filt + ((size_t)(cb * taps + t) * 16 + 4 * qq))
                             : floatx4{0.f, 0.f, 0.f, 0.f};
         for (int m = lane; m < HoWo; m += 64) {
-            const int oy = div_Wo.div(m), ox = m - oy * Wo;
+            const int oy = fdiv(div_Wo, m), ox = m - oy * Wo;
             const int src = in_off + k * in_plane + win0 + oy * stride * in_Wp + ox * stride;
             floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -479,7 +488,7 @@ __device__ __forceinline__ void resident_head(ResKernArgs ka, int li, floatx4 *l
         const float *src = t + ((c >> 2) * in_plane + in_org) * 4 + (c & 3);
         float sum = 0.f;
         for (int m = quarter; m < HW; m += 4) {
-            const int y = div_W.div(m), x = m - y * W;
+            const int y = fdiv(div_W, m), x = m - y * W;
             sum += src[(y * in_Wp + x) * 4];
         }
         sum += __shfl_xor(sum, 1, 64);
@@ -535,7 +544,7 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
             if (w < ka->layer[0].nGroups) {
                 FastDiv d0;
                 d0.magic = ka->layer[0].div_nTg.magic; d0.shift = ka->layer[0].div_nTg.shift; d0.d = ka->layer[0].div_nTg.d;
-                stem_filter(ka, d0.div(w), lane, stem_fa);
+                stem_filter(ka, fdiv(d0, w), lane, stem_fa);
             }
             // fewer than 16 channels, blocked [y][x][c] or plain [c][y][x]: float planes [c][rows][pixels] in LDS
             const float *gin = ka->in + (size_t)n * in_floats;
@@ -546,14 +555,14 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
             for (int i = (int)threadIdx.x; i < in_floats; i += kResThreads) {
                 int c, y, x;
                 if (stem_in == 2) {
-                    const int row = div_sW.div(i);          // c * H + y
+                    const int row = fdiv(div_sW, i);          // c * H + y
                     x = i - row * sW;
-                    c = div_sH.div(row);
+                    c = fdiv(div_sH, row);
                     y = row - c * sH;
                 } else {
-                    const int pixel = div_sC.div(i);
+                    const int pixel = fdiv(div_sC, i);
                     c = i - pixel * sC;
-                    y = div_sW.div(pixel);
+                    y = fdiv(div_sW, pixel);
                     x = pixel - y * sW;
                 }
                 t[c * s_plane + s_org + y * s_Wp + x] = gin[i];
@@ -564,8 +573,8 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
 #pragma unroll 4
             for (int i = (int)threadIdx.x; i < (in_floats >> 2); i += kResThreads) {
                 const int pixel = i >> 2;
-                const int cbrow = div_sW.div(pixel), x = pixel - cbrow * sW;
-                const int cb = div_sH.div(cbrow), y = cbrow - cb * sH;
+                const int cbrow = fdiv(div_sW, pixel), x = pixel - cbrow * sW;
+                const int cb = fdiv(div_sH, cbrow), y = cbrow - cb * sH;
                 lds[s_off + (cb * 4 + (i & 3)) * s_plane + s_org + y * s_Wp + x] = gin[i];
             }
             clear_border(lds + s_off, ka->snCb * 4, sH, sW, ka->spt, ka->spb, ka->spl, ka->spr, w, lane);
