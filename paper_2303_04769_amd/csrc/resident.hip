@@ -236,7 +236,12 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
             const int oy = fdiv(div_Wo, mc), ox = mc - oy * Wo;
             base[t] = in_off + q * in_plane + win0 + oy * stride * in_Wp + ox * stride;
             base2[t] = in2_off + q * in2_plane + win2 + oy * stride2 * in2_Wp + ox * stride2;
-            o_at[t] = out_off >= 0 ? out_off + (cob * 4 + q) * out_plane + out_org + oy * out_Wp + ox : (cob * HoWo + mc) * 4 + q;
+            {
+                // (a select by mask: as a two-way expression this becomes a branch per tile)
+                const int gm = out_off >> 31;        // all ones when the result goes to HBM
+                const int o_lds = out_off + (cob * 4 + q) * out_plane + out_org + oy * out_Wp + ox, o_glb = (cob * HoWo + mc) * 4 + q;
+                o_at[t] = (o_lds & ~gm) | (o_glb & gm);
+            }
             r_at[t] = res_off + (cob * 4 + q) * res_plane + res_org + oy * res_Wp + ox;
         }
         floatx4 acc[T], b[T];
@@ -379,7 +384,12 @@ __device__ __forceinline__ void resident_stem(ResKernArgs ka, floatx4 *lds, floa
             const int mc = m[t] < HoWo ? m[t] : HoWo - 1;
             const int oy = fdiv(div_Wo, mc), ox = mc - oy * Wo;
             base[t] = win0 + oy * stride * in_Wp + ox * stride;
-            o_at[t] = out_off >= 0 ? out_off + (cob * 4 + q) * out_plane + out_org + oy * out_Wp + ox : (cob * HoWo + mc) * 4 + q;
+            {
+                // (a select by mask: as a two-way expression this becomes a branch per tile)
+                const int gm = out_off >> 31;        // all ones when the result goes to HBM
+                const int o_lds = out_off + (cob * 4 + q) * out_plane + out_org + oy * out_Wp + ox, o_glb = (cob * HoWo + mc) * 4 + q;
+                o_at[t] = (o_lds & ~gm) | (o_glb & gm);
+            }
         }
         floatx4 acc[T];
 #pragma unroll
