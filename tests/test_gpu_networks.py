@@ -755,3 +755,29 @@ def test_resident_runs_with_depthwise_layers(name, idx, N, launches):
         assert_close(got[n:n + 1], O.run_network(net, x[n:n + 1], ws), K, f"{name} resident, image {n} of {N}")
     if N <= 8:
         assert_close(got, _run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF).reshape(N, -1), K, f"{name}: resident vs layer by layer")
+
+
+def test_resident_run_falls_back_when_tensors_do_not_fit():
+    """Two 32-channel 72x72 tensors are 1.3 MB per image: no image-resident run even when forced; a later part of the
+    same table (after two stride-2 layers, 18x18) does fit and is taken."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("too_large_then_small", 32, 72, 72)
+    net.wshapes = [((32, 32, 3, 3), 288), ((32, 32, 3, 3), 288), ((32, 32, 3, 3), 288), ((32, 32, 3, 3), 288), ((16, 32, 1, 1), 32)]
+    p1, p2 = (1, 1, 1, 1), (0, 1, 0, 1)
+    net.layers = [
+        Layer("conv", 32, 32, 72, 72, 3, 3, 1, p1, src=IN, dst=0, w=0),
+        Layer("relu", 32, 32, 72, 72, src=0, dst=0),
+        Layer("conv", 32, 32, 72, 72, 3, 3, 2, p2, src=0, dst=1, w=1),
+        Layer("conv", 32, 32, 36, 36, 3, 3, 2, p2, src=1, dst=0, w=2),
+        Layer("relu", 32, 32, 18, 18, src=0, dst=0),
+        Layer("conv", 32, 32, 18, 18, 3, 3, 1, p1, src=0, dst=1, w=3),
+        Layer("conv", 32, 16, 18, 18, 1, 1, 1, (0, 0, 0, 0), src=1, dst=OUT, w=4),
+    ]
+    N = 2
+    x, ws = WL.network_tensors(net, N, 4242)
+    pn = S.PackedNetwork(net, ws, DEV)
+    on, off = pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON), pn.launches_at(N, S.SMALL_RUN_RESIDENT_OFF)
+    assert off == [0, 2, 3, 5, 6] and on[:2] == [0, 2] and len(on) < len(off), (on, off)
+    ref = O.run_network(net, x, ws)
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(ref.shape)
+    assert_close(got, ref, 288 * 16, "large then small, resident where it fits")
