@@ -69,7 +69,7 @@ struct ResLayerDev {
     int win0;                       // index inside an input plane of the window origin of output pixel (0, 0)
     int epilogue, T, nTg, nGroups;  // nTg: tile groups per output block; nGroups = nCob * nTg
     int tapoff[kResMaxTaps];        // dy * in.Wp + dx
-    int oH, oW, opt, opb, opl, opr; // the output tensor's image size and padding (border clearing)
+    int oH, oW, opt, opb, opc;      // the output tensor's image size and padding (border clearing)
     FastDiv div_Wo, div_nTg;
 };
 
@@ -78,7 +78,7 @@ struct ResArgs {
     float *out;
     int N, n_layers;
     ResTensorDev src;               // where the run's input goes
-    int sH, sW, snCb, spt, spb, spl, spr;
+    int sH, sW, snCb, spt, spb, spc;
     int in_floats, out_floats;      // floats per image of the run's input and output in HBM
     int stem_in;                    // the input has sC < 16 channels: 0 no, 1 blocked [H][W][sC], 2 plain [sC][H][W]
     int sC;
@@ -90,24 +90,26 @@ struct ResArgs {
 
 typedef const __attribute__((address_space(4))) ResArgs *ResKernArgs;
 
-// Clears the padding rows and columns of the planes of a tensor (float4 planes of 4 channels, or float planes of
-// one channel for a first layer's input): wave w takes planes w, w + 8, ...; no divisions (vector-ALU time is
-// matrix-pipe time here).
+// Clears the padding of the planes of a tensor (float4 planes of 4 channels, or float planes of one channel for a
+// first layer's input): wave w takes planes w, w + 8, ...; no divisions (vector-ALU time is matrix-pipe time
+// here). A plane is pt padding rows, H image rows, pb padding rows, every row pc padding pixels followed by W
+// pixels, and pc more padding pixels at the very end: the pixel to the right of a row's last one is the next
+// row's first padding pixel, so left and right padding share their columns (34 x 33 + 1 instead of 34 x 34 pixels
+// for a 32 x 32 image padded by one).
 template <typename E>
-__device__ __forceinline__ void clear_border(E *tensor, int n_planes, int H, int W, int pt, int pb, int pl, int pr, int w, int lane)
+__device__ __forceinline__ void clear_border(E *tensor, int n_planes, int H, int W, int pt, int pb, int pc, int w, int lane)
 {
-    const int Wp = pl + W + pr, plane = (pt + H + pb) * Wp;
-    const int top = pt * Wp, bot = pb * Wp;
+    const int Wp = pc + W, plane = (pt + H + pb) * Wp + pc;
+    const int top = pt * Wp, bot = pb * Wp + pc;
     const E zero = E{};
     for (int k = w; k < n_planes; k += kResWaves) {
         E *t = tensor + k * plane;
         for (int r = lane; r < top; r += 64) t[r] = zero;
         for (int r = lane; r < bot; r += 64) t[(pt + H) * Wp + r] = zero;
-        if (pl + pr) {
+        if (pc) {
             for (int row = lane; row < H; row += 64) {
                 E *line = t + (pt + row) * Wp;
-                for (int x = 0; x < pl; ++x) line[x] = zero;
-                for (int x = 0; x < pr; ++x) line[pl + W + x] = zero;
+                for (int x = 0; x < pc; ++x) line[x] = zero;
             }
         }
     }
@@ -577,7 +579,7 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
                 }
                 t[c * s_plane + s_org + y * s_Wp + x] = gin[i];
             }
-            clear_border(t, sC, sH, sW, ka->spt, ka->spb, ka->spl, ka->spr, w, lane);
+            clear_border(t, sC, sH, sW, ka->spt, ka->spb, ka->spc, w, lane);
         } else {
             const floatx4 *gin = reinterpret_cast<const floatx4 *>(ka->in + (size_t)n * in_floats);
 #pragma unroll 4
@@ -587,7 +589,7 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
                 const int cb = fdiv(div_sH, cbrow), y = cbrow - cb * sH;
                 lds[s_off + (cb * 4 + (i & 3)) * s_plane + s_org + y * s_Wp + x] = gin[i];
             }
-            clear_border(lds + s_off, ka->snCb * 4, sH, sW, ka->spt, ka->spb, ka->spl, ka->spr, w, lane);
+            clear_border(lds + s_off, ka->snCb * 4, sH, sW, ka->spt, ka->spb, ka->spc, w, lane);
         }
         __syncthreads();
 
@@ -615,7 +617,7 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
             // while the others still compute)
             if (kind != RES_HEAD && ka->layer[li].out.off >= 0)
                 clear_border(lds + ka->layer[li].out.off, ka->layer[li].nCob * 4, ka->layer[li].oH, ka->layer[li].oW,
-                             ka->layer[li].opt, ka->layer[li].opb, ka->layer[li].opl, ka->layer[li].opr, w, lane);
+                             ka->layer[li].opt, ka->layer[li].opb, ka->layer[li].opc, w, lane);
             if (li + 1 < n_layers) prefetch_first(ka, li + 1, w, lane, a_pre);
             else if (n + (int)gridDim.x < N) prefetch_first(ka, 0, w, lane, a_pre);
             __syncthreads();   // the layer's output is complete, its input may be overwritten
@@ -749,7 +751,8 @@ bool plan_prefix(const ResGroup *g_in, int n_in, ResArgs &a, int &lds_bytes)
     }
     for (int k = 0; k < n_inst; ++k) {
         const Pads &pd = inst[k].pad;
-        const int padded = (pd.t + inst[k].H + pd.b) * (pd.l + inst[k].W + pd.r);
+        const int pc = imax(pd.l, pd.r);       // left and right padding share their columns
+        const int padded = (pd.t + inst[k].H + pd.b) * (pc + inst[k].W) + pc;
         inst[k].bytes = inst[k].planar ? (inst[k].C * padded * 4 + 63) / 64 * 64 : (inst[k].C / 16) * padded * 64;
     }
     // regions, in the order of the run
@@ -797,15 +800,15 @@ bool plan_prefix(const ResGroup *g_in, int n_in, ResArgs &a, int &lds_bytes)
 
     auto dev = [&](int i) {
         const Instance &t = inst[i];
-        const int Wp = t.pad.l + t.W + t.pad.r;
-        return ResTensorDev{t.off / 16, Wp, (t.pad.t + t.H + t.pad.b) * Wp, t.pad.t * Wp + t.pad.l};
+        const int pc = imax(t.pad.l, t.pad.r), Wp = pc + t.W;
+        return ResTensorDev{t.off / 16, Wp, (t.pad.t + t.H + t.pad.b) * Wp + pc, t.pad.t * Wp + pc};
     };
     memset(&a, 0, sizeof(a));
     a.n_layers = n;
     a.slot = peak / 16;
     a.src = dev(0);
     a.sH = inst[0].H; a.sW = inst[0].W; a.snCb = inst[0].C / 16; a.sC = inst[0].C;
-    a.spt = inst[0].pad.t; a.spb = inst[0].pad.b; a.spl = inst[0].pad.l; a.spr = inst[0].pad.r;
+    a.spt = inst[0].pad.t; a.spb = inst[0].pad.b; a.spc = imax(inst[0].pad.l, inst[0].pad.r);
     a.stem_in = g[0].kind == RESIDENT_STEM ? (g[0].plain_input ? 2 : 1) : 0;
     a.in_floats = inst[0].C * a.sH * a.sW;
     a.out_floats = g[n - 1].Co * g[n - 1].Ho * g[n - 1].Wo;
@@ -824,14 +827,14 @@ bool plan_prefix(const ResGroup *g_in, int n_in, ResArgs &a, int &lds_bytes)
         d.out = k + 1 < n ? dev(out_i[k]) : ResTensorDev{-1, 0, 0, 0};
         d.res = res_i[k] >= 0 ? dev(res_i[k]) : ResTensorDev{0, 0, 0, 0};
         d.Wo = c.Wo; d.HoWo = c.Ho * c.Wo; d.nCib = c.Ci / 16; d.nCob = c.Co / 16; d.stride = c.stride; d.taps = c.kh * c.kw;
-        d.win0 = (x.pad.t - c.pt) * d.in.Wp + (x.pad.l - c.pl);
+        d.win0 = (x.pad.t - c.pt) * d.in.Wp + (imax(x.pad.l, x.pad.r) - c.pl);
         if (pj[k]) {
             const Instance &x2 = inst[in2_i[k]];
             d.filt2 = pj[k]->filt;
             d.in2 = dev(in2_i[k]);
             d.nCib2 = pj[k]->Ci / 16;
             d.stride2 = pj[k]->stride;
-            d.win2 = x2.pad.t * d.in2.Wp + x2.pad.l;
+            d.win2 = x2.pad.t * d.in2.Wp + imax(x2.pad.l, x2.pad.r);
         }
         d.epilogue = c.epilogue;
         // tiles per wave and step: the split that needs the fewest rounds of the 8 waves, the larger group on a tie
@@ -861,7 +864,7 @@ bool plan_prefix(const ResGroup *g_in, int n_in, ResArgs &a, int &lds_bytes)
             d.nCob = 1; d.T = 1; d.nTg = 1; d.nGroups = 1; d.taps = 0;
             continue;
         }
-        d.oH = y.H; d.oW = y.W; d.opt = y.pad.t; d.opb = y.pad.b; d.opl = y.pad.l; d.opr = y.pad.r;
+        d.oH = y.H; d.oW = y.W; d.opt = y.pad.t; d.opb = y.pad.b; d.opc = imax(y.pad.l, y.pad.r);
         d.div_Wo = make_fastdiv(c.Wo);
         d.div_nTg = make_fastdiv(d.nTg);
     }
