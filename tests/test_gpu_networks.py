@@ -781,3 +781,35 @@ def test_resident_run_falls_back_when_tensors_do_not_fit():
     ref = O.run_network(net, x, ws)
     got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(ref.shape)
     assert_close(got, ref, 288 * 16, "large then small, resident where it fits")
+
+
+@pytest.mark.parametrize("case", [
+    # (C0, H, W, first layer (Co, kh, kw, stride, pad), second layer (kh, kw, pad))
+    (4, 13, 17, (16, 3, 3, 1, (1, 1, 1, 1)), (1, 9, (0, 0, 4, 4))),
+    (8, 12, 10, (32, 2, 2, 2, (0, 0, 0, 0)), (9, 1, (4, 4, 0, 0))),
+    (1, 21, 19, (16, 5, 5, 2, (2, 2, 2, 2)), (3, 3, (1, 1, 1, 1))),
+    (2, 9, 30, (48, 4, 5, 1, (1, 2, 2, 2)), (1, 1, (0, 0, 0, 0))),
+])
+def test_resident_run_with_unusual_windows(case):
+    """First layers with other channel counts and window shapes (reductions of 36, 32, 25 and 40 values), followed by
+    nine-tap convolutions that are not 3x3 (1x9, 9x1; padding on one axis only), inside one image-resident run."""
+    from workloads.nets import Layer, Network, IN, OUT
+    C0, H, W, (Co, kh, kw, s, pad), (kh2, kw2, pad2) = case
+    net = Network("unusual_windows", C0, H, W)
+    a = Layer("conv", C0, Co, H, W, kh, kw, s, pad, src=IN, dst=0, w=0)
+    b = Layer("conv", Co, 32, a.Ho, a.Wo, kh2, kw2, 1, pad2, src=0, dst=1, w=1)
+    net.wshapes = [((Co, C0, kh, kw), C0 * kh * kw), ((32, Co, kh2, kw2), Co * kh2 * kw2), ((16, 32, 3, 3), 288)]
+    net.layers = [a, Layer("relu", Co, Co, a.Ho, a.Wo, src=0, dst=0), b, Layer("relu", 32, 32, b.Ho, b.Wo, src=1, dst=1),
+                  Layer("conv", 32, 16, b.Ho, b.Wo, 3, 3, 1, (1, 1, 1, 1), src=1, dst=OUT, w=2)]
+    N = 3
+    x, ws = WL.network_tensors(net, N, 9100 + C0)
+    pn = S.PackedNetwork(net, ws, DEV)
+    assert pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON) == [0], pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON)
+    ref = O.run_network(net, x, ws)
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(ref.shape)
+    assert_close(got, ref, 288 * 9, f"unusual windows {case}")
+    # the same from the plain input
+    g = Guarded(pn.out_elems(N))
+    pn.run_opt(dev(x), g.t, N, S.SMALL_RUN_RESIDENT_ON | S.SMALL_RUN_PLAIN_INPUT)
+    L = net.layers[-1]
+    assert_close(O.unpack(g.check(), (N, L.Co, L.Ho, L.Wo), L.Cob).reshape(ref.shape), ref, 288 * 9, "from the plain input")
