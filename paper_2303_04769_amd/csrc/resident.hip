@@ -1,28 +1,33 @@
-// A run of convolutions in one kernel, one image per workgroup, every tensor between them in LDS.
+// A run of layers in one kernel, one image per workgroup, every tensor between them in LDS.
 //
 // The small networks of Section "MLPerf:Tiny Inference Models" have activations of a few tens of kilobytes per
 // image: 16 x 32 x 32 floats are 64 KB, and a compute unit of this chip has 160 KB of LDS. So a workgroup can
-// take one image through a whole run of convolution layers (with their folded ReLU / residual add, Table 2) and
-// touch HBM only for the run's input, its last output and the filters (which all workgroups share through L2).
-// This is the abstract fused layer of the paper's "Conclusion & Future Directions" taken across layers of the
-// partial-reduction class of Table 1, where a pixel tile cannot be carried from layer to layer because of the
-// halo: the whole image is the tile. What it removes is per-launch cost (ramp, drain, the gap between dependent
-// kernels), which dominates layer-by-layer runs of these networks at a batch of a few hundred images.
+// take one image through a whole run of layers and touch HBM only for the run's input, its last output and the
+// filters (which all workgroups share through L2): a first convolution on fewer than 16 input channels, then
+// convolutions on 16-channel blocks (with their folded ReLU / residual add, Table 2; a 1x1 projection shortcut
+// becomes extra reduction rounds of the convolution it is added to) and depthwise convolutions, closed by an
+// average pooling over the whole image + fully connected layer. This is the abstract fused layer of the paper's
+// "Conclusion & Future Directions" taken across layers of the partial-reduction class of Table 1, where a pixel tile
+// cannot be carried from layer to layer because of the halo: the whole image is the tile. What it removes is
+// per-launch cost (ramp, drain, the gap between dependent kernels), which dominates layer-by-layer runs of these
+// networks at a batch of a few hundred images.
 //
 // LDS layout. Every tensor of the run lives in LDS as [C/16][4][rows][pixels][4]: a 16-channel block is split into
 // four planes of 4 channels, so that the 16 lanes which read 16 neighbouring pixels' float4 touch 256 contiguous
 // bytes (with all 16 channels of a pixel together they would be 64 bytes apart and share LDS banks). Zero-padded
-// by as many rows / columns as its consumers' windows reach outside the image, so that the reduction loop reads
-// with no bounds test at all: the address of an input value is (tile base) + (tap, input block offset), the
-// second term wave-uniform. A layer's workgroup first clears the border of its output tensor, then computes the
-// interior; a barrier separates layers. Regions are handed out by the host from the tensors' lifetimes; the
-// result of a convolution with a residual add overwrites the residual in place when nothing else reads it
-// (each lane reads exactly the elements it then writes), which is what lets the 16-channel stage of the
-// residual CNN (three live 72 KB tensors in the table) fit.
+// by as many rows / columns as its consumers' windows reach outside the image (left and right padding share their
+// columns, see clear_border), so that the reduction loop reads with no bounds test at all: the address of an input
+// value is (tile base) + (tap, input block offset), the second term wave-uniform. The padding of a layer's result
+// is cleared by the waves that finish the layer early; a barrier separates layers. Regions are handed out by the
+// host from the tensors' lifetimes (first fit); the result of a convolution with a residual add overwrites the
+// residual in place when nothing else reads it (each lane reads exactly the elements it then writes), which is
+// what lets the 16-channel stage of the residual CNN (three live 70 KB tensors in the table) fit. The top 8 KB
+// are the waves' private kilobytes for filter blocks in transit.
 //
-// Work split. 8 waves. A wave takes (output channel block, group of T 16-pixel tiles) pairs; per reduction step
-// (input block, tap) it reads T float4 B operands from LDS and 4 A operands (filter values, from global memory,
-// L2-resident, requested one input block ahead) and issues 4 T matrix instructions:
+// Work split. 8 waves (two per SIMD, 256 registers each). A wave takes (output channel block, group of T 16-pixel
+// tiles) pairs; per reduction step (input block, tap) it reads T float4 B operands from LDS, takes the step's 4 A
+// operands (a 16 x 16 filter block, requested from global memory one round of taps ahead as one coalesced float4
+// per lane and transposed through the wave's LDS kilobyte one step ahead) and issues 4 T matrix instructions:
 //   A (filter):  lane (p = l % 16, q = l / 16) in MFMA j supplies filt[ci = 4q + j][co = p];
 //   B (input):   lane (p, q) supplies channels 4q .. 4q + 3 of pixel p as one float4 (MFMA j takes element j);
 //   D (output):  lane (p, q) receives channels 4q .. 4q + 3 of pixel p: the B layout again, stored as one float4.
@@ -55,9 +60,9 @@ enum : int { RES_CONV = 0, RES_STEM = 1, RES_HEAD = 2, RES_DW = 3 };
 constexpr int kStemMaxK = 40;        // reduction length of a first layer (input channels x taps), 10 steps of 4
 
 struct ResLayerDev {
-    int kind;                       // RES_CONV; RES_DW: depthwise convolution (at most 9 taps); RES_STEM: the first layer on an input of fewer than 16 channels (LDS
-                                    // holds it as [C][rows][pixels] floats); RES_HEAD: average pooling over the whole
-                                    // image + fully connected layer
+    int kind;                       // RES_CONV; RES_DW: depthwise convolution (at most 9 taps); RES_STEM: the first
+                                    // layer on an input of fewer than 16 channels (LDS holds it as [C][rows][pixels]
+                                    // floats); RES_HEAD: average pooling over the whole image + fully connected layer
     int K;                          // STEM: Ci * kh * kw; HEAD: channels
     int Co, Cob;                    // HEAD: outputs and their block
     const float *filt;
