@@ -222,6 +222,15 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
         ar[0] = p1[0];
     }
 
+    // A wave's next group often is the same tiles a whole number of image rows further down (same output block, no
+    // ragged tile): its indices then follow from the previous group's by additions.
+    constexpr int kStepPixels = kResWaves * T * 16;
+    const int step_rows = fdiv(div_Wo, kStepPixels);
+    const bool by_rows = step_rows * Wo == kStepPixels;
+    const int d_base = step_rows * stride * in_Wp, d_base2 = step_rows * stride2 * in2_Wp, d_res = step_rows * res_Wp;
+    const int d_out = out_off >= 0 ? step_rows * out_Wp : kStepPixels * 4;
+    int base[T], base2[T], m[T], o_at[T], r_at[T];   // where the tile's values are read, stored, the residual read
+    bool inside_before = false;
     for (int g = w; g < nGroups; g += kResWaves) {
         // Index arithmetic and stores of one wave compete with the matrix instructions of the wave that shares its
         // SIMD, and lose: without a higher priority a wave's set-up takes several times longer, and the two waves
@@ -235,7 +244,15 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
 #pragma unroll
             for (int c = 0; c < kResMaxProj; ++c) proj[c] = f2[(c < nCib2 ? c : 0) * 64];
         }
-        int base[T], base2[T], m[T], o_at[T], r_at[T];   // where the tile's values are read, stored, the residual read
+        const bool inside = (tg * T + T) * 16 <= HoWo;
+        const bool step = g != w && by_rows && inside_before && inside && tg >= kResWaves;
+        inside_before = inside;
+        if (step) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                base[t] += d_base; base2[t] += d_base2; m[t] += kStepPixels; o_at[t] += d_out; r_at[t] += d_res;
+            }
+        } else
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             m[t] = (tg * T + t) * 16 + p;
