@@ -231,7 +231,8 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
  * "Conclusion & Future Directions" across layers of Table 1's partial-reduction class. Depthwise convolutions
  * (16-channel blocks, at most 9 taps, filter 16-byte aligned) may stand inside a run, and a 1x1 convolution added onto
  * the convolution before it (a projection shortcut) is folded into that one. Without either RESIDENT flag such runs
- * are used when 160 <= N <= 256 (about one image per compute unit, one round) and the run averages at least
+ * are used when 144 <= N <= 256 or 448 <= N <= 512 (one or two full rounds of one image per compute unit; measured
+ * break-even points against the layer-by-layer kernels) and the run averages at least
  * 500000 multiply-adds per layer and image (below that the per-layer cost inside a workgroup outweighs the
  * launches saved: measured on the depthwise-separable CNNs); small_network_run,
  * small_network_run_plain and small_network_run_range follow that rule too (small_network_run_plain then also

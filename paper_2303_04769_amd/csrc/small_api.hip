@@ -691,15 +691,20 @@ int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now,
     return macs >= 5e5 * taken ? taken : 0;
 }
 
-// Image-resident runs pay off when the batch is about one image per compute unit: with fewer images most of the
-// chip idles for the time one image takes, and from two rounds on the layer-by-layer kernels, whose per-launch
-// costs are then spread over more images, are as fast or faster (measured on the residual CNN: 89 against 109 us
-// at 256 images, 169 against 170 us at 512, 329 against 290 us at 1024).
+// Image-resident runs pay off when the batch is about one or two images per compute unit. A run costs rounds x
+// (one image in one workgroup); layer-by-layer launches cost a fixed part plus a part per image, so with few images
+// they win because most of the chip would idle for the time one image takes, and from three rounds on because
+// their fixed part is spread over more images. Measured on the residual CNN (us, layer by layer / resident):
+// 81 / 82 at 128 images, 96 / 82 at 160, 109 / 82 at 256, 141 / 156 at 384, 164 / 156 at 448, 169 / 156 at 512,
+// 231 / 230 at 768, 289 / 305 at 1024.
 bool resident_batch(int N, unsigned flags)
 {
     if (flags & SMALL_RUN_RESIDENT_OFF) return false;
     if (flags & SMALL_RUN_RESIDENT_ON) return true;
-    return N <= kResidentWorkgroups && 8 * N >= 5 * kResidentWorkgroups;
+    const int rounds = (N + kResidentWorkgroups - 1) / kResidentWorkgroups;
+    if (rounds == 1) return 16 * N >= 9 * kResidentWorkgroups;        // at least 144 images
+    if (rounds == 2) return 8 * N >= 14 * kResidentWorkgroups;        // at least 448
+    return false;
 }
 
 // Walks the table once: validates every layer, tracks the shape held by every logical buffer and

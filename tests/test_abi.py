@@ -108,8 +108,8 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
         if L.w is not None:
             tr[k].filt = 0x1000
     at = lambda N, flags=0: B.small_network_launches_at(tr, N, r.C0, r.H0, r.W0, flags)
-    assert at(256) == [0] == at(160) == at(200) == at(1, B.SMALL_RUN_RESIDENT_ON) == at(1000, B.SMALL_RUN_RESIDENT_ON)
-    assert at(1) == at(159) == at(257) == at(512) == at(256, B.SMALL_RUN_RESIDENT_OFF) == B.small_network_launches(tr)
+    assert at(256) == [0] == at(144) == at(200) == at(448) == at(512) == at(1, B.SMALL_RUN_RESIDENT_ON) == at(1000, B.SMALL_RUN_RESIDENT_ON)
+    assert at(1) == at(143) == at(257) == at(447) == at(513) == at(1024) == at(256, B.SMALL_RUN_RESIDENT_OFF) == B.small_network_launches(tr)
     # too little arithmetic per layer for a workgroup-per-image run: the depthwise-separable networks stay layer by
     # layer unless forced
     for other in (WL.dsep_cnn(), a):

@@ -619,7 +619,7 @@ def test_resident_run_is_the_default_at_full_batches():
     x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 2)
     pn = S.PackedNetwork(net, ws, DEV)
     assert pn.launches_at(N) == [0] and len(pn.launches_at(N, S.SMALL_RUN_RESIDENT_OFF)) == 10
-    assert len(pn.launches_at(64)) == 10 and len(pn.launches_at(300)) == 10 and len(pn.launches_at(200)) == 1
+    assert len(pn.launches_at(64)) == 10 and len(pn.launches_at(300)) == 10 and len(pn.launches_at(200)) == 1 and len(pn.launches_at(512)) == 1
     a = _run(net, x, ws).reshape(N, -1)
     b = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(N, -1)
     assert_bits(a, b, "default run at batch 256 is the resident run")
