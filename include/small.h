@@ -233,8 +233,8 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
  * the convolution before it (a projection shortcut) is folded into that one. Without either RESIDENT flag such runs
  * are used when 144 <= N <= 256 or 448 <= N <= 512 (one or two full rounds of one image per compute unit; measured
  * break-even points against the layer-by-layer kernels) and the run averages at least
- * 500000 multiply-adds per layer and image (below that the per-layer cost inside a workgroup outweighs the
- * launches saved: measured on the depthwise-separable CNNs); small_network_run,
+ * 250000 (one round) or 500000 (two rounds) multiply-adds per layer and image (below that the per-layer cost inside
+ * a workgroup outweighs the launches saved: measured on the depthwise-separable CNNs); small_network_run,
  * small_network_run_plain and small_network_run_range follow that rule too (small_network_run_plain then also
  * accepts tables whose first layer only the run's own first-layer code can take from a plain tensor). Results
  * agree with the layer-by-layer kernels within the conv tolerance, not bit for bit (another summation order).
