@@ -221,6 +221,11 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
 /* small_network_run_opt: small_network_run with options (flags, a sum of SMALL_RUN_*; unknown bits: SMALL_ERR_SHAPE).
  *   SMALL_RUN_PLAIN_INPUT   `in` is a plain [N][C0][H0][W0] tensor: exactly small_network_run_plain.
  *   SMALL_RUN_RESIDENT_OFF  never use image-resident runs (below); SMALL_RUN_RESIDENT_ON: use them at any batch size.
+ *   SMALL_RUN_PLAIN_OUTPUT  the caller reads `out_blocked` as a plain [N][C][H][W] tensor (the layout change at the
+ *                           network's other boundary). Accepted when blocked and plain layout coincide, i.e. the
+ *                           result has one pixel per image and one channel block (H = W = 1, C = Cb: the logits of a
+ *                           classifier head); then no small_unpack is needed. Otherwise SMALL_ERR_LAYER, nothing
+ *                           enqueued: run without the flag and call small_unpack.
  * Image-resident runs: consecutive layers whose per-image tensors fit 152 KB of LDS together run as ONE launch,
  * one image per workgroup (256 workgroups, further images in further rounds): optionally a first convolution on
  * fewer than 16 input channels that reads the network input (Ci * kh * kw <= 40), then convolutions with 16-channel
@@ -240,7 +245,7 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
  * agree with the layer-by-layer kernels within the conv tolerance, not bit for bit (another summation order).
  * small_network_launches_at: the first layer of every launch that a run with these N, C0, H0, W0 and flags makes
  * (small_network_launches: the batch-independent list without image-resident runs). Host-only, no GPU needed. */
-enum { SMALL_RUN_PLAIN_INPUT = 1, SMALL_RUN_RESIDENT_OFF = 2, SMALL_RUN_RESIDENT_ON = 4 };
+enum { SMALL_RUN_PLAIN_INPUT = 1, SMALL_RUN_RESIDENT_OFF = 2, SMALL_RUN_RESIDENT_ON = 4, SMALL_RUN_PLAIN_OUTPUT = 8 };
 int small_network_run_opt(const small_layer *layers, int n_layers, const float *in, float *out_blocked, void *workspace,
                           size_t workspace_bytes, int N, int C0, int H0, int W0, unsigned flags, void *stream);
 int small_network_launches_at(const small_layer *layers, int n_layers, int N, int C0, int H0, int W0, unsigned flags,

@@ -298,7 +298,7 @@ def small_network_run_plain(table, in_nchw, out_blocked, workspace, workspace_by
                                           workspace_bytes, N, C0, H0, W0, _stream(stream)), "small_network_run_plain")
 
 
-SMALL_RUN_PLAIN_INPUT, SMALL_RUN_RESIDENT_OFF, SMALL_RUN_RESIDENT_ON = 1, 2, 4
+SMALL_RUN_PLAIN_INPUT, SMALL_RUN_RESIDENT_OFF, SMALL_RUN_RESIDENT_ON, SMALL_RUN_PLAIN_OUTPUT = 1, 2, 4, 8
 
 
 def small_network_run_opt(table, in_tensor, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, flags, stream=None):

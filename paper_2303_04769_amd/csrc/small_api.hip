@@ -906,6 +906,12 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
         if (!run && l.dst >= 0 && out_elems > plan.slot_elems[l.dst]) plan.slot_elems[l.dst] = out_elems;
         if (!run && l.dst == SMALL_BUF_OUT && out_elems > plan.out_elems) plan.out_elems = out_elems;
     }
+    if (flags & SMALL_RUN_PLAIN_OUTPUT) {
+        // The caller takes the result as a plain [N][C][H][W] tensor. That is what the last layer writes anyway when
+        // the two layouts coincide: one pixel per image and one channel block (the logits of a classifier head).
+        const Shape &r = shp[idx(SMALL_BUF_OUT)];
+        if (!r.set || r.H != 1 || r.W != 1 || r.C != r.Cb) return SMALL_ERR_LAYER;
+    }
     if (!run) {
         size_t m = 0;
         for (int k = 0; k < SMALL_MAX_SLOTS; ++k)
@@ -957,7 +963,7 @@ static int network_run_impl(const small_layer *layers, int n_layers, const float
 int small_network_run_opt(const small_layer *layers, int n_layers, const float *in, float *out_blocked, void *workspace,
                           size_t workspace_bytes, int N, int C0, int H0, int W0, unsigned flags, void *stream)
 {
-    if (flags & ~(unsigned)(SMALL_RUN_PLAIN_INPUT | SMALL_RUN_RESIDENT_OFF | SMALL_RUN_RESIDENT_ON)) return SMALL_ERR_SHAPE;
+    if (flags & ~(unsigned)(SMALL_RUN_PLAIN_INPUT | SMALL_RUN_RESIDENT_OFF | SMALL_RUN_RESIDENT_ON | SMALL_RUN_PLAIN_OUTPUT)) return SMALL_ERR_SHAPE;
     return network_run_impl(layers, n_layers, in, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, 0, INT_MAX,
                             stream, flags);
 }
@@ -966,7 +972,7 @@ int small_network_launches_at(const small_layer *layers, int n_layers, int N, in
                               int *first_layer, int *n_launches)
 {
     if (!layers || !n_launches) return SMALL_ERR_NULL;
-    if (flags & ~(unsigned)(SMALL_RUN_PLAIN_INPUT | SMALL_RUN_RESIDENT_OFF | SMALL_RUN_RESIDENT_ON)) return SMALL_ERR_SHAPE;
+    if (flags & ~(unsigned)(SMALL_RUN_PLAIN_INPUT | SMALL_RUN_RESIDENT_OFF | SMALL_RUN_RESIDENT_ON | SMALL_RUN_PLAIN_OUTPUT)) return SMALL_ERR_SHAPE;
     NetPlan plan;
     return walk(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr, 0, INT_MAX, flags,
                 first_layer, n_launches);

@@ -123,7 +123,13 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
         assert (plan(256) == [0]) == (other is a) and (plan(256) == B.small_network_launches(to)) == (other is not a)
     assert at(256, B.SMALL_RUN_PLAIN_INPUT) == [0] == at(2, B.SMALL_RUN_PLAIN_INPUT | B.SMALL_RUN_RESIDENT_ON)
     n = C.c_int(0)
-    assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 8, None, C.byref(n)) == 2     # unknown flag
+    assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 16, None, C.byref(n)) == 2    # unknown flag
+    # plain output: only where the blocked result is the plain one (the classifiers' logits), not for a feature map
+    assert at(256, B.SMALL_RUN_PLAIN_OUTPUT | B.SMALL_RUN_PLAIN_INPUT) == [0]
+    s1 = WL.single_conv_relu()
+    ts = B.make_layer_table(s1.layers, [None] * len(s1.wshapes))
+    ts[0].filt = 0x1000
+    assert lib.small_network_launches_at(ts, len(ts), 4, s1.C0, s1.H0, s1.W0, B.SMALL_RUN_PLAIN_OUTPUT, None, C.byref(n)) == 7
     assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 0, None, None) == 1
     # planning looks ahead over layers that have not been validated yet: a bad buffer id further down is an error
     # code, whatever the flags

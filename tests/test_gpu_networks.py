@@ -813,3 +813,28 @@ def test_resident_run_with_unusual_windows(case):
     pn.run_opt(dev(x), g.t, N, S.SMALL_RUN_RESIDENT_ON | S.SMALL_RUN_PLAIN_INPUT)
     L = net.layers[-1]
     assert_close(O.unpack(g.check(), (N, L.Co, L.Ho, L.Wo), L.Cob).reshape(ref.shape), ref, 288 * 9, "from the plain input")
+
+
+@pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 256), ("residual_cnn", 2, 5), ("audio_cnn", 4, 7), ("dsep_cnn", 3, 2)])
+def test_plain_output_is_the_unpacked_result(name, idx, N):
+    """The logits of the classifier heads (one pixel, one channel block) are the same bytes blocked or plain: a run
+    with SMALL_RUN_PLAIN_OUTPUT equals small_unpack of a run without it; a feature-map result is refused."""
+    net = getattr(WL, name)()
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 90 + idx)
+    pn = S.PackedNetwork(net, ws, DEV)
+    xb = pn.pack_input(dev(x))
+    L = net.layers[-1]
+    g0, g1 = Guarded(pn.out_elems(N)), Guarded(pn.out_elems(N))
+    pn.run_opt(xb, g0.t, N, 0)
+    plain = torch.empty(pn.out_elems(N), dtype=torch.float32, device=DEV)
+    S.small_unpack(g0.t, plain, N, L.Co, L.Ho, L.Wo, L.Cob)
+    pn.run_opt(xb, g1.t, N, S.SMALL_RUN_PLAIN_OUTPUT)
+    assert_bits(g1.check(), plain.cpu().numpy(), f"{name}: plain output")
+    assert_close(g1.check().reshape(N, -1), O.run_network(net, x, ws), _maxK(net) * 9, f"{name}: plain output vs oracle")
+    fm = WL.single_conv_relu()
+    xf, wf = WL.network_tensors(fm, 2, 3)
+    pf = S.PackedNetwork(fm, wf, DEV)
+    gf = Guarded(pf.out_elems(2))
+    with pytest.raises(S.SmallError) as e:
+        pf.run_opt(pf.pack_input(dev(xf)), gf.t, 2, S.SMALL_RUN_PLAIN_OUTPUT)
+    assert e.value.code == 7 and (gf.check() == np.float32(CANARY)).all()
