@@ -69,6 +69,7 @@ struct ResLayerDev {
     const float *filt2;             // CONV: a 1x1 convolution of a second tensor (in2) summed into the same result:
     ResTensorDev in2;               // the projection shortcut of a residual block as extra reduction rounds
     int nCib2, stride2, win2;       // (nCib2 = 0: none)
+    int rows3;                      // CONV with nine taps: they are a 3 x 3 window
     ResTensorDev in, out, res;      // out.off < 0: the run's last layer, the result goes to HBM
     int Wo, HoWo, nCib, nCob, stride, taps;
     int win0;                       // index inside an input plane of the window origin of output pixel (0, 0)
@@ -181,7 +182,9 @@ __device__ __forceinline__ void prefetch_first(ResKernArgs ka, int li, int w, in
 // ar: on entry the filter blocks of this wave's first round (prefetch_first). Ring entry x > 0 holds tap x of the
 // current round until step x - 1 passes it on to LDS, and is then refilled with tap x of the next round; entry 0
 // is passed on in a round's last step (for the next round's first) and refilled from the round after that.
-template <int T, int TAPS>
+// ROWS3: the nine taps are a 3 x 3 window: per round the three row bases of every tile are formed once and the
+// column offsets travel as immediates of the LDS reads, instead of one address addition per read.
+template <int T, int TAPS, bool ROWS3>
 __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *lds, floatx4 *gout, int w, int lane,
                                               floatx4 (&ar)[kResMaxTaps], int slot)
 {
@@ -283,6 +286,13 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
             // made a round ahead into requests made at the point of use
             GlobalFloat4s p1 = round_block<TAPS>(f0, r1, div_nTg, nCib), p2 = round_block<TAPS>(f0, r2, div_nTg, nCib);
             asm volatile("" : "+v"(p1), "+v"(p2));
+            int rowb[T][3];
+            if (ROWS3) {
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) rowb[t][r] = base[t] + coff + r * in_Wp;
+            }
 #pragma unroll
             for (int tap = 0; tap < TAPS; ++tap) {
                 constexpr int kLast = TAPS - 1;
@@ -295,8 +305,13 @@ __device__ __forceinline__ void resident_conv(ResKernArgs ka, int li, floatx4 *l
                 for (int j = 0; j < 4; ++j) a_nxt[j] = slot_r[j * 64];
                 ar[x] = x ? p1[x * 64] : p2[0];
                 if (tap < kLast) {
+                    if (ROWS3) {
 #pragma unroll
-                    for (int t = 0; t < T; ++t) b_nxt[t] = lds[base[t] + coff + tapoff[tap + 1]];
+                        for (int t = 0; t < T; ++t) b_nxt[t] = lds[rowb[t][(tap + 1) / 3] + (tap + 1) % 3];
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < T; ++t) b_nxt[t] = lds[base[t] + coff + tapoff[tap + 1]];
+                    }
                 } else if (cib + 1 < nCib) {
 #pragma unroll
                     for (int t = 0; t < T; ++t) b_nxt[t] = lds[base[t] + coff + 4 * in_plane + tapoff[0]];
@@ -626,14 +641,16 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
                 resident_head(ka, li, lds, gout_f, slot, w, lane);
             } else if (kind == RES_DW) {
                 resident_dw(ka, li, lds, gout, w, lane);
+            } else if (taps == 9 && ka->layer[li].rows3) {
+                if (T == 4) resident_conv<4, 9, true>(ka, li, lds, gout, w, lane, a_pre, slot);
+                else if (T == 2) resident_conv<2, 9, true>(ka, li, lds, gout, w, lane, a_pre, slot);
+                else resident_conv<1, 9, true>(ka, li, lds, gout, w, lane, a_pre, slot);
             } else if (taps == 9) {
-                if (T == 4) resident_conv<4, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
-                else if (T == 2) resident_conv<2, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
-                else resident_conv<1, 9>(ka, li, lds, gout, w, lane, a_pre, slot);
+                resident_conv<1, 9, false>(ka, li, lds, gout, w, lane, a_pre, slot);      // (1 x 9, 9 x 1: one tile at a time)
             } else {
-                if (T == 4) resident_conv<4, 1>(ka, li, lds, gout, w, lane, a_pre, slot);
-                else if (T == 2) resident_conv<2, 1>(ka, li, lds, gout, w, lane, a_pre, slot);
-                else resident_conv<1, 1>(ka, li, lds, gout, w, lane, a_pre, slot);
+                if (T == 4) resident_conv<4, 1, false>(ka, li, lds, gout, w, lane, a_pre, slot);
+                else if (T == 2) resident_conv<2, 1, false>(ka, li, lds, gout, w, lane, a_pre, slot);
+                else resident_conv<1, 1, false>(ka, li, lds, gout, w, lane, a_pre, slot);
             }
             // the padding of the result (nobody reads it before the barrier; a wave that is done early does this
             // while the others still compute)
@@ -871,6 +888,8 @@ bool plan_prefix(const ResGroup *g_in, int n_in, ResArgs &a, int &lds_bytes)
             }
         }
         if (d.kind == RES_STEM) d.T = 4;
+        d.rows3 = d.kind == RES_CONV && d.taps == 9 && c.kw == 3;
+        if (d.kind == RES_CONV && d.taps == 9 && !d.rows3) d.T = 1;     // the kernel has that case for single tiles only
         d.nTg = (tiles + d.T - 1) / d.T;
         d.nGroups = d.nCob * d.nTg;
         if (d.kind == RES_CONV || d.kind == RES_DW)
