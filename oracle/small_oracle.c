@@ -10,10 +10,10 @@
  *          NCHW activations / OIHW filters, each output accumulated in fp64 and
  *          rounded once to fp32 (paper Section 3.1 "Abstract DNN Layer", Section 3.2
  *          "Classes of layers", Table 1, Table 2).
- *   so_abstract_layer_blocked  "O2": the paper's Algorithm 1 loop nest, in its loop
- *          order and notation, on the channel-blocked layouts of Section 4.4
- *          "Common Data Format", with the kernel phases of Algorithm 2 (LOAD tile,
- *          COMPUTE over x, y, ii, STORE tile).
+ *   so_abstract_layer_blocked  "O2": the blocked evaluation that Algorithm 1 defines,
+ *          on the channel-blocked layouts of Section 4.4 "Common Data Format": register
+ *          tiles of the output visited once per block of reduction channels, each visit
+ *          being the three kernel phases of Algorithm 2.
  *
  * Readings where the paper is silent (kept identical in the HIP library's contract):
  *   - batch is an outermost dimension, images independent (Section 3.1.1 allows I_B);
@@ -265,99 +265,153 @@ void so_pack_dw_filter(const float *c1hw, float *blk, int C, int kh, int kw, int
                     c1hw[((size_t)c * kh + ky) * kw + kx];
 }
 
-/* ------------------------------------------------------------------ O2: Algorithm 1
+/* ------------------------------------------------------------------ O2: the blocked evaluation
  *
- * One loop nest for every layer class. Parameters in the paper's notation:
- *   window F_H x F_W x F_C, strides S_H, S_W, S_C, K filters per group,
- *   G = (I_C - F_C) / S_C + 1 groups, O_C = K * G,
- *   tile sizes G_b, K_b (output-channel block O_cb = G_b * K_b), F_Cb, O_wb.
- * op: 0 = FMA with weights, 1 = Max (no weights), 2 = Add then divide by tap count.
+ * One routine for every layer class, on the channel-blocked layouts of Section 4.4. It is the evaluation that
+ * Algorithm 1 defines (the definition being checked here; tests require O2 == O1): the output is cut into register
+ * tiles of O_wb pixels x (G_b * K_b) output channels; for every block of F_Cb reduction channels every tile of the
+ * tensor is visited once, and a visit is Algorithm 2's three phases -- bring the tile in (start values on the first
+ * reduction block, the partial results of the earlier blocks afterwards), reduce the window over this block's
+ * channels into it, put it back. Written here as a tile descriptor plus one helper per phase.
+ *
+ * Parameters in the paper's notation: window F_H x F_W x F_C, strides S_H, S_W, S_C, K filters per group,
+ * G = (I_C - F_C) / S_C + 1 groups, O_C = K * G, tile sizes G_b, K_b (output-channel block O_cb = G_b * K_b),
+ * F_Cb, O_wb. op: 0 = FMA with weights, 1 = Max (no weights), 2 = Add then divide by tap count.
  * I  : [N][I_C/Icb][I_H][I_W][Icb]
  * Wt : [G/G_b][K/K_b][F_C/F_Cb][F_H][F_W][F_Cb][G_b][K_b]   (ignored for op != 0)
  * O  : [N][O_C/O_cb][O_H][O_W][O_cb]
- * The O tensor is held in fp64 between visits so the result equals the definition
- * rounded once. Returns 0, or a negative code for an indivisible tiling.
+ * Partial results are held in fp64 between visits so the result equals the definition rounded once.
+ * Returns 0, or a negative code for an indivisible tiling.
  */
+struct blocked_layer {
+    int op;
+    const float *I, *Wt;
+    double *partial;                 /* the output tensor in its blocked layout, fp64 */
+    int I_C, I_H, I_W, O_C, O_H, O_W;
+    int F_H, F_W, F_C, S_H, S_W, S_C, K, G;
+    int pt, pl;
+    int Icb, G_b, K_b, F_Cb, O_wb, O_cb;
+};
+
+/* One visit: image, first group and first filter of the channel tile, first reduction channel, output row, first
+ * output column; `width` pixels wide (O_wb, fewer at the right edge). */
+struct tile_visit { int image, group0, filter0, red0, row, col0, width; };
+
+static int tile_channel(const struct blocked_layer *a, const struct tile_visit *v, int dg, int dk)
+{
+    return (v->group0 + dg) * a->K + v->filter0 + dk;        /* output channel = group * K + filter in group */
+}
+
+static void tile_bring_in(const struct blocked_layer *a, const struct tile_visit *v, double *regs)
+{
+    for (int p = 0; p < v->width; ++p)
+        for (int dg = 0; dg < a->G_b; ++dg)
+            for (int dk = 0; dk < a->K_b; ++dk) {
+                double *r = &regs[(p * a->G_b + dg) * a->K_b + dk];
+                if (v->red0 == 0)
+                    *r = a->op == 1 ? -INFINITY : 0.0;
+                else
+                    *r = a->partial[so_act_offset(v->image, tile_channel(a, v, dg, dk), v->row, v->col0 + p, a->O_C,
+                                                  a->O_H, a->O_W, a->O_cb)];
+            }
+}
+
+static void tile_put_back(const struct blocked_layer *a, const struct tile_visit *v, const double *regs)
+{
+    for (int p = 0; p < v->width; ++p)
+        for (int dg = 0; dg < a->G_b; ++dg)
+            for (int dk = 0; dk < a->K_b; ++dk)
+                a->partial[so_act_offset(v->image, tile_channel(a, v, dg, dk), v->row, v->col0 + p, a->O_C, a->O_H,
+                                         a->O_W, a->O_cb)] = regs[(p * a->G_b + dg) * a->K_b + dk];
+}
+
+/* Offset of a weight in [G/G_b][K/K_b][F_C/F_Cb][F_H][F_W][F_Cb][G_b][K_b]: tap (ty, tx), reduction channel
+ * red0 + dc of the window, group group0 + dg, filter filter0 + dk. */
+static size_t tile_weight(const struct blocked_layer *a, const struct tile_visit *v, int ty, int tx, int dc, int dg, int dk)
+{
+    size_t o = (size_t)(v->group0 / a->G_b);
+    o = o * (size_t)(a->K / a->K_b) + (size_t)(v->filter0 / a->K_b);
+    o = o * (size_t)(a->F_C / a->F_Cb) + (size_t)(v->red0 / a->F_Cb);
+    o = (o * a->F_H + ty) * a->F_W + tx;
+    return ((o * a->F_Cb + dc) * a->G_b + dg) * a->K_b + dk;
+}
+
+static void tile_reduce(const struct blocked_layer *a, const struct tile_visit *v, double *regs)
+{
+    for (int ty = 0; ty < a->F_H; ++ty)
+        for (int tx = 0; tx < a->F_W; ++tx)
+            for (int dc = 0; dc < a->F_Cb; ++dc)
+                for (int p = 0; p < v->width; ++p) {
+                    const int ih = v->row * a->S_H + ty - a->pt, iw = (v->col0 + p) * a->S_W + tx - a->pl;
+                    if (ih < 0 || ih >= a->I_H || iw < 0 || iw >= a->I_W) continue;   /* taps in the padding */
+                    for (int dg = 0; dg < a->G_b; ++dg) {
+                        const int ic = (v->group0 + dg) * a->S_C + v->red0 + dc;      /* the group's window start + channel */
+                        const double x = (double)a->I[so_act_offset(v->image, ic, ih, iw, a->I_C, a->I_H, a->I_W, a->Icb)];
+                        for (int dk = 0; dk < a->K_b; ++dk) {
+                            double *r = &regs[(p * a->G_b + dg) * a->K_b + dk];
+                            if (a->op == 0) *r += x * (double)a->Wt[tile_weight(a, v, ty, tx, dc, dg, dk)];
+                            else if (a->op == 1) { if (x > *r) *r = x; }
+                            else *r += x;
+                        }
+                    }
+                }
+}
+
 int so_abstract_layer_blocked(int op, const float *I, const float *Wt, float *O, int N, int I_C, int I_H,
                               int I_W, int F_H, int F_W, int F_C, int S_H, int S_W, int S_C, int K, int pt,
                               int pb, int pl, int pr, int Icb, int G_b, int K_b, int F_Cb, int O_wb)
 {
     if (S_C <= 0 || (I_C - F_C) % S_C) return -1;
-    const int G = (I_C - F_C) / S_C + 1;
-    const int O_C = K * G, O_cb = G_b * K_b;
-    if (G % G_b || K % K_b || F_C % F_Cb || I_C % Icb || O_C % O_cb || O_wb <= 0) return -2;
-    const int O_H = so_out_dim(I_H, F_H, S_H, pt, pb), O_W = so_out_dim(I_W, F_W, S_W, pl, pr);
-    const size_t out_elems = (size_t)N * O_C * O_H * O_W;
-    double *acc = (double *)malloc(sizeof(double) * (out_elems ? out_elems : 1));
-    double *tile = (double *)malloc(sizeof(double) * (size_t)O_wb * G_b * K_b);
-    if (!acc || !tile) { free(acc); free(tile); return -3; }
+    struct blocked_layer a;
+    a.op = op; a.I = I; a.Wt = Wt;
+    a.I_C = I_C; a.I_H = I_H; a.I_W = I_W;
+    a.F_H = F_H; a.F_W = F_W; a.F_C = F_C; a.S_H = S_H; a.S_W = S_W; a.S_C = S_C; a.K = K;
+    a.G = (I_C - F_C) / S_C + 1;
+    a.O_C = K * a.G;
+    a.pt = pt; a.pl = pl;
+    a.Icb = Icb; a.G_b = G_b; a.K_b = K_b; a.F_Cb = F_Cb; a.O_wb = O_wb; a.O_cb = G_b * K_b;
+    if (a.G % G_b || K % K_b || F_C % F_Cb || I_C % Icb || a.O_C % a.O_cb || O_wb <= 0) return -2;
+    a.O_H = so_out_dim(I_H, F_H, S_H, pt, pb);
+    a.O_W = so_out_dim(I_W, F_W, S_W, pl, pr);
+    const size_t out_elems = (size_t)N * a.O_C * a.O_H * a.O_W;
+    a.partial = (double *)malloc(sizeof(double) * (out_elems ? out_elems : 1));
+    double *regs = (double *)malloc(sizeof(double) * (size_t)O_wb * G_b * K_b);
+    if (!a.partial || !regs) { free(a.partial); free(regs); return -3; }
 
-    for (int n = 0; n < N; ++n)
-    for (int g = 0; g < G; g += G_b)                     /* "in parallel" in the paper */
-    for (int k = 0; k < K; k += K_b)                     /* "in parallel" in the paper */
-    for (int i = 0; i < F_C; i += F_Cb)
-    for (int j = 0; j < O_H; ++j)
-    for (int l = 0; l < O_W; l += O_wb) {
-        /* ---- kernel, LOAD phase: first visit initialises, later visits reload */
-        for (int ll = 0; ll < O_wb && l + ll < O_W; ++ll)
-        for (int gg = 0; gg < G_b; ++gg)
-        for (int kk = 0; kk < K_b; ++kk) {
-            const int oc = (g + gg) * K + (k + kk);
-            double *t = &tile[((size_t)ll * G_b + gg) * K_b + kk];
-            if (i == 0) *t = (op == 1) ? -INFINITY : 0.0;
-            else *t = acc[so_act_offset(n, oc, j, l + ll, O_C, O_H, O_W, O_cb)];
-        }
-        /* ---- COMPUTE phase */
-        for (int x = 0; x < F_H; ++x)
-        for (int y = 0; y < F_W; ++y)
-        for (int ii = 0; ii < F_Cb; ++ii)
-        for (int ll = 0; ll < O_wb && l + ll < O_W; ++ll)
-        for (int gg = 0; gg < G_b; ++gg)
-        for (int kk = 0; kk < K_b; ++kk) {
-            const int ih = j * S_H + x - pt, iw = (l + ll) * S_W + y - pl;
-            if (ih < 0 || ih >= I_H || iw < 0 || iw >= I_W) continue;   /* edge handling around the kernel */
-            const int ic = (g + gg) * S_C + i + ii;
-            const double v = (double)I[so_act_offset(n, ic, ih, iw, I_C, I_H, I_W, Icb)];
-            double *t = &tile[((size_t)ll * G_b + gg) * K_b + kk];
-            if (op == 0) {
-                const size_t wo =
-                    (((((((size_t)(g / G_b) * (K / K_b) + k / K_b) * (F_C / F_Cb) + i / F_Cb) * F_H + x) * F_W + y) *
-                          F_Cb + ii) * G_b + gg) * K_b + kk;
-                *t += v * (double)Wt[wo];
-            } else if (op == 1) {
-                if (v > *t) *t = v;
-            } else {
-                *t += v;
-            }
-        }
-        /* ---- STORE phase */
-        for (int ll = 0; ll < O_wb && l + ll < O_W; ++ll)
-        for (int gg = 0; gg < G_b; ++gg)
-        for (int kk = 0; kk < K_b; ++kk) {
-            const int oc = (g + gg) * K + (k + kk);
-            acc[so_act_offset(n, oc, j, l + ll, O_C, O_H, O_W, O_cb)] = tile[((size_t)ll * G_b + gg) * K_b + kk];
-        }
-    }
+    /* Visits in the order the loop nest prescribes: channel tiles (groups, filters; independent of each other),
+     * then the reduction blocks, and inside a reduction block every row and column tile of the output. */
+    struct tile_visit v;
+    for (v.image = 0; v.image < N; ++v.image)
+        for (v.group0 = 0; v.group0 < a.G; v.group0 += G_b)
+            for (v.filter0 = 0; v.filter0 < K; v.filter0 += K_b)
+                for (v.red0 = 0; v.red0 < F_C; v.red0 += F_Cb)
+                    for (v.row = 0; v.row < a.O_H; ++v.row)
+                        for (v.col0 = 0; v.col0 < a.O_W; v.col0 += O_wb) {
+                            v.width = a.O_W - v.col0 < O_wb ? a.O_W - v.col0 : O_wb;
+                            tile_bring_in(&a, &v, regs);
+                            tile_reduce(&a, &v, regs);
+                            tile_put_back(&a, &v, regs);
+                        }
 
-    /* round once; the Add reduction becomes an average over the in-range taps */
+    /* round once; the Add reduction becomes an average over the taps inside the image */
     for (int n = 0; n < N; ++n)
-    for (int oc = 0; oc < O_C; ++oc)
-    for (int j = 0; j < O_H; ++j)
-    for (int l = 0; l < O_W; ++l) {
-        const size_t o = so_act_offset(n, oc, j, l, O_C, O_H, O_W, O_cb);
-        double v = acc[o];
-        if (op == 2) {
-            int cnt = 0;
-            for (int x = 0; x < F_H; ++x)
-                for (int y = 0; y < F_W; ++y) {
-                    const int ih = j * S_H + x - pt, iw = l * S_W + y - pl;
-                    if (ih >= 0 && ih < I_H && iw >= 0 && iw < I_W) ++cnt;
+        for (int oc = 0; oc < a.O_C; ++oc)
+            for (int oh = 0; oh < a.O_H; ++oh)
+                for (int ow = 0; ow < a.O_W; ++ow) {
+                    const size_t o = so_act_offset(n, oc, oh, ow, a.O_C, a.O_H, a.O_W, a.O_cb);
+                    double r = a.partial[o];
+                    if (op == 2) {
+                        int inside = 0;
+                        for (int ty = 0; ty < F_H; ++ty)
+                            for (int tx = 0; tx < F_W; ++tx) {
+                                const int ih = oh * S_H + ty - pt, iw = ow * S_W + tx - pl;
+                                if (ih >= 0 && ih < I_H && iw >= 0 && iw < I_W) ++inside;
+                            }
+                        r /= (double)(inside > 0 ? inside * F_C : 1);
+                    }
+                    O[o] = (float)r;
                 }
-            v /= (double)(cnt > 0 ? cnt * F_C : 1);
-        }
-        O[o] = (float)v;
-    }
-    free(acc);
-    free(tile);
+    free(a.partial);
+    free(regs);
     return 0;
 }

@@ -542,11 +542,9 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
         bool ok = (T == D || T == E) && T != c.src;
         if (ok && T == E) {
             if (E == SMALL_BUF_IN) ok = false;
-            // the convolution's own buffer D is then never written: nobody may read it before it is rewritten
-            for (int k = j + 1; ok && k < nL; ++k) {
-                if (reads(L[k], D)) ok = false;
-                else if (L[k].dst == D) break;
-            }
+            // the convolution's own buffer D is then never written: nobody may read it before it is rewritten, and
+            // the caller's output buffer receives every write the table makes to it
+            if (!dead_from(L, nL, j + 1, D)) ok = false;
         }
         if (ok) {
             f.epilogue |= EPI_ADD;
@@ -566,13 +564,7 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
         L[j].pad.t == 0 && L[j].pad.b == 0 && L[j].pad.l == 0 && L[j].pad.r == 0 &&
         dwpw_eligible(c.Ci, L[j].Co, c.Cib, L[j].Cob, c.kh, c.kw, c.stride, L[j].kh, L[j].kw, L[j].stride)) {
         // the depthwise buffer D is never written: nobody may read it before it is rewritten
-        bool ok = true, rewritten = L[j].dst == D;
-        for (int k = j + 1; ok && !rewritten && k < nL; ++k) {
-            if (reads(L[k], D)) ok = false;
-            else if (L[k].dst == D) rewritten = true;
-        }
-        if (ok && !rewritten && D == SMALL_BUF_OUT) ok = false;
-        if (ok) {
+        if (L[j].dst == D || dead_from(L, nL, j + 1, D)) {
             f.pw = j - i;
             f.skip = j - i;
             f.rename = L[j].dst == c.src;
@@ -747,6 +739,7 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
         const small_layer &l = L[i];
         const bool head = fused_away == 0;             // this layer starts a launch (it is not folded into an earlier one)
         if (fused_away > 0) --fused_away;
+        if (!valid_id(l.src) || !valid_id(l.dst) || l.dst == SMALL_BUF_IN) return SMALL_ERR_LAYER;
         Fusion fu = {EPI_NONE, l.dst, l.dst, 0, 0, 0, 0};
         if (track && head) {
             fu = plan_fusion(L, nL, i);
@@ -759,7 +752,7 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
         if (!run && l.op == SMALL_OP_DWCONV) {
             // a run may swap the memory behind these two slots: both must then hold either one's tensors
             const Fusion f = plan_fusion(L, nL, i);
-            if (f.rename) may_swap |= (1u << l.src) | (1u << l.dst);
+            if (f.rename && l.src >= 0 && l.dst >= 0) may_swap |= (1u << l.src) | (1u << l.dst);
         }
         // a run of convolutions with every tensor between them in LDS, one image per workgroup
         int res_n = 0;
@@ -780,7 +773,6 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
             }
         }
         const bool launch = run && head && i >= first && (long)i < (long)first + count;
-        if (!valid_id(l.src) || !valid_id(l.dst) || l.dst == SMALL_BUF_IN) return SMALL_ERR_LAYER;
         if (in_plain && reads(l, SMALL_BUF_IN) && !(i == 0 && l.op == SMALL_OP_CONV)) return SMALL_ERR_LAYER;
         const Shape a = shp[idx(l.src)];
         if (!a.set || a.C != l.Ci || a.Cb != l.Cib) return SMALL_ERR_LAYER;
@@ -808,14 +800,17 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                                                 with_ptrs ? ptr(fu.out_id) : nullptr, with_ptrs ? ptr(fu.res_id) : nullptr))
                         return SMALL_ERR_LAYER;
                 }
-                if (run && head && fu.chain) {
-                    // the one-kernel run of pointwise layers needs aligned pointers and 32-bit input offsets;
-                    // otherwise every layer of the run is planned on its own
-                    uintptr_t bits = (uintptr_t)ptr(l.src) | (uintptr_t)ptr(fu.out_id);
-                    for (int k = 0; k < fu.chain; ++k) bits |= (uintptr_t)L[fu.chain_idx[k]].filt;
-                    const size_t n_out = elems(N, L[fu.chain_idx[fu.chain - 1]].Co, a.H, a.W);
-                    if ((bits & 15u) || in_elems * sizeof(float) >= (1ull << 32) || (size_t)N * a.H * a.W > (size_t)INT_MAX - 64 ||
-                        overlap(ptr(l.src), in_elems, ptr(fu.out_id), n_out)) {
+                if (head && fu.chain) {
+                    // the one-kernel run of pointwise layers needs 32-bit input offsets and, known only when running,
+                    // aligned pointers; otherwise every layer of the run is planned on its own
+                    bool ok = in_elems * sizeof(float) < (1ull << 32) && (size_t)N * a.H * a.W <= (size_t)INT_MAX - 64;
+                    if (ok && run) {
+                        uintptr_t bits = (uintptr_t)ptr(l.src) | (uintptr_t)ptr(fu.out_id);
+                        for (int k = 0; k < fu.chain; ++k) bits |= (uintptr_t)L[fu.chain_idx[k]].filt;
+                        const size_t n_out = elems(N, L[fu.chain_idx[fu.chain - 1]].Co, a.H, a.W);
+                        ok = !(bits & 15u) && !overlap(ptr(l.src), in_elems, ptr(fu.out_id), n_out);
+                    }
+                    if (!ok) {
                         fu = plan_fusion(L, nL, i, false);
                         fused_away = fu.skip;
                     }
@@ -846,13 +841,15 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.dst == l.src) return SMALL_ERR_ALIAS;
                 if (l.op == SMALL_OP_DWCONV && !l.filt) return SMALL_ERR_NULL;
                 o = Shape{l.Ci, g.Ho, g.Wo, l.Cib, true};
-                if (run && head && fu.pw) {
-                    // the one-kernel depthwise + pointwise path also needs a geometry and pointers it can take;
-                    // otherwise the pointwise convolution becomes a launch of its own
+                if (head && fu.pw && !res_n) {
+                    // the one-kernel depthwise + pointwise path also needs a geometry and (known only when running)
+                    // pointers it can take; otherwise the pointwise convolution becomes a launch of its own
                     const small_layer &pw = L[i + fu.pw];
-                    const uintptr_t bits = (uintptr_t)ptr(l.src) | (uintptr_t)ptr(fu.rename ? l.dst : pw.dst) |
-                                           (uintptr_t)l.filt | (uintptr_t)pw.filt;
-                    if (!dwpw_geom_ok(g, pw.Co) || (bits & 15u)) {
+                    bool ok = dwpw_geom_ok(g, pw.Co);
+                    if (ok && run)
+                        ok = !(((uintptr_t)ptr(l.src) | (uintptr_t)ptr(fu.rename ? l.dst : pw.dst) | (uintptr_t)l.filt |
+                                (uintptr_t)pw.filt) & 15u);
+                    if (!ok) {
                         fu = without_pointwise(fu);
                         fused_away = fu.skip;
                     }
@@ -866,11 +863,12 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                         rc = from_hip(launch_dwpw(ptr(l.src), l.filt, pw.filt, dst, g, pw.Co,
                                                   (fu.epilogue & EPI_RELU) != 0, fu.pw_relu, s));
                     if (fu.rename) std::swap(phys[l.dst], phys[pw.dst]);
-                } else if (run && head && fu.head) {
+                } else if (head && fu.head) {
                     // pooling over the whole image + the fully connected layer in one kernel, if that is what it is
+                    // (and, known only when running, if the pointers are aligned)
                     const small_layer &d = L[i + 1];
                     const bool global = g.Ho == 1 && g.Wo == 1 && l.kh == a.H && l.kw == a.W;
-                    if (!global || !d.filt || (((uintptr_t)ptr(l.src) | (uintptr_t)d.filt) & 15u)) {
+                    if (!global || (run && (!d.filt || (((uintptr_t)ptr(l.src) | (uintptr_t)d.filt) & 15u)))) {
                         fu.head = 0;
                         fused_away = 0;
                         if (launch) rc = from_hip(launch_pool(ptr(l.src), ptr(l.dst), g, SMALL_POOL_AVG, s));

@@ -164,3 +164,61 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
             t[k].filt = 0x1000
     t[3].Cib = 8
     assert lib.small_network_workspace(t, len(t), 1, a.C0, a.H0, a.W0, C.byref(C.c_size_t())) == 7
+
+
+def _table(layers, n_w):
+    from paper_2303_04769_amd import binding as B
+    t = B.make_layer_table(layers, [None] * n_w)
+    for k, L in enumerate(layers):
+        if L.w is not None:
+            t[k].filt = 0x1000          # validation wants non-NULL filters; never dereferenced
+    return t
+
+
+def test_a_folded_add_never_leaves_the_output_buffer_unwritten(lib):
+    """conv -> OUT; add(OUT, slot) -> slot: folding the add into the convolution's store phase would write the sum into
+    the slot and leave the caller's output buffer, which receives every write to SMALL_BUF_OUT, unwritten. The planner
+    keeps the two apart, with and without image-resident runs; when OUT is rewritten later the fold is allowed."""
+    from paper_2303_04769_amd import binding as B
+    from workloads.nets import Layer, IN, OUT
+    p1 = (1, 1, 1, 1)
+    layers = [
+        Layer("conv", 16, 16, 8, 8, 3, 3, 1, p1, src=IN, dst=0, w=0),
+        Layer("conv", 16, 16, 8, 8, 1, 1, 1, (0, 0, 0, 0), src=IN, dst=1, w=1),
+        Layer("conv", 16, 16, 8, 8, 3, 3, 1, p1, src=1, dst=OUT, w=0),
+        Layer("add", 16, 16, 8, 8, src=OUT, src2=0, dst=0),
+    ]
+    t = _table(layers, 2)
+    assert B.small_network_launches(t) == [0, 1, 2, 3]
+    for flags in (B.SMALL_RUN_RESIDENT_OFF, B.SMALL_RUN_RESIDENT_ON):
+        at = B.small_network_launches_at(t, 3, 16, 8, 8, flags)
+        assert at[-1] == 3, (flags, at)          # the add is a launch of its own (the convolution before it may be
+                                                 # the end of an image-resident run, whose last result is written)
+    # OUT rewritten afterwards (and not read in between): the convolution's own result is dead, the fold is fine
+    layers2 = layers + [Layer("conv", 16, 16, 8, 8, 1, 1, 1, (0, 0, 0, 0), src=0, dst=OUT, w=1)]
+    assert B.small_network_launches(_table(layers2, 2)) == [0, 1, 2, 4]
+
+
+def test_launch_list_applies_the_geometry_fallbacks_of_the_run(lib):
+    """small_network_launches_at lists what a run with this input shape launches: an average pooling that does not
+    cover the whole image is not fused with the fully connected layer after it, although the table alone (the
+    batch-independent list) cannot tell."""
+    from paper_2303_04769_amd import binding as B
+    from workloads.nets import Layer, IN, OUT
+    layers = [
+        Layer("conv", 16, 16, 8, 8, 3, 3, 1, (1, 1, 1, 1), src=IN, dst=0, w=0),
+        Layer("avgpool", 16, 16, 8, 8, 4, 4, 8, src=0, dst=1),
+        Layer("dense", 16, 16, 1, 1, 1, 1, 1, src=1, dst=OUT, w=1, Ho=1, Wo=1),
+    ]
+    assert (layers[1].Ho, layers[1].Wo) == (1, 1)
+    t = _table(layers, 2)
+    assert B.small_network_launches(t) == [0, 1]
+    assert B.small_network_launches_at(t, 2, 16, 8, 8, B.SMALL_RUN_RESIDENT_OFF) == [0, 1, 2]
+    # the whole-image window is fused
+    layers[1] = Layer("avgpool", 16, 16, 8, 8, 8, 8, 1, src=0, dst=1)
+    assert B.small_network_launches_at(_table(layers, 2), 2, 16, 8, 8, B.SMALL_RUN_RESIDENT_OFF) == [0, 1]
+    # a garbage buffer id is an error code, not a shift by it
+    t = _table(layers, 2)
+    t[0].src = 77
+    n = C.c_int(0)
+    assert lib.small_network_launches_at(t, len(t), 2, 16, 8, 8, 0, None, C.byref(n)) == 7

@@ -176,12 +176,7 @@ def test_conv2d_first_layer_matrix_core(case):
     x = (rng.random((N, Ci, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
     w = (rng.random((Co, Ci, kh, kw), dtype=np.float32) * 2 - 1).astype(np.float32)
     got = run_conv(x, w, s, pad)
-    ref = O.conv2d(x, w, s, pad) if N <= 20 else None
-    if ref is None:      # many images: the oracle recomputes a sample (images are independent)
-        for n in (0, N // 2, N - 1):
-            assert_close(got[n:n + 1], O.conv2d(x[n:n + 1], w, s, pad), Ci * kh * kw, f"first layer {case} image {n}")
-    else:
-        assert_close(got, ref, Ci * kh * kw, f"first layer {case}")
+    assert_close(got, O.conv2d(x, w, s, pad), Ci * kh * kw, f"first layer {case}, all {N} images")
 
 
 def test_conv_identity_filter_is_exact():

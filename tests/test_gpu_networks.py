@@ -1,5 +1,5 @@
-"""GPU parity for small_network_run on the four stand-in networks, and full-size sampled
-checks of the roofline sweep layers in the launch configuration the benchmark times."""
+"""GPU parity for small_network_run on the four stand-in networks, and full-size checks of the
+roofline sweep layers in the launch configuration the benchmark times."""
 import numpy as np
 import pytest
 import torch
@@ -27,7 +27,14 @@ def _run(net, x, ws, flags=None):
 
 
 def _maxK(net):
-    return max(L.Ci * L.kh * L.kw for L in net.layers if L.op in ("conv", "dense"))
+    """The stated rule for network results: K of the longest reduction among the layers."""
+    return max([L.Ci * L.kh * L.kw for L in net.layers if L.op in ("conv", "dense")] + [9])
+
+
+# max |gpu - oracle| of the logits that the kernels of this tree show on the seeded inputs (fp32 sums against the
+# oracle's fp64 ones); the full-batch tests allow 20 times as much, far below the stated tolerance (>= 1e-4)
+# (measured: 1.2e-6 .. 1.4e-6 at max|ref| 4.4 .. 5.4; 1.0e-7 .. 1.2e-7 at 0.16 .. 0.25; 5e-7 .. 7e-7 at 3.1 .. 3.9; 3.8e-6 .. 5.7e-6 at 6.3 .. 7.0)
+OBSERVED_ERR = {"residual_cnn": 1.5e-6, "dsep_cnn": 1.5e-7, "audio_cnn": 8.0e-7, "dense_autoencoder": 6.0e-6}
 
 
 def test_single_conv_relu_workload():
@@ -57,40 +64,45 @@ def test_dsep_variant_block1_stride1():
 
 @pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 256), ("dsep_cnn", 3, 256), ("audio_cnn", 4, 1024),
                                         ("dense_autoencoder", 5, 256), ("dense_autoencoder", 5, 40000)])
-def test_networks_full_batch_sampled(name, idx, N):
-    """Full batch on the GPU; the oracle recomputes a sample of images one by one (images are independent)."""
+def test_networks_full_batch(name, idx, N):
+    """Full batch on the GPU in the launch configuration the benchmark times; every image against the oracle, at the
+    stated tolerance and within 20 times the error these kernels show today (a change of summation order or a
+    lost term in one image, round or tile would show)."""
     net = getattr(WL, name)()
     x, ws = WL.network_tensors(net, N, WL.BASE_SEED + idx)
     got = _run(net, x, ws).reshape(N, -1)
-    assert np.isfinite(got).all()
-    for n in (0, N // 3, N - 1):
-        ref = O.run_network(net, x[n:n + 1], ws)
-        assert_close(got[n:n + 1], ref, _maxK(net), f"{name} image {n} of {N}")
+    ref = O.run_network(net, x, ws)
+    err = assert_close(got, ref, _maxK(net), f"{name} N={N}")
+    assert err <= 20 * OBSERVED_ERR[name], f"{name} N={N}: max |gpu-ref| = {err:.3e}, 20x the usual {OBSERVED_ERR[name]:.1e}"
 
 
-def test_intermediate_layers_of_residual_cnn():
-    """Layer-by-layer: every intermediate compared with its own layer's K (src/dst bookkeeping included)."""
-    net = WL.residual_cnn()
-    x, ws = WL.network_tensors(net, 2, WL.BASE_SEED + 2)
+@pytest.mark.parametrize("name,idx", [("residual_cnn", 2), ("dsep_cnn", 3), ("audio_cnn", 4), ("dense_autoencoder", 5)])
+def test_intermediate_layers(name, idx):
+    """Layer by layer: the table cut after every layer (its result redirected to the output buffer), each intermediate
+    compared with its own layer's K (src / dst bookkeeping and every fusion boundary included: a cut table fuses what
+    a table ending there would)."""
+    net = getattr(WL, name)()
+    N = 2
+    x, ws = WL.network_tensors(net, N, WL.BASE_SEED + idx)
     _, trace = O.run_network(net, x, ws, return_all=True)
     pn = S.PackedNetwork(net, ws, DEV)
     xb = pn.pack_input(dev(x))
-    for upto in (1, 2, 4, 5, 7, 9, 12, 16):
+    for upto in range(1, len(net.layers) + 1):
         sub = net.layers[:upto]
         last = sub[-1]
         saved = last.dst
         last.dst = WL.nets.OUT
         try:
             table = S.make_layer_table(sub, pn.filters)
-            nbytes = S.small_network_workspace(table, 2, net.C0, net.H0, net.W0)
+            nbytes = S.small_network_workspace(table, N, net.C0, net.H0, net.W0)
             ws_t = torch.empty(max(nbytes, 256) // 4, dtype=torch.float32, device=DEV)
-            g = Guarded(2 * last.Co * last.Ho * last.Wo)
-            S.small_network_run(table, xb, g.t, ws_t, nbytes, 2, net.C0, net.H0, net.W0)
-            got = O.unpack(g.check(), (2, last.Co, last.Ho, last.Wo), last.Cob)
+            g = Guarded(N * last.Co * last.Ho * last.Wo)
+            S.small_network_run(table, xb, g.t, ws_t, nbytes, N, net.C0, net.H0, net.W0)
+            got = O.unpack(g.check(), (N, last.Co, last.Ho, last.Wo), last.Cob)
         finally:
             last.dst = saved
-        K = last.Ci * last.kh * last.kw if last.op == "conv" else 1
-        assert_close(got, trace[upto - 1], max(K, 1), f"residual_cnn after layer {upto} ({last.op})")
+        K = last.Ci * last.kh * last.kw if last.op in ("conv", "dense") else (last.kh * last.kw if last.op in ("dw", "avgpool") else 1)
+        assert_close(got, trace[upto - 1].reshape(got.shape), K, f"{name} after layer {upto} ({last.op})")
 
 
 @pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 1), ("dsep_cnn", 3, 2), ("audio_cnn", 4, 5),
@@ -167,17 +179,14 @@ def test_depthwise_pointwise_block(case):
     assert heads == ["relu", "dw", "maxpool"], heads          # the block is one launch
     x, ws = WL.network_tensors(net, N, 4242)
     got = _run(net, x, ws)
-    sample = range(N) if N <= 64 else (0, 1, N // 2, N - 2, N - 1)      # many images: the oracle recomputes a few
-    for n in ([slice(0, N)] if N <= 64 else [slice(k, k + 1) for k in sample]):
-        mid = O.dwconv2d(O.relu(x[n]), ws[0], stride, pad)
-        if relu_mid:
-            mid = O.relu(mid)
-        ref = O.conv2d(mid, ws[1], 1, (0, 0, 0, 0))
-        if relu_out:
-            ref = O.relu(ref)
-        # two chained reductions: the error of the depthwise sum (K = 9) is amplified by the pointwise one (K = C)
-        assert_close(got[n], ref, 9 * C, f"dw+pw block {case} images {n}")
-    assert np.isfinite(got).all()
+    mid = O.dwconv2d(O.relu(x), ws[0], stride, pad)
+    if relu_mid:
+        mid = O.relu(mid)
+    ref = O.conv2d(mid, ws[1], 1, (0, 0, 0, 0))
+    if relu_out:
+        ref = O.relu(ref)
+    # the rule for a table's result: K of its longest reduction (the pointwise layer's C; the depthwise one has 9)
+    assert_close(got, ref, max(C, 9), f"dw+pw block {case}, all {N} images")
 
 
 def test_depthwise_output_read_later_is_not_fused():
@@ -192,7 +201,7 @@ def test_depthwise_output_read_later_is_not_fused():
     x, ws = WL.network_tensors(net, 3, 77)
     mid = O.relu(O.dwconv2d(O.relu(x), ws[0], 1, pad))
     ref = O.add(O.conv2d(mid, ws[1], 1, (0, 0, 0, 0)), mid)
-    assert_close(_run(net, x, ws), ref, 9 * 32, "dw kept, conv + add")
+    assert_close(_run(net, x, ws), ref, 32, "dw kept, conv + add")
 
 
 # ------------------------------------------------------------------ runs of pointwise layers in one kernel
@@ -254,12 +263,7 @@ def test_pointwise_run(case):
     x, ws = WL.network_tensors(net, N, 777)
     got = _run(net, x, ws)
     ref = _chain_ref(x, ws, relus)
-    K = 1
-    for c in widths[:-1]:
-        K *= c
-    # chained reductions amplify each other's rounding error; He-scaled weights keep magnitudes level,
-    # so the error grows like the number of layers, not like the product of the widths
-    assert_close(got, ref, max(widths) * n_pw, f"pointwise run {widths} {H}x{W} N={N}")
+    assert_close(got, ref, max(widths[:-1]), f"pointwise run {widths} {H}x{W} N={N}")
 
 
 def test_pointwise_run_keeps_tensors_that_are_read_later():
@@ -277,7 +281,7 @@ def test_pointwise_run_keeps_tensors_that_are_read_later():
     c = lambda h, w: O.conv2d(h, w, 1, (0, 0, 0, 0))
     t0 = c(x, ws[0])
     ref = c(O.add(c(c(t0, ws[1]), ws[2]), t0), ws[3])
-    assert_close(_run(net, x, ws), ref, 32 * 4, "run with a tensor kept for a later add")
+    assert_close(_run(net, x, ws), ref, 32, "run with a tensor kept for a later add")
     # 0 -> 1 -> 2 -> 0: the third layer would overwrite the run's own input while other workgroups still read
     # it, so the run ends before it
     net.layers = [Layer("relu", 32, 32, 1, 1, src=IN, dst=0), D(0, 0, 1), D(1, 1, 2), D(2, 2, 0),
@@ -287,7 +291,7 @@ def test_pointwise_run_keeps_tensors_that_are_read_later():
     assert S.small_network_launches(table) == [0, 1, 3, 4]
     x, ws = WL.network_tensors(net, 33, 6)
     ref = c(c(c(O.relu(x), ws[0]), ws[1]), ws[2])
-    assert_close(_run(net, x, ws), ref, 32 * 3, "run that may not end in its own input")
+    assert_close(_run(net, x, ws), ref, 32, "run that may not end in its own input")
 
 
 # ------------------------------------------------------------------ network head in one kernel
@@ -436,18 +440,17 @@ def test_random_layer_tables(seed):
     x, ws = WL.network_tensors(net, N, 13000 + seed)
     ref = O.run_network(net, x, ws)
     got = _run(net, x, ws).reshape(ref.shape)
-    # errors of chained layers compound: the bound is that of the largest reduction, times the depth
-    depth = sum(L.op in ("conv", "dw", "dense") for L in net.layers)
-    K = max([L.Ci * L.kh * L.kw for L in net.layers if L.op in ("conv", "dense")] + [9])
     ops = "/".join(L.op for L in net.layers)
-    assert_close(got, ref, K * max(depth, 1) ** 2, f"random table {seed}: {ops}")
+    assert_close(got, ref, _maxK(net), f"random table {seed}: {ops}")
 
 
-# ------------------------------------------------------------------ full-size sweep layers (sampled)
+# ------------------------------------------------------------------ full-size sweep layers
 
 @pytest.mark.parametrize("C,H", WL.sweep_shapes()["conv"])
 @pytest.mark.parametrize("kind", ["conv3x3", "conv1x1", "dw3x3"])
-def test_sweep_layers_full_size_sampled(kind, C, H):
+def test_sweep_layers_full_size(kind, C, H):
+    """The sweep layers at their full size (N = 64), as the benchmark launches them; all 64 images against the oracle
+    (pixel tiles straddle rows and images at 7 x 7 and 14 x 14)."""
     N = WL.SWEEP_N
     rng = np.random.default_rng(WL.BASE_SEED + 5)
     x = WL.uniform_pm1(rng, (N, C, H, H))
@@ -467,8 +470,7 @@ def test_sweep_layers_full_size_sampled(kind, C, H):
         K = C * k * k
         ref_fn = lambda xs: O.conv2d(xs, w, 1, p)
     got = O.unpack(g.check(), x.shape, 16)
-    for n in (0, 37, N - 1):
-        assert_close(got[n:n + 1], ref_fn(x[n:n + 1]), K, f"{kind} C={C} H={H} image {n}")
+    assert_close(got, ref_fn(x), K, f"{kind} C={C} H={H}, all {N} images")
 
 
 def test_sweep_pool_relu_full_size():
@@ -484,8 +486,7 @@ def test_sweep_pool_relu_full_size():
     g = Guarded(N * C * 27 * 27)
     S.small_pool2d(xb, g.t, N, C, H, H, 3, 3, 2, (0, 0, 0, 0), 16, S.POOL_MAX)
     got = O.unpack(g.check(), (N, C, 27, 27), 16)
-    for n in (0, 21, N - 1):
-        assert_bits(got[n:n + 1], O.pool2d(x[n:n + 1], (3, 3), 2), f"maxpool image {n}")
+    assert_bits(got, O.pool2d(x, (3, 3), 2), "maxpool full size")
 
 
 def test_fusion_keeps_table_semantics():
@@ -516,6 +517,31 @@ def test_fusion_keeps_table_semantics():
     assert_close(got, ref, 144, "fusion probe (folded)")
 
 
+@pytest.mark.parametrize("flags", ["off", "on"])
+def test_output_buffer_receives_every_write(flags):
+    """conv -> OUT; add(OUT, slot 0) -> slot 0: the caller's output buffer holds the convolution's result afterwards
+    (folding the add into the convolution's store phase would have left it unwritten), layer by layer and with
+    image-resident runs."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("out_write_probe", 16, 8, 8)
+    net.wshapes = [((16, 16, 3, 3), 144), ((16, 16, 1, 1), 16)]
+    p1 = (1, 1, 1, 1)
+    net.layers = [
+        Layer("conv", 16, 16, 8, 8, 3, 3, 1, p1, src=IN, dst=0, w=0),
+        Layer("conv", 16, 16, 8, 8, 1, 1, 1, (0, 0, 0, 0), src=IN, dst=1, w=1),
+        Layer("conv", 16, 16, 8, 8, 3, 3, 1, p1, src=1, dst=OUT, w=0),
+        Layer("add", 16, 16, 8, 8, src=OUT, src2=0, dst=0),
+    ]
+    x, ws = WL.network_tensors(net, 3, 515)
+    N = 3
+    pn = S.PackedNetwork(net, ws, DEV)
+    g = Guarded(N * 16 * 8 * 8)
+    pn.run_opt(pn.pack_input(dev(x)), g.t, N, S.SMALL_RUN_RESIDENT_ON if flags == "on" else S.SMALL_RUN_RESIDENT_OFF)
+    got = O.unpack(g.check(), (N, 16, 8, 8), 16)
+    ref = O.conv2d(O.conv2d(x, ws[1], 1, (0, 0, 0, 0)), ws[0], 1, p1)
+    assert_close(got, ref, 144, f"conv into OUT followed by an add into a slot (resident {flags})")
+
+
 def _run_both(net, x, ws):
     """Blocked outputs of small_pack + small_network_run and of small_network_run_plain on the same input."""
     N = x.shape[0]
@@ -534,15 +560,14 @@ def _run_both(net, x, ws):
                                         ("dsep_cnn", 3, 19), ("audio_cnn", 4, 132), ("audio_cnn", 4, 301)])
 def test_run_from_plain_input(name, idx, N):
     """The first layer reads the plain tensor itself: same bits as packing first (the same products are added in
-    the same order), and the sampled images agree with the oracle."""
+    the same order), and every image agrees with the oracle."""
     net = getattr(WL, name)()
     x, ws = WL.network_tensors(net, N, WL.BASE_SEED + idx + 20)
     out0, out1 = _run_both(net, x, ws)
     assert_bits(out1, out0, f"{name} N={N}: plain input vs packed input")
     L = net.layers[-1]
     got = O.unpack(out1, (N, L.Co, L.Ho, L.Wo), L.Cob).reshape(N, -1)
-    for n in (0, N // 2, N - 1):
-        assert_close(got[n:n + 1], O.run_network(net, x[n:n + 1], ws), _maxK(net), f"{name} image {n} of {N}")
+    assert_close(got, O.run_network(net, x, ws), _maxK(net), f"{name}, all {N} images")
 
 
 def test_run_from_plain_input_refuses_what_it_cannot_take():
@@ -589,9 +614,9 @@ def test_run_from_plain_input_with_first_layer_into_add():
     x, ws = WL.network_tensors(net, N, 123)
     out0, out1 = _run_both(net, x, ws)
     assert_bits(out1, out0, "plain vs packed")
-    a = O.relu(O.conv2d(x[:3], ws[0], 2, (0, 1, 0, 1)))
+    a = O.relu(O.conv2d(x, ws[0], 2, (0, 1, 0, 1)))
     ref = O.add(O.conv2d(a, ws[1], 1, (0, 0, 0, 0)), a)
-    assert_close(O.unpack(out1, (N, 16, 20, 12), 16)[:3], ref, 27, "plain first layer, kept")
+    assert_close(O.unpack(out1, (N, 16, 20, 12), 16), ref, 27, "plain first layer, kept")
 
 
 # ------------------------------------------------------------------ image-resident runs (one image per workgroup)
@@ -600,17 +625,17 @@ def test_run_from_plain_input_with_first_layer_into_add():
 def test_resident_run_residual_cnn(N):
     """The whole residual CNN (3-channel first layer, eight convolutions with ReLU / residual add, strides 1 and 2,
     1x1 projections, average pooling + fully connected layer) as one launch with all tensors in LDS: against the
-    oracle on sampled images, and against the layer-by-layer run."""
+    oracle on every image, and against the layer-by-layer run."""
     net = WL.residual_cnn()
     x, ws = WL.network_tensors(net, N, WL.BASE_SEED + 40 + N)
     pn = S.PackedNetwork(net, ws, DEV)
     assert pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON) == [0]       # first layer, eight convolutions and the head
     got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(N, -1)
     base = _run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF).reshape(N, -1)
-    K = _maxK(net) * 9
+    K = _maxK(net)
     assert_close(got, base, K, f"resident vs layer by layer, N={N}")
-    for n in sorted({0, N // 2, N - 1}):
-        assert_close(got[n:n + 1], O.run_network(net, x[n:n + 1], ws), K, f"resident image {n} of {N}")
+    err = assert_close(got, O.run_network(net, x, ws), K, f"resident run, all {N} images")
+    assert err <= 20 * OBSERVED_ERR["residual_cnn"], f"resident run N={N}: max |gpu-ref| = {err:.3e}"
 
 
 def test_resident_run_is_the_default_at_full_batches():
@@ -688,10 +713,8 @@ def test_resident_runs_on_random_conv_tables(seed):
     x, ws = WL.network_tensors(net, N, 32000 + seed)
     ref = O.run_network(net, x, ws)
     got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(ref.shape)
-    depth = sum(L.op == "conv" for L in net.layers)
-    K = max(L.Ci * L.kh * L.kw for L in net.layers if L.op == "conv")
     ops = "/".join(f"{L.op}{L.kh}s{L.stride}" if L.op == "conv" else L.op for L in net.layers)
-    assert_close(got, ref, K * depth ** 2, f"conv table {seed}: {ops}")
+    assert_close(got, ref, _maxK(net), f"conv table {seed}: {ops}")
 
 
 @pytest.mark.parametrize("seed", range(40))
@@ -703,9 +726,7 @@ def test_random_layer_tables_with_resident_runs(seed):
     x, ws = WL.network_tensors(net, N, 13000 + seed)
     ref = O.run_network(net, x, ws)
     got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(ref.shape)
-    depth = sum(L.op in ("conv", "dw", "dense") for L in net.layers)
-    K = max([L.Ci * L.kh * L.kw for L in net.layers if L.op in ("conv", "dense")] + [9])
-    assert_close(got, ref, K * max(depth, 1) ** 2, f"random table {seed} (resident)")
+    assert_close(got, ref, _maxK(net), f"random table {seed} (resident)")
 
 
 @pytest.mark.parametrize("C,Co,H,W,s", [(48, 32, 11, 9, 2), (16, 16, 8, 8, 1), (64, 48, 13, 16, 2), (32, 64, 6, 5, 1)])
@@ -735,8 +756,8 @@ def test_resident_run_folds_the_projection_shortcut(C, Co, H, W, s):
     assert pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON) == [0]
     got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON)
     ref = O.run_network(net, x, ws).reshape(got.shape)
-    assert_close(got, ref, max(C, Co) * 9 * 9, "projection block, resident")
-    assert_close(_run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF), ref, max(C, Co) * 9 * 9, "projection block, layer by layer")
+    assert_close(got, ref, _maxK(net), "projection block, resident")
+    assert_close(_run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF), ref, _maxK(net), "projection block, layer by layer")
 
 
 @pytest.mark.parametrize("name,idx,N,launches", [("audio_cnn", 4, 1, 1), ("audio_cnn", 4, 5, 1), ("dsep_cnn", 3, 2, 6),
@@ -750,9 +771,9 @@ def test_resident_runs_with_depthwise_layers(name, idx, N, launches):
     pn = S.PackedNetwork(net, ws, DEV)
     assert len(pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON)) == launches
     got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(N, -1)
-    K = _maxK(net) * 9
-    for n in sorted({0, N // 2, N - 1}):
-        assert_close(got[n:n + 1], O.run_network(net, x[n:n + 1], ws), K, f"{name} resident, image {n} of {N}")
+    K = _maxK(net)
+    err = assert_close(got, O.run_network(net, x, ws), K, f"{name} resident, all {N} images")
+    assert err <= 20 * OBSERVED_ERR[name], f"{name} resident N={N}: max |gpu-ref| = {err:.3e}"
     if N <= 8:
         assert_close(got, _run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF).reshape(N, -1), K, f"{name}: resident vs layer by layer")
 
@@ -780,7 +801,7 @@ def test_resident_run_falls_back_when_tensors_do_not_fit():
     assert off == [0, 2, 3, 5, 6] and on[:2] == [0, 2] and len(on) < len(off), (on, off)
     ref = O.run_network(net, x, ws)
     got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(ref.shape)
-    assert_close(got, ref, 288 * 16, "large then small, resident where it fits")
+    assert_close(got, ref, 288, "large then small, resident where it fits")
 
 
 @pytest.mark.parametrize("case", [
@@ -807,12 +828,12 @@ def test_resident_run_with_unusual_windows(case):
     assert pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON) == [0], pn.launches_at(N, S.SMALL_RUN_RESIDENT_ON)
     ref = O.run_network(net, x, ws)
     got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_ON).reshape(ref.shape)
-    assert_close(got, ref, 288 * 9, f"unusual windows {case}")
+    assert_close(got, ref, _maxK(net), f"unusual windows {case}")
     # the same from the plain input
     g = Guarded(pn.out_elems(N))
     pn.run_opt(dev(x), g.t, N, S.SMALL_RUN_RESIDENT_ON | S.SMALL_RUN_PLAIN_INPUT)
     L = net.layers[-1]
-    assert_close(O.unpack(g.check(), (N, L.Co, L.Ho, L.Wo), L.Cob).reshape(ref.shape), ref, 288 * 9, "from the plain input")
+    assert_close(O.unpack(g.check(), (N, L.Co, L.Ho, L.Wo), L.Cob).reshape(ref.shape), ref, _maxK(net), "from the plain input")
 
 
 @pytest.mark.parametrize("name,idx,N", [("residual_cnn", 2, 256), ("residual_cnn", 2, 5), ("audio_cnn", 4, 7), ("dsep_cnn", 3, 2)])
@@ -830,7 +851,7 @@ def test_plain_output_is_the_unpacked_result(name, idx, N):
     S.small_unpack(g0.t, plain, N, L.Co, L.Ho, L.Wo, L.Cob)
     pn.run_opt(xb, g1.t, N, S.SMALL_RUN_PLAIN_OUTPUT)
     assert_bits(g1.check(), plain.cpu().numpy(), f"{name}: plain output")
-    assert_close(g1.check().reshape(N, -1), O.run_network(net, x, ws), _maxK(net) * 9, f"{name}: plain output vs oracle")
+    assert_close(g1.check().reshape(N, -1), O.run_network(net, x, ws), _maxK(net), f"{name}: plain output vs oracle")
     fm = WL.single_conv_relu()
     xf, wf = WL.network_tensors(fm, 2, 3)
     pf = S.PackedNetwork(fm, wf, DEV)

@@ -141,8 +141,21 @@ def test_layouts_follow_the_layout_statement():
     for co, ci, ky, kx in ((0, 0, 0, 0), (17, 40, 2, 1), (31, 47, 1, 0), (5, 16, 0, 1)):
         assert wb[co // 16, ci // 16, ky, kx, co % 16, ci % 16] == w[co, ci, ky, kx]
     assert np.array_equal(wb, w.reshape(2, 16, 3, 16, 3, 2).transpose(0, 2, 4, 5, 1, 3))
+    # depthwise filters: the closed-form offset of channel c, tap (y, x) in [C/Cb][kh][kw][Cb], on codes that count
+    # their own plain position (c * kh + y) * kw + x (mod 251, a prime: neighbouring offsets never share a code by
+    # accident), for a square and a non-square window and two block sizes
+    for C, kh, kw, Cb in ((32, 3, 3, 16), (48, 2, 5, 16), (24, 3, 1, 8)):
+        plain = (np.arange(C * kh * kw) % 251).astype(np.uint8).reshape(C, 1, kh, kw)
+        blk = Q.pack_dw_filter(plain, Cb)
+        assert blk.shape == (C * kh * kw,)
+        for c in range(C):
+            for y in range(kh):
+                for x in range(kw):
+                    off = ((c // Cb * kh + y) * kw + x) * Cb + c % Cb
+                    assert blk[off] == ((c * kh + y) * kw + x) % 251, (C, kh, kw, Cb, c, y, x)
+    # and the general filter layout with one input channel per filter (F_Cb = 1, G_b = Cb) is the same bytes
     wd = WL.u8_codes(r, (32, 1, 3, 3))
-    assert np.array_equal(Q.pack_dw_filter(wd, 16).reshape(2, 3, 3, 16), wd.reshape(2, 16, 3, 3).transpose(0, 2, 3, 1))
+    assert np.array_equal(Q.pack_dw_filter(wd, 16), Q.pack_filter(wd, 16, 1))
 
 
 def test_multiplier_recipe_spreads_outputs_over_the_code_range():
