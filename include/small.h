@@ -44,7 +44,8 @@ enum {
     SMALL_ERR_LAUNCH = 5, /* the HIP runtime refused the launch */
     SMALL_ERR_WORKSPACE = 6, /* workspace too small or misaligned (small_network_run) */
     SMALL_ERR_LAYER = 7,  /* malformed layer table (bad op, bad buffer id, block mismatch between layers) */
-    SMALL_ERR_QUANT = 8   /* quantization parameters out of range, or a reduction too long for int32 sums */
+    SMALL_ERR_QUANT = 8,  /* quantization parameters out of range, or a reduction too long for int32 sums */
+    SMALL_ERR_STATIC = 9  /* small_network_run_static: the run needs more than SMALL_STATIC_WORKSPACE_BYTES */
 };
 
 typedef struct { int t, b, l, r; } small_pad; /* zero padding: top, bottom, left, right */
@@ -288,6 +289,21 @@ int small_network_launches(const small_layer *layers, int n_layers, int *first_l
 int small_network_run_range(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,
                             void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, int first,
                             int count, void *stream);
+
+/* small_network_run_static: small_network_run_opt for callers that cannot allocate device memory or hand over a
+ * workspace of their own -- code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. The
+ * layer workspace is an array of SMALL_STATIC_WORKSPACE_BYTES (64 MiB) inside the library's device image, one copy per
+ * GPU, held until the process ends; the caller passes only the input and the output. Same kernels, same results
+ * (bit for bit) as small_network_run_opt with a workspace of that size. The call allocates nothing and frees nothing
+ * (the first call on a device looks the array's address up once; make that call outside a graph capture).
+ * A table and batch whose small_network_workspace size exceeds SMALL_STATIC_WORKSPACE_BYTES: SMALL_ERR_STATIC, nothing
+ * enqueued (64 MiB holds, for example, the residual CNN of 32x32x3 images up to batch 256). Every call on a GPU uses
+ * that GPU's one array: calls that may overlap on one GPU (different streams, or replays of graphs that captured it)
+ * race on it, and the array keeps the last call's tensors; nothing in it needs clearing, every layer writes its
+ * result before a later layer reads it. in / out_blocked / flags as for small_network_run_opt. */
+enum { SMALL_STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024 };
+int small_network_run_static(const small_layer *layers, int n_layers, const float *in, float *out_blocked, int N, int C0,
+                             int H0, int W0, unsigned flags, void *stream);
 
 #ifdef __cplusplus
 }

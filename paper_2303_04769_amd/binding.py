@@ -24,7 +24,7 @@ EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "sma
            "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_probe_mfma", "small_pack_u8", "small_unpack_u8",
            "small_pack_filter_u8", "small_filter_sums_u8", "small_conv2d_u8", "small_dwconv2d_u8", "small_dense_u8", "small_pool2d_u8", "small_relu_u8",
            "small_network_workspace", "small_network_run", "small_network_run_plain", "small_network_run_opt", "small_network_launches", "small_network_launches_at",
-           "small_network_run_range"]
+           "small_network_run_range", "small_network_run_static"]
 
 
 class SmallError(RuntimeError):
@@ -97,6 +97,7 @@ def load():
                                           C.POINTER(C.c_int)]),
         "small_network_launches": (i, [C.POINTER(small_layer), i, C.POINTER(i), C.POINTER(i)]),
         "small_network_run_range": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, i, i, p]),
+        "small_network_run_static": (i, [C.POINTER(small_layer), i, p, p, i, i, i, i, C.c_uint, p]),
     }
     for name, (res, args) in sig.items():
         f = getattr(lib, name)     # AttributeError if the library does not export it
@@ -330,6 +331,14 @@ def small_network_run_range(table, in_blocked, out_blocked, workspace, workspace
                                           C.c_void_p(workspace.data_ptr()) if workspace is not None else None,
                                           workspace_bytes, N, C0, H0, W0, first, count, _stream(stream)),
            "small_network_run_range")
+
+
+STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024
+
+
+def small_network_run_static(table, in_tensor, out_blocked, N, C0, H0, W0, flags=0, stream=None):
+    _check(load().small_network_run_static(table, len(table), _ptr(in_tensor), _ptr(out_blocked), N, C0, H0, W0, flags,
+                                           _stream(stream)), "small_network_run_static")
 
 
 class PackedNetwork:

@@ -113,6 +113,7 @@ const char *small_strerror(int code)
         case SMALL_ERR_WORKSPACE: return "workspace too small or misaligned";
         case SMALL_ERR_LAYER: return "malformed layer table";
         case SMALL_ERR_QUANT: return "quantization parameters out of range or reduction too long for int32";
+        case SMALL_ERR_STATIC: return "table and batch need more workspace than the built-in array holds (SMALL_STATIC_WORKSPACE_BYTES)";
         default: return "unknown error";
     }
 }
@@ -981,6 +982,42 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
 {
     return network_run_impl(layers, n_layers, in_nchw, out_blocked, workspace, workspace_bytes, N, C0, H0, W0, 0,
                             INT_MAX, stream, SMALL_RUN_PLAIN_INPUT);
+}
+
+// The layer workspace of small_network_run_static: one array per GPU, part of the library's device image, held from
+// the moment the library is loaded on that GPU until the process ends.
+static __device__ __align__(256) unsigned char scratch[SMALL_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];      // the array's address on every device that has asked for it
+
+// The device address of `scratch` on the current device (in host code the array's name is not an address).
+int scratch_address(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SMALL_ERR_LAUNCH;
+    void *q = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!q) {
+        if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return SMALL_ERR_LAUNCH;
+        __atomic_store_n(&g_scratch_ptr[dev], q, __ATOMIC_RELEASE);     // every thread obtains the same address
+    }
+    *ptr = q;
+    return SMALL_OK;
+}
+}  // namespace
+
+int small_network_run_static(const small_layer *layers, int n_layers, const float *in, float *out_blocked, int N, int C0,
+                             int H0, int W0, unsigned flags, void *stream)
+{
+    if (flags & ~(unsigned)(SMALL_RUN_PLAIN_INPUT | SMALL_RUN_RESIDENT_OFF | SMALL_RUN_RESIDENT_ON | SMALL_RUN_PLAIN_OUTPUT)) return SMALL_ERR_SHAPE;
+    size_t need = 0;
+    if (int rc = small_network_workspace(layers, n_layers, N, C0, H0, W0, &need)) return rc;
+    if (need > (size_t)SMALL_STATIC_WORKSPACE_BYTES) return SMALL_ERR_STATIC;
+    void *ws = nullptr;
+    if (int rc = scratch_address(&ws)) return rc;
+    return network_run_impl(layers, n_layers, in, out_blocked, ws, (size_t)SMALL_STATIC_WORKSPACE_BYTES, N, C0, H0, W0, 0,
+                            INT_MAX, stream, flags);
 }
 
 int small_network_run_range(const small_layer *layers, int n_layers, const float *in_blocked, float *out_blocked,

@@ -24,7 +24,7 @@ def _declared():
 def test_every_declared_symbol_is_exported(lib):
     from paper_2303_04769_amd import binding
     names = _declared()
-    assert len(names) == 33 and set(names) == set(binding.EXPORTS)
+    assert len(names) == 34 and set(names) == set(binding.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
 
