@@ -542,6 +542,7 @@ const char *conv_kernel_name(const LayerGeom &g)
         if (g.Cib == 8 && g.kh == 1 && g.kw == 1) return "conv_small<8,1,1>";
         return "conv_small<0,0,0>";
     }
+    if (conv_pw_eligible(g)) return conv_pw_kernel_name(g);
     const int tile = pick_tile(g);
     if (conv_same_eligible(g))
         snprintf(name, sizeof(name), "%s<%s,%d,%d,%d>", conv_same_images_per_workgroup(g, tile) ? "conv16_img" : "conv16_same",
@@ -613,6 +614,7 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
         hipLaunchKernelGGL(conv_direct, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cib, g.Cob, total);
         return hipGetLastError();
     }
+    if (conv_pw_eligible(g)) return launch_conv_pw(in, filt, out, a.res, g, epilogue, s);
     const int tile = pick_tile(g);
     if (conv_same_eligible(g)) return launch_conv_same(in, filt, out, a.res, g, tile, epilogue, s);
     switch (tile) {

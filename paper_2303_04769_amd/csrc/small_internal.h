@@ -140,6 +140,14 @@ int conv_same_images_per_workgroup(const LayerGeom &g, int tile);
 hipError_t launch_conv_same(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
                             int tile, int epilogue, hipStream_t s);
 
+// Pointwise (1x1, stride 1, unpadded) convolution with the filter resident on the compute unit and autonomous
+// waves that stream 16-pixel groups (conv_pw.hip): 64 -> 64 and 128 -> 128 channels, at least 32768 pixels, 16-byte
+// aligned pointers.
+bool conv_pw_eligible(const LayerGeom &g);
+const char *conv_pw_kernel_name(const LayerGeom &g);
+hipError_t launch_conv_pw(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
+                          int epilogue, hipStream_t s);
+
 // Depthwise 3x3 (+ ReLU) followed by pointwise 1x1 (+ ReLU) in one launch, 16-channel blocks. dwpw_eligible looks
 // at what a layer table states (channels, blocks, windows, strides); dwpw_geom_ok at the image geometry.
 constexpr size_t kDwPwMaxLds = 160 * 1024;

@@ -153,6 +153,31 @@ def test_conv2d_persistent_variant(case):
     assert_close(got, O.conv2d(x, w, stride, pad), Ci * k * k, f"conv persistent {case}")
 
 
+POINTWISE_STREAM_CASES = [  # N, C, H, W: 64 or 128 channels, at least 32768 pixels
+    (3, 64, 105, 105),       # 33075 pixels: groups of 16 straddle images, the last group has 3 pixels
+    (70, 64, 25, 19),        # 33250 pixels, many small images, ragged end (2 pixels)
+    (11, 128, 55, 55),       # 128 channels: two waves share a pixel group; 33275 pixels (11 in the last group)
+    (9, 128, 61, 60),        # 32940 pixels: a tail of units after the full rounds
+    (16, 64, 64, 64),        # 65536 pixels: 4096 groups = 2 full rounds on 2048 waves, no tail, no ragged group
+    (17, 64, 64, 64),        # ... and one image more: a short tail
+    (40, 128, 30, 30),       # 36000 pixels = 2250 groups: fewer tasks than two rounds of 512 tasks
+]
+
+
+@pytest.mark.parametrize("case", POINTWISE_STREAM_CASES)
+def test_conv2d_pointwise_stream(case):
+    """1x1 convolutions on 64 / 128 channels with many pixels run in the persistent kernel with the filter resident
+    (asserted by name): full rounds of tasks, the finer units of the tail, and the ragged last group."""
+    N, C, H, W = case
+    name = S.small_conv2d_kernel(N, C, C, H, W, 1, 1, 1, (0, 0, 0, 0), 16, 16)
+    assert name.startswith("pw16_stream"), (case, name)
+    rng = np.random.default_rng(6100 + N + C)
+    x = (rng.random((N, C, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    w = (rng.random((C, C, 1, 1), dtype=np.float32) * 2 - 1).astype(np.float32)
+    got = run_conv(x, w, 1, (0, 0, 0, 0))
+    assert_close(got, O.conv2d(x, w, 1, (0, 0, 0, 0)), C, f"pointwise stream {case}")
+
+
 FIRST_LAYER_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad: at least 16384 output pixels, one short input block
     (17, 3, 16, 32, 32, 3, 3, 1, (1, 1, 1, 1)),      # K = 27: the residual network's first layer, ragged pixel tail
     (8, 3, 8, 96, 96, 3, 3, 2, (0, 1, 0, 1)),        # 8-channel output block, stride 2, bottom / right padding

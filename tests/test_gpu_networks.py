@@ -542,6 +542,31 @@ def test_output_buffer_receives_every_write(flags):
     assert_close(got, ref, 144, f"conv into OUT followed by an add into a slot (resident {flags})")
 
 
+@pytest.mark.parametrize("C,N,H,W", [(64, 9, 61, 61), (128, 10, 58, 57)])
+def test_pointwise_stream_epilogues(C, N, H, W):
+    """The persistent 1x1 kernel inside a layer table: ReLU folded into its store phase, and a residual add (+ ReLU)
+    onto another buffer (the variant that reads the residual tensor), ragged pixel count."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("pointwise_stream_epilogues", C, H, W)
+    net.wshapes = [((C, C, 1, 1), C), ((C, C, 1, 1), C)]
+    z = (0, 0, 0, 0)
+    net.layers = [
+        Layer("conv", C, C, H, W, 1, 1, 1, z, src=IN, dst=0, w=0),
+        Layer("relu", C, C, H, W, src=0, dst=0),
+        Layer("conv", C, C, H, W, 1, 1, 1, z, src=0, dst=1, w=1),
+        Layer("add", C, C, H, W, src=1, src2=0, dst=1),
+        Layer("relu", C, C, H, W, src=1, dst=1),
+        Layer("maxpool", C, C, H, W, 1, 1, 1, z, src=1, dst=OUT),
+    ]
+    assert S.small_conv2d_kernel(N, C, C, H, W, 1, 1, 1, z, 16, 16).startswith("pw16_stream")
+    table = S.make_layer_table(net.layers, [None] * 2)
+    assert S.small_network_launches(table) == [0, 2, 5]
+    x, ws = WL.network_tensors(net, N, 6200 + C)
+    a = O.relu(O.conv2d(x, ws[0], 1, z))
+    ref = O.relu(O.add(O.conv2d(a, ws[1], 1, z), a))
+    assert_close(_run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF), ref, C, f"pointwise stream with epilogues, C={C}")
+
+
 def _run_both(net, x, ws):
     """Blocked outputs of small_pack + small_network_run and of small_network_run_plain on the same input."""
     N = x.shape[0]
