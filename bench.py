@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--only", default="", help="comma-separated sweep layers to run (e.g. dw3x3,relu); skips the rest")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-networks", action="store_true")
+    ap.add_argument("--resident-timing", action="store_true",
+                    help="per-layer cycle stamps of the image-resident run (needs a library built with SMALL_RES_TIMING=1)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the CPU-oracle sample")
     return ap.parse_args()
 
@@ -145,6 +147,9 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.resident_timing:
+        resident_timing(S, net, N)
+        return
     t0 = time.perf_counter()
     e0, e1 = ev(), ev()
     e0.record()
@@ -297,6 +302,31 @@ def main():
                                   "single_thread_sample": "first %d images, one pass of %.2f s" % (n_1, dt1),
                                   "max_abs_diff_vs_gpu": err}
     print(json.dumps(result))
+
+
+def resident_timing(S, net, N):
+    """Developer aid: cycle stamps that a library built with SMALL_RES_TIMING=1 leaves behind (workgroups 0 and 100, every
+    wave, per layer of the last image-resident launch): time in the layer's own code, in the work after it (border
+    clearing, requests for the next layer) and at the barrier, in shader clock cycles."""
+    import ctypes as C
+    import numpy as np
+    lib = S.binding.load()
+    if not hasattr(lib, "small_debug_resident_timing"):
+        sys.exit("bench.py --resident-timing: the library was built without SMALL_RES_TIMING=1")
+    buf = (C.c_ulonglong * (2 * 8 * 64))()
+    lib.small_debug_resident_timing.argtypes = [C.POINTER(C.c_ulonglong)]
+    if lib.small_debug_resident_timing(buf) != 0:
+        sys.exit("bench.py --resident-timing: reading the stamps failed")
+    t = np.array(buf[:], dtype=np.int64).reshape(2, 8, 64)
+    n_launch_layers = sum(1 for k in range(15) if t[0, 0, 2 + 4 * k] > 0)
+    for b, wg in enumerate((0, 100)):
+        t0 = int(t[b, :, 0].min())
+        print("workgroup %d: input staged after %d cycles" % (wg, int(t[b, :, 1].max()) - t0))
+        for li in range(n_launch_layers):
+            e, c, pb, ab = (t[b, :, 2 + 4 * li + k] for k in range(4))
+            print("  layer %2d: wall %6d | per wave: code %s  after %s  barrier %s"
+                  % (li, int((ab - e).max()), (c - e).tolist(), (pb - c).tolist(), (ab - pb).tolist()))
+        print("  total %d cycles" % (int(t[b, :, 5 + 4 * (n_launch_layers - 1)].max()) - t0))
 
 
 def spin(fn, seconds=0.12):

@@ -12,6 +12,12 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc", 
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# SMALL_RES_TIMING=1 in the environment builds the image-resident run with cycle stamps per layer and wave (read back by
+# `bench.py --resident-timing`); the stamps cost a few store instructions per layer, so the default build has none.
+if os.environ.get("SMALL_RES_TIMING"):
+    FLAGS = FLAGS + ["-DSMALL_RES_TIMING"]
+
+
 def _stale(target, deps):
     if not os.path.exists(target):
         return True

@@ -38,6 +38,13 @@
 namespace small {
 namespace {
 
+#ifdef SMALL_RES_TIMING
+__device__ unsigned long long g_res_t[2 * 8 * 64];
+#define RES_STAMP(slot_) do { if (tblk >= 0 && lane == 0) g_res_t[(tblk * 8 + w) * 64 + (slot_)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define RES_STAMP(slot_) do { } while (0)
+#endif
+
 constexpr int kResWaves = 8;
 constexpr int kResThreads = kResWaves * 64;
 constexpr int kResLdsBytes = 160 * 1024;
@@ -103,12 +110,13 @@ typedef const __attribute__((address_space(4))) ResArgs *ResKernArgs;
 // row's first padding pixel, so left and right padding share their columns (34 x 33 + 1 instead of 34 x 34 pixels
 // for a 32 x 32 image padded by one).
 template <typename E>
-__device__ __forceinline__ void clear_border(E *tensor, int n_planes, int H, int W, int pt, int pb, int pc, int w, int lane)
+__device__ __forceinline__ void clear_border(E *tensor, int n_planes, int H, int W, int pt, int pb, int pc, int w, int lane,
+                                             int n_waves = kResWaves)
 {
     const int Wp = pc + W, plane = (pt + H + pb) * Wp + pc;
     const int top = pt * Wp, bot = pb * Wp + pc;
     const E zero = E{};
-    for (int k = w; k < n_planes; k += kResWaves) {
+    for (int k = w; k < n_planes; k += n_waves) {
         E *t = tensor + k * plane;
         for (int r = lane; r < top; r += 64) t[r] = zero;
         for (int r = lane; r < bot; r += 64) t[(pt + H) * Wp + r] = zero;
@@ -580,6 +588,10 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
     div_sW.magic = ka->div_sW.magic; div_sW.shift = ka->div_sW.shift; div_sW.d = ka->div_sW.d;
     div_sH.magic = ka->div_sH.magic; div_sH.shift = ka->div_sH.shift; div_sH.d = ka->div_sH.d;
 
+#ifdef SMALL_RES_TIMING
+    const int tblk = blockIdx.x == 0 ? 0 : (blockIdx.x == 100 ? 1 : -1);
+#endif
+    RES_STAMP(0);
     const int slot = ka->slot;
     floatx4 a_pre[kResMaxTaps];
 #pragma unroll
@@ -629,12 +641,18 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
             clear_border(lds + s_off, ka->snCb * 4, sH, sW, ka->spt, ka->spb, ka->spc, w, lane);
         }
         __syncthreads();
+        RES_STAMP(1);
 
         float *gout_f = ka->out + (size_t)n * out_floats;
         floatx4 *gout = reinterpret_cast<floatx4 *>(gout_f);
         for (int li = 0; li < n_layers; ++li) {
             // (a_pre holds this wave's first filter values of layer li)
             const int T = ka->layer[li].T, taps = ka->layer[li].taps, kind = ka->layer[li].kind;
+            RES_STAMP(2 + 4 * li);
+            // The padding of the result is cleared by the upper four waves BEFORE they start on the layer (nobody
+            // reads or writes it during the layer): the two waves of a SIMD then run half a set-up apart, and one's
+            // set-up and store phases fall into the other's matrix loop instead of coinciding with its own.
+            
             if (kind == RES_STEM) {
                 resident_stem(ka, lds, gout, w, lane, stem_fa);
             } else if (kind == RES_HEAD) {
@@ -652,6 +670,7 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
                 else if (T == 2) resident_conv<2, 1, false>(ka, li, lds, gout, w, lane, a_pre, slot);
                 else resident_conv<1, 1, false>(ka, li, lds, gout, w, lane, a_pre, slot);
             }
+            RES_STAMP(3 + 4 * li);
             // the padding of the result (nobody reads it before the barrier; a wave that is done early does this
             // while the others still compute)
             if (kind != RES_HEAD && ka->layer[li].out.off >= 0)
@@ -659,7 +678,9 @@ __global__ void __launch_bounds__(kResThreads) __attribute__((amdgpu_waves_per_e
                              ka->layer[li].opt, ka->layer[li].opb, ka->layer[li].opc, w, lane);
             if (li + 1 < n_layers) prefetch_first(ka, li + 1, w, lane, a_pre);
             else if (n + (int)gridDim.x < N) prefetch_first(ka, 0, w, lane, a_pre);
+            RES_STAMP(4 + 4 * li);
             __syncthreads();   // the layer's output is complete, its input may be overwritten
+            RES_STAMP(5 + 4 * li);
             }
     }
 }
@@ -913,6 +934,13 @@ bool plan_prefix(const ResGroup *g_in, int n_in, ResArgs &a, int &lds_bytes)
 }
 
 }  // namespace
+
+#ifdef SMALL_RES_TIMING
+extern "C" int small_debug_resident_timing(unsigned long long *host_out)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_res_t), sizeof(unsigned long long) * 2 * 8 * 64);
+}
+#endif
 
 int resident_groups(const ResGroup *g, int n, const bool *closed_after)
 {
