@@ -22,7 +22,9 @@
  *     may equal an input exactly (in place);
  *   - padding is explicit zero padding, 4-sided; output size per side is
  *     floor((in + lo + hi - k) / stride) + 1 (the paper's output-size equation of
- *     Section 3.1.2 extended with padding and floor);
+ *     Section 3.1.2 extended with padding and floor). Every padding must be smaller than the
+ *     window on its axis (pad.t, pad.b < kh; pad.l, pad.r < kw), so that no window lies entirely
+ *     in the padding (a maximum or an average over no element has no value): SMALL_ERR_SHAPE otherwise;
  *   - return value: SMALL_OK (0) or an error code below. When an error is returned
  *     nothing has been enqueued. No exception crosses this boundary.
  */
@@ -38,7 +40,8 @@ extern "C" {
 enum {
     SMALL_OK = 0,
     SMALL_ERR_NULL = 1,   /* a required pointer is NULL */
-    SMALL_ERR_SHAPE = 2,  /* non-positive dim, window larger than the padded input, C % Cb != 0, size overflow */
+    SMALL_ERR_SHAPE = 2,  /* non-positive dim, window larger than the padded input, padding >= window, C % Cb != 0,
+                             size overflow */
     SMALL_ERR_BLOCK = 3,  /* block size with no kernel (Cb > 64) */
     SMALL_ERR_ALIAS = 4,  /* in/out overlap where it is not allowed */
     SMALL_ERR_LAUNCH = 5, /* the HIP runtime refused the launch */
@@ -129,12 +132,6 @@ int small_batchnorm(const float *in, const float *scale, const float *shift, flo
 int small_upsample(const float *in, float *out, int N, int C, int H, int W, int fh, int fw, int Cb, void *stream);
 int small_group_conv2d(const float *in, const float *filt, float *out, int N, int Ci, int F_C, int S_C, int K, int H, int W,
                        int kh, int kw, int stride, small_pad pad, int Cib, int F_Cb, int Cob, void *stream);
-
-/* ---- measurement aid, not a layer: the fp32 matrix rate the chip sustains, for quoting roofline fractions against
- * a measured peak as well as the published one. Launches `workgroups` x 4 wavefronts, each running `iters` rounds
- * of eight independent 16x16x4 fp32 matrix instructions on registers (2048 flop per instruction and wavefront:
- * workgroups * 4 * iters * 8 * 2048 flop in all); out receives workgroups * 256 floats (checksums). */
-int small_probe_mfma(float *out, int workgroups, int iters, void *stream);
 
 /* ---- quantized layers: uint8 codes in and out, int32 sums (Section "Memory Usage Comparison": inputs and
  * outputs of the quantized models are uint8, partial results are accumulated in int32; Section "Quantized
@@ -228,7 +225,7 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
  *                           classifier head); then no small_unpack is needed. Otherwise SMALL_ERR_LAYER, nothing
  *                           enqueued: run without the flag and call small_unpack.
  * Image-resident runs: consecutive layers whose per-image tensors fit 152 KB of LDS together run as ONE launch,
- * one image per workgroup (256 workgroups, further images in further rounds): optionally a first convolution on
+ * one image per workgroup (one workgroup per compute unit, further images in further rounds): optionally a first convolution on
  * fewer than 16 input channels that reads the network input (Ci * kh * kw <= 40), then convolutions with 16-channel
  * blocks in and out (1 or 9 filter taps, any stride and padding, with their folded ReLU / residual add), optionally
  * closed by an average pooling over the whole image + fully connected layer (C <= 256, Co <= 16). Only the run's
@@ -237,8 +234,9 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
  * "Conclusion & Future Directions" across layers of Table 1's partial-reduction class. Depthwise convolutions
  * (16-channel blocks, at most 9 taps, filter 16-byte aligned) may stand inside a run, and a 1x1 convolution added onto
  * the convolution before it (a projection shortcut) is folded into that one. Without either RESIDENT flag such runs
- * are used when 144 <= N <= 256 or 448 <= N <= 512 (one or two full rounds of one image per compute unit; measured
- * break-even points against the layer-by-layer kernels) and the run averages at least
+ * are used when the batch is 9/16 .. 1 or 1 3/4 .. 2 rounds of one image per compute unit (on the 256 compute units of
+ * an MI355X: 144 <= N <= 256 or 448 <= N <= 512; measured break-even points against the layer-by-layer kernels) and
+ * the run averages at least
  * 250000 (one round) or 500000 (two rounds) multiply-adds per layer and image (below that the per-layer cost inside
  * a workgroup outweighs the launches saved: measured on the depthwise-separable CNNs); small_network_run,
  * small_network_run_plain and small_network_run_range follow that rule too (small_network_run_plain then also

@@ -21,7 +21,7 @@ _OPS = {"conv": OP_CONV, "dw": OP_DWCONV, "maxpool": OP_MAXPOOL, "avgpool": OP_A
 
 EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "small_pack_filter",
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
-           "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_probe_mfma", "small_pack_u8", "small_unpack_u8",
+           "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_pack_u8", "small_unpack_u8",
            "small_pack_filter_u8", "small_filter_sums_u8", "small_conv2d_u8", "small_dwconv2d_u8", "small_dense_u8", "small_pool2d_u8", "small_relu_u8",
            "small_network_workspace", "small_network_run", "small_network_run_plain", "small_network_run_opt", "small_network_launches", "small_network_launches_at",
            "small_network_run_range", "small_network_run_static"]
@@ -79,7 +79,6 @@ def load():
         "small_batchnorm": (i, [p, p, p, p, i, i, i, i, i, p]),
         "small_upsample": (i, [p, p, i, i, i, i, i, i, i, p]),
         "small_group_conv2d": (i, [p, p, p, i, i, i, i, i, i, i, i, i, i, small_pad, i, i, i, p]),
-        "small_probe_mfma": (i, [p, i, i, p]),
         "small_pack_u8": (i, [p, p, i, i, i, i, i, p]),
         "small_unpack_u8": (i, [p, p, i, i, i, i, i, p]),
         "small_pack_filter_u8": (i, [p, p, i, i, i, i, i, i, p]),
@@ -201,8 +200,27 @@ def small_group_conv2d(inp, filt, out, N, Ci, F_C, S_C, K, H, W, kh, kw, stride,
                                      Cib, F_Cb, Cob, _stream(stream)), "small_group_conv2d")
 
 
+PROBE_LIB_PATH = os.path.join(_HERE, "libsmall_probe.so")
+_probe = None
+
+
+def load_probe():
+    """The benchmark's matrix-rate probe (include/small_probe.h), a library of its own."""
+    global _probe
+    if _probe is None:
+        if not os.path.exists(PROBE_LIB_PATH):
+            from .build import build_lib
+            build_lib()
+        lib = C.CDLL(PROBE_LIB_PATH)
+        lib.small_probe_mfma.restype, lib.small_probe_mfma.argtypes = C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        _probe = lib
+    return _probe
+
+
 def small_probe_mfma(out, workgroups, iters, stream=None):
-    _check(load().small_probe_mfma(_ptr(out), workgroups, iters, _stream(stream)), "small_probe_mfma")
+    rc = load_probe().small_probe_mfma(_ptr(out), workgroups, iters, _stream(stream))
+    if rc:
+        raise RuntimeError(f"small_probe_mfma: error {rc}")
 
 
 def _ptr8(t):

@@ -6,7 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsmall_hip.so")
-SOURCES = ["elementwise.hip", "window.hip", "window_rows.hip", "conv.hip", "conv_same.hip", "conv_pw.hip", "dwpw.hip", "chain.hip", "resident.hip", "quant.hip", "probe.hip", "table2.hip", "small_api.hip"]
+PROBE_LIB = os.path.join(HERE, "libsmall_probe.so")       # the benchmark's matrix-rate probe, a library of its own
+SOURCES = ["elementwise.hip", "window.hip", "window_rows.hip", "conv.hip", "conv_same.hip", "conv_pw.hip", "dwpw.hip", "chain.hip", "resident.hip", "quant.hip", "table2.hip", "small_api.hip"]
 # packed fp32 VALU ops are switched off for every device translation unit
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function", "-Wno-pass-failed",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -51,6 +52,12 @@ def build_lib(force=False, verbose=False):
         raise RuntimeError("hipcc failed\n" + "\n".join(failed))
     if force or procs or _stale(LIB, objs):
         subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
+    probe_src = os.path.join(CSRC, "probe.hip")
+    if force or _stale(PROBE_LIB, [probe_src, os.path.join(HERE, "..", "include", "small_probe.h")]):
+        out = subprocess.run([hipcc] + FLAGS + ["-shared", probe_src, "-o", PROBE_LIB], stdout=subprocess.PIPE,
+                             stderr=subprocess.STDOUT, text=True)
+        if out.returncode:
+            raise RuntimeError("hipcc failed\nprobe.hip:\n" + out.stdout)
     return LIB
 
 

@@ -394,7 +394,7 @@ void launch_mfma(const ConvArgs &a, hipStream_t s)
 // leave 4 or more of them resident per compute unit, which hides each other's prologue, barrier and
 // store phases. 1x1 (little work per pixel): 32 pixels x 64 channels, or 32 x 32 for narrow layers.
 // 3x3: the candidate with the least work on the busiest compute unit (workgroups are spread evenly,
-// so that is ceil(workgroups / 256) x tile area), 64 x 32 preferred on near-ties for its operand reuse.
+// so that is ceil(workgroups / compute units) x tile area), 64 x 32 preferred on near-ties for its operand reuse.
 int pick_tile(const LayerGeom &g)
 {
     const long M = (long)g.N * g.Ho * g.Wo;
@@ -405,11 +405,12 @@ int pick_tile(const LayerGeom &g)
     static const Cand narrow[] = {{SAME_128x16, 128, 16, 1.0}, {SAME_64x16, 64, 16, 1.05}};
     const Cand *cands = g.Co >= 32 ? wide : narrow;
     const int n = g.Co >= 32 ? 3 : 2;
+    const long cus = device_cus();
     int best = cands[0].tile;
     double best_cost = 0;
     for (int i = 0; i < n; ++i) {
         const long wgs = ((M + cands[i].tm - 1) / cands[i].tm) * ((g.Co + cands[i].tn - 1) / cands[i].tn);
-        const double cost = (double)((wgs + 255) / 256) * cands[i].tm * cands[i].tn * cands[i].penalty;
+        const double cost = (double)((wgs + cus - 1) / cus) * cands[i].tm * cands[i].tn * cands[i].penalty;
         if (i == 0 || cost < best_cost) { best = cands[i].tile; best_cost = cost; }
     }
     return best;

@@ -238,17 +238,6 @@ __global__ void __launch_bounds__(64 * kPwMaxWaves) pw16_stream(PwArgs a)
     }
 }
 
-int device_cus()
-{
-    static const int n = [] {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 256;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
-        return cus;
-    }();
-    return n;
-}
-
 // PER_CU workgroups of four waves per compute unit: with 64 channels two (eight waves hide the load latency of a layer
 // that is bound by HBM; measured 18.2 us against 19.6 with one), with 128 channels one (the 64 KB filter and the
 // rings allow no more, and the layer is bound by the matrix pipe: one wave per SIMD keeps it busy).

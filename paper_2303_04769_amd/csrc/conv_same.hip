@@ -574,7 +574,8 @@ int images_per_workgroup(int N, int HW, int nCib, int nCob)     // HW: pixels of
     const long tpi = (HW + C::TM - 1) / C::TM;
     if (KS == 1 || tpi * C::TM * 100 > (long)HW * 108 || N < 2) return 0;   // measured: no gain for 1x1 filters
     const long positions = tpi * ((nCob + C::NSUB - 1) / C::NSUB);
-    constexpr long kCUs = 256, kMinPerCU = 4;
+    const long kCUs = device_cus();
+    constexpr long kMinPerCU = 4;
     const double t_tile = (double)nsteps * C::NS * 4 * WM * WN * 32;   // matrix-pipe cycles of one wave per tile
     const double t_setup = 2500;                                       // set-up, launch and first-load latency, cycles
     int best = 0;

@@ -260,7 +260,7 @@ DwPwPlan make_plan(const LayerGeom &g, int Co)
     // when that leaves compute units without a workgroup
     int wn = std::min(4, nCob);
     const long tiles = (long)p.n_mtiles * ((g.N + p.ipt - 1) / p.ipt);
-    while (wn > 1 && tiles * ((nCob + wn - 1) / wn) < 256) wn = (wn + 1) / 2;
+    while (wn > 1 && tiles * ((nCob + wn - 1) / wn) < device_cus()) wn = (wn + 1) / 2;
     p.wn = wn;
     int ent = 0;
     for (int m = 0; m < p.n_mtiles; ++m) {
@@ -278,7 +278,7 @@ DwPwPlan make_plan(const LayerGeom &g, int Co)
     // LDS if three stages fit in that; otherwise by depth: up to 48 KiB of ring.
     const size_t room = kDwPwMaxLds > fixed + 256 ? kDwPwMaxLds - fixed - 256 : 0;
     size_t budget = std::min<size_t>(48 * 1024, room);
-    if (tiles * ((nCob + wn - 1) / wn) >= 1024 && fixed + 256 + 3 * (size_t)p.stage_bytes <= 40 * 1024)
+    if (tiles * ((nCob + wn - 1) / wn) >= 4 * device_cus() && fixed + 256 + 3 * (size_t)p.stage_bytes <= 40 * 1024)
         budget = 40 * 1024 - fixed - 256;
     p.stages = (int)std::min<size_t>({(size_t)kMaxStages, budget / (size_t)p.stage_bytes, (size_t)(63 / p.lps + 1)});
     p.lds = (size_t)((p.stages * p.stage_bytes + 255) & ~255) + fixed;

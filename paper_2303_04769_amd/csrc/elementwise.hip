@@ -204,4 +204,15 @@ hipError_t launch_pack_filter(const float *oihw, float *blk, int Co, int Ci, int
     return hipGetLastError();
 }
 
+int device_cus()
+{
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+        return cus;
+    }();
+    return n;
+}
+
 }  // namespace small

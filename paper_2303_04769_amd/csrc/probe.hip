@@ -1,11 +1,15 @@
-// Measurement aid, not a layer: a register-resident loop of independent fp32 matrix instructions, to read the
-// matrix rate this chip actually sustains (the roofline fractions are quoted against the published peak and
-// against this). Every wave runs `iters` rounds of eight independent v_mfma_f32_16x16x4_f32 accumulations on
-// operands it never reloads and stores one value at the end so that nothing is optimised away.
-#include "small_internal.h"
+// Measurement aid, not a layer and not part of libsmall_hip: a register-resident loop of independent fp32 matrix
+// instructions, to read the matrix rate this chip actually sustains (the benchmark quotes roofline fractions against
+// the published peak and against this). Built into a library of its own (libsmall_probe.so, include/small_probe.h).
+// Every wave runs `iters` rounds of eight independent v_mfma_f32_16x16x4_f32 accumulations on operands it never
+// reloads and stores one value at the end so that nothing is optimised away.
+#include "../../include/small_probe.h"
 
-namespace small {
+#include <hip/hip_runtime.h>
+
 namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 __global__ void __launch_bounds__(256) mfma_probe_kernel(float *out, int iters, float seed)
 {
@@ -25,10 +29,11 @@ __global__ void __launch_bounds__(256) mfma_probe_kernel(float *out, int iters, 
 
 }  // namespace
 
-hipError_t launch_mfma_probe(float *out, int workgroups, int iters, hipStream_t s)
+extern "C" int small_probe_mfma(float *out, int workgroups, int iters, void *stream)
 {
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, s, out, iters, 0.25f);
-    return hipGetLastError();
+    if (!out) return 1;
+    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0) return 2;
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(256), 0, reinterpret_cast<hipStream_t>(stream), out,
+                       iters, 0.25f);
+    return hipGetLastError() == hipSuccess ? 0 : 5;
 }
-
-}  // namespace small

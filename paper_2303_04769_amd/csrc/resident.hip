@@ -966,7 +966,7 @@ hipError_t launch_resident(const ResGroup *g, int n, const float *in, float *out
     static hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(resident_run),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kResLdsBytes);
     if (attr != hipSuccess) return attr;
-    const int grid = N < kResidentWorkgroups ? N : kResidentWorkgroups;
+    const int grid = N < device_cus() ? N : device_cus();       // one workgroup per compute unit; more images: further rounds
     hipLaunchKernelGGL(resident_run, dim3((unsigned)grid), dim3(kResThreads), (size_t)lds, s, a);
     return hipGetLastError();
 }

@@ -261,13 +261,6 @@ int small_group_conv2d(const float *in, const float *filt, float *out, int N, in
     return from_hip(launch_group_conv(in, filt, out, g, F_C, S_C, K, F_Cb, as_stream(stream)));
 }
 
-int small_probe_mfma(float *out, int workgroups, int iters, void *stream)
-{
-    if (!out) return SMALL_ERR_NULL;
-    if (workgroups <= 0 || workgroups > (1 << 20) || iters <= 0) return SMALL_ERR_SHAPE;
-    return from_hip(launch_mfma_probe(out, workgroups, iters, as_stream(stream)));
-}
-
 // ---- quantized (uint8) layers
 
 }  // extern "C"
@@ -683,7 +676,7 @@ int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now,
     }
     // (measured break-even: the audio CNN, 0.27 M multiply-adds per layer, gains 2..10 % in one round and loses 10 %
     // in two; the depthwise-separable CNN, 0.09 M, always loses)
-    const double least = N <= kResidentWorkgroups ? 2.5e5 : 5e5;
+    const double least = N <= device_cus() ? 2.5e5 : 5e5;
     return macs >= least * taken ? taken : 0;
 }
 
@@ -697,9 +690,10 @@ bool resident_batch(int N, unsigned flags)
 {
     if (flags & SMALL_RUN_RESIDENT_OFF) return false;
     if (flags & SMALL_RUN_RESIDENT_ON) return true;
-    const int rounds = (N + kResidentWorkgroups - 1) / kResidentWorkgroups;
-    if (rounds == 1) return 16 * N >= 9 * kResidentWorkgroups;        // at least 144 images
-    if (rounds == 2) return 8 * N >= 14 * kResidentWorkgroups;        // at least 448
+    const int cus = device_cus();
+    const int rounds = (N + cus - 1) / cus;
+    if (rounds == 1) return 16 * N >= 9 * cus;        // at least 9/16 of a round: 144 images on 256 compute units
+    if (rounds == 2) return 8 * N >= 14 * cus;        // at least 1 3/4 rounds: 448
     return false;
 }
 

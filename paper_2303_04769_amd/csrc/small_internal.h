@@ -53,6 +53,11 @@ inline FastDiv make_fastdiv(int d)
     return f;
 }
 
+// Compute units of the current device (asked once; 256 -- an MI355X -- when no device can be asked, so that the
+// host-only planning calls give the same answers on a machine without a GPU). Launch shapes, tile choices and the
+// batch windows of image-resident runs are derived from it.
+int device_cus();
+
 // Direct global -> LDS loads, issued from inline assembly so that the compiler does not serialise them
 // against every LDS read; the issuing kernel tracks them by hand with wait_vmcnt.
 // 64 lanes x 16 B: global (base + per-lane byte offset) -> LDS (wave-uniform byte address + 16 * lane).
@@ -105,7 +110,6 @@ bool conv_takes_plain_input(const LayerGeom &g, const void *in, const void *filt
 // them in LDS (resident.hip). A group is one convolution as the runner launches it: logical buffer ids of its
 // input, residual (EPI_ADD only) and result, geometry, epilogue.
 constexpr int kResMaxLayers = 12;
-constexpr int kResidentWorkgroups = 256;     // one per compute unit; images beyond that are taken in further rounds
 // kind: RESIDENT_CONV (16-channel blocks in and out); RESIDENT_STEM: a first layer on fewer than 16 input channels
 // (only as group 0; plain_input: its input tensor is a plain [N][Ci][H][W] one, else blocked with Cib = Ci);
 // RESIDENT_HEAD: average pooling over the whole image followed by a fully connected layer (only as the last group;
@@ -195,9 +199,5 @@ hipError_t launch_filter_sums_u8(const unsigned char *filt, int *sums, int Co, i
 hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
                             int mode, const QuantParams &q, hipStream_t s);
 hipError_t launch_relu_u8(const unsigned char *in, unsigned char *out, size_t n, int z, hipStream_t s);
-
-// Measurement aid (probe.hip): `workgroups` x 4 waves, each `iters` x 8 independent 16x16x4 fp32 matrix instructions
-// on registers; out receives workgroups * 256 floats.
-hipError_t launch_mfma_probe(float *out, int workgroups, int iters, hipStream_t s);
 
 }  // namespace small

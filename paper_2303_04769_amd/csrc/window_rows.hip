@@ -249,7 +249,7 @@ hipError_t launch_cfg(RowsArgs a, const RowsPlan &p, hipStream_t s)
     a.stages = p.stages;
     a.stage_bytes = p.stage_bytes;
     // planes per workgroup: as many workgroups as are resident at once (LDS-limited, at most 8 per compute unit)
-    const long resident = 256 * std::max<long>(1, std::min<long>(8, (long)(160 * 1024 / p.lds)));
+    const long resident = device_cus() * std::max<long>(1, std::min<long>(8, (long)(160 * 1024 / p.lds)));
     const long per_wg = std::max<long>(1, ((long)a.n_mtiles * a.n_planes + resident - 1) / resident);
     a.n_groups = (int)((a.n_planes + per_wg - 1) / per_wg);
     a.dW = make_fastdiv(a.W);

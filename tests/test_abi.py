@@ -15,8 +15,8 @@ def lib():
     return binding.load()
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "small.h")).read()
+def _declared(header="small.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(small_[a-z0-9_]+)\s*\(", text)))
 
@@ -24,9 +24,13 @@ def _declared():
 def test_every_declared_symbol_is_exported(lib):
     from paper_2303_04769_amd import binding
     names = _declared()
-    assert len(names) == 34 and set(names) == set(binding.EXPORTS)
+    assert len(names) == 33 and set(names) == set(binding.EXPORTS)
     for n in names:
         assert getattr(lib, n) is not None
+    # the benchmark's probe is a library and a header of its own, outside the layer ABI
+    assert _declared("small_probe.h") == ["small_probe_mfma"] and not hasattr(lib, "small_probe_mfma")
+    assert binding.load_probe().small_probe_mfma is not None
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["small.h", "small_probe.h"]
 
 
 def test_out_dim_and_strerror(lib):
@@ -50,6 +54,12 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert lib.small_pool2d(fake, C.c_void_p(0x10000000), 1, 16, 2, 2, 3, 3, 1, small_pad(0, 0, 0, 0), 16, 0, None) == 2
     assert lib.small_pool2d(fake, C.c_void_p(0x10000000), 1, 16, 8, 8, 3, 3, 1, pad, 16, 7, None) == 2
     assert lib.small_pack(fake, fake, 1, 16, 4, 4, 16, None) == 4
+    # a padding as large as the window on its axis is refused (a window entirely in the padding has no maximum / mean)
+    far0 = C.c_void_p(0x10000000)
+    for bad in (small_pad(3, 0, 0, 0), small_pad(0, 3, 0, 0), small_pad(0, 0, 3, 0), small_pad(1, 1, 1, 5)):
+        assert lib.small_conv2d(fake, fake, far0, 1, 16, 16, 8, 8, 3, 3, 1, bad, 16, 16, None) == 2
+        assert lib.small_dwconv2d(fake, fake, far0, 1, 16, 8, 8, 3, 3, 1, bad, 16, None) == 2
+        assert lib.small_pool2d(fake, far0, 1, 16, 8, 8, 3, 3, 1, bad, 16, 0, None) == 2
     # quantized layers: parameter ranges and the int32 bound on the reduction length
     from paper_2303_04769_amd.binding import small_quant
     far = C.c_void_p(0x10000000)
