@@ -89,7 +89,7 @@ def main():
     if args.only:   # developer shortcut: selected sweep rows only, one JSON row per line ("u8" = the quantized sweep)
         only = set(args.only.split(","))
         if only != {"u8"}:
-            for row in sweep(S, WL, torch, np, dev, timed, only - {"u8"}):
+            for row in sweep(S, WL, torch, np, dev, timed, only - {"u8"}, cpu=not args.no_cpu):
                 print(json.dumps(row))
         if "u8" in only:
             for row in sweep_u8(S, WL, torch, dev, timed):
@@ -258,7 +258,7 @@ def main():
 
     # ------------------------------------------------------------------ roofline layer sweep
     if not args.no_sweep:
-        result["sweep"] = sweep(S, WL, torch, np, dev, timed)
+        result["sweep"] = sweep(S, WL, torch, np, dev, timed, cpu=not args.no_cpu)
         c = [r for r in result["sweep"] if r["layer"] == "conv3x3" and not r.get("paper_layer_study")]
         best = max(c, key=lambda r: r["frac"])
         result["roofline_sweep_conv3x3"] = {"bound": "mfma", "achieved": best["tflops"], "peak": PEAK_MFMA_F32 / 1e12,
@@ -296,7 +296,25 @@ def main():
         O.run_network(net, x[:n_1], ws)
         dt1 = time.perf_counter() - t
         O.set_threads(used)
+        others = []
+        for oname, oidx, n_all, n_one in (("dsep_cnn", 3, 64, 4), ("audio_cnn", 4, 256, 16), ("dense_autoencoder", 5, 8192, 512)):
+            onet = getattr(WL, oname)()
+            ox, ows = WL.network_tensors(onet, n_all, WL.BASE_SEED + oidx)
+            O.run_network(onet, ox[:2], ows)
+            t = time.perf_counter()
+            O.run_network(onet, ox, ows)
+            ta = time.perf_counter() - t
+            O.set_threads(1)
+            t = time.perf_counter()
+            O.run_network(onet, ox[:n_one], ows)
+            t1 = time.perf_counter() - t
+            O.set_threads(used)
+            others.append({"network": oname, "images_per_s": round(n_all / ta, 1), "cores": used,
+                           "sample": "%d seeded images, one pass of %.2f s" % (n_all, ta),
+                           "single_thread_images_per_s": round(n_one / t1, 2),
+                           "single_thread_sample": "%d images, one pass of %.2f s" % (n_one, t1)})
         result["cpu_baseline"] = {"value": round(n_s / dt, 2), "unit": "images/s", "cores": used, "kind": "oracle",
+                                  "networks": others,
                                   "sample": "first %d of the %d images of the same batch, %d passes of %.2f s" % (n_s, N, passes, dt),
                                   "single_thread_value": round(n_1 / dt1, 2),
                                   "single_thread_sample": "first %d images, one pass of %.2f s" % (n_1, dt1),
@@ -376,13 +394,37 @@ def _traffic(kernel):
         return None
 
 
-def sweep(S, WL, torch, np, dev, timed, only=None):
-    """Layer sweep at batch 64: every layer on its own, HBM-bound layers with rotated buffers."""
+def sweep(S, WL, torch, np, dev, timed, only=None, cpu=False):
+    """Layer sweep at batch 64: every layer on its own, HBM-bound layers with rotated buffers. cpu: the CPU oracle is
+    timed beside every row on the first 4 of the 64 images (one thread, then all cores), scaled to 64."""
     def want(name):
         return not only or name in only
     Nb = WL.SWEEP_N
     rng = np.random.default_rng(WL.BASE_SEED + 5)
     rows = []
+    ORACLE_N = 4
+
+    def oracle_beside(row, fn):
+        """fn(): the oracle on an N = 4 slice of the row's layer; adds its time scaled to the 64 images of the row."""
+        if not cpu:
+            return row
+        from oracle import oracle as O
+        cores = min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", 1 << 20)))
+        used = O.set_threads(cores)
+        fn()                                   # first touch of the arrays
+        t = time.perf_counter()
+        fn()
+        t_all = time.perf_counter() - t
+        O.set_threads(1)
+        t = time.perf_counter()
+        fn()
+        t_one = time.perf_counter() - t
+        O.set_threads(used)
+        k = Nb / ORACLE_N
+        row["oracle"] = {"ms_all_cores": round(t_all * k * 1e3, 2), "cores": used, "ms_one_thread": round(t_one * k * 1e3, 2),
+                         "sample": "first %d of the %d images, time scaled by %d" % (ORACLE_N, Nb, int(k)),
+                         "gpu_over_all_cores": round(t_all * k / (row["us"] * 1e-6), 1)}
+        return row
 
     def rand(n):
         return (torch.rand(n, device=dev, dtype=torch.float32) * 2 - 1)
@@ -419,12 +461,17 @@ def sweep(S, WL, torch, np, dev, timed, only=None):
             tmin, tmed = best_of(fn, 30 if k == 3 else 100)
             flops = 2.0 * Nb * C * H * H * C * k * k
             byts = 4.0 * (2 * n_act + C * C * k * k)
-            rows.append({"layer": name, "shape": "N64 C%d %dx%d" % (C, H, H), "paper_layer_study": (C, H) in shapes["paper_layer_study"],
-                         "us": round(tmin * 1e6, 2),
-                         "us_median": round(tmed * 1e6, 2), "tflops": round(flops / tmin / 1e12, 2),
-                         "frac": round(flops / tmin / PEAK_MFMA_F32, 4), "gbs": round(byts / tmin / 1e9, 1),
-                         "frac_hbm": round(byts / tmin / PEAK_HBM, 4),
-                         "kernel": S.small_conv2d_kernel(Nb, C, C, H, H, k, k, 1, pad, 16, 16)})
+            row = {"layer": name, "shape": "N64 C%d %dx%d" % (C, H, H), "paper_layer_study": (C, H) in shapes["paper_layer_study"],
+                   "us": round(tmin * 1e6, 2),
+                   "us_median": round(tmed * 1e6, 2), "tflops": round(flops / tmin / 1e12, 2),
+                   "frac": round(flops / tmin / PEAK_MFMA_F32, 4), "gbs": round(byts / tmin / 1e9, 1),
+                   "frac_hbm": round(byts / tmin / PEAK_HBM, 4),
+                   "kernel": S.small_conv2d_kernel(Nb, C, C, H, H, k, k, 1, pad, 16, 16)}
+            if cpu:
+                from oracle import oracle as O
+                xo, wo = WL.uniform_pm1(rng, (ORACLE_N, C, H, H)), WL.uniform_pm1(rng, (C, C, k, k))
+                oracle_beside(row, lambda: O.conv2d(xo, wo, 1, pad))
+            rows.append(row)
         if want("dw3x3"):
             wd = torch.from_numpy(WL.uniform_pm1(rng, (C * 9,))).to(dev)
             fn = lambda r: S.small_dwconv2d(ins[r % sets], wd, outs[r % sets], Nb, C, H, H, 3, 3, 1, (1, 1, 1, 1), 16)
@@ -432,10 +479,15 @@ def sweep(S, WL, torch, np, dev, timed, only=None):
             # the same layer on one buffer pair: the tensors then stay in the 256 MB Infinity Cache (not an HBM figure)
             twarm, _ = best_of(lambda r: S.small_dwconv2d(ins[0], wd, outs[0], Nb, C, H, H, 3, 3, 1, (1, 1, 1, 1), 16), 100)
             byts = 4.0 * (2 * n_act + 9 * C)
-            rows.append({"layer": "dw3x3", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
-                         "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
-                         "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": sets,
-                         "us_cache_warm": round(twarm * 1e6, 2), "gbs_cache_warm": round(byts / twarm / 1e9, 1)})
+            row = {"layer": "dw3x3", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                   "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
+                   "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": sets,
+                   "us_cache_warm": round(twarm * 1e6, 2), "gbs_cache_warm": round(byts / twarm / 1e9, 1)}
+            if cpu:
+                from oracle import oracle as O
+                xo, wo = WL.uniform_pm1(rng, (ORACLE_N, C, H, H)), WL.uniform_pm1(rng, (C, 1, 3, 3))
+                oracle_beside(row, lambda: O.dwconv2d(xo, wo, 1, (1, 1, 1, 1)))
+            rows.append(row)
         del ins, outs
     C, H = WL.sweep_shapes()["pool_relu"]
     n_act = Nb * C * H * H
@@ -443,26 +495,61 @@ def sweep(S, WL, torch, np, dev, timed, only=None):
     sets = 2
     ins = [rand(n_act) for _ in range(sets)]
     outs = [torch.empty(n_act, device=dev, dtype=torch.float32) for _ in range(sets)]
-    if not (want("relu") or want("maxpool3x3s2") or want("pack")):
+    if not (want("relu") or want("maxpool3x3s2") or want("pack") or want("table2")):
         return rows
+    if cpu:
+        from oracle import oracle as O
+        xo = WL.uniform_pm1(rng, (ORACLE_N, C, H, H))
     fn = lambda r: S.small_relu(ins[r % sets], outs[r % sets], n_act)
     tmin, tmed = best_of(fn, 50)
-    rows.append({"layer": "relu", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
-                 "us_median": round(tmed * 1e6, 2), "gbs": round(8.0 * n_act / tmin / 1e9, 1),
-                 "frac": round(8.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": sets})
+    rows.append(oracle_beside({"layer": "relu", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                               "us_median": round(tmed * 1e6, 2), "gbs": round(8.0 * n_act / tmin / 1e9, 1),
+                               "frac": round(8.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": sets}, lambda: O.relu(xo)))
     ins.append(rand(n_act))
     fn = lambda r: S.small_pool2d(ins[r % 3], outs[r % sets], Nb, C, H, H, 3, 3, 2, (0, 0, 0, 0), 16, S.POOL_MAX)
     tmin, tmed = best_of(fn, 50)
     byts = 4.0 * (n_act + n_pool)
-    rows.append({"layer": "maxpool3x3s2", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
-                 "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
-                 "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": 3})
+    rows.append(oracle_beside({"layer": "maxpool3x3s2", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                               "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
+                               "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": 3}, lambda: O.pool2d(xo, (3, 3), 2)))
     # pack / unpack of the largest activation (network boundary only)
     fn = lambda r: S.small_pack(ins[r % 3], outs[r % sets], Nb, C, H, H, 16)
     tmin, tmed = best_of(fn, 30)
-    rows.append({"layer": "pack", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
-                 "us_median": round(tmed * 1e6, 2), "gbs": round(8.0 * n_act / tmin / 1e9, 1),
-                 "frac": round(8.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": 3})
+    rows.append(oracle_beside({"layer": "pack", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                               "us_median": round(tmed * 1e6, 2), "gbs": round(8.0 * n_act / tmin / 1e9, 1),
+                               "frac": round(8.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": 3}, lambda: O.pack(xo, 16)))
+    # ---- the remaining layers of Table 2 at the same size: batch normalization (one FMA per element, HBM-bound),
+    # nearest-neighbour upsampling by 2 x 2 (input N64 C256 28x28), group convolution (8 groups of 32 channels, 3x3)
+    scale, shift = rand(C) + 1.5, rand(C)
+    fn = lambda r: S.small_batchnorm(ins[r % 3], scale, shift, outs[r % sets], Nb, C, H, H, 16)
+    tmin, tmed = best_of(fn, 50)
+    rows.append(oracle_beside({"layer": "batchnorm", "shape": "N64 C%d %dx%d" % (C, H, H), "us": round(tmin * 1e6, 2),
+                               "us_median": round(tmed * 1e6, 2), "gbs": round(8.0 * n_act / tmin / 1e9, 1),
+                               "frac": round(8.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": 3},
+                              lambda: O.batchnorm(xo, np.full(C, 1.5, np.float32), np.zeros(C, np.float32))))
+    Hu = H // 2
+    n_small = Nb * C * Hu * Hu
+    fn = lambda r: S.small_upsample(ins[r % 3][:n_small], outs[r % sets], Nb, C, Hu, Hu, 2, 2, 16)
+    tmin, tmed = best_of(fn, 50)
+    byts = 4.0 * (n_small + n_act)
+    rows.append(oracle_beside({"layer": "upsample2x2", "shape": "N64 C%d %dx%d" % (C, Hu, Hu), "us": round(tmin * 1e6, 2),
+                               "us_median": round(tmed * 1e6, 2), "gbs": round(byts / tmin / 1e9, 1),
+                               "frac": round(byts / tmin / PEAK_HBM, 4), "buffer_sets": 3},
+                              lambda: O.upsample(xo[:, :, :Hu, :Hu], 2, 2)))
+    Hg, FC = 28, 32
+    n_g = Nb * C * Hg * Hg
+    wg = rand(C * FC * 9)
+    fn = lambda r: S.small_group_conv2d(ins[r % 3][:n_g], wg, outs[r % sets][:n_g], Nb, C, FC, FC, FC, Hg, Hg, 3, 3, 1, (1, 1, 1, 1), 16, 16, 16)
+    tmin, tmed = best_of(fn, 30)
+    flops = 2.0 * Nb * C * Hg * Hg * FC * 9
+    row = {"layer": "groupconv3x3", "shape": "N64 C%d %dx%d, %d groups of %d" % (C, Hg, Hg, C // FC, FC), "us": round(tmin * 1e6, 2),
+           "us_median": round(tmed * 1e6, 2), "tflops": round(flops / tmin / 1e12, 2), "frac": round(flops / tmin / PEAK_MFMA_F32, 4),
+           "gbs": round(4.0 * (2 * n_g + C * FC * 9) / tmin / 1e9, 1), "kernel": S.small_group_conv2d_kernel(C, FC, FC, FC, 3, 3, 16, 16, 16)
+           if hasattr(S, "small_group_conv2d_kernel") else "group_conv_direct"}
+    if cpu:
+        wo = WL.uniform_pm1(rng, (C, FC, 3, 3))
+        oracle_beside(row, lambda: O.group_conv2d(xo[:, :, :Hg, :Hg], wo, FC, FC, FC, 1, (1, 1, 1, 1)))
+    rows.append(row)
     return rows
 
 
