@@ -114,7 +114,7 @@ int small_add(const float *a, const float *b, float *out, size_t n_elems, void *
 int small_dense(const float *in, const float *filt, float *out, int N, int Ci, int Co, int Cib, int Cob,
                 void *stream);
 
-/* ---- the remaining layers of Table 2. They are not part of small_network_run's layer table.
+/* ---- the remaining layers of Table 2 (also ops of small_network_run's layer table, see below).
  * small_batchnorm: batch normalization as the single-element FMA of Table 2, statistics folded by the
  *   caller: out[n,c,h,w] = in[n,c,h,w] * scale[c] + shift[c] (one fused multiply-add). scale, shift: C floats
  *   in plain channel order. out may equal in exactly (in place).
@@ -181,9 +181,16 @@ int small_relu_u8(const unsigned char *in, unsigned char *out, size_t n_elems, i
  * sized for the largest tensor any layer writes to it.
  * For op RELU / ADD / MAXPOOL / AVGPOOL, Ci is the channel count and Co must equal Ci.
  * For ADD, src2 is the second operand. For DENSE, kh/kw must equal the input H/W.
- * filt is the layer's blocked device filter (NULL for layers without weights). */
+ * filt is the layer's blocked device filter (NULL for layers without weights).
+ * The remaining rows of Table 2 as ops:
+ *   SMALL_OP_BATCHNORM  y = x * scale[c] + shift[c]; Co = Ci, Cob = Cib; filt: 2 * Ci floats, scale[0 .. Ci) then
+ *                       shift[0 .. Ci), plain channel order; dst may equal src (in place).
+ *   SMALL_OP_UPSAMPLE   nearest neighbour by the integer factors kh (rows) and kw (columns); Co = Ci, Cob = Cib.
+ *   SMALL_OP_GROUPCONV  small_group_conv2d: Ci, Co all input / output channels, F_C, S_C the group's window and stride
+ *                       over the channels, K = Co / ((Ci - F_C) / S_C + 1) filters per group; the filter's channel
+ *                       block F_Cb is min(16, F_C) and must divide F_C. F_C and S_C are ignored by every other op. */
 enum { SMALL_OP_CONV = 0, SMALL_OP_DWCONV = 1, SMALL_OP_MAXPOOL = 2, SMALL_OP_AVGPOOL = 3, SMALL_OP_RELU = 4,
-       SMALL_OP_ADD = 5, SMALL_OP_DENSE = 6 };
+       SMALL_OP_ADD = 5, SMALL_OP_DENSE = 6, SMALL_OP_BATCHNORM = 7, SMALL_OP_UPSAMPLE = 8, SMALL_OP_GROUPCONV = 9 };
 enum { SMALL_BUF_IN = -1, SMALL_BUF_OUT = -2, SMALL_MAX_SLOTS = 8 };
 
 typedef struct {
@@ -193,6 +200,7 @@ typedef struct {
     int Cib, Cob;
     int src, src2, dst;
     const float *filt;
+    int F_C, S_C;
 } small_layer;
 
 /* Bytes of workspace small_network_run needs for this table and input shape (host only, enqueues nothing).
@@ -256,6 +264,12 @@ int small_network_launches_at(const small_layer *layers, int n_layers, int N, in
  * convolution or depthwise convolution, and an addition of the convolution's output to another buffer
  * (residual connection), optionally followed by an in-place ReLU. Results are bit-identical to the
  * unfused sequence and every buffer that is read later holds what the table says.
+ * An in-place batch normalization directly after a convolution or fully connected layer (before the addition and the
+ * ReLU, the order of a residual block: conv, norm, add, ReLU) is folded the same way -- one fused multiply-add per
+ * element in the store phase, the same operation the separate layer performs -- where the convolution's kernel has
+ * that epilogue (16-channel blocks, 16-byte aligned parameters); elsewhere the runner launches the convolution and
+ * then the normalization (with the ReLU, if one follows) over its result. A ReLU in place after a batch
+ * normalization that stands alone runs in the normalization's kernel.
  * A depthwise 3x3 convolution (16-channel blocks, stride 1 or 2, optional in-place ReLU) whose output is read
  * only by an unpadded stride-1 1x1 convolution (optional in-place ReLU) runs with it in one kernel: the
  * depthwise result stays on the compute unit and its buffer is never written (allowed only when no later

@@ -237,6 +237,13 @@ def run_network(net, x, ws, return_all=False):
             y = add(a, bufs[L.src2])
         elif L.op == "dense":
             y = dense(a, ws[L.w])
+        elif L.op == "bn":
+            y = batchnorm(a, ws[L.w][0], ws[L.w][1])
+        elif L.op == "upsample":
+            y = upsample(a, L.kh, L.kw)
+        elif L.op == "gconv":
+            G = (L.Ci - L.F_C) // L.S_C + 1
+            y = group_conv2d(a, ws[L.w], L.F_C, L.S_C, L.Co // G, L.stride, L.pad)
         else:
             raise ValueError(L.op)
         bufs[L.dst] = y

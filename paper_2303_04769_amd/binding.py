@@ -14,10 +14,10 @@ LIB_PATH = os.path.join(_HERE, "libsmall_hip.so")
 
 OK = 0
 POOL_MAX, POOL_AVG = 0, 1
-OP_CONV, OP_DWCONV, OP_MAXPOOL, OP_AVGPOOL, OP_RELU, OP_ADD, OP_DENSE = range(7)
+OP_CONV, OP_DWCONV, OP_MAXPOOL, OP_AVGPOOL, OP_RELU, OP_ADD, OP_DENSE, OP_BATCHNORM, OP_UPSAMPLE, OP_GROUPCONV = range(10)
 BUF_IN, BUF_OUT, MAX_SLOTS = -1, -2, 8
 _OPS = {"conv": OP_CONV, "dw": OP_DWCONV, "maxpool": OP_MAXPOOL, "avgpool": OP_AVGPOOL, "relu": OP_RELU,
-        "add": OP_ADD, "dense": OP_DENSE}
+        "add": OP_ADD, "dense": OP_DENSE, "bn": OP_BATCHNORM, "upsample": OP_UPSAMPLE, "gconv": OP_GROUPCONV}
 
 EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "small_pack_filter",
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
@@ -46,7 +46,8 @@ class small_quant(C.Structure):
 class small_layer(C.Structure):
     _fields_ = [("op", C.c_int), ("Ci", C.c_int), ("Co", C.c_int), ("kh", C.c_int), ("kw", C.c_int),
                 ("stride", C.c_int), ("pad", small_pad), ("Cib", C.c_int), ("Cob", C.c_int),
-                ("src", C.c_int), ("src2", C.c_int), ("dst", C.c_int), ("filt", C.c_void_p)]
+                ("src", C.c_int), ("src2", C.c_int), ("dst", C.c_int), ("filt", C.c_void_p),
+                ("F_C", C.c_int), ("S_C", C.c_int)]
 
 
 _lib = None
@@ -290,12 +291,14 @@ def small_relu_u8(inp, out, n, z, stream=None):
 
 def make_layer_table(layers, filters):
     """ctypes array of small_layer from records with fields op, Ci, Co, kh, kw, stride, pad,
-    Cib, Cob, src, src2, dst, w (index into `filters`, the blocked device filters, or None)."""
+    Cib, Cob, src, src2, dst, w (index into `filters`, the blocked device filters, or None), and for
+    group convolutions F_C, S_C."""
     arr = (small_layer * len(layers))()
     for k, L in enumerate(layers):
         f = filters[L.w] if L.w is not None else None
         arr[k] = small_layer(_OPS[L.op], L.Ci, L.Co, L.kh, L.kw, L.stride, _pad(L.pad), L.Cib, L.Cob,
-                             L.src, L.src2, L.dst, f.data_ptr() if f is not None else None)
+                             L.src, L.src2, L.dst, f.data_ptr() if f is not None else None,
+                             getattr(L, "F_C", 0), getattr(L, "S_C", 0))
     return arr
 
 
@@ -373,6 +376,10 @@ class PackedNetwork:
             dst = torch.empty(src.numel(), dtype=torch.float32, device=self.device)
             if L.op == "dw":
                 small_pack_dw_filter(src, dst, L.Ci, L.kh, L.kw, L.Cib)
+            elif L.op == "bn":                   # [2][C]: scale, then shift, as they are
+                dst.copy_(src.reshape(-1))
+            elif L.op == "gconv":                # [Co][F_C][kh][kw] in the general layout with Ci = F_C
+                small_pack_filter(src, dst, L.Co, L.F_C, L.kh, L.kw, L.Cob, min(16, L.F_C))
             else:
                 small_pack_filter(src, dst, L.Co, L.Ci, L.kh, L.kw, L.Cob, L.Cib)
             self.filters.append(dst)

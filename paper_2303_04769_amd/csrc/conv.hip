@@ -530,6 +530,21 @@ const char *const kTileWaves[] = {"2,2,4,4", "1,4,4,2", "2,2,4,2", "2,2,2,2", "4
 
 }  // namespace
 
+int group_conv_same_tile(const LayerGeom &g, int F_C, int S_C, int K)
+{
+    if (g.Cib != 16 || g.Cob != 16 || F_C % 16 || S_C % 16 || K % 16 || F_C <= 0 || S_C <= 0 || K <= 0) return -1;
+    LayerGeom one = g;                   // one group as a convolution of its own: what the kernels must be able to take
+    one.Ci = F_C;
+    one.Co = K;
+    // (byte offsets are those of the whole tensors)
+    if (!conv_same_eligible(one) || !((size_t)g.N * g.Ci * g.H * g.W < ((size_t)1 << 30)) ||
+        !((size_t)g.N * g.Co * g.Ho * g.Wo < ((size_t)1 << 30)))
+        return -1;
+    // the tile's output channels must not straddle groups
+    if (g.kh == 1) return K % 64 == 0 ? SAME_32x64 : K % 32 == 0 ? SAME_32x32 : SAME_64x16;
+    return K % 32 == 0 ? SAME_64x32 : SAME_64x16;
+}
+
 const char *conv_kernel_name(const LayerGeom &g)
 {
     static thread_local char name[64];
@@ -559,9 +574,18 @@ bool conv_takes_plain_input(const LayerGeom &g, const void *in, const void *filt
     return aligned && first_mfma_steps(g) && use_small(g);
 }
 
-hipError_t launch_conv(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g, int epilogue,
-                       hipStream_t s, bool plain_input)
+bool conv_epilogue_takes_bn(const LayerGeom &g, const void *in, const void *filt, const void *out, const void *res,
+                            const void *bn)
 {
+    const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt | (uintptr_t)res | (uintptr_t)bn) & 15u) == 0);
+    return aligned && g.Cib == 16 && g.Cob == 16 && (conv_pw_eligible(g) || conv_same_eligible(g));
+}
+
+hipError_t launch_conv(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g, int epilogue,
+                       hipStream_t s, bool plain_input, const float *bn)
+{
+    if ((epilogue & EPI_BN) && !conv_epilogue_takes_bn(g, in, filt, out, (epilogue & EPI_ADD) ? res : out, bn))
+        return hipErrorInvalidValue;        // (the runner launches the normalization on its own in that case)
     ConvArgs a;
     a.in = in; a.filt = filt; a.out = out; a.res = (epilogue & EPI_ADD) ? res : out;
     a.N = g.N; a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo;
@@ -615,9 +639,9 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
         hipLaunchKernelGGL(conv_direct, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, g.Cib, g.Cob, total);
         return hipGetLastError();
     }
-    if (conv_pw_eligible(g)) return launch_conv_pw(in, filt, out, a.res, g, epilogue, s);
+    if (conv_pw_eligible(g)) return launch_conv_pw(in, filt, out, a.res, g, epilogue, s, bn);
     const int tile = pick_tile(g);
-    if (conv_same_eligible(g)) return launch_conv_same(in, filt, out, a.res, g, tile, epilogue, s);
+    if (conv_same_eligible(g)) return launch_conv_same(in, filt, out, a.res, g, tile, epilogue, s, 0, 0, 0, bn);
     switch (tile) {
         case SAME_128x128: launch_mfma<2, 2, 4, 4>(a, s); break;
         case SAME_64x128: launch_mfma<1, 4, 4, 2>(a, s); break;

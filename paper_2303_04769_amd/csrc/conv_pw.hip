@@ -39,6 +39,7 @@ struct PwArgs {
     const float *filt;
     float *out;
     const float *res;
+    const float *bn;          // EPI_BN: scale[0 .. Co) then shift[0 .. Co)
     int M, HW;                // pixels over all images, pixels per image
     int n_groups;             // ceil(M / 16)
     int epilogue;
@@ -140,6 +141,7 @@ __global__ void __launch_bounds__(64 * kPwMaxWaves) pw16_stream(PwArgs a)
     }
     const float *a_lds = lds_f + (size_t)part * COW * NCIB * 256 + lane;
 
+    using std::integral_constant;
     // acc[0 .. NJ) = filter blocks (NJ blocks from slab row fa_base, or the register copy) x the operands of `stage`
     auto reduce = [&](int stage, floatx4 *acc, auto nj, auto from_regs, const float *fa_base) __attribute__((always_inline)) {
         constexpr int NJ = decltype(nj)::value;
@@ -170,20 +172,42 @@ __global__ void __launch_bounds__(64 * kPwMaxWaves) pw16_stream(PwArgs a)
             }
         }
     };
-    auto finish = [&](floatx4 v, const char *res_p) __attribute__((always_inline)) -> floatx4 {
+    // a folded batch normalization: the parameters of this lane's four channels of output block cob
+    const bool norm = (a.epilogue & EPI_BN) != 0;            // uniform
+    auto bn_of = [&](int cob, floatx4 &sc, floatx4 &sh) __attribute__((always_inline)) {
+        const float *bn_c = a.bn + cob * 16 + lq * 4;
+        sc = *reinterpret_cast<const floatx4 *>(bn_c);
+        sh = *reinterpret_cast<const floatx4 *>(bn_c + NCOB * 16);
+    };
+    floatx4 bn_sc[COW], bn_sh[COW];                          // of the tasks' output blocks, loaded once
+#pragma unroll
+    for (int j = 0; j < COW; ++j) {
+        bn_sc[j] = bn_sh[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (norm) bn_of(part * COW + j, bn_sc[j], bn_sh[j]);
+    }
+    auto finish = [&](floatx4 v, const char *res_p, floatx4 sc, floatx4 sh) __attribute__((always_inline)) -> floatx4 {
+        if (norm) {
+            v.x = fmaf(v.x, sc.x, sh.x); v.y = fmaf(v.y, sc.y, sh.y); v.z = fmaf(v.z, sc.z, sh.z); v.w = fmaf(v.w, sc.w, sh.w);
+        }
         if constexpr (ADD) v += *reinterpret_cast<const floatx4 *>(res_p);
         v.x = (relu && !(v.x > 0.f)) ? 0.f : v.x; v.y = (relu && !(v.y > 0.f)) ? 0.f : v.y;
         v.z = (relu && !(v.z > 0.f)) ? 0.f : v.z; v.w = (relu && !(v.w > 0.f)) ? 0.f : v.w;
         return v;
     };
-    // stores NJ consecutive output blocks from block `cob` on
-    auto store = [&](int grp, int cob, const floatx4 *acc, auto nj) __attribute__((always_inline)) {
+    // stores NJ consecutive output blocks from block `cob` on (sc, sh: their normalization parameters)
+    auto store = [&](int grp, int cob, const floatx4 *acc, auto nj, const floatx4 *sc, const floatx4 *sh) __attribute__((always_inline)) {
         const unsigned o_off = pixel_byte(grp, lp, NCOB) + (unsigned)lq * 16u;
 #pragma unroll
         for (int j = 0; j < decltype(nj)::value; ++j) {
             const size_t cb = (size_t)(cob + j) * plane + o_off;
-            __builtin_nontemporal_store(finish(acc[j], res_c + cb), reinterpret_cast<floatx4 *>(out_c + cb));
+            __builtin_nontemporal_store(finish(acc[j], res_c + cb, sc[j], sh[j]), reinterpret_cast<floatx4 *>(out_c + cb));
         }
+    };
+    // (a unit's output block changes from unit to unit: its parameters are loaded when it is stored)
+    auto store_unit = [&](int grp, int cob, const floatx4 *acc) __attribute__((always_inline)) {
+        floatx4 sc[1] = {floatx4{0.f, 0.f, 0.f, 0.f}}, sh[1] = {floatx4{0.f, 0.f, 0.f, 0.f}};
+        if (norm) bn_of(cob, sc[0], sh[0]);
+        store(grp, cob, acc, integral_constant<int, 1>{}, sc, sh);
     };
 
     // Item i works on stage i % (DEPTH + 1) and refills stage (i + DEPTH) % (DEPTH + 1), which item i - 1 has read
@@ -192,7 +216,6 @@ __global__ void __launch_bounds__(64 * kPwMaxWaves) pw16_stream(PwArgs a)
     // pixels again, unused) and the stores of the items before it that were issued since -- DEPTH * COW between tasks
     // in the steady state, fewer for the wave's first tasks (they stand outside the loop) and for units (one store
     // each: their waits count the requests only, which also waits for older stores; harmless in a tail).
-    using std::integral_constant;
     int i = 0, st = 0;                                      // item, its stage
     auto task = [&](int stage, auto newer) __attribute__((always_inline)) {
         const int sn = stage + DEPTH >= DEPTH + 1 ? stage - 1 : stage + DEPTH;
@@ -200,7 +223,7 @@ __global__ void __launch_bounds__(64 * kPwMaxWaves) pw16_stream(PwArgs a)
         wait_vmcnt<decltype(newer)::value>();
         floatx4 acc[COW];
         reduce(stage, acc, integral_constant<int, COW>{}, integral_constant<bool, AREG>{}, a_lds);
-        store(g0 + i * gstride, part * COW, acc, integral_constant<int, COW>{});
+        store(g0 + i * gstride, part * COW, acc, integral_constant<int, COW>{}, bn_sc, bn_sh);
         ++i;
     };
     static_assert(DEPTH >= 1 && DEPTH <= 3, "one to three items ahead");
@@ -221,7 +244,7 @@ __global__ void __launch_bounds__(64 * kPwMaxWaves) pw16_stream(PwArgs a)
         const int u = gw + (i - rounds) * n_all, cob = u % NCOB;
         floatx4 acc[1];
         reduce(st, acc, integral_constant<int, 1>{}, integral_constant<bool, false>{}, lds_f + (size_t)cob * NCIB * 256 + lane);
-        store(tail0 + u / NCOB, cob, acc, integral_constant<int, 1>{});
+        store_unit(tail0 + u / NCOB, cob, acc);
         ++i;
         st = st == DEPTH ? 0 : st + 1;
     }
@@ -234,7 +257,7 @@ __global__ void __launch_bounds__(64 * kPwMaxWaves) pw16_stream(PwArgs a)
         wait_vmcnt<0>();
         floatx4 acc[1];
         reduce(0, acc, integral_constant<int, 1>{}, integral_constant<bool, false>{}, lds_f + (size_t)cob * NCIB * 256 + lane);
-        if (n_full * 16 + lp < a.M) store(n_full, cob, acc, integral_constant<int, 1>{});
+        if (n_full * 16 + lp < a.M) store_unit(n_full, cob, acc);
     }
 }
 
@@ -281,10 +304,11 @@ const char *conv_pw_kernel_name(const LayerGeom &g)
 }
 
 hipError_t launch_conv_pw(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
-                          int epilogue, hipStream_t s)
+                          int epilogue, hipStream_t s, const float *bn)
 {
     PwArgs a;
     a.in = in; a.filt = filt; a.out = out; a.res = (epilogue & EPI_ADD) ? res : out;
+    a.bn = (epilogue & EPI_BN) ? bn : filt;
     a.HW = g.H * g.W;
     a.M = g.N * a.HW;
     a.n_groups = (a.M + 15) / 16;

@@ -44,9 +44,14 @@ struct SameArgs {
     const float *filt;
     float *out;
     const float *res;
+    const float *bn;            // EPI_BN: scale[0 .. Co) then shift[0 .. Co)
     int N, H, W, HW;            // input image
     int Ho, Wo, HWo, stride;    // output image
-    int nCib, nCob;
+    int nCib, nCob;             // input blocks of a reduction, output blocks of the tensor
+    // group convolution (partial-channel reduction): output blocks [j * gk, (j + 1) * gk) reduce the nCib input blocks
+    // from block j * gs on; in_blocks: channel blocks of an input image in memory. A plain convolution is one group:
+    // gk = nCob, gs = 0, in_blocks = nCib.
+    int in_blocks, gk, gs;
     int kh, pt, pl;
     int M;          // N * Ho * Wo
     int n_mtiles, n_cotiles;
@@ -59,8 +64,13 @@ struct SameArgs {
     FastDiv dGP;    // division by n_groups * n_mtiles
 };
 
-__device__ __forceinline__ floatx4 epi4(floatx4 v, int epi, const float *res)
+// bn_c: scale of this lane's four channels; bn_c + Co floats: their shifts
+__device__ __forceinline__ floatx4 epi4(floatx4 v, int epi, const float *res, const float *bn_c = nullptr, int Co = 0)
 {
+    if (epi & EPI_BN) {
+        const floatx4 sc = *reinterpret_cast<const floatx4 *>(bn_c), sh = *reinterpret_cast<const floatx4 *>(bn_c + Co);
+        v.x = fmaf(v.x, sc.x, sh.x); v.y = fmaf(v.y, sc.y, sh.y); v.z = fmaf(v.z, sc.z, sh.z); v.w = fmaf(v.w, sc.w, sh.w);
+    }
     if (epi & EPI_ADD) v += *reinterpret_cast<const floatx4 *>(res);
     if (epi & EPI_RELU) {
         v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
@@ -115,6 +125,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
     else { co_tile = a.dMt.div((int)wg); m_tile = (int)wg - co_tile * a.n_mtiles; }
     const int m0 = m_tile * TM;
     const int cob0 = co_tile * NSUB;
+    const int cib0 = (cob0 / a.gk) * a.gs;                 // first input block of this tile's group
     const int lp = lane & 15, lq = lane >> 4;
 
     // Everything that depends on the lane is computed here, once: inside the reduction loop only
@@ -159,7 +170,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
 #pragma unroll
             for (int y = 0; y < KS; ++y) {
                 const int row = min(max(hb + y - a.pt, 0), a.H - 1);
-                d_voff[j][y] = (unsigned)((((n * a.nCib + dc) * a.H + row) * a.W + wb) * 16 + quad * 4) * 4u;
+                d_voff[j][y] = (unsigned)((((n * a.in_blocks + cib0 + dc) * a.H + row) * a.W + wb) * 16 + quad * 4) * 4u;
             }
             d_lds[j] = __builtin_amdgcn_readfirstlane((unsigned)((dc * ENTP + chunk * 16) * 64));
         } else {
@@ -307,11 +318,12 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_same(SameArgs a
         const int cob = cob0 + wave_n * WN + j;
         if (cob >= a.nCob) continue;
         const size_t cb = (size_t)cob * a.HWo * 64;
+        const float *bn_c = a.bn + cob * 16 + lq * 4;
 #pragma unroll
         for (int i = 0; i < WM; ++i) {
             if (!o_ok[i]) continue;
             *reinterpret_cast<floatx4 *>(out_c + cb + o_off[i]) =
-                epi4(acc[i][j], a.epilogue, reinterpret_cast<const float *>(res_c + cb + o_off[i]));
+                epi4(acc[i][j], a.epilogue, reinterpret_cast<const float *>(res_c + cb + o_off[i]), bn_c, a.nCob * 16);
         }
     }
 }
@@ -356,6 +368,7 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
     }
     const int m0 = m_tile * TM;            // first pixel of the tile inside its image
     const int cob0 = co_tile * NSUB;
+    const int cib0 = (cob0 / a.gk) * a.gs;                 // first input block of this tile's group
 
     // ---- load descriptors, relative to the start of an image (see conv16_same for the scheme)
     unsigned d_voff[LPS][KS];
@@ -441,14 +454,14 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
     char *out_c = reinterpret_cast<char *>(a.out);
     const char *res_c = reinterpret_cast<const char *>(a.res);
     const size_t planeA = (size_t)a.HW * 64 * NA;          // bytes between the inputs of consecutive steps' Ci blocks
-    const size_t imgA = (size_t)a.nCib * a.HW * 64;        // bytes of one input image
+    const size_t imgA = (size_t)a.in_blocks * a.HW * 64;   // bytes of one input image
     const size_t imgO = (size_t)a.nCob * a.HWo * 64;       // bytes of one output image
     constexpr size_t rowB = (size_t)KS * 1024;             // bytes between filter rows; a Ci block is KS rows
     int i_n = grp, i_step = 0;                             // i_n >= N: nothing left to load
     int ahead = 0;                                         // steps issued and not yet computed
     auto issue_bases = [&](const char *&baseA, const char *&baseB, int y) __attribute__((always_inline)) {
         const int cstep = i_step / KS;
-        baseA = in_c + (size_t)i_n * imgA + (size_t)cstep * planeA;
+        baseA = in_c + (size_t)i_n * imgA + (size_t)cib0 * a.HW * 64 + (size_t)cstep * planeA;
         baseB = filt_c + ((size_t)cstep * NA * KS + y) * rowB;
     };
     auto issue_done = [&]() __attribute__((always_inline)) {
@@ -537,11 +550,13 @@ __global__ void __launch_bounds__(64 * WAVES_M * WAVES_N) conv16_img(SameArgs a)
                     const int cob = cob0 + wave_n * WN + j;
                     if (cob < a.nCob) {
                         const size_t cb = (size_t)n * imgO + (size_t)cob * a.HWo * 64;
+                        const float *bn_c = a.bn + cob * 16 + lq * 4;
 #pragma unroll
                         for (int i = 0; i < WM; ++i) {
                             if (o_ok[i])
                                 *reinterpret_cast<floatx4 *>(out_c + cb + o_off[i]) =
-                                    epi4(acc[i][j], a.epilogue, reinterpret_cast<const float *>(res_c + cb + o_off[i]));
+                                    epi4(acc[i][j], a.epilogue, reinterpret_cast<const float *>(res_c + cb + o_off[i]), bn_c,
+                                         a.nCob * 16);
                         }
                     }
                 }
@@ -703,22 +718,30 @@ auto with_shape(const LayerGeom &g, int tile, Args &&...args)
 }  // namespace
 
 hipError_t launch_conv_same(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
-                            int tile, int epilogue, hipStream_t s)
+                            int tile, int epilogue, hipStream_t s, int F_C, int S_C, int K, const float *bn)
 {
     SameArgs a;
     a.in = in; a.filt = filt; a.out = out; a.res = (epilogue & EPI_ADD) ? res : out;
+    a.bn = (epilogue & EPI_BN) ? bn : filt;        // (a valid address when unused)
     a.N = g.N; a.H = g.H; a.W = g.W; a.HW = g.H * g.W;
     a.Ho = g.Ho; a.Wo = g.Wo; a.HWo = g.Ho * g.Wo; a.stride = g.stride;
     a.nCib = g.Ci / 16; a.nCob = g.Co / 16;
+    a.in_blocks = a.nCib; a.gk = a.nCob; a.gs = 0;
+    if (F_C) { a.nCib = F_C / 16; a.gk = K / 16; a.gs = S_C / 16; }
     a.kh = g.kh; a.pt = g.pt; a.pl = g.pl;
     a.M = g.N * a.HWo;
     a.n_mtiles = 0; a.n_cotiles = 0;
     // Consecutive workgroups run on one XCD and share its 4 MB L2: when the whole filter fits there, walk the
     // channel tiles of one pixel tile first (the input is then fetched from HBM once, not once per channel
     // tile); a larger filter is kept resident tile by tile instead.
-    a.co_fast = (size_t)g.Co * g.Ci * g.kh * g.kw * 4 <= (size_t)3 << 20;
+    a.co_fast = (size_t)g.Co * (F_C ? F_C : g.Ci) * g.kh * g.kw * 4 <= (size_t)3 << 20;
     a.epilogue = epilogue;
     a.n_groups = 1;
+    if (F_C) {
+        LayerGeom gg = g;
+        gg.Ci = F_C;                     // what the kernel variants are chosen by: the reduction of one group
+        return with_shape<LaunchTile>(gg, tile, a, s);
+    }
     return with_shape<LaunchTile>(g, tile, a, s);
 }
 

@@ -81,12 +81,15 @@ int plan_conv(ConvPlan &p, int N, int Ci, int Co, int H, int W, int kh, int kw, 
     return p.filt_elems ? SMALL_OK : SMALL_ERR_SHAPE;
 }
 
+// bn (EPI_BN): scale[0 .. Co) then shift[0 .. Co); the caller has made sure that the layer's kernel has that epilogue
+// (conv_epilogue_takes_bn).
 int run_conv(const float *in, const float *filt, float *out, const float *res, const ConvPlan &p, int epilogue,
-             hipStream_t s, bool plain_input = false)
+             hipStream_t s, bool plain_input = false, const float *bn = nullptr)
 {
     if (!in || !filt || !out) return SMALL_ERR_NULL;
+    if ((epilogue & EPI_BN) && !bn) return SMALL_ERR_NULL;
     if (overlap(in, p.in_elems, out, p.out_elems) || overlap(filt, p.filt_elems, out, p.out_elems)) return SMALL_ERR_ALIAS;
-    return from_hip(launch_conv(in, filt, out, res, p.g, epilogue, s, plain_input));
+    return from_hip(launch_conv(in, filt, out, res, p.g, epilogue, s, plain_input, bn));
 }
 
 }  // namespace
@@ -440,10 +443,11 @@ inline bool reads(const small_layer &l, int id) { return l.src == id || (l.op ==
 // The tensors between them are never written.
 // head: layer i is an average pooling whose output only the fully connected layer i + 1 reads; when the pooling
 // window turns out to be the whole image, both run in one kernel and the pooled tensor is never written.
+// bn > 0: layer i + bn is an in-place batch normalization of layer i's result, folded into its store phase (EPI_BN).
 struct Fusion {
     int epilogue; int out_id; int res_id; int skip; int pw; int pw_relu; int rename;
     int chain; int chain_idx[kChainMaxLayers]; int chain_relu[kChainMaxLayers];
-    int head;
+    int head; int bn;
 };
 
 bool pointwise(const small_layer &l)
@@ -524,6 +528,14 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
         }
         return f;
     }
+    if (c.op == SMALL_OP_BATCHNORM) {
+        // a ReLU in place on the normalized tensor runs in the normalization's kernel
+        if (i + 1 < nL && L[i + 1].op == SMALL_OP_RELU && L[i + 1].src == c.dst && L[i + 1].dst == c.dst) {
+            f.epilogue |= EPI_RELU;
+            f.skip = 1;
+        }
+        return f;
+    }
     if (!conv && c.op != SMALL_OP_DWCONV) return f;
     if (conv && allow_chain) {
         plan_chain(L, nL, i, f);
@@ -531,6 +543,16 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
     }
     int j = i + 1;
     const int D = c.dst;
+    // conv, norm (in place), [add], [ReLU]: the normalization becomes the first step of the store phase (where the
+    // layer's kernel turns out to have no such epilogue, the runner takes this fusion back and runs the layers as the
+    // table lists them)
+    if (conv && j < nL && L[j].op == SMALL_OP_BATCHNORM && L[j].src == D && L[j].dst == D && L[j].Ci == c.Co &&
+        L[j].Cib == c.Cob) {
+        f.epilogue |= EPI_BN;
+        f.bn = j - i;
+        f.skip = 1;
+        ++j;
+    }
     if (conv && j < nL && L[j].op == SMALL_OP_ADD && L[j].src != L[j].src2 && (L[j].src == D || L[j].src2 == D)) {
         const int E = L[j].src == D ? L[j].src2 : L[j].src, T = L[j].dst;
         bool ok = (T == D || T == E) && T != c.src;
@@ -544,7 +566,7 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
             f.epilogue |= EPI_ADD;
             f.out_id = T;
             f.res_id = E;
-            f.skip = 1;
+            ++f.skip;
             ++j;
         }
     }
@@ -633,7 +655,7 @@ int plan_resident_run(const small_layer *L, int nL, int i, const Shape *shp_now,
         ConvPlan p;
         if (plan_conv(p, 1, l.Ci, l.Co, a.H, a.W, l.kh, l.kw, l.stride, l.pad, l.Cib, l.Cob)) break;
         const Fusion fu = plan_fusion(L, nL, k, false);
-        if (fu.pw || fu.head || fu.chain) break;
+        if (fu.pw || fu.head || fu.chain || (fu.epilogue & EPI_BN)) break;
         // (the layers ahead have not been validated yet: ids taken from them are checked here)
         if (fu.out_id < SMALL_BUF_OUT || fu.out_id >= SMALL_MAX_SLOTS || fu.out_id == SMALL_BUF_IN ||
             fu.res_id < SMALL_BUF_OUT || fu.res_id >= SMALL_MAX_SLOTS)
@@ -787,6 +809,19 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.dst == l.src) return SMALL_ERR_ALIAS;
                 if (!l.filt) return SMALL_ERR_NULL;
                 o = Shape{l.Co, p.g.Ho, p.g.Wo, l.Cob, true};
+                if (head && (fu.epilogue & EPI_BN)) {
+                    // the normalization is folded only into kernels that have the epilogue (geometry; when running
+                    // also the pointers): otherwise this layer and the ones after it run as the table lists them
+                    const small_layer &b = L[i + fu.bn];
+                    bool ok = !fu.chain && !res_n && p.g.Cib == 16 && p.g.Cob == 16 && (conv_pw_eligible(p.g) || conv_same_eligible(p.g));
+                    if (ok && run)
+                        ok = b.filt && conv_epilogue_takes_bn(p.g, ptr(l.src), l.filt, ptr(fu.out_id),
+                                                              (fu.epilogue & EPI_ADD) ? ptr(fu.res_id) : ptr(fu.out_id), b.filt);
+                    if (!ok) {
+                        fu = Fusion{EPI_NONE, l.dst, l.dst, 0, 0, 0, 0};
+                        fused_away = 0;
+                    }
+                }
                 const bool plain = in_plain && i == 0 && !res_n;
                 if (plain) {
                     if (fu.chain) return SMALL_ERR_LAYER;        // a pointwise run does not start from a plain tensor
@@ -821,7 +856,8 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 } else if (launch && res_n) {
                     rc = from_hip(launch_resident(res_g, res_n, ptr(l.src), ptr(res_g[res_n - 1].dst), N, s));
                 } else if (launch) {
-                    rc = run_conv(ptr(l.src), l.filt, ptr(fu.out_id), ptr(fu.res_id), p, fu.epilogue, s, plain);
+                    rc = run_conv(ptr(l.src), l.filt, ptr(fu.out_id), ptr(fu.res_id), p, fu.epilogue, s, plain,
+                                  (fu.epilogue & EPI_BN) ? L[i + fu.bn].filt : nullptr);
                 }
                 break;
             }
@@ -882,6 +918,41 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.Co != l.Ci || l.Cob != l.Cib) return SMALL_ERR_LAYER;
                 if (launch) rc = from_hip(launch_relu(ptr(l.src), ptr(l.dst), in_elems, s));
                 break;
+            case SMALL_OP_BATCHNORM:
+                if (l.Co != l.Ci || l.Cob != l.Cib) return SMALL_ERR_LAYER;
+                if (!l.filt) return SMALL_ERR_NULL;
+                if ((size_t)a.H * a.W * a.Cb > kMaxElems) return SMALL_ERR_SHAPE;
+                if (launch)
+                    rc = from_hip(launch_batchnorm(ptr(l.src), l.filt, l.filt + l.Ci, ptr(l.dst), N, l.Ci, a.H, a.W, l.Cib, s,
+                                                   (fu.epilogue & EPI_RELU) != 0));
+                break;
+            case SMALL_OP_UPSAMPLE: {
+                if (l.Co != l.Ci || l.Cob != l.Cib || l.kh <= 0 || l.kw <= 0) return SMALL_ERR_LAYER;
+                if (l.dst == l.src) return SMALL_ERR_ALIAS;
+                if ((size_t)a.H * l.kh > kMaxElems || (size_t)a.W * l.kw > kMaxElems) return SMALL_ERR_SHAPE;
+                o = Shape{l.Ci, a.H * l.kh, a.W * l.kw, l.Cib, true};
+                if (!elems(N, o.C, o.H, o.W)) return SMALL_ERR_SHAPE;
+                if (launch) rc = from_hip(launch_upsample(ptr(l.src), ptr(l.dst), N, l.Ci, a.H, a.W, l.kh, l.kw, l.Cib, s));
+                break;
+            }
+            case SMALL_OP_GROUPCONV: {
+                if (l.F_C <= 0 || l.S_C <= 0 || l.F_C > l.Ci || (l.Ci - l.F_C) % l.S_C) return SMALL_ERR_LAYER;
+                const int groups = (l.Ci - l.F_C) / l.S_C + 1;
+                if (l.Co <= 0 || l.Co % groups) return SMALL_ERR_LAYER;
+                const int F_Cb = l.F_C < 16 ? l.F_C : 16;
+                if (l.F_C % F_Cb) return SMALL_ERR_LAYER;
+                LayerGeom g;
+                size_t ni, no;
+                rc = window_geom(g, N, l.Ci, l.Co, a.H, a.W, l.kh, l.kw, l.stride, l.pad, l.Cib, l.Cob, &ni, &no);
+                if (rc) return rc;
+                if (l.dst == l.src) return SMALL_ERR_ALIAS;
+                if (!l.filt) return SMALL_ERR_NULL;
+                if (!elems(l.Co, l.F_C, l.kh, l.kw)) return SMALL_ERR_SHAPE;
+                o = Shape{l.Co, g.Ho, g.Wo, l.Cob, true};
+                if (launch)
+                    rc = from_hip(launch_group_conv(ptr(l.src), l.filt, ptr(l.dst), g, l.F_C, l.S_C, l.Co / groups, F_Cb, s));
+                break;
+            }
             case SMALL_OP_ADD: {
                 if (l.Co != l.Ci || l.Cob != l.Cib || !valid_id(l.src2)) return SMALL_ERR_LAYER;
                 const Shape b = shp[idx(l.src2)];

@@ -77,7 +77,9 @@ __device__ __forceinline__ void wait_vmcnt()
 }
 
 // Epilogue fused into the convolution's STORE phase (the paper's "abstract fused layer" direction).
-enum : int { EPI_NONE = 0, EPI_RELU = 1, EPI_ADD = 2 };   // ADD: accumulate onto the tensor `res` (same layout as out)
+// ADD: accumulate onto the tensor `res` (same layout as out). BN: y = y * scale[c] + shift[c] first (batch normalization
+// folded behind the reduction; parameters: scale[0 .. C) then shift[0 .. C), 16-byte aligned). Order: BN, ADD, RELU.
+enum : int { EPI_NONE = 0, EPI_RELU = 1, EPI_ADD = 2, EPI_BN = 4 };
 
 hipError_t launch_relu(const float *in, float *out, size_t n, hipStream_t s);
 hipError_t launch_add(const float *a, const float *b, float *out, size_t n, hipStream_t s);
@@ -101,7 +103,11 @@ hipError_t launch_avgpool_dense(const float *in, const float *filt, float *out, 
 // res: tensor added to the result when epilogue has EPI_ADD (may be `out` itself: each lane reads the
 // elements it is about to write), else ignored.
 hipError_t launch_conv(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
-                       int epilogue, hipStream_t s, bool plain_input = false);
+                       int epilogue, hipStream_t s, bool plain_input = false, const float *bn = nullptr);
+// true when the kernel launch_conv picks for this layer applies EPI_BN itself; otherwise the caller launches the
+// normalization after the convolution
+bool conv_epilogue_takes_bn(const LayerGeom &g, const void *in, const void *filt, const void *out, const void *res,
+                            const void *bn);
 // plain_input: `in` is a plain [N][Ci][H][W] tensor instead of a blocked one. Only the first-layer matrix-core kernel
 // takes that (one input block of fewer than 16 channels, a reduction of 5..8, 25..28 or 37..40 values, at least
 // 16384 output pixels, 16-byte aligned pointers); conv_takes_plain_input tells, and launch_conv fails otherwise.
@@ -141,8 +147,15 @@ bool conv_same_eligible(const LayerGeom &g);     // stride 1, output size == inp
 int conv_same_planes(const LayerGeom &g);        // Ci blocks staged per reduction step (1x1 filters)
 // images each workgroup walks in the image-aligned persistent variant, 0 = flat variant (host arithmetic only)
 int conv_same_images_per_workgroup(const LayerGeom &g, int tile);
+// F_C > 0: a group convolution (partial-channel reduction) on the same kernels: g.Ci, g.Co are all input / output
+// channels, group j = output channels [j K, (j + 1) K) reduces input channels [j S_C, j S_C + F_C); F_C, S_C, K
+// multiples of 16 and the tile's output channels a divisor of K.
 hipError_t launch_conv_same(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
-                            int tile, int epilogue, hipStream_t s);
+                            int tile, int epilogue, hipStream_t s, int F_C = 0, int S_C = 0, int K = 0,
+                            const float *bn = nullptr);
+// tile (SAME_*) for a group convolution that launch_conv_same takes, or -1: geometry of conv_same_eligible, channel
+// counts as above
+int group_conv_same_tile(const LayerGeom &g, int F_C, int S_C, int K);
 
 // Pointwise (1x1, stride 1, unpadded) convolution with the filter resident on the compute unit and autonomous
 // waves that stream 16-pixel groups (conv_pw.hip): 64 -> 64 and 128 -> 128 channels, at least 32768 pixels, 16-byte
@@ -150,7 +163,7 @@ hipError_t launch_conv_same(const float *in, const float *filt, float *out, cons
 bool conv_pw_eligible(const LayerGeom &g);
 const char *conv_pw_kernel_name(const LayerGeom &g);
 hipError_t launch_conv_pw(const float *in, const float *filt, float *out, const float *res, const LayerGeom &g,
-                          int epilogue, hipStream_t s);
+                          int epilogue, hipStream_t s, const float *bn = nullptr);
 
 // Depthwise 3x3 (+ ReLU) followed by pointwise 1x1 (+ ReLU) in one launch, 16-channel blocks. dwpw_eligible looks
 // at what a layer table states (channels, blocks, windows, strides); dwpw_geom_ok at the image geometry.
@@ -174,7 +187,7 @@ hipError_t launch_dense_chain(const float *in, float *out, const ChainLayer *lay
 // Remaining Table 2 layers (table2.hip): y = x * scale[c] + shift[c]; nearest-neighbour upsampling by integer
 // factors; group convolution (geometry in g with g.Ci = all input channels, g.Co = G * K, g.Cib the activation block).
 hipError_t launch_batchnorm(const float *in, const float *scale, const float *shift, float *out, int N, int C, int H, int W,
-                            int Cb, hipStream_t s);
+                            int Cb, hipStream_t s, bool relu = false);
 hipError_t launch_upsample(const float *in, float *out, int N, int C, int H, int W, int fh, int fw, int Cb, hipStream_t s);
 hipError_t launch_group_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int F_C, int S_C, int K,
                              int F_Cb, hipStream_t s);

@@ -15,7 +15,7 @@ constexpr int kBlock = 256;
 template <int VEC>
 __global__ void __launch_bounds__(kBlock) batchnorm_kernel(const float *__restrict__ in, const float *__restrict__ scale,
                                                            const float *__restrict__ shift, float *__restrict__ out,
-                                                           size_t n_vec, int Cb, int nCb, FastDiv dPlane)
+                                                           size_t n_vec, int Cb, int nCb, FastDiv dPlane, int relu)
 {
     const size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
     if (v >= n_vec) return;
@@ -30,9 +30,14 @@ __global__ void __launch_bounds__(kBlock) batchnorm_kernel(const float *__restri
         floatx4 y;
         y.x = fmaf(x.x, scale[c + 0], shift[c + 0]); y.y = fmaf(x.y, scale[c + 1], shift[c + 1]);
         y.z = fmaf(x.z, scale[c + 2], shift[c + 2]); y.w = fmaf(x.w, scale[c + 3], shift[c + 3]);
+        if (relu) {
+            y.x = y.x > 0.f ? y.x : 0.f; y.y = y.y > 0.f ? y.y : 0.f;
+            y.z = y.z > 0.f ? y.z : 0.f; y.w = y.w > 0.f ? y.w : 0.f;
+        }
         *reinterpret_cast<floatx4 *>(out + e) = y;
     } else {
-        out[e] = fmaf(in[e], scale[c], shift[c]);
+        const float y = fmaf(in[e], scale[c], shift[c]);
+        out[e] = relu ? (y > 0.f ? y : 0.f) : y;
     }
 }
 
@@ -100,7 +105,7 @@ __global__ void __launch_bounds__(kBlock) group_conv_direct(GroupArgs a, size_t 
 }  // namespace
 
 hipError_t launch_batchnorm(const float *in, const float *scale, const float *shift, float *out, int N, int C, int H, int W,
-                            int Cb, hipStream_t s)
+                            int Cb, hipStream_t s, bool relu)
 {
     const size_t total = (size_t)N * C * H * W;
     const FastDiv plane = make_fastdiv(H * W * Cb);
@@ -108,10 +113,10 @@ hipError_t launch_batchnorm(const float *in, const float *scale, const float *sh
     if (vec) {
         const size_t n_vec = total / 4;
         hipLaunchKernelGGL((batchnorm_kernel<4>), dim3((unsigned)((n_vec + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, scale,
-                           shift, out, n_vec, Cb, C / Cb, plane);
+                           shift, out, n_vec, Cb, C / Cb, plane, relu ? 1 : 0);
     } else {
         hipLaunchKernelGGL((batchnorm_kernel<1>), dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, scale,
-                           shift, out, total, Cb, C / Cb, plane);
+                           shift, out, total, Cb, C / Cb, plane, relu ? 1 : 0);
     }
     return hipGetLastError();
 }
@@ -134,6 +139,11 @@ hipError_t launch_upsample(const float *in, float *out, int N, int C, int H, int
 hipError_t launch_group_conv(const float *in, const float *filt, float *out, const LayerGeom &g, int F_C, int S_C, int K,
                              int F_Cb, hipStream_t s)
 {
+    // channel counts in whole 16-blocks and a geometry the matrix-core convolution takes: the same kernels, every
+    // tile inside one group (Table 1 row "Partial Channel Reduction" on the full-reduction kernels)
+    const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 15u) == 0);
+    const int tile = aligned && F_Cb == 16 ? group_conv_same_tile(g, F_C, S_C, K) : -1;
+    if (tile >= 0) return launch_conv_same(in, filt, out, out, g, tile, EPI_NONE, s, F_C, S_C, K);
     GroupArgs a;
     a.in = in; a.filt = filt; a.out = out;
     a.N = g.N; a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo;

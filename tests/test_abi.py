@@ -232,3 +232,36 @@ def test_launch_list_applies_the_geometry_fallbacks_of_the_run(lib):
     t[0].src = 77
     n = C.c_int(0)
     assert lib.small_network_launches_at(t, len(t), 2, 16, 8, 8, 0, None, C.byref(n)) == 7
+
+
+def test_batch_normalization_folds_into_the_convolution_before_it(lib):
+    """conv, norm, [add], [ReLU]: one launch by the table; a run whose convolution kernel has no such epilogue (here: a
+    window of 5 x 5) lists the layers one by one. A normalization that stands alone takes the ReLU after it."""
+    from paper_2303_04769_amd import binding as B
+    from workloads.nets import Layer, IN, OUT
+    p1 = (1, 1, 1, 1)
+
+    def block(k, pad):
+        return [
+            Layer("conv", 32, 32, 10, 10, k, k, 1, pad, src=IN, dst=0, w=0),
+            Layer("bn", 32, 32, 10, 10, src=0, dst=0, w=1),
+            Layer("add", 32, 32, 10, 10, src=0, src2=IN, dst=0),
+            Layer("relu", 32, 32, 10, 10, src=0, dst=0),
+            Layer("bn", 32, 32, 10, 10, src=0, dst=1, w=1),
+            Layer("relu", 32, 32, 10, 10, src=1, dst=1),
+            Layer("upsample", 32, 32, 10, 10, 2, 2, src=1, dst=OUT),
+        ]
+    t3 = _table(block(3, p1), 2)
+    assert B.small_network_launches(t3) == [0, 4, 6]
+    assert B.small_network_launches_at(t3, 2, 32, 10, 10, B.SMALL_RUN_RESIDENT_OFF) == [0, 4, 6]
+    t5 = _table(block(5, (2, 2, 2, 2)), 2)
+    assert B.small_network_launches(t5) == [0, 4, 6]                      # the table alone cannot tell
+    assert B.small_network_launches_at(t5, 2, 32, 10, 10, 0) == [0, 1, 2, 3, 4, 6]
+    # workspace: the upsampled tensor goes to OUT, slots 0 and 1 hold 32 x 10 x 10
+    assert B.small_network_workspace(t3, 2, 32, 10, 10) == 2 * 2 * 32 * 100 * 4
+    # malformed: a group convolution whose groups do not tile the channels, an upsampling factor of zero
+    bad = _table([Layer("gconv", 32, 32, 10, 10, 3, 3, 1, p1, src=IN, dst=OUT, w=0, F_C=12, S_C=16)], 1)
+    assert lib.small_network_workspace(bad, 1, 1, 32, 10, 10, C.byref(C.c_size_t())) == 7
+    bad = _table([Layer("upsample", 32, 32, 10, 10, 2, 2, src=IN, dst=OUT)], 0)
+    bad[0].kw = 0
+    assert lib.small_network_workspace(bad, 1, 1, 32, 10, 10, C.byref(C.c_size_t())) == 7

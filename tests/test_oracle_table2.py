@@ -108,3 +108,30 @@ def test_upsample_is_element_repetition(fh, fw):
     assert np.array_equal(got, ref)
     # every fh x fw block of the output is constant and strided sampling gives the input back
     assert np.array_equal(got[:, :, ::fh, ::fw], x)
+
+
+def test_run_network_with_table2_ops_matches_a_library_composition():
+    """The oracle's network runner on a table with batch normalization, upsampling and a group convolution against
+    the same composition of a library's CPU ops in fp64."""
+    import torch
+    import torch.nn.functional as F
+    from workloads.nets import Layer, Network, IN, OUT
+    from oracle import oracle as O
+    net = Network("table2_probe", 8, 6, 5)
+    net.layers = [
+        Layer("bn", 8, 8, 6, 5, src=IN, dst=0, w=0),
+        Layer("relu", 8, 8, 6, 5, src=0, dst=0),
+        Layer("upsample", 8, 8, 6, 5, 2, 3, src=0, dst=1),
+        Layer("gconv", 8, 6, 12, 15, 3, 3, 2, (1, 0, 1, 1), src=1, dst=OUT, w=1, F_C=4, S_C=4, Cob=6),
+    ]
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((2, 8, 6, 5)).astype(np.float32)
+    bn = np.stack([rng.random(8) + 0.5, rng.standard_normal(8)]).astype(np.float32)
+    w = rng.standard_normal((6, 4, 3, 3)).astype(np.float32)
+    got = O.run_network(net, x, [bn, w])
+    t = torch.from_numpy(x).double() * torch.from_numpy(bn[0]).double().view(1, 8, 1, 1) + torch.from_numpy(bn[1]).double().view(1, 8, 1, 1)
+    t = t.float().double().clamp_min(0)                       # every layer's result is rounded to fp32
+    t = F.interpolate(t, scale_factor=(2, 3), mode="nearest")
+    t = F.conv2d(F.pad(t, (1, 1, 1, 0)), torch.from_numpy(w).double(), stride=2, groups=2)
+    assert got.shape == tuple(t.shape) == (2, 6, 6, 8)
+    assert np.allclose(got, t.numpy(), rtol=0, atol=1e-5)

@@ -34,7 +34,7 @@ def same_pad(i: int, k: int, s: int) -> Tuple[int, int]:
 
 @dataclass
 class Layer:
-    op: str                      # conv | dw | maxpool | avgpool | relu | add | dense
+    op: str                      # conv | dw | maxpool | avgpool | relu | add | dense | bn | upsample | gconv
     Ci: int
     Co: int
     H: int                       # input height / width seen by this layer
@@ -51,10 +51,14 @@ class Layer:
     w: Optional[int] = None      # index into the network's weight list
     Ho: int = 0
     Wo: int = 0
+    F_C: int = 0                 # gconv: channels of a group's window and its stride over the channels
+    S_C: int = 0                 # (upsample: kh, kw are the factors; bn: w -> [2][C] scale, shift)
 
     def __post_init__(self):
         self.Cib = self.Cib or block_of(self.Ci)
         self.Cob = self.Cob or block_of(self.Co)
+        if self.op == "upsample" and not self.Ho:
+            self.Ho, self.Wo = self.H * self.kh, self.W * self.kw
         if not self.Ho:
             t, b, l, r = self.pad
             self.Ho = (self.H + t + b - self.kh) // self.stride + 1
