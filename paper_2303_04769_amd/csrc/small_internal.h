@@ -93,6 +93,10 @@ hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode
 // depthwise 3x3, 16-channel blocks, input rows staged by the load unit (window_rows.hip); pointers 16-byte aligned
 bool dw_rows_eligible(const LayerGeom &g);
 hipError_t launch_dw_rows(const float *in, const float *filt, float *out, const LayerGeom &g, int relu, hipStream_t s);
+// depthwise 3x3, stride 1, padding 1, 16-channel blocks: rows through registers, neighbours by lane shifts
+// (window_dpp.hip); pointers 16-byte aligned
+bool dw_dpp_eligible(const LayerGeom &g);
+hipError_t launch_dw_dpp(const float *in, const float *filt, float *out, const LayerGeom &g, int relu, hipStream_t s);
 
 // Global average pooling + fully connected layer in one launch (network heads): in [N][C/16][HW][16] (16-byte
 // aligned), filt [Co/Cob][C/16][1][1][16][Cob], out [N][Co]; C <= 256, Co <= 16.

@@ -308,6 +308,8 @@ hipError_t launch_window(const float *in, const float *filt, float *out, const L
 hipError_t launch_dwconv(const float *in, const float *filt, float *out, const LayerGeom &g, int epilogue, hipStream_t s)
 {
     const bool aligned = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 15u) == 0);
+    if (aligned && (epilogue & ~EPI_RELU) == 0 && dw_dpp_eligible(g))
+        return launch_dw_dpp(in, filt, out, g, (epilogue & EPI_RELU) != 0, s);
     if (aligned && (epilogue & ~EPI_RELU) == 0 && dw_rows_eligible(g))
         return launch_dw_rows(in, filt, out, g, (epilogue & EPI_RELU) != 0, s);
     return launch_window<OP_DW>(in, filt, out, g, epilogue, s);

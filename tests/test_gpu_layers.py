@@ -274,6 +274,40 @@ def test_dwconv2d_large(case):
     assert_close(O.unpack(g.check(), ref.shape, 16), ref, 9, f"dw large {case}")
 
 
+DW_LANES_CASES = [  # N, C, H, W: 3x3, stride 1, padding 1, 16-channel blocks
+    (6, 64, 56, 56),           # four bands of 14 columns; the planes cut into row strips
+    (20, 128, 28, 28),         # two bands
+    (70, 256, 14, 14),         # one band: lanes 0 and 15 of a row of lanes stay zero
+    (300, 512, 7, 7),          # two planes side by side in the 16 lanes
+    (3, 16, 5, 5),             # ... an odd number of planes: the last pair has one
+    (5, 48, 7, 3),             # ... narrow
+    (1, 16, 1, 1),             # one pixel
+    (2, 32, 1, 40),            # one row: every output touches the top and the bottom edge; three bands (14, 14, 12)
+    (9, 48, 61, 63),           # three channel blocks, five bands (the last of 7 columns), strips of unequal height
+    (70, 32, 33, 17),          # two bands, three columns in the second
+    (12, 32, 52, 15),          # 15 columns: one more than a band
+    (5, 32, 70, 100),          # eight bands, the last of two columns
+    (600, 16, 2, 64),          # two rows
+    (400, 16, 33, 8),          # eight columns: one plane per row of lanes again
+    (64, 64, 56, 56),          # the benchmark row
+]
+
+
+@pytest.mark.parametrize("case", DW_LANES_CASES)
+def test_dwconv2d_lane_shift(case):
+    """Depthwise 3x3 layers with stride 1 and padding 1 run with the rows in registers and the horizontal neighbours
+    taken from the next lanes: bands and their halo lanes, plane pairs, row strips, both image edges, ragged rows.
+    The filters are random, so a shift in the wrong direction or a swapped row shows."""
+    N, C, H, W = case
+    rng = np.random.default_rng(7300 + N + C)
+    x = (rng.random((N, C, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    w = (rng.random((C, 1, 3, 3), dtype=np.float32) * 2 - 1).astype(np.float32)
+    ref = O.dwconv2d(x, w, 1, (1, 1, 1, 1))
+    g = Guarded(ref.size)
+    S.small_dwconv2d(dev(O.pack(x, 16)), dev(O.pack_dw_filter(w, 16)), g.t, N, C, H, W, 3, 3, 1, (1, 1, 1, 1), 16)
+    assert_close(O.unpack(g.check(), ref.shape, 16), ref, 9, f"dw lanes {case}")
+
+
 POOL_CASES = [  # N, C, H, W, kh, kw, stride, pad
     (2, 32, 13, 11, 3, 3, 2, (0, 0, 0, 0)),
     (1, 16, 56, 56, 3, 3, 2, (0, 0, 0, 0)),
