@@ -28,6 +28,19 @@ class Quant:
     hi: int = 255
 
 
+@dataclass
+class QuantAdd:
+    """y = clamp(zy + round_half_up(((a - za) * mult_a + (b - zb) * mult_b) / 2**shift), lo, hi)."""
+    za: int = 128
+    zb: int = 128
+    zy: int = 128
+    mult_a: int = 1 << 30
+    mult_b: int = 1 << 30
+    shift: int = 30
+    lo: int = 0
+    hi: int = 255
+
+
 def build(force=False):
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-o", _LIB, _SRC])
@@ -120,6 +133,49 @@ def relu(x, z):
     y = np.empty_like(x)
     lib().sq_relu(_pu8(x), _pu8(y), C.c_size_t(x.size), int(z))
     return y
+
+
+def add(a, b, q):
+    a, b = _u8(a), _u8(b)
+    assert a.shape == b.shape
+    y = np.empty_like(a)
+    lib().sq_add(_pu8(a), _pu8(b), _pu8(y), C.c_size_t(a.size), q.za, q.zb, q.zy, q.mult_a, q.mult_b, q.shift, q.lo, q.hi)
+    return y
+
+
+def run_network(net, x, ws, qs, upto=None, taps=None):
+    """The layers of a table (workloads.nets.Network) on codes, one after the other on plain NCHW uint8 tensors.
+    ws: OIHW uint8 filters by weight index; qs: one entry per layer -- Quant for conv / dw / dense, QuantAdd for add,
+    the zero point (int) for relu, None for the pools (or the parameter dicts of workloads.quantized_network_tensors). Buffers are named by the table's ids; returns the tensor
+    written to OUT (or by layer `upto`); taps, if a dict, receives every layer's result by layer index."""
+    from workloads.nets import IN, OUT
+    buf = {IN: _u8(x)}
+    last = None
+    for i, (l, q) in enumerate(zip(net.layers, qs)):
+        if isinstance(q, dict):
+            q = q["z"] if "z" in q else (QuantAdd(**q) if "za" in q else Quant(**q))
+        src = buf[l.src]
+        if l.op == "conv":
+            y = conv2d(src, ws[l.w], l.stride, l.pad, q)
+        elif l.op == "dw":
+            y = dwconv2d(src, ws[l.w], l.stride, l.pad, q)
+        elif l.op == "dense":
+            y = dense(src, ws[l.w], q)
+        elif l.op in ("maxpool", "avgpool"):
+            y = pool2d(src, (l.kh, l.kw), l.stride, l.pad, "max" if l.op == "maxpool" else "avg")
+        elif l.op == "relu":
+            y = relu(src, q)
+        elif l.op == "add":
+            y = add(src, buf[l.src2], q)
+        else:
+            raise ValueError("no quantized layer for op " + l.op)
+        buf[l.dst] = y
+        last = y
+        if taps is not None:
+            taps[i] = y
+        if upto is not None and i == upto:
+            return y
+    return buf.get(OUT, last)
 
 
 def pack(x, Cb):

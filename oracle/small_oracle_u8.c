@@ -18,11 +18,21 @@
  * lo = zy. Taps outside the image contribute nothing (the padding value is the zero point).
  * Max pooling compares codes (scale > 0 keeps the order) and skips out-of-image taps;
  * average pooling is floor((sum + n/2) / n) over the n in-image taps; ReLU is max(x, z).
+ * Addition (the residual blocks of Section "MLPerf:Tiny Inference Models" on codes) takes two
+ * tensors with scales and zero points of their own; both are brought to the output's scale by a
+ * multiplier each and one common shift, with a single rounding:
+ *
+ *   acc = (a - za) * mult_a + (b - zb) * mult_b                          (int64, exact)
+ *   y   = clamp(zy + floor((acc + 2^(shift-1)) / 2^shift), lo, hi)       (no rounding term when shift == 0)
+ *
+ * i.e. mult_a / 2^shift stands for scale_a / scale_y and mult_b / 2^shift for scale_b / scale_y.
  *
  * Parity pins (tests/test_oracle_u8.py): accumulators == a library fp64 convolution of the
  * zero-point-shifted tensors (exact for these magnitudes); requantization == exact rational
  * rounding, hand-worked values, identity for mult = 2^shift; pooling and ReLU == the fp32
- * oracle applied to the codes; layouts == the offset formulas of the layout statement.
+ * oracle applied to the codes; layouts == the offset formulas of the layout statement;
+ * addition == exact rational arithmetic on every pair of codes, plain integer addition for
+ * equal unit scales, the real-valued sum within half an output step.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -126,6 +136,20 @@ void sq_pool2d(const uint8_t *x, uint8_t *y, int N, int C, int H, int W, int kh,
                     y[(((size_t)n * C + c) * Ho + oh) * Wo + ow] =
                         (uint8_t)(mode == 0 ? m : (cnt > 0 ? (sum + cnt / 2) / cnt : 0));
                 }
+}
+
+/* Single-element layer with two inputs on codes (rule in the header). */
+void sq_add(const uint8_t *a, const uint8_t *b, uint8_t *y, size_t n, int za, int zb, int zy, int32_t mult_a, int32_t mult_b,
+            int shift, int lo, int hi)
+{
+    for (size_t i = 0; i < n; ++i) {
+        int64_t v = (int64_t)((int)a[i] - za) * mult_a + (int64_t)((int)b[i] - zb) * mult_b;
+        if (shift > 0) v = floor_shift(v + ((int64_t)1 << (shift - 1)), shift);
+        v += zy;
+        if (v < lo) v = lo;
+        if (v > hi) v = hi;
+        y[i] = (uint8_t)v;
+    }
 }
 
 void sq_relu(const uint8_t *x, uint8_t *y, size_t n, int z)

@@ -164,3 +164,125 @@ def test_multiplier_recipe_spreads_outputs_over_the_code_range():
     mult, shift = WL.u8_multiplier(32 * 9)
     y = Q.conv2d(x, w, 1, (1, 1, 1, 1), Q.Quant(mult=mult, shift=shift))
     assert 20 < y.std() < 70 and (y == 0).mean() < 0.05 and (y == 255).mean() < 0.05
+
+
+# ------------------------------------------------------------------ addition with two input scales, layer chains
+
+ADD_PARAMS = [  # za, zb, zy, mult_a, mult_b, shift, lo, hi
+    (128, 128, 128, 3 << 28, 1 << 29, 30, 0, 255),
+    (0, 255, 17, (1 << 31) - 1, 1, 31, 0, 255),
+    (200, 3, 100, 12345, 67890, 7, 10, 240),
+    (5, 9, 0, 7, 3, 0, 0, 255),                       # shift 0: no rounding term
+    (128, 128, 128, 0, 1 << 20, 20, 128, 255),        # one input switched off, ReLU bound
+    (255, 0, 255, 1 << 30, 1 << 30, 31, 0, 255),
+]
+
+
+@pytest.mark.parametrize("params", ADD_PARAMS)
+def test_add_equals_exact_integer_arithmetic_on_every_pair_of_codes(params):
+    """All 65536 (a, b) pairs against floor((acc + half) / 2^shift) in numpy int64 (floor_divide rounds towards
+    minus infinity, the sums stay below 2^41) -- written here from the rule, not through the oracle's C code."""
+    za, zb, zy, ma, mb, sh, lo, hi = params
+    a, b = np.meshgrid(np.arange(256, dtype=np.uint8), np.arange(256, dtype=np.uint8), indexing="ij")
+    got = Q.add(a, b, Q.QuantAdd(za, zb, zy, ma, mb, sh, lo, hi))
+    acc = (a.astype(np.int64) - za) * ma + (b.astype(np.int64) - zb) * mb
+    half = (1 << (sh - 1)) if sh > 0 else 0
+    ref = np.clip(zy + np.floor_divide(acc + half, 1 << sh), lo, hi)
+    assert np.array_equal(got.astype(np.int64), ref)
+    # and a handful of pairs in exact rational arithmetic
+    for ai, bi in [(0, 0), (255, 255), (za, zb), (1, 254), (77, 200)]:
+        v = Fraction((ai - za) * ma + (bi - zb) * mb, 1 << sh)
+        r = math.floor(v + Fraction(1, 2)) if sh > 0 else int(v)
+        assert got[ai, bi] == min(max(zy + r, lo), hi)
+
+
+def test_add_with_unit_scales_is_plain_saturating_addition_and_commutes():
+    r = _rng(31)
+    a, b = WL.u8_codes(r, (3, 16, 5, 7)), WL.u8_codes(r, (3, 16, 5, 7))
+    q = Q.QuantAdd(0, 0, 0, 1 << 12, 1 << 12, 12, 0, 255)
+    assert np.array_equal(Q.add(a, b, q), np.minimum(a.astype(np.int32) + b, 255).astype(np.uint8))
+    q1 = Q.QuantAdd(10, 20, 30, 12345, 54321, 16, 0, 255)
+    q2 = Q.QuantAdd(20, 10, 30, 54321, 12345, 16, 0, 255)
+    assert np.array_equal(Q.add(a, b, q1), Q.add(b, a, q2))
+
+
+def test_add_is_within_half_a_step_of_the_real_valued_sum():
+    """Codes stand for scale * (code - zero point); with multipliers mult / 2^shift = scale_in / scale_out the result
+    is the nearest code of the real sum wherever it is not clamped."""
+    r = _rng(32)
+    a, b = WL.u8_codes(r, (4096,)), WL.u8_codes(r, (4096,))
+    sa, sb, sy, sh = 0.031, 0.012, 0.05, 24
+    q = Q.QuantAdd(120, 131, 128, int(round(sa / sy * (1 << sh))), int(round(sb / sy * (1 << sh))), sh, 0, 255)
+    y = Q.add(a, b, q).astype(np.float64)
+    real = sa * (a.astype(np.float64) - 120) + sb * (b.astype(np.float64) - 131)
+    free = (y > 0) & (y < 255)
+    assert free.sum() > 2000
+    assert np.all(np.abs(sy * (y[free] - 128) - real[free]) <= sy * (0.5 + 1e-4))
+
+
+def _small_residual_table():
+    """conv -> relu -> conv -> add(skip) -> relu -> maxpool -> avgpool -> dense on small tensors: every op of the
+    quantized path, a second operand from an older buffer, buffers reused."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("u8_chain", 16, 6, 6)
+    net.wshapes = [((16, 16, 3, 3), 144), ((16, 1, 3, 3), 9), ((16, 16, 1, 1), 16), ((4, 16, 1, 1), 16)]
+    p1, z = (1, 1, 1, 1), (0, 0, 0, 0)
+    net.layers = [
+        Layer("conv", 16, 16, 6, 6, 3, 3, 1, p1, src=IN, dst=0, w=0),
+        Layer("relu", 16, 16, 6, 6, src=0, dst=0),
+        Layer("dw", 16, 16, 6, 6, 3, 3, 1, p1, src=0, dst=1, w=1),
+        Layer("conv", 16, 16, 6, 6, 1, 1, 1, z, src=1, dst=2, w=2),
+        Layer("add", 16, 16, 6, 6, src=2, src2=0, dst=2),
+        Layer("relu", 16, 16, 6, 6, src=2, dst=2),
+        Layer("maxpool", 16, 16, 6, 6, 2, 2, 2, z, src=2, dst=1),
+        Layer("avgpool", 16, 16, 3, 3, 3, 3, 1, z, src=1, dst=0),
+        Layer("dense", 16, 4, 1, 1, 1, 1, 1, z, src=0, dst=OUT, w=3),
+    ]
+    return net
+
+
+def test_run_network_is_the_composition_of_its_layers():
+    net = _small_residual_table()
+    x, ws, qs = WL.quantized_network_tensors(net, 3, 777)
+    taps = {}
+    out = Q.run_network(net, x, ws, qs, taps=taps)
+    a = Q.relu(Q.conv2d(x, ws[0], 1, (1, 1, 1, 1), Q.Quant(**qs[0])), 128)
+    b = Q.conv2d(Q.dwconv2d(a, ws[1], 1, (1, 1, 1, 1), Q.Quant(**qs[2])), ws[2], 1, (0, 0, 0, 0), Q.Quant(**qs[3]))
+    c = Q.relu(Q.add(b, a, Q.QuantAdd(**qs[4])), 128)
+    d = Q.pool2d(Q.pool2d(c, (2, 2), 2, mode="max"), (3, 3), 1, mode="avg")
+    ref = Q.dense(d, ws[3], Q.Quant(**qs[8]))
+    assert out.shape == (3, 4, 1, 1) and np.array_equal(out, ref)
+    assert np.array_equal(taps[1], a) and np.array_equal(taps[5], c) and np.array_equal(taps[7], d)
+    assert np.array_equal(Q.run_network(net, x, ws, qs, upto=4), Q.add(b, a, Q.QuantAdd(**qs[4])))
+    assert len(np.unique(out)) > 4                      # the parameters of the recipe spread the codes
+
+
+def test_run_network_with_unit_scales_is_the_float_oracle_on_integers():
+    """With every multiplier 2^shift (scale 1), weights in {-1, 0, 1} around their zero point and inputs small enough
+    that nothing saturates, a chain of quantized layers is exact integer arithmetic: code - zero point must equal the
+    float oracle's network on the shifted tensors (all values are small integers, exact in fp32)."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("u8_exact", 16, 5, 5)
+    net.wshapes = [((16, 16, 3, 3), 144), ((16, 1, 3, 3), 9), ((16, 16, 1, 1), 16)]
+    p1, z = (1, 1, 1, 1), (0, 0, 0, 0)
+    net.layers = [
+        Layer("conv", 16, 16, 5, 5, 3, 3, 1, p1, src=IN, dst=0, w=0),
+        Layer("dw", 16, 16, 5, 5, 3, 3, 2, p1, src=0, dst=1, w=1),
+        Layer("conv", 16, 16, 3, 3, 1, 1, 1, z, src=1, dst=2, w=2),
+        Layer("add", 16, 16, 3, 3, src=2, src2=1, dst=OUT),
+    ]
+    r = _rng(41)
+    x = (100 + r.integers(-1, 2, size=(2, 16, 5, 5))).astype(np.uint8)          # x - zx in {-1, 0, 1}
+    ws = [(90 + r.integers(-1, 2, size=shp) * (r.random(shp) < 0.3)).astype(np.uint8) for shp, _ in net.wshapes]
+    unit = dict(zw=90, mult=1 << 10, shift=10, lo=0, hi=255)
+    qs = [dict(zx=100, zy=128, **unit), dict(zx=128, zy=128, **unit), dict(zx=128, zy=60, **unit),
+          dict(za=60, zb=128, zy=128, mult_a=1 << 10, mult_b=1 << 10, shift=10, lo=0, hi=255)]
+    taps = {}
+    out = Q.run_network(net, x, ws, qs, taps=taps)
+    xs, wsf = x.astype(np.float32) - 100, [w.astype(np.float32) - 90 for w in ws]
+    _, trace = O.run_network(net, xs, wsf, return_all=True)
+    for i, zy in enumerate([128, 128, 60, 128]):
+        ref = trace[i]
+        assert np.abs(ref).max() >= 3 and np.abs(ref).max() < 60, i                 # not trivial, not clamped
+        assert np.array_equal(taps[i].astype(np.int32) - zy, ref.astype(np.int32)), i
+    assert np.array_equal(out, taps[3])

@@ -59,3 +59,29 @@ def u8_multiplier(K, spread=40.0, shift=31):
     m = spread / (np.sqrt(float(K)) * 74.0 * 74.0)
     mult = int(round(m * (1 << shift)))
     return min(max(mult, 1), (1 << 31) - 1), shift
+
+
+def quantized_network_tensors(net, N, seed):
+    """A quantized stand-in of a float layer table: input codes [N, C0, H0, W0] and OIHW filter codes, uniform over
+    0..255, and one parameter record per layer (plain dicts, no arithmetic): every tensor has zero point 128;
+    conv / dw / dense: {"zx", "zw", "zy", "mult", "shift", "lo", "hi"} with the multiplier of u8_multiplier for
+    the layer's reduction length; add: {"za", "zb", "zy", "mult_a", "mult_b", "shift", "lo", "hi"} with the two
+    inputs weighted 3/4 and 1/2 (two different input scales); relu: {"z": 128}; pools: None."""
+    rng = np.random.default_rng(seed)
+    x = u8_codes(rng, (N, net.C0, net.H0, net.W0))
+    ws = [u8_codes(rng, shp) for shp, _ in net.wshapes]
+    qs = []
+    for l in net.layers:
+        if l.op in ("conv", "dw", "dense"):
+            K = l.kh * l.kw * (1 if l.op == "dw" else l.Ci)
+            mult, shift = u8_multiplier(K)
+            qs.append({"zx": 128, "zw": 128, "zy": 128, "mult": mult, "shift": shift, "lo": 0, "hi": 255})
+        elif l.op == "add":
+            qs.append({"za": 128, "zb": 128, "zy": 128, "mult_a": 3 << 28, "mult_b": 1 << 29, "shift": 30, "lo": 0, "hi": 255})
+        elif l.op == "relu":
+            qs.append({"z": 128})
+        elif l.op in ("maxpool", "avgpool"):
+            qs.append(None)
+        else:
+            raise ValueError("no quantized stand-in for op " + l.op)
+    return x, ws, qs
