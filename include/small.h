@@ -174,6 +174,45 @@ int small_pool2d_u8(const unsigned char *in, unsigned char *out, int N, int C, i
                     small_pad pad, int Cb, int mode, void *stream);
 int small_relu_u8(const unsigned char *in, unsigned char *out, size_t n_elems, int z, void *stream);
 
+/* Addition of two quantized tensors (the residual blocks of Section "MLPerf:Tiny Inference Models" on codes). The
+ * operands have scales and zero points of their own; the paper gives no rule, this library brings both to the
+ * output's scale with a multiplier each and one common shift, rounding once:
+ *   acc = (a - za) * mult_a + (b - zb) * mult_b                                          (64-bit, exact)
+ *   y   = clamp(zy + floor((acc + 2^(shift-1)) / 2^shift), lo, hi)                       (no rounding term when shift == 0)
+ * so mult_a / 2^shift stands for scale_a / scale_y, mult_b / 2^shift for scale_b / scale_y. 0 <= za, zb, zy <= 255;
+ * 0 <= mult_a, mult_b <= 2^31 - 1; 0 <= shift <= 31; 0 <= lo <= hi <= 255. Element-wise on n_elems bytes (any layout,
+ * the same for all three tensors); out may be a or b (in place), other overlaps: SMALL_ERR_ALIAS. Bit-exact. */
+typedef struct { int za, zb, zy, mult_a, mult_b, shift, lo, hi; } small_quant_add;
+int small_add_u8(const unsigned char *a, const unsigned char *b, unsigned char *out, size_t n_elems, const small_quant_add *q,
+                 void *stream);
+
+/* A whole quantized network (Section "Quantized Inference" runs entire models on uint8 tensors): a table of layers
+ * over shared buffers as for small_network_run below -- same buffer ids, same sizing rule (bytes instead of floats),
+ * the same checks before anything is enqueued -- with the ops SMALL_OP_CONV, DWCONV, MAXPOOL, AVGPOOL, RELU, ADD and
+ * DENSE (others: SMALL_ERR_LAYER). q: parameters of CONV / DWCONV / DENSE (q.zx must be the source tensor's zero
+ * point); RELU uses q.zy as the tensor's zero point and nothing else of q; qa: parameters of ADD (src = a, src2 = b);
+ * the pools have none (codes in, codes out, same scale). filt: blocked uint8 filter in the layout of
+ * small_conv2d_u8 / small_dwconv2d_u8, filt_sums: optional, as for small_conv2d_u8. Layers run one after the other
+ * through the entry points above, except that an in-place ReLU directly after a CONV / DWCONV / DENSE / ADD goes
+ * into that layer's lower clamp (lo = max(lo, z): the same codes). Results are bit-exact.
+ * small_network_workspace_u8: bytes of workspace (host only). small_network_run_u8: in_blocked [N][C0/Cb0][H0][W0][Cb0]
+ * bytes with Cb0 = layers[0].Cib; out_blocked receives every write to SMALL_BUF_OUT; workspace 256-byte aligned. */
+typedef struct {
+    int op;
+    int Ci, Co, kh, kw, stride;
+    small_pad pad;
+    int Cib, Cob;
+    int src, src2, dst;
+    const unsigned char *filt;
+    const int *filt_sums;
+    small_quant q;
+    small_quant_add qa;
+} small_layer_u8;
+int small_network_workspace_u8(const small_layer_u8 *layers, int n_layers, int N, int C0, int H0, int W0, size_t *bytes);
+int small_network_run_u8(const small_layer_u8 *layers, int n_layers, const unsigned char *in_blocked,
+                         unsigned char *out_blocked, void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0,
+                         void *stream);
+
 /* ---- a whole network: a table of layers over shared buffers (Section "Memory Usage
  * Comparison": buffers are shared across layers; nothing is reformatted between layers).
  * Logical buffer ids: SMALL_BUF_IN = the caller's blocked input (read-only), SMALL_BUF_OUT = the

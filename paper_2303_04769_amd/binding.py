@@ -23,6 +23,7 @@ EXPORTS = ["small_out_dim", "small_strerror", "small_pack", "small_unpack", "sma
            "small_pack_dw_filter", "small_conv2d", "small_conv2d_kernel", "small_dwconv2d", "small_pool2d", "small_relu", "small_add",
            "small_dense", "small_batchnorm", "small_upsample", "small_group_conv2d", "small_pack_u8", "small_unpack_u8",
            "small_pack_filter_u8", "small_filter_sums_u8", "small_conv2d_u8", "small_dwconv2d_u8", "small_dense_u8", "small_pool2d_u8", "small_relu_u8",
+           "small_add_u8", "small_network_workspace_u8", "small_network_run_u8",
            "small_network_workspace", "small_network_run", "small_network_run_plain", "small_network_run_opt", "small_network_launches", "small_network_launches_at",
            "small_network_run_range", "small_network_run_static"]
 
@@ -41,6 +42,19 @@ class small_quant(C.Structure):
     """y = clamp(zy + round_half_up(acc * mult / 2**shift), lo, hi), acc = sum (x - zx) * (w - zw)."""
     _fields_ = [("zx", C.c_int), ("zw", C.c_int), ("zy", C.c_int), ("mult", C.c_int), ("shift", C.c_int),
                 ("lo", C.c_int), ("hi", C.c_int)]
+
+
+class small_quant_add(C.Structure):
+    """y = clamp(zy + round_half_up(((a - za) * mult_a + (b - zb) * mult_b) / 2**shift), lo, hi)."""
+    _fields_ = [("za", C.c_int), ("zb", C.c_int), ("zy", C.c_int), ("mult_a", C.c_int), ("mult_b", C.c_int),
+                ("shift", C.c_int), ("lo", C.c_int), ("hi", C.c_int)]
+
+
+class small_layer_u8(C.Structure):
+    _fields_ = [("op", C.c_int), ("Ci", C.c_int), ("Co", C.c_int), ("kh", C.c_int), ("kw", C.c_int),
+                ("stride", C.c_int), ("pad", small_pad), ("Cib", C.c_int), ("Cob", C.c_int),
+                ("src", C.c_int), ("src2", C.c_int), ("dst", C.c_int), ("filt", C.c_void_p), ("filt_sums", C.c_void_p),
+                ("q", small_quant), ("qa", small_quant_add)]
 
 
 class small_layer(C.Structure):
@@ -89,6 +103,9 @@ def load():
         "small_dense_u8": (i, [p, p, p, i, i, i, i, i, C.POINTER(small_quant), p, p]),
         "small_pool2d_u8": (i, [p, p, i, i, i, i, i, i, i, small_pad, i, i, p]),
         "small_relu_u8": (i, [p, p, sz, i, p]),
+        "small_add_u8": (i, [p, p, p, sz, C.POINTER(small_quant_add), p]),
+        "small_network_workspace_u8": (i, [C.POINTER(small_layer_u8), i, i, i, i, i, C.POINTER(sz)]),
+        "small_network_run_u8": (i, [C.POINTER(small_layer_u8), i, p, p, p, sz, i, i, i, i, p]),
         "small_network_workspace": (i, [C.POINTER(small_layer), i, i, i, i, i, C.POINTER(sz)]),
         "small_network_run": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
         "small_network_run_plain": (i, [C.POINTER(small_layer), i, p, p, p, sz, i, i, i, i, p]),
@@ -360,6 +377,88 @@ STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024
 def small_network_run_static(table, in_tensor, out_blocked, N, C0, H0, W0, flags=0, stream=None):
     _check(load().small_network_run_static(table, len(table), _ptr(in_tensor), _ptr(out_blocked), N, C0, H0, W0, flags,
                                            _stream(stream)), "small_network_run_static")
+
+
+def small_add_u8(a, b, out, n, q, stream=None):
+    """q: small_quant_add, or anything with its eight fields (a dict, oracle-side records)."""
+    _check(load().small_add_u8(_ptr8(a), _ptr8(b), _ptr8(out), n, C.byref(_quant_add(q)), _stream(stream)), "small_add_u8")
+
+
+def _quant_add(q):
+    if isinstance(q, small_quant_add):
+        return q
+    get = (lambda k: q[k]) if isinstance(q, dict) else (lambda k: getattr(q, k))
+    return small_quant_add(*[int(get(k)) for k in ("za", "zb", "zy", "mult_a", "mult_b", "shift", "lo", "hi")])
+
+
+def _quant_of(q):
+    if isinstance(q, small_quant):
+        return q
+    get = (lambda k: q[k]) if isinstance(q, dict) else (lambda k: getattr(q, k))
+    return small_quant(*[int(get(k)) for k in ("zx", "zw", "zy", "mult", "shift", "lo", "hi")])
+
+
+class PackedNetworkU8:
+    """Device-resident form of a quantized layer table: uint8 filters packed once (small_pack_filter_u8; depthwise
+    filters [C/Cb][kh][kw][Cb]), their per-channel sums taken once (small_filter_sums_u8), the table of small_layer_u8
+    records built from a workloads layer table and its per-layer parameter records."""
+
+    def __init__(self, net, weights, params, device="cuda:0"):
+        self.net, self.device = net, torch.device(device)
+        self.filters, self.sums = {}, {}
+        for L in net.layers:
+            if L.w is None:
+                continue
+            src = torch.from_numpy(weights[L.w]).to(self.device).contiguous()
+            if L.op == "dw":
+                dst = src.reshape(L.Ci // L.Cib, L.Cib, L.kh, L.kw).permute(0, 2, 3, 1).contiguous().reshape(-1)
+            else:
+                dst = torch.empty(src.numel(), dtype=torch.uint8, device=self.device)
+                small_pack_filter_u8(src, dst, L.Co, L.Ci, L.kh, L.kw, L.Cob, L.Cib)
+                sums = torch.empty(L.Co, dtype=torch.int32, device=self.device)
+                small_filter_sums_u8(dst, sums, L.Co, L.Ci, L.kh, L.kw, L.Cob, L.Cib)
+                self.sums[L.w] = sums
+            self.filters[L.w] = dst
+        arr = (small_layer_u8 * len(net.layers))()
+        for k, (L, q) in enumerate(zip(net.layers, params)):
+            arr[k].op = _OPS[L.op]
+            arr[k].Ci, arr[k].Co, arr[k].kh, arr[k].kw, arr[k].stride = L.Ci, L.Co, L.kh, L.kw, L.stride
+            arr[k].pad = small_pad(*L.pad)
+            arr[k].Cib, arr[k].Cob = L.Cib, L.Cob
+            arr[k].src, arr[k].src2, arr[k].dst = L.src, L.src2, L.dst
+            arr[k].filt = self.filters[L.w].data_ptr() if L.w is not None else None
+            arr[k].filt_sums = self.sums[L.w].data_ptr() if L.w in self.sums else None
+            if L.op in ("conv", "dw", "dense"):
+                arr[k].q = _quant_of(q)
+            elif L.op == "add":
+                arr[k].qa = _quant_add(q)
+            elif L.op == "relu":
+                arr[k].q = small_quant(0, 0, int(q["z"] if isinstance(q, dict) else q), 0, 0, 0, 255)
+        self.table = arr
+        self._ws = {}
+
+    def workspace(self, N):
+        if N not in self._ws:
+            nbytes = C.c_size_t(0)
+            _check(load().small_network_workspace_u8(self.table, len(self.table), N, self.net.C0, self.net.H0, self.net.W0,
+                                                     C.byref(nbytes)), "small_network_workspace_u8")
+            self._ws[N] = (torch.empty(max(nbytes.value, 256), dtype=torch.uint8, device=self.device), nbytes.value)
+        return self._ws[N]
+
+    def pack_input(self, x_nchw):
+        N = x_nchw.shape[0]
+        xb = torch.empty(x_nchw.numel(), dtype=torch.uint8, device=self.device)
+        small_pack_u8(x_nchw, xb, N, self.net.C0, self.net.H0, self.net.W0, self.net.layers[0].Cib)
+        return xb
+
+    def out_elems(self, N):
+        L = self.net.layers[-1]
+        return N * L.Co * L.Ho * L.Wo
+
+    def run(self, in_blocked, out_blocked, N, stream=None):
+        ws, nbytes = self.workspace(N)
+        _check(load().small_network_run_u8(self.table, len(self.table), _ptr8(in_blocked), _ptr8(out_blocked), _ptr8(ws), nbytes,
+                                           N, self.net.C0, self.net.H0, self.net.W0, _stream(stream)), "small_network_run_u8")
 
 
 class PackedNetwork:

@@ -545,18 +545,107 @@ __global__ void __launch_bounds__(256) relu_u8_kernel(const unsigned char *in, u
     if (i < n) out[i] = in[i] > z ? in[i] : (unsigned char)z;
 }
 
-__global__ void __launch_bounds__(256) relu_u8_words(const unsigned *in, unsigned *out, size_t n_words, int z)
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
+
+// Byte-wise unsigned maximum of two words, as two packed 16-bit maxima over the even and the odd bytes.
+struct SplitBytes { ushortx2 even, odd; };
+__device__ __forceinline__ SplitBytes split_bytes(unsigned w)
+{
+    return SplitBytes{__builtin_bit_cast(ushortx2, w & 0x00ff00ffu), __builtin_bit_cast(ushortx2, (w >> 8) & 0x00ff00ffu)};
+}
+__device__ __forceinline__ SplitBytes max_bytes(SplitBytes a, SplitBytes b)
+{
+    return SplitBytes{__builtin_elementwise_max(a.even, b.even), __builtin_elementwise_max(a.odd, b.odd)};
+}
+__device__ __forceinline__ unsigned join_bytes(SplitBytes a)
+{
+    return __builtin_bit_cast(unsigned, a.even) | (__builtin_bit_cast(unsigned, a.odd) << 8);
+}
+
+// 16 bytes per lane, streaming loads and stores
+__global__ void __launch_bounds__(256) relu_u8_vec16(const uintx4 *in, uintx4 *out, size_t n_vec, int z)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n_words) return;
-    const unsigned w = in[i];
-    unsigned y = 0;
+    if (i >= n_vec) return;
+    const uintx4 v = __builtin_nontemporal_load(in + i);
+    const SplitBytes zz = split_bytes((unsigned)z * 0x01010101u);
+    uintx4 y;
+    y.x = join_bytes(max_bytes(split_bytes(v.x), zz));
+    y.y = join_bytes(max_bytes(split_bytes(v.y), zz));
+    y.z = join_bytes(max_bytes(split_bytes(v.z), zz));
+    y.w = join_bytes(max_bytes(split_bytes(v.w), zz));
+    __builtin_nontemporal_store(y, out + i);
+}
+
+__device__ __forceinline__ unsigned add_one_u8(unsigned a, unsigned b, const AddQuantParams &q)
+{
+    long v = (long)((int)a - q.za) * (long)q.mult_a + (long)((int)b - q.zb) * (long)q.mult_b;
+    if (q.shift > 0) v = (v + (1L << (q.shift - 1))) >> q.shift;
+    v += q.zy;
+    v = v < q.lo ? q.lo : v;
+    v = v > q.hi ? q.hi : v;
+    return (unsigned)v;
+}
+
+__global__ void __launch_bounds__(256) add_u8_kernel(const unsigned char *a, const unsigned char *b, unsigned char *out, size_t n,
+                                                     AddQuantParams q)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) out[i] = (unsigned char)add_one_u8(a[i], b[i], q);
+}
+
+__global__ void __launch_bounds__(256) add_u8_vec16(const uintx4 *a, const uintx4 *b, uintx4 *out, size_t n_vec, AddQuantParams q)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n_vec) return;
+    const uintx4 va = __builtin_nontemporal_load(a + i), vb = __builtin_nontemporal_load(b + i);
+    uintx4 y;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const unsigned b = (w >> (8 * v)) & 255u;
-        y |= (b > (unsigned)z ? b : (unsigned)z) << (8 * v);
+    for (int w = 0; w < 4; ++w) {
+        unsigned r = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r |= add_one_u8((va[w] >> (8 * k)) & 255u, (vb[w] >> (8 * k)) & 255u, q) << (8 * k);
+        y[w] = r;
     }
-    out[i] = y;
+    __builtin_nontemporal_store(y, out + i);
+}
+
+// Max pooling on 16-byte blocks: a lane owns one output pixel's block and reads the 16 bytes of every tap inside the
+// image (taps outside are skipped, as the layer's definition says); the running maximum stays split into even and
+// odd bytes, so a tap costs three instructions to split and two packed maxima per word.
+struct QPool16Args {
+    const uintx4 *in;
+    uintx4 *out;
+    int H, W, Ho, Wo, kh, kw, stride, pt, pl;
+    FastDiv div_Wo, div_Ho;
+};
+
+__global__ void __launch_bounds__(256) maxpool_u8_16(QPool16Args a, int total)
+{
+    const int i = (int)blockIdx.x * 256 + (int)threadIdx.x;          // output pixel over (plane, row, column)
+    if (i >= total) return;
+    const int t = a.div_Wo.div(i), ow = i - t * a.Wo;
+    const int plane = a.div_Ho.div(t), oh = t - plane * a.Ho;
+    const uintx4 *img = a.in + (size_t)plane * a.H * a.W;
+    SplitBytes m[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) m[w] = split_bytes(0u);
+    for (int ky = 0; ky < a.kh; ++ky) {
+        const int ih = oh * a.stride + ky - a.pt;
+        if (ih < 0 || ih >= a.H) continue;
+        for (int kx = 0; kx < a.kw; ++kx) {
+            const int iw = ow * a.stride + kx - a.pl;
+            if (iw < 0 || iw >= a.W) continue;
+            const uintx4 v = img[ih * a.W + iw];
+#pragma unroll
+            for (int w = 0; w < 4; ++w) m[w] = max_bytes(m[w], split_bytes(v[w]));
+        }
+    }
+    uintx4 y;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) y[w] = join_bytes(m[w]);
+    __builtin_nontemporal_store(y, a.out + i);
 }
 
 inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
@@ -666,6 +755,16 @@ hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, 
         return hipGetLastError();
     }
     const size_t n_out = (size_t)g.N * g.Ci * g.Ho * g.Wo;
+    if (mode == 1 && g.Cib == 16 && ((((uintptr_t)in | (uintptr_t)out) & 15u) == 0) && n_out / 16 < ((size_t)1 << 31) &&
+        (size_t)g.N * g.Ci * g.H * g.W < ((size_t)1 << 31)) {
+        QPool16Args p;
+        p.in = reinterpret_cast<const uintx4 *>(in); p.out = reinterpret_cast<uintx4 *>(out);
+        p.H = g.H; p.W = g.W; p.Ho = g.Ho; p.Wo = g.Wo; p.kh = g.kh; p.kw = g.kw; p.stride = g.stride; p.pt = g.pt; p.pl = g.pl;
+        p.div_Wo = make_fastdiv(g.Wo); p.div_Ho = make_fastdiv(g.Ho);
+        const int total = (int)(n_out / 16);
+        hipLaunchKernelGGL(maxpool_u8_16, dim3(blocks_for((size_t)total)), dim3(256), 0, s, p, total);
+        return hipGetLastError();
+    }
     const bool words4 = g.Cib % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)(filt ? filt : in)) & 3u) == 0);
     a.div_groups = make_fastdiv(words4 ? g.Cib / 4 : g.Cib);
     a.div_Wo = make_fastdiv(g.Wo);
@@ -679,10 +778,20 @@ hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, 
 
 hipError_t launch_relu_u8(const unsigned char *in, unsigned char *out, size_t n, int z, hipStream_t s)
 {
-    if (n % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out) & 3u) == 0))
-        hipLaunchKernelGGL(relu_u8_words, dim3(blocks_for(n / 4)), dim3(256), 0, s, reinterpret_cast<const unsigned *>(in),
-                           reinterpret_cast<unsigned *>(out), n / 4, z);
+    if (n % 16 == 0 && ((((uintptr_t)in | (uintptr_t)out) & 15u) == 0))
+        hipLaunchKernelGGL(relu_u8_vec16, dim3(blocks_for(n / 16)), dim3(256), 0, s, reinterpret_cast<const uintx4 *>(in),
+                           reinterpret_cast<uintx4 *>(out), n / 16, z);
     else hipLaunchKernelGGL(relu_u8_kernel, dim3(blocks_for(n)), dim3(256), 0, s, in, out, n, z);
+    return hipGetLastError();
+}
+
+hipError_t launch_add_u8(const unsigned char *a, const unsigned char *b, unsigned char *out, size_t n, const AddQuantParams &q,
+                         hipStream_t s)
+{
+    if (n % 16 == 0 && ((((uintptr_t)a | (uintptr_t)b | (uintptr_t)out) & 15u) == 0))
+        hipLaunchKernelGGL(add_u8_vec16, dim3(blocks_for(n / 16)), dim3(256), 0, s, reinterpret_cast<const uintx4 *>(a),
+                           reinterpret_cast<const uintx4 *>(b), reinterpret_cast<uintx4 *>(out), n / 16, q);
+    else hipLaunchKernelGGL(add_u8_kernel, dim3(blocks_for(n)), dim3(256), 0, s, a, b, out, n, q);
     return hipGetLastError();
 }
 

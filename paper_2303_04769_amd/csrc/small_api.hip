@@ -409,6 +409,179 @@ int small_relu_u8(const unsigned char *in, unsigned char *out, size_t n_elems, i
     return from_hip(launch_relu_u8(in, out, n_elems, z, as_stream(stream)));
 }
 
+
+}  // extern "C"
+
+namespace {
+
+int check_quant_add(const small_quant_add *q, AddQuantParams &out)
+{
+    if (!q) return SMALL_ERR_NULL;
+    if (q->za < 0 || q->za > 255 || q->zb < 0 || q->zb > 255 || q->zy < 0 || q->zy > 255) return SMALL_ERR_QUANT;
+    if (q->mult_a < 0 || q->mult_b < 0 || q->shift < 0 || q->shift > 31) return SMALL_ERR_QUANT;
+    if (q->lo < 0 || q->hi > 255 || q->lo > q->hi) return SMALL_ERR_QUANT;
+    out = AddQuantParams{q->za, q->zb, q->zy, q->mult_a, q->mult_b, q->shift, q->lo, q->hi};
+    return SMALL_OK;
+}
+
+// ---- a table of quantized layers over shared buffers: the walk of small_network_run on bytes, layer by layer.
+struct ShapeU8 { int C, H, W, Cb; bool set; };
+
+struct NetPlanU8 {
+    size_t slot_bytes[SMALL_MAX_SLOTS];
+    size_t slot_off[SMALL_MAX_SLOTS];
+    size_t bytes;
+};
+
+inline bool valid_buf(int id) { return id >= SMALL_BUF_OUT && id < SMALL_MAX_SLOTS; }
+
+// An in-place ReLU (zero point z) directly after layer i, whose lower clamp can take it: clamp(v, max(lo, z), hi)
+// is relu(clamp(v, lo, hi)) for z <= hi, the same codes.
+bool relu_follows_u8(const small_layer_u8 *L, int nL, int i)
+{
+    if (i + 1 >= nL) return false;
+    const small_layer_u8 &l = L[i], &r = L[i + 1];
+    if (r.op != SMALL_OP_RELU || r.src != l.dst || r.dst != l.dst) return false;
+    const int hi = l.op == SMALL_OP_ADD ? l.qa.hi : l.q.hi;
+    return r.q.zy >= 0 && r.q.zy <= hi;
+}
+
+// run = false: shapes, parameters and workspace sizes only. Every layer is checked before the first one runs
+// (the caller walks twice).
+int walk_u8(const small_layer_u8 *L, int nL, int N, int C0, int H0, int W0, NetPlanU8 &plan, bool run, const unsigned char *in,
+            unsigned char *out, unsigned char *ws, hipStream_t s)
+{
+    if (!L || nL <= 0 || N <= 0 || C0 <= 0 || H0 <= 0 || W0 <= 0) return SMALL_ERR_SHAPE;
+    ShapeU8 shp_store[SMALL_MAX_SLOTS + 2] = {};
+    ShapeU8 *shp = shp_store + 2;                              // ids -2 .. SMALL_MAX_SLOTS - 1
+    shp[SMALL_BUF_IN] = ShapeU8{C0, H0, W0, L[0].Cib, true};
+    if (!run) {
+        for (int k = 0; k < SMALL_MAX_SLOTS; ++k) plan.slot_bytes[k] = 0;
+    }
+    auto ptr = [&](int id) -> unsigned char * {
+        if (id == SMALL_BUF_IN) return const_cast<unsigned char *>(in);
+        if (id == SMALL_BUF_OUT) return out;
+        return ws + plan.slot_off[id];
+    };
+    for (int i = 0; i < nL; ++i) {
+        small_layer_u8 l = L[i];
+        if (!valid_buf(l.src) || !valid_buf(l.dst) || l.dst == SMALL_BUF_IN || !shp[l.src].set) return SMALL_ERR_LAYER;
+        const ShapeU8 si = shp[l.src];
+        if (l.Ci != si.C || l.Cib != si.Cb) return SMALL_ERR_LAYER;
+        const bool fold = (l.op == SMALL_OP_CONV || l.op == SMALL_OP_DWCONV || l.op == SMALL_OP_DENSE || l.op == SMALL_OP_ADD) &&
+                          relu_follows_u8(L, nL, i);
+        if (fold) {
+            if (l.op == SMALL_OP_ADD) l.qa.lo = l.qa.lo > L[i + 1].q.zy ? l.qa.lo : L[i + 1].q.zy;
+            else l.q.lo = l.q.lo > L[i + 1].q.zy ? l.q.lo : L[i + 1].q.zy;
+        }
+        ShapeU8 so = ShapeU8{l.Co, si.H, si.W, l.Cob, true};
+        int rc = SMALL_OK;
+        LayerGeom g;
+        size_t ni = 0, no = 0;
+        QuantParams qp;
+        switch (l.op) {
+        case SMALL_OP_CONV:
+        case SMALL_OP_DENSE: {
+            if (l.op == SMALL_OP_DENSE && (l.kh != si.H || l.kw != si.W)) return SMALL_ERR_LAYER;
+            const small_pad pad = l.op == SMALL_OP_DENSE ? small_pad{0, 0, 0, 0} : l.pad;
+            const int stride = l.op == SMALL_OP_DENSE ? 1 : l.stride;
+            if ((rc = window_geom(g, N, l.Ci, l.Co, si.H, si.W, l.kh, l.kw, stride, pad, l.Cib, l.Cob, &ni, &no))) return rc;
+            if ((rc = check_quant(&l.q, (long)l.Ci * l.kh * l.kw, qp))) return rc;
+            if (!l.filt) return SMALL_ERR_NULL;
+            so.H = g.Ho; so.W = g.Wo;
+            if (run) rc = small_conv2d_u8(ptr(l.src), l.filt, ptr(l.dst), N, l.Ci, l.Co, si.H, si.W, l.kh, l.kw, stride, pad, l.Cib,
+                                          l.Cob, &l.q, l.filt_sums, s);
+            break;
+        }
+        case SMALL_OP_DWCONV:
+            if (l.Co != l.Ci || l.Cob != l.Cib) return SMALL_ERR_LAYER;
+            if ((rc = window_geom(g, N, l.Ci, l.Co, si.H, si.W, l.kh, l.kw, l.stride, l.pad, l.Cib, l.Cob, &ni, &no))) return rc;
+            if ((rc = check_quant(&l.q, (long)l.kh * l.kw, qp))) return rc;
+            if (!l.filt) return SMALL_ERR_NULL;
+            so.H = g.Ho; so.W = g.Wo;
+            if (run) rc = small_dwconv2d_u8(ptr(l.src), l.filt, ptr(l.dst), N, l.Ci, si.H, si.W, l.kh, l.kw, l.stride, l.pad, l.Cib,
+                                            &l.q, s);
+            break;
+        case SMALL_OP_MAXPOOL:
+        case SMALL_OP_AVGPOOL:
+            if (l.Co != l.Ci || l.Cob != l.Cib) return SMALL_ERR_LAYER;
+            if ((rc = window_geom(g, N, l.Ci, l.Co, si.H, si.W, l.kh, l.kw, l.stride, l.pad, l.Cib, l.Cob, &ni, &no))) return rc;
+            so.H = g.Ho; so.W = g.Wo;
+            if (run) rc = small_pool2d_u8(ptr(l.src), ptr(l.dst), N, l.Ci, si.H, si.W, l.kh, l.kw, l.stride, l.pad, l.Cib,
+                                          l.op == SMALL_OP_MAXPOOL ? SMALL_POOL_MAX : SMALL_POOL_AVG, s);
+            break;
+        case SMALL_OP_RELU:
+            if (l.Co != l.Ci || l.Cob != l.Cib) return SMALL_ERR_LAYER;
+            if (l.q.zy < 0 || l.q.zy > 255) return SMALL_ERR_QUANT;
+            if (run) rc = small_relu_u8(ptr(l.src), ptr(l.dst), (size_t)N * si.C * si.H * si.W, l.q.zy, s);
+            break;
+        case SMALL_OP_ADD: {
+            if (l.Co != l.Ci || l.Cob != l.Cib || !valid_buf(l.src2) || !shp[l.src2].set) return SMALL_ERR_LAYER;
+            const ShapeU8 s2 = shp[l.src2];
+            if (s2.C != si.C || s2.H != si.H || s2.W != si.W || s2.Cb != si.Cb) return SMALL_ERR_LAYER;
+            AddQuantParams ap;
+            if ((rc = check_quant_add(&l.qa, ap))) return rc;
+            if (run) rc = small_add_u8(ptr(l.src), ptr(l.src2), ptr(l.dst), (size_t)N * si.C * si.H * si.W, &l.qa, s);
+            break;
+        }
+        default:
+            return SMALL_ERR_LAYER;
+        }
+        if (rc) return rc;
+        shp[l.dst] = so;
+        if (!run && l.dst >= 0) {
+            const size_t b = (size_t)N * so.C * so.H * so.W;
+            if (b > plan.slot_bytes[l.dst]) plan.slot_bytes[l.dst] = b;
+        }
+        if (fold) ++i;                                         // the ReLU went into the layer's lower clamp
+    }
+    if (!run) {
+        size_t off = 0;
+        for (int k = 0; k < SMALL_MAX_SLOTS; ++k) {
+            plan.slot_off[k] = off;
+            off += (plan.slot_bytes[k] + 255) / 256 * 256;
+        }
+        plan.bytes = off;
+    }
+    return SMALL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int small_add_u8(const unsigned char *a, const unsigned char *b, unsigned char *out, size_t n_elems, const small_quant_add *q,
+                 void *stream)
+{
+    AddQuantParams ap;
+    if (int rc = check_quant_add(q, ap)) return rc;
+    if (!a || !b || !out) return SMALL_ERR_NULL;
+    if (!n_elems) return SMALL_ERR_SHAPE;
+    if ((a != out && overlap_bytes(a, n_elems, out, n_elems)) || (b != out && overlap_bytes(b, n_elems, out, n_elems)))
+        return SMALL_ERR_ALIAS;
+    return from_hip(launch_add_u8(a, b, out, n_elems, ap, as_stream(stream)));
+}
+
+int small_network_workspace_u8(const small_layer_u8 *layers, int n_layers, int N, int C0, int H0, int W0, size_t *bytes)
+{
+    if (!bytes) return SMALL_ERR_NULL;
+    NetPlanU8 plan;
+    if (int rc = walk_u8(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr)) return rc;
+    *bytes = plan.bytes;
+    return SMALL_OK;
+}
+
+int small_network_run_u8(const small_layer_u8 *layers, int n_layers, const unsigned char *in_blocked, unsigned char *out_blocked,
+                         void *workspace, size_t workspace_bytes, int N, int C0, int H0, int W0, void *stream)
+{
+    NetPlanU8 plan;
+    if (int rc = walk_u8(layers, n_layers, N, C0, H0, W0, plan, false, nullptr, nullptr, nullptr, nullptr)) return rc;
+    if (!in_blocked || !out_blocked) return SMALL_ERR_NULL;
+    if (plan.bytes && (!workspace || workspace_bytes < plan.bytes || ((uintptr_t)workspace & 255u))) return SMALL_ERR_WORKSPACE;
+    return walk_u8(layers, n_layers, N, C0, H0, W0, plan, true, in_blocked, out_blocked, static_cast<unsigned char *>(workspace),
+                   as_stream(stream));
+}
+
 }  // extern "C"
 
 // ------------------------------------------------------------------------------------------------

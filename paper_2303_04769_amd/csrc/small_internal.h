@@ -216,5 +216,9 @@ hipError_t launch_filter_sums_u8(const unsigned char *filt, int *sums, int Co, i
 hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
                             int mode, const QuantParams &q, hipStream_t s);
 hipError_t launch_relu_u8(const unsigned char *in, unsigned char *out, size_t n, int z, hipStream_t s);
+// y = clamp(zy + floor(((a - za) mult_a + (b - zb) mult_b + 2^(shift-1)) / 2^shift), lo, hi); out may be a or b
+struct AddQuantParams { int za, zb, zy, mult_a, mult_b, shift, lo, hi; };
+hipError_t launch_add_u8(const unsigned char *a, const unsigned char *b, unsigned char *out, size_t n, const AddQuantParams &q,
+                         hipStream_t s);
 
 }  // namespace small

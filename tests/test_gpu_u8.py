@@ -235,3 +235,142 @@ def test_conv_random_geometries(seed):
     Cib, Cob = min(16, Ci), min(16, Co)
     what = f"conv u8 N={N} {Ci}->{Co} {H}x{W} k={kh}x{kw} s={s} pad={pad} z=({zx},{zw})"
     _same(_conv(x, w, s, pad, q, Cib, Cob, with_sums=bool(seed & 2)), ref, what)
+
+
+# ------------------------------------------------------------------ vectorised element-wise kernels, add, networks
+
+@pytest.mark.parametrize("n", [16, 4096 * 16, 100000 * 16 + 16])
+def test_relu_sixteen_bytes_per_lane(n):
+    """Multiples of 16 bytes on aligned buffers take the 16-byte kernel (split even / odd bytes, packed 16-bit max)."""
+    x = WL.u8_codes(_rng(9), (n,))
+    for z in (0, 1, 127, 128, 200, 255):
+        g = Guarded8(n)
+        S.small_relu_u8(dev8(x), g.t, n, z)
+        assert np.array_equal(g.check(), Q.relu(x, z)), z
+
+
+@pytest.mark.parametrize("case", [(2, 64, 30, 30, 3, 3, 2, (0, 0, 0, 0)), (3, 16, 9, 7, 3, 3, 1, (1, 1, 1, 1)),
+                                  (2, 32, 8, 8, 2, 2, 2, (0, 1, 0, 1)), (5, 48, 5, 5, 5, 5, 1, (0, 0, 0, 0)),
+                                  (1, 16, 1, 1, 1, 1, 1, (0, 0, 0, 0)), (4, 256, 56, 56, 3, 3, 2, (0, 0, 0, 0))])
+def test_max_pooling_on_16_byte_blocks(case):
+    N, C, H, W, kh, kw, s, pad = case
+    x = WL.u8_codes(_rng(10), (N, C, H, W))
+    x[0, :, 0, 0] = 0                                  # a window of zeros at a padded corner
+    ref = Q.pool2d(x, (kh, kw), s, pad, "max")
+    g = Guarded8(ref.size)
+    S.small_pool2d_u8(dev8(Q.pack(x, 16)), g.t, N, C, H, W, kh, kw, s, pad, 16, S.POOL_MAX)
+    _same(Q.unpack(g.check(), ref.shape, 16), ref, f"max pool u8 {case}")
+
+
+ADD_PARAMS = [(128, 128, 128, 3 << 28, 1 << 29, 30, 0, 255), (0, 255, 17, (1 << 31) - 1, 1, 31, 0, 255),
+              (200, 3, 100, 12345, 67890, 7, 10, 240), (5, 9, 0, 7, 3, 0, 0, 255), (255, 0, 255, 1 << 30, 1 << 30, 31, 0, 255),
+              (128, 128, 128, (1 << 31) - 1, (1 << 31) - 1, 0, 0, 255)]
+
+
+@pytest.mark.parametrize("params", ADD_PARAMS)
+@pytest.mark.parametrize("n", [1, 15, 65536, 100003])
+def test_add_two_scales(params, n):
+    """Every pair of codes occurs (n = 65536 is the full 256 x 256 table); odd sizes take the byte kernel."""
+    q = Q.QuantAdd(*params)
+    if n == 65536:
+        a, b = [v.reshape(-1).copy() for v in np.meshgrid(np.arange(256, dtype=np.uint8), np.arange(256, dtype=np.uint8), indexing="ij")]
+    else:
+        r = _rng(11)
+        a, b = WL.u8_codes(r, (n,)), WL.u8_codes(r, (n,))
+    ref = Q.add(a, b, q)
+    g = Guarded8(n)
+    S.small_add_u8(dev8(a), dev8(b), g.t, n, q)
+    _same(g.check(), ref, f"add u8 {params} n={n}")
+    t = dev8(a)
+    S.small_add_u8(t, dev8(b), t, n, q)               # in place on the first operand
+    torch.cuda.synchronize()
+    _same(t.cpu().numpy(), ref, "add u8 in place")
+
+
+def _run_u8(net, x, ws, qs):
+    pn = S.PackedNetworkU8(net, ws, qs, DEV)
+    N = x.shape[0]
+    g = Guarded8(pn.out_elems(N))
+    pn.run(pn.pack_input(dev8(x)), g.t, N)
+    L = net.layers[-1]
+    return Q.unpack(g.check(), (N, L.Co, L.Ho, L.Wo), L.Cob)
+
+
+def _chain_table():
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("u8_chain", 16, 6, 6)
+    net.wshapes = [((16, 16, 3, 3), 144), ((16, 1, 3, 3), 9), ((16, 16, 1, 1), 16), ((4, 16, 1, 1), 16)]
+    p1, z = (1, 1, 1, 1), (0, 0, 0, 0)
+    net.layers = [
+        Layer("conv", 16, 16, 6, 6, 3, 3, 1, p1, src=IN, dst=0, w=0),
+        Layer("relu", 16, 16, 6, 6, src=0, dst=0),
+        Layer("dw", 16, 16, 6, 6, 3, 3, 1, p1, src=0, dst=1, w=1),
+        Layer("conv", 16, 16, 6, 6, 1, 1, 1, z, src=1, dst=2, w=2),
+        Layer("add", 16, 16, 6, 6, src=2, src2=0, dst=2),
+        Layer("relu", 16, 16, 6, 6, src=2, dst=2),
+        Layer("maxpool", 16, 16, 6, 6, 2, 2, 2, z, src=2, dst=1),
+        Layer("avgpool", 16, 16, 3, 3, 3, 3, 1, z, src=1, dst=0),
+        Layer("dense", 16, 4, 1, 1, 1, 1, 1, z, src=0, dst=OUT, w=3),
+    ]
+    return net
+
+
+def test_network_every_op_and_every_prefix():
+    """A table with every op of the quantized path: the whole run and every prefix of it (the prefix's last layer
+    redirected to the output buffer) equal the oracle's chain, code for code: this checks each intermediate tensor."""
+    import copy
+    net = _chain_table()
+    x, ws, qs = WL.quantized_network_tensors(net, 5, 4242)
+    _same(_run_u8(net, x, ws, qs), Q.run_network(net, x, ws, qs), "u8 chain")
+    for upto in range(len(net.layers) - 1):
+        if net.layers[upto + 1].op == "relu" and net.layers[upto + 1].src == net.layers[upto].dst:
+            continue                                   # the next layer's ReLU is folded only when it is in the table
+        sub = copy.deepcopy(net)
+        sub.layers = sub.layers[:upto + 1]
+        sub.layers[-1].dst = -2
+        _same(_run_u8(sub, x, ws, qs[:upto + 1]), Q.run_network(net, x, ws, qs, upto=upto), f"u8 chain prefix {upto}")
+
+
+def test_network_relu_that_must_not_be_folded():
+    """A ReLU into another buffer is a layer of its own: the convolution's result stays as it was for the add."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("u8_nofold", 16, 5, 5)
+    net.wshapes = [((16, 16, 3, 3), 144)]
+    net.layers = [Layer("conv", 16, 16, 5, 5, 3, 3, 1, (1, 1, 1, 1), src=IN, dst=0, w=0),
+                  Layer("relu", 16, 16, 5, 5, src=0, dst=1),
+                  Layer("add", 16, 16, 5, 5, src=0, src2=1, dst=OUT)]
+    x, ws, qs = WL.quantized_network_tensors(net, 3, 4243)
+    ref = Q.run_network(net, x, ws, qs)
+    assert (Q.run_network(net, x, ws, qs, upto=0) < 128).any()
+    _same(_run_u8(net, x, ws, qs), ref, "u8 relu into another buffer")
+
+
+@pytest.mark.parametrize("name,N", [("residual_cnn", 7), ("residual_cnn", 256), ("audio_cnn", 33), ("dsep_cnn", 3)])
+def test_quantized_networks(name, N):
+    """The stand-in networks on codes (seeded codes and parameters, every tensor's zero point 128): every image of
+    the batch, code for code."""
+    net = getattr(WL, name)()
+    x, ws, qs = WL.quantized_network_tensors(net, N, WL.BASE_SEED + 300 + N)
+    ref = Q.run_network(net, x, ws, qs)
+    assert len(np.unique(ref)) > min(8, ref.size // 2), "the recipe's parameters must not collapse or saturate the logits"
+    _same(_run_u8(net, x, ws, qs), ref, f"u8 {name} batch {N}")
+
+
+def test_network_table_errors():
+    net = _chain_table()
+    x, ws, qs = WL.quantized_network_tensors(net, 2, 4244)
+    pn = S.PackedNetworkU8(net, ws, qs, DEV)
+    pn.table[3].Ci = 32                                 # block / channel mismatch with the tensor in its source buffer
+    with pytest.raises(S.SmallError) as e:
+        pn.workspace(2)
+    assert e.value.code == 7
+    pn = S.PackedNetworkU8(net, ws, qs, DEV)
+    pn.table[4].qa.shift = 40
+    with pytest.raises(S.SmallError) as e:
+        pn.workspace(2)
+    assert e.value.code == 8
+    pn = S.PackedNetworkU8(net, ws, qs, DEV)
+    pn.table[0].op = 7                                  # batch normalization has no quantized layer
+    with pytest.raises(S.SmallError) as e:
+        pn.workspace(2)
+    assert e.value.code == 7

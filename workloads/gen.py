@@ -53,10 +53,11 @@ def u8_codes(rng, shape):
     return rng.integers(0, 256, size=shape, dtype=np.uint8)
 
 
-def u8_multiplier(K, spread=40.0, shift=31):
-    """(mult, shift) with mult / 2**shift = spread / (sqrt(K) * 74 * 74): a sum of K products of two
-    uniform codes minus their zero points has a standard deviation of about sqrt(K) * 74 * 74."""
-    m = spread / (np.sqrt(float(K)) * 74.0 * 74.0)
+def u8_multiplier(K, spread=40.0, shift=31, x_rms=74.0):
+    """(mult, shift) with mult / 2**shift = spread / (sqrt(K) * x_rms * 74): a sum of K products of a code minus its
+    zero point with that root mean square (74 for uniform codes) and a uniform filter code minus its zero point has
+    a standard deviation of about sqrt(K) * x_rms * 74."""
+    m = spread / (np.sqrt(float(K)) * x_rms * 74.0)
     mult = int(round(m * (1 << shift)))
     return min(max(mult, 1), (1 << 31) - 1), shift
 
@@ -70,18 +71,30 @@ def quantized_network_tensors(net, N, seed):
     rng = np.random.default_rng(seed)
     x = u8_codes(rng, (N, net.C0, net.H0, net.W0))
     ws = [u8_codes(rng, shp) for shp, _ in net.wshapes]
+    # Multipliers are chosen so that the codes keep spreading through the network: a rough root mean square of
+    # (code - 128) is carried per buffer (uniform input: 74; after a weighted layer: the spread asked for, 40; after
+    # a ReLU: / sqrt 2; after an average over many values of a rectified tensor: about their mean, 0.56 of it).
+    rms = {-1: 74.0}
     qs = []
     for l in net.layers:
+        r = rms[l.src]
         if l.op in ("conv", "dw", "dense"):
             K = l.kh * l.kw * (1 if l.op == "dw" else l.Ci)
-            mult, shift = u8_multiplier(K)
+            mult, shift = u8_multiplier(K, x_rms=r)
             qs.append({"zx": 128, "zw": 128, "zy": 128, "mult": mult, "shift": shift, "lo": 0, "hi": 255})
+            r = 40.0
         elif l.op == "add":
             qs.append({"za": 128, "zb": 128, "zy": 128, "mult_a": 3 << 28, "mult_b": 1 << 29, "shift": 30, "lo": 0, "hi": 255})
+            r = float(np.hypot(0.75 * r, 0.5 * rms[l.src2]))
         elif l.op == "relu":
             qs.append({"z": 128})
-        elif l.op in ("maxpool", "avgpool"):
+            r = r / np.sqrt(2.0)
+        elif l.op == "avgpool":
+            qs.append(None)
+            r = 0.56 * r if l.kh * l.kw >= 9 else r
+        elif l.op == "maxpool":
             qs.append(None)
         else:
             raise ValueError("no quantized stand-in for op " + l.op)
+        rms[l.dst] = r
     return x, ws, qs
