@@ -17,6 +17,7 @@ Also reported on the same JSON line:
   sweep         the roofline layer sweep (batch 64, Cb = 16): conv GFLOP/s against the fp32 MFMA peak,
                 depthwise / max-pool / ReLU GB/s against the HBM peak, buffers rotated so that
                 at least 512 MB are touched between reuses of a buffer;
+  networks_u8   the CNN stand-ins on the quantized path (small_network_run_u8), the quantized oracle beside them
   sweep_u8      the same layers on the quantized path (uint8 codes, int32 sums): conv TOP/s against the int8
                 MFMA peak and GB/s against the HBM peak;
   networks      images/s of the four stand-in networks at batch 1 and at their large batch;
@@ -93,6 +94,8 @@ def main():
                 print(json.dumps(row))
         if "u8" in only:
             for row in sweep_u8(S, WL, torch, dev, timed):
+                print(json.dumps(row))
+            for row in networks_u8(S, WL, torch, dev, timed, cpu=not args.no_cpu):
                 print(json.dumps(row))
         return
 
@@ -270,6 +273,7 @@ def main():
     # ------------------------------------------------------------------ networks
     if not args.no_networks:
         result["networks"] = networks(S, WL, torch, dev, timed)
+        result["networks_u8"] = networks_u8(S, WL, torch, dev, timed, cpu=not args.no_cpu)
 
     # ------------------------------------------------------------------ CPU oracle beside it
     if not args.no_cpu:
@@ -621,7 +625,44 @@ def sweep_u8(S, WL, torch, dev, timed):
     rows.append({"layer": "maxpool3x3s2", "shape": shape, "us": round(tmin * 1e6, 2), "us_median": round(tmed * 1e6, 2),
                  "gbs": round((n_act + n_pool) / tmin / 1e9, 1), "frac": round((n_act + n_pool) / tmin / PEAK_HBM, 4),
                  "buffer_sets": sets})
+    from paper_2303_04769_amd.binding import small_quant_add
+    qa = small_quant_add(120, 131, 128, 3 << 28, 1 << 29, 30, 0, 255)
+    fn = lambda r: S.small_add_u8(ins[r % sets], ins[(r + 1) % sets], outs[r % sets], n_act, qa)
+    tmin, tmed = best_of(fn, 240)
+    rows.append({"layer": "add", "shape": shape, "us": round(tmin * 1e6, 2), "us_median": round(tmed * 1e6, 2),
+                 "gbs": round(3.0 * n_act / tmin / 1e9, 1), "frac": round(3.0 * n_act / tmin / PEAK_HBM, 4), "buffer_sets": sets})
     return rows
+
+
+def networks_u8(S, WL, torch, dev, timed, cpu=False):
+    """The stand-in networks on the quantized path (uint8 codes, seeded parameters): small_network_run_u8 from the
+    blocked input to the blocked logits; cpu: the quantized oracle beside it (all cores, a bounded slice of the batch)."""
+    out = []
+    for name, idx, N in (("residual_cnn", 2, 256), ("dsep_cnn", 3, 256), ("audio_cnn", 4, 1024)):
+        net = getattr(WL, name)()
+        x, ws, qs = WL.quantized_network_tensors(net, N, WL.BASE_SEED + 300 + idx)
+        pn = S.PackedNetworkU8(net, ws, qs, dev)
+        xb = pn.pack_input(torch.from_numpy(x).to(dev))
+        o = torch.empty(pn.out_elems(N), dtype=torch.uint8, device=dev)
+        fn = lambda r: pn.run(xb, o, N)
+        spin(fn)
+        t = min(timed(fn, 100) for _ in range(3))
+        row = {"network": name, "batch": N, "ms": round(t * 1e3, 4), "images_per_s": round(N / t, 1),
+               "tops": round(2.0 * net.macs_per_image() * N / t / 1e12, 3), "layers": len(net.layers)}
+        if cpu:
+            from oracle import oracle_u8 as Q
+            n_s = min(N, 64)
+            Q.run_network(net, x[:2], ws, qs)
+            t0 = time.perf_counter()
+            ref = Q.run_network(net, x[:n_s], ws, qs)
+            dt = time.perf_counter() - t0
+            L = net.layers[-1]
+            got = o.cpu().numpy()[:n_s * L.Co].reshape(n_s, L.Co)
+            row["oracle"] = {"images_per_s": round(n_s / dt, 1), "cores": len(os.sched_getaffinity(0)),
+                             "sample": "first %d images, one pass of %.2f s" % (n_s, dt),
+                             "codes_equal": bool((got == ref.reshape(n_s, L.Co)).all())}
+        out.append(row)
+    return out
 
 
 def networks(S, WL, torch, dev, timed):

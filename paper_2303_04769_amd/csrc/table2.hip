@@ -41,22 +41,29 @@ __global__ void __launch_bounds__(kBlock) batchnorm_kernel(const float *__restri
     }
 }
 
-// out[n][cb][oh][ow][:] = in[n][cb][oh / fh][ow / fw][:]; one lane per VEC output floats.
+// out[n][cb][oh][ow][:] = in[n][cb][oh / fh][ow / fw][:]. One lane per VEC input floats: the value is read once
+// (streaming load) and written fh * fw times (streaming stores); index arithmetic in 32 bits by launch constants.
 template <int VEC>
-__global__ void __launch_bounds__(kBlock) upsample_kernel(const float *__restrict__ in, float *__restrict__ out, size_t n_vec,
-                                                          int H, int W, int fh, int fw, int Cb)
+__global__ void __launch_bounds__(kBlock) upsample_kernel(const float *__restrict__ in, float *__restrict__ out, unsigned n_vec,
+                                                          int W, int fh, int fw, int Cb, FastDiv by_per_px, FastDiv by_W)
 {
-    const size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    const unsigned v = blockIdx.x * kBlock + threadIdx.x;
     if (v >= n_vec) return;
-    const int Ho = H * fh, Wo = W * fw, per_px = Cb / VEC;
-    size_t t = v;
-    const int q = (int)(t % per_px); t /= per_px;
-    const int ow = (int)(t % Wo); t /= Wo;
-    const int oh = (int)(t % Ho);
-    const size_t plane = t / Ho;                     // n * nCb + cb
-    const size_t src = ((plane * H + oh / fh) * W + ow / fw) * Cb + (size_t)q * VEC;
-    if (VEC == 4) *reinterpret_cast<floatx4 *>(out + v * 4) = *reinterpret_cast<const floatx4 *>(in + src);
-    else out[v] = in[src];
+    const int per_px = Cb / VEC;
+    const int px = by_per_px.div((int)v), q = (int)v - px * per_px;          // px: pixel over (plane, row, column)
+    const int row = by_W.div(px), w = px - row * W;                          // row: over (plane, image row)
+    const size_t Wo = (size_t)W * fw;
+    float *o = out + (((size_t)row * fh) * Wo + (size_t)w * fw) * Cb + q * VEC;
+    if (VEC == 4) {
+        const floatx4 x = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(in) + v);
+        for (int dy = 0; dy < fh; ++dy)
+            for (int dx = 0; dx < fw; ++dx)
+                __builtin_nontemporal_store(x, reinterpret_cast<floatx4 *>(o + ((size_t)dy * Wo + dx) * Cb));
+    } else {
+        const float x = in[v];
+        for (int dy = 0; dy < fh; ++dy)
+            for (int dx = 0; dx < fw; ++dx) o[((size_t)dy * Wo + dx) * Cb] = x;
+    }
 }
 
 struct GroupArgs {
@@ -123,16 +130,16 @@ hipError_t launch_batchnorm(const float *in, const float *scale, const float *sh
 
 hipError_t launch_upsample(const float *in, float *out, int N, int C, int H, int W, int fh, int fw, int Cb, hipStream_t s)
 {
-    const size_t total = (size_t)N * C * H * fh * W * fw;
+    const size_t total = (size_t)N * C * H * W;                  // input elements (< 2^31: checked by the caller)
     const bool vec = Cb % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out) & 15u) == 0);
-    if (vec) {
-        const size_t n_vec = total / 4;
-        hipLaunchKernelGGL((upsample_kernel<4>), dim3((unsigned)((n_vec + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, out, n_vec,
-                           H, W, fh, fw, Cb);
-    } else {
-        hipLaunchKernelGGL((upsample_kernel<1>), dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, out, total,
-                           H, W, fh, fw, Cb);
-    }
+    const int per_px = vec ? Cb / 4 : Cb;
+    const unsigned n = (unsigned)(vec ? total / 4 : total);
+    if (vec)
+        hipLaunchKernelGGL((upsample_kernel<4>), dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, in, out, n, W, fh, fw, Cb,
+                           make_fastdiv(per_px), make_fastdiv(W));
+    else
+        hipLaunchKernelGGL((upsample_kernel<1>), dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, in, out, n, W, fh, fw, Cb,
+                           make_fastdiv(per_px), make_fastdiv(W));
     return hipGetLastError();
 }
 
