@@ -41,29 +41,26 @@ __global__ void __launch_bounds__(kBlock) batchnorm_kernel(const float *__restri
     }
 }
 
-// out[n][cb][oh][ow][:] = in[n][cb][oh / fh][ow / fw][:]. One lane per VEC input floats: the value is read once
-// (streaming load) and written fh * fw times (streaming stores); index arithmetic in 32 bits by launch constants.
+// out[n][cb][oh][ow][:] = in[n][cb][oh / fh][ow / fw][:]. One lane per VEC output floats, so a wave's stores are one
+// contiguous run of the output (streaming); the copies of an input pixel along a row are neighbouring lanes (one
+// request to the cache), the copies along a column come from L2. Index arithmetic in 32 bits by launch constants.
+struct UpsampleDivs { FastDiv per_px, Wo, Ho, fw, fh; };
+
 template <int VEC>
 __global__ void __launch_bounds__(kBlock) upsample_kernel(const float *__restrict__ in, float *__restrict__ out, unsigned n_vec,
-                                                          int W, int fh, int fw, int Cb, FastDiv by_per_px, FastDiv by_W)
+                                                          int H, int W, int Cb, UpsampleDivs d)
 {
     const unsigned v = blockIdx.x * kBlock + threadIdx.x;
     if (v >= n_vec) return;
-    const int per_px = Cb / VEC;
-    const int px = by_per_px.div((int)v), q = (int)v - px * per_px;          // px: pixel over (plane, row, column)
-    const int row = by_W.div(px), w = px - row * W;                          // row: over (plane, image row)
-    const size_t Wo = (size_t)W * fw;
-    float *o = out + (((size_t)row * fh) * Wo + (size_t)w * fw) * Cb + q * VEC;
-    if (VEC == 4) {
-        const floatx4 x = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(in) + v);
-        for (int dy = 0; dy < fh; ++dy)
-            for (int dx = 0; dx < fw; ++dx)
-                __builtin_nontemporal_store(x, reinterpret_cast<floatx4 *>(o + ((size_t)dy * Wo + dx) * Cb));
-    } else {
-        const float x = in[v];
-        for (int dy = 0; dy < fh; ++dy)
-            for (int dx = 0; dx < fw; ++dx) o[((size_t)dy * Wo + dx) * Cb] = x;
-    }
+    const int per_px = Cb / VEC, Wo = (int)d.Wo.d, Ho = (int)d.Ho.d;
+    const int opx = d.per_px.div((int)v), q = (int)v - opx * per_px;        // output pixel over (plane, row, column)
+    const int orow = d.Wo.div(opx), ow = opx - orow * Wo;                    // output row over (plane, row)
+    const int plane = d.Ho.div(orow), oh = orow - plane * Ho;
+    const size_t src = (((size_t)plane * H + d.fh.div(oh)) * W + d.fw.div(ow)) * Cb + q * VEC;
+    if (VEC == 4)
+        __builtin_nontemporal_store(*reinterpret_cast<const floatx4 *>(in + src), reinterpret_cast<floatx4 *>(out) + v);
+    else
+        out[v] = in[src];
 }
 
 struct GroupArgs {
@@ -130,16 +127,13 @@ hipError_t launch_batchnorm(const float *in, const float *scale, const float *sh
 
 hipError_t launch_upsample(const float *in, float *out, int N, int C, int H, int W, int fh, int fw, int Cb, hipStream_t s)
 {
-    const size_t total = (size_t)N * C * H * W;                  // input elements (< 2^31: checked by the caller)
+    const size_t total = (size_t)N * C * H * fh * W * fw;         // output elements (< 2^31: checked by the caller)
     const bool vec = Cb % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out) & 15u) == 0);
-    const int per_px = vec ? Cb / 4 : Cb;
     const unsigned n = (unsigned)(vec ? total / 4 : total);
-    if (vec)
-        hipLaunchKernelGGL((upsample_kernel<4>), dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, in, out, n, W, fh, fw, Cb,
-                           make_fastdiv(per_px), make_fastdiv(W));
-    else
-        hipLaunchKernelGGL((upsample_kernel<1>), dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, in, out, n, W, fh, fw, Cb,
-                           make_fastdiv(per_px), make_fastdiv(W));
+    const UpsampleDivs d = {make_fastdiv(vec ? Cb / 4 : Cb), make_fastdiv(W * fw), make_fastdiv(H * fh), make_fastdiv(fw),
+                            make_fastdiv(fh)};
+    if (vec) hipLaunchKernelGGL((upsample_kernel<4>), dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, in, out, n, H, W, Cb, d);
+    else hipLaunchKernelGGL((upsample_kernel<1>), dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, in, out, n, H, W, Cb, d);
     return hipGetLastError();
 }
 
