@@ -22,27 +22,6 @@ namespace {
 
 typedef int intx4 __attribute__((ext_vector_type(4)));
 
-// q.amax > 0: sums beyond +-amax saturate the output anyway (|amax * mult / 2^shift| >= 512) and within it the
-// scaled value fits 32 bits, so one clamp of the sum replaces 64-bit compares and selects after the product
-// (the host derives amax; 0 = scale too large for that, take the wide path). Same codes either way.
-__device__ __forceinline__ int requant(int acc, const QuantParams &q)
-{
-    if (q.amax > 0) {
-        const int c = acc < -q.amax ? -q.amax : (acc > q.amax ? q.amax : acc);
-        long v = (long)c * (long)q.mult;
-        if (q.shift > 0) v = (v + (1L << (q.shift - 1))) >> q.shift;
-        int r = (int)v + q.zy;
-        r = r < q.lo ? q.lo : r;
-        return r > q.hi ? q.hi : r;
-    }
-    long v = (long)acc * (long)q.mult;
-    if (q.shift > 0) v = (v + (1L << (q.shift - 1))) >> q.shift;
-    v += q.zy;
-    v = v < q.lo ? q.lo : v;
-    v = v > q.hi ? q.hi : v;
-    return (int)v;
-}
-
 struct QConvArgs {
     const unsigned char *in, *filt;
     unsigned char *out;
@@ -545,7 +524,6 @@ __global__ void __launch_bounds__(256) relu_u8_kernel(const unsigned char *in, u
     if (i < n) out[i] = in[i] > z ? in[i] : (unsigned char)z;
 }
 
-typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
 typedef unsigned short ushortx2 __attribute__((ext_vector_type(2)));
 
 // Byte-wise unsigned maximum of two words, as two packed 16-bit maxima over the even and the odd bytes.
@@ -742,6 +720,7 @@ hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, 
     a.kh = g.kh; a.kw = g.kw; a.stride = g.stride; a.pt = g.pt; a.pl = g.pl;
     a.mode = mode;
     a.q = q;
+    if (mode == 0 && dw_dpp_u8_eligible(g, q, in, filt, out)) return launch_dw_dpp_u8(in, filt, out, g, q, s);
     if (mode == 0 && g.Cib == 16 && g.kh == 3 && g.kw == 3 &&
         ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 3u) == 0) && (size_t)g.N * a.nCb <= 65535) {
         QDw3Args d;

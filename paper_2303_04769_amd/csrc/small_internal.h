@@ -76,6 +76,28 @@ __device__ __forceinline__ void wait_vmcnt()
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
 
+// Lane shifts over rows of 16 lanes (DPP): lane l reads lane l - 1 (kRowShr1) or l + 1 (kRowShl1) of its row; zero is
+// shifted in at the row's ends. The depthwise kernels take a window's left and right neighbours this way.
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+constexpr int kRowShr1 = 0x111;
+constexpr int kRowShl1 = 0x101;
+template <int CTRL>
+__device__ __forceinline__ float lane_shift1(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ __forceinline__ floatx4 lane_shift(floatx4 v)
+{
+    const float x = v.x, y = v.y, z = v.z, w = v.w;      // (scalars first: the builtin takes values, not vector elements)
+    return floatx4{lane_shift1<CTRL>(x), lane_shift1<CTRL>(y), lane_shift1<CTRL>(z), lane_shift1<CTRL>(w)};
+}
+// Buffer-descriptor addressing (raw buffers over a whole tensor): an offset at or beyond the descriptor's size reads
+// zeros and drops stores, which serves as a branch-free mask. kBeyond: an offset no tensor of less than 2 GiB reaches.
+constexpr unsigned kBeyond = 0x80000000u;
+constexpr int kRawBuffer = 0x00020000;         // descriptor word 3: untyped 32-bit data, no swizzle, no stride
+constexpr int kNonTemporal = 2;
+
 // Epilogue fused into the convolution's STORE phase (the paper's "abstract fused layer" direction).
 // ADD: accumulate onto the tensor `res` (same layout as out). BN: y = y * scale[c] + shift[c] first (batch normalization
 // folded behind the reduction; parameters: scale[0 .. C) then shift[0 .. C), 16-byte aligned). Order: BN, ADD, RELU.
@@ -200,6 +222,27 @@ hipError_t launch_group_conv(const float *in, const float *filt, float *out, con
 // y = clamp(zy + ((int64)acc * mult + 2^(shift-1)) >> shift, lo, hi) (no rounding term when shift == 0).
 // amax: host-derived clamp of the sum that makes the 32-bit requantization path exact (0 = not available).
 struct QuantParams { int zx, zw, zy, mult, shift, lo, hi, amax; };
+// q.amax > 0: sums beyond +-amax saturate the output anyway (|amax * mult / 2^shift| >= 512) and within it the
+// scaled value fits 32 bits, so one clamp of the sum replaces 64-bit compares and selects after the product
+// (the host derives amax; 0 = scale too large for that, take the wide path). Same codes either way.
+__device__ __forceinline__ int requant(int acc, const QuantParams &q)
+{
+    if (q.amax > 0) {
+        const int c = acc < -q.amax ? -q.amax : (acc > q.amax ? q.amax : acc);
+        long v = (long)c * (long)q.mult;
+        if (q.shift > 0) v = (v + (1L << (q.shift - 1))) >> q.shift;
+        int r = (int)v + q.zy;
+        r = r < q.lo ? q.lo : r;
+        return r > q.hi ? q.hi : r;
+    }
+    long v = (long)acc * (long)q.mult;
+    if (q.shift > 0) v = (v + (1L << (q.shift - 1))) >> q.shift;
+    v += q.zy;
+    v = v < q.lo ? q.lo : v;
+    v = v > q.hi ? q.hi : v;
+    return (int)v;
+}
+
 hipError_t launch_pack_u8(const unsigned char *nchw, unsigned char *blk, int N, int C, int H, int W, int Cb, bool unpack,
                           hipStream_t s);
 hipError_t launch_pack_filter_u8(const unsigned char *oihw, unsigned char *blk, int Co, int Ci, int kh, int kw, int Cob,
@@ -216,6 +259,10 @@ hipError_t launch_filter_sums_u8(const unsigned char *filt, int *sums, int Co, i
 hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
                             int mode, const QuantParams &q, hipStream_t s);
 hipError_t launch_relu_u8(const unsigned char *in, unsigned char *out, size_t n, int z, hipStream_t s);
+// quantized depthwise 3x3, stride 1, padding 1, 16-byte blocks, 4-byte aligned pointers (window_dpp_u8.hip)
+bool dw_dpp_u8_eligible(const LayerGeom &g, const QuantParams &q, const void *in, const void *filt, const void *out);
+hipError_t launch_dw_dpp_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
+                            const QuantParams &q, hipStream_t s);
 // y = clamp(zy + floor(((a - za) mult_a + (b - zb) mult_b + 2^(shift-1)) / 2^shift), lo, hi); out may be a or b
 struct AddQuantParams { int za, zb, zy, mult_a, mult_b, shift, lo, hi; };
 hipError_t launch_add_u8(const unsigned char *a, const unsigned char *b, unsigned char *out, size_t n, const AddQuantParams &q,

@@ -15,26 +15,26 @@ constexpr int kBlock = 256;
 template <int VEC>
 __global__ void __launch_bounds__(kBlock) batchnorm_kernel(const float *__restrict__ in, const float *__restrict__ scale,
                                                            const float *__restrict__ shift, float *__restrict__ out,
-                                                           size_t n_vec, int Cb, int nCb, FastDiv dPlane, int relu)
+                                                           unsigned n_vec, int Cb, int nCb, FastDiv by_plane, FastDiv by_nCb,
+                                                           FastDiv by_Cb, int relu)
 {
-    const size_t v = (size_t)blockIdx.x * kBlock + threadIdx.x;
+    const unsigned v = blockIdx.x * kBlock + threadIdx.x;
     if (v >= n_vec) return;
-    const size_t e = v * VEC;
-    // plane index and position inside the plane; planes hold HW * Cb elements (< 2^31, checked by the caller)
-    const size_t plane_elems = dPlane.d;
-    const size_t plane = e / plane_elems;
-    const int within = (int)(e - plane * plane_elems);
-    const int c = (int)(plane % (size_t)nCb) * Cb + within % Cb;
+    const int e = (int)v * VEC;                                  // element index (< 2^31, checked by the caller)
+    // plane index and position inside the plane (planes hold HW * Cb elements): 32-bit divisions by launch constants
+    const int plane = by_plane.div(e), within = e - plane * (int)by_plane.d;
+    const int c = (plane - by_nCb.div(plane) * nCb) * Cb + (within - by_Cb.div(within) * Cb);
     if (VEC == 4) {
-        const floatx4 x = *reinterpret_cast<const floatx4 *>(in + e);
+        const floatx4 x = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(in + e));
+        const floatx4 sc = *reinterpret_cast<const floatx4 *>(scale + c), sh = *reinterpret_cast<const floatx4 *>(shift + c);
         floatx4 y;
-        y.x = fmaf(x.x, scale[c + 0], shift[c + 0]); y.y = fmaf(x.y, scale[c + 1], shift[c + 1]);
-        y.z = fmaf(x.z, scale[c + 2], shift[c + 2]); y.w = fmaf(x.w, scale[c + 3], shift[c + 3]);
+        y.x = fmaf(x.x, sc.x, sh.x); y.y = fmaf(x.y, sc.y, sh.y);
+        y.z = fmaf(x.z, sc.z, sh.z); y.w = fmaf(x.w, sc.w, sh.w);
         if (relu) {
             y.x = y.x > 0.f ? y.x : 0.f; y.y = y.y > 0.f ? y.y : 0.f;
             y.z = y.z > 0.f ? y.z : 0.f; y.w = y.w > 0.f ? y.w : 0.f;
         }
-        *reinterpret_cast<floatx4 *>(out + e) = y;
+        __builtin_nontemporal_store(y, reinterpret_cast<floatx4 *>(out + e));
     } else {
         const float y = fmaf(in[e], scale[c], shift[c]);
         out[e] = relu ? (y > 0.f ? y : 0.f) : y;
@@ -112,16 +112,16 @@ hipError_t launch_batchnorm(const float *in, const float *scale, const float *sh
                             int Cb, hipStream_t s, bool relu)
 {
     const size_t total = (size_t)N * C * H * W;
-    const FastDiv plane = make_fastdiv(H * W * Cb);
-    const bool vec = Cb % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out) & 15u) == 0);
-    if (vec) {
-        const size_t n_vec = total / 4;
-        hipLaunchKernelGGL((batchnorm_kernel<4>), dim3((unsigned)((n_vec + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, scale,
-                           shift, out, n_vec, Cb, C / Cb, plane, relu ? 1 : 0);
-    } else {
-        hipLaunchKernelGGL((batchnorm_kernel<1>), dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, in, scale,
-                           shift, out, total, Cb, C / Cb, plane, relu ? 1 : 0);
-    }
+    const FastDiv plane = make_fastdiv(H * W * Cb), by_nCb = make_fastdiv(C / Cb), by_Cb = make_fastdiv(Cb);
+    // float4 accesses: blocks of a multiple of four channels, and scale / shift 16-byte aligned as well
+    const bool vec = Cb % 4 == 0 && ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)scale | (uintptr_t)shift) & 15u) == 0);
+    const unsigned n = (unsigned)(vec ? total / 4 : total);
+    if (vec)
+        hipLaunchKernelGGL((batchnorm_kernel<4>), dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, in, scale, shift, out, n, Cb,
+                           C / Cb, plane, by_nCb, by_Cb, relu ? 1 : 0);
+    else
+        hipLaunchKernelGGL((batchnorm_kernel<1>), dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, in, scale, shift, out, n, Cb,
+                           C / Cb, plane, by_nCb, by_Cb, relu ? 1 : 0);
     return hipGetLastError();
 }
 

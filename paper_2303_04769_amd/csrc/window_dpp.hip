@@ -29,8 +29,6 @@ namespace small {
 
 namespace {
 
-typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-
 struct DppArgs {
     const float *in;
     const float *filt;     // [C/16][3][3][16]
@@ -45,23 +43,6 @@ struct DppArgs {
     unsigned bytes;        // of the input = of the output tensor (< 2^31)
 };
 
-constexpr unsigned kBeyond = 0x80000000u;      // an offset no tensor this kernel takes reaches
-constexpr int kRawBuffer = 0x00020000;         // descriptor word 3: untyped 32-bit data, no swizzle, no stride
-constexpr int kNonTemporal = 2;
-
-template <int CTRL>
-__device__ __forceinline__ float lane_shift1(float v)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
-}
-template <int CTRL>
-__device__ __forceinline__ floatx4 lane_shift(floatx4 v)
-{
-    const float x = v.x, y = v.y, z = v.z, w = v.w;      // (scalars first: the builtin takes values, not vector elements)
-    return floatx4{lane_shift1<CTRL>(x), lane_shift1<CTRL>(y), lane_shift1<CTRL>(z), lane_shift1<CTRL>(w)};
-}
-constexpr int kRowShr1 = 0x111;    // lane l reads lane l - 1 of its row of 16 (lane 0: zero)
-constexpr int kRowShl1 = 0x101;    // lane l reads lane l + 1 (lane 15: zero)
 
 // SEG: lanes per plane in a row of 16 lanes (16: one plane, bands of 14 output pixels with a halo lane on each
 // side; 8: two planes of at most 7 pixels, each behind one zero lane).

@@ -374,3 +374,48 @@ def test_network_table_errors():
     with pytest.raises(S.SmallError) as e:
         pn.workspace(2)
     assert e.value.code == 7
+
+
+DW_LANES_U8_CASES = [  # N, C, H, W, zx, zw: 3x3, stride 1, padding 1, 16-byte blocks
+    (3, 64, 56, 56, 120, 131),          # four bands of 14 columns, eight row strips
+    (5, 128, 28, 28, 128, 128),
+    (9, 256, 14, 14, 0, 255),           # one band; zero points at the ends of the code range
+    (11, 512, 7, 7, 255, 0),            # two planes side by side in a row of 16 lanes
+    (3, 16, 5, 5, 17, 201),             # ... an odd number of planes
+    (5, 48, 7, 3, 130, 120),
+    (1, 16, 1, 1, 128, 128),
+    (2, 32, 1, 40, 100, 60),
+    (4, 48, 61, 63, 7, 250),
+    (7, 32, 33, 17, 128, 128),
+    (2, 32, 70, 100, 200, 100),
+]
+
+
+@pytest.mark.parametrize("case", DW_LANES_U8_CASES)
+def test_depthwise_lane_shift(case):
+    """Quantized depthwise 3x3 with stride 1 and padding 1: the kernel that keeps rows in registers as exact floats
+    and takes the horizontal neighbours from the next lanes; random filters, zero points away from 128 (the padding
+    reads as zx, lanes at a unit's end shift in zero), a ReLU clamp in the middle of the codes."""
+    N, C, H, W, zx, zw = case
+    r = _rng(12)
+    x, w = WL.u8_codes(r, (N, C, H, W)), WL.u8_codes(r, (C, 1, 3, 3))
+    pad = (1, 1, 1, 1)
+    q = _quant_for(Q.dwconv2d_acc(x, w, 1, pad, zx, zw), zx, zw, relu=True)
+    ref = Q.dwconv2d(x, w, 1, pad, q)
+    assert len(np.unique(ref)) > 8
+    g = Guarded8(ref.size)
+    S.small_dwconv2d_u8(dev8(Q.pack(x, 16)), dev8(Q.pack_dw_filter(w, 16)), g.t, N, C, H, W, 3, 3, 1, pad, 16, q)
+    _same(Q.unpack(g.check(), ref.shape, 16), ref, f"dw u8 lanes {case}")
+
+
+@pytest.mark.parametrize("mult,shift", [(1 << 20, 0), ((1 << 31) - 1, 0), (1, 31), (0, 5), ((1 << 31) - 1, 31), (3, 1)])
+def test_depthwise_extreme_scales(mult, shift):
+    """Scales from 'everything saturates' to 'everything rounds to the zero point': whichever requantization path the
+    layer takes (the clamped one or the wide one), the codes are the oracle's."""
+    r = _rng(13)
+    x, w = WL.u8_codes(r, (3, 32, 9, 20)), WL.u8_codes(r, (32, 1, 3, 3))
+    q = Q.Quant(zx=99, zw=140, zy=77, mult=mult, shift=shift, lo=3, hi=250)
+    ref = Q.dwconv2d(x, w, 1, (1, 1, 1, 1), q)
+    g = Guarded8(ref.size)
+    S.small_dwconv2d_u8(dev8(Q.pack(x, 16)), dev8(Q.pack_dw_filter(w, 16)), g.t, 3, 32, 9, 20, 3, 3, 1, (1, 1, 1, 1), 16, q)
+    _same(Q.unpack(g.check(), ref.shape, 16), ref, f"dw u8 scale {mult} / 2^{shift}")
