@@ -153,6 +153,41 @@ __global__ void __launch_bounds__(kBlock) pack16(float *__restrict__ plain_base,
     }
 }
 
+// 16-channel blocks with a multiple of four pixels per plane: no LDS. A wave moves a tile of 64 pixels x 16 channels
+// (4 KB): lane (r, g) holds channels 4r .. 4r + 3 of pixels 4g .. 4g + 3. On the plain side that is four 16-byte
+// accesses (one per channel: four consecutive pixels of its row), on the blocked side four 16-byte accesses (one per
+// pixel: its channel quad r); between the two lies a 4 x 4 transposition inside the lane's registers, i.e. nothing.
+// Every access of a wave covers whole 64-byte (blocked) or 256-byte (plain) runs.
+template <bool kUnpack>
+__global__ void __launch_bounds__(kBlock) pack16_reg(float *__restrict__ plain_base, float *__restrict__ blk_base, int C, int HW,
+                                                     int tiles_per_plane, int n_wave_tiles, FastDiv by_tiles, FastDiv by_nCb)
+{
+    const int wave_tile = (int)blockIdx.x * (kBlock / 64) + (int)(threadIdx.x >> 6);
+    if (wave_tile >= n_wave_tiles) return;
+    const int plane = by_tiles.div(wave_tile), tile = wave_tile - plane * tiles_per_plane;       // plane = n * nCb + cb
+    const int nCb = C >> 4;
+    const int n = by_nCb.div(plane), cb = plane - n * nCb;
+    const int lane = threadIdx.x & 63, r = lane & 3, g = lane >> 2;
+    const int p = tile * 64 + g * 4;                            // first of this lane's four pixels
+    if (p >= HW) return;                                        // (HW is a multiple of 4: all four or none)
+    float *plain = plain_base + ((size_t)n * C + (size_t)cb * 16 + 4 * r) * HW + p;
+    float *blk = blk_base + ((size_t)plane * HW + p) * 16 + 4 * r;
+    floatx4 v[4];
+    if (!kUnpack) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(plain + (size_t)i * HW));
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            __builtin_nontemporal_store(floatx4{v[0][j], v[1][j], v[2][j], v[3][j]}, reinterpret_cast<floatx4 *>(blk + j * 16));
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(blk + j * 16));
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_nontemporal_store(floatx4{v[0][i], v[1][i], v[2][i], v[3][i]}, reinterpret_cast<floatx4 *>(plain + (size_t)i * HW));
+    }
+}
+
 // Filters are packed once per network; one thread per blocked element.
 __global__ void __launch_bounds__(kBlock) pack_filter_kernel(const float *__restrict__ oihw, float *__restrict__ blk,
                                                               int Co, int Ci, int kh, int kw, int Cob, int Cib)
@@ -180,6 +215,18 @@ hipError_t launch_add(const float *a, const float *b, float *out, size_t n, hipS
 hipError_t launch_pack(const float *src, float *dst, int N, int C, int H, int W, int Cb, bool unpack, hipStream_t s)
 {
     const int HW = H * W;
+    if (Cb == 16 && HW % 4 == 0 && ((((uintptr_t)src | (uintptr_t)dst) & 15u) == 0)) {
+        const int tiles = (HW + 63) / 64;
+        const long waves = (long)N * (C / 16) * tiles;
+        const unsigned grid = (unsigned)((waves + kBlock / 64 - 1) / (kBlock / 64));
+        if (unpack)
+            hipLaunchKernelGGL(pack16_reg<true>, dim3(grid), dim3(kBlock), 0, s, dst, const_cast<float *>(src), C, HW, tiles,
+                               (int)waves, make_fastdiv(tiles), make_fastdiv(C / 16));
+        else
+            hipLaunchKernelGGL(pack16_reg<false>, dim3(grid), dim3(kBlock), 0, s, const_cast<float *>(src), dst, C, HW, tiles,
+                               (int)waves, make_fastdiv(tiles), make_fastdiv(C / 16));
+        return hipGetLastError();
+    }
     if (Cb == 16 && HW >= 64 && ((uintptr_t)(unpack ? src : dst) & 15u) == 0) {
         const dim3 grid16((unsigned)(N * (C / 16)), (unsigned)((HW + kPix16 - 1) / kPix16));
         if (unpack) hipLaunchKernelGGL(pack16<true>, grid16, dim3(kBlock), 0, s, dst, const_cast<float *>(src), C, HW);

@@ -21,7 +21,8 @@ def _blk(C):
 
 @pytest.mark.parametrize("N,C,H,W,Cb", [(2, 32, 5, 7, 16), (1, 3, 96, 96, 3), (3, 8, 9, 13, 8), (2, 1, 49, 10, 1),
                                          (1, 64, 1, 1, 16), (2, 10, 1, 1, 10), (1, 48, 17, 9, 16), (1, 12, 3, 70, 4),
-                                         (2, 32, 20, 20, 16), (1, 16, 16, 16, 16), (3, 64, 56, 56, 16), (2, 16, 8, 8, 16)])
+                                         (2, 32, 20, 20, 16), (1, 16, 16, 16, 16), (3, 64, 56, 56, 16), (2, 16, 8, 8, 16),
+                                         (5, 48, 14, 14, 16), (1, 16, 2, 2, 16), (3, 16, 2, 2, 16), (7, 32, 3, 4, 16), (2, 16, 50, 50, 16)])
 def test_pack_unpack_bit_exact(N, C, H, W, Cb):
     rng = np.random.default_rng(N * 1000 + C)
     x = rng.standard_normal((N, C, H, W)).astype(np.float32)
