@@ -290,7 +290,8 @@ int small_network_run_plain(const small_layer *layers, int n_layers, const float
  * accepts tables whose first layer only the run's own first-layer code can take from a plain tensor). Results
  * agree with the layer-by-layer kernels within the conv tolerance, not bit for bit (another summation order).
  * small_network_launches_at: the first layer of every launch that a run with these N, C0, H0, W0 and flags makes
- * (small_network_launches: the batch-independent list without image-resident runs). Host-only, no GPU needed. */
+ * (small_network_launches: the list that depends on the table alone: without image-resident runs and without the
+ * runs of depthwise + pointwise blocks below, which depend on the image size). Host-only, no GPU needed. */
 enum { SMALL_RUN_PLAIN_INPUT = 1, SMALL_RUN_RESIDENT_OFF = 2, SMALL_RUN_RESIDENT_ON = 4, SMALL_RUN_PLAIN_OUTPUT = 8 };
 int small_network_run_opt(const small_layer *layers, int n_layers, const float *in, float *out_blocked, void *workspace,
                           size_t workspace_bytes, int N, int C0, int H0, int W0, unsigned flags, void *stream);
@@ -314,6 +315,11 @@ int small_network_launches_at(const small_layer *layers, int n_layers, int N, in
  * depthwise result stays on the compute unit and its buffer is never written (allowed only when no later
  * layer reads that buffer before it is rewritten). The depthwise sum is then taken in a different order
  * than by small_dwconv2d: results agree within the tolerance of the two layers, not bit for bit.
+ * Two to eight such pairs in a row -- depthwise stride 1 with padding 1, 64 -> 64 or 128 -> 128 channels in every pair,
+ * each pair reading what the pair before wrote, images of at most 64 pixels --
+ * run in ONE kernel from the first pair's source to the last pair's destination: a workgroup keeps whole images on
+ * the compute unit through all pairs. Every buffer the table writes inside the run except that destination is
+ * never written (same liveness rule); the destination may be the run's own source buffer. Same tolerance.
  * A run of two to sixteen pointwise layers (SMALL_OP_DENSE on 1x1 images, unpadded stride-1 1x1 SMALL_OP_CONV;
  * at most 128 channels per tensor, in 16-channel blocks, or 8 channels in one 8-channel block for tensors
  * inside the run), each optionally followed by an in-place ReLU and each read only by the next, runs in one

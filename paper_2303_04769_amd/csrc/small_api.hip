@@ -767,6 +767,53 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
     return f;
 }
 
+// A run of depthwise + pointwise blocks from layer i on that one launch of dwpw_chain.hip can take: every block is a
+// pair plan_fusion already joins (depthwise 3x3, stride 1, padding 1 -> 1x1 convolution, in-place ReLUs folded), C -> C
+// channels, each block reading what the one before wrote. The launch writes the last block's destination only, so
+// every other buffer the table writes inside the run must be dead afterwards. Returns the number of blocks (0 or
+// >= 2); dw_idx / pw_idx: table indices, relu flags per block, *covered: layers of the run after layer i.
+int plan_dwpw_run(const small_layer *L, int nL, int i, int *dw_idx, int *pw_idx, int *dw_relu, int *pw_relu, int *covered)
+{
+    int n = 0, k = i, end = i;
+    const int C = L[i].Ci;
+    while (k < nL && n < kDwpwChainMaxBlocks) {
+        const small_layer &d = L[k];
+        if (d.op != SMALL_OP_DWCONV || d.Ci != C || d.Cib != 16 || d.kh != 3 || d.kw != 3 || d.stride != 1 || d.pad.t != 1 ||
+            d.pad.b != 1 || d.pad.l != 1 || d.pad.r != 1)
+            break;
+        const Fusion f = plan_fusion(L, nL, k);
+        if (!f.pw) break;
+        const small_layer &pw = L[k + f.pw];
+        if (pw.Co != C || pw.Cob != 16) break;
+        if (n > 0 && d.src != L[pw_idx[n - 1]].dst) break;
+        dw_idx[n] = k;
+        pw_idx[n] = k + f.pw;
+        dw_relu[n] = (f.epilogue & EPI_RELU) != 0;
+        pw_relu[n] = f.pw_relu;
+        ++n;
+        end = k + f.skip;
+        k = end + 1;
+    }
+    // shorten the run until everything it does not write is dead behind it
+    while (n >= 2) {
+        const int last = pw_idx[n - 1], T = L[last].dst;
+        const int after = last + 1 + pw_relu[n - 1];
+        bool ok = T != SMALL_BUF_IN;
+        for (int b = 0; b < n && ok; ++b) {
+            const int ids[2] = {L[dw_idx[b]].dst, L[pw_idx[b]].dst};
+            for (int id : ids)
+                if (id != T && !dead_from(L, nL, after, id)) ok = false;
+        }
+        // the run's input may be its output (each workgroup reads its images before it writes them), nothing else may
+        if (ok) {
+            *covered = after - 1 - i;
+            return n;
+        }
+        --n;
+    }
+    return 0;
+}
+
 // The convolution groups from layer i on that may run as one image-resident launch (resident.hip): fills rg
 // and the table index of every group's last layer, returns how many groups the launch takes (0: none).
 // shp: the shapes the logical buffers hold before layer i (indexed by id + 2).
@@ -1058,7 +1105,30 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                         fused_away = fu.skip;
                     }
                 }
-                if (l.op == SMALL_OP_DWCONV && res_n) {
+                // several such blocks in a row on small images: one launch for the whole run
+                int run_blocks = 0, run_dw[kDwpwChainMaxBlocks], run_pw[kDwpwChainMaxBlocks], run_dr[kDwpwChainMaxBlocks],
+                    run_pr[kDwpwChainMaxBlocks], run_covered = 0;
+                if (head && fu.pw && !res_n && l.op == SMALL_OP_DWCONV && g.Ho == a.H && g.Wo == a.W &&
+                    dwpw_chain_eligible(l.Ci, a.H, a.W) && in_elems * sizeof(float) < ((size_t)1 << 32)) {
+                    run_blocks = plan_dwpw_run(L, nL, i, run_dw, run_pw, run_dr, run_pr, &run_covered);
+                    if (run_blocks && run) {
+                        const float *rin = ptr(l.src);
+                        float *rout = ptr(L[run_pw[run_blocks - 1]].dst);
+                        uintptr_t bits = (uintptr_t)rin | (uintptr_t)rout;
+                        for (int b = 0; b < run_blocks; ++b) bits |= (uintptr_t)L[run_dw[b]].filt | (uintptr_t)L[run_pw[b]].filt;
+                        if ((bits & 15u) || (rin != rout && overlap(rin, in_elems, rout, in_elems))) run_blocks = 0;
+                    }
+                }
+                if (run_blocks) {
+                    fused_away = run_covered;
+                    if (launch) {
+                        DwpwChainBlock cb[kDwpwChainMaxBlocks];
+                        for (int b = 0; b < run_blocks; ++b)
+                            cb[b] = DwpwChainBlock{L[run_dw[b]].filt, L[run_pw[b]].filt, run_dr[b], run_pr[b]};
+                        rc = from_hip(launch_dwpw_chain(ptr(l.src), ptr(L[run_pw[run_blocks - 1]].dst), cb, run_blocks, N, l.Ci, a.H,
+                                                        a.W, s));
+                    }
+                } else if (l.op == SMALL_OP_DWCONV && res_n) {
                     if (launch) rc = from_hip(launch_resident(res_g, res_n, ptr(l.src), ptr(res_g[res_n - 1].dst), N, s));
                 } else if (l.op == SMALL_OP_DWCONV && fu.pw) {
                     const small_layer &pw = L[i + fu.pw];

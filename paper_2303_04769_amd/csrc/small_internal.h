@@ -210,6 +210,16 @@ bool chain_layer_eligible(int Ci, int Co, int Cib, int Cob);
 hipError_t launch_dense_chain(const float *in, float *out, const ChainLayer *layers, int n_layers, long M, int HW,
                               hipStream_t s);
 
+// A run of [depthwise 3x3 stride 1 padding 1 (+ ReLU)] -> [1x1 convolution (+ ReLU)] blocks, each C -> C channels
+// (C = 64 or 128, 16-channel blocks) on images of at most 128 pixels, in one launch (dwpw_chain.hip). out may be in
+// itself (a workgroup reads its images before it writes them) but may not overlap it otherwise; pointers 16-byte
+// aligned; tensors smaller than 4 GiB.
+constexpr int kDwpwChainMaxBlocks = 8;
+struct DwpwChainBlock { const float *dw, *pw; int dw_relu, pw_relu; };
+bool dwpw_chain_eligible(int C, int H, int W);
+hipError_t launch_dwpw_chain(const float *in, float *out, const DwpwChainBlock *blocks, int n_blocks, int N, int C, int H, int W,
+                             hipStream_t s);
+
 // Remaining Table 2 layers (table2.hip): y = x * scale[c] + shift[c]; nearest-neighbour upsampling by integer
 // factors; group convolution (geometry in g with g.Ci = all input channels, g.Co = G * K, g.Cib the activation block).
 hipError_t launch_batchnorm(const float *in, const float *scale, const float *shift, float *out, int N, int C, int H, int W,

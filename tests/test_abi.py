@@ -128,9 +128,13 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
             if L.w is not None:
                 to[k].filt = 0x1000
         plan = lambda N, flags=0: B.small_network_launches_at(to, N, other.C0, other.H0, other.W0, flags)
-        assert plan(512) == B.small_network_launches(to) and len(plan(256, B.SMALL_RUN_RESIDENT_ON)) < len(plan(512))
+        # layer by layer, except that consecutive depthwise + pointwise blocks on small images (known only with the
+        # geometry) are one launch: the five 128-channel blocks on 3x3 images (the audio CNN's 25x5 images are too large)
+        expect = B.small_network_launches(to) if other is a else [0, 2, 4, 6, 10, 14, 18, 22, 26, 46, 50, 54]
+        assert plan(512) == expect and set(expect) <= set(B.small_network_launches(to))
+        assert len(plan(256, B.SMALL_RUN_RESIDENT_ON)) < len(plan(512))
         # the audio CNN (0.27 M multiply-adds per layer) is taken in one round, where it measures a few percent faster
-        assert (plan(256) == [0]) == (other is a) and (plan(256) == B.small_network_launches(to)) == (other is not a)
+        assert (plan(256) == [0]) == (other is a) and (plan(256) == expect) == (other is not a)
     assert at(256, B.SMALL_RUN_PLAIN_INPUT) == [0] == at(2, B.SMALL_RUN_PLAIN_INPUT | B.SMALL_RUN_RESIDENT_ON)
     n = C.c_int(0)
     assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 16, None, C.byref(n)) == 2    # unknown flag

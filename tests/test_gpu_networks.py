@@ -884,3 +884,66 @@ def test_plain_output_is_the_unpacked_result(name, idx, N):
     with pytest.raises(S.SmallError) as e:
         pf.run_opt(pf.pack_input(dev(xf)), gf.t, 2, S.SMALL_RUN_PLAIN_OUTPUT)
     assert e.value.code == 7 and (gf.check() == np.float32(CANARY)).all()
+
+
+# ------------------------------------------------------------------ runs of depthwise + pointwise blocks in one launch
+
+def _dwpw_run_net(C, H, W, n_blocks, relus, alternate=True, tail=True):
+    """n_blocks pairs [depthwise 3x3 s1 p1 (+ReLU)] -> [1x1 conv (+ReLU)], C -> C; alternate: two buffers used in turn
+    (the pair's output goes back into the depthwise layer's source, as the stand-in networks do), else a fresh buffer
+    per layer; tail: a max pooling into OUT after the run (else the last pair writes OUT itself)."""
+    from workloads.nets import Layer, Network, IN, OUT
+    net = Network("dwpw_run", C, H, W)
+    p1, z = (1, 1, 1, 1), (0, 0, 0, 0)
+    src, k = IN, 0
+    for b in range(n_blocks):
+        dw_relu, pw_relu = relus[b % len(relus)]
+        d = 0 if (src != 0) else 1
+        if not alternate:
+            d = (2 * b) % 4
+        net.wshapes.append(((C, 1, 3, 3), 9))
+        net.layers.append(Layer("dw", C, C, H, W, 3, 3, 1, p1, src=src, dst=d, w=k)); k += 1
+        if dw_relu:
+            net.layers.append(Layer("relu", C, C, H, W, src=d, dst=d))
+        last = b + 1 == n_blocks and not tail
+        if alternate:
+            t = OUT if last else (src if src != IN else 1 - d)
+        else:
+            t = OUT if last else (2 * b + 1) % 4
+        net.wshapes.append(((C, C, 1, 1), C))
+        net.layers.append(Layer("conv", C, C, H, W, 1, 1, 1, z, src=d, dst=t, w=k)); k += 1
+        if pw_relu:
+            net.layers.append(Layer("relu", C, C, H, W, src=t, dst=t))
+        src = t
+    if tail:
+        net.layers.append(Layer("maxpool", C, C, H, W, 1, 1, 1, z, src=src, dst=OUT))
+    return net
+
+
+DWPW_RUN_CASES = [  # C, H, W, N, blocks, (dw relu, pw relu) pattern, alternate buffers, tail
+    (128, 3, 3, 256, 5, [(1, 1)], True, True),            # the depthwise-separable CNN's tail: one image per workgroup
+    (128, 3, 3, 1000, 5, [(1, 1)], True, True),           # three images per workgroup, the last workgroup with one
+    (128, 3, 3, 4100, 3, [(1, 0), (0, 1)], True, False),  # seven images per workgroup; ReLUs missing here and there; ends in OUT
+    (128, 3, 3, 1, 8, [(1, 1)], True, True),              # batch 1, the longest run
+    (64, 6, 6, 37, 2, [(1, 1)], True, True),              # four channel blocks: two waves share a block; 36 of 64 slots
+    (64, 5, 3, 300, 4, [(0, 0)], False, True),            # 15 pixels: two slots groups... a fresh buffer per layer, no ReLU at all
+    (128, 8, 8, 9, 3, [(1, 1)], True, True),              # an image fills all 64 slots
+    (64, 7, 7, 5, 2, [(1, 1)], False, False),             # 49 of 64 slots
+    (128, 1, 1, 77, 4, [(1, 1)], True, True),             # one pixel: only the centre tap exists
+    (64, 2, 30, 11, 3, [(1, 1)], True, True),             # 60 pixels in two long rows
+]
+
+
+@pytest.mark.parametrize("case", DWPW_RUN_CASES)
+def test_depthwise_pointwise_runs(case):
+    """Several depthwise + pointwise blocks on small images are one launch (asserted through the launch list); the
+    result agrees with the oracle's layer-by-layer chain for every image, within the tolerance of the longest reduction."""
+    C, H, W, N, n_blocks, relus, alternate, tail = case
+    net = _dwpw_run_net(C, H, W, n_blocks, relus, alternate, tail)
+    x, ws = WL.network_tensors(net, N, 8800 + C + N)
+    pn = S.PackedNetwork(net, ws, DEV)
+    heads = pn.launches_at(N, S.SMALL_RUN_RESIDENT_OFF)
+    assert heads == ([0, len(net.layers) - 1] if tail else [0]), heads
+    ref = O.run_network(net, x, ws)
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF)
+    assert_close(got, ref.reshape(got.shape), C, f"dwpw run {case}")
