@@ -332,12 +332,87 @@ hipError_t launch_wn(const DwPwArgs &a, const DwPwPlan &p, hipStream_t s)
     }
 }
 
+// Eight input channels in one 8-channel block -> sixteen output channels: too little reduction for the matrix cores
+// (K = 8), so the block runs on the vector units: a lane owns one output pixel, gathers its window (two float4 per
+// tap, taps outside the image skipped), forms the eight depthwise sums, applies the ReLU and multiplies them with the
+// 8 x 16 pointwise filter; both filters are broadcast from LDS. in [N][1][H][W][8], dw [1][3][3][8], pw
+// [1][1][1][1][8][16], out [N][1][Ho][Wo][16].
+struct DwPw8Args {
+    const float *in, *dwf, *pwf;
+    float *out;
+    int H, W, Ho, Wo, stride, pt, pl;
+    int total;            // output pixels over all images
+    int relu_mid, relu_out;
+    FastDiv by_Wo, by_Ho;
+};
+
+__global__ void __launch_bounds__(256) dwpw8_16(DwPw8Args a)
+{
+    __shared__ floatx4 w_dw[18], w_pw[32];
+    if (threadIdx.x < 18) w_dw[threadIdx.x] = reinterpret_cast<const floatx4 *>(a.dwf)[threadIdx.x];
+    else if (threadIdx.x >= 64 && threadIdx.x < 96) w_pw[threadIdx.x - 64] = reinterpret_cast<const floatx4 *>(a.pwf)[threadIdx.x - 64];
+    __syncthreads();
+    const int m = (int)blockIdx.x * 256 + (int)threadIdx.x;
+    if (m >= a.total) return;
+    const int t = a.by_Wo.div(m), ow = m - t * a.Wo;
+    const int n = a.by_Ho.div(t), oh = t - n * a.Ho;
+    const floatx4 *img = reinterpret_cast<const floatx4 *>(a.in) + (size_t)n * a.H * a.W * 2;
+    // all eighteen loads are issued unconditionally (a tap outside the image reads a valid pixel and is dropped by a
+    // zero factor below: loads under a divergent branch would be waited for one by one)
+    floatx4 v[18];
+    float on[9];
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky) {
+        const int ih = oh * a.stride + ky - a.pt;
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx) {
+            const int iw = ow * a.stride + kx - a.pl;
+            const bool inside = ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            const floatx4 *px = img + (inside ? (ih * a.W + iw) * 2 : 0);
+            v[(ky * 3 + kx) * 2] = px[0];
+            v[(ky * 3 + kx) * 2 + 1] = px[1];
+            on[ky * 3 + kx] = inside ? 1.f : 0.f;
+        }
+    }
+    floatx4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};       // depthwise sums of channels 0..3, 4..7
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        lo += v[2 * t] * (w_dw[2 * t] * on[t]);
+        hi += v[2 * t + 1] * (w_dw[2 * t + 1] * on[t]);
+    }
+    if (a.relu_mid) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            lo[c] = lo[c] > 0.f ? lo[c] : 0.f;
+            hi[c] = hi[c] > 0.f ? hi[c] : 0.f;
+        }
+    }
+    floatx4 acc[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int ci = 0; ci < 8; ++ci) {
+        const float x = ci < 4 ? lo[ci] : hi[ci - 4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] += w_pw[ci * 4 + k] * x;
+    }
+    floatx4 *o = reinterpret_cast<floatx4 *>(a.out) + (size_t)m * 4;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        floatx4 v = acc[k];
+        if (a.relu_out) {
+            v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
+            v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
+        }
+        __builtin_nontemporal_store(v, o + k);
+    }
+}
+
 }  // namespace
 
 bool dwpw_eligible(int C, int Co, int Cb, int Cob_pw, int kh, int kw, int stride, int pw_kh, int pw_kw, int pw_stride)
 {
-    if (Cb != 16 || Cob_pw != 16 || kh != 3 || kw != 3 || stride < 1) return false;
-    if (pw_kh != 1 || pw_kw != 1 || pw_stride != 1 || C % 16 || Co % 16) return false;
+    if (kh != 3 || kw != 3 || stride < 1 || pw_kh != 1 || pw_kw != 1 || pw_stride != 1) return false;
+    if (C == 8 && Cb == 8 && Co == 16 && Cob_pw == 16) return true;        // the vector-unit kernel
+    if (Cb != 16 || Cob_pw != 16 || C % 16 || Co % 16) return false;
     // resident filters + the smallest ring must fit
     const size_t fixed = (size_t)(C / 16) * (std::min(4, Co / 16) * 1024 + 9 * 64);
     return fixed + 2 * (4 * 1024 + 16) + 256 <= kDwPwMaxLds;
@@ -345,6 +420,7 @@ bool dwpw_eligible(int C, int Co, int Cb, int Cob_pw, int kh, int kw, int stride
 
 bool dwpw_geom_ok(const LayerGeom &g, int Co)
 {
+    if (g.Cib == 8) return (size_t)g.N * g.Ho * g.Wo < ((size_t)1 << 31) && (size_t)g.N * g.H * g.W * 8 < ((size_t)1 << 31);
     // per-lane 32-bit byte offsets span the images of a tile group
     const bool small_enough = (size_t)g.N * g.Ci * g.H * g.W < ((size_t)1 << 30) &&
                               (size_t)64 * g.Ci * g.H * g.W * 4 < ((size_t)1 << 31) &&
@@ -355,6 +431,16 @@ bool dwpw_geom_ok(const LayerGeom &g, int Co)
 hipError_t launch_dwpw(const float *in, const float *dw_filt, const float *pw_filt, float *out, const LayerGeom &g, int Co,
                        int relu_mid, int relu_out, hipStream_t s)
 {
+    if (g.Cib == 8) {
+        DwPw8Args b;
+        b.in = in; b.dwf = dw_filt; b.pwf = pw_filt; b.out = out;
+        b.H = g.H; b.W = g.W; b.Ho = g.Ho; b.Wo = g.Wo; b.stride = g.stride; b.pt = g.pt; b.pl = g.pl;
+        b.total = g.N * g.Ho * g.Wo;
+        b.relu_mid = relu_mid; b.relu_out = relu_out;
+        b.by_Wo = make_fastdiv(g.Wo); b.by_Ho = make_fastdiv(g.Ho);
+        hipLaunchKernelGGL(dwpw8_16, dim3((unsigned)((b.total + 255) / 256)), dim3(256), 0, s, b);
+        return hipGetLastError();
+    }
     DwPwArgs a = {};
     a.in = in; a.dwf = dw_filt; a.pwf = pw_filt; a.out = out;
     a.N = g.N; a.H = g.H; a.W = g.W; a.HW = g.H * g.W;

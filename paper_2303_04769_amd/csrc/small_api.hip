@@ -749,7 +749,7 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
         ++j;
     }
     if (c.op == SMALL_OP_DWCONV && j < nL && L[j].op == SMALL_OP_CONV && L[j].src == D && L[j].dst != SMALL_BUF_IN &&
-        (L[j].dst != c.src || (c.src >= 0 && D >= 0)) && L[j].Cib == 16 && L[j].Ci == c.Ci &&
+        (L[j].dst != c.src || (c.src >= 0 && D >= 0)) && L[j].Cib == c.Cib && L[j].Ci == c.Ci &&
         L[j].pad.t == 0 && L[j].pad.b == 0 && L[j].pad.l == 0 && L[j].pad.r == 0 &&
         dwpw_eligible(c.Ci, L[j].Co, c.Cib, L[j].Cob, c.kh, c.kw, c.stride, L[j].kh, L[j].kw, L[j].stride)) {
         // the depthwise buffer D is never written: nobody may read it before it is rewritten

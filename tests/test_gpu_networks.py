@@ -167,6 +167,9 @@ BLOCK_CASES = [  # N, C, Co, H, W, stride, relu_mid, relu_out
     (600, 64, 64, 25, 5, 1, True, True),      # 125-pixel images, many of them: each workgroup walks several
     (520, 16, 32, 20, 20, 2, True, True),     # 100-pixel outputs of a stride-2 layer, many images
     (140, 32, 32, 16, 24, 1, True, False),    # 384-pixel images: six full tiles
+    (9, 8, 16, 48, 48, 2, True, True),        # eight channels in one 8-channel block -> 16: the vector-unit kernel
+    (3, 8, 16, 13, 11, 1, False, True),       # ... stride 1, odd image, no ReLU between
+    (260, 8, 16, 5, 7, 2, True, False),       # ... many small images, ragged last workgroup
 ]
 
 
@@ -785,8 +788,8 @@ def test_resident_run_folds_the_projection_shortcut(C, Co, H, W, s):
     assert_close(_run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF), ref, _maxK(net), "projection block, layer by layer")
 
 
-@pytest.mark.parametrize("name,idx,N,launches", [("audio_cnn", 4, 1, 1), ("audio_cnn", 4, 5, 1), ("dsep_cnn", 3, 2, 6),
-                                                 ("audio_cnn", 4, 260, 1), ("dsep_cnn", 3, 130, 6)])
+@pytest.mark.parametrize("name,idx,N,launches", [("audio_cnn", 4, 1, 1), ("audio_cnn", 4, 5, 1), ("dsep_cnn", 3, 2, 5),
+                                                 ("audio_cnn", 4, 260, 1), ("dsep_cnn", 3, 130, 5)])
 def test_resident_runs_with_depthwise_layers(name, idx, N, launches):
     """Depthwise 3x3 (+ ReLU) and 1x1 convolutions alternate inside image-resident runs: the audio CNN (first layer
     with a 10x4 window on one channel, four depthwise-separable blocks, pooling + fully connected head) is one
