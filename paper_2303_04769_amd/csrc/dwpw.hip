@@ -346,6 +346,44 @@ struct DwPw8Args {
     FastDiv by_Wo, by_Ho;
 };
 
+// What a lane does with its window (eighteen float4: two per tap) and the filters in LDS
+__device__ __forceinline__ void dwpw8_finish(const floatx4 (&v)[18], const float (&on)[9], const floatx4 *w_dw, const floatx4 *w_pw,
+                                             floatx4 *o, int relu_mid, int relu_out)
+{
+    floatx4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};       // depthwise sums of channels 0..3, 4..7
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        lo += v[2 * t] * (w_dw[2 * t] * on[t]);
+        hi += v[2 * t + 1] * (w_dw[2 * t + 1] * on[t]);
+    }
+    if (relu_mid) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            lo[c] = lo[c] > 0.f ? lo[c] : 0.f;
+            hi[c] = hi[c] > 0.f ? hi[c] : 0.f;
+        }
+    }
+    floatx4 acc[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int ci = 0; ci < 8; ++ci) {
+        const float x = ci < 4 ? lo[ci] : hi[ci - 4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] += w_pw[ci * 4 + k] * x;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        floatx4 y = acc[k];
+        if (relu_out) {
+            y.x = y.x > 0.f ? y.x : 0.f; y.y = y.y > 0.f ? y.y : 0.f;
+            y.z = y.z > 0.f ? y.z : 0.f; y.w = y.w > 0.f ? y.w : 0.f;
+        }
+        __builtin_nontemporal_store(y, o + k);
+    }
+}
+
+// A lane per output pixel, the window gathered from memory: all eighteen loads are issued unconditionally (a tap
+// outside the image reads a valid pixel and is dropped by a zero factor: loads under a divergent branch would be
+// waited for one by one).
 __global__ void __launch_bounds__(256) dwpw8_16(DwPw8Args a)
 {
     __shared__ floatx4 w_dw[18], w_pw[32];
@@ -357,8 +395,6 @@ __global__ void __launch_bounds__(256) dwpw8_16(DwPw8Args a)
     const int t = a.by_Wo.div(m), ow = m - t * a.Wo;
     const int n = a.by_Ho.div(t), oh = t - n * a.Ho;
     const floatx4 *img = reinterpret_cast<const floatx4 *>(a.in) + (size_t)n * a.H * a.W * 2;
-    // all eighteen loads are issued unconditionally (a tap outside the image reads a valid pixel and is dropped by a
-    // zero factor below: loads under a divergent branch would be waited for one by one)
     floatx4 v[18];
     float on[9];
 #pragma unroll
@@ -374,36 +410,50 @@ __global__ void __launch_bounds__(256) dwpw8_16(DwPw8Args a)
             on[ky * 3 + kx] = inside ? 1.f : 0.f;
         }
     }
-    floatx4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};       // depthwise sums of channels 0..3, 4..7
+    dwpw8_finish(v, on, w_dw, w_pw, reinterpret_cast<floatx4 *>(a.out) + (size_t)m * 4, a.relu_mid, a.relu_out);
+}
+
+// The same with the input rows of a tile staged in LDS: a workgroup owns TR whole output rows of one image
+// (TR * Wo <= 256 lanes); the input rows they touch are one contiguous piece of memory, copied with consecutive lanes
+// on consecutive 16 bytes (a lane-per-pixel gather from memory touches every cache line of the piece in every load
+// instruction: 15 us instead of 7 on the first block of the depthwise-separable CNN at batch 256).
+struct DwPw8Tile { int TR, tiles_per_image, rows_max; };
+
+__global__ void __launch_bounds__(256) dwpw8_16_rows(DwPw8Args a, DwPw8Tile tl)
+{
+    extern __shared__ floatx4 lds[];
+    floatx4 *w_dw = lds, *w_pw = lds + 18, *rows = lds + 50;
+    const int tid = (int)threadIdx.x;
+    if (tid < 18) w_dw[tid] = reinterpret_cast<const floatx4 *>(a.dwf)[tid];
+    else if (tid >= 64 && tid < 96) w_pw[tid - 64] = reinterpret_cast<const floatx4 *>(a.pwf)[tid - 64];
+    const int n = (int)blockIdx.x / tl.tiles_per_image, tile = (int)blockIdx.x - n * tl.tiles_per_image;
+    const int oh0 = tile * tl.TR, n_out_rows = min(tl.TR, a.Ho - oh0);
+    // input rows ih0 .. ih1 - 1 (inside the image) serve the tile
+    const int ih0 = max(oh0 * a.stride - a.pt, 0), ih1 = min((oh0 + n_out_rows - 1) * a.stride - a.pt + 3, a.H);
+    const floatx4 *img = reinterpret_cast<const floatx4 *>(a.in) + (size_t)n * a.H * a.W * 2;
+    const int n_vec = (ih1 - ih0) * a.W * 2;
+    for (int c = tid; c < n_vec; c += 256) rows[c] = __builtin_nontemporal_load(img + ih0 * a.W * 2 + c);
+    __syncthreads();
+    const int r = a.by_Wo.div(tid), ow = tid - r * a.Wo;
+    if (r >= n_out_rows) return;
+    const int oh = oh0 + r;
+    floatx4 v[18];
+    float on[9];
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
-        lo += v[2 * t] * (w_dw[2 * t] * on[t]);
-        hi += v[2 * t + 1] * (w_dw[2 * t + 1] * on[t]);
-    }
-    if (a.relu_mid) {
+    for (int ky = 0; ky < 3; ++ky) {
+        const int ih = oh * a.stride + ky - a.pt;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            lo[c] = lo[c] > 0.f ? lo[c] : 0.f;
-            hi[c] = hi[c] > 0.f ? hi[c] : 0.f;
+        for (int kx = 0; kx < 3; ++kx) {
+            const int iw = ow * a.stride + kx - a.pl;
+            const bool inside = ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            const floatx4 *px = rows + (inside ? ((ih - ih0) * a.W + iw) * 2 : 0);
+            v[(ky * 3 + kx) * 2] = px[0];
+            v[(ky * 3 + kx) * 2 + 1] = px[1];
+            on[ky * 3 + kx] = inside ? 1.f : 0.f;
         }
     }
-    floatx4 acc[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-    for (int ci = 0; ci < 8; ++ci) {
-        const float x = ci < 4 ? lo[ci] : hi[ci - 4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) acc[k] += w_pw[ci * 4 + k] * x;
-    }
-    floatx4 *o = reinterpret_cast<floatx4 *>(a.out) + (size_t)m * 4;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        floatx4 v = acc[k];
-        if (a.relu_out) {
-            v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
-            v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
-        }
-        __builtin_nontemporal_store(v, o + k);
-    }
+    const size_t m = ((size_t)n * a.Ho + oh) * a.Wo + ow;
+    dwpw8_finish(v, on, w_dw, w_pw, reinterpret_cast<floatx4 *>(a.out) + m * 4, a.relu_mid, a.relu_out);
 }
 
 }  // namespace
@@ -438,6 +488,18 @@ hipError_t launch_dwpw(const float *in, const float *dw_filt, const float *pw_fi
         b.total = g.N * g.Ho * g.Wo;
         b.relu_mid = relu_mid; b.relu_out = relu_out;
         b.by_Wo = make_fastdiv(g.Wo); b.by_Ho = make_fastdiv(g.Ho);
+        // whole output rows per workgroup with their input rows in LDS, where rows are short enough
+        if (g.Wo <= 128) {
+            DwPw8Tile tl;
+            tl.TR = std::min(g.Ho, 256 / g.Wo);
+            tl.rows_max = std::min(g.H, (tl.TR - 1) * g.stride + 3);
+            const size_t lds = (size_t)(50 + tl.rows_max * g.W * 2) * 16;
+            if (lds <= 64 * 1024) {
+                tl.tiles_per_image = (g.Ho + tl.TR - 1) / tl.TR;
+                hipLaunchKernelGGL(dwpw8_16_rows, dim3((unsigned)(g.N * tl.tiles_per_image)), dim3(256), lds, s, b, tl);
+                return hipGetLastError();
+            }
+        }
         hipLaunchKernelGGL(dwpw8_16, dim3((unsigned)((b.total + 255) / 256)), dim3(256), 0, s, b);
         return hipGetLastError();
     }

@@ -170,6 +170,8 @@ BLOCK_CASES = [  # N, C, Co, H, W, stride, relu_mid, relu_out
     (9, 8, 16, 48, 48, 2, True, True),        # eight channels in one 8-channel block -> 16: the vector-unit kernel
     (3, 8, 16, 13, 11, 1, False, True),       # ... stride 1, odd image, no ReLU between
     (260, 8, 16, 5, 7, 2, True, False),       # ... many small images, ragged last workgroup
+    (2, 8, 16, 9, 300, 1, True, True),        # ... rows too long for the row-staged variant: the gather kernel
+    (3, 8, 16, 70, 100, 2, True, True),       # ... 50-pixel output rows: five rows per workgroup, 35 rows
 ]
 
 
