@@ -42,6 +42,8 @@ __device__ __forceinline__ void store_tiles(const QConvArgs &a, const intx4 (&ac
     const int za = a.q.zx - 128, zb = a.q.zw - 128;
     const unsigned K = (unsigned)a.n_chunks * 16u;
     const unsigned kab = K * (unsigned)(za * zb);
+    const bool narrow = a.q.amax > 0;                  // (uniform) the five-instruction requantization applies
+    const long bias = requant_bias(a.q);
 #pragma unroll
     for (int wm = 0; wm < WM; ++wm) {
         const int m = tile0 + wm * 16 + p;
@@ -55,7 +57,7 @@ __device__ __forceinline__ void store_tiles(const QConvArgs &a, const intx4 (&ac
                 // wrap-around arithmetic: the true sum fits 32 bits, the partial terms need not
                 const unsigned v = (unsigned)acc[wm][wn][r] - (unsigned)zb * (unsigned)acc_s[wm][r] -
                                    (unsigned)za * (unsigned)acc_w[wn][r] + kab;
-                packed |= (unsigned)requant((int)v, a.q) << (8 * r);
+                packed |= (unsigned)(narrow ? requant_clamped((int)v, a.q, bias) : requant((int)v, a.q)) << (8 * r);
             }
             unsigned *o = reinterpret_cast<unsigned *>(a.out + (((size_t)n * a.nCob + cob0 + wn) * a.HoWo + pix) * 16 + g * 4);
             *o = packed;

@@ -253,6 +253,20 @@ __device__ __forceinline__ int requant(int acc, const QuantParams &q)
     return (int)v;
 }
 
+// The same for layers with q.amax > 0, in five instructions: the sum is clamped to +-amax first (beyond it the output
+// saturates anyway, within it everything below fits), and bias = 2^(shift-1) + zy * 2^shift (requant_bias) carries the
+// rounding term and the zero point through the one shift.
+__device__ __forceinline__ long requant_bias(const QuantParams &q)
+{
+    return (q.shift > 0 ? 1L << (q.shift - 1) : 0L) + ((long)q.zy << q.shift);
+}
+__device__ __forceinline__ int requant_clamped(int acc, const QuantParams &q, long bias)
+{
+    const int c = min(max(acc, -q.amax), q.amax);
+    const int r = (int)(((long)c * (long)q.mult + bias) >> q.shift);
+    return min(max(r, q.lo), q.hi);
+}
+
 hipError_t launch_pack_u8(const unsigned char *nchw, unsigned char *blk, int N, int C, int H, int W, int Cb, bool unpack,
                           hipStream_t s);
 hipError_t launch_pack_filter_u8(const unsigned char *oihw, unsigned char *blk, int Co, int Ci, int kh, int kw, int Cob,
