@@ -723,6 +723,7 @@ hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, 
     a.mode = mode;
     a.q = q;
     if (mode == 0 && dw_dpp_u8_eligible(g, q, in, filt, out)) return launch_dw_dpp_u8(in, filt, out, g, q, s);
+    if (pool_dpp_u8_eligible(g, mode, in, out)) return launch_pool_dpp_u8(in, out, g, s);
     if (mode == 0 && g.Cib == 16 && g.kh == 3 && g.kw == 3 &&
         ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 3u) == 0) && (size_t)g.N * a.nCb <= 65535) {
         QDw3Args d;

@@ -262,6 +262,21 @@ def test_max_pooling_on_16_byte_blocks(case):
     _same(Q.unpack(g.check(), ref.shape, 16), ref, f"max pool u8 {case}")
 
 
+@pytest.mark.parametrize("shape", [(2, 16, 3, 3), (2, 32, 64, 64), (1, 16, 20, 130), (3, 48, 33, 66), (2, 16, 4, 5), (1, 16, 57, 125),
+                                   (2, 16, 31, 63), (1, 32, 16, 127), (7, 80, 14, 14)])
+def test_max_pooling_3x3_stride_2_by_lane_shifts(shape):
+    """The 3x3 / stride 2 / unpadded window on 16-byte blocks: bands of 64 pixels (31 outputs) and strips of 7 output rows,
+    at widths of one band, a band and one pixel, several bands, and heights that split into ragged strips."""
+    N, C, H, W = shape
+    x = WL.u8_codes(_rng(11), (N, C, H, W))
+    x[:, :, ::3, ::5] = 255
+    x[0, :, :3, :3] = 0
+    ref = Q.pool2d(x, (3, 3), 2, (0, 0, 0, 0), "max")
+    g = Guarded8(ref.size)
+    S.small_pool2d_u8(dev8(Q.pack(x, 16)), g.t, N, C, H, W, 3, 3, 2, (0, 0, 0, 0), 16, S.POOL_MAX)
+    _same(Q.unpack(g.check(), ref.shape, 16), ref, f"max pool u8 3x3 s2 {shape}")
+
+
 ADD_PARAMS = [(128, 128, 128, 3 << 28, 1 << 29, 30, 0, 255), (0, 255, 17, (1 << 31) - 1, 1, 31, 0, 255),
               (200, 3, 100, 12345, 67890, 7, 10, 240), (5, 9, 0, 7, 3, 0, 0, 255), (255, 0, 255, 1 << 30, 1 << 30, 31, 0, 255),
               (128, 128, 128, (1 << 31) - 1, (1 << 31) - 1, 0, 0, 255)]
