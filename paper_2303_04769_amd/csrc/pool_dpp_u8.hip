@@ -92,7 +92,7 @@ __global__ void __launch_bounds__(256) maxpool3s2_u8_rows(PoolU8Args a)
 #pragma unroll
     for (int j = 0; j < kPoolInRows; ++j) {
         const bool have = col_in && j < n_in;
-        raw[j] = __builtin_amdgcn_raw_buffer_load_b128(src, have ? at_in + (unsigned)((2 * r0 + j) * a.W * 16) : kBeyond, 0, 0);
+        raw[j] = __builtin_amdgcn_raw_buffer_load_b128(src, have ? at_in + (unsigned)((2 * r0 + j) * a.W * 16) : kBeyond, 0, kNonTemporal);
     }
     Split h[3];                                                  // horizontal maxima of the rows 2r, 2r + 1, 2r + 2
 #pragma unroll

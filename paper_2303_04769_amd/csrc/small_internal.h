@@ -283,6 +283,9 @@ hipError_t launch_filter_sums_u8(const unsigned char *filt, int *sums, int Co, i
 hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
                             int mode, const QuantParams &q, hipStream_t s);
 hipError_t launch_relu_u8(const unsigned char *in, unsigned char *out, size_t n, int z, hipStream_t s);
+// max pooling 3x3, stride 2, no padding, 16-channel blocks, 16-byte aligned pointers (pool_dpp.hip)
+bool pool_dpp_eligible(const LayerGeom &g, const void *in, const void *out);
+hipError_t launch_pool_dpp(const float *in, float *out, const LayerGeom &g, hipStream_t s);
 // quantized max pooling 3x3, stride 2, no padding, 16-byte blocks, 16-byte aligned pointers (pool_dpp_u8.hip); mode 1 = max
 bool pool_dpp_u8_eligible(const LayerGeom &g, int mode, const void *in, const void *out);
 hipError_t launch_pool_dpp_u8(const unsigned char *in, unsigned char *out, const LayerGeom &g, hipStream_t s);

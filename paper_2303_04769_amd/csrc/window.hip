@@ -381,6 +381,7 @@ hipError_t launch_avgpool_dense(const float *in, const float *filt, float *out, 
 
 hipError_t launch_pool(const float *in, float *out, const LayerGeom &g, int mode, hipStream_t s)
 {
+    if (mode == 0 && pool_dpp_eligible(g, in, out)) return launch_pool_dpp(in, out, g, s);
     if (mode == 0) return launch_window<OP_MAX>(in, nullptr, out, g, EPI_NONE, s);
     const bool global = g.Ho == 1 && g.Wo == 1 && g.kh == g.H && g.kw == g.W && g.pt == 0 && g.pl == 0;
     const bool aligned = ((((uintptr_t)in | (uintptr_t)out) & 15u) == 0);

@@ -370,6 +370,28 @@ def test_pool2d_large(case, mode):
         assert_close(got, ref, 9, f"avgpool large {case}")
 
 
+@pytest.mark.parametrize("shape", [(2, 16, 3, 3), (2, 32, 16, 16), (1, 16, 20, 31), (3, 48, 33, 30), (2, 16, 4, 5), (1, 16, 57, 125),
+                                   (2, 16, 31, 15), (1, 32, 16, 17), (7, 80, 14, 14), (4, 256, 56, 56)])
+def test_maxpool_3x3_stride_2_by_lane_shifts(shape):
+    """The 3x3 / stride 2 / unpadded window on 16-channel blocks: bands of 16 pixels (7 outputs) and strips of 7 output rows, at
+    widths of one band, a band and one pixel, many bands, and heights that split into ragged strips; +0 / -0 ties, NaNs and
+    whole windows of NaN as the reference scan resolves them."""
+    N, C, H, W = shape
+    rng = np.random.default_rng(N * 1000 + H * 10 + W)
+    x = (rng.random((N, C, H, W), dtype=np.float32) * 2 - 1).astype(np.float32)
+    flat = x.reshape(-1)
+    idx = rng.integers(0, flat.size, flat.size // 5)
+    flat[idx[0::4]] = 0.0
+    flat[idx[1::4]] = -0.0
+    flat[idx[2::4]] = np.nan
+    flat[idx[3::4]] = -np.inf
+    x[0, :, :3, :3] = np.nan
+    ref = O.pool2d(x, (3, 3), 2, (0, 0, 0, 0), "max")
+    g = Guarded(ref.size)
+    S.small_pool2d(dev(O.pack(x, 16)), g.t, N, C, H, W, 3, 3, 2, (0, 0, 0, 0), 16, S.POOL_MAX)
+    assert_bits(O.unpack(g.check(), ref.shape, 16), ref, f"maxpool 3x3 s2 {shape}")
+
+
 def test_maxpool_ties_and_nan_bit_exact():
     x = np.zeros((1, 16, 4, 4), np.float32)
     x[0, :, 0, 0], x[0, :, 0, 1] = -0.0, 0.0          # first seen is -0
