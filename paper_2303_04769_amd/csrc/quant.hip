@@ -691,6 +691,8 @@ bool conv_u8_uses_mfma(const LayerGeom &g, const void *in, const void *filt, con
 hipError_t launch_conv_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
                           const QuantParams &q, const int *filt_sums, hipStream_t s)
 {
+    if (conv_first_u8_eligible(g, out)) return launch_conv_first_u8(in, filt, out, g, q, s);
+    if (dense_u8_eligible(g, in, filt)) return launch_dense_u8(in, filt, out, g, q, s);
     const QConvArgs a = conv_args(in, filt, out, g, q, filt_sums);
     if (conv_u8_uses_mfma(g, in, filt, out)) {
         int wm = 4, wn = 4;
@@ -724,6 +726,7 @@ hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, 
     a.q = q;
     if (mode == 0 && dw_dpp_u8_eligible(g, q, in, filt, out)) return launch_dw_dpp_u8(in, filt, out, g, q, s);
     if (pool_dpp_u8_eligible(g, mode, in, out)) return launch_pool_dpp_u8(in, out, g, s);
+    if (avgpool_global_u8_eligible(g, mode, in, out)) return launch_avgpool_global_u8(in, out, g, s);
     if (mode == 0 && g.Cib == 16 && g.kh == 3 && g.kw == 3 &&
         ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)filt) & 3u) == 0) && (size_t)g.N * a.nCb <= 65535) {
         QDw3Args d;

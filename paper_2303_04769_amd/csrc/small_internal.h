@@ -283,6 +283,17 @@ hipError_t launch_filter_sums_u8(const unsigned char *filt, int *sums, int Co, i
 hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
                             int mode, const QuantParams &q, hipStream_t s);
 hipError_t launch_relu_u8(const unsigned char *in, unsigned char *out, size_t n, int z, hipStream_t s);
+// the ends of a quantized network (quant_ends.hip): the first convolution on a 3-channel (3x3) or 1-channel (10x4) input
+// with 8 or 16 output channels per block, global average pooling on 16-byte blocks (mode 2 = average), a fully connected
+// layer with fewer than 16 outputs per block
+bool conv_first_u8_eligible(const LayerGeom &g, const void *out);
+hipError_t launch_conv_first_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
+                                const QuantParams &q, hipStream_t s);
+bool avgpool_global_u8_eligible(const LayerGeom &g, int mode, const void *in, const void *out);
+hipError_t launch_avgpool_global_u8(const unsigned char *in, unsigned char *out, const LayerGeom &g, hipStream_t s);
+bool dense_u8_eligible(const LayerGeom &g, const void *in, const void *filt);
+hipError_t launch_dense_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
+                           const QuantParams &q, hipStream_t s);
 // max pooling 3x3, stride 2, no padding, 16-channel blocks, 16-byte aligned pointers (pool_dpp.hip)
 bool pool_dpp_eligible(const LayerGeom &g, const void *in, const void *out);
 hipError_t launch_pool_dpp(const float *in, float *out, const LayerGeom &g, hipStream_t s);

@@ -277,6 +277,59 @@ def test_max_pooling_3x3_stride_2_by_lane_shifts(shape):
     _same(Q.unpack(g.check(), ref.shape, 16), ref, f"max pool u8 3x3 s2 {shape}")
 
 
+FIRST_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad, zx, zw, Cob
+    (3, 3, 16, 32, 32, 3, 3, 1, (1, 1, 1, 1), 128, 128, 16),     # residual CNN's first layer
+    (2, 3, 8, 96, 96, 3, 3, 2, (0, 1, 0, 1), 117, 140, 8),       # depthwise-separable CNN's
+    (5, 1, 64, 49, 10, 10, 4, 2, (4, 5, 1, 1), 3, 250, 16),      # audio CNN's: four blocks of output channels
+    (1, 3, 64, 7, 9, 3, 3, 1, (0, 0, 0, 0), 0, 0, 16),
+    (2, 3, 32, 17, 5, 3, 3, 2, (1, 1, 1, 1), 255, 255, 8),
+    (9, 1, 8, 12, 6, 10, 4, 1, (5, 4, 2, 1), 128, 1, 8),
+    (300, 3, 16, 3, 3, 3, 3, 1, (1, 1, 1, 1), 90, 200, 16),      # more images than pixels per image
+    (1, 1, 16, 10, 4, 10, 4, 1, (0, 0, 0, 0), 128, 128, 16),     # a single output pixel
+]
+
+
+@pytest.mark.parametrize("case", FIRST_CASES)
+def test_first_convolution(case):
+    """First layers on 3 (3x3) or 1 (10x4) input channels: one lane per output pixel around four-byte dot products."""
+    N, Ci, Co, H, W, kh, kw, s, pad, zx, zw, Cob = case
+    r = _rng(12)
+    x, w = WL.u8_codes(r, (N, Ci, H, W)), WL.u8_codes(r, (Co, Ci, kh, kw))
+    for relu in (False, True):
+        q = _quant_for(Q.conv2d_acc(x, w, s, pad, zx, zw), zx, zw, relu)
+        ref = Q.conv2d(x, w, s, pad, q)
+        _same(_conv(x, w, s, pad, q, Ci, Cob), ref, f"first conv u8 {case} relu={relu}")
+    assert len(np.unique(ref)) > 8
+    q = _quant(Ci * kh * kw, zx, zw, mult=(1 << 31) - 1, shift=0, zy=9)        # the wide requantization path
+    _same(_conv(x, w, s, pad, q, Ci, Cob), Q.conv2d(x, w, s, pad, q), f"first conv u8 wide {case}")
+
+
+@pytest.mark.parametrize("shape", [(1, 16, 1, 1), (3, 64, 8, 8), (5, 64, 25, 5), (2, 256, 2, 2), (7, 80, 3, 3), (2, 16, 40, 37), (260, 32, 2, 3)])
+def test_global_average_pooling(shape):
+    N, C, H, W = shape
+    x = WL.u8_codes(_rng(13), (N, C, H, W))
+    x[0, :8] = 255
+    x[-1, -3:] = 0
+    ref = Q.pool2d(x, (H, W), 1, (0, 0, 0, 0), "avg")
+    g = Guarded8(ref.size)
+    S.small_pool2d_u8(dev8(Q.pack(x, 16)), g.t, N, C, H, W, H, W, 1, (0, 0, 0, 0), 16, S.POOL_AVG)
+    _same(Q.unpack(g.check(), ref.shape, 16), ref, f"global average u8 {shape}")
+
+
+@pytest.mark.parametrize("case", [(1, 16, 2, 2), (256, 64, 10, 10), (7, 256, 2, 2), (300, 64, 12, 12), (5, 128, 24, 12), (3, 48, 15, 5),
+                                  (2, 1024, 9, 9)])
+def test_small_fully_connected(case):
+    """Fewer than 16 outputs per block: a wave per (image, output block), the input blocks split over four parts."""
+    N, Ci, Co, Cob = case
+    r = _rng(14)
+    x, w = WL.u8_codes(r, (N, Ci, 1, 1)), WL.u8_codes(r, (Co, Ci, 1, 1))
+    for zx, zw in ((128, 128), (3, 250), (255, 0)):
+        q = _quant_for(Q.conv2d_acc(x, w, 1, (0, 0, 0, 0), zx, zw), zx, zw)
+        g = Guarded8(N * Co)
+        S.small_dense_u8(dev8(Q.pack(x, 16)), dev8(Q.pack_filter(w, Cob, 16)), g.t, N, Ci, Co, 16, Cob, q)
+        _same(Q.unpack(g.check(), (N, Co, 1, 1), Cob), Q.dense(x, w, q), f"dense u8 {case} z=({zx},{zw})")
+
+
 ADD_PARAMS = [(128, 128, 128, 3 << 28, 1 << 29, 30, 0, 255), (0, 255, 17, (1 << 31) - 1, 1, 31, 0, 255),
               (200, 3, 100, 12345, 67890, 7, 10, 240), (5, 9, 0, 7, 3, 0, 0, 255), (255, 0, 255, 1 << 30, 1 << 30, 31, 0, 255),
               (128, 128, 128, (1 << 31) - 1, (1 << 31) - 1, 0, 0, 255)]
