@@ -28,7 +28,7 @@ struct QConvArgs {
     int N, H, W, Ho, Wo, HoWo, M;
     int nCib, nCob, Cib, Cob, kh, kw, stride, pt, pl;
     int n_chunks;     // nCib * kh * kw (matrix-core kernel)
-    FastDiv div_HoWo, div_Wo;
+    FastDiv div_HoWo, div_Wo, div_taps, div_kw;
     const int *filt_sums;   // per output channel: sum of the filter's codes over the whole reduction, or null
     QuantParams q;
 };
@@ -249,6 +249,104 @@ __global__ void __launch_bounds__(256) conv_u8_mfma(QConvArgs a)
         multiply(fa0, fb0);
         load(fa0, fb0);               // step t + 2
         multiply(fa1, fb1);
+    }
+
+    if (use_w && a.filt_sums) {
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) acc_w[wn] = signed_filter_sums(a, cob0 + wn, g);
+    }
+    store_tiles<WM, WN>(a, acc, acc_s, acc_w, tile0, cob0, p, g);
+}
+
+// The same tile for short reductions (at most 4 * STEPS chunks: 16 or 32 input channels under a 3x3 window, up to 64
+// under 1x1): every operand of the whole reduction is requested before the first matrix instruction, from addresses that
+// are always valid (chunks past the end and taps outside the image are replaced afterwards), so a wave waits for memory
+// once instead of once per step, which is what these launches' time consists of.
+template <int WM, int WN, int CORR, int STEPS>
+__global__ void __launch_bounds__(256) conv_u8_mfma_short(QConvArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p = lane & 15, g = lane >> 4;
+    const int cob0 = blockIdx.y * WN;
+    const int tile0 = ((int)blockIdx.x * 4 + wave) * (16 * WM);
+    const int HW = a.H * a.W;
+    const int za = a.q.zx - 128;
+    constexpr bool use_s = CORR >= 1, mfma_w = CORR == 2;
+    const bool use_w = za != 0;
+
+    int ih0[WM], iw0[WM];
+    const intx4 *img[WM];
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm) {
+        int m = tile0 + wm * 16 + p;
+        m = m < a.M ? m : a.M - 1;
+        const int n = a.div_HoWo.div(m), rem = m - n * a.HoWo;
+        const int oh = a.div_Wo.div(rem), ow = rem - oh * a.Wo;
+        ih0[wm] = oh * a.stride - a.pt;
+        iw0[wm] = ow * a.stride - a.pl;
+        img[wm] = reinterpret_cast<const intx4 *>(a.in) + (size_t)n * a.nCib * HW;
+    }
+    const intx4 *filt = reinterpret_cast<const intx4 *>(a.filt) + (size_t)cob0 * a.n_chunks * 16 + p;
+    const size_t cob_stride = (size_t)a.n_chunks * 16;
+    const int flip = (int)0x80808080u;
+    const int pad = (a.q.zx * 0x01010101) ^ flip;
+    const intx4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    const intx4 zero = {0, 0, 0, 0};
+
+    intx4 ra[STEPS][WN], rb[STEPS][WM];
+    bool live[STEPS], inside[STEPS][WM];
+#pragma unroll
+    for (int t = 0; t < STEPS; ++t) {
+        // this lane group's chunk of step t: c = (cib * kh + ky) * kw + kx
+        const int c_raw = 4 * t + g;
+        live[t] = c_raw < a.n_chunks;
+        const int c = live[t] ? c_raw : a.n_chunks - 1;
+        const int cib = a.div_taps.div(c), tap = c - cib * a.kh * a.kw;
+        const int ky = a.div_kw.div(tap), kx = tap - ky * a.kw;
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) ra[t][wn] = filt[wn * cob_stride + (size_t)c * 16];
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm) {
+            const int ih = ih0[wm] + ky, iw = iw0[wm] + kx;
+            inside[t][wm] = ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+            rb[t][wm] = img[wm][inside[t][wm] ? cib * HW + ih * a.W + iw : 0];
+        }
+    }
+
+    intx4 acc[WM][WN], acc_s[WM], acc_w[WN];
+#pragma unroll
+    for (int wm = 0; wm < WM; ++wm) {
+        acc_s[wm] = zero;
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) acc[wm][wn] = zero;
+    }
+#pragma unroll
+    for (int wn = 0; wn < WN; ++wn) acc_w[wn] = zero;
+
+#pragma unroll
+    for (int t = 0; t < STEPS; ++t) {
+        intx4 fa[WN], fb[WM];
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) fa[wn][k] = live[t] ? ra[t][wn][k] ^ flip : 0;
+        }
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) fb[wm][k] = live[t] ? (inside[t][wm] ? rb[t][wm][k] ^ flip : pad) : 0;
+        }
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm) {
+#pragma unroll
+            for (int wn = 0; wn < WN; ++wn)
+                acc[wm][wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], fb[wm], acc[wm][wn], 0, 0, 0);
+            if (use_s) acc_s[wm] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb[wm], acc_s[wm], 0, 0, 0);
+        }
+        if (mfma_w) {
+#pragma unroll
+            for (int wn = 0; wn < WN; ++wn) acc_w[wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[wn], ones, acc_w[wn], 0, 0, 0);
+        }
     }
 
     if (use_w && a.filt_sums) {
@@ -651,6 +749,8 @@ QConvArgs conv_args(const unsigned char *in, const unsigned char *filt, unsigned
     a.n_chunks = a.nCib * g.kh * g.kw;
     a.div_HoWo = make_fastdiv(a.HoWo);
     a.div_Wo = make_fastdiv(g.Wo);
+    a.div_taps = make_fastdiv(g.kh * g.kw);
+    a.div_kw = make_fastdiv(g.kw);
     a.filt_sums = filt_sums;
     a.q = q;
     return a;
@@ -702,6 +802,9 @@ hipError_t launch_conv_u8(const unsigned char *in, const unsigned char *filt, un
 #define SMALL_U8_CASE(M_, N_, C_)                                                                            \
     if (wm == M_ && wn == N_ && corr == C_) {                                                                \
         if (a.nCib % 4 == 0) hipLaunchKernelGGL((conv_u8_mfma4<M_, N_, C_, 3>), grid, dim3(256), 0, s, a);   \
+        else if (a.n_chunks <= 4) hipLaunchKernelGGL((conv_u8_mfma_short<M_, N_, C_, 1>), grid, dim3(256), 0, s, a);  \
+        else if (a.n_chunks <= 12) hipLaunchKernelGGL((conv_u8_mfma_short<M_, N_, C_, 3>), grid, dim3(256), 0, s, a); \
+        else if (a.n_chunks <= 20) hipLaunchKernelGGL((conv_u8_mfma_short<M_, N_, C_, 5>), grid, dim3(256), 0, s, a); \
         else hipLaunchKernelGGL((conv_u8_mfma<M_, N_, C_>), grid, dim3(256), 0, s, a);                       \
     }
 #define SMALL_U8_TILE(M_, N_) SMALL_U8_CASE(M_, N_, 0) SMALL_U8_CASE(M_, N_, 1) SMALL_U8_CASE(M_, N_, 2)
