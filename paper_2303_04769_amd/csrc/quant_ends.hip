@@ -1,5 +1,6 @@
 // The two ends of a quantized network (Section "Quantized Inference": whole models on uint8 tensors with int32
-// partial sums): the first convolution on an input of one or three channels, the global average pooling and the
+// partial sums): the first convolution on an input of one or three channels (and the pointwise convolution on the
+// eight channels such a layer may produce), the global average pooling and the
 // small fully connected layer that close it. None of them has the 16 x 16 channel blocks the 8-bit matrix-core
 // kernel needs, and all of them are small: plain vector code around the four-byte dot product (v_dot4_u32_u8),
 // with the zero points taken out afterwards,
@@ -25,21 +26,20 @@ struct FirstU8Args {
     QuantParams q;
 };
 
-constexpr int kFirstMaxCo = 64;
-
-// One lane per output pixel: it gathers its window (K = KH * KW * CIB bytes, reduction index k = tap * CIB + channel,
-// padded with zeros to KD words) into registers once and walks the output channels; the filters sit in LDS as one
-// row of KD words per output channel (all lanes read the same word: a broadcast) beside their sums. A lane stores
-// the COB codes of its pixel at once, so a wave's store is one contiguous run.
+// One lane per (output pixel, block of COB output channels; blockIdx.y counts the blocks): it gathers its window
+// (K = KH * KW * CIB bytes, reduction index k = tap * CIB + channel, padded with zeros to KD words) into registers
+// and walks the block's channels; the block's filters sit in LDS as one row of KD words per output channel (all lanes
+// read the same word: a broadcast) beside their sums. A lane stores the COB codes of its pixel at once, so a wave's
+// store is one contiguous run.
 template <int KH, int KW, int CIB, int COB>
 __global__ void __launch_bounds__(256) conv_first_u8(FirstU8Args a)
 {
     constexpr int K = KH * KW * CIB, KD = (K + 15) / 16 * 4;
-    __shared__ __attribute__((aligned(16))) unsigned wl[kFirstMaxCo * KD];
-    __shared__ int sw[kFirstMaxCo];
-    const int tid = threadIdx.x, Co = a.nCob * COB;
-    for (int i = tid; i < Co * KD; i += 256) {
-        const int cg = i / KD, kd = i - cg * KD, cob = cg / COB, co = cg - cob * COB;
+    __shared__ __attribute__((aligned(16))) unsigned wl[COB * KD];
+    __shared__ int sw[COB];
+    const int tid = threadIdx.x, cob = blockIdx.y;
+    for (int i = tid; i < COB * KD; i += 256) {
+        const int co = i / KD, kd = i - co * KD;
         unsigned w = 0;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
@@ -49,12 +49,12 @@ __global__ void __launch_bounds__(256) conv_first_u8(FirstU8Args a)
         wl[i] = w;
     }
     __syncthreads();
-    if (tid < Co) {
+    if (tid < COB) {
         unsigned s = 0;
+#pragma unroll
         for (int kd = 0; kd < KD; ++kd) s = dot4(wl[tid * KD + kd], kOnes, s);
         sw[tid] = (int)s;
     }
-    __syncthreads();
 
     const int m_raw = (int)blockIdx.x * 256 + tid;
     const bool live = m_raw < a.M;
@@ -88,25 +88,23 @@ __global__ void __launch_bounds__(256) conv_first_u8(FirstU8Args a)
 #pragma unroll
     for (int kd = 0; kd < KD; ++kd) sx = dot4(x[kd], kOnes, sx);
     const int base = K * a.q.zx * a.q.zw - a.q.zw * (int)sx;
+    __syncthreads();                                     // the filter sums
 
-    for (int cob = 0; cob < a.nCob; ++cob) {
-        unsigned packed[COB / 4];
+    unsigned packed[COB / 4];
 #pragma unroll
-        for (int j = 0; j < COB / 4; ++j) packed[j] = 0;
+    for (int j = 0; j < COB / 4; ++j) packed[j] = 0;
 #pragma unroll
-        for (int co = 0; co < COB; ++co) {
-            const unsigned *w = wl + (cob * COB + co) * KD;
-            unsigned dot = 0;
+    for (int co = 0; co < COB; ++co) {
+        unsigned dot = 0;
 #pragma unroll
-            for (int kd = 0; kd < KD; ++kd) dot = dot4(x[kd], w[kd], dot);
-            const int acc = (int)dot - a.q.zx * sw[cob * COB + co] + base;
-            packed[co / 4] |= (unsigned)requant(acc, a.q) << (8 * (co % 4));
-        }
-        if (live) {
-            unsigned char *o = a.out + ((size_t)(n * a.nCob + cob) * a.HoWo + pix) * COB;
-            if constexpr (COB == 16) *reinterpret_cast<uintx4 *>(o) = uintx4{packed[0], packed[1], packed[2], packed[3]};
-            else *reinterpret_cast<uint2 *>(o) = uint2{packed[0], packed[1]};
-        }
+        for (int kd = 0; kd < KD; ++kd) dot = dot4(x[kd], wl[co * KD + kd], dot);
+        const int acc = (int)dot - a.q.zx * sw[co] + base;
+        packed[co / 4] |= (unsigned)requant(acc, a.q) << (8 * (co % 4));
+    }
+    if (live) {
+        unsigned char *o = a.out + ((size_t)(n * a.nCob + cob) * a.HoWo + pix) * COB;
+        if constexpr (COB == 16) *reinterpret_cast<uintx4 *>(o) = uintx4{packed[0], packed[1], packed[2], packed[3]};
+        else *reinterpret_cast<uint2 *>(o) = uint2{packed[0], packed[1]};
     }
 }
 
@@ -199,7 +197,7 @@ __global__ void __launch_bounds__(256) dense_u8(DenseU8Args a)
 template <int KH, int KW, int CIB>
 hipError_t launch_first(const FirstU8Args &a, int Cob, hipStream_t s)
 {
-    const dim3 grid((unsigned)((a.M + 255) / 256));
+    const dim3 grid((unsigned)((a.M + 255) / 256), (unsigned)a.nCob);
     if (Cob == 16) hipLaunchKernelGGL((conv_first_u8<KH, KW, CIB, 16>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((conv_first_u8<KH, KW, CIB, 8>), grid, dim3(256), 0, s, a);
     return hipGetLastError();
@@ -209,8 +207,9 @@ hipError_t launch_first(const FirstU8Args &a, int Cob, hipStream_t s)
 
 bool conv_first_u8_eligible(const LayerGeom &g, const void *out)
 {
-    const bool shape = (g.kh == 3 && g.kw == 3 && g.Cib == 3) || (g.kh == 10 && g.kw == 4 && g.Cib == 1);
-    if (!shape || g.Ci != g.Cib || (g.Cob != 16 && g.Cob != 8) || g.Co > kFirstMaxCo) return false;
+    const bool shape = (g.kh == 3 && g.kw == 3 && g.Cib == 3) || (g.kh == 10 && g.kw == 4 && g.Cib == 1) ||
+                       (g.kh == 1 && g.kw == 1 && g.Cib == 8);
+    if (!shape || g.Ci != g.Cib || (g.Cob != 16 && g.Cob != 8) || g.Co / g.Cob > 65535) return false;
     if (((uintptr_t)out & (uintptr_t)(g.Cob - 1)) != 0) return false;
     return (size_t)g.N * g.Ho * g.Wo < ((size_t)1 << 31) && (size_t)g.N * g.H * g.W * g.Ci < ((size_t)1 << 31);
 }
@@ -225,6 +224,7 @@ hipError_t launch_conv_first_u8(const unsigned char *in, const unsigned char *fi
     a.div_HoWo = make_fastdiv(a.HoWo);
     a.div_Wo = make_fastdiv(g.Wo);
     a.q = q;
+    if (g.Cib == 8) return launch_first<1, 1, 8>(a, g.Cob, s);
     return g.Cib == 3 ? launch_first<3, 3, 3>(a, g.Cob, s) : launch_first<10, 4, 1>(a, g.Cob, s);
 }
 

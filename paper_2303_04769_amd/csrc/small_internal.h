@@ -284,7 +284,7 @@ hipError_t launch_window_u8(const unsigned char *in, const unsigned char *filt, 
                             int mode, const QuantParams &q, hipStream_t s);
 hipError_t launch_relu_u8(const unsigned char *in, unsigned char *out, size_t n, int z, hipStream_t s);
 // the ends of a quantized network (quant_ends.hip): the first convolution on a 3-channel (3x3) or 1-channel (10x4) input
-// with 8 or 16 output channels per block, global average pooling on 16-byte blocks (mode 2 = average), a fully connected
+// or a 1x1 convolution on 8 channels, with 8 or 16 output channels per block, global average pooling on 16-byte blocks (mode 2 = average), a fully connected
 // layer with fewer than 16 outputs per block
 bool conv_first_u8_eligible(const LayerGeom &g, const void *out);
 hipError_t launch_conv_first_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,

@@ -286,6 +286,8 @@ FIRST_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad, zx, zw, Cob
     (9, 1, 8, 12, 6, 10, 4, 1, (5, 4, 2, 1), 128, 1, 8),
     (300, 3, 16, 3, 3, 3, 3, 1, (1, 1, 1, 1), 90, 200, 16),      # more images than pixels per image
     (1, 1, 16, 10, 4, 10, 4, 1, (0, 0, 0, 0), 128, 128, 16),     # a single output pixel
+    (3, 8, 16, 24, 24, 1, 1, 1, (0, 0, 0, 0), 131, 120, 16),     # pointwise convolution on the 8-channel block
+    (2, 8, 24, 5, 7, 1, 1, 2, (0, 0, 0, 0), 0, 255, 8),
 ]
 
 
