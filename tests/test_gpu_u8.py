@@ -277,6 +277,34 @@ def test_max_pooling_3x3_stride_2_by_lane_shifts(shape):
     _same(Q.unpack(g.check(), ref.shape, 16), ref, f"max pool u8 3x3 s2 {shape}")
 
 
+WIDE_CONV_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad, zx, zw, relu: input and output channels multiples of 64
+    (2, 64, 64, 9, 7, 3, 3, 1, (1, 1, 1, 1), 120, 131, False),     # 63 pixels: a ragged fourth tile
+    (3, 64, 128, 20, 18, 3, 3, 1, (1, 1, 1, 1), 128, 128, True),   # no corrections; two groups of output blocks
+    (2, 128, 64, 11, 13, 3, 3, 2, (0, 1, 0, 1), 0, 255, False),    # stride 2, extreme zero points
+    (1, 64, 64, 33, 40, 3, 3, 1, (1, 1, 1, 1), 17, 128, True),     # only the filter sums
+    (2, 64, 64, 8, 8, 2, 4, 1, (0, 1, 2, 1), 128, 200, False),     # an uneven window; only the pixel sums
+    (1, 256, 64, 6, 5, 3, 3, 1, (1, 1, 1, 1), 140, 100, False),    # four steps per tap
+    (2, 64, 64, 5, 5, 5, 5, 1, (2, 2, 2, 2), 99, 160, True),       # 25 taps: an odd number of steps
+    (70, 64, 64, 3, 3, 3, 3, 1, (1, 1, 1, 1), 131, 120, False),    # many images of less than one tile
+    (1, 64, 64, 57, 56, 1, 3, 1, (0, 0, 1, 1), 120, 131, False),   # a one-row window
+]
+
+
+@pytest.mark.parametrize("case", WIDE_CONV_CASES)
+def test_conv_four_blocks_per_step(case):
+    """Layers whose matrix instruction takes one tap of four input blocks, with the filter sums given and taken inside."""
+    N, Ci, Co, H, W, kh, kw, s, pad, zx, zw, relu = case
+    r = _rng(15)
+    x, w = WL.u8_codes(r, (N, Ci, H, W)), WL.u8_codes(r, (Co, Ci, kh, kw))
+    q = _quant_for(Q.conv2d_acc(x, w, s, pad, zx, zw), zx, zw, relu)
+    ref = Q.conv2d(x, w, s, pad, q)
+    _same(_conv(x, w, s, pad, q, 16, 16, with_sums=True), ref, f"conv u8, sums given {case}")
+    _same(_conv(x, w, s, pad, q, 16, 16), ref, f"conv u8 {case}")
+    assert len(np.unique(ref)) > 8
+    q = _quant(Ci * kh * kw, zx, zw, mult=(1 << 31) - 1, shift=0, zy=9)        # the wide requantization path
+    _same(_conv(x, w, s, pad, q, 16, 16, with_sums=True), Q.conv2d(x, w, s, pad, q), f"conv u8 wide {case}")
+
+
 FIRST_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad, zx, zw, Cob
     (3, 3, 16, 32, 32, 3, 3, 1, (1, 1, 1, 1), 128, 128, 16),     # residual CNN's first layer
     (2, 3, 8, 96, 96, 3, 3, 2, (0, 1, 0, 1), 117, 140, 8),       # depthwise-separable CNN's
