@@ -454,6 +454,16 @@ def test_quantized_networks(name, N):
     _same(_run_u8(net, x, ws, qs), ref, f"u8 {name} batch {N}")
 
 
+@pytest.mark.parametrize("name,N", [("dsep_cnn", 256), ("audio_cnn", 1024)])
+def test_quantized_networks_full_batch_sampled(name, N):
+    """The batches the benchmark times; the oracle recomputes the first and the last sixteen images (images are independent)."""
+    net = getattr(WL, name)()
+    x, ws, qs = WL.quantized_network_tensors(net, N, WL.BASE_SEED + 300 + N)
+    got = _run_u8(net, x, ws, qs)
+    for lo in (0, N - 16):
+        _same(got[lo:lo + 16], Q.run_network(net, x[lo:lo + 16], ws, qs), f"u8 {name} batch {N}, images {lo}..{lo + 15}")
+
+
 def test_network_table_errors():
     net = _chain_table()
     x, ws, qs = WL.quantized_network_tensors(net, 2, 4244)
