@@ -315,11 +315,13 @@ int small_network_launches_at(const small_layer *layers, int n_layers, int N, in
  * depthwise result stays on the compute unit and its buffer is never written (allowed only when no later
  * layer reads that buffer before it is rewritten). The depthwise sum is then taken in a different order
  * than by small_dwconv2d: results agree within the tolerance of the two layers, not bit for bit.
- * Two to eight such pairs in a row -- depthwise stride 1 with padding 1, 64 -> 64 or 128 -> 128 channels in every pair,
- * each pair reading what the pair before wrote, images of at most 64 pixels --
+ * Two to twelve such pairs in a row -- any strides, paddings and channel counts (multiples of 16), each pair reading
+ * what the pair before wrote, every tensor of the run an image of at most 64 pixels --
  * run in ONE kernel from the first pair's source to the last pair's destination: a workgroup keeps whole images on
  * the compute unit through all pairs. Every buffer the table writes inside the run except that destination is
- * never written (same liveness rule); the destination may be the run's own source buffer. Same tolerance.
+ * never written (same liveness rule); the destination may be the run's own source buffer (when the pairs change the
+ * tensor's shape, the runner then writes into the memory of the last depthwise layer's buffer and lets the two
+ * workspace slots change places, as for a single pair). Same tolerance.
  * A run of two to sixteen pointwise layers (SMALL_OP_DENSE on 1x1 images, unpadded stride-1 1x1 SMALL_OP_CONV;
  * at most 128 channels per tensor, in 16-channel blocks, or 8 channels in one 8-channel block for tensors
  * inside the run), each optionally followed by an in-place ReLU and each read only by the next, runs in one

@@ -7,7 +7,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsmall_hip.so")
 PROBE_LIB = os.path.join(HERE, "libsmall_probe.so")       # the benchmark's matrix-rate probe, a library of its own
-SOURCES = ["elementwise.hip", "window.hip", "window_rows.hip", "window_dpp.hip", "window_dpp_u8.hip", "pool_dpp_u8.hip", "quant_ends.hip", "pool_dpp.hip", "conv.hip", "conv_same.hip", "conv_pw.hip", "dwpw.hip", "dwpw_chain.hip", "chain.hip", "resident.hip", "quant.hip", "table2.hip", "small_api.hip"]
+SOURCES = ["elementwise.hip", "window.hip", "window_rows.hip", "window_dpp.hip", "window_dpp_u8.hip", "pool_dpp_u8.hip", "quant_ends.hip", "pool_dpp.hip", "conv.hip", "conv_same.hip", "conv_pw.hip", "dwpw.hip", "dwpw_run.hip", "chain.hip", "resident.hip", "quant.hip", "table2.hip", "small_api.hip"]
 # packed fp32 VALU ops are switched off for every device translation unit
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function", "-Wno-pass-failed",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -767,51 +767,75 @@ Fusion plan_fusion(const small_layer *L, int nL, int i, bool allow_chain = true)
     return f;
 }
 
-// A run of depthwise + pointwise blocks from layer i on that one launch of dwpw_chain.hip can take: every block is a
-// pair plan_fusion already joins (depthwise 3x3, stride 1, padding 1 -> 1x1 convolution, in-place ReLUs folded), C -> C
-// channels, each block reading what the one before wrote. The launch writes the last block's destination only, so
-// every other buffer the table writes inside the run must be dead afterwards. Returns the number of blocks (0 or
-// >= 2); dw_idx / pw_idx: table indices, relu flags per block, *covered: layers of the run after layer i.
-int plan_dwpw_run(const small_layer *L, int nL, int i, int *dw_idx, int *pw_idx, int *dw_relu, int *pw_relu, int *covered)
+// A run of depthwise + pointwise blocks that one launch of dwpw_run.hip takes: every block is a pair plan_fusion already
+// joins (depthwise 3x3 -> 1x1 convolution, in-place ReLUs folded) on images of at most 64 pixels, each block reading what
+// the one before wrote; strides, paddings and channel counts may change from block to block. The launch writes the last
+// block's result only, so every other buffer the table writes inside the run must be dead afterwards.
+struct DwpwRun {
+    int n;                                  // blocks (0: no run)
+    int dw_idx[kDwpwChainMaxBlocks], pw_idx[kDwpwChainMaxBlocks];
+    DwpwRunBlock block[kDwpwChainMaxBlocks];
+    int covered;                            // layers behind layer i that the launch covers
+    int rename;                             // the result goes to the memory of the last depthwise layer's destination,
+                                            // which then changes places with the memory of the last convolution's
+};
+
+// The run of depthwise + pointwise blocks from layer i on (a depthwise layer whose input is an H x W image) that one
+// launch of dwpw_run.hip takes. Pointer-free: the same answer whether the table is being planned or run.
+DwpwRun plan_dwpw_run(const small_layer *L, int nL, int i, int H, int W)
 {
-    int n = 0, k = i, end = i;
-    const int C = L[i].Ci;
+    DwpwRun r;
+    memset(&r, 0, sizeof(r));
+    int n = 0, k = i, C = L[i].Ci;
     while (k < nL && n < kDwpwChainMaxBlocks) {
         const small_layer &d = L[k];
-        if (d.op != SMALL_OP_DWCONV || d.Ci != C || d.Cib != 16 || d.kh != 3 || d.kw != 3 || d.stride != 1 || d.pad.t != 1 ||
-            d.pad.b != 1 || d.pad.l != 1 || d.pad.r != 1)
-            break;
+        if (d.op != SMALL_OP_DWCONV || d.Ci != C || d.Cib != 16 || d.kh != 3 || d.kw != 3 || d.stride < 1) break;
+        if (d.pad.t < 0 || d.pad.b < 0 || d.pad.l < 0 || d.pad.r < 0 || d.pad.t > 2 || d.pad.b > 2 || d.pad.l > 2 || d.pad.r > 2) break;
         const Fusion f = plan_fusion(L, nL, k);
         if (!f.pw) break;
         const small_layer &pw = L[k + f.pw];
-        if (pw.Co != C || pw.Cob != 16) break;
-        if (n > 0 && d.src != L[pw_idx[n - 1]].dst) break;
-        dw_idx[n] = k;
-        pw_idx[n] = k + f.pw;
-        dw_relu[n] = (f.epilogue & EPI_RELU) != 0;
-        pw_relu[n] = f.pw_relu;
+        if (pw.Cob != 16 || pw.Co % 16) break;
+        if (n > 0 && d.src != L[r.pw_idx[n - 1]].dst) break;
+        const int Ho = small_out_dim(H, 3, d.stride, d.pad.t, d.pad.b), Wo = small_out_dim(W, 3, d.stride, d.pad.l, d.pad.r);
+        if (Ho < 1 || Wo < 1 || (long)H * W > 64 || (long)Ho * Wo > 64) break;
+        r.dw_idx[n] = k;
+        r.pw_idx[n] = k + f.pw;
+        r.block[n] = DwpwRunBlock{d.filt, pw.filt, (f.epilogue & EPI_RELU) != 0, f.pw_relu, C, pw.Co, H, W, Ho, Wo, d.stride,
+                                  d.pad.t, d.pad.l};
         ++n;
-        end = k + f.skip;
-        k = end + 1;
+        C = pw.Co; H = Ho; W = Wo;
+        k = k + f.skip + 1;
     }
-    // shorten the run until everything it does not write is dead behind it
-    while (n >= 2) {
-        const int last = pw_idx[n - 1], T = L[last].dst;
-        const int after = last + 1 + pw_relu[n - 1];
+    // shorten the run until its shapes fit, everything it does not write is dead behind it, and its result has a
+    // place that is not its input
+    for (; n >= 2; --n) {
+        if (!dwpw_run_eligible(r.block, n)) continue;
+        const int last = r.pw_idx[n - 1], T = L[last].dst, S = L[i].src;
+        const int after = last + 1 + r.block[n - 1].pw_relu;
         bool ok = T != SMALL_BUF_IN;
         for (int b = 0; b < n && ok; ++b) {
-            const int ids[2] = {L[dw_idx[b]].dst, L[pw_idx[b]].dst};
+            const int ids[2] = {L[r.dw_idx[b]].dst, L[r.pw_idx[b]].dst};
             for (int id : ids)
                 if (id != T && !dead_from(L, nL, after, id)) ok = false;
         }
-        // the run's input may be its output (each workgroup reads its images before it writes them), nothing else may
-        if (ok) {
-            *covered = after - 1 - i;
-            return n;
+        if (!ok) continue;
+        bool same_shape = true;
+        for (int b = 0; b < n; ++b)
+            if (r.block[b].Cin != r.block[b].Cout || r.block[b].Hi != r.block[b].Ho || r.block[b].Wi != r.block[b].Wo) same_shape = false;
+        int rename = 0;
+        if (T == S && !same_shape) {
+            // in place with changing shapes: workgroups would write over images others have not read yet
+            const int B = L[r.dw_idx[n - 1]].dst;
+            if (S < 0 || B < 0 || B == S) continue;
+            rename = 1;
         }
-        --n;
+        r.n = n;
+        r.covered = after - 1 - i;
+        r.rename = rename;
+        return r;
     }
-    return 0;
+    r.n = 0;
+    return r;
 }
 
 // The convolution groups from layer i on that may run as one image-resident launch (resident.hip): fills rg
@@ -1092,7 +1116,24 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (l.dst == l.src) return SMALL_ERR_ALIAS;
                 if (l.op == SMALL_OP_DWCONV && !l.filt) return SMALL_ERR_NULL;
                 o = Shape{l.Ci, g.Ho, g.Wo, l.Cib, true};
-                if (head && fu.pw && !res_n) {
+                // several such blocks in a row on small images: one launch for the whole run
+                DwpwRun dr;
+                dr.n = 0;
+                if (head && fu.pw && !res_n && l.op == SMALL_OP_DWCONV && l.Cib == 16 && (long)a.H * a.W <= 64 &&
+                    in_elems * sizeof(float) < ((size_t)1 << 32)) {
+                    dr = plan_dwpw_run(L, nL, i, a.H, a.W);
+                    if (dr.n && run) {
+                        const small_layer &ldw = L[dr.dw_idx[dr.n - 1]], &lpw = L[dr.pw_idx[dr.n - 1]];
+                        const DwpwRunBlock &lb = dr.block[dr.n - 1];
+                        const float *rin = ptr(l.src);
+                        float *rout = ptr(dr.rename ? ldw.dst : lpw.dst);
+                        const size_t out_elems = (size_t)N * lb.Cout * lb.Ho * lb.Wo;
+                        uintptr_t bits = (uintptr_t)rin | (uintptr_t)rout;
+                        for (int b = 0; b < dr.n; ++b) bits |= (uintptr_t)dr.block[b].dw | (uintptr_t)dr.block[b].pw;
+                        if ((bits & 15u) || (rin != rout && overlap(rin, in_elems, rout, out_elems))) dr.n = 0;
+                    }
+                }
+                if (!dr.n && head && fu.pw && !res_n) {
                     // the one-kernel depthwise + pointwise path also needs a geometry and (known only when running)
                     // pointers it can take; otherwise the pointwise convolution becomes a launch of its own
                     const small_layer &pw = L[i + fu.pw];
@@ -1105,29 +1146,11 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                         fused_away = fu.skip;
                     }
                 }
-                // several such blocks in a row on small images: one launch for the whole run
-                int run_blocks = 0, run_dw[kDwpwChainMaxBlocks], run_pw[kDwpwChainMaxBlocks], run_dr[kDwpwChainMaxBlocks],
-                    run_pr[kDwpwChainMaxBlocks], run_covered = 0;
-                if (head && fu.pw && !res_n && l.op == SMALL_OP_DWCONV && g.Ho == a.H && g.Wo == a.W &&
-                    dwpw_chain_eligible(l.Ci, a.H, a.W) && in_elems * sizeof(float) < ((size_t)1 << 32)) {
-                    run_blocks = plan_dwpw_run(L, nL, i, run_dw, run_pw, run_dr, run_pr, &run_covered);
-                    if (run_blocks && run) {
-                        const float *rin = ptr(l.src);
-                        float *rout = ptr(L[run_pw[run_blocks - 1]].dst);
-                        uintptr_t bits = (uintptr_t)rin | (uintptr_t)rout;
-                        for (int b = 0; b < run_blocks; ++b) bits |= (uintptr_t)L[run_dw[b]].filt | (uintptr_t)L[run_pw[b]].filt;
-                        if ((bits & 15u) || (rin != rout && overlap(rin, in_elems, rout, in_elems))) run_blocks = 0;
-                    }
-                }
-                if (run_blocks) {
-                    fused_away = run_covered;
-                    if (launch) {
-                        DwpwChainBlock cb[kDwpwChainMaxBlocks];
-                        for (int b = 0; b < run_blocks; ++b)
-                            cb[b] = DwpwChainBlock{L[run_dw[b]].filt, L[run_pw[b]].filt, run_dr[b], run_pr[b]};
-                        rc = from_hip(launch_dwpw_chain(ptr(l.src), ptr(L[run_pw[run_blocks - 1]].dst), cb, run_blocks, N, l.Ci, a.H,
-                                                        a.W, s));
-                    }
+                if (dr.n) {
+                    const small_layer &ldw = L[dr.dw_idx[dr.n - 1]], &lpw = L[dr.pw_idx[dr.n - 1]];
+                    fused_away = dr.covered;
+                    if (launch) rc = from_hip(launch_dwpw_run(ptr(l.src), ptr(dr.rename ? ldw.dst : lpw.dst), dr.block, dr.n, N, s));
+                    if (dr.rename) std::swap(phys[ldw.dst], phys[lpw.dst]);
                 } else if (l.op == SMALL_OP_DWCONV && res_n) {
                     if (launch) rc = from_hip(launch_resident(res_g, res_n, ptr(l.src), ptr(res_g[res_n - 1].dst), N, s));
                 } else if (l.op == SMALL_OP_DWCONV && fu.pw) {

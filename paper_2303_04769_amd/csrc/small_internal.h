@@ -210,15 +210,18 @@ bool chain_layer_eligible(int Ci, int Co, int Cib, int Cob);
 hipError_t launch_dense_chain(const float *in, float *out, const ChainLayer *layers, int n_layers, long M, int HW,
                               hipStream_t s);
 
-// A run of [depthwise 3x3 stride 1 padding 1 (+ ReLU)] -> [1x1 convolution (+ ReLU)] blocks, each C -> C channels
-// (C = 64 or 128, 16-channel blocks) on images of at most 128 pixels, in one launch (dwpw_chain.hip). out may be in
-// itself (a workgroup reads its images before it writes them) but may not overlap it otherwise; pointers 16-byte
-// aligned; tensors smaller than 4 GiB.
-constexpr int kDwpwChainMaxBlocks = 8;
-struct DwpwChainBlock { const float *dw, *pw; int dw_relu, pw_relu; };
-bool dwpw_chain_eligible(int C, int H, int W);
-hipError_t launch_dwpw_chain(const float *in, float *out, const DwpwChainBlock *blocks, int n_blocks, int N, int C, int H, int W,
-                             hipStream_t s);
+// A run of [depthwise 3x3, any stride and padding (+ ReLU)] -> [1x1 convolution Cin -> Cout (+ ReLU)] blocks on 16-channel
+// blocks, every tensor of the run an image of at most 64 pixels, each block reading what the one before wrote, in one
+// launch (dwpw_run.hip). out may not overlap in, except that a run whose blocks all keep the shape may work in place (a
+// workgroup reads its images before it writes them); pointers 16-byte aligned; tensors smaller than 4 GiB.
+constexpr int kDwpwChainMaxBlocks = 12;
+struct DwpwRunBlock {
+    const float *dw, *pw;
+    int dw_relu, pw_relu;
+    int Cin, Cout, Hi, Wi, Ho, Wo, stride, pt, pl;
+};
+bool dwpw_run_eligible(const DwpwRunBlock *blocks, int n_blocks);      // shapes only
+hipError_t launch_dwpw_run(const float *in, float *out, const DwpwRunBlock *blocks, int n_blocks, int N, hipStream_t s);
 
 // Remaining Table 2 layers (table2.hip): y = x * scale[c] + shift[c]; nearest-neighbour upsampling by integer
 // factors; group convolution (geometry in g with g.Ci = all input channels, g.Co = G * K, g.Cib the activation block).

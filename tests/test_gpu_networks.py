@@ -925,6 +925,64 @@ def _dwpw_run_net(C, H, W, n_blocks, relus, alternate=True, tail=True):
     return net
 
 
+def _dwpw_var_net(C0, H, W, spec, alternate=True, tail=True):
+    """Pairs [depthwise 3x3, stride s, SAME padding, ReLU] -> [1x1 conv C -> Cout, ReLU] with (Cout, s) per pair from spec;
+    alternate: two buffers used in turn (the pair's output goes back into the depthwise layer's source), else a fresh
+    buffer per layer; tail: a max pooling into OUT after the run (else the last pair writes OUT itself)."""
+    from workloads.nets import Layer, Network, IN, OUT, same_pad
+    net = Network("dwpw_var_run", C0, H, W)
+    z = (0, 0, 0, 0)
+    src, k, C = IN, 0, C0
+    for b, (Co, s) in enumerate(spec):
+        d = (0 if src != 0 else 1) if alternate else (2 * b) % 4
+        pad = same_pad(H, 3, s) + same_pad(W, 3, s)
+        Ho, Wo = -(-H // s), -(-W // s)
+        net.wshapes.append(((C, 1, 3, 3), 9))
+        net.layers.append(Layer("dw", C, C, H, W, 3, 3, s, pad, src=src, dst=d, w=k)); k += 1
+        net.layers.append(Layer("relu", C, C, Ho, Wo, src=d, dst=d))
+        last = b + 1 == len(spec) and not tail
+        if alternate:
+            t = OUT if last else (src if src != IN else 1 - d)
+        else:
+            t = OUT if last else (2 * b + 1) % 4
+        net.wshapes.append(((Co, C, 1, 1), C))
+        net.layers.append(Layer("conv", C, Co, Ho, Wo, 1, 1, 1, z, src=d, dst=t, w=k)); k += 1
+        net.layers.append(Layer("relu", Co, Co, Ho, Wo, src=t, dst=t))
+        src, C, H, W = t, Co, Ho, Wo
+    if tail:
+        net.layers.append(Layer("maxpool", C, C, H, W, 1, 1, 1, z, src=src, dst=OUT))
+    return net
+
+
+_DSEP_HALF = [(64, 1), (128, 2)] + [(128, 1)] * 5 + [(256, 2), (256, 1)]
+DWPW_VAR_CASES = [  # C0, H, W, N, [(Cout, stride)], alternate buffers, tail
+    (64, 6, 6, 256, _DSEP_HALF, True, True),                 # the depthwise-separable CNN from its 6x6 images on: 9 blocks
+    (64, 6, 6, 1, _DSEP_HALF, True, True),
+    (64, 6, 6, 1000, _DSEP_HALF, True, False),               # several rounds of workgroups; the last block writes OUT
+    (32, 4, 4, 100, [(64, 1), (32, 1), (16, 1), (48, 1)], True, True),     # 2, 4, 1 and 3 channel blocks: parts of groups
+    (16, 7, 5, 33, [(32, 2), (64, 2)], True, True),          # odd sizes under stride 2: 7x5 -> 4x3 -> 2x2
+    (16, 8, 8, 70, [(16, 3), (32, 1), (32, 2)], False, False),             # stride 3; a fresh buffer per layer
+    (128, 3, 3, 300, [(256, 2), (256, 1)], False, True),     # shapes change, buffers do not alternate
+    (48, 2, 2, 17, [(48, 1), (96, 2), (96, 1)], True, True), # down to one pixel
+]
+
+
+@pytest.mark.parametrize("case", DWPW_VAR_CASES)
+def test_depthwise_pointwise_runs_with_changing_shapes(case):
+    """Runs whose strides and channel counts change from block to block are one launch as well (launch list); the result
+    agrees with the oracle's layer-by-layer chain for every image, within the tolerance of the longest reduction."""
+    C0, H, W, N, spec, alternate, tail = case
+    net = _dwpw_var_net(C0, H, W, spec, alternate, tail)
+    x, ws = WL.network_tensors(net, N, 8900 + C0 + N)
+    pn = S.PackedNetwork(net, ws, DEV)
+    heads = pn.launches_at(N, S.SMALL_RUN_RESIDENT_OFF)
+    assert heads == ([0, len(net.layers) - 1] if tail else [0]), heads
+    ref = O.run_network(net, x, ws)
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF)
+    assert_close(got, ref.reshape(got.shape), max(C0, max(c for c, _ in spec)), f"dwpw run, changing shapes {case}")
+    assert np.abs(ref).max() > 1e-3
+
+
 DWPW_RUN_CASES = [  # C, H, W, N, blocks, (dw relu, pw relu) pattern, alternate buffers, tail
     (128, 3, 3, 256, 5, [(1, 1)], True, True),            # the depthwise-separable CNN's tail: one image per workgroup
     (128, 3, 3, 1000, 5, [(1, 1)], True, True),           # three images per workgroup, the last workgroup with one
