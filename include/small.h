@@ -321,7 +321,9 @@ int small_network_launches_at(const small_layer *layers, int n_layers, int N, in
  * the compute unit through all pairs. Every buffer the table writes inside the run except that destination is
  * never written (same liveness rule); the destination may be the run's own source buffer (when the pairs change the
  * tensor's shape, the runner then writes into the memory of the last depthwise layer's buffer and lets the two
- * workspace slots change places, as for a single pair). Same tolerance.
+ * workspace slots change places, as for a single pair). When the run is followed by an average pooling over the whole
+ * image and a fully connected layer of at most 16 outputs that alone read its result, these close the same kernel: the
+ * run's last tensor is then never written (same liveness rule) and the launch writes the logits. Same tolerance.
  * A run of two to sixteen pointwise layers (SMALL_OP_DENSE on 1x1 images, unpadded stride-1 1x1 SMALL_OP_CONV;
  * at most 128 channels per tensor, in 16-channel blocks, or 8 channels in one 8-channel block for tensors
  * inside the run), each optionally followed by an in-place ReLU and each read only by the next, runs in one

@@ -46,6 +46,8 @@ struct DrArgs {
     int N, G, n_blocks;
     int act_bytes;         // of one activation buffer
     FastDiv by_HWi0;       // pixels per image of the run's input
+    const float *head;     // closing average over the last result's pixels + fully connected layer [Co/Cob][C/16][16][Cob],
+    int head_Co, head_Cob; // or null: the last result goes to memory
     DrBlock block[kDwpwChainMaxBlocks];
 };
 
@@ -200,6 +202,7 @@ __global__ void __launch_bounds__(kDrThreads) dwpw_run(DrArgs args)
         const FastDiv by_nCbi = dr_fd(ka->block[b].by_nCbi), by_nCbo = dr_fd(ka->block[b].by_nCbo);
         const int ngi = dr_groups(G, HWi), ng = dr_groups(G, HWo);
         const bool last = b + 1 == n_blocks;
+        const bool to_memory = last && ka->head == nullptr;
 
         // ---------------- depthwise stage: buffer 0 [nCbi][ngi] -> buffer 1 [nCbi][ng]
         for (int item = w; item < nCbi * ng; item += kDrWaves) {
@@ -267,7 +270,7 @@ __global__ void __launch_bounds__(kDrThreads) dwpw_run(DrArgs args)
                         v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
                         v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
                     }
-                    if (last) {
+                    if (to_memory) {
                         const int m = (g0 + k) * 16 + p;
                         const int im = by_HWo.div(m), pix = m - im * HWo;
                         if (im < G && img0 + im < N)
@@ -279,7 +282,50 @@ __global__ void __launch_bounds__(kDrThreads) dwpw_run(DrArgs args)
                 }
             }
         }
-        if (!last) __syncthreads();                     // buffer 0 is complete (and buffer 1 free again)
+        if (!to_memory) __syncthreads();                // buffer 0 is complete (and buffer 1 free again)
+    }
+
+    // ---------------- the network's head on the last result (buffer 0): mean over the pixels, fully connected layer
+    if (ka->head != nullptr) {
+        const int nCb = ka->block[n_blocks - 1].nCbo, C = nCb * 16;
+        const int HW = ka->block[n_blocks - 1].Ho * ka->block[n_blocks - 1].Wo, ng = dr_groups(G, HW);
+        const int Co = ka->head_Co, Cob = ka->head_Cob;
+        const float *act = reinterpret_cast<const float *>(lds_c + act0);
+        float *red = reinterpret_cast<float *>(lds_c + act1);          // [wave][16 outputs]
+        const float scale = 1.f / (float)HW;
+        const int tid = threadIdx.x;
+        for (int im = 0; im < G && img0 + im < N; ++im) {
+            float part[16];
+#pragma unroll
+            for (int o = 0; o < 16; ++o) part[o] = 0.f;
+            for (int c = tid; c < C; c += kDrThreads) {
+                float sum = 0.f;
+                for (int pix = 0; pix < HW; ++pix) {
+                    const int m = im * HW + pix;
+                    sum += act[(((c >> 4) * ng + (m >> 4)) * 64 + ((c & 15) >> 2) * 16 + (m & 15)) * 4 + (c & 3)];
+                }
+#pragma unroll
+                for (int o = 0; o < 16; ++o)
+                    if (o < Co) part[o] = fmaf(sum, ka->head[((size_t)(o / Cob) * C + c) * Cob + o % Cob], part[o]);
+            }
+#pragma unroll
+            for (int o = 0; o < 16; ++o) {
+                if (o < Co) {
+                    float v = part[o];
+#pragma unroll
+                    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+                    if (lane == 0) red[w * 16 + o] = v;
+                }
+            }
+            __syncthreads();
+            if (tid < Co) {
+                float v = 0.f;
+#pragma unroll
+                for (int k = 0; k < kDrWaves; ++k) v += red[k * 16 + tid];
+                ka->out[(size_t)(img0 + im) * Co + tid] = v * scale;
+            }
+            __syncthreads();
+        }
     }
     wait_vmcnt<0>();        // copies issued past the run's last step must land before the workgroup's LDS is released
 }
@@ -323,10 +369,12 @@ bool dwpw_run_eligible(const DwpwRunBlock *b, int n)
     return kDrRingBytes + 2 * dr_act_bytes(b, n, 1) <= kDrLdsMax;
 }
 
-hipError_t launch_dwpw_run(const float *in, float *out, const DwpwRunBlock *blocks, int n_blocks, int N, hipStream_t s)
+hipError_t launch_dwpw_run(const float *in, float *out, const DwpwRunBlock *blocks, int n_blocks, int N, const DwpwRunHead &head,
+                           hipStream_t s)
 {
     DrArgs a;
     a.in = in; a.out = out;
+    a.head = head.filt; a.head_Co = head.Co; a.head_Cob = head.Cob;
     a.N = N; a.n_blocks = n_blocks;
     int most_px = 1;
     for (int i = 0; i < kDwpwChainMaxBlocks; ++i) {

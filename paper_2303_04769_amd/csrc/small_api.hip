@@ -778,6 +778,9 @@ struct DwpwRun {
     int covered;                            // layers behind layer i that the launch covers
     int rename;                             // the result goes to the memory of the last depthwise layer's destination,
                                             // which then changes places with the memory of the last convolution's
+    int head;                               // table index of a fully connected layer that closes the run (behind an
+                                            // average over the whole image), or 0: the launch then writes that layer's
+                                            // destination and never the run's last tensor
 };
 
 // The run of depthwise + pointwise blocks from layer i on (a depthwise layer whose input is an H x W image) that one
@@ -832,6 +835,18 @@ DwpwRun plan_dwpw_run(const small_layer *L, int nL, int i, int H, int W)
         r.n = n;
         r.covered = after - 1 - i;
         r.rename = rename;
+        // the network's head behind the run: average over the whole (last) image + fully connected layer
+        if (after + 1 < nL && L[after].op == SMALL_OP_AVGPOOL && L[after].src == T && T >= 0) {
+            const small_layer &pl = L[after], &d = L[after + 1];
+            const DwpwRunBlock &lb = r.block[n - 1];
+            const Fusion hf = plan_fusion(L, nL, after);
+            if (hf.head && pl.kh == lb.Ho && pl.kw == lb.Wo && pl.Ci == lb.Cout && pl.Cib == 16 && d.dst != S &&
+                dead_from(L, nL, after + 2, T)) {
+                r.head = after + 1;
+                r.covered += 2;
+                r.rename = 0;
+            }
+        }
         return r;
     }
     r.n = 0;
@@ -1126,11 +1141,13 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                         const small_layer &ldw = L[dr.dw_idx[dr.n - 1]], &lpw = L[dr.pw_idx[dr.n - 1]];
                         const DwpwRunBlock &lb = dr.block[dr.n - 1];
                         const float *rin = ptr(l.src);
-                        float *rout = ptr(dr.rename ? ldw.dst : lpw.dst);
-                        const size_t out_elems = (size_t)N * lb.Cout * lb.Ho * lb.Wo;
-                        uintptr_t bits = (uintptr_t)rin | (uintptr_t)rout;
+                        float *rout = ptr(dr.head ? L[dr.head].dst : (dr.rename ? ldw.dst : lpw.dst));
+                        const size_t out_elems = dr.head ? (size_t)N * L[dr.head].Co : (size_t)N * lb.Cout * lb.Ho * lb.Wo;
+                        uintptr_t bits = (uintptr_t)rin | (uintptr_t)(dr.head ? nullptr : rout);
                         for (int b = 0; b < dr.n; ++b) bits |= (uintptr_t)dr.block[b].dw | (uintptr_t)dr.block[b].pw;
-                        if ((bits & 15u) || (rin != rout && overlap(rin, in_elems, rout, out_elems))) dr.n = 0;
+                        if (dr.head && !L[dr.head].filt) bits |= 1u;
+                        if ((bits & 15u) || (rin != rout && overlap(rin, in_elems, rout, out_elems)) || (dr.head && rin == rout))
+                            dr.n = 0;
                     }
                 }
                 if (!dr.n && head && fu.pw && !res_n) {
@@ -1149,7 +1166,10 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 if (dr.n) {
                     const small_layer &ldw = L[dr.dw_idx[dr.n - 1]], &lpw = L[dr.pw_idx[dr.n - 1]];
                     fused_away = dr.covered;
-                    if (launch) rc = from_hip(launch_dwpw_run(ptr(l.src), ptr(dr.rename ? ldw.dst : lpw.dst), dr.block, dr.n, N, s));
+                    const DwpwRunHead hd = dr.head ? DwpwRunHead{L[dr.head].filt, L[dr.head].Co, L[dr.head].Cob} : DwpwRunHead{nullptr, 0, 0};
+                    if (launch)
+                        rc = from_hip(launch_dwpw_run(ptr(l.src), ptr(dr.head ? L[dr.head].dst : (dr.rename ? ldw.dst : lpw.dst)),
+                                                      dr.block, dr.n, N, hd, s));
                     if (dr.rename) std::swap(phys[ldw.dst], phys[lpw.dst]);
                 } else if (l.op == SMALL_OP_DWCONV && res_n) {
                     if (launch) rc = from_hip(launch_resident(res_g, res_n, ptr(l.src), ptr(res_g[res_n - 1].dst), N, s));

@@ -221,7 +221,11 @@ struct DwpwRunBlock {
     int Cin, Cout, Hi, Wi, Ho, Wo, stride, pt, pl;
 };
 bool dwpw_run_eligible(const DwpwRunBlock *blocks, int n_blocks);      // shapes only
-hipError_t launch_dwpw_run(const float *in, float *out, const DwpwRunBlock *blocks, int n_blocks, int N, hipStream_t s);
+// head.filt != null: the run closes with the mean over the last result's pixels and a fully connected layer on it
+// (at most 16 outputs, filter [Co/Cob][C/16][1][1][16][Cob]); out is then [N][Co] and the last result is not written.
+struct DwpwRunHead { const float *filt; int Co, Cob; };
+hipError_t launch_dwpw_run(const float *in, float *out, const DwpwRunBlock *blocks, int n_blocks, int N, const DwpwRunHead &head,
+                           hipStream_t s);
 
 // Remaining Table 2 layers (table2.hip): y = x * scale[c] + shift[c]; nearest-neighbour upsampling by integer
 // factors; group convolution (geometry in g with g.Ci = all input channels, g.Co = G * K, g.Cib the activation block).

@@ -983,6 +983,39 @@ def test_depthwise_pointwise_runs_with_changing_shapes(case):
     assert np.abs(ref).max() > 1e-3
 
 
+DWPW_HEAD_CASES = [  # C0, H, W, N, [(Cout, stride)], outputs, output block
+    (64, 6, 6, 300, [(64, 1), (128, 2), (256, 2)], 2, 2),        # two outputs, as the depthwise-separable CNN
+    (128, 3, 3, 4100, [(128, 1), (128, 1)], 10, 10),             # seven images per workgroup
+    (32, 4, 4, 19, [(64, 2), (64, 1), (96, 1)], 16, 8),          # two blocks of eight outputs; 96 channels
+    (16, 1, 1, 5, [(32, 1), (16, 1)], 3, 3),                     # one pixel
+    (48, 5, 7, 64, [(48, 2), (80, 1)], 12, 12),
+]
+
+
+@pytest.mark.parametrize("case", DWPW_HEAD_CASES)
+def test_depthwise_pointwise_runs_closed_by_the_head(case):
+    """A run followed by the average over the whole image and a fully connected layer is one launch that writes the
+    logits only; every image against the oracle's layer-by-layer chain."""
+    from workloads.nets import Layer, OUT
+    C0, H, W, N, spec, Co, Cob = case
+    net = _dwpw_var_net(C0, H, W, spec, True, True)
+    pool_in = net.layers[-1]                      # the generator's closing max pooling: replaced by the head
+    C, Ho, Wo, src = pool_in.Ci, pool_in.H, pool_in.W, pool_in.src
+    net.layers.pop()
+    free = 2                                       # the generator alternates buffers 0 and 1
+    net.layers.append(Layer("avgpool", C, C, Ho, Wo, Ho, Wo, 1, (0, 0, 0, 0), src=src, dst=free))
+    net.wshapes.append(((Co, C, 1, 1), C))
+    net.layers.append(Layer("dense", C, Co, 1, 1, 1, 1, 1, (0, 0, 0, 0), src=free, dst=OUT, w=len(net.wshapes) - 1, Cob=Cob))
+    x, ws = WL.network_tensors(net, N, 9100 + C0 + N)
+    pn = S.PackedNetwork(net, ws, DEV)
+    heads = pn.launches_at(N, S.SMALL_RUN_RESIDENT_OFF)
+    assert heads == [0], heads
+    ref = O.run_network(net, x, ws)
+    got = _run(net, x, ws, S.SMALL_RUN_RESIDENT_OFF)
+    assert_close(got, ref.reshape(got.shape), max(C0, max(c for c, _ in spec)), f"dwpw run with head {case}")
+    assert np.abs(ref).max() > 1e-3
+
+
 DWPW_RUN_CASES = [  # C, H, W, N, blocks, (dw relu, pw relu) pattern, alternate buffers, tail
     (128, 3, 3, 256, 5, [(1, 1)], True, True),            # the depthwise-separable CNN's tail: one image per workgroup
     (128, 3, 3, 1000, 5, [(1, 1)], True, True),           # three images per workgroup, the last workgroup with one
