@@ -316,7 +316,8 @@ int small_network_launches_at(const small_layer *layers, int n_layers, int N, in
  * layer reads that buffer before it is rewritten). The depthwise sum is then taken in a different order
  * than by small_dwconv2d: results agree within the tolerance of the two layers, not bit for bit.
  * Two to twelve such pairs in a row -- any strides, paddings and channel counts (multiples of 16), each pair reading
- * what the pair before wrote, every tensor of the run an image of at most 64 pixels --
+ * what the pair before wrote, every tensor of the run a small image (at most 256 pixels and 6144 values; with one image
+ * per workgroup only up to one round of workgroups: the launch list depends on the batch) --
  * run in ONE kernel from the first pair's source to the last pair's destination: a workgroup keeps whole images on
  * the compute unit through all pairs. Every buffer the table writes inside the run except that destination is
  * never written (same liveness rule); the destination may be the run's own source buffer (when the pairs change the

@@ -363,10 +363,32 @@ bool dwpw_run_eligible(const DwpwRunBlock *b, int n)
     for (int i = 0; i < n; ++i) {
         if (b[i].Cin % 16 || b[i].Cout % 16 || b[i].Cin < 16 || b[i].Cout < 16) return false;
         if (b[i].Hi < 1 || b[i].Wi < 1 || b[i].Ho < 1 || b[i].Wo < 1 || b[i].stride < 1) return false;
-        if ((long)b[i].Hi * b[i].Wi > 64 || (long)b[i].Ho * b[i].Wo > 64) return false;    // whole images in 64 pixel slots
+        if ((long)b[i].Hi * b[i].Wi > kDwpwRunMaxPixels || (long)b[i].Ho * b[i].Wo > kDwpwRunMaxPixels) return false;
+        // one workgroup per image must beat a launch per block: images of 8000 values (the audio CNN's 64 x 25 x 5) lose,
+        // 35 -> 53 us for the network at batch 1 and 116 -> 190 at 1024; images of 4608 (32 x 12 x 12) gain
+        if ((long)b[i].Cin * b[i].Hi * b[i].Wi > kDwpwRunMaxValues || (long)b[i].Cout * b[i].Ho * b[i].Wo > kDwpwRunMaxValues) return false;
+        // a pointwise item holds accumulators for at most four pixel groups (one image per workgroup; with more images
+        // per workgroup the launch keeps within 64 pixel slots)
+        const int ng = (b[i].Ho * b[i].Wo + 15) / 16, nCbo = b[i].Cout / 16;
+        const int parts = nCbo >= kDrWaves ? 1 : std::min(kDrWaves / nCbo, ng);
+        if ((ng + parts - 1) / parts > 4) return false;
         if (i > 0 && (b[i].Cin != b[i - 1].Cout || b[i].Hi != b[i - 1].Ho || b[i].Wi != b[i - 1].Wo)) return false;
     }
     return kDrRingBytes + 2 * dr_act_bytes(b, n, 1) <= kDrLdsMax;
+}
+
+int dwpw_run_images(const DwpwRunBlock *blocks, int n_blocks, int N)
+{
+    // As many images as 64 pixel slots (and LDS) hold, fewer where one round of workgroups does with fewer. Small tiles waste matrix-instruction lanes (a 3 x 3 image fills 9 of 16) and stream the filters more often,
+    // but these runs are bound by the chain of stages of one workgroup, not by arithmetic.
+    int most_px = 1;
+    for (int i = 0; i < n_blocks; ++i) most_px = std::max({most_px, blocks[i].Hi * blocks[i].Wi, blocks[i].Ho * blocks[i].Wo});
+    int G = std::max(1, 64 / most_px);
+    while (G > 1 && kDrRingBytes + 2 * dr_act_bytes(blocks, n_blocks, G) > kDrLdsMax) --G;
+    // no more than one round of workgroups needs (640 images on 256 compute units: three per workgroup, 214 workgroups,
+    // not two and 320)
+    const int one_round = (N + device_cus() - 1) / device_cus();
+    return std::max(1, std::min(G, one_round));
 }
 
 hipError_t launch_dwpw_run(const float *in, float *out, const DwpwRunBlock *blocks, int n_blocks, int N, const DwpwRunHead &head,
@@ -376,7 +398,6 @@ hipError_t launch_dwpw_run(const float *in, float *out, const DwpwRunBlock *bloc
     a.in = in; a.out = out;
     a.head = head.filt; a.head_Co = head.Co; a.head_Cob = head.Cob;
     a.N = N; a.n_blocks = n_blocks;
-    int most_px = 1;
     for (int i = 0; i < kDwpwChainMaxBlocks; ++i) {
         const DwpwRunBlock &b = blocks[i < n_blocks ? i : n_blocks - 1];
         DrBlock &d = a.block[i];
@@ -385,14 +406,9 @@ hipError_t launch_dwpw_run(const float *in, float *out, const DwpwRunBlock *bloc
         d.Hi = b.Hi; d.Wi = b.Wi; d.Ho = b.Ho; d.Wo = b.Wo; d.stride = b.stride; d.pt = b.pt; d.pl = b.pl;
         d.by_HWo = make_fastdiv(b.Ho * b.Wo); d.by_Wo = make_fastdiv(b.Wo);
         d.by_nCbi = make_fastdiv(d.nCbi); d.by_nCbo = make_fastdiv(d.nCbo);
-        most_px = std::max({most_px, b.Hi * b.Wi, b.Ho * b.Wo});
     }
     a.by_HWi0 = make_fastdiv(blocks[0].Hi * blocks[0].Wi);
-    // Images per workgroup: as many as 64 pixel slots hold, fewer where that leaves compute units without a workgroup
-    // or LDS without room. Small tiles waste matrix-instruction lanes (a 3 x 3 image fills 9 of 16) and stream the
-    // filters more often, but these runs are bound by the chain of stages of one workgroup, not by arithmetic.
-    int G = std::max(1, 64 / most_px);
-    while (G > 1 && ((N + G - 1) / G < device_cus() || kDrRingBytes + 2 * dr_act_bytes(blocks, n_blocks, G) > kDrLdsMax)) --G;
+    const int G = dwpw_run_images(blocks, n_blocks, N);
     a.G = G;
     a.act_bytes = (int)dr_act_bytes(blocks, n_blocks, G);
     // the filter ring as deep as LDS allows: a run streams all its filters through every workgroup, and what bounds it is

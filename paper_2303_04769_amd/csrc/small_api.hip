@@ -784,8 +784,8 @@ struct DwpwRun {
 };
 
 // The run of depthwise + pointwise blocks from layer i on (a depthwise layer whose input is an H x W image) that one
-// launch of dwpw_run.hip takes. Pointer-free: the same answer whether the table is being planned or run.
-DwpwRun plan_dwpw_run(const small_layer *L, int nL, int i, int H, int W)
+// launch of dwpw_run.hip takes at batch N. Pointer-free: the same answer whether the table is being planned or run.
+DwpwRun plan_dwpw_run(const small_layer *L, int nL, int i, int H, int W, int N)
 {
     DwpwRun r;
     memset(&r, 0, sizeof(r));
@@ -800,7 +800,7 @@ DwpwRun plan_dwpw_run(const small_layer *L, int nL, int i, int H, int W)
         if (pw.Cob != 16 || pw.Co % 16) break;
         if (n > 0 && d.src != L[r.pw_idx[n - 1]].dst) break;
         const int Ho = small_out_dim(H, 3, d.stride, d.pad.t, d.pad.b), Wo = small_out_dim(W, 3, d.stride, d.pad.l, d.pad.r);
-        if (Ho < 1 || Wo < 1 || (long)H * W > 64 || (long)Ho * Wo > 64) break;
+        if (Ho < 1 || Wo < 1 || (long)H * W > kDwpwRunMaxPixels || (long)Ho * Wo > kDwpwRunMaxPixels) break;
         r.dw_idx[n] = k;
         r.pw_idx[n] = k + f.pw;
         r.block[n] = DwpwRunBlock{d.filt, pw.filt, (f.epilogue & EPI_RELU) != 0, f.pw_relu, C, pw.Co, H, W, Ho, Wo, d.stride,
@@ -813,6 +813,11 @@ DwpwRun plan_dwpw_run(const small_layer *L, int nL, int i, int H, int W)
     // place that is not its input
     for (; n >= 2; --n) {
         if (!dwpw_run_eligible(r.block, n)) continue;
+        // a workgroup that holds one image takes it through the whole run: beyond one round of such workgroups a launch per
+        // block is faster, and so is a later, shorter run on smaller images, several per workgroup (depthwise-separable
+        // CNN at 384 / 512 / 1024 images: one run from the 12 x 12 images on 152 / 162 / 302 us, blocks up to the 3 x 3
+        // images layer by layer and a run from there 133 / 147 / 216 us, all layer by layer 165 / 181 / 271 us)
+        if (dwpw_run_images(r.block, n, N) == 1 && N > device_cus()) continue;
         const int last = r.pw_idx[n - 1], T = L[last].dst, S = L[i].src;
         const int after = last + 1 + r.block[n - 1].pw_relu;
         bool ok = T != SMALL_BUF_IN;
@@ -1134,9 +1139,9 @@ int walk(const small_layer *L, int nL, int N, int C0, int H0, int W0, NetPlan &p
                 // several such blocks in a row on small images: one launch for the whole run
                 DwpwRun dr;
                 dr.n = 0;
-                if (head && fu.pw && !res_n && l.op == SMALL_OP_DWCONV && l.Cib == 16 && (long)a.H * a.W <= 64 &&
+                if (head && fu.pw && !res_n && l.op == SMALL_OP_DWCONV && l.Cib == 16 && (long)a.H * a.W <= kDwpwRunMaxPixels &&
                     in_elems * sizeof(float) < ((size_t)1 << 32)) {
-                    dr = plan_dwpw_run(L, nL, i, a.H, a.W);
+                    dr = plan_dwpw_run(L, nL, i, a.H, a.W, N);
                     if (dr.n && run) {
                         const small_layer &ldw = L[dr.dw_idx[dr.n - 1]], &lpw = L[dr.pw_idx[dr.n - 1]];
                         const DwpwRunBlock &lb = dr.block[dr.n - 1];

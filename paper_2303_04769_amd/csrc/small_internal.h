@@ -211,16 +211,20 @@ hipError_t launch_dense_chain(const float *in, float *out, const ChainLayer *lay
                               hipStream_t s);
 
 // A run of [depthwise 3x3, any stride and padding (+ ReLU)] -> [1x1 convolution Cin -> Cout (+ ReLU)] blocks on 16-channel
-// blocks, every tensor of the run an image of at most 64 pixels, each block reading what the one before wrote, in one
+// blocks, every tensor of the run an image of at most 256 pixels (and few enough pixel groups per output block: see
+// dwpw_run_eligible), each block reading what the one before wrote, in one
 // launch (dwpw_run.hip). out may not overlap in, except that a run whose blocks all keep the shape may work in place (a
 // workgroup reads its images before it writes them); pointers 16-byte aligned; tensors smaller than 4 GiB.
 constexpr int kDwpwChainMaxBlocks = 12;
+constexpr int kDwpwRunMaxPixels = 256;       // per image, for every tensor of a run
+constexpr int kDwpwRunMaxValues = 6144;      // ... and values per image
 struct DwpwRunBlock {
     const float *dw, *pw;
     int dw_relu, pw_relu;
     int Cin, Cout, Hi, Wi, Ho, Wo, stride, pt, pl;
 };
 bool dwpw_run_eligible(const DwpwRunBlock *blocks, int n_blocks);      // shapes only
+int dwpw_run_images(const DwpwRunBlock *blocks, int n_blocks, int N);  // images per workgroup of the launch at batch N
 // head.filt != null: the run closes with the mean over the last result's pixels and a fully connected layer on it
 // (at most 16 outputs, filter [Co/Cob][C/16][1][1][16][Cob]); out is then [N][Co] and the last result is not written.
 struct DwpwRunHead { const float *filt; int Co, Cob; };

@@ -130,11 +130,15 @@ def test_workspace_follows_the_buffer_sharing_rule(lib, golden):
         plan = lambda N, flags=0: B.small_network_launches_at(to, N, other.C0, other.H0, other.W0, flags)
         # layer by layer, except that consecutive depthwise + pointwise blocks on small images (known only with the
         # geometry) are one launch: the nine blocks from the 6x6 images on with the head (the audio CNN's 25x5 images are too large)
-        expect = B.small_network_launches(to) if other is a else [0, 2, 6, 10, 14, 18]
+        # (from the 12x12 images on when a workgroup per image is one round of workgroups, else from the 3x3 images on,
+        # several images per workgroup)
+        expect = B.small_network_launches(to) if other is a else [0, 2, 6, 10, 14, 18, 22, 26]
         assert plan(512) == expect and set(expect) <= set(B.small_network_launches(to))
+        if other is not a:
+            assert plan(1, B.SMALL_RUN_RESIDENT_OFF) == [0, 2, 6, 10] == plan(256, B.SMALL_RUN_RESIDENT_OFF) and plan(257) == expect == plan(4096)
         assert len(plan(256, B.SMALL_RUN_RESIDENT_ON)) < len(plan(512))
         # the audio CNN (0.27 M multiply-adds per layer) is taken in one round, where it measures a few percent faster
-        assert (plan(256) == [0]) == (other is a) and (plan(256) == expect) == (other is not a)
+        assert (plan(256) == [0]) == (other is a) and (plan(256) == [0, 2, 6, 10]) == (other is not a)
     assert at(256, B.SMALL_RUN_PLAIN_INPUT) == [0] == at(2, B.SMALL_RUN_PLAIN_INPUT | B.SMALL_RUN_RESIDENT_ON)
     n = C.c_int(0)
     assert lib.small_network_launches_at(tr, len(tr), 256, r.C0, r.H0, r.W0, 16, None, C.byref(n)) == 2    # unknown flag
