@@ -204,22 +204,51 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
         {
             const char *stage = lds_c + slot * a.stage_bytes;
             const char *wrow = lds_c + w_addr + cb * (9 * 64);
+            // the window in two batches of reads (five taps, then four): left to itself the compiler reads a tap and its
+            // filter value and waits for them before it reads the next, nine LDS latencies in a row per step (all nine at
+            // once measure the same and take 32 more registers)
+            floatx4 v[5], w[5];
 #pragma unroll
-            for (int k = 0; k < 9; ++k) {
-                const floatx4 v = *reinterpret_cast<const floatx4 *>(stage + p_addr[k]);
-                const floatx4 w = *reinterpret_cast<const floatx4 *>(wrow + k * 64);
-                dw.x = fmaf(v.x, w.x, dw.x); dw.y = fmaf(v.y, w.y, dw.y);
-                dw.z = fmaf(v.z, w.z, dw.z); dw.w = fmaf(v.w, w.w, dw.w);
+            for (int k = 0; k < 5; ++k) {
+                v[k] = *reinterpret_cast<const floatx4 *>(stage + p_addr[k]);
+                w[k] = *reinterpret_cast<const floatx4 *>(wrow + k * 64);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 5; ++k) {
+                dw.x = fmaf(v[k].x, w[k].x, dw.x); dw.y = fmaf(v[k].y, w[k].y, dw.y);
+                dw.z = fmaf(v[k].z, w[k].z, dw.z); dw.w = fmaf(v[k].w, w[k].w, dw.w);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                v[k] = *reinterpret_cast<const floatx4 *>(stage + p_addr[5 + k]);
+                w[k] = *reinterpret_cast<const floatx4 *>(wrow + (5 + k) * 64);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                dw.x = fmaf(v[k].x, w[k].x, dw.x); dw.y = fmaf(v[k].y, w[k].y, dw.y);
+                dw.z = fmaf(v[k].z, w[k].z, dw.z); dw.w = fmaf(v[k].w, w[k].w, dw.w);
             }
             if (a.relu_mid) {
                 dw.x = dw.x > 0.f ? dw.x : 0.f; dw.y = dw.y > 0.f ? dw.y : 0.f;
                 dw.z = dw.z > 0.f ? dw.z : 0.f; dw.w = dw.w > 0.f ? dw.w : 0.f;
             }
         }
+        // (the accumulators named as tied operands: through the builtin the compiler renames them from step to step and
+        // copies all sixteen registers twice per step to undo it)
+        {
+            const float d0 = dw.x, d1 = dw.y, d2 = dw.z, d3 = dw.w;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+            for (int j = 0; j < WN; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(fb[j][0]), "v"(d0));
 #pragma unroll
-            for (int j = 0; j < WN; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(fb[j][r], dw[r], acc[j], 0, 0, 0);
+            for (int j = 0; j < WN; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(fb[j][1]), "v"(d1));
+#pragma unroll
+            for (int j = 0; j < WN; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(fb[j][2]), "v"(d2));
+#pragma unroll
+            for (int j = 0; j < WN; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(fb[j][3]), "v"(d3));
+        }
         if (++slot == a.stages) slot = 0;
         if (++cb < a.nCb) continue;
         cb = 0;
