@@ -380,10 +380,20 @@ __device__ __forceinline__ void dwpw8_finish(const floatx4 (&v)[18], const float
                                              floatx4 *o, int relu_mid, int relu_out)
 {
     floatx4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};       // depthwise sums of channels 0..3, 4..7
+    // filter values in batches of reads (left to itself the compiler reads two, waits, uses them, reads the next two:
+    // 25 LDS latencies in a row per pixel)
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
-        lo += v[2 * t] * (w_dw[2 * t] * on[t]);
-        hi += v[2 * t + 1] * (w_dw[2 * t + 1] * on[t]);
+    for (int t0 = 0; t0 < 9; t0 += 3) {
+        floatx4 f[6];
+#pragma unroll
+        for (int k = 0; k < 6; ++k) f[k] = w_dw[2 * t0 + k];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            lo += v[2 * (t0 + t)] * (f[2 * t] * on[t0 + t]);
+            hi += v[2 * (t0 + t) + 1] * (f[2 * t + 1] * on[t0 + t]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
     if (relu_mid) {
 #pragma unroll
@@ -394,10 +404,19 @@ __device__ __forceinline__ void dwpw8_finish(const floatx4 (&v)[18], const float
     }
     floatx4 acc[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-    for (int ci = 0; ci < 8; ++ci) {
-        const float x = ci < 4 ? lo[ci] : hi[ci - 4];
+    for (int c0 = 0; c0 < 8; c0 += 2) {
+        floatx4 f[8];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) acc[k] += w_pw[ci * 4 + k] * x;
+        for (int k = 0; k < 8; ++k) f[k] = w_pw[c0 * 4 + k];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int ci = c0 + c;
+            const float x = ci < 4 ? lo[ci] : hi[ci - 4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) acc[k] += f[c * 4 + k] * x;
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
