@@ -28,6 +28,11 @@ def _stale(target, deps):
 
 def build_lib(force=False, verbose=False):
     os.makedirs(OBJ, exist_ok=True)
+    # objects built with other flags (the timing build) are never mixed with this build's
+    stamp = os.path.join(OBJ, "flags.txt")
+    flags = " ".join(FLAGS)
+    if not os.path.exists(stamp) or open(stamp).read() != flags:
+        force = True
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     headers = [os.path.join(CSRC, "small_internal.h"), os.path.join(HERE, "..", "include", "small.h")]
     objs, procs = [], []
@@ -50,6 +55,8 @@ def build_lib(force=False, verbose=False):
             print(out)
     if failed:
         raise RuntimeError("hipcc failed\n" + "\n".join(failed))
+    with open(stamp, "w") as f:
+        f.write(flags)
     if force or procs or _stale(LIB, objs):
         subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
     probe_src = os.path.join(CSRC, "probe.hip")
