@@ -431,10 +431,19 @@ struct FirstArgs {
     int plain_input;      // the input is a plain [N][C][H][W] tensor (the network's own input): the layout change
                           // of the network boundary then happens in this kernel's gathers
     FastDiv div_HoWo, div_Wo;
+    unsigned in_bytes, filt_bytes, out_bytes;       // each below 2 GiB
 };
 
 // CIB, KW > 0: the layer's input block and window width as compile-time constants (the decoding of k into
 // (tap, channel) is then free); 0, 0: read from the arguments.
+// A wave gathers the input values of its WM groups of 16 pixels once and walks the output blocks with them in
+// registers (a workgroup per output block would gather them once per block: 24.6 against 21 us on the audio
+// CNN's first layer, 64 output channels, at batch 1024). Every access goes through a buffer descriptor over its
+// whole tensor (tensors below 2 GiB): an offset of 32 bits per access instead of a 64-bit address, and masks (a
+// tap outside the image, a pixel past the end, a channel the block does not have) are offsets beyond the
+// descriptor, which read zero and drop stores, instead of selects on the values. The kernel's time is the
+// output stream, address arithmetic and waiting, not matrix instructions: 1600 vector instructions per wave
+// with 64-bit addresses and selects, 500 this way (21 -> 16 us on that layer).
 template <int KT, int WM, int CIB, int KW>
 __global__ void __launch_bounds__(256) conv_first_mfma(FirstArgs f)
 {
@@ -442,11 +451,13 @@ __global__ void __launch_bounds__(256) conv_first_mfma(FirstArgs f)
     const int cib = CIB ? CIB : f.Cib, kw = KW ? KW : a.kw;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int p = lane & 15, q = lane >> 4;
-    const int cob = blockIdx.y;
     const int tile0 = ((int)blockIdx.x * 4 + wave) * (16 * WM);
+    const __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.in), 0, f.in_bytes, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t flt = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.filt), 0, f.filt_bytes, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t dst = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, f.out_bytes, kRawBuffer);
+    const __amdgpu_buffer_rsrc_t res = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(a.res), 0, f.out_bytes, kRawBuffer);
 
-    // this lane's reduction elements: k = 4t + q -> (dy, dx, ci), offset inside the window in floats
-    float fa[KT];
+    // this lane's reduction elements: k = 4t + q -> (dy, dx, ci), byte offset inside the window
     int koff[KT], kdy[KT], kdx[KT];
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
@@ -454,84 +465,17 @@ __global__ void __launch_bounds__(256) conv_first_mfma(FirstArgs f)
         const int tap = k / cib, ci = k - tap * cib;
         kdy[t] = tap / kw;
         kdx[t] = tap - kdy[t] * kw;
-        koff[t] = f.plain_input ? ci * a.H * a.W + kdy[t] * a.W + kdx[t] : (kdy[t] * a.W + kdx[t]) * cib + ci;
-        const bool live = k < f.K && p < f.Cob;
-        fa[t] = live ? a.filt[((size_t)cob * f.K + k) * f.Cob + p] : 0.f;
+        koff[t] = 4 * (f.plain_input ? ci * a.H * a.W + kdy[t] * a.W + kdx[t] : (kdy[t] * a.W + kdx[t]) * cib + ci);
         if (k >= f.K) kdy[t] = 1 << 20;      // never inside the image: the operand reads as zero
     }
-
-    // All input values of the wave's WM pixel groups are requested before the first matrix instruction: a wave
-    // has only a few hundred cycles of arithmetic, so the loads of one group after the other would each expose
-    // their full latency (and the grid is a single round of waves).
-    float fb[WM][KT];
-    unsigned valid[WM];
-#pragma unroll
-    for (int wm = 0; wm < WM; ++wm) {
-        int m = tile0 + wm * 16 + p;
-        m = m < a.M ? m : a.M - 1;
-        const int n = f.div_HoWo.div(m), rem = m - n * a.HoWo;
-        const int oy = f.div_Wo.div(rem), ox = rem - oy * a.Wo;
-        const int iy0 = oy * a.stride - a.pt, ix0 = ox * a.stride - a.pl;
-        const int org = (iy0 * a.W + ix0) * (f.plain_input ? 1 : cib); // window origin inside the image, may be negative
-        const float *image = a.in + (size_t)n * a.H * a.W * cib;
-        valid[wm] = 0;
-#pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            const bool inside = (unsigned)(iy0 + kdy[t]) < (unsigned)a.H && (unsigned)(ix0 + kdx[t]) < (unsigned)a.W;
-            fb[wm][t] = image[inside ? org + koff[t] : 0];            // outside: the image's first value, replaced below
-            valid[wm] |= inside ? 1u << t : 0u;
-        }
-    }
-    floatx4 acc[WM];
-#pragma unroll
-    for (int wm = 0; wm < WM; ++wm) {
-        acc[wm] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int t = 0; t < KT; ++t)
-            acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[t], (valid[wm] >> t) & 1u ? fb[wm][t] : 0.f, acc[wm], 0, 0, 0);
-    }
-
-    // lane (p, q) holds output channels 4q .. 4q+3 of pixel p
-    if (4 * q >= f.Cob) return;
-#pragma unroll
-    for (int wm = 0; wm < WM; ++wm) {
-        const int m = tile0 + wm * 16 + p;
-        if (m >= a.M) continue;
-        const int n = f.div_HoWo.div(m), pix = m - n * a.HoWo;
-        const size_t e = (((size_t)n * a.nCob + cob) * a.HoWo + pix) * f.Cob + 4 * q;
-        *reinterpret_cast<floatx4 *>(a.out + e) = epilogue4(acc[wm], a.epilogue, a.res + e);
-    }
-}
-
-// The same for layers with several output blocks: the gathered input values serve all of them (a workgroup per
-// output block, as above, would gather them once per block: 24.6 against 21 us on the audio CNN's first layer, 64
-// output channels, at batch 1024).
-template <int KT, int WM, int CIB, int KW>
-__global__ void __launch_bounds__(256) conv_first_mfma_all(FirstArgs f)
-{
-    const ConvArgs &a = f.c;
-    const int cib = CIB ? CIB : f.Cib, kw = KW ? KW : a.kw;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int p = lane & 15, q = lane >> 4;
-    const int tile0 = ((int)blockIdx.x * 4 + wave) * (16 * WM);
-
-    // this lane's reduction elements: k = 4t + q -> (dy, dx, ci), offset inside the window in floats
-    int koff[KT], kdy[KT], kdx[KT];
-#pragma unroll
-    for (int t = 0; t < KT; ++t) {
-        const int k = 4 * t + q;
-        const int tap = k / cib, ci = k - tap * cib;
-        kdy[t] = tap / kw;
-        kdx[t] = tap - kdy[t] * kw;
-        koff[t] = f.plain_input ? ci * a.H * a.W + kdy[t] * a.W + kdx[t] : (kdy[t] * a.W + kdx[t]) * cib + ci;
-        if (k >= f.K) kdy[t] = 1 << 20;      // never inside the image: the operand reads as zero
-    }
+    // filter value (block cob, k = 4t + q, channel p) sits at ((cob K + k) Cob + p) floats
+    const unsigned f_at = p < f.Cob ? (unsigned)(q * f.Cob + p) * 4u : kBeyond;
+    const int f_step = 16 * f.Cob, f_block = 4 * f.K * f.Cob;
     auto filter_of = [&](int cob, float (&fa)[KT]) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
-            const int k = 4 * t + q;
-            const bool live = k < f.K && p < f.Cob;
-            fa[t] = live ? a.filt[((size_t)cob * f.K + k) * f.Cob + p] : 0.f;
+            const bool live = t + 1 < KT || 4 * t + q < f.K;
+            fa[t] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(flt, live ? f_at + (unsigned)(cob * f_block + t * f_step) : kBeyond, 0, 0));
         }
     };
     float fa[KT];
@@ -542,27 +486,25 @@ __global__ void __launch_bounds__(256) conv_first_mfma_all(FirstArgs f)
     // their full latency (and the grid is a single round of waves). They serve every output block: the wave walks
     // the blocks with the gathered values in registers (a workgroup per output block would gather them again).
     float fb[WM][KT];
-    int m_of[WM];
+    unsigned o_at[WM];
+    const int image_bytes = 4 * a.H * a.W * cib, px_bytes = 4 * (f.plain_input ? 1 : cib);
 #pragma unroll
     for (int wm = 0; wm < WM; ++wm) {
-        int m = tile0 + wm * 16 + p;
-        m_of[wm] = m;
-        m = m < a.M ? m : a.M - 1;
+        const int m_own = tile0 + wm * 16 + p;
+        const int m = m_own < a.M ? m_own : a.M - 1;
         const int n = f.div_HoWo.div(m), rem = m - n * a.HoWo;
         const int oy = f.div_Wo.div(rem), ox = rem - oy * a.Wo;
         const int iy0 = oy * a.stride - a.pt, ix0 = ox * a.stride - a.pl;
-        const int org = (iy0 * a.W + ix0) * (f.plain_input ? 1 : cib); // window origin inside the image, may be negative
-        const float *image = a.in + (size_t)n * a.H * a.W * cib;
-        unsigned valid = 0;
+        const int org = n * image_bytes + (iy0 * a.W + ix0) * px_bytes;       // window origin, may lie before the image
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
             const bool inside = (unsigned)(iy0 + kdy[t]) < (unsigned)a.H && (unsigned)(ix0 + kdx[t]) < (unsigned)a.W;
-            fb[wm][t] = image[inside ? org + koff[t] : 0];            // outside: the image's first value, replaced below
-            valid |= inside ? 1u << t : 0u;
+            fb[wm][t] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(src, inside ? (unsigned)(org + koff[t]) : kBeyond, 0, 0));
         }
-#pragma unroll
-        for (int t = 0; t < KT; ++t) fb[wm][t] = (valid >> t) & 1u ? fb[wm][t] : 0.f;
+        // lane (p, q) holds output channels 4q .. 4q+3 of pixel p
+        o_at[wm] = (m_own < a.M && 4 * q < f.Cob) ? (unsigned)(((n * a.nCob * a.HoWo + rem) * f.Cob + 4 * q) * 4) : kBeyond;
     }
+    const int o_block = 4 * a.HoWo * f.Cob;
     for (int cob = 0; cob < a.nCob; ++cob) {
         float fn[KT];
         filter_of(cob + 1 < a.nCob ? cob + 1 : cob, fn);          // the next block's filter values, under way early
@@ -573,16 +515,16 @@ __global__ void __launch_bounds__(256) conv_first_mfma_all(FirstArgs f)
 #pragma unroll
             for (int t = 0; t < KT; ++t) acc[wm] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[t], fb[wm][t], acc[wm], 0, 0, 0);
         }
-        // lane (p, q) holds output channels 4q .. 4q+3 of pixel p
-        if (4 * q < f.Cob) {
 #pragma unroll
-            for (int wm = 0; wm < WM; ++wm) {
-                const int m = m_of[wm];
-                if (m >= a.M) continue;
-                const int n = f.div_HoWo.div(m), pix = m - n * a.HoWo;
-                const size_t e = (((size_t)n * a.nCob + cob) * a.HoWo + pix) * f.Cob + 4 * q;
-                *reinterpret_cast<floatx4 *>(a.out + e) = epilogue4(acc[wm], a.epilogue, a.res + e);
+        for (int wm = 0; wm < WM; ++wm) {
+            const unsigned o = o_at[wm] + (unsigned)(cob * o_block);
+            floatx4 v = acc[wm];
+            if (a.epilogue & EPI_ADD) v += __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(res, o, 0, 0));
+            if (a.epilogue & EPI_RELU) {
+                v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
+                v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
             }
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(uintx4, v), dst, o, 0, 0);
         }
 #pragma unroll
         for (int t = 0; t < KT; ++t) fa[t] = fn[t];
@@ -590,10 +532,12 @@ __global__ void __launch_bounds__(256) conv_first_mfma_all(FirstArgs f)
 }
 
 // Which layers the kernel above takes: one input block of fewer than 16 channels, a reduction of 5..8 (the
-// pointwise layer after an 8-channel depthwise one), 25..28 or 37..40 values.
+// pointwise layer after an 8-channel depthwise one), 25..28 or 37..40 values, input and output tensors below 2 GiB
+// each (32-bit buffer offsets).
 int first_mfma_steps(const LayerGeom &g)
 {
     if (g.Ci != g.Cib || g.Cib >= 16 || (g.Cob != 8 && g.Cob != 16)) return 0;
+    if ((size_t)g.N * g.H * g.W * g.Ci * 4 >= kBeyond || (size_t)g.N * g.Ho * g.Wo * g.Co * 4 >= kBeyond) return 0;
     const int K = g.Cib * g.kh * g.kw, kt = (K + 3) / 4;
     return (kt == 2 || kt == 7 || kt == 10) ? kt : 0;
 }
@@ -690,11 +634,12 @@ hipError_t launch_conv(const float *in, const float *filt, float *out, const flo
         f.plain_input = plain_input ? 1 : 0;
         f.div_HoWo = make_fastdiv(a.HoWo);
         f.div_Wo = make_fastdiv(g.Wo);
-        const dim3 grid((unsigned)((a.M + 255) / 256), (unsigned)a.nCob), grid_all((unsigned)((a.M + 255) / 256), 1u);
+        const dim3 grid((unsigned)((a.M + 255) / 256));
         const int kt = first_mfma_steps(g);
-        if (a.nCob > 1 && g.Cib == 1 && g.kw == 4 && kt == 10) hipLaunchKernelGGL((conv_first_mfma_all<10, 4, 1, 4>), grid_all, dim3(256), 0, s, f);
-        else if (a.nCob > 1 && g.Cib == 3 && g.kw == 3 && kt == 7) hipLaunchKernelGGL((conv_first_mfma_all<7, 4, 3, 3>), grid_all, dim3(256), 0, s, f);
-        else if (g.Cib == 3 && g.kw == 3 && kt == 7) hipLaunchKernelGGL((conv_first_mfma<7, 4, 3, 3>), grid, dim3(256), 0, s, f);
+        f.in_bytes = (unsigned)((size_t)g.N * g.H * g.W * g.Ci * 4);
+        f.out_bytes = (unsigned)((size_t)a.M * g.Co * 4);
+        f.filt_bytes = (unsigned)((size_t)g.Co * f.K * 4);
+        if (g.Cib == 3 && g.kw == 3 && kt == 7) hipLaunchKernelGGL((conv_first_mfma<7, 4, 3, 3>), grid, dim3(256), 0, s, f);
         else if (g.Cib == 1 && g.kw == 4 && kt == 10) hipLaunchKernelGGL((conv_first_mfma<10, 4, 1, 4>), grid, dim3(256), 0, s, f);
         else if (g.Cib == 8 && g.kw == 1 && kt == 2) hipLaunchKernelGGL((conv_first_mfma<2, 4, 8, 1>), grid, dim3(256), 0, s, f);
         else if (kt == 2) hipLaunchKernelGGL((conv_first_mfma<2, 4, 0, 0>), grid, dim3(256), 0, s, f);
