@@ -21,6 +21,7 @@
 #include "small_internal.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace small {
 
@@ -50,9 +51,9 @@ struct DwPwArgs {
 
 // Staged input rows of the tile that starts at output pixel m0 of a tile group: rows are numbered through the
 // images of the group (image * H + row); the tile needs rows [lo, hi]. Same arithmetic on host and device.
-__host__ __device__ inline void tile_rows(int m0, int GHW, int HWo, int Wo, int H, int stride, int pt, int &lo, int &hi)
+__host__ __device__ inline void tile_rows(int m0, int TM, int GHW, int HWo, int Wo, int H, int stride, int pt, int &lo, int &hi)
 {
-    const int f0 = m0, f1 = (m0 + kTM - 1 < GHW - 1) ? m0 + kTM - 1 : GHW - 1;
+    const int f0 = m0, f1 = (m0 + TM - 1 < GHW - 1) ? m0 + TM - 1 : GHW - 1;
     const int img0 = f0 / HWo, oh0 = (f0 - img0 * HWo) / Wo;
     const int img1 = f1 / HWo, oh1 = (f1 - img1 * HWo) / Wo;
     int r0 = oh0 * stride - pt, r1 = oh1 * stride - pt + 2;
@@ -62,37 +63,65 @@ __host__ __device__ inline void tile_rows(int m0, int GHW, int HWo, int Wo, int 
     hi = img1 * H + r1;
 }
 
-// LPS: load instructions per wave and step (a stage holds up to 64 * LPS entries). WN: 16-channel output blocks.
-template <int WN, int LPS>
-__global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
+// max(x, 0) in one instruction per value (the compiler's form quiets the operand first: two)
+__device__ __forceinline__ float relu1(float x)
 {
-    constexpr int NW = 4, NT = 256, TM = kTM;
+    float r;
+    asm("v_max_f32 %0, 0, %1" : "=v"(r) : "v"(x));
+    return r;
+}
+__device__ __forceinline__ floatx4 relu4(floatx4 v) { return floatx4{relu1(v.x), relu1(v.y), relu1(v.z), relu1(v.w)}; }
+
+// LPS: load instructions per wave and step (a stage holds up to 64 * LPS entries). WN: 16-channel output blocks.
+// OWN: narrow images, whose 16-pixel tiles touch at most 16 * LPS input pixels. Every wave (eight per workgroup) then
+// stages the rows of its own 16 pixels into a ring of its own (kOwnStages steps) and nothing in the step loop couples
+// the waves: no barrier, and a wait on a fixed number of outstanding loads. With shared stages the four waves of a
+// workgroup, each on another SIMD and held up there by other workgroups' matrix instructions, meet at a barrier every
+// step, and the step takes as long as the slowest of them. The halo rows of neighbouring tiles are fetched by both
+// waves (from L2).
+constexpr int kOwnStages = 3;
+template <int WN, int LPS, bool OWN>
+__global__ void __launch_bounds__(OWN ? 512 : 256) dwpw16_img(DwPwArgs a)
+{
+    constexpr int NW = OWN ? 8 : 4, NT = 64 * NW, TM = OWN ? 16 : kTM;
     static_assert((kMaxStages - 1) * LPS < 64, "too many loads in flight for vmcnt");
+    static_assert(kOwnStages == 3, "the step loop is unrolled over the ring");
 
     extern __shared__ floatx4 lds[];
     const unsigned lds_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) void *)lds;
     char *lds_c = reinterpret_cast<char *>(lds);
     const int zero_rel = a.stage_bytes - 16;
-    const int pwf_off = (a.stages * a.stage_bytes + 255) & ~255;
+    const int stages = OWN ? kOwnStages : a.stages;
+    const int pwf_off = ((OWN ? NW : 1) * stages * a.stage_bytes + 255) & ~255;
     const int dwf_off = pwf_off + a.nCb * (WN * 1024);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lp = lane & 15, lq = lane >> 4;
+    const int ring = OWN ? wave * stages * a.stage_bytes : 0;       // this wave's stages start here
 
-    // workgroup -> (image group, pixel tile of the group, channel tile), channel tile fastest
-    const int wg = (int)xcd_contiguous(blockIdx.x, gridDim.x);
-    const int t = a.dCt.div(wg);
-    const int co_tile = wg - t * a.n_cotiles;
-    const int grp = a.dMt.div(t);
-    const int m_tile = t - grp * a.n_mtiles;
+    // workgroup (OWN: wave) -> (image group, pixel tile of the group, channel tile), channel tile fastest
+    int co_tile, grp, m_tile;
+    if (OWN) {
+        const int wv = (int)xcd_contiguous(blockIdx.x, gridDim.x) * NW + wave;
+        co_tile = (int)blockIdx.y;
+        grp = a.dMt.div(wv);
+        m_tile = wv - grp * a.n_mtiles;
+        if (grp >= a.n_groups) { grp = a.n_igroups; m_tile = 0; }    // a wave without work: it only helps fetch the filters
+    } else {
+        const int wg = (int)xcd_contiguous(blockIdx.x, gridDim.x);
+        const int t = a.dCt.div(wg);
+        co_tile = wg - t * a.n_cotiles;
+        grp = a.dMt.div(t);
+        m_tile = t - grp * a.n_mtiles;
+    }
     const int m0 = m_tile * TM;            // first pixel of the tile inside its tile group
     const int cob0 = co_tile * WN;
     const size_t planeA = (size_t)a.HW * 64;
     const size_t imgA = (size_t)a.nCb * planeA;
     const size_t imgO = (size_t)a.nCob * a.HWo * 64;
     int row_lo, row_hi;
-    tile_rows(m0, a.GHW, a.HWo, a.Wo, a.H, a.stride, a.pt, row_lo, row_hi);
+    tile_rows(m0, TM, a.GHW, a.HWo, a.Wo, a.H, a.stride, a.pt, row_lo, row_hi);
 
     // ---- load descriptors of a step (one 16-channel block of the tile's input rows), relative to the first
     // image of the tile group and to the channel block. Chunks past the tile's rows repeat its last row.
@@ -101,7 +130,7 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
     const int n_chunks = (a.stage_bytes - 16) / 1024;
 #pragma unroll
     for (int j = 0; j < LPS; ++j) {
-        const int chunk = min(j * NW + wave, n_chunks - 1);
+        const int chunk = min(OWN ? j : j * NW + wave, n_chunks - 1);
         const int e = chunk * 16 + (lane >> 2);
         const int quad = (lane & 3) ^ ((e >> 1) & 3);
         const int er = a.dW.div(e);
@@ -112,7 +141,7 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
     }
 
     // ---- this lane's pixel: tap addresses in a stage, mid-tile address, output offset
-    const int px = wave * 16 + lp;
+    const int px = OWN ? lp : wave * 16 + lp;
     const bool o_ok = m0 + px < a.GHW;
     unsigned p_addr[9];
     unsigned o_off;
@@ -128,7 +157,7 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
                 const int ir = oh * a.stride + y - a.pt, ic = ow * a.stride + x - a.pl;
                 const bool ok = (unsigned)ir < (unsigned)a.H && (unsigned)ic < (unsigned)a.W;
                 const int e = (img * a.H + ir - row_lo) * a.W + ic;
-                p_addr[y * 3 + x] = ok ? (unsigned)((e * 4 + (lq ^ ((e >> 1) & 3))) * 16) : (unsigned)zero_rel;
+                p_addr[y * 3 + x] = (unsigned)ring + (ok ? (unsigned)((e * 4 + (lq ^ ((e >> 1) & 3))) * 16) : (unsigned)zero_rel);
             }
     }
     const unsigned b_addr = (unsigned)(pwf_off + lane * 4);
@@ -140,18 +169,20 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
     // tile group q covers images first_image(q) .. + ipt - 1
     auto first_image = [&](int q) __attribute__((always_inline)) { return min(q * a.ipt, a.N - a.ipt); };
     int i_n = grp, i_cb = 0, i_slot = 0, ahead = 0;        // i_n, n: tile groups
+    // (OWN: a step is issued in every turn of the loop, so that the number of loads in flight is a constant; past the
+    // wave's last step it fetches the batch's last tile group again, into a slot nobody reads any more)
     auto issue_step = [&]() __attribute__((always_inline)) {
-        const char *base = in_c + (size_t)first_image(i_n) * imgA + (size_t)i_cb * planeA;
-        const unsigned stage_lds = lds_base + (unsigned)(i_slot * a.stage_bytes);
+        const char *base = in_c + (size_t)first_image(OWN ? min(i_n, a.n_igroups - 1) : i_n) * imgA + (size_t)i_cb * planeA;
+        const unsigned stage_lds = lds_base + (unsigned)(ring + i_slot * a.stage_bytes);
 #pragma unroll
         for (int j = 0; j < LPS; ++j) dma16(base, d_voff[j], stage_lds + d_lds[j]);
         ++ahead;
-        if (++i_slot == a.stages) i_slot = 0;
+        if (++i_slot == stages) i_slot = 0;
         if (++i_cb == a.nCb) { i_cb = 0; i_n += a.n_groups; }
     };
     // the input pipeline starts before the resident operands are fetched, so that both latencies overlap
-    for (int s = 0; s < a.stages - 1; ++s)
-        if (i_n < a.n_igroups) issue_step();
+    for (int s = 0; s < stages - 1; ++s)
+        if (OWN || i_n < a.n_igroups) issue_step();
 
     // ---- resident operands: pointwise filter slabs of this channel tile and all depthwise taps
     {
@@ -166,16 +197,20 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
         const int ndw = a.nCb * 9 * 4;                                   // float4s
         for (int e = tid; e < ndw; e += NT)
             *reinterpret_cast<floatx4 *>(lds_c + dwf_off + e * 16) = reinterpret_cast<const floatx4 *>(a.dwf)[e];
-        if (tid < a.stages) *reinterpret_cast<floatx4 *>(lds_c + tid * a.stage_bytes + zero_rel) = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (OWN ? lane < stages : tid < stages)
+            *reinterpret_cast<floatx4 *>(lds_c + ring + (OWN ? lane : tid) * a.stage_bytes + zero_rel) = floatx4{0.f, 0.f, 0.f, 0.f};
         wait_vmcnt<0>();                                                 // also the first input steps: they are older
         __syncthreads();
     }
 
-    int cb = 0, slot = 0;                                  // channel block being reduced, its ring slot
+    int cb = 0, slot = 0, n = grp;                         // channel block being reduced, its ring slot, its tile group
     floatx4 acc[WN];
 #pragma unroll
     for (int j = 0; j < WN; ++j) acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
-    for (int n = grp; n < a.n_igroups;) {
+    // One step: a channel block of the tile. stage_off: where the step's stage starts in the ring (OWN: a constant, so
+    // that it becomes the immediate offset of the window reads: a vector instruction costs its full issue time here,
+    // the matrix pipe does not hide it).
+    auto step = [&](auto stage_off) __attribute__((always_inline)) {
         // pointwise filter fragments of this channel block: independent of the staged input, requested first
         float fb[WN][4];
         {
@@ -186,23 +221,28 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
                 for (int r = 0; r < 4; ++r) fb[j][r] = *reinterpret_cast<const float *>(bs + j * 1024 + r * 256);
         }
         // the step to compute has landed once at most the loads of the steps issued after it are outstanding
-        switch (ahead - 1) {
-            case 0: wait_vmcnt<0>(); break;
-            case 1: wait_vmcnt<LPS>(); break;
-            case 2: wait_vmcnt<2 * LPS>(); break;
-            case 3: wait_vmcnt<3 * LPS>(); break;
-            case 4: wait_vmcnt<4 * LPS>(); break;
-            case 5: wait_vmcnt<5 * LPS>(); break;
-            case 6: wait_vmcnt<6 * LPS>(); break;
-            default: wait_vmcnt<7 * LPS>(); break;
+        if (OWN) {
+            issue_step();                                  // into the slot that was computed one step ago
+            wait_vmcnt<(kOwnStages - 1) * LPS>();
+        } else {
+            switch (ahead - 1) {
+                case 0: wait_vmcnt<0>(); break;
+                case 1: wait_vmcnt<LPS>(); break;
+                case 2: wait_vmcnt<2 * LPS>(); break;
+                case 3: wait_vmcnt<3 * LPS>(); break;
+                case 4: wait_vmcnt<4 * LPS>(); break;
+                case 5: wait_vmcnt<5 * LPS>(); break;
+                case 6: wait_vmcnt<6 * LPS>(); break;
+                default: wait_vmcnt<7 * LPS>(); break;
+            }
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            --ahead;
+            if (i_n < a.n_igroups) issue_step();           // into the slot that was computed one step ago
         }
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        --ahead;
-        if (i_n < a.n_igroups) issue_step();               // into the slot that was computed one step ago
         floatx4 dw = floatx4{0.f, 0.f, 0.f, 0.f};
         {
-            const char *stage = lds_c + slot * a.stage_bytes;
+            const char *stage = lds_c + stage_off;
             const char *wrow = lds_c + w_addr + cb * (9 * 64);
             // the window in two batches of reads (five taps, then four): left to itself the compiler reads a tap and its
             // filter value and waits for them before it reads the next, nine LDS latencies in a row per step (all nine at
@@ -231,17 +271,20 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
                 dw.x = fmaf(v[k].x, w[k].x, dw.x); dw.y = fmaf(v[k].y, w[k].y, dw.y);
                 dw.z = fmaf(v[k].z, w[k].z, dw.z); dw.w = fmaf(v[k].w, w[k].w, dw.w);
             }
-            if (a.relu_mid) {
-                dw.x = dw.x > 0.f ? dw.x : 0.f; dw.y = dw.y > 0.f ? dw.y : 0.f;
-                dw.z = dw.z > 0.f ? dw.z : 0.f; dw.w = dw.w > 0.f ? dw.w : 0.f;
-            }
+            if (a.relu_mid) dw = relu4(dw);
         }
         // (the accumulators named as tied operands: through the builtin the compiler renames them from step to step and
-        // copies all sixteen registers twice per step to undo it)
+        // copies all sixteen registers twice per step to undo it; a tile's first matrix instructions start from zero
+        // instead of sixteen cleared registers per tile)
         {
             const float d0 = dw.x, d1 = dw.y, d2 = dw.z, d3 = dw.w;
+            if (cb == 0) {
 #pragma unroll
-            for (int j = 0; j < WN; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(fb[j][0]), "v"(d0));
+                for (int j = 0; j < WN; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, 0" : "=&v"(acc[j]) : "v"(fb[j][0]), "v"(d0));
+            } else {
+#pragma unroll
+                for (int j = 0; j < WN; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(fb[j][0]), "v"(d0));
+            }
 #pragma unroll
             for (int j = 0; j < WN; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(fb[j][1]), "v"(d1));
 #pragma unroll
@@ -249,26 +292,37 @@ __global__ void __launch_bounds__(256) dwpw16_img(DwPwArgs a)
 #pragma unroll
             for (int j = 0; j < WN; ++j) asm volatile("v_mfma_f32_16x16x4_f32 %0, %1, %2, %0" : "+v"(acc[j]) : "v"(fb[j][3]), "v"(d3));
         }
-        if (++slot == a.stages) slot = 0;
-        if (++cb < a.nCb) continue;
+        if (++cb < a.nCb) return;
         cb = 0;
 
         // ---- STORE phase of this tile
 #pragma unroll
         for (int j = 0; j < WN; ++j) {
             const int cob = cob0 + j;
-            if (cob < a.nCob && o_ok) {
-                floatx4 v = acc[j];
-                if (a.relu_out) {
-                    v.x = v.x > 0.f ? v.x : 0.f; v.y = v.y > 0.f ? v.y : 0.f;
-                    v.z = v.z > 0.f ? v.z : 0.f; v.w = v.w > 0.f ? v.w : 0.f;
-                }
-                *reinterpret_cast<floatx4 *>(out_c + (size_t)first_image(n) * imgO + (size_t)cob * a.HWo * 64 + o_off) = v;
-            }
-            acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (cob < a.nCob && o_ok)
+                *reinterpret_cast<floatx4 *>(out_c + (size_t)first_image(n) * imgO + (size_t)cob * a.HWo * 64 + o_off) =
+                    a.relu_out ? relu4(acc[j]) : acc[j];
         }
         n += a.n_groups;
+    };
+    if constexpr (OWN) {
+        constexpr int SB = LPS * 1024 + 16;                // bytes of a stage, the host's figure
+        if (n < a.n_igroups)
+            for (;;) {
+                step(std::integral_constant<int, 0>{});
+                if (n >= a.n_igroups) break;
+                step(std::integral_constant<int, SB>{});
+                if (n >= a.n_igroups) break;
+                step(std::integral_constant<int, 2 * SB>{});
+                if (n >= a.n_igroups) break;
+            }
+    } else {
+        while (n < a.n_igroups) {
+            step(slot * a.stage_bytes);
+            if (++slot == stages) slot = 0;
+        }
     }
+    if (OWN) wait_vmcnt<0>();          // (the extra steps still write to this workgroup's LDS)
 }
 
 // Host-side shape of a launch: images per tile, staged entries per step, ring depth, LDS bytes.
@@ -276,6 +330,7 @@ struct DwPwPlan {
     int ipt, GHW, n_mtiles, chunks, stage_bytes, stages, lps, wn;
     size_t lds;
     bool ok;
+    bool own;       // every wave stages the rows of its own 16 pixels (n_mtiles then counts 16-pixel tiles)
 };
 
 DwPwPlan make_plan(const LayerGeom &g, int Co)
@@ -294,7 +349,7 @@ DwPwPlan make_plan(const LayerGeom &g, int Co)
     int ent = 0;
     for (int m = 0; m < p.n_mtiles; ++m) {
         int lo, hi;
-        tile_rows(m * kTM, p.GHW, HWo, g.Wo, g.H, g.stride, g.pt, lo, hi);
+        tile_rows(m * kTM, kTM, p.GHW, HWo, g.Wo, g.H, g.stride, g.pt, lo, hi);
         ent = std::max(ent, (hi - lo + 1) * g.W);
     }
     p.chunks = (ent + 15) / 16;
@@ -312,13 +367,34 @@ DwPwPlan make_plan(const LayerGeom &g, int Co)
     p.stages = (int)std::min<size_t>({(size_t)kMaxStages, budget / (size_t)p.stage_bytes, (size_t)(63 / p.lps + 1)});
     p.lds = (size_t)((p.stages * p.stage_bytes + 255) & ~255) + fixed;
     p.ok = p.chunks <= 32 && p.stages >= 2 && p.lds <= kDwPwMaxLds;
+    // narrow images: a ring per wave, when two workgroups of eight waves still fit a compute unit
+    if (p.ok) {
+        const int n16 = (p.GHW + 15) / 16;
+        int ent16 = 0;
+        for (int m = 0; m < n16; ++m) {
+            int lo, hi;
+            tile_rows(m * 16, 16, p.GHW, HWo, g.Wo, g.H, g.stride, g.pt, lo, hi);
+            ent16 = std::max(ent16, (hi - lo + 1) * g.W);
+        }
+        const int stage16 = 2 * 1024 + 16;
+        const size_t lds16 = (size_t)((8 * kOwnStages * stage16 + 255) & ~255) + fixed;
+        if (ent16 <= 32 && 2 * lds16 <= 160 * 1024) {
+            p.own = true;
+            p.n_mtiles = n16;
+            p.chunks = (ent16 + 15) / 16;
+            p.stage_bytes = stage16;
+            p.lps = 2;
+            p.stages = kOwnStages;
+            p.lds = lds16;
+        }
+    }
     return p;
 }
 
-template <int WN, int LPS>
+template <int WN, int LPS, bool OWN = false>
 hipError_t launch_cfg(DwPwArgs a, const DwPwPlan &p, hipStream_t s)
 {
-    auto kern = dwpw16_img<WN, LPS>;
+    auto kern = dwpw16_img<WN, LPS, OWN>;
     static size_t lds_allowed = 64 * 1024;
     if (p.lds > lds_allowed) {
         const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -335,8 +411,10 @@ hipError_t launch_cfg(DwPwArgs a, const DwPwPlan &p, hipStream_t s)
     a.stage_bytes = p.stage_bytes;
     // tile groups per workgroup: enough workgroups to fill the chip (as many as LDS lets be resident, at most 4
     // per compute unit), the rest of the batch is walked by each workgroup with its set-up paid once
+    // (with a ring per wave, positions are taken by waves, eight to a workgroup, two workgroups per compute unit)
     const long positions = (long)a.n_mtiles * a.n_cotiles;
-    const long resident = 256 * std::max<long>(1, std::min<long>(4, (long)(160 * 1024 / p.lds)));
+    const long resident = OWN ? 256 * 8 * std::max<long>(1, std::min<long>(2, (long)(160 * 1024 / p.lds)))
+                              : 256 * std::max<long>(1, std::min<long>(4, (long)(160 * 1024 / p.lds)));
     const long per_wg = std::max<long>(1, std::min<long>(a.n_igroups, (positions * a.n_igroups + resident - 1) / resident));
     a.n_groups = (int)((a.n_igroups + per_wg - 1) / per_wg);
     a.dW = make_fastdiv(a.W);
@@ -345,6 +423,11 @@ hipError_t launch_cfg(DwPwArgs a, const DwPwPlan &p, hipStream_t s)
     a.dHWo = make_fastdiv(a.HWo);
     a.dMt = make_fastdiv(a.n_mtiles);
     a.dCt = make_fastdiv(a.n_cotiles);
+    if (OWN) {
+        const dim3 grid((unsigned)(((long)a.n_mtiles * a.n_groups + 7) / 8), (unsigned)a.n_cotiles);
+        hipLaunchKernelGGL(kern, grid, dim3(512), p.lds, s, a);
+        return hipGetLastError();
+    }
     const unsigned grid = (unsigned)(positions * a.n_groups);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), p.lds, s, a);
     return hipGetLastError();
@@ -353,6 +436,7 @@ hipError_t launch_cfg(DwPwArgs a, const DwPwPlan &p, hipStream_t s)
 template <int WN>
 hipError_t launch_wn(const DwPwArgs &a, const DwPwPlan &p, hipStream_t s)
 {
+    if (p.own) return launch_cfg<WN, 2, true>(a, p, s);
     switch (p.lps) {
         case 2: return launch_cfg<WN, 2>(a, p, s);
         case 4: return launch_cfg<WN, 4>(a, p, s);
