@@ -50,12 +50,19 @@ struct DwPwArgs {
 };
 
 // Staged input rows of the tile that starts at output pixel m0 of a tile group: rows are numbered through the
-// images of the group (image * H + row); the tile needs rows [lo, hi]. Same arithmetic on host and device.
-__host__ __device__ inline void tile_rows(int m0, int TM, int GHW, int HWo, int Wo, int H, int stride, int pt, int &lo, int &hi)
+// images of the group (image * H + row); the tile needs rows [lo, hi]. Same arithmetic on host and device (the
+// device divides by multiplication: an integer division is some thirty vector instructions, four of them here).
+struct PlainDiv {
+    int d;
+    __host__ __device__ int div(int n) const { return n / d; }
+};
+template <typename Div>
+__host__ __device__ inline void tile_rows(int m0, int TM, int GHW, int HWo, int Wo, int H, int stride, int pt, const Div &by_HWo,
+                                          const Div &by_Wo, int &lo, int &hi)
 {
     const int f0 = m0, f1 = (m0 + TM - 1 < GHW - 1) ? m0 + TM - 1 : GHW - 1;
-    const int img0 = f0 / HWo, oh0 = (f0 - img0 * HWo) / Wo;
-    const int img1 = f1 / HWo, oh1 = (f1 - img1 * HWo) / Wo;
+    const int img0 = by_HWo.div(f0), oh0 = by_Wo.div(f0 - img0 * HWo);
+    const int img1 = by_HWo.div(f1), oh1 = by_Wo.div(f1 - img1 * HWo);
     int r0 = oh0 * stride - pt, r1 = oh1 * stride - pt + 2;
     r0 = r0 < 0 ? 0 : (r0 > H - 1 ? H - 1 : r0);
     r1 = r1 < 0 ? 0 : (r1 > H - 1 ? H - 1 : r1);
@@ -121,7 +128,7 @@ __global__ void __launch_bounds__(OWN ? 512 : 256) dwpw16_img(DwPwArgs a)
     const size_t imgA = (size_t)a.nCb * planeA;
     const size_t imgO = (size_t)a.nCob * a.HWo * 64;
     int row_lo, row_hi;
-    tile_rows(m0, TM, a.GHW, a.HWo, a.Wo, a.H, a.stride, a.pt, row_lo, row_hi);
+    tile_rows(m0, TM, a.GHW, a.HWo, a.Wo, a.H, a.stride, a.pt, a.dHWo, a.dWo, row_lo, row_hi);
 
     // ---- load descriptors of a step (one 16-channel block of the tile's input rows), relative to the first
     // image of the tile group and to the channel block. Chunks past the tile's rows repeat its last row.
@@ -349,7 +356,7 @@ DwPwPlan make_plan(const LayerGeom &g, int Co)
     int ent = 0;
     for (int m = 0; m < p.n_mtiles; ++m) {
         int lo, hi;
-        tile_rows(m * kTM, kTM, p.GHW, HWo, g.Wo, g.H, g.stride, g.pt, lo, hi);
+        tile_rows(m * kTM, kTM, p.GHW, HWo, g.Wo, g.H, g.stride, g.pt, PlainDiv{HWo}, PlainDiv{g.Wo}, lo, hi);
         ent = std::max(ent, (hi - lo + 1) * g.W);
     }
     p.chunks = (ent + 15) / 16;
@@ -373,7 +380,7 @@ DwPwPlan make_plan(const LayerGeom &g, int Co)
         int ent16 = 0;
         for (int m = 0; m < n16; ++m) {
             int lo, hi;
-            tile_rows(m * 16, 16, p.GHW, HWo, g.Wo, g.H, g.stride, g.pt, lo, hi);
+            tile_rows(m * 16, 16, p.GHW, HWo, g.Wo, g.H, g.stride, g.pt, PlainDiv{HWo}, PlainDiv{g.Wo}, lo, hi);
             ent16 = std::max(ent16, (hi - lo + 1) * g.W);
         }
         const int stage16 = 2 * 1024 + 16;
