@@ -3,8 +3,8 @@
 // the fp32 layer's, so the bound is vector arithmetic (36 multiply-adds, 8 conversions and 4 requantizations per
 // 4 output bytes), not memory.
 //
-// The mapping is window_dpp.hip's: a wave owns 16 neighbouring pixels of a strip of at most 7 rows of one plane (or
-// two planes of at most 7 pixels side by side), lane = 16 q + l holding the four channels 4q .. 4q + 3 of pixel l --
+// The mapping is window_dpp.hip's: a wave owns 16 neighbouring pixels of a strip of at most 7 rows of one plane
+// (or several narrow planes side by side), lane = 16 q + l holding the four channels 4q .. 4q + 3 of pixel l --
 // one 32-bit word of the pixel's 16-byte block. Every lane requests its nine input words at once (buffer
 // addressing: lanes and rows outside the image read as the code zx); the bytes become floats x, the left and right
 // neighbours come from lanes l - 1 and l + 1 by lane shifts of those floats (zero is shifted in at a band's ends:
@@ -29,11 +29,15 @@ struct DppU8Args {
     int nb;                // bands per row
     int sp;                // row strips per plane
     int n_units;           // plane groups * sp * nb: one per wave
+    int ppb;               // planes per band of 16 lanes (SEG 0), else unused
     unsigned bytes;        // of the input = of the output tensor (< 2^31)
-    FastDiv by_nb, by_sp, by_nCb;
+    FastDiv by_nb, by_sp, by_nCb, by_W;
     QuantParams q;
 };
 
+// Output rows per strip (two more input rows prime the window). Strips of 13 rows, tried where they still leave two
+// waves for every SIMD, save a tenth of the vector work and measure 10-30 % slower: a wave is one serial chain from
+// its loads to its last row, and what hides it is the number of waves.
 constexpr int kStripRowsU8 = 7;
 constexpr int kStepsU8 = kStripRowsU8 + 2;
 
@@ -49,6 +53,10 @@ __device__ __forceinline__ unsigned requant_clamped(float acc, const QuantParams
     return (unsigned)min(max(r, q.lo), q.hi);
 }
 
+// SEG 16: a band is 16 neighbouring pixels of one plane (14 outputs). SEG 8: rows of at most 7 pixels, two planes
+// side by side with a lane of padding on their left. SEG 0: rows of at most 5 pixels, floor(16 / W) planes back to
+// back without padding lanes (three planes of the audio CNN's 5-pixel rows instead of two): the neighbour a plane's
+// first and last pixel would take from the plane next to it is replaced by the code zx with a select.
 template <int SEG>
 __global__ void __launch_bounds__(256) dw16_dpp_u8(DppU8Args a)
 {
@@ -64,15 +72,22 @@ __global__ void __launch_bounds__(256) dw16_dpp_u8(DppU8Args a)
     const int n_in = r1 - r0 + 2;
 
     int plane, x;
+    bool lane_used = true;
     if (SEG == 16) {
         plane = pg;
         x = band * 14 - 1 + l;
-    } else {
+    } else if (SEG == 8) {
         plane = pg * 2 + (l >> 3);
         x = (l & 7) - 1;
+    } else {
+        const int pi = a.by_W.div(l);
+        plane = pg * a.ppb + pi;
+        x = l - pi * a.W;
+        lane_used = pi < a.ppb;
     }
-    const bool col_in = x >= 0 && x < a.W && plane < a.n_planes;
-    const bool col_out = col_in && (SEG == 8 || (l >= 1 && l <= 14));
+    const bool col_in = lane_used && x >= 0 && x < a.W && plane < a.n_planes;
+    const bool col_out = col_in && (SEG != 16 || (l >= 1 && l <= 14));
+    const bool at_left = x == 0, at_right = x == a.W - 1;          // (SEG 0)
     const int row_bytes = a.W * 16;
     const unsigned at = (unsigned)plane * (unsigned)(a.H * row_bytes) + (unsigned)(x * 16 + q * 4);
 
@@ -115,6 +130,10 @@ __global__ void __launch_bounds__(256) dw16_dpp_u8(DppU8Args a)
         row[j] = floatx4{byte_of(raw[j], 0), byte_of(raw[j], 1), byte_of(raw[j], 2), byte_of(raw[j], 3)};
         row_l[j] = lane_shift<kRowShr1>(row[j]);
         row_r[j] = lane_shift<kRowShl1>(row[j]);
+        if (SEG == 0) {
+            row_l[j] = at_left ? floatx4{zx, zx, zx, zx} : row_l[j];
+            row_r[j] = at_right ? floatx4{zx, zx, zx, zx} : row_r[j];
+        }
         if (j < 2) continue;
         floatx4 acc = acc0;
         acc += row[j - 1] * w[4];
@@ -153,17 +172,20 @@ hipError_t launch_dw_dpp_u8(const unsigned char *in, const unsigned char *filt, 
     a.n_planes = g.N * a.nCb;
     a.bytes = (unsigned)((size_t)g.N * g.Ci * g.H * g.W);
     a.q = q;
-    const bool pairs = g.W <= 7;
-    a.nb = pairs ? 1 : (g.W + 13) / 14;
-    const long groups = pairs ? (a.n_planes + 1) / 2 : a.n_planes;
+    const int seg = g.W <= 5 ? 0 : g.W <= 7 ? 8 : 16;
+    a.ppb = seg == 0 ? 16 / g.W : seg == 8 ? 2 : 1;
+    a.nb = seg == 16 ? (g.W + 13) / 14 : 1;
+    const long groups = (a.n_planes + a.ppb - 1) / a.ppb;
     a.sp = (g.H + kStripRowsU8 - 1) / kStripRowsU8;
     a.n_units = (int)(groups * a.sp * a.nb);
     a.by_nb = make_fastdiv(a.nb);
     a.by_sp = make_fastdiv(a.sp);
     a.by_nCb = make_fastdiv(a.nCb);
-    const unsigned wgs = (unsigned)((a.n_units + 3) / 4);
-    if (pairs) hipLaunchKernelGGL((dw16_dpp_u8<8>), dim3(wgs), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((dw16_dpp_u8<16>), dim3(wgs), dim3(256), 0, s, a);
+    a.by_W = make_fastdiv(g.W);
+    const dim3 grid((unsigned)((a.n_units + 3) / 4)), block(256);
+    if (seg == 0) hipLaunchKernelGGL((dw16_dpp_u8<0>), grid, block, 0, s, a);
+    else if (seg == 8) hipLaunchKernelGGL((dw16_dpp_u8<8>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((dw16_dpp_u8<16>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 

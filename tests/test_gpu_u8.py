@@ -496,6 +496,12 @@ DW_LANES_U8_CASES = [  # N, C, H, W, zx, zw: 3x3, stride 1, padding 1, 16-byte b
     (4, 48, 61, 63, 7, 250),
     (7, 32, 33, 17, 128, 128),
     (2, 32, 70, 100, 200, 100),
+    (5, 64, 25, 5, 130, 120),           # three planes of 5-pixel rows back to back, 20 planes: the last band holds two
+    (3, 48, 9, 4, 3, 250),              # four planes per band, 9 planes
+    (7, 16, 6, 3, 250, 3),              # five planes per band and an unused lane
+    (9, 32, 4, 2, 128, 7),              # eight planes per band
+    (5, 16, 3, 1, 77, 200),             # sixteen one-pixel rows per band
+    (770, 64, 25, 5, 130, 120),         # a full batch of them: 3080 planes, the last band holds two
 ]
 
 
