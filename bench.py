@@ -383,9 +383,20 @@ def measured_peaks(S, torch, dev, timed):
     spin(fr)
     tr = min(timed(fr, 10) for _ in range(3))
     del src, dst
+    # what a vector instruction costs next to the matrix pipe: rounds of sixteen matrix instructions (512 pipe cycles)
+    # with 0 / 32 / 64 / 96 multiply-adds beside them, four waves per SIMD; cycles per round and wave at 2.4 GHz
+    wgs4, it4 = 256 * 4, 2048
+    out4 = torch.empty(wgs4 * 256, dtype=torch.float32, device=dev)
+    mix = {}
+    for valu in (0, 32, 64, 96):
+        fm = lambda r: S.small_probe_mfma_valu(out4, wgs4, it4, valu)
+        spin(fm, 0.2)
+        mix[str(valu)] = round(min(timed(fm, 10) for _ in range(3)) * 2.4e9 / it4 / 4, 1)
     return {"mfma_f32_tflops": round(mfma, 1), "hbm_copy_gbs": round(8.0 * n / tc / 1e9, 1),
             "hbm_relu_gbs": round(8.0 * n / tr / 1e9, 1),
-            "note": "small_probe_mfma (register-resident 16x16x4 fp32 MFMA loop); torch copy_ and small_relu over 1 GiB in + 1 GiB out"}
+            "cycles_per_16_mfma_with_valu": mix,
+            "note": "small_probe_mfma (register-resident 16x16x4 fp32 MFMA loop); torch copy_ and small_relu over 1 GiB in + 1 GiB out; "
+                    "small_probe_mfma_valu (the same loop with independent fp32 multiply-adds beside it)"}
 
 
 def _traffic(kernel):

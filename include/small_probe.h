@@ -1,7 +1,7 @@
 /*
  * small_probe.h -- C ABI of libsmall_probe: a measurement aid for the benchmark, NOT part of the layer library
  * (include/small.h, libsmall_hip). It measures the fp32 matrix rate the chip sustains, so that roofline fractions can
- * be quoted against a measured peak next to the published one.
+ * be quoted against a measured peak next to the published one, and what vector instructions cost beside it.
  */
 #ifndef SMALL_PROBE_H
 #define SMALL_PROBE_H
@@ -16,6 +16,13 @@ extern "C" {
  * receives workgroups * 256 floats (checksums). Returns 0, 1 (out is NULL), 2 (workgroups outside 1 .. 2^20 or
  * iters < 1) or 5 (the launch failed); nothing is enqueued on an error. */
 int small_probe_mfma(float *out, int workgroups, int iters, void *stream);
+
+/* The same with vector-ALU work beside the matrix instructions: every wavefront runs `iters` rounds of `valu` (0, 32,
+ * 64 or 96) independent fp32 multiply-adds on registers followed by sixteen 16x16x4 fp32 matrix instructions on four
+ * accumulators. The time a round takes beyond valu = 0 is what vector instructions cost next to the matrix pipe.
+ * out as above (a lane's checksum: its sixteen accumulator values plus valu * iters * a * b, with the operands a, b of
+ * small_probe_mfma). Returns 0, 1 (out is NULL), 2 (workgroups or iters out of range, valu not one of the four) or 5. */
+int small_probe_mfma_valu(float *out, int workgroups, int iters, int valu, void *stream);
 
 #ifdef __cplusplus
 }

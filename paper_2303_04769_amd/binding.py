@@ -231,6 +231,8 @@ def load_probe():
             build_lib()
         lib = C.CDLL(PROBE_LIB_PATH)
         lib.small_probe_mfma.restype, lib.small_probe_mfma.argtypes = C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        lib.small_probe_mfma_valu.restype = C.c_int
+        lib.small_probe_mfma_valu.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         _probe = lib
     return _probe
 
@@ -239,6 +241,12 @@ def small_probe_mfma(out, workgroups, iters, stream=None):
     rc = load_probe().small_probe_mfma(_ptr(out), workgroups, iters, _stream(stream))
     if rc:
         raise RuntimeError(f"small_probe_mfma: error {rc}")
+
+
+def small_probe_mfma_valu(out, workgroups, iters, valu, stream=None):
+    rc = load_probe().small_probe_mfma_valu(_ptr(out), workgroups, iters, valu, _stream(stream))
+    if rc:
+        raise RuntimeError(f"small_probe_mfma_valu: error {rc}")
 
 
 def _ptr8(t):

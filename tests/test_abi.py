@@ -28,8 +28,8 @@ def test_every_declared_symbol_is_exported(lib):
     for n in names:
         assert getattr(lib, n) is not None
     # the benchmark's probe is a library and a header of its own, outside the layer ABI
-    assert _declared("small_probe.h") == ["small_probe_mfma"] and not hasattr(lib, "small_probe_mfma")
-    assert binding.load_probe().small_probe_mfma is not None
+    assert _declared("small_probe.h") == ["small_probe_mfma", "small_probe_mfma_valu"] and not hasattr(lib, "small_probe_mfma")
+    assert binding.load_probe().small_probe_mfma is not None and binding.load_probe().small_probe_mfma_valu is not None
     assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["small.h", "small_probe.h"]
 
 

@@ -428,6 +428,23 @@ def test_matrix_rate_probe_computes_what_it_says():
     assert np.allclose(got, ref[None, None, :], rtol=1e-5, atol=0)
 
 
+def test_matrix_and_vector_probe_computes_what_it_says():
+    """small_probe_mfma_valu: four accumulators, each 4 * iters times A x B as above, and valu * iters multiply-adds
+    a * b spread over eight registers, with a = 0.25 + (lane & 7) / 1000 and b = 0.75."""
+    wgs, iters = 2, 3
+    lane = np.arange(64)
+    q = lane // 16
+    rows = np.stack([4 * q + r for r in range(4)])
+    for valu in (0, 32, 64, 96):
+        g = Guarded(wgs * 256)
+        S.small_probe_mfma_valu(g.t, wgs, iters, valu)
+        got = g.check().reshape(wgs, 4, 64)
+        ref = 4 * 4 * iters * 4 * 0.75 * (0.25 + (rows & 7) / 1000.0).sum(axis=0) + valu * iters * (0.25 + (lane & 7) / 1000.0) * 0.75
+        assert np.allclose(got, ref.astype(np.float32)[None, None, :], rtol=1e-5, atol=0), valu
+    with pytest.raises(RuntimeError):
+        S.small_probe_mfma_valu(g.t, wgs, iters, 7)
+
+
 # ------------------------------------------------------------------ seeded random geometries
 
 def _random_geometry(rng, max_hw=34):
