@@ -385,7 +385,9 @@ DwPwPlan make_plan(const LayerGeom &g, int Co)
         }
         const int stage16 = 2 * 1024 + 16;
         const size_t lds16 = (size_t)((8 * kOwnStages * stage16 + 255) & ~255) + fixed;
-        if (ent16 <= 32 && 2 * lds16 <= 160 * 1024) {
+        // (eight waves to a workgroup: with fewer than a workgroup per compute unit the four-wave kernel covers more of them)
+        const long waves16 = (long)n16 * ((g.N + p.ipt - 1) / p.ipt) * ((nCob + wn - 1) / wn);
+        if (ent16 <= 32 && 2 * lds16 <= 160 * 1024 && waves16 >= 8L * device_cus()) {
             p.own = true;
             p.n_mtiles = n16;
             p.chunks = (ent16 + 15) / 16;

@@ -165,6 +165,8 @@ BLOCK_CASES = [  # N, C, Co, H, W, stride, relu_mid, relu_out
     (70, 64, 64, 6, 6, 2, True, True),        # 6 x 6 -> 3 x 3 with stride 2
     (9, 32, 32, 5, 5, 1, False, True),        # 25-pixel images: two per tile
     (600, 64, 64, 25, 5, 1, True, True),      # 125-pixel images, many of them: each workgroup walks several
+    (3600, 32, 48, 3, 3, 1, True, True),      # ... a ring per wave with seven 9-pixel images per tile group, three output blocks
+    (700, 16, 16, 6, 6, 1, False, True),      # ... with a ragged third tile (36 pixels)
     (520, 16, 32, 20, 20, 2, True, True),     # 100-pixel outputs of a stride-2 layer, many images
     (140, 32, 32, 16, 24, 1, True, False),    # 384-pixel images: six full tiles
     (9, 8, 16, 48, 48, 2, True, True),        # eight channels in one 8-channel block -> 16: the vector-unit kernel
