@@ -22,6 +22,7 @@ struct FirstU8Args {
     const unsigned char *in, *filt;
     unsigned char *out;
     int H, W, Ho, Wo, HoWo, M, nCob, stride, pt, pl;
+    unsigned in_bytes;
     FastDiv div_HoWo, div_Wo;
     QuantParams q;
 };
@@ -61,27 +62,63 @@ __global__ void __launch_bounds__(256) conv_first_u8(FirstU8Args a)
     const int m = live ? m_raw : a.M - 1;
     const int n = a.div_HoWo.div(m), pix = m - n * a.HoWo;
     const int oh = a.div_Wo.div(pix), ow = pix - oh * a.Wo;
-    const unsigned char *img = a.in + (size_t)n * a.H * a.W * CIB;
-
+    // The window, row by row: a row's KW * CIB bytes are contiguous in memory and, in reduction order, contiguous in
+    // the K-byte string x, so a row is NDW unaligned 32-bit loads (a load per byte, with its clamps, select and shift,
+    // was two thirds of this kernel's vector instructions). Bytes of columns outside the image and whole rows outside
+    // it become the code zx; bytes past the row's window become zero.
+    constexpr int NB = KW * CIB, NDW = (NB + 3) / 4;
+    const __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(a.in), 0, a.in_bytes, kRawBuffer);
+    const int ih0 = oh * a.stride - a.pt, iw0 = ow * a.stride - a.pl;
+    const unsigned zx4 = (unsigned)a.q.zx * kOnes;
+    unsigned keep[NDW], fill[NDW];          // byte masks of a row's words: inside the image; outside it but inside the window
+#pragma unroll
+    for (int d = 0; d < NDW; ++d) {
+        keep[d] = 0; fill[d] = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int j = 4 * d + b;
+            if (j < NB) {
+                const int col = iw0 + j / CIB;
+                if (col >= 0 && col < a.W) keep[d] |= 0xffu << (8 * b);
+                else fill[d] |= 0xffu << (8 * b);
+            }
+        }
+        fill[d] &= zx4;
+    }
+    const int first = n * a.H * a.W * CIB + (ih0 * a.W + iw0) * CIB;        // byte offset of the window's first row
+    // A 32-bit access that straddles either end of the tensor reads zero as a whole, also its bytes inside: where a
+    // wave has such an access, words are read from the nearest offset inside and shifted into place.
+    const int lim = (int)a.in_bytes - 4;
+    const int last = first + (KH - 1) * a.W * CIB + 4 * (NDW - 1);
+    const bool at_an_end = __builtin_amdgcn_ballot_w64(first < 0 || last > lim) != 0;
     unsigned x[KD];
 #pragma unroll
     for (int kd = 0; kd < KD; ++kd) x[kd] = 0;
 #pragma unroll
     for (int ky = 0; ky < KH; ++ky) {
-        const int ih = oh * a.stride + ky - a.pt;
-        const bool row_in = ih >= 0 && ih < a.H;
-        const unsigned char *row = img + min(max(ih, 0), a.H - 1) * a.W * CIB;
+        const bool row_in = (unsigned)(ih0 + ky) < (unsigned)a.H;
+        unsigned r[NDW];
 #pragma unroll
-        for (int kx = 0; kx < KW; ++kx) {
-            const int iw = ow * a.stride + kx - a.pl;
-            const bool inside = row_in && iw >= 0 && iw < a.W;
-            const unsigned char *px = row + min(max(iw, 0), a.W - 1) * CIB;
-#pragma unroll
-            for (int c = 0; c < CIB; ++c) {
-                const int k = (ky * KW + kx) * CIB + c;
-                const unsigned b = inside ? (unsigned)px[c] : (unsigned)a.q.zx;
-                x[k / 4] |= b << (8 * (k % 4));
+        for (int d = 0; d < NDW; ++d) {
+            const int off = first + ky * a.W * CIB + 4 * d;
+            unsigned v;
+            if (!at_an_end) {
+                v = __builtin_amdgcn_raw_buffer_load_b32(src, row_in ? (unsigned)off : kBeyond, 0, 0);
+            } else {
+                const int inside = min(max(off, 0), lim), by = off - inside;       // by < 0: the word lies before the tensor
+                const unsigned w = __builtin_amdgcn_raw_buffer_load_b32(src, row_in ? (unsigned)inside : kBeyond, 0, 0);
+                v = by == 0 ? w : (by < 0 ? (by > -4 ? w << (-8 * by) : 0u) : (by < 4 ? w >> (8 * by) : 0u));
             }
+            // (a row outside the image: zx in every byte of the window)
+            const unsigned window = 4 * d + 4 <= NB ? 0xffffffffu : (NB > 4 * d ? (1u << (8 * (NB - 4 * d))) - 1u : 0u);
+            r[d] = row_in ? ((v & keep[d]) | fill[d]) : (zx4 & window);
+        }
+        const int at = ky * NB;                    // the row's place in x, in bytes (a constant once unrolled)
+#pragma unroll
+        for (int d = 0; d < NDW; ++d) {
+            const int word = (at + 4 * d) / 4, sh = 8 * ((at + 4 * d) % 4);
+            if (word < KD) x[word] |= r[d] << sh;
+            if (sh != 0 && word + 1 < KD) x[word + 1] |= r[d] >> (32 - sh);
         }
     }
     unsigned sx = 0;
@@ -90,6 +127,8 @@ __global__ void __launch_bounds__(256) conv_first_u8(FirstU8Args a)
     const int base = K * a.q.zx * a.q.zw - a.q.zw * (int)sx;
     __syncthreads();                                     // the filter sums
 
+    const bool narrow = a.q.amax > 0;                    // (uniform) the five-instruction requantization applies
+    const long bias = requant_bias(a.q);
     unsigned packed[COB / 4];
 #pragma unroll
     for (int j = 0; j < COB / 4; ++j) packed[j] = 0;
@@ -99,7 +138,7 @@ __global__ void __launch_bounds__(256) conv_first_u8(FirstU8Args a)
 #pragma unroll
         for (int kd = 0; kd < KD; ++kd) dot = dot4(x[kd], wl[co * KD + kd], dot);
         const int acc = (int)dot - a.q.zx * sw[co] + base;
-        packed[co / 4] |= (unsigned)requant(acc, a.q) << (8 * (co % 4));
+        packed[co / 4] |= (unsigned)(narrow ? requant_clamped(acc, a.q, bias) : requant(acc, a.q)) << (8 * (co % 4));
     }
     if (live) {
         unsigned char *o = a.out + ((size_t)(n * a.nCob + cob) * a.HoWo + pix) * COB;
@@ -211,7 +250,8 @@ bool conv_first_u8_eligible(const LayerGeom &g, const void *out)
                        (g.kh == 1 && g.kw == 1 && g.Cib == 8);
     if (!shape || g.Ci != g.Cib || (g.Cob != 16 && g.Cob != 8) || g.Co / g.Cob > 65535) return false;
     if (((uintptr_t)out & (uintptr_t)(g.Cob - 1)) != 0) return false;
-    return (size_t)g.N * g.Ho * g.Wo < ((size_t)1 << 31) && (size_t)g.N * g.H * g.W * g.Ci < ((size_t)1 << 31);
+    return (size_t)g.N * g.Ho * g.Wo < ((size_t)1 << 31) && (size_t)g.N * g.H * g.W * g.Ci < ((size_t)1 << 31) &&
+           (size_t)g.N * g.H * g.W * g.Ci >= 4;
 }
 
 hipError_t launch_conv_first_u8(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
@@ -221,6 +261,7 @@ hipError_t launch_conv_first_u8(const unsigned char *in, const unsigned char *fi
     a.in = in; a.filt = filt; a.out = out;
     a.H = g.H; a.W = g.W; a.Ho = g.Ho; a.Wo = g.Wo; a.HoWo = g.Ho * g.Wo; a.M = g.N * a.HoWo;
     a.nCob = g.Co / g.Cob; a.stride = g.stride; a.pt = g.pt; a.pl = g.pl;
+    a.in_bytes = (unsigned)((size_t)g.N * g.H * g.W * g.Ci);
     a.div_HoWo = make_fastdiv(a.HoWo);
     a.div_Wo = make_fastdiv(g.Wo);
     a.q = q;
