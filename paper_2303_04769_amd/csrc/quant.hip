@@ -732,10 +732,15 @@ inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 // operand wm of them, and the sign flips of both cost vector instructions, which is what bounds these kernels:
 // two pixel groups and as many output blocks (up to four) as divide the layer measured best at the sweep shapes,
 // also where that leaves fewer workgroups than compute units.
-void pick_conv_tile(int nCob, int &wm, int &wn)
+// A reduction of at most four chunks (pointwise layers on up to 64 channels) is one step: load, multiply,
+// requantize, store, with every wave of the launch in the same phase at the same time. Two output blocks per
+// workgroup instead of four then give twice the waves to overlap those phases (10.7 -> 9.9 us on the audio CNN's
+// pointwise layers at batch 1024; one block per workgroup: slower again, the input is then read four times).
+void pick_conv_tile(int nCob, int n_chunks, int &wm, int &wn)
 {
     wm = 2;
     wn = nCob % 4 == 0 ? 4 : (nCob % 2 == 0 ? 2 : 1);
+    if (wn == 4 && n_chunks <= 4) wn = 2;
 }
 
 QConvArgs conv_args(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
@@ -796,7 +801,7 @@ hipError_t launch_conv_u8(const unsigned char *in, const unsigned char *filt, un
     const QConvArgs a = conv_args(in, filt, out, g, q, filt_sums);
     if (conv_u8_uses_mfma(g, in, filt, out)) {
         int wm = 4, wn = 4;
-        pick_conv_tile(a.nCob, wm, wn);
+        pick_conv_tile(a.nCob, a.n_chunks, wm, wn);
         const dim3 grid((unsigned)((a.M + 64 * wm - 1) / (64 * wm)), (unsigned)(a.nCob / wn));
         const int corr = (q.zx != 128 && !filt_sums) ? 2 : (q.zw != 128 ? 1 : 0);
 #define SMALL_U8_CASE(M_, N_, C_)                                                                            \
