@@ -1,19 +1,15 @@
 // Quantized depthwise 3x3 convolution, stride 1, padding 1, 16-byte channel blocks: the uint8 counterpart of
-// window_dpp.hip. uint8 codes in and out, exact sums, the library's requantization rule; HBM traffic is a quarter of
-// the fp32 layer's, so the bound is vector arithmetic (36 multiply-adds, 8 conversions and 4 requantizations per
-// 4 output bytes), not memory.
+// window_dpp.hip. uint8 codes in and out, exact int32 sums, the library's requantization rule; HBM traffic is a
+// quarter of the fp32 layer's, so the bound is vector arithmetic, not memory.
 //
 // The mapping is window_dpp.hip's: a wave owns 16 neighbouring pixels of a strip of at most 7 rows of one plane
 // (or several narrow planes side by side), lane = 16 q + l holding the four channels 4q .. 4q + 3 of pixel l --
 // one 32-bit word of the pixel's 16-byte block. Every lane requests its nine input words at once (buffer
-// addressing: lanes and rows outside the image read as the code zx); the bytes become floats x, the left and right
-// neighbours come from lanes l - 1 and l + 1 by lane shifts of those floats (zero is shifted in at a band's ends:
-// lanes 0 and 15 produce no output there, except lane 15 of a pair of planes, whose sum is corrected), the nine
-// taps w' = w - zw are floats in registers, and sum over all nine taps of x w' - zx sum w' -- the sum over the
-// taps inside the image of (x - zx)(w - zw), since every other tap reads zx -- is exact in fp32 in any order
-// (integers below 2^24). The sum goes back to int, through the requantization (the clamped 64-bit form: the host
-// sends only layers whose scale allows it), into its byte of the output word. Vector arithmetic per output word:
-// 36 multiply-adds, 8 lane shifts, 4 conversions, 4 requantizations of five instructions.
+// addressing: lanes and rows outside the image read as the code zx); the left and right neighbours come from
+// lanes l - 1 and l + 1 by lane shifts of the words (zero is shifted in at a band's ends: lanes 0 and 15 produce no
+// output there, or the value is replaced). The sums are taken with four-byte signed dot products over the three
+// taps of a window row (see the kernel), go through the requantization (the clamped 64-bit form: the host sends only
+// layers whose scale allows it) and into their byte of the output word.
 #include "small_internal.h"
 
 namespace small {
@@ -41,23 +37,11 @@ struct DppU8Args {
 constexpr int kStripRowsU8 = 7;
 constexpr int kStepsU8 = kStripRowsU8 + 2;
 
-__device__ __forceinline__ float byte_of(unsigned w, int c) { return (float)((w >> (8 * c)) & 255u); }
-
-// clamp(zy + floor((acc * mult + 2^(shift-1)) / 2^shift), lo, hi) for layers with q.amax > 0: the sum is clamped to
-// +-amax first (beyond it the output saturates anyway, within it everything below fits), and bias =
-// 2^(shift-1) + zy * 2^shift carries the rounding term and the zero point through the one shift.
-__device__ __forceinline__ unsigned requant_clamped(float acc, const QuantParams &q, float amax, long bias)
-{
-    const int c = (int)__builtin_amdgcn_fmed3f(acc, -amax, amax);
-    const int r = (int)(((long)c * (long)q.mult + bias) >> q.shift);
-    return (unsigned)min(max(r, q.lo), q.hi);
-}
-
 // SEG 16: a band is 16 neighbouring pixels of one plane (14 outputs). SEG 8: rows of at most 7 pixels, two planes
 // side by side with a lane of padding on their left. SEG 0: rows of at most 5 pixels, floor(16 / W) planes back to
 // back without padding lanes (three planes of the audio CNN's 5-pixel rows instead of two): the neighbour a plane's
 // first and last pixel would take from the plane next to it is replaced by the code zx with a select.
-template <int SEG>
+template <int SEG, bool HAS_ZB>
 __global__ void __launch_bounds__(256) dw16_dpp_u8(DppU8Args a)
 {
     const int lane = threadIdx.x & 63;
@@ -104,49 +88,73 @@ __global__ void __launch_bounds__(256) dw16_dpp_u8(DppU8Args a)
         const unsigned v = __builtin_amdgcn_raw_buffer_load_b32(src, have ? at + (unsigned)(r * row_bytes) : kBeyond, 0, 0);
         raw[j] = have ? v : zx4;
     }
-    // the plane's nine taps of this quad as floats w - zw
-    const float zx = (float)a.q.zx, zw = (float)a.q.zw;
-    floatx4 w[9];
+    // Everything below works on signed bytes x' = x - 128 and w' = w - 128 (one exclusive-or per word), whose products
+    // the four-byte signed dot product sums exactly:
+    //     sum (x - zx)(w - zw) = sum x' w' + b sum x' + a sum w' + 9 a b,   a = 128 - zx, b = 128 - zw,
+    // over all nine taps, those outside the image carrying the code zx. A dot product wants the three taps of one
+    // window row of ONE channel in a word, the tensor has the four channels of one pixel in a word: per input row the
+    // words of the left neighbour, the pixel and the right neighbour (lane shifts of the raw words: two per row, not
+    // eight) are transposed into four words [left, centre, right, 0], one per channel, with two byte permutes each;
+    // every such word serves three output rows. The filter is transposed the same way once. Per output word: 2 lane
+    // shifts, 8 permutes and 12 dot products, where the float form of this kernel had 8 shifts, 4 conversions and 36
+    // multiply-adds; with zw = 128 (b = 0) the sum of the window's codes is not needed at all.
+    const unsigned flip = 0x80808080u;
+    const int za = 128 - a.q.zx, zb = 128 - a.q.zw;
+    auto channel_words = [&](unsigned left, unsigned mid, unsigned right, unsigned (&t)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const unsigned lm = __builtin_amdgcn_perm(mid, left, 0x0c0c0000u | (unsigned)((4 + c) << 8) | (unsigned)c);
+            t[c] = __builtin_amdgcn_perm(right, lm, 0x0c000100u | (unsigned)((4 + c) << 16));
+        }
+    };
+    unsigned wt[3][4];                                      // [window row][channel]: its three taps
+    int cst[4];                                             // a sum w' + 9 a b per channel
     {
         const int pc = min(plane, a.n_planes - 1), cb = pc - a.by_nCb.div(pc) * a.nCb;
         const unsigned *tp = reinterpret_cast<const unsigned *>(a.filt) + cb * 36 + q;
 #pragma unroll
-        for (int k = 0; k < 9; ++k) {
-            const unsigned wr = tp[k * 4];
-            w[k] = floatx4{byte_of(wr, 0) - zw, byte_of(wr, 1) - zw, byte_of(wr, 2) - zw, byte_of(wr, 3) - zw};
-        }
-    }
-    floatx4 wsum = w[0];
+        for (int c = 0; c < 4; ++c) cst[c] = 0;
 #pragma unroll
-    for (int k = 1; k < 9; ++k) wsum += w[k];
-    floatx4 acc0 = wsum * (-zx);                               // - zx * sum of the taps
-    if (SEG == 8 && l == 15) acc0 += (w[2] + w[5] + w[8]) * zx;       // its right neighbours read 0, not zx
-    const long bias = (a.q.shift > 0 ? 1L << (a.q.shift - 1) : 0L) + ((long)a.q.zy << a.q.shift);
-    const float amax = (float)min(a.q.amax, 1 << 24);          // (sums stay below 2^24: a larger bound never binds)
+        for (int r = 0; r < 3; ++r) {
+            channel_words(tp[(3 * r) * 4] ^ flip, tp[(3 * r + 1) * 4] ^ flip, tp[(3 * r + 2) * 4] ^ flip, wt[r]);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) cst[c] = __builtin_amdgcn_sdot4((int)wt[r][c], 0x00010101, cst[c], false);
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) cst[c] = za * cst[c] + 9 * za * zb;
+    }
+    const long bias = requant_bias(a.q);
+    const unsigned zxs = zx4 ^ flip;                        // the padding code as signed bytes
 
-    floatx4 row[kStepsU8], row_l[kStepsU8], row_r[kStepsU8];
+    unsigned tw[kStepsU8][4];                               // [input row][channel]: left, centre and right value
+    int sx[kStepsU8][4];                                    // their sums (zb != 0 only)
 #pragma unroll
     for (int j = 0; j < kStepsU8; ++j) {
-        row[j] = floatx4{byte_of(raw[j], 0), byte_of(raw[j], 1), byte_of(raw[j], 2), byte_of(raw[j], 3)};
-        row_l[j] = lane_shift<kRowShr1>(row[j]);
-        row_r[j] = lane_shift<kRowShl1>(row[j]);
+        const unsigned mid = raw[j] ^ flip;
+        unsigned left = (unsigned)__builtin_amdgcn_update_dpp(0, (int)mid, kRowShr1, 0xf, 0xf, true);
+        unsigned right = (unsigned)__builtin_amdgcn_update_dpp(0, (int)mid, kRowShl1, 0xf, 0xf, true);
+        // (zero is shifted in at the ends of a row of 16 lanes; where such a lane has an output, it wants zx there)
         if (SEG == 0) {
-            row_l[j] = at_left ? floatx4{zx, zx, zx, zx} : row_l[j];
-            row_r[j] = at_right ? floatx4{zx, zx, zx, zx} : row_r[j];
+            left = at_left ? zxs : left;
+            right = at_right ? zxs : right;
+        } else if (SEG == 8) {
+            right = l == 15 ? zxs : right;
+        }
+        channel_words(left, mid, right, tw[j]);
+        if (HAS_ZB) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) sx[j][c] = __builtin_amdgcn_sdot4((int)tw[j][c], 0x00010101, 0, false);
         }
         if (j < 2) continue;
-        floatx4 acc = acc0;
-        acc += row[j - 1] * w[4];
-        acc += row[j - 2] * w[1];
-        acc += row[j] * w[7];
-        acc += row_l[j - 2] * w[0];
-        acc += row_l[j - 1] * w[3];
-        acc += row_l[j] * w[6];
-        acc += row_r[j - 2] * w[2];
-        acc += row_r[j - 1] * w[5];
-        acc += row_r[j] * w[8];
-        const unsigned y = requant_clamped(acc.x, a.q, amax, bias) | (requant_clamped(acc.y, a.q, amax, bias) << 8) |
-                           (requant_clamped(acc.z, a.q, amax, bias) << 16) | (requant_clamped(acc.w, a.q, amax, bias) << 24);
+        unsigned y = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            int acc = __builtin_amdgcn_sdot4((int)tw[j - 2][c], (int)wt[0][c], cst[c], false);
+            acc = __builtin_amdgcn_sdot4((int)tw[j - 1][c], (int)wt[1][c], acc, false);
+            acc = __builtin_amdgcn_sdot4((int)tw[j][c], (int)wt[2][c], acc, false);
+            if (HAS_ZB) acc += zb * (sx[j - 2][c] + sx[j - 1][c] + sx[j][c]);
+            y |= (unsigned)requant_clamped(acc, a.q, bias) << (8 * c);
+        }
         const unsigned off = (col_out && j < n_in) ? at + (unsigned)((r0 + j - 2) * row_bytes) : kBeyond;
         __builtin_amdgcn_raw_buffer_store_b32(y, dst, off, 0, kNonTemporal);
     }
@@ -183,9 +191,15 @@ hipError_t launch_dw_dpp_u8(const unsigned char *in, const unsigned char *filt, 
     a.by_nCb = make_fastdiv(a.nCb);
     a.by_W = make_fastdiv(g.W);
     const dim3 grid((unsigned)((a.n_units + 3) / 4)), block(256);
-    if (seg == 0) hipLaunchKernelGGL((dw16_dpp_u8<0>), grid, block, 0, s, a);
-    else if (seg == 8) hipLaunchKernelGGL((dw16_dpp_u8<8>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((dw16_dpp_u8<16>), grid, block, 0, s, a);
+    if (q.zw == 128) {
+        if (seg == 0) hipLaunchKernelGGL((dw16_dpp_u8<0, false>), grid, block, 0, s, a);
+        else if (seg == 8) hipLaunchKernelGGL((dw16_dpp_u8<8, false>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((dw16_dpp_u8<16, false>), grid, block, 0, s, a);
+    } else {
+        if (seg == 0) hipLaunchKernelGGL((dw16_dpp_u8<0, true>), grid, block, 0, s, a);
+        else if (seg == 8) hipLaunchKernelGGL((dw16_dpp_u8<8, true>), grid, block, 0, s, a);
+        else hipLaunchKernelGGL((dw16_dpp_u8<16, true>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
 }
 
