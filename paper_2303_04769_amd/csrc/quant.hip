@@ -732,15 +732,16 @@ inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 // operand wm of them, and the sign flips of both cost vector instructions, which is what bounds these kernels:
 // two pixel groups and as many output blocks (up to four) as divide the layer measured best at the sweep shapes,
 // also where that leaves fewer workgroups than compute units.
-// A reduction of at most four chunks (pointwise layers on up to 64 channels) is one step: load, multiply,
+// A reduction of at most eight chunks (pointwise layers on up to 128 channels) is one or two steps: load, multiply,
 // requantize, store, with every wave of the launch in the same phase at the same time. Two output blocks per
 // workgroup instead of four then give twice the waves to overlap those phases (10.7 -> 9.9 us on the audio CNN's
-// pointwise layers at batch 1024; one block per workgroup: slower again, the input is then read four times).
+// pointwise layers at batch 1024, 14.9 -> 13.6 and 9.9 -> 8.9 us at the sweep's 64- and 128-channel shapes; with 16
+// chunks it loses, 7.1 -> 7.5 us; one block per workgroup: slower again, the input is then read four times).
 void pick_conv_tile(int nCob, int n_chunks, int &wm, int &wn)
 {
     wm = 2;
     wn = nCob % 4 == 0 ? 4 : (nCob % 2 == 0 ? 2 : 1);
-    if (wn == 4 && n_chunks <= 4) wn = 2;
+    if (wn == 4 && n_chunks <= 8) wn = 2;
 }
 
 QConvArgs conv_args(const unsigned char *in, const unsigned char *filt, unsigned char *out, const LayerGeom &g,
