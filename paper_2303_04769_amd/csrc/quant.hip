@@ -481,6 +481,90 @@ __global__ void __launch_bounds__(256) conv_u8_mfma4(QConvArgs a)
     store_tiles<WM, WN>(a, acc, acc_s, acc_w, tile0, cob0, p, g);
 }
 
+// Pointwise layers (1x1 window, stride 1, no padding) on 64 or 128 input channels: the kernel above is one or two steps
+// per workgroup there -- load, multiply, requantize, store, every wave of a round in the same phase at the same time,
+// and a launch is a few rounds of load latencies (13.6 us for 26 MB at the sweep's 64-channel shape). Here a wave keeps
+// the filter operands of its WN output blocks in registers (a pointwise filter is all of 4 or 8 matrix operands per
+// output block) and walks tiles of 16 * WM pixels: the next tile's pixels are requested before the current tile is
+// multiplied and requantized, so the vector work of one tile hides the load latency of the next.
+template <int WM, int WN, int CORR, int GROUPS>
+__global__ void __launch_bounds__(256) pw_u8_stream(QConvArgs a, int n_tiles, int n_waves)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int p = lane & 15, g = lane >> 4;
+    const int cob0 = blockIdx.y * WN;
+    const int wv = (int)blockIdx.x * 4 + wave;
+    if (wv >= n_waves) return;
+    const int za = a.q.zx - 128;
+    constexpr bool use_s = CORR >= 1, mfma_w = CORR == 2;
+    const bool use_w = za != 0;
+    const int flip = (int)0x80808080u;
+    const intx4 ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    const intx4 zero = {0, 0, 0, 0};
+
+    // filter block (cob, cib) holds 16 rows of 16 bytes: row p of blocks (cob0 + wn, 4j + g)
+    intx4 fa[GROUPS][WN], acc_w[WN];
+    {
+        const intx4 *filt = reinterpret_cast<const intx4 *>(a.filt) + ((size_t)cob0 * a.nCib + g) * 16 + p;
+#pragma unroll
+        for (int j = 0; j < GROUPS; ++j)
+#pragma unroll
+            for (int wn = 0; wn < WN; ++wn) fa[j][wn] = filt[((size_t)wn * a.nCib + 4 * j) * 16] ^ flip;
+#pragma unroll
+        for (int wn = 0; wn < WN; ++wn) {
+            acc_w[wn] = zero;
+            if (mfma_w) {
+#pragma unroll
+                for (int j = 0; j < GROUPS; ++j) acc_w[wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[j][wn], ones, acc_w[wn], 0, 0, 0);
+            }
+        }
+        if (use_w && a.filt_sums) {
+#pragma unroll
+            for (int wn = 0; wn < WN; ++wn) acc_w[wn] = signed_filter_sums(a, cob0 + wn, g);
+        }
+    }
+    const size_t group_stride = (size_t)4 * a.HoWo;      // four input blocks further, in 16-byte units
+    auto request = [&](int tile, intx4 (&rb)[GROUPS][WM]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm) {
+            int m = tile * (16 * WM) + wm * 16 + p;
+            m = m < a.M ? m : a.M - 1;
+            const int n = a.div_HoWo.div(m), pix = m - n * a.HoWo;
+            const intx4 *px = reinterpret_cast<const intx4 *>(a.in) + ((size_t)n * a.nCib + g) * a.HoWo + pix;
+#pragma unroll
+            for (int j = 0; j < GROUPS; ++j) rb[j][wm] = px[j * group_stride];
+        }
+    };
+    intx4 cur[GROUPS][WM];
+    request(wv, cur);
+    for (int tile = wv; tile < n_tiles; tile += n_waves) {
+        intx4 nxt[GROUPS][WM];
+        request(tile + n_waves < n_tiles ? tile + n_waves : tile, nxt);
+        __builtin_amdgcn_sched_barrier(0);             // the requests above stay ahead of the arithmetic below
+        intx4 acc[WM][WN], acc_s[WM];
+#pragma unroll
+        for (int wm = 0; wm < WM; ++wm) {
+            acc_s[wm] = zero;
+#pragma unroll
+            for (int wn = 0; wn < WN; ++wn) acc[wm][wn] = zero;
+        }
+#pragma unroll
+        for (int j = 0; j < GROUPS; ++j)
+#pragma unroll
+            for (int wm = 0; wm < WM; ++wm) {
+                const intx4 fb = cur[j][wm] ^ flip;
+#pragma unroll
+                for (int wn = 0; wn < WN; ++wn) acc[wm][wn] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[j][wn], fb, acc[wm][wn], 0, 0, 0);
+                if (use_s) acc_s[wm] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb, acc_s[wm], 0, 0, 0);
+            }
+        store_tiles<WM, WN>(a, acc, acc_s, acc_w, tile * (16 * WM), cob0, p, g);
+#pragma unroll
+        for (int j = 0; j < GROUPS; ++j)
+#pragma unroll
+            for (int wm = 0; wm < WM; ++wm) cur[j][wm] = nxt[j][wm];
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ single channel
 
 struct QWindowArgs {
@@ -801,10 +885,24 @@ hipError_t launch_conv_u8(const unsigned char *in, const unsigned char *filt, un
     if (dense_u8_eligible(g, in, filt)) return launch_dense_u8(in, filt, out, g, q, s);
     const QConvArgs a = conv_args(in, filt, out, g, q, filt_sums);
     if (conv_u8_uses_mfma(g, in, filt, out)) {
+        const int corr = (q.zx != 128 && !filt_sums) ? 2 : (q.zw != 128 ? 1 : 0);
+        // pointwise layers on 64 or 128 channels with enough pixels for a round of waves: the streaming kernel
+        if (g.kh == 1 && g.kw == 1 && g.stride == 1 && g.pt == 0 && g.pl == 0 && g.Ho == g.H && g.Wo == g.W &&
+            (a.nCib == 4 || a.nCib == 8) && a.nCob % 2 == 0 && (long)a.M >= 32L * 4 * device_cus()) {
+            const int n_tiles = (a.M + 31) / 32;
+            const int resident = 16 * device_cus();                                 // waves per output-block pair
+            const int per_wave = (n_tiles + resident - 1) / resident;
+            const int n_waves = (n_tiles + per_wave - 1) / per_wave;
+            const dim3 grid((unsigned)((n_waves + 3) / 4), (unsigned)(a.nCob / 2));
+#define SMALL_PW_CASE(C_, G_)                                                                                \
+    if (corr == C_ && a.nCib == 4 * G_) hipLaunchKernelGGL((pw_u8_stream<2, 2, C_, G_>), grid, dim3(256), 0, s, a, n_tiles, n_waves);
+            SMALL_PW_CASE(0, 1) SMALL_PW_CASE(1, 1) SMALL_PW_CASE(2, 1) SMALL_PW_CASE(0, 2) SMALL_PW_CASE(1, 2) SMALL_PW_CASE(2, 2)
+#undef SMALL_PW_CASE
+            return hipGetLastError();
+        }
         int wm = 4, wn = 4;
         pick_conv_tile(a.nCob, a.n_chunks, wm, wn);
         const dim3 grid((unsigned)((a.M + 64 * wm - 1) / (64 * wm)), (unsigned)(a.nCob / wn));
-        const int corr = (q.zx != 128 && !filt_sums) ? 2 : (q.zw != 128 ? 1 : 0);
 #define SMALL_U8_CASE(M_, N_, C_)                                                                            \
     if (wm == M_ && wn == N_ && corr == C_) {                                                                \
         if (a.nCib % 4 == 0) hipLaunchKernelGGL((conv_u8_mfma4<M_, N_, C_, 3>), grid, dim3(256), 0, s, a);   \

@@ -290,6 +290,31 @@ WIDE_CONV_CASES = [  # N, Ci, Co, H, W, kh, kw, stride, pad, zx, zw, relu: input
 ]
 
 
+POINTWISE_STREAM_CASES = [  # N, Ci, Co, H, W, zx, zw, relu: at least 32768 pixels, 64 or 128 input channels
+    (40, 64, 64, 29, 29, 120, 131, True),       # 33640 pixels: a ragged last tile; both correction sums
+    (20, 128, 96, 41, 41, 128, 128, False),     # two groups of input blocks, six output blocks, no corrections
+    (33000, 64, 32, 1, 1, 7, 128, True),        # one pixel per image; only the filter sums
+    (9, 128, 64, 61, 60, 128, 250, False),      # only the pixel sums
+]
+
+
+@pytest.mark.parametrize("case", POINTWISE_STREAM_CASES)
+def test_pointwise_conv_streaming(case):
+    """1x1 convolutions on 64 or 128 channels with enough pixels for the kernel that keeps the filter in registers and
+    walks pixel tiles; with the filter sums given and taken inside, and on the wide requantization path."""
+    N, Ci, Co, H, W, zx, zw, relu = case
+    r = _rng(21)
+    x, w = WL.u8_codes(r, (N, Ci, H, W)), WL.u8_codes(r, (Co, Ci, 1, 1))
+    pad = (0, 0, 0, 0)
+    q = _quant_for(Q.conv2d_acc(x, w, 1, pad, zx, zw), zx, zw, relu)
+    ref = Q.conv2d(x, w, 1, pad, q)
+    _same(_conv(x, w, 1, pad, q, 16, 16, with_sums=True), ref, f"pointwise u8, sums given {case}")
+    _same(_conv(x, w, 1, pad, q, 16, 16), ref, f"pointwise u8 {case}")
+    assert len(np.unique(ref)) > 8
+    q = _quant(Ci, zx, zw, mult=(1 << 31) - 1, shift=0, zy=9)        # the wide requantization path
+    _same(_conv(x, w, 1, pad, q, 16, 16, with_sums=True), Q.conv2d(x, w, 1, pad, q), f"pointwise u8 wide {case}")
+
+
 @pytest.mark.parametrize("case", WIDE_CONV_CASES)
 def test_conv_four_blocks_per_step(case):
     """Layers whose matrix instruction takes one tap of four input blocks, with the filter sums given and taken inside."""
