@@ -60,11 +60,18 @@ __device__ __forceinline__ const float *dr_uniform(const float *p)
     return (const float *)(((uintptr_t)hi << 32) | lo);
 }
 
-// a division constant read from the kernel arguments (scalar loads)
-__device__ __forceinline__ FastDiv dr_fd(const __attribute__((address_space(4))) FastDiv &x)
+// A division constant read from the kernel arguments (scalar loads), in two registers instead of three: the kernel
+// lives at the limit of the scalar registers (what does not fit is kept in lanes of a vector register and fetched from
+// there, inside the loops too), and it holds six of these. A divisor of 1 is marked in the shift.
+struct DrDiv {
+    unsigned magic, shift;
+    __device__ __forceinline__ int div(int n) const { return (shift & 0x80u) ? n : (int)(__umulhi((unsigned)n, magic) >> shift); }
+};
+__device__ __forceinline__ DrDiv dr_fd(const __attribute__((address_space(4))) FastDiv &x)
 {
-    FastDiv f;
-    f.magic = x.magic; f.shift = x.shift; f.d = x.d;
+    DrDiv f;
+    f.magic = x.magic;
+    f.shift = x.d == 1 ? 0x80u : x.shift;
     return f;
 }
 // pixel groups of a tensor of G images
@@ -131,7 +138,7 @@ __global__ void __launch_bounds__(kDrThreads) dwpw_run(DrArgs args)
     int c_b = 0, c_phase = 0, c_item = w;
     const float *c_dw, *c_pw;
     int c_nCbi, c_nCbo, c_lim_dw, c_lim_pw;
-    FastDiv c_by_nCbi, c_by_nCbo;
+    DrDiv c_by_nCbi, c_by_nCbo;
     const float *c_src;
     int c_left = 0, c_stride = 0;
     unsigned c_off = off_dw, ws = 0;                    // ws: ring slot of the next copy
@@ -198,8 +205,8 @@ __global__ void __launch_bounds__(kDrThreads) dwpw_run(DrArgs args)
         const int HWi = Hi * Wi, HWo = ka->block[b].Ho * Wo;
         const int stride = ka->block[b].stride, pt = ka->block[b].pt, pl = ka->block[b].pl;
         const int dw_relu = ka->block[b].dw_relu, pw_relu = ka->block[b].pw_relu;
-        const FastDiv by_HWo = dr_fd(ka->block[b].by_HWo), by_Wo = dr_fd(ka->block[b].by_Wo);
-        const FastDiv by_nCbi = dr_fd(ka->block[b].by_nCbi), by_nCbo = dr_fd(ka->block[b].by_nCbo);
+        const DrDiv by_HWo = dr_fd(ka->block[b].by_HWo), by_Wo = dr_fd(ka->block[b].by_Wo);
+        const DrDiv by_nCbi = dr_fd(ka->block[b].by_nCbi), by_nCbo = dr_fd(ka->block[b].by_nCbo);
         const int ngi = dr_groups(G, HWi), ng = dr_groups(G, HWo);
         const bool last = b + 1 == n_blocks;
         const bool to_memory = last && ka->head == nullptr;
